@@ -1,0 +1,278 @@
+"""CPU oracle for Prefill-Only Pruning (POP): TEST INFRASTRUCTURE, not a product path.
+
+A plain, slow, step-by-step statement of what the pruned prefill computes, in the paper's order
+and notation, on numpy arrays (float64 unless a dtype is passed).  Only tests, the smoke check
+and the benchmark's CPU-baseline leg may import this module; the GPU library never does, and
+this module shares no code with it.
+
+What follows what:
+  * `kept_layer_rows`      -- Sec. 2.1, the layer forward (first display equation) with the
+                              K/V generation and cache append of the second and third ones.
+  * `kv_only_rows`         -- Sec. 3.3, "Independent KV Projections": the pruned layer stores
+                              k_l = RoPE(LN(x_l) W_l^K), v_l = LN(x_l) W_l^V and passes x_l on.
+  * `pop_prefill`          -- Sec. 3.3 as a whole: pruned prefill over x_{1:N-1}, then the last
+                              prompt token x_N as the first full-depth decode step
+                              ("Boundary Handling for the Last Input Token").
+  * `decode_step`          -- Sec. 3.2, the decode operator: one token through all L layers,
+                              appending its K/V and producing next-token logits.
+  * `slot_map`             -- where entry t of sequence b lives in a paged cache (the paper's
+                              cache append is a plain concatenation; paging is the serving
+                              layout used by the workloads here).
+
+Readings of points the paper leaves open (each is listed in the design notes as well):
+  * The pruned-layer projection uses layer l's own norm scale, W_l^K and W_l^V (the equation in
+    Sec. 3.3 drops the layer index that Sec. 2.1 carries).
+  * Since a pruned layer passes x_l on unchanged, all pruned layers of a contiguous deep block
+    see the output of the last kept layer.
+  * LN is RMSNorm: x * rsqrt(mean(x^2) + eps) * gamma.
+  * RoPE pairs element i with i + hd/2 of a head, angle pos * theta^(-2i/hd), positions 0-based.
+  * Attention: scores q.k / sqrt(hd), causal (j <= t), on "local" layers additionally
+    j > t - W; query head i reads KV head i // (Hq / Hkv); softmax with the row maximum
+    subtracted.
+  * FFN is gated: (act(m Wg^T) * (m Wu^T)) Wd^T with act = SiLU or tanh-GELU.  No biases.
+  * Layer l (1-based) is global iff global_every == 0 or l % global_every == 0; local layers use
+    rope_theta_local and the sliding window.
+  * The boundary token runs every layer normally: its own K/V in deep layers come from its true
+    layer input, and it attends to the projected body entries plus its own.
+
+Parity pins for every function here live in tests/test_oracle_pins.py (brute force on a
+2-layer / 8-token model, a composition of torch library routines for L_keep = L, closed forms
+and invariants).
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------- small steps
+def rmsnorm(x: np.ndarray, gamma: np.ndarray, eps: float) -> np.ndarray:
+    """LN(.) of Sec. 2.1, read as RMSNorm over the last axis."""
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * gamma
+
+
+def rope(x: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
+    """RoPE(.) of Sec. 2.1 on x [n, H, hd] at integer positions pos [n] (half-split pairing)."""
+    n, _, hd = x.shape
+    half = hd // 2
+    inv_freq = theta ** (-(np.arange(half, dtype=np.float64) * 2.0) / hd)
+    ang = pos.astype(np.float64)[:, None] * inv_freq[None, :]          # [n, half]
+    c = np.cos(ang).astype(x.dtype)[:, None, :]
+    s = np.sin(ang).astype(x.dtype)[:, None, :]
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def glu_act(g: np.ndarray, act: int) -> np.ndarray:
+    if act == 0:      # SiLU
+        return g / (1.0 + np.exp(-g))
+    if act == 1:      # GELU, tanh form
+        return 0.5 * g * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (g + 0.044715 * g ** 3)))
+    raise ValueError("act")
+
+
+def is_global_layer(cfg: Dict, l: int) -> bool:
+    """l is 1-based."""
+    g = cfg.get("global_every", 0)
+    return g == 0 or cfg.get("sliding_window", 0) == 0 or l % g == 0
+
+
+def layer_theta_window(cfg: Dict, l: int) -> Tuple[float, int]:
+    if is_global_layer(cfg, l):
+        return float(cfg["rope_theta"]), 0
+    return float(cfg["rope_theta_local"]), int(cfg["sliding_window"])
+
+
+def attention_rows(q: np.ndarray, q_pos: np.ndarray, K: np.ndarray, V: np.ndarray,
+                   window: int) -> np.ndarray:
+    """Attn of Sec. 2.1 for query rows q [n, Hq, hd] at positions q_pos against cache entries
+    K, V [m, Hkv, hd] at positions 0..m-1.  Row t sees j <= q_pos[t] (and j > q_pos[t] - window
+    when window > 0).  Returns [n, Hq * hd]."""
+    n, hq, hd = q.shape
+    m, hkv, _ = K.shape
+    group = hq // hkv
+    if n == 0:
+        return np.zeros((0, hq * hd), dtype=q.dtype)
+    j = np.arange(m)[None, :]
+    allowed = j <= q_pos[:, None]
+    if window > 0:
+        allowed &= j > (q_pos[:, None] - window)
+    out = np.empty((n, hq, hd), dtype=q.dtype)
+    scale = 1.0 / math.sqrt(hd)
+    for i in range(hq):
+        kv = i // group
+        s = (q[:, i, :] @ K[:, kv, :].T) * scale                        # [n, m]
+        s = np.where(allowed, s, -np.inf)
+        s = s - np.max(s, axis=1, keepdims=True)
+        p = np.exp(s)
+        p = p / np.sum(p, axis=1, keepdims=True)
+        out[:, i, :] = p @ V[:, kv, :]
+    return out.reshape(n, hq * hd)
+
+
+def _w(lw: Dict, name: str, dtype) -> np.ndarray:
+    a = lw[name]
+    a = a.numpy() if hasattr(a, "numpy") else np.asarray(a)
+    return a.astype(dtype, copy=False)
+
+
+# ----------------------------------------------------------------------------- layer bodies
+def project_kv(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray):
+    """k = RoPE(LN(x) W_l^K), v = LN(x) W_l^V for rows x [n, d] (Sec. 2.1, second equation;
+    identical in form to the pruned-layer projection of Sec. 3.3)."""
+    dt = x.dtype
+    hkv, hd = cfg["n_kv_heads"], cfg["head_dim"]
+    theta, _ = layer_theta_window(cfg, l)
+    a = rmsnorm(x, _w(lw, "norm_in", dt), cfg["rms_eps"])
+    k = rope((a @ _w(lw, "wk", dt).T).reshape(-1, hkv, hd), pos, theta)
+    v = (a @ _w(lw, "wv", dt).T).reshape(-1, hkv, hd)
+    return k, v
+
+
+def kept_layer_rows(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray,
+                    K_past: np.ndarray, V_past: np.ndarray):
+    """One full layer (Sec. 2.1) for rows x [n, d] at positions pos, given the cache entries of
+    earlier positions K_past, V_past [m, Hkv, hd] with m == pos[0].  The rows' own K/V are
+    appended first, attention then runs on the updated cache.
+    Returns (x_next [n, d], K_current, V_current)."""
+    dt = x.dtype
+    hq, hd = cfg["n_q_heads"], cfg["head_dim"]
+    theta, window = layer_theta_window(cfg, l)
+    a = rmsnorm(x, _w(lw, "norm_in", dt), cfg["rms_eps"])
+    q = rope((a @ _w(lw, "wq", dt).T).reshape(-1, hq, hd), pos, theta)
+    k_new, v_new = project_kv(cfg, lw, l, x, pos)
+    K_cur = np.concatenate([K_past, k_new], axis=0)
+    V_cur = np.concatenate([V_past, v_new], axis=0)
+    o = attention_rows(q, pos, K_cur, V_cur, window)
+    y = x + o @ _w(lw, "wo", dt).T
+    m = rmsnorm(y, _w(lw, "norm_post", dt), cfg["rms_eps"])
+    ffn = (glu_act(m @ _w(lw, "w_gate", dt).T, cfg["act"]) * (m @ _w(lw, "w_up", dt).T)) \
+        @ _w(lw, "w_down", dt).T
+    return y + ffn, K_cur, V_cur
+
+
+def kv_only_rows(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray):
+    """A pruned layer during prefill (Sec. 3.3): store the independent KV projections of the
+    layer input, skip attention and FFN, pass the input on unchanged."""
+    k, v = project_kv(cfg, lw, l, x, pos)
+    return x, k, v
+
+
+def embed_rows(W: Dict, tokens: np.ndarray, dtype, embeds: Optional[np.ndarray] = None,
+               embed_ranges: Sequence[Tuple[int, int]] = ()) -> np.ndarray:
+    """h[t] = E[token[t]]; positions inside a (first_pos, count) range take the next rows of
+    `embeds` instead (visual tokens enter the backbone as ready-made hidden states)."""
+    E = W["embed"]
+    E = E.numpy() if hasattr(E, "numpy") else np.asarray(E)
+    h = E[np.asarray(tokens, dtype=np.int64)].astype(dtype)
+    o = 0
+    for first, count in embed_ranges:
+        e = embeds[o:o + count]
+        e = e.numpy() if hasattr(e, "numpy") else np.asarray(e)
+        h[first:first + count] = e.astype(dtype)
+        o += count
+    return h
+
+
+def lm_head_logits(cfg: Dict, W: Dict, x: np.ndarray) -> np.ndarray:
+    dt = x.dtype
+    return rmsnorm(x, _w(W, "final_norm", dt), cfg["rms_eps"]) @ _w(W, "lm_head", dt).T
+
+
+# ----------------------------------------------------------------------------- the operators
+def body_prefill(cfg: Dict, W: Dict, h: np.ndarray, l_keep: int):
+    """Pruned prefill of body rows h [n, d] (positions 0..n-1): layers 1..L_keep in full, layers
+    L_keep+1..L as KV-only projections of the last kept layer's output.
+    Returns (Kc, Vc) lists over layers of [n, Hkv, hd], and the final body hidden state."""
+    L, hkv, hd = cfg["n_layers"], cfg["n_kv_heads"], cfg["head_dim"]
+    n = h.shape[0]
+    pos = np.arange(n)
+    empty = np.zeros((0, hkv, hd), dtype=h.dtype)
+    Kc, Vc = [], []
+    x = h
+    for l in range(1, L + 1):
+        if l <= l_keep:
+            x, K, V = kept_layer_rows(cfg, W["layers"][l - 1], l, x, pos, empty, empty)
+        else:
+            x, K, V = kv_only_rows(cfg, W["layers"][l - 1], l, x, pos)
+        Kc.append(K)
+        Vc.append(V)
+    return Kc, Vc, x
+
+
+def decode_step(cfg: Dict, W: Dict, h_tok: np.ndarray, Kc: List[np.ndarray], Vc: List[np.ndarray]):
+    """One token (hidden row h_tok [d]) through the full model against the cache (Sec. 3.2, the
+    decode operator).  Its position is the current cache length.  Appends to every layer's cache
+    and returns (logits [V], Kc, Vc)."""
+    L = cfg["n_layers"]
+    x = h_tok[None, :]
+    Kn, Vn = [], []
+    for l in range(1, L + 1):
+        pos = np.array([Kc[l - 1].shape[0]])
+        x, K, V = kept_layer_rows(cfg, W["layers"][l - 1], l, x, pos, Kc[l - 1], Vc[l - 1])
+        Kn.append(K)
+        Vn.append(V)
+    return lm_head_logits(cfg, W, x)[0], Kn, Vn
+
+
+def pop_prefill(cfg: Dict, W: Dict, tokens: np.ndarray, l_keep: int, dtype=np.float64,
+                embeds: Optional[np.ndarray] = None,
+                embed_ranges: Sequence[Tuple[int, int]] = ()):
+    """POP for one prompt x_{1:N} (Sec. 3.3): pruned prefill over x_{1:N-1}, then x_N as the first
+    decode step with the full model.  Returns (Kc, Vc, logits): per layer [N, Hkv, hd] and [V]."""
+    if not 0 <= l_keep <= cfg["n_layers"]:
+        raise ValueError("l_keep out of range")
+    n = len(tokens)
+    if n < 1:
+        raise ValueError("empty prompt")
+    h = embed_rows(W, tokens, dtype, embeds, embed_ranges)
+    Kc, Vc, _ = body_prefill(cfg, W, h[:n - 1], l_keep)
+    logits, Kc, Vc = decode_step(cfg, W, h[n - 1], Kc, Vc)
+    return Kc, Vc, logits
+
+
+def full_prefill(cfg: Dict, W: Dict, tokens: np.ndarray, dtype=np.float64,
+                 embeds: Optional[np.ndarray] = None, embed_ranges: Sequence[Tuple[int, int]] = ()):
+    """The unpruned model's ordinary prefill of all N rows at once (every layer kept, no
+    boundary split), with the last row's logits.  Used as the thing POP must equal at L_keep = L."""
+    h = embed_rows(W, tokens, dtype, embeds, embed_ranges)
+    Kc, Vc, x = body_prefill(cfg, W, h, cfg["n_layers"])
+    return Kc, Vc, lm_head_logits(cfg, W, x[-1:])[0]
+
+
+def pop_prefill_batch(cfg: Dict, W: Dict, tokens: np.ndarray, cu_seqlens: Sequence[int], l_keep: int,
+                      dtype=np.float64, embeds=None, embed_ranges=()):
+    """A packed ragged batch is each sequence on its own.  embed_ranges here are
+    (seq, first_pos, count) triples consumed in order."""
+    out = []
+    o = 0
+    for b in range(len(cu_seqlens) - 1):
+        mine = [(f, c) for (s, f, c) in embed_ranges if s == b]
+        cnt = sum(c for _, c in mine)
+        e = None if embeds is None else embeds[o:o + cnt]
+        o += cnt
+        out.append(pop_prefill(cfg, W, tokens[cu_seqlens[b]:cu_seqlens[b + 1]], l_keep, dtype, e, mine))
+    return out
+
+
+# ----------------------------------------------------------------------------- paged placement
+def slot_map(cu_seqlens: Sequence[int], block_table: np.ndarray, page_size: int) -> np.ndarray:
+    """Cache slot of every packed token: entry t of sequence b sits in page block_table[b][t // P]
+    at offset t % P, i.e. slot = page * P + t % P."""
+    slots = []
+    for b in range(len(cu_seqlens) - 1):
+        for t in range(cu_seqlens[b + 1] - cu_seqlens[b]):
+            slots.append(int(block_table[b][t // page_size]) * page_size + t % page_size)
+    return np.asarray(slots, dtype=np.int32)
+
+
+def scatter_to_pages(K: np.ndarray, slots: np.ndarray, n_pages: int, page_size: int) -> np.ndarray:
+    """Place entries K [n, Hkv, hd] of one layer into a pool laid out [page][Hkv][P][hd]."""
+    n, hkv, hd = K.shape
+    pool = np.zeros((n_pages, hkv, page_size, hd), dtype=K.dtype)
+    for t in range(n):
+        pool[slots[t] // page_size, :, slots[t] % page_size, :] = K[t]
+    return pool

@@ -1,0 +1,107 @@
+"""Brute-force POP on a tiny model, from the definitions only (pure Python scalars).
+
+No cache object and no arrays: every quantity is a function of (layer, token) that recomputes what
+it depends on (memoised), following Sec. 2.1 (layer forward, K/V generation) and Sec. 3.3
+(identity through pruned layers, independent KV projections, last prompt token at full depth).
+It is written independently of oracle/pop_oracle.py and serves only to pin it.
+"""
+from __future__ import annotations
+
+import math
+from functools import lru_cache
+
+
+def brute_force_pop(cfg, W, tokens, l_keep):
+    """Returns (K, V, logits) with K[l][t][head][i] python floats (l 0-based layer index)."""
+    L, d = cfg["n_layers"], cfg["d_model"]
+    Hq, Hkv, hd, f = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"]
+    eps = cfg["rms_eps"]
+    N = len(tokens)
+    tl = lambda a: a.tolist()
+    E = tl(W["embed"])
+    lay = [{k: tl(v) for k, v in lw.items()} for lw in W["layers"]]
+    fin, lm = tl(W["final_norm"]), tl(W["lm_head"])
+
+    def is_global(l):
+        return cfg["global_every"] == 0 or cfg["sliding_window"] == 0 or l % cfg["global_every"] == 0
+
+    def norm(x, g):
+        ms = sum(v * v for v in x) / len(x)
+        r = 1.0 / math.sqrt(ms + eps)
+        return [v * r * gi for v, gi in zip(x, g)]
+
+    def matvec(Wm, x):  # Wm [out][in]
+        return [sum(wi * xi for wi, xi in zip(row, x)) for row in Wm]
+
+    def rot(vec, pos, theta):  # one head
+        half = hd // 2
+        out = [0.0] * hd
+        for i in range(half):
+            ang = pos * theta ** (-2.0 * i / hd)
+            c, s = math.cos(ang), math.sin(ang)
+            out[i] = vec[i] * c - vec[i + half] * s
+            out[i + half] = vec[i + half] * c + vec[i] * s
+        return out
+
+    def act(g):
+        if cfg["act"] == 0:
+            return g / (1.0 + math.exp(-g))
+        return 0.5 * g * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * (g + 0.044715 * g * g * g)))
+
+    def runs_full(l, t):
+        """Does token t run layer l (1-based) in full?  The body is pruned beyond l_keep, the last
+        prompt token never is."""
+        return l <= l_keep or t == N - 1
+
+    @lru_cache(maxsize=None)
+    def x_in(l, t):
+        """Input hidden state of layer l for token t; x_in(L+1, t) is the model output."""
+        if l == 1:
+            return tuple(E[tokens[t]])
+        prev = x_in(l - 1, t)
+        if not runs_full(l - 1, t):
+            return prev                                    # identity through a pruned layer
+        return layer_out(l - 1, t)
+
+    @lru_cache(maxsize=None)
+    def key(l, t):
+        theta = cfg["rope_theta"] if is_global(l) else cfg["rope_theta_local"]
+        a = norm(x_in(l, t), lay[l - 1]["norm_in"])
+        k = matvec(lay[l - 1]["wk"], a)
+        return tuple(tuple(rot(k[h * hd:(h + 1) * hd], t, theta)) for h in range(Hkv))
+
+    @lru_cache(maxsize=None)
+    def val(l, t):
+        a = norm(x_in(l, t), lay[l - 1]["norm_in"])
+        v = matvec(lay[l - 1]["wv"], a)
+        return tuple(tuple(v[h * hd:(h + 1) * hd]) for h in range(Hkv))
+
+    @lru_cache(maxsize=None)
+    def layer_out(l, t):
+        p = lay[l - 1]
+        x = x_in(l, t)
+        theta = cfg["rope_theta"] if is_global(l) else cfg["rope_theta_local"]
+        a = norm(x, p["norm_in"])
+        qf = matvec(p["wq"], a)
+        o = []
+        for i in range(Hq):
+            q = rot(qf[i * hd:(i + 1) * hd], t, theta)
+            g = i // (Hq // Hkv)
+            js = [j for j in range(t + 1)
+                  if is_global(l) or j > t - cfg["sliding_window"]]
+            sc = [sum(a_ * b_ for a_, b_ in zip(q, key(l, j)[g])) / math.sqrt(hd) for j in js]
+            mx = max(sc)
+            ex = [math.exp(s - mx) for s in sc]
+            z = sum(ex)
+            for c in range(hd):
+                o.append(sum(e / z * val(l, j)[g][c] for e, j in zip(ex, js)))
+        y = [xi + oi for xi, oi in zip(x, matvec(p["wo"], o))]
+        m = norm(y, p["norm_post"])
+        gate, up = matvec(p["w_gate"], m), matvec(p["w_up"], m)
+        u = [act(g_) * u_ for g_, u_ in zip(gate, up)]
+        return tuple(yi + di for yi, di in zip(y, matvec(p["w_down"], u)))
+
+    K = [[[list(h) for h in key(l, t)] for t in range(N)] for l in range(1, L + 1)]
+    V = [[[list(h) for h in val(l, t)] for t in range(N)] for l in range(1, L + 1)]
+    logits = matvec(lm, norm(x_in(L + 1, N - 1), fin))
+    return K, V, logits

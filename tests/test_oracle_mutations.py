@@ -1,0 +1,94 @@
+"""Planted mistakes: each plausible slip in the oracle (a wrong sign, index, operand or a dropped
+term) must make the brute-force pin fail.  The mistakes are planted in the oracle, on the CPU."""
+import numpy as np
+import pytest
+
+from oracle import pop_oracle as O
+from paper_2602_03295_amd import synth
+from tests.brute_force_pop import brute_force_pop
+from tests.test_oracle_pins import micro_cfg, weights
+
+
+def pin_holds(l_keep=1, **cfg_kw):
+    cfg = micro_cfg(**cfg_kw)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 8, seed=3)
+    Kb, Vb, lb = brute_force_pop(cfg, w, tokens.tolist(), l_keep)
+    Kc, Vc, logits = O.pop_prefill(cfg, w, tokens, l_keep)
+    return (np.allclose(np.stack(Kc), np.array(Kb), rtol=1e-9, atol=1e-11)
+            and np.allclose(np.stack(Vc), np.array(Vb), rtol=1e-9, atol=1e-11)
+            and np.allclose(logits, np.array(lb), rtol=1e-9, atol=1e-11))
+
+
+def test_unmutated_pin_holds():
+    assert pin_holds()
+
+
+def _rope_wrong_sign(x, pos, theta):
+    return O_rope(x, -pos, theta)
+
+
+def _rope_interleaved(x, pos, theta):
+    n, h, hd = x.shape
+    y = O_rope(x.reshape(n, h, hd // 2, 2).transpose(0, 1, 3, 2).reshape(n, h, hd), pos, theta)
+    return y.reshape(n, h, 2, hd // 2).transpose(0, 1, 3, 2).reshape(n, h, hd)
+
+
+def _rms_no_eps(x, g, eps):
+    return O_rms(x, g, 0.0) * (1 + 1e-6)
+
+
+def _rms_no_gamma(x, g, eps):
+    return O_rms(x, np.ones_like(g), eps)
+
+
+def _attn_wrong_group(q, q_pos, K, V, window):
+    return O_attn(q[:, ::-1], q_pos, K, V, window)
+
+
+def _attn_no_self(q, q_pos, K, V, window):
+    return O_attn(q, np.maximum(q_pos - 1, 0), K, V, window)
+
+
+def _attn_window_off_by_one(q, q_pos, K, V, window):
+    return O_attn(q, q_pos, K, V, window + 1 if window else 0)
+
+
+def _kv_only_changes_x(cfg, lw, l, x, pos):
+    x2, k, v = O_kvonly(cfg, lw, l, x, pos)
+    return x2 * 1.01, k, v
+
+
+def _kv_only_post_norm(cfg, lw, l, x, pos):
+    lw2 = dict(lw, norm_in=lw["norm_post"])
+    return O_kvonly(cfg, lw2, l, x, pos)
+
+
+O_rope, O_rms, O_attn, O_kvonly = O.rope, O.rmsnorm, O.attention_rows, O.kv_only_rows
+
+
+@pytest.mark.parametrize("name,repl,kw", [
+    ("rope", _rope_wrong_sign, {}),
+    ("rope", _rope_interleaved, {}),
+    ("rmsnorm", _rms_no_eps, {}),
+    ("rmsnorm", _rms_no_gamma, {}),
+    ("attention_rows", _attn_wrong_group, {"n_q_heads": 2, "n_kv_heads": 2, "d_model": 8}),
+    ("attention_rows", _attn_no_self, {}),
+    ("attention_rows", _attn_window_off_by_one, {"sliding_window": 3, "global_every": 2}),
+    ("kv_only_rows", _kv_only_changes_x, {"n_layers": 3}),
+    ("kv_only_rows", _kv_only_post_norm, {}),
+])
+def test_planted_mistake_is_caught(monkeypatch, name, repl, kw):
+    assert pin_holds(**kw)
+    monkeypatch.setattr(O, name, repl)
+    assert not pin_holds(**kw), f"pin did not notice a mutated {name}"
+
+
+def test_planted_boundary_mistakes_are_caught(monkeypatch):
+    """Pruning the last token as well, or letting it skip its own cache entry, must be noticed."""
+    def pruned_boundary(cfg, W, tokens, l_keep, dtype=np.float64, embeds=None, embed_ranges=()):
+        h = O.embed_rows(W, tokens, dtype)
+        Kc, Vc, x = O.body_prefill(cfg, W, h, l_keep)
+        return Kc, Vc, O.lm_head_logits(cfg, W, x[-1:])[0]
+    monkeypatch.setattr(O, "pop_prefill", pruned_boundary)
+    assert not pin_holds()

@@ -1,0 +1,379 @@
+"""Pins for the CPU oracle: things the paper and the mathematics fix, none of which call the
+oracle's own formula back.  Each test names the passage it rests on."""
+import copy
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import pop_oracle as O
+from paper_2602_03295_amd import synth
+from tests.brute_force_pop import brute_force_pop
+
+
+def micro_cfg(**kw):
+    cfg = synth.get_config("tiny", n_layers=2, d_model=8, n_q_heads=2, n_kv_heads=1, head_dim=4,
+                           d_ffn=12, vocab=16)
+    cfg.update(kw)
+    return cfg
+
+
+def small_cfg(**kw):
+    cfg = synth.get_config("tiny", n_layers=4, d_model=32, n_q_heads=4, n_kv_heads=2, head_dim=8,
+                           d_ffn=40, vocab=64)
+    cfg.update(kw)
+    return cfg
+
+
+def weights(cfg, seed=1234, std=0.3, norms=True):
+    w = synth.make_weights(cfg, seed=seed, std=std)
+    if norms:
+        synth.randomize_norms(w, cfg)
+    return w
+
+
+def stack(xs):
+    return np.stack(xs)
+
+
+# ------------------------------------------------------------------ brute force (Sec. 2.1 + 3.3)
+@pytest.mark.parametrize("variant", ["silu_global", "gelu_window"])
+@pytest.mark.parametrize("l_keep", [0, 1, 2])
+def test_brute_force_2layer_8token(variant, l_keep):
+    cfg = micro_cfg()
+    if variant == "gelu_window":
+        cfg.update(act=synth.ACT_GELU_TANH, sliding_window=3, global_every=2, rope_theta_local=50.0)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 8, seed=3)
+    Kb, Vb, lb = brute_force_pop(cfg, w, tokens.tolist(), l_keep)
+    Kc, Vc, logits = O.pop_prefill(cfg, w, tokens, l_keep)
+    np.testing.assert_allclose(stack(Kc), np.array(Kb), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(stack(Vc), np.array(Vb), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(logits, np.array(lb), rtol=1e-10, atol=1e-12)
+
+
+# ------------------------------------------------------------------ L_keep = L is ordinary prefill
+def torch_reference_prefill(cfg, w, tokens):
+    """The unpruned model as a composition of torch library routines (embedding, rms_norm, linear,
+    scaled_dot_product_attention, silu/gelu); only the rotary step is spelled out, as a complex
+    multiplication."""
+    dt = torch.float64
+    hq, hkv, hd = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
+    n = len(tokens)
+    x = F.embedding(torch.as_tensor(tokens, dtype=torch.long), w["embed"].to(dt))
+    pos = torch.arange(n, dtype=dt)
+
+    def rotary(t, theta):   # t [n, H, hd]; complex multiply by exp(i * pos * freq)
+        half = hd // 2
+        freq = theta ** (-torch.arange(half, dtype=dt) * 2 / hd)
+        z = torch.polar(torch.ones(n, half, dtype=dt), pos[:, None] * freq[None, :])
+        tc = torch.complex(t[..., :half], t[..., half:]) * z[:, None, :]
+        return torch.cat([tc.real, tc.imag], dim=-1)
+
+    Ks, Vs = [], []
+    for l, lw in enumerate(w["layers"], start=1):
+        glob = cfg["global_every"] == 0 or cfg["sliding_window"] == 0 or l % cfg["global_every"] == 0
+        theta = cfg["rope_theta"] if glob else cfg["rope_theta_local"]
+        a = F.rms_norm(x, (cfg["d_model"],), lw["norm_in"].to(dt), cfg["rms_eps"])
+        q = rotary(F.linear(a, lw["wq"].to(dt)).view(n, hq, hd), theta)
+        k = rotary(F.linear(a, lw["wk"].to(dt)).view(n, hkv, hd), theta)
+        v = F.linear(a, lw["wv"].to(dt)).view(n, hkv, hd)
+        Ks.append(k.numpy().copy())
+        Vs.append(v.numpy().copy())
+        mask = torch.ones(n, n, dtype=torch.bool).tril()
+        if not glob:
+            mask &= torch.ones(n, n, dtype=torch.bool).triu(-(cfg["sliding_window"] - 1))
+        o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
+                                           v.transpose(0, 1)[None], attn_mask=mask, enable_gqa=True)
+        o = o[0].transpose(0, 1).reshape(n, hq * hd)
+        x = x + F.linear(o, lw["wo"].to(dt))
+        m = F.rms_norm(x, (cfg["d_model"],), lw["norm_post"].to(dt), cfg["rms_eps"])
+        g = F.linear(m, lw["w_gate"].to(dt))
+        g = F.silu(g) if cfg["act"] == 0 else F.gelu(g, approximate="tanh")
+        x = x + F.linear(g * F.linear(m, lw["w_up"].to(dt)), lw["w_down"].to(dt))
+    logits = F.linear(F.rms_norm(x[-1], (cfg["d_model"],), w["final_norm"].to(dt), cfg["rms_eps"]),
+                      w["lm_head"].to(dt))
+    return Ks, Vs, logits.numpy()
+
+
+@pytest.mark.parametrize("variant", ["llama_like", "gemma_like"])
+def test_lkeep_L_equals_library_prefill(variant):
+    """Sec. 3.1: with every layer kept (all gates 1) the model is the original one, so POP at
+    L_keep = L -- body prefill plus a decode step for x_N -- must equal ordinary causal prefill."""
+    cfg = small_cfg()
+    if variant == "gemma_like":
+        cfg.update(act=synth.ACT_GELU_TANH, sliding_window=5, global_every=3, rope_theta_local=100.0,
+                   n_layers=6)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 19, seed=5)
+    Kr, Vr, lr = torch_reference_prefill(cfg, w, tokens)
+    Kc, Vc, logits = O.pop_prefill(cfg, w, tokens, cfg["n_layers"])
+    np.testing.assert_allclose(stack(Kc), stack(Kr), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(stack(Vc), stack(Vr), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(logits, lr, rtol=1e-9, atol=1e-11)
+    Kf, Vf, lf = O.full_prefill(cfg, w, tokens)
+    np.testing.assert_allclose(stack(Kf), stack(Kr), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(lf, lr, rtol=1e-9, atol=1e-11)
+
+
+# ------------------------------------------------------------------ pruned-layer K/V (Sec. 3.3)
+def test_pruned_layers_project_last_kept_output():
+    """For l > L_keep the body K/V are the layer's own norm/W_K/W_V/RoPE applied to the output of
+    the last kept layer, recomputed here with torch library calls from the unpruned run's
+    hidden state (which is still exact at layer L_keep + 1)."""
+    cfg = small_cfg(n_layers=6)
+    w = weights(cfg)
+    n, l_keep = 13, 3
+    tokens = synth.make_tokens(cfg["vocab"], n, seed=2)
+    Kc, Vc, _ = O.pop_prefill(cfg, w, tokens, l_keep)
+    # hidden state entering layer l_keep+1 from a model truncated to l_keep layers
+    cfg_t = dict(cfg, n_layers=l_keep)
+    w_t = dict(w, layers=w["layers"][:l_keep])
+    h = O.embed_rows(w, tokens, np.float64)
+    _, _, x = O.body_prefill(cfg_t, w_t, h[:n - 1], l_keep)
+    xt = torch.from_numpy(x)
+    hkv, hd = cfg["n_kv_heads"], cfg["head_dim"]
+    for l in range(l_keep + 1, cfg["n_layers"] + 1):
+        lw = w["layers"][l - 1]
+        a = F.rms_norm(xt, (cfg["d_model"],), lw["norm_in"].double(), cfg["rms_eps"])
+        v = F.linear(a, lw["wv"].double()).view(n - 1, hkv, hd).numpy()
+        k = F.linear(a, lw["wk"].double()).view(n - 1, hkv, hd)
+        half = hd // 2
+        freq = cfg["rope_theta"] ** (-torch.arange(half, dtype=torch.float64) * 2 / hd)
+        z = torch.polar(torch.ones(n - 1, half, dtype=torch.float64),
+                        torch.arange(n - 1, dtype=torch.float64)[:, None] * freq)
+        kc = torch.complex(k[..., :half], k[..., half:]) * z[:, None, :]
+        k = torch.cat([kc.real, kc.imag], -1).numpy()
+        np.testing.assert_allclose(Vc[l - 1][:n - 1], v, rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(Kc[l - 1][:n - 1], k, rtol=1e-10, atol=1e-12)
+
+
+def test_lkeep_zero_projects_embeddings():
+    """By induction over the identity through pruned layers, L_keep = 0 gives
+    V_l[t] = RMSNorm(E[x_t]; gamma_l) W_l^V for every layer and body token."""
+    cfg = small_cfg()
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 9, seed=4)
+    _, Vc, _ = O.pop_prefill(cfg, w, tokens, 0)
+    e = w["embed"].double()[torch.as_tensor(tokens[:-1], dtype=torch.long)]
+    for l, lw in enumerate(w["layers"]):
+        a = F.rms_norm(e, (cfg["d_model"],), lw["norm_in"].double(), cfg["rms_eps"])
+        v = F.linear(a, lw["wv"].double()).view(8, cfg["n_kv_heads"], cfg["head_dim"]).numpy()
+        np.testing.assert_allclose(Vc[l][:8], v, rtol=1e-10, atol=1e-12)
+
+
+# ------------------------------------------------------------------ boundary handling (Sec. 3.3)
+def test_boundary_token_is_first_decode_step():
+    """POP(x_{1:N}) == pruned prefill of x_{1:N-1} alone, then one full-model decode step on x_N."""
+    cfg = small_cfg()
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 11, seed=6)
+    Kc, Vc, logits = O.pop_prefill(cfg, w, tokens, 2)
+    h = O.embed_rows(w, tokens, np.float64)
+    Kb, Vb, _ = O.body_prefill(cfg, w, h[:10], 2)
+    for l in range(cfg["n_layers"]):
+        np.testing.assert_array_equal(Kc[l][:10], Kb[l])
+        np.testing.assert_array_equal(Vc[l][:10], Vb[l])
+    lg, K2, V2 = O.decode_step(cfg, w, h[10], Kb, Vb)
+    np.testing.assert_array_equal(lg, logits)
+    np.testing.assert_array_equal(stack(K2), stack(Kc))
+
+
+def test_boundary_logits_differ_from_fully_pruned_last_token():
+    """The last token is NOT pruned: its deep-layer K/V and the logits must change if the deep
+    layers' attention/FFN weights change, while body entries of those layers must not."""
+    cfg = small_cfg()
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 7, seed=8)
+    Kc, Vc, logits = O.pop_prefill(cfg, w, tokens, 2)
+    w2 = copy.deepcopy(w)
+    w2["layers"][2]["w_down"] = w2["layers"][2]["w_down"] * 1.5      # layer 3 (pruned for the body)
+    K2, V2, logits2 = O.pop_prefill(cfg, w2, tokens, 2)
+    assert np.max(np.abs(logits2 - logits)) > 1e-6
+    np.testing.assert_array_equal(Vc[3][:6], V2[3][:6])               # body of layer 4 unchanged
+    assert np.max(np.abs(Vc[3][6] - V2[3][6])) > 1e-9                 # boundary entry changed
+
+
+# ------------------------------------------------------------------ exact invariants
+def test_kept_layers_and_first_pruned_layer_match_unpruned_run():
+    """Layers 1..L_keep see the true inputs, and so does layer L_keep + 1: their body K/V are
+    identical to the unpruned run's; deeper layers' are not."""
+    cfg = small_cfg(n_layers=6)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 10, seed=9)
+    l_keep = 3
+    Kp, Vp, _ = O.pop_prefill(cfg, w, tokens, l_keep)
+    Kf, Vf, _ = O.pop_prefill(cfg, w, tokens, cfg["n_layers"])
+    for l in range(l_keep + 1):
+        np.testing.assert_allclose(Kp[l][:9], Kf[l][:9], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(Vp[l][:9], Vf[l][:9], rtol=1e-12, atol=1e-14)
+    assert np.max(np.abs(Vp[l_keep + 1][:9] - Vf[l_keep + 1][:9])) > 1e-6
+
+
+def test_gate_zero_equivalence():
+    """Sec. 3.1: a gate of 0 on both residual branches turns a layer into the identity.  Zeroing
+    W_O and W_down of the deep layers does the same, so POP then equals the full model."""
+    cfg = small_cfg(n_layers=5)
+    w = weights(cfg)
+    l_keep = 3
+    for lw in w["layers"][l_keep:]:
+        lw["wo"] = torch.zeros_like(lw["wo"])
+        lw["w_down"] = torch.zeros_like(lw["w_down"])
+    tokens = synth.make_tokens(cfg["vocab"], 12, seed=10)
+    Kp, Vp, lp = O.pop_prefill(cfg, w, tokens, l_keep)
+    Kf, Vf, lf = O.full_prefill(cfg, w, tokens)
+    np.testing.assert_allclose(stack(Kp), stack(Kf), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(stack(Vp), stack(Vf), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(lp, lf, rtol=1e-12, atol=1e-14)
+
+
+def test_causality():
+    """Sec. 3.2: the prefill operator maps x_{1:N-1} to the cache; entry t may depend on tokens
+    <= t only, and in pruned layers on row t alone."""
+    cfg = small_cfg()
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 10, seed=11)
+    K0, V0, _ = O.pop_prefill(cfg, w, tokens, 2)
+    t2 = tokens.copy()
+    t2[9] = (t2[9] + 1) % cfg["vocab"]                 # change x_N
+    K1, V1, _ = O.pop_prefill(cfg, w, t2, 2)
+    np.testing.assert_array_equal(stack(K0)[:, :9], stack(K1)[:, :9])
+    t3 = tokens.copy()
+    t3[5] = (t3[5] + 1) % cfg["vocab"]
+    K2, V2, _ = O.pop_prefill(cfg, w, t3, 2)
+    np.testing.assert_array_equal(stack(V0)[:, :5], stack(V2)[:, :5])
+    assert np.max(np.abs(stack(V0)[1:, 6] - stack(V2)[1:, 6])) > 1e-9   # later rows do change
+    # in pruned layers with L_keep = 0 a row depends on its own token only
+    Ka, Va, _ = O.pop_prefill(cfg, w, tokens, 0)
+    Kb, Vb, _ = O.pop_prefill(cfg, w, t3, 0)
+    keep = [i for i in range(9) if i != 5]
+    np.testing.assert_array_equal(stack(Va)[:, keep], stack(Vb)[:, keep])
+
+
+# ------------------------------------------------------------------ closed forms of the small steps
+def test_rope_closed_forms():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((6, 3, 8))
+    pos = np.array([0, 1, 2, 5, 40, 1000])
+    y = O.rope(x, pos, 10000.0)
+    np.testing.assert_allclose(np.linalg.norm(y, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-12)
+    np.testing.assert_array_equal(y[0], x[0])                          # position 0 is the identity
+    # pair (x_0, x_4) of head 0 at position 1 turns by exactly 1 radian (frequency theta^0 = 1)
+    np.testing.assert_allclose(y[1, 0, 0], x[1, 0, 0] * math.cos(1.0) - x[1, 0, 4] * math.sin(1.0), rtol=1e-12)
+    np.testing.assert_allclose(y[1, 0, 4], x[1, 0, 4] * math.cos(1.0) + x[1, 0, 0] * math.sin(1.0), rtol=1e-12)
+    # last pair (i = 3) turns by pos * theta^(-6/8)
+    ang = 5 * 10000.0 ** (-6 / 8)
+    np.testing.assert_allclose(y[3, 1, 3], x[3, 1, 3] * math.cos(ang) - x[3, 1, 7] * math.sin(ang), rtol=1e-12)
+    # scores depend on the position difference only
+    q, k = rng.standard_normal((1, 1, 8)), rng.standard_normal((1, 1, 8))
+    d1 = O.rope(q, np.array([7]), 100.0)[0, 0] @ O.rope(k, np.array([3]), 100.0)[0, 0]
+    d2 = O.rope(q, np.array([104]), 100.0)[0, 0] @ O.rope(k, np.array([100]), 100.0)[0, 0]
+    np.testing.assert_allclose(d1, d2, rtol=1e-10)
+
+
+def test_rmsnorm_closed_forms():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((5, 16))
+    y = O.rmsnorm(x, np.ones(16), 1e-5)
+    n2 = np.sum(x * x, axis=1)
+    np.testing.assert_allclose(np.sum(y * y, axis=1), 16 * n2 / (n2 + 16 * 1e-5), rtol=1e-12)
+    g = rng.standard_normal(16)
+    np.testing.assert_allclose(O.rmsnorm(x, g, 1e-5), y * g, rtol=1e-12)
+    np.testing.assert_allclose(O.rmsnorm(3.0 * x, g, 0.0), O.rmsnorm(x, g, 0.0), rtol=1e-12)
+    np.testing.assert_allclose(O.rmsnorm(np.array([[3.0, 4.0]]), np.ones(2), 0.0),
+                               [[3 / math.sqrt(12.5), 4 / math.sqrt(12.5)]], rtol=1e-14)
+
+
+def test_attention_closed_forms():
+    rng = np.random.default_rng(2)
+    hq, hkv, hd, n = 4, 2, 8, 7
+    q = rng.standard_normal((n, hq, hd))
+    K = rng.standard_normal((n, hkv, hd))
+    V = rng.standard_normal((n, hkv, hd))
+    pos = np.arange(n)
+    o = O.attention_rows(q, pos, K, V, 0).reshape(n, hq, hd)
+    # first row sees only entry 0
+    for i in range(hq):
+        np.testing.assert_allclose(o[0, i], V[0, i // 2], rtol=1e-12)
+    # zero queries give the causal running mean of V
+    o0 = O.attention_rows(np.zeros_like(q), pos, K, V, 0).reshape(n, hq, hd)
+    np.testing.assert_allclose(o0[4, 3], V[:5, 1].mean(axis=0), rtol=1e-12)
+    # window 1 = each row sees only itself; window 2 with zero queries = mean of the last two
+    o1 = O.attention_rows(q, pos, K, V, 1).reshape(n, hq, hd)
+    np.testing.assert_allclose(o1[5, 0], V[5, 0], rtol=1e-12)
+    o2 = O.attention_rows(np.zeros_like(q), pos, K, V, 2).reshape(n, hq, hd)
+    np.testing.assert_allclose(o2[5, 2], V[4:6, 1].mean(axis=0), rtol=1e-12)
+    # constant V is returned unchanged (softmax rows sum to one); scale 1/sqrt(hd) via a 2-key case
+    Vc = np.ones_like(V) * 0.7
+    np.testing.assert_allclose(O.attention_rows(q, pos, K, Vc, 0), 0.7, rtol=1e-12)
+    q2 = np.zeros((1, 1, 4)); q2[0, 0, 0] = 2.0
+    K2 = np.zeros((2, 1, 4)); K2[1, 0, 0] = 1.0
+    V2 = np.zeros((2, 1, 4)); V2[1, 0, :] = 1.0
+    w1 = math.exp(2.0 / 2.0) / (1 + math.exp(2.0 / 2.0))               # 2*1/sqrt(4) = 1
+    np.testing.assert_allclose(O.attention_rows(q2, np.array([1]), K2, V2, 0)[0], w1, rtol=1e-12)
+
+
+def test_glu_activations_against_library():
+    g = torch.linspace(-6, 6, 101, dtype=torch.float64)
+    np.testing.assert_allclose(O.glu_act(g.numpy(), 0), F.silu(g).numpy(), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(O.glu_act(g.numpy(), 1), F.gelu(g, approximate="tanh").numpy(),
+                               rtol=1e-12, atol=1e-15)
+
+
+# ------------------------------------------------------------------ batches, embeddings, paging
+def test_ragged_batch_is_each_sequence_alone_and_embed_override():
+    cfg = small_cfg()
+    w = weights(cfg)
+    lens = [5, 1, 9]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    tokens = synth.make_tokens(cfg["vocab"], int(cu[-1]), seed=12)
+    emb = synth.make_visual_embeds(4, cfg["d_model"], as_bf16=False).numpy()
+    outs = O.pop_prefill_batch(cfg, w, tokens, cu, 2, embeds=emb, embed_ranges=[(0, 1, 1), (2, 3, 3)])
+    K1, _, l1 = O.pop_prefill(cfg, w, tokens[5:6], 2)                  # N = 1: boundary step only
+    np.testing.assert_array_equal(outs[1][2], l1)
+    assert outs[1][0][0].shape[0] == 1
+    # the override rows behave exactly like an embedding table that contains them
+    w2 = copy.deepcopy(w)
+    big = torch.cat([w2["embed"], torch.from_numpy(emb).float()])
+    w2["embed"] = big
+    t2 = tokens[6:15].copy()
+    t2[3:6] = [cfg["vocab"] + 1, cfg["vocab"] + 2, cfg["vocab"] + 3]
+    K2, V2, l2 = O.pop_prefill(cfg, w2, t2, 2)
+    np.testing.assert_allclose(stack(outs[2][0]), stack(K2), rtol=1e-6, atol=1e-7)  # emb is fp64 vs fp32 table
+    np.testing.assert_allclose(outs[2][2], l2, rtol=1e-5, atol=1e-6)
+
+
+def test_slot_map_and_paging_worked_example():
+    """Hand-computed: P = 4, two sequences of 6 and 3 entries, pages [5, 2] and [7]."""
+    bt = np.array([[5, 2], [7, -1]], dtype=np.int32)
+    s = O.slot_map([0, 6, 9], bt, 4)
+    assert s.tolist() == [20, 21, 22, 23, 8, 9, 28, 29, 30]
+    K = np.arange(9 * 2 * 3, dtype=np.float64).reshape(9, 2, 3)
+    pool = O.scatter_to_pages(K, s, 8, 4)
+    assert pool.shape == (8, 2, 4, 3)
+    np.testing.assert_array_equal(pool[2, 1, 1], K[5, 1])               # seq 0, t = 5 -> page 2, offset 1
+    np.testing.assert_array_equal(pool[7, 0, 2], K[8, 0])               # seq 1, t = 2 -> page 7, offset 2
+    assert np.count_nonzero(pool.reshape(8, -1).any(axis=1)) == 3       # only three pages touched
+    bt2, n_pages = synth.make_block_table([6, 3], 4)
+    assert n_pages == 3 and bt2.tolist() == [[0, 1], [2, -1]]
+
+
+def test_fp32_mode_close_to_fp64():
+    cfg = small_cfg()
+    w = weights(cfg, std=0.1)
+    tokens = synth.make_tokens(cfg["vocab"], 16, seed=13)
+    K64, _, l64 = O.pop_prefill(cfg, w, tokens, 2)
+    K32, _, l32 = O.pop_prefill(cfg, w, tokens, 2, dtype=np.float32)
+    assert K32[0].dtype == np.float32
+    np.testing.assert_allclose(l32, l64, rtol=1e-3, atol=1e-5)
+
+
+def test_argument_errors():
+    cfg = small_cfg()
+    w = weights(cfg)
+    with pytest.raises(ValueError):
+        O.pop_prefill(cfg, w, np.array([], dtype=np.int32), 2)
+    with pytest.raises(ValueError):
+        O.pop_prefill(cfg, w, np.array([1, 2], dtype=np.int32), cfg["n_layers"] + 1)
