@@ -1,0 +1,183 @@
+/*
+ * pop.h -- C ABI of the POP (Prefill-Only Pruning) prefill library for AMD MI355X (gfx950).
+ *
+ * The library computes the pruned prefill forward pass of a decoder-only transformer as defined in
+ * the POP paper, Sec. 3.3 ("Prefill-Only Pruning for Efficient Inference"):
+ *   - layers 1..L_keep run in full for the prompt body (Sec. 2.1, layer forward + K/V generation +
+ *     cache append);
+ *   - layers L_keep+1..L are skipped for the body (identity on the hidden state) but still receive
+ *     their KV-cache entries through the "independent KV projections"
+ *         k_l = RoPE(LN(x_l) W_l^K),  v_l = LN(x_l) W_l^V
+ *     with the layer's own norm scale and projection matrices;
+ *   - the last prompt token of every sequence (the boundary token) is processed at full depth as the
+ *     first decode step ("Boundary Handling for the Last Input Token"), so the first generated
+ *     token's logits come from the whole model.
+ * The decode operator of Sec. 3.2 (one token through all layers against the cache) is exported as
+ * pop_decode_step; it is the same code the boundary token runs.
+ *
+ * Conventions
+ *   Memory     Every DEVICE pointer is caller-owned device memory (weights, cache pool, workspace,
+ *              logits).  The library allocates small host structs only, released by the matching
+ *              pop_free_model / pop_cache_destroy.  HOST pointers are read during the call only.
+ *   Layout     All matrices are row-major [out_features, in_features] (the contraction index is
+ *              contiguous), elements bf16.  Norm scales are fp32 [d_model].
+ *   Errors     Every call returns a pop_status.  Argument errors are detected on the host before
+ *              anything is enqueued and leave cache contents and lengths unchanged;
+ *              pop_last_error() then returns a message (thread-local, static storage).
+ *   Asynchrony On POP_OK the work is enqueued on `stream` (a hipStream_t); outputs are valid once
+ *              the caller has synchronised with it.  Host input arrays may be reused on return.
+ *   Determinism Same inputs give bit-identical outputs (no floating-point atomics).
+ *   Alignment  Device pointers must be 16-byte aligned (256 for the workspace).
+ */
+#ifndef POP_H_
+#define POP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pop_model pop_model; /* opaque host-side handle over caller-owned device weights */
+typedef struct pop_cache pop_cache; /* opaque host-side handle over a caller-owned device pool   */
+typedef void* pop_stream;           /* a hipStream_t (0 = the null stream)                        */
+
+typedef enum {
+  POP_OK = 0,
+  POP_EINVAL = -1,       /* NULL pointer, bad count, bad l_keep, token id out of range, ...        */
+  POP_ESHAPE = -2,       /* model shape the kernels do not cover                                   */
+  POP_EALIGN = -3,       /* misaligned device pointer                                              */
+  POP_ENOSPACE = -4,     /* not enough pages, page-table columns, workspace or pool bytes          */
+  POP_ESTATE = -5,       /* e.g. decode on a sequence that was never prefilled                     */
+  POP_EHIP = -6,         /* a HIP runtime call or launch failed                                    */
+  POP_EUNSUPPORTED = -7  /* valid request the build does not implement (e.g. fp32 weights)         */
+} pop_status;
+
+/* Message of the last failing call on this thread ("" if none).  Never freed by the caller. */
+const char* pop_last_error(void);
+/* Library version string. */
+const char* pop_version(void);
+
+enum { POP_DTYPE_F32 = 0, POP_DTYPE_BF16 = 1 };
+enum { POP_ACT_SILU = 0, POP_ACT_GELU_TANH = 1 };
+
+/* Model shape (Sec. 2.1: L layers, hidden size d, GQA attention block + gated FFN block). */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  int32_t dtype;           /* POP_DTYPE_*; only POP_DTYPE_BF16 is implemented                      */
+  int32_t act;             /* POP_ACT_*: FFN = (act(m Wg^T) * (m Wu^T)) Wd^T                       */
+  float rms_eps;           /* LN(x) = x * rsqrt(mean(x^2) + rms_eps) * gamma                       */
+  float rope_theta;        /* RoPE base of global-attention layers                                 */
+  float rope_theta_local;  /* RoPE base of sliding-window layers                                   */
+  int32_t sliding_window;  /* 0 = none; W > 0: a local layer's row t sees positions t-W+1 .. t     */
+  int32_t global_every;    /* 0 = every layer global; g > 0: 1-based layer l is global iff l%g==0  */
+  int32_t page_size;       /* tokens per KV-cache page, a power of two (16)                        */
+} pop_config;
+
+typedef struct {
+  const void* norm_in;   /* DEVICE fp32 [d]                 input norm scale (the LN of Sec. 2.1)  */
+  const void* wqkv;      /* DEVICE bf16 [Dq + 2 Dkv, d]     rows ordered W^Q | W^K | W^V           */
+  const void* wo;        /* DEVICE bf16 [d, Dq]                                                    */
+  const void* norm_post; /* DEVICE fp32 [d]                 norm in front of the FFN block         */
+  const void* w_gate_up; /* DEVICE bf16 [2 f, d]            rows ordered gate | up                 */
+  const void* w_down;    /* DEVICE bf16 [d, f]                                                     */
+} pop_layer_weights;
+
+typedef struct {
+  const void* embed;               /* DEVICE bf16 [vocab, d]                                       */
+  const void* final_norm;          /* DEVICE fp32 [d]                                              */
+  const void* lm_head;             /* DEVICE bf16 [vocab, d]                                       */
+  const pop_layer_weights* layers; /* HOST array of n_layers entries (copied by pop_load_weights)  */
+} pop_weights;
+
+/*
+ * Validates the shape and records the weight pointers (borrowed: they must outlive the model).
+ * Host-only, enqueues nothing, allocates no device memory.
+ * Errors: POP_EINVAL (NULL, non-positive sizes, Hq % Hkv != 0), POP_ESHAPE (head_dim not in
+ * {64,128,256}, d_model or d_ffn not a multiple of 8, page_size not a power of two in 1..256),
+ * POP_EALIGN, POP_EUNSUPPORTED (dtype).
+ */
+pop_status pop_load_weights(const pop_config* cfg, const pop_weights* w, pop_model** out);
+void pop_free_model(pop_model* m);
+
+/*
+ * KV cache (Sec. 2.1, cache append) stored in pages.  Device layout, bf16:
+ *     pool[layer][kv][page][kv_head][slot_in_page][head_dim],   kv = 0 for K, 1 for V.
+ * Entry t of sequence b lives in page block_table[b][t / P] at offset t % P.
+ */
+size_t pop_cache_bytes(const pop_config* cfg, int32_t n_pages);
+/* Upper bound of the workspace pop_prefill / pop_decode_step need for at most max_tokens packed
+ * tokens in at most max_seqs sequences whose page tables have max_pages_per_seq columns. */
+size_t pop_workspace_bytes(const pop_config* cfg, int32_t max_tokens, int32_t max_seqs,
+                           int32_t max_pages_per_seq);
+/* Wraps a device pool of at least pop_cache_bytes(cfg, n_pages) bytes.  Contents are not touched.
+ * Errors: POP_EINVAL, POP_EALIGN, POP_ENOSPACE (bytes too small). */
+pop_status pop_cache_create(const pop_config* cfg, void* dev_pool, size_t bytes, int32_t n_pages,
+                            int32_t max_seqs, int32_t max_pages_per_seq, pop_cache** out);
+void pop_cache_destroy(pop_cache* c); /* does not free dev_pool */
+/* Number of live sequences and their current lengths (host_out has room for max_seqs values). */
+int32_t pop_cache_n_seqs(const pop_cache* c);
+pop_status pop_cache_seq_lens(const pop_cache* c, int32_t* host_out);
+
+/*
+ * Cache slot of every packed token (integer, host-only):
+ *     slot[cu_seqlens[b] + t] = block_table[b * max_pages_per_seq + t / P] * P + t % P.
+ * This is the function pop_prefill uses for its own addressing.
+ * Errors: POP_EINVAL (NULL, n_seqs < 1, cu_seqlens not starting at 0 / not strictly increasing,
+ * page id outside [0, n_pages), a page used twice), POP_ENOSPACE (a sequence needs more columns
+ * than max_pages_per_seq or reaches an unassigned (negative) entry).
+ */
+pop_status pop_slot_map(const int32_t* host_cu_seqlens, int32_t n_seqs, const int32_t* host_block_table,
+                        int32_t max_pages_per_seq, int32_t page_size, int32_t n_pages,
+                        int32_t* host_slots_out);
+
+typedef struct {
+  const int32_t* tokens;       /* HOST [T] packed token ids of all sequences                        */
+  const int32_t* cu_seqlens;   /* HOST [n_seqs + 1], cu[0] = 0, strictly increasing, cu[n_seqs] = T */
+  int32_t n_seqs;
+  const int32_t* block_table;  /* HOST [n_seqs][max_pages_per_seq] page ids, negative = unassigned;
+                                  must cover every position the sequences will reach, including
+                                  later decode steps                                                */
+  const void* embeds;          /* DEVICE bf16 [sum of counts, d] or NULL: rows that replace the
+                                  embedding lookup (e.g. visual tokens fed as hidden states)        */
+  const int32_t* embed_ranges; /* HOST [n_ranges][3] = (seq, first_pos, count), rows of `embeds`
+                                  consumed in this order; ranges must not overlap                   */
+  int32_t n_ranges;
+  int32_t l_keep;              /* 0 .. n_layers: layers 1..l_keep are kept for the body             */
+  int32_t mode;                /* POP_MODE_POP: the last token of each sequence is the boundary token:
+                                  full depth, logits returned.
+                                  POP_MODE_BODY_ONLY: every given token is a body token (pruned
+                                  beyond l_keep); no logits.  pop_decode_step on the next token then
+                                  completes the same computation.                                   */
+} pop_prefill_args;
+enum { POP_MODE_POP = 0, POP_MODE_BODY_ONLY = 1 };
+
+/*
+ * Pruned prefill (Sec. 3.3).  Starts sequences 0..n_seqs-1 from empty (a cache that was in use is
+ * reset), writes the K/V entries of all n_layers layers for every given token and, in POP mode, the
+ * boundary tokens' next-token logits.
+ *   dev_logits   DEVICE fp32 [n_seqs, vocab]; may be NULL in POP_MODE_BODY_ONLY.
+ *   dev_workspace DEVICE scratch of at least pop_workspace_bytes(cfg, T, n_seqs, max_pages_per_seq).
+ * Errors (all before any launch): POP_EINVAL (NULL, l_keep outside [0, L], n_seqs < 1 or above the
+ * cache's max_seqs, an empty sequence, token id outside [0, vocab), bad embed range), POP_ENOSPACE
+ * (pages, workspace), POP_EALIGN.  POP_EHIP if a launch fails.
+ */
+pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* args, float* dev_logits,
+                       void* dev_workspace, size_t workspace_bytes, pop_stream stream);
+
+/*
+ * One decode step (Sec. 3.2): token host_tokens[b] is appended to sequence b at position len_b, runs
+ * all n_layers layers against the cache, and its next-token logits are written to
+ * dev_logits[b, :] (DEVICE fp32 [n_seqs, vocab]).  n_seqs must equal the cache's live sequences.
+ * Errors: POP_EINVAL, POP_ESTATE (no prefilled sequences), POP_ENOSPACE (a sequence has no page
+ * assigned for position len_b, or workspace too small), POP_EHIP.
+ */
+pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_tokens, int32_t n_seqs,
+                           float* dev_logits, void* dev_workspace, size_t workspace_bytes,
+                           pop_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POP_H_ */

@@ -1,0 +1,47 @@
+/*
+ * pop_ops.h -- single steps of the POP prefill path, exported so that each kernel can be checked
+ * against the same step of a reference implementation and timed on its own.  Same conventions as
+ * pop.h: DEVICE pointers are caller-owned, 16-byte aligned; work is enqueued on `stream`.
+ */
+#ifndef POP_OPS_H_
+#define POP_OPS_H_
+
+#include "pop.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* LN(.) of Sec. 2.1 as RMSNorm: out[r,:] = bf16(x[r,:] * rsqrt(mean(x[r,:]^2) + eps) * gamma).
+ * x DEVICE fp32 [rows, d], gamma DEVICE fp32 [d], out DEVICE bf16 [rows, d]; d % 8 == 0, d <= 8192. */
+pop_status pop_op_rmsnorm(const float* x, const float* gamma, void* out, int32_t rows, int32_t d, float eps,
+                          pop_stream stream);
+
+/* Projection of Sec. 2.1 (Attn / FFN blocks): C = A[M,K] * W[N,K]^T, bf16 inputs, fp32 accumulation.
+ *   epilogue 0: out bf16 [M, ldc] = C          1: out fp32 [M, ldc] += C (residual update)
+ *            2: W is [2N, K] (gate rows, then up rows); out bf16 [M, ldc] = act(gate) * up
+ *            3: out fp32 [M, ldc] = C
+ * Requirements: K, lda, ldw multiples of 8; ldc multiple of 4; operands below 2 GiB each.
+ * Errors: POP_EINVAL / POP_EALIGN / POP_ESHAPE on a violated requirement, POP_EHIP. */
+pop_status pop_op_gemm(const void* A, int64_t lda, const void* W, int64_t ldw, void* out, int64_t ldc,
+                       int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t act, pop_stream stream);
+
+/* Same contraction for M <= 64 rows with the bandwidth-bound kernel of the boundary token
+ * (Sec. 3.3, "Boundary Handling"): epilogue 0: out fp32 = C, 1: out fp32 += C, 2: GLU -> bf16.
+ * Operands are dense (lda = ldw = K). */
+pop_status pop_op_gemv(const void* x, const void* W, void* out, int64_t ldo, int32_t M, int32_t N, int32_t K,
+                       int32_t epilogue, int32_t act, pop_stream stream);
+
+/* RoPE on q and k followed by causal GQA attention (Sec. 2.1: K/V generation and Attn) over packed
+ * sequences.  qkv DEVICE bf16 [T, (Hq + 2 Hkv) * hd], rows q | k | v, q and k are rotated IN PLACE;
+ * out DEVICE bf16 [T, Hq * hd].  host_cu_seqlens HOST [n_seqs + 1].  window 0 = global.
+ * workspace: at least pop_op_rope_attention_workspace(...) bytes. */
+size_t pop_op_rope_attention_workspace(int32_t T, int32_t n_seqs, int32_t n_kv_heads, int32_t head_dim);
+pop_status pop_op_rope_attention(void* qkv, const int32_t* host_cu_seqlens, int32_t n_seqs, int32_t n_q_heads,
+                                 int32_t n_kv_heads, int32_t head_dim, float rope_theta, int32_t window,
+                                 void* out, void* workspace, size_t workspace_bytes, pop_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POP_OPS_H_ */

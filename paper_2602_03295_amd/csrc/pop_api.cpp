@@ -1,0 +1,760 @@
+// Host side of the POP prefill library: argument validation, paged-cache slot mapping, workspace
+// carving and the per-layer launch schedule (kept layers / KV-only layers / boundary rows) behind
+// the C ABI of pop.h.  Everything here is decided before the first launch, so every error path can
+// be exercised without a GPU.
+#include "../../include/pop.h"
+#include "../../include/pop_ops.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "pop_kernels.h"
+
+using pop::bf16_t;
+
+// ----------------------------------------------------------------------------------------- errors
+namespace {
+thread_local std::string g_last_error;
+
+pop_status fail(pop_status st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return st;
+}
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+#define POP_HIP(expr)                                                                              \
+  do {                                                                                             \
+    hipError_t e_ = (expr);                                                                        \
+    if (e_ != hipSuccess) return fail(POP_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));    \
+  } while (0)
+
+pop_status check_config(const pop_config* c) {
+  if (!c) return fail(POP_EINVAL, "config is NULL");
+  if (c->n_layers < 1 || c->d_model < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1 ||
+      c->d_ffn < 1 || c->vocab < 1)
+    return fail(POP_EINVAL, "config has a non-positive size");
+  if (c->n_q_heads % c->n_kv_heads) return fail(POP_EINVAL, "n_q_heads %d is not a multiple of n_kv_heads %d",
+                                                 c->n_q_heads, c->n_kv_heads);
+  if (c->n_q_heads / c->n_kv_heads > 8) return fail(POP_ESHAPE, "more than 8 query heads per KV head");
+  if (c->dtype != POP_DTYPE_BF16 && c->dtype != POP_DTYPE_F32) return fail(POP_EINVAL, "unknown dtype %d", c->dtype);
+  if (c->dtype != POP_DTYPE_BF16) return fail(POP_EUNSUPPORTED, "only bf16 weights are implemented");
+  if (c->act != POP_ACT_SILU && c->act != POP_ACT_GELU_TANH) return fail(POP_EINVAL, "unknown activation %d", c->act);
+  if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256)
+    return fail(POP_ESHAPE, "head_dim %d is not one of 64, 128, 256", c->head_dim);
+  if (c->d_model % 8 || c->d_ffn % 8) return fail(POP_ESHAPE, "d_model and d_ffn must be multiples of 8");
+  if (c->d_model > 8192) return fail(POP_ESHAPE, "d_model above 8192");
+  if (c->page_size < 1 || c->page_size > 256 || (c->page_size & (c->page_size - 1)))
+    return fail(POP_ESHAPE, "page_size %d is not a power of two in 1..256", c->page_size);
+  if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return fail(POP_EINVAL, "bad rms_eps / rope_theta");
+  if (c->sliding_window < 0 || c->global_every < 0) return fail(POP_EINVAL, "negative sliding_window / global_every");
+  if (c->sliding_window > 0 && c->global_every > 0 && !(c->rope_theta_local > 0.f))
+    return fail(POP_EINVAL, "bad rope_theta_local");
+  return POP_OK;
+}
+
+bool layer_is_global(const pop_config& c, int l /*1-based*/) {
+  return c.global_every == 0 || c.sliding_window == 0 || l % c.global_every == 0;
+}
+}  // namespace
+
+struct pop_model {
+  pop_config cfg;
+  pop_weights w;
+  std::vector<pop_layer_weights> layers;
+  int Dq, Dkv, Dqkv;
+};
+
+struct pop_cache {
+  pop_config cfg;
+  bf16_t* pool;
+  size_t bytes;
+  int n_pages, max_seqs, max_pages;
+  int n_seqs;                        // live sequences
+  std::vector<int32_t> seq_lens;     // [max_seqs]
+  std::vector<int32_t> block_table;  // [max_seqs][max_pages]
+  size_t layer_stride() const {      // elements between the K pools of consecutive layers
+    return 2 * pool_stride();
+  }
+  size_t pool_stride() const {
+    return (size_t)n_pages * cfg.n_kv_heads * cfg.page_size * cfg.head_dim;
+  }
+  bf16_t* k_pool(int l0) const { return pool + (size_t)l0 * layer_stride(); }
+  bf16_t* v_pool(int l0) const { return k_pool(l0) + pool_stride(); }
+};
+
+// ----------------------------------------------------------------------------------------- workspace
+namespace {
+
+constexpr int kKvChunk = 8;  // pruned layers projected per batched GEMM
+
+struct Workspace {
+  // int32 meta (one upload per call)
+  size_t meta_bytes;
+  size_t o_tokens, o_row_src, o_pos, o_slot, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start,
+      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_wlist;
+  // device buffers
+  size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_a_multi, o_kv_out;
+  size_t o_xb, o_ab, o_qkvb, o_qb, o_attnb, o_ub, o_part;
+  size_t total;
+  int Tp_max, nt64_max, nta_max, n_splits_max;
+};
+
+Workspace carve(const pop_config& c, int T, int B, int maxp) {
+  Workspace w{};
+  const size_t d = c.d_model, hd = c.head_dim;
+  const size_t Dq = (size_t)c.n_q_heads * hd, Dkv = (size_t)c.n_kv_heads * hd, Dqkv = Dq + 2 * Dkv;
+  const size_t f = c.d_ffn;
+  w.Tp_max = (int)round_up((size_t)T + 63 * (size_t)B, 64);
+  w.nt64_max = T / 64 + B;
+  w.nta_max = T / 128 + B;
+  const long long max_len = (long long)maxp * c.page_size;
+  w.n_splits_max = (int)std::max<long long>(1, (max_len + 255) / 256);
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = o;
+    o += round_up(bytes, 256);
+    return at;
+  };
+  w.o_tokens = take(4 * (size_t)T);
+  w.o_row_src = take(4 * (size_t)T);
+  w.o_pos = take(4 * (size_t)T);
+  w.o_slot = take(4 * (size_t)T);
+  w.o_cu = take(4 * ((size_t)B + 1));
+  w.o_vt_off = take(4 * (size_t)B);
+  w.o_t64_seq = take(4 * (size_t)w.nt64_max);
+  w.o_t64_start = take(4 * (size_t)w.nt64_max);
+  w.o_ta_seq = take(4 * (size_t)w.nta_max);
+  w.o_ta_start = take(4 * (size_t)w.nta_max);
+  w.o_bnd_row = take(4 * (size_t)B);
+  w.o_bnd_pos = take(4 * (size_t)B);
+  w.o_bnd_slot = take(4 * (size_t)B);
+  w.o_bt = take(4 * (size_t)B * maxp);
+  w.o_wlist = take(8 * (size_t)c.n_layers);
+  w.meta_bytes = o;
+  w.o_h = take(4 * (size_t)T * d);
+  w.o_a = take(2 * (size_t)T * d);
+  w.o_qkv = take(2 * (size_t)T * Dqkv);
+  w.o_attn = take(2 * (size_t)T * Dq);
+  w.o_u = take(2 * (size_t)T * f);
+  w.o_vT = take(2 * Dkv * (size_t)w.Tp_max);
+  w.o_cs_g = take(8 * (size_t)T * (hd / 2));
+  w.o_cs_l = take(8 * (size_t)T * (hd / 2));
+  const size_t rc = std::min(kKvChunk, c.n_layers);
+  w.o_a_multi = take(2 * rc * (size_t)T * d);
+  w.o_kv_out = take(2 * rc * (size_t)T * 2 * Dkv);
+  w.o_xb = take(4 * (size_t)B * d);
+  w.o_ab = take(2 * (size_t)B * std::max(d, Dq));
+  w.o_qkvb = take(4 * (size_t)B * Dqkv);
+  w.o_qb = take(2 * (size_t)B * Dq);
+  w.o_attnb = take(2 * (size_t)B * Dq);
+  w.o_ub = take(2 * (size_t)B * f);
+  w.o_part = take(4 * (size_t)B * c.n_q_heads * w.n_splits_max * (hd + 2));
+  w.total = o;
+  return w;
+}
+
+template <typename T>
+T* at(void* base, size_t off) {
+  return reinterpret_cast<T*>(reinterpret_cast<char*>(base) + off);
+}
+
+// Slot mapping and its validation (shared by pop_slot_map and pop_prefill).
+pop_status slot_map_impl(const int32_t* cu, int n_seqs, const int32_t* bt, int maxp, int P, int n_pages,
+                         int32_t* slots, int extra_positions /* room checked beyond each length */) {
+  if (!cu || !bt) return fail(POP_EINVAL, "cu_seqlens / block_table is NULL");
+  if (n_seqs < 1) return fail(POP_EINVAL, "n_seqs %d < 1", n_seqs);
+  if (maxp < 1 || P < 1 || n_pages < 1) return fail(POP_EINVAL, "bad page geometry");
+  if (cu[0] != 0) return fail(POP_EINVAL, "cu_seqlens[0] = %d, expected 0", cu[0]);
+  std::vector<uint8_t> used((size_t)n_pages, 0);
+  for (int b = 0; b < n_seqs; ++b) {
+    const long long len = (long long)cu[b + 1] - cu[b];
+    if (len < 1) return fail(POP_EINVAL, "sequence %d has length %lld (cu_seqlens must be strictly increasing)", b, len);
+    const long long need = (len + extra_positions + P - 1) / P;
+    if (need > maxp) return fail(POP_ENOSPACE, "sequence %d needs %lld pages, the table has %d columns", b, need, maxp);
+    for (int pg = 0; pg < maxp; ++pg) {
+      const int id = bt[(size_t)b * maxp + pg];
+      if (id < 0) {
+        if (pg < need) return fail(POP_ENOSPACE, "sequence %d has no page for position %d", b, pg * P);
+        continue;
+      }
+      if (id >= n_pages) return fail(POP_EINVAL, "page id %d of sequence %d is outside [0, %d)", id, b, n_pages);
+      if (used[id]) return fail(POP_EINVAL, "page %d is assigned twice", id);
+      used[id] = 1;
+    }
+    if (slots)
+      for (long long t = 0; t < len; ++t)
+        slots[cu[b] + t] = bt[(size_t)b * maxp + t / P] * P + (int)(t % P);
+  }
+  return POP_OK;
+}
+
+struct LayerCtx {
+  const pop_model* m;
+  pop_cache* c;
+  void* ws;
+  const Workspace* w;
+  hipStream_t st;
+};
+
+// One decode-style layer for B rows held in xb (fp32 [B, d]); pos/slot are device arrays [B].
+pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32_t* pos, const int32_t* slot,
+                        int max_len) {
+  const pop_config& c = x.m->cfg;
+  const pop_layer_weights& lw = x.m->layers[l - 1];
+  const int d = c.d_model, f = c.d_ffn, Dq = x.m->Dq, Dqkv = x.m->Dqkv;
+  float* xb = at<float>(x.ws, x.w->o_xb);
+  bf16_t* ab = at<bf16_t>(x.ws, x.w->o_ab);
+  float* qkvb = at<float>(x.ws, x.w->o_qkvb);
+  bf16_t* qb = at<bf16_t>(x.ws, x.w->o_qb);
+  bf16_t* attnb = at<bf16_t>(x.ws, x.w->o_attnb);
+  bf16_t* ub = at<bf16_t>(x.ws, x.w->o_ub);
+  const bool glob = layer_is_global(c, l);
+  pop::launch_rmsnorm(xb, nullptr, nullptr, (const float*)lw.norm_in, ab, nullptr, B, d, c.rms_eps, x.st);
+  pop::launch_gemv(ab, (const bf16_t*)lw.wqkv, qkvb, B, Dqkv, d, Dqkv, pop::GEMV_STORE_F32, 0, x.st);
+  pop::launch_rope_append(qkvb, Dqkv, qb, c.n_q_heads, c.n_kv_heads, c.head_dim, pos, slot,
+                          glob ? (double)c.rope_theta : (double)c.rope_theta_local, x.c->k_pool(l - 1),
+                          x.c->v_pool(l - 1), c.page_size, B, x.st);
+  pop::AttnDecodeArgs ad{};
+  ad.q = qb;
+  ad.k_pool = x.c->k_pool(l - 1);
+  ad.v_pool = x.c->v_pool(l - 1);
+  ad.block_table = at<int32_t>(x.ws, x.w->o_bt);
+  ad.max_pages = x.c->max_pages;
+  ad.page_size = c.page_size;
+  ad.pos = pos;
+  ad.window = glob ? 0 : c.sliding_window;
+  ad.B = B;
+  ad.n_q_heads = c.n_q_heads;
+  ad.n_kv_heads = c.n_kv_heads;
+  ad.hd = c.head_dim;
+  const int span = ad.window > 0 ? std::min(max_len, ad.window) : max_len;
+  ad.n_splits = std::max(1, (span + 255) / 256);
+  ad.max_len = max_len;
+  ad.part = at<float>(x.ws, x.w->o_part);
+  ad.out = attnb;
+  pop::launch_attention_decode(ad, x.st);
+  pop::launch_gemv(attnb, (const bf16_t*)lw.wo, xb, B, d, Dq, d, pop::GEMV_ADD_F32, 0, x.st);
+  pop::launch_rmsnorm(xb, nullptr, nullptr, (const float*)lw.norm_post, ab, nullptr, B, d, c.rms_eps, x.st);
+  pop::launch_gemv(ab, (const bf16_t*)lw.w_gate_up, ub, B, f, d, f, pop::GEMV_GLU_BF16, c.act, x.st);
+  pop::launch_gemv(ub, (const bf16_t*)lw.w_down, xb, B, d, f, d, pop::GEMV_ADD_F32, 0, x.st);
+  POP_HIP(hipGetLastError());
+  return POP_OK;
+}
+
+pop_status lm_head(const LayerCtx& x, int B, float* dev_logits) {
+  const pop_config& c = x.m->cfg;
+  float* xb = at<float>(x.ws, x.w->o_xb);
+  bf16_t* ab = at<bf16_t>(x.ws, x.w->o_ab);
+  pop::launch_rmsnorm(xb, nullptr, nullptr, (const float*)x.m->w.final_norm, ab, nullptr, B, c.d_model, c.rms_eps,
+                      x.st);
+  pop::launch_gemv(ab, (const bf16_t*)x.m->w.lm_head, dev_logits, B, c.vocab, c.d_model, c.vocab,
+                   pop::GEMV_STORE_F32, 0, x.st);
+  POP_HIP(hipGetLastError());
+  return POP_OK;
+}
+
+pop_status gemm_or_fail(const pop::GemmArgs& g, hipStream_t st, const char* what) {
+  hipError_t e = pop::launch_gemm(g, st);
+  if (e != hipSuccess) return fail(POP_EHIP, "%s GEMM launch failed: %s", what, hipGetErrorString(e));
+  return POP_OK;
+}
+
+}  // namespace
+
+// ----------------------------------------------------------------------------------------- C ABI
+extern "C" {
+
+const char* pop_last_error(void) { return g_last_error.c_str(); }
+const char* pop_version(void) { return "pop-mi355x 0.1 (gfx950)"; }
+
+pop_status pop_load_weights(const pop_config* cfg, const pop_weights* w, pop_model** out) {
+  if (!out) return fail(POP_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (pop_status st = check_config(cfg)) return st;
+  if (!w || !w->layers) return fail(POP_EINVAL, "weights / layers is NULL");
+  if (!w->embed || !w->final_norm || !w->lm_head) return fail(POP_EINVAL, "embed / final_norm / lm_head is NULL");
+  if (!aligned16(w->embed) || !aligned16(w->final_norm) || !aligned16(w->lm_head))
+    return fail(POP_EALIGN, "embed / final_norm / lm_head not 16-byte aligned");
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const pop_layer_weights& lw = w->layers[l];
+    const void* ps[6] = {lw.norm_in, lw.wqkv, lw.wo, lw.norm_post, lw.w_gate_up, lw.w_down};
+    for (const void* p : ps) {
+      if (!p) return fail(POP_EINVAL, "layer %d has a NULL weight pointer", l + 1);
+      if (!aligned16(p)) return fail(POP_EALIGN, "layer %d has a weight pointer that is not 16-byte aligned", l + 1);
+    }
+  }
+  pop_model* m = new (std::nothrow) pop_model();
+  if (!m) return fail(POP_EINVAL, "out of host memory");
+  m->cfg = *cfg;
+  m->w = *w;
+  m->layers.assign(w->layers, w->layers + cfg->n_layers);
+  m->w.layers = m->layers.data();
+  m->Dq = cfg->n_q_heads * cfg->head_dim;
+  m->Dkv = cfg->n_kv_heads * cfg->head_dim;
+  m->Dqkv = m->Dq + 2 * m->Dkv;
+  *out = m;
+  return POP_OK;
+}
+
+void pop_free_model(pop_model* m) { delete m; }
+
+size_t pop_cache_bytes(const pop_config* cfg, int32_t n_pages) {
+  if (!cfg || n_pages < 1 || cfg->n_layers < 1 || cfg->n_kv_heads < 1 || cfg->head_dim < 1 || cfg->page_size < 1)
+    return 0;
+  return (size_t)cfg->n_layers * 2 * n_pages * cfg->n_kv_heads * cfg->page_size * cfg->head_dim * sizeof(bf16_t);
+}
+
+size_t pop_workspace_bytes(const pop_config* cfg, int32_t max_tokens, int32_t max_seqs, int32_t max_pages_per_seq) {
+  if (check_config(cfg) != POP_OK || max_tokens < 1 || max_seqs < 1 || max_pages_per_seq < 1) return 0;
+  return carve(*cfg, max_tokens, max_seqs, max_pages_per_seq).total;
+}
+
+pop_status pop_cache_create(const pop_config* cfg, void* dev_pool, size_t bytes, int32_t n_pages, int32_t max_seqs,
+                            int32_t max_pages_per_seq, pop_cache** out) {
+  if (!out) return fail(POP_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (pop_status st = check_config(cfg)) return st;
+  if (!dev_pool) return fail(POP_EINVAL, "dev_pool is NULL");
+  if (!aligned16(dev_pool)) return fail(POP_EALIGN, "dev_pool not 16-byte aligned");
+  if (n_pages < 1 || max_seqs < 1 || max_pages_per_seq < 1) return fail(POP_EINVAL, "non-positive cache geometry");
+  if ((long long)n_pages * cfg->page_size >= (1LL << 31)) return fail(POP_EINVAL, "slot index would overflow int32");
+  const size_t need = pop_cache_bytes(cfg, n_pages);
+  if (bytes < need) return fail(POP_ENOSPACE, "pool has %zu bytes, %zu needed for %d pages", bytes, need, n_pages);
+  pop_cache* c = new (std::nothrow) pop_cache();
+  if (!c) return fail(POP_EINVAL, "out of host memory");
+  c->cfg = *cfg;
+  c->pool = reinterpret_cast<bf16_t*>(dev_pool);
+  c->bytes = bytes;
+  c->n_pages = n_pages;
+  c->max_seqs = max_seqs;
+  c->max_pages = max_pages_per_seq;
+  c->n_seqs = 0;
+  c->seq_lens.assign(max_seqs, 0);
+  c->block_table.assign((size_t)max_seqs * max_pages_per_seq, -1);
+  *out = c;
+  return POP_OK;
+}
+
+void pop_cache_destroy(pop_cache* c) { delete c; }
+
+int32_t pop_cache_n_seqs(const pop_cache* c) { return c ? c->n_seqs : 0; }
+
+pop_status pop_cache_seq_lens(const pop_cache* c, int32_t* host_out) {
+  if (!c || !host_out) return fail(POP_EINVAL, "cache / host_out is NULL");
+  std::copy(c->seq_lens.begin(), c->seq_lens.end(), host_out);
+  return POP_OK;
+}
+
+pop_status pop_slot_map(const int32_t* host_cu_seqlens, int32_t n_seqs, const int32_t* host_block_table,
+                        int32_t max_pages_per_seq, int32_t page_size, int32_t n_pages, int32_t* host_slots_out) {
+  if (!host_slots_out) return fail(POP_EINVAL, "host_slots_out is NULL");
+  return slot_map_impl(host_cu_seqlens, n_seqs, host_block_table, max_pages_per_seq, page_size, n_pages,
+                       host_slots_out, 0);
+}
+
+pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, float* dev_logits, void* dev_workspace,
+                       size_t workspace_bytes, pop_stream stream) {
+  // ------------------------------------------------------------------ validation (no launches yet)
+  if (!m || !c || !a) return fail(POP_EINVAL, "model / cache / args is NULL");
+  const pop_config& cfg = m->cfg;
+  if (std::memcmp(&cfg, &c->cfg, sizeof cfg) != 0) return fail(POP_EINVAL, "cache was created for another config");
+  if (!a->tokens || !a->cu_seqlens || !a->block_table) return fail(POP_EINVAL, "tokens / cu_seqlens / block_table is NULL");
+  if (a->n_seqs < 1 || a->n_seqs > c->max_seqs)
+    return fail(POP_EINVAL, "n_seqs %d outside [1, %d]", a->n_seqs, c->max_seqs);
+  if (a->l_keep < 0 || a->l_keep > cfg.n_layers)
+    return fail(POP_EINVAL, "l_keep %d outside [0, %d]", a->l_keep, cfg.n_layers);
+  if (a->mode != POP_MODE_POP && a->mode != POP_MODE_BODY_ONLY) return fail(POP_EINVAL, "unknown mode %d", a->mode);
+  if (a->mode == POP_MODE_POP && !dev_logits) return fail(POP_EINVAL, "dev_logits is NULL");
+  if (dev_logits && !aligned16(dev_logits)) return fail(POP_EALIGN, "dev_logits not 16-byte aligned");
+  if (!dev_workspace) return fail(POP_EINVAL, "dev_workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(dev_workspace) & 255) return fail(POP_EALIGN, "dev_workspace not 256-byte aligned");
+  const int B = a->n_seqs, P = cfg.page_size, maxp = c->max_pages;
+  std::vector<int32_t> slots;
+  {
+    // lengths first (slot_map_impl re-checks), to size the slot array
+    if (a->cu_seqlens[0] != 0) return fail(POP_EINVAL, "cu_seqlens[0] = %d, expected 0", a->cu_seqlens[0]);
+    for (int b = 0; b < B; ++b)
+      if (a->cu_seqlens[b + 1] <= a->cu_seqlens[b])
+        return fail(POP_EINVAL, "sequence %d is empty (cu_seqlens must be strictly increasing)", b);
+  }
+  const int T = a->cu_seqlens[B];
+  slots.resize(T);
+  if (pop_status st = slot_map_impl(a->cu_seqlens, B, a->block_table, maxp, P, c->n_pages, slots.data(), 0)) return st;
+  for (int t = 0; t < T; ++t)
+    if (a->tokens[t] < 0 || a->tokens[t] >= cfg.vocab)
+      return fail(POP_EINVAL, "token %d at packed index %d is outside [0, %d)", a->tokens[t], t, cfg.vocab);
+  std::vector<int32_t> row_src((size_t)T, -1);
+  if (a->n_ranges < 0 || (a->n_ranges > 0 && (!a->embed_ranges || !a->embeds)))
+    return fail(POP_EINVAL, "embed ranges given without embeds / embed_ranges");
+  if (a->embeds && !aligned16(a->embeds)) return fail(POP_EALIGN, "embeds not 16-byte aligned");
+  {
+    int next_row = 0;
+    for (int r = 0; r < a->n_ranges; ++r) {
+      const int sb = a->embed_ranges[3 * r], first = a->embed_ranges[3 * r + 1], cnt = a->embed_ranges[3 * r + 2];
+      if (sb < 0 || sb >= B || first < 0 || cnt < 0 ||
+          (long long)first + cnt > (long long)a->cu_seqlens[sb + 1] - a->cu_seqlens[sb])
+        return fail(POP_EINVAL, "embed range %d (seq %d, first %d, count %d) is outside its sequence", r, sb, first, cnt);
+      for (int i = 0; i < cnt; ++i) {
+        int32_t& rs = row_src[(size_t)a->cu_seqlens[sb] + first + i];
+        if (rs >= 0) return fail(POP_EINVAL, "embed ranges overlap at sequence %d position %d", sb, first + i);
+        rs = next_row++;
+      }
+    }
+  }
+  const Workspace w = carve(cfg, T, B, maxp);
+  if (workspace_bytes < w.total)
+    return fail(POP_ENOSPACE, "workspace has %zu bytes, %zu needed for %d tokens in %d sequences", workspace_bytes,
+                w.total, T, B);
+  const int d = cfg.d_model, f = cfg.d_ffn, hd = cfg.head_dim, Dq = m->Dq, Dkv = m->Dkv, Dqkv = m->Dqkv;
+  if ((long long)T * std::max(std::max(Dqkv, f), d) * 2 >= (1LL << 31))
+    return fail(POP_ESHAPE, "an activation matrix would exceed 2 GiB; split the batch");
+
+  // ------------------------------------------------------------------ host-side meta
+  std::vector<unsigned char> meta(w.meta_bytes, 0);
+  auto mi = [&](size_t off) { return reinterpret_cast<int32_t*>(meta.data() + off); };
+  std::copy(a->tokens, a->tokens + T, mi(w.o_tokens));
+  std::copy(row_src.begin(), row_src.end(), mi(w.o_row_src));
+  std::copy(slots.begin(), slots.end(), mi(w.o_slot));
+  std::copy(a->cu_seqlens, a->cu_seqlens + B + 1, mi(w.o_cu));
+  int n_t64 = 0, n_ta = 0, Tp = 0, max_len = 0;
+  std::vector<std::pair<int, int>> atiles;  // (start, seq)
+  for (int b = 0; b < B; ++b) {
+    const int s0 = a->cu_seqlens[b], len = a->cu_seqlens[b + 1] - s0;
+    max_len = std::max(max_len, len);
+    for (int t = 0; t < len; ++t) mi(w.o_pos)[s0 + t] = t;
+    mi(w.o_vt_off)[b] = Tp;
+    Tp += (int)round_up(len, 64);
+    for (int p0 = 0; p0 < len; p0 += 64) {
+      mi(w.o_t64_seq)[n_t64] = b;
+      mi(w.o_t64_start)[n_t64++] = p0;
+    }
+    for (int q0 = 0; q0 < len; q0 += 128) atiles.emplace_back(q0, b);
+    mi(w.o_bnd_row)[b] = s0 + len - 1;
+    mi(w.o_bnd_pos)[b] = len - 1;
+    mi(w.o_bnd_slot)[b] = slots[s0 + len - 1];
+    std::copy(a->block_table + (size_t)b * maxp, a->block_table + (size_t)(b + 1) * maxp, mi(w.o_bt) + (size_t)b * maxp);
+  }
+  // heaviest query tiles (latest rows) first
+  std::stable_sort(atiles.begin(), atiles.end(),
+                   [](const std::pair<int, int>& x, const std::pair<int, int>& y) { return x.first > y.first; });
+  for (auto& t : atiles) {
+    mi(w.o_ta_seq)[n_ta] = t.second;
+    mi(w.o_ta_start)[n_ta++] = t.first;
+  }
+  {
+    const bf16_t** wl = reinterpret_cast<const bf16_t**>(meta.data() + w.o_wlist);
+    for (int l = 0; l < cfg.n_layers; ++l)
+      wl[l] = reinterpret_cast<const bf16_t*>(m->layers[l].wqkv) + (size_t)Dq * d;  // rows W^K | W^V
+  }
+
+  // ------------------------------------------------------------------ launches
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  void* ws = dev_workspace;
+  POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
+  // sequences start from empty; record the new state now that nothing can fail on arguments
+  c->n_seqs = B;
+  std::fill(c->seq_lens.begin(), c->seq_lens.end(), 0);
+  std::fill(c->block_table.begin(), c->block_table.end(), -1);
+  for (int b = 0; b < B; ++b) {
+    c->seq_lens[b] = a->cu_seqlens[b + 1] - a->cu_seqlens[b];
+    std::copy(a->block_table + (size_t)b * maxp, a->block_table + (size_t)(b + 1) * maxp,
+              c->block_table.begin() + (size_t)b * maxp);
+  }
+
+  const int32_t* d_tokens = at<int32_t>(ws, w.o_tokens);
+  const int32_t* d_row_src = at<int32_t>(ws, w.o_row_src);
+  const int32_t* d_pos = at<int32_t>(ws, w.o_pos);
+  const int32_t* d_slot = at<int32_t>(ws, w.o_slot);
+  const int32_t* d_cu = at<int32_t>(ws, w.o_cu);
+  const int32_t* d_vt_off = at<int32_t>(ws, w.o_vt_off);
+  float* h = at<float>(ws, w.o_h);
+  bf16_t* abuf = at<bf16_t>(ws, w.o_a);
+  bf16_t* qkv = at<bf16_t>(ws, w.o_qkv);
+  bf16_t* attn = at<bf16_t>(ws, w.o_attn);
+  bf16_t* u = at<bf16_t>(ws, w.o_u);
+  bf16_t* vT = at<bf16_t>(ws, w.o_vT);
+  float2* cs_g = at<float2>(ws, w.o_cs_g);
+  float2* cs_l = at<float2>(ws, w.o_cs_l);
+
+  pop::launch_embed((const bf16_t*)m->w.embed, d_tokens, a->n_ranges > 0 ? d_row_src : nullptr,
+                    (const bf16_t*)a->embeds, h, T, d, st);
+  bool any_local = false;
+  for (int l = 1; l <= cfg.n_layers; ++l) any_local |= !layer_is_global(cfg, l);
+  pop::launch_rope_table(d_pos, cs_g, T, hd, (double)cfg.rope_theta, st);
+  if (any_local) pop::launch_rope_table(d_pos, cs_l, T, hd, (double)cfg.rope_theta_local, st);
+  POP_HIP(hipGetLastError());
+
+  pop::RopeWriteArgs rw{};
+  rw.n_q_heads = cfg.n_q_heads;
+  rw.n_kv_heads = cfg.n_kv_heads;
+  rw.hd = hd;
+  rw.slot = d_slot;
+  rw.page_size = P;
+  rw.Tp = Tp;
+  rw.cu_seqlens = d_cu;
+  rw.vt_off = d_vt_off;
+  rw.tile_seq = at<int32_t>(ws, w.o_t64_seq);
+  rw.tile_start = at<int32_t>(ws, w.o_t64_start);
+  rw.n_tiles = n_t64;
+
+  // ---- kept layers 1..l_keep over all given rows (Sec. 2.1)
+  for (int l = 1; l <= a->l_keep; ++l) {
+    const pop_layer_weights& lw = m->layers[l - 1];
+    const bool glob = layer_is_global(cfg, l);
+    pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_in, abuf, nullptr, T, d, cfg.rms_eps, st);
+    pop::GemmArgs g{};
+    g.batch = 1;
+    g.A = abuf; g.lda = d; g.W = (const bf16_t*)lw.wqkv; g.ldw = d; g.out = qkv; g.ldc = Dqkv;
+    g.M = T; g.N = Dqkv; g.K = d; g.epilogue = pop::EPI_STORE_BF16;
+    if (pop_status s = gemm_or_fail(g, st, "QKV")) return s;
+    rw.qkv = qkv; rw.ld = Dqkv; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
+    rw.cs = glob ? cs_g : cs_l;
+    rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
+    rw.vT = vT;
+    pop::launch_rope_write(rw, st);
+    pop::AttnPrefillArgs ap{};
+    ap.qkv = qkv; ap.ld = Dqkv; ap.q_col = 0; ap.k_col = Dq; ap.vT = vT; ap.Tp = Tp; ap.out = attn;
+    ap.T = T; ap.n_q_heads = cfg.n_q_heads; ap.n_kv_heads = cfg.n_kv_heads; ap.hd = hd;
+    ap.window = glob ? 0 : cfg.sliding_window;
+    ap.cu_seqlens = d_cu; ap.vt_off = d_vt_off;
+    ap.tile_seq = at<int32_t>(ws, w.o_ta_seq); ap.tile_start = at<int32_t>(ws, w.o_ta_start); ap.n_tiles = n_ta;
+    {
+      hipError_t e = pop::launch_attention_prefill(ap, st);
+      if (e != hipSuccess) return fail(POP_EHIP, "attention launch failed: %s", hipGetErrorString(e));
+    }
+    g.A = attn; g.lda = Dq; g.W = (const bf16_t*)lw.wo; g.ldw = Dq; g.out = h; g.ldc = d;
+    g.M = T; g.N = d; g.K = Dq; g.epilogue = pop::EPI_ADD_F32;
+    if (pop_status s = gemm_or_fail(g, st, "O")) return s;
+    pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_post, abuf, nullptr, T, d, cfg.rms_eps, st);
+    g.A = abuf; g.lda = d; g.W = (const bf16_t*)lw.w_gate_up; g.ldw = d; g.out = u; g.ldc = f;
+    g.M = T; g.N = f; g.K = d; g.epilogue = pop::EPI_GLU_BF16; g.act = cfg.act;
+    if (pop_status s = gemm_or_fail(g, st, "gate/up")) return s;
+    g.A = u; g.lda = f; g.W = (const bf16_t*)lw.w_down; g.ldw = f; g.out = h; g.ldc = d;
+    g.M = T; g.N = d; g.K = f; g.epilogue = pop::EPI_ADD_F32;
+    if (pop_status s = gemm_or_fail(g, st, "down")) return s;
+  }
+
+  // ---- pruned layers l_keep+1..L: independent KV projections of the frozen hidden state (Sec. 3.3)
+  {
+    bf16_t* a_multi = at<bf16_t>(ws, w.o_a_multi);
+    bf16_t* kv_out = at<bf16_t>(ws, w.o_kv_out);
+    const bf16_t* const* wlist = at<const bf16_t*>(ws, w.o_wlist);
+    for (int l0 = a->l_keep + 1; l0 <= cfg.n_layers; l0 += kKvChunk) {
+      const int n = std::min(kKvChunk, cfg.n_layers - l0 + 1);
+      pop::GammaList gl{};
+      for (int j = 0; j < n; ++j) gl.g[j] = (const float*)m->layers[l0 - 1 + j].norm_in;
+      pop::launch_rmsnorm_multi(h, gl, n, a_multi, (size_t)T * d, T, d, cfg.rms_eps, st);
+      pop::GemmArgs g{};
+      g.A = a_multi; g.lda = d; g.W = nullptr; g.ldw = d; g.out = kv_out; g.ldc = 2 * Dkv;
+      g.M = T; g.N = 2 * Dkv; g.K = d; g.epilogue = pop::EPI_STORE_BF16;
+      g.batch = n; g.strideA = (long long)T * d; g.strideC = (long long)T * 2 * Dkv;
+      g.W_list = wlist + (l0 - 1);
+      if (pop_status s = gemm_or_fail(g, st, "K/V-only")) return s;
+      for (int j = 0; j < n; ++j) {
+        const int l = l0 + j;
+        rw.qkv = kv_out + (size_t)j * T * 2 * Dkv; rw.ld = 2 * Dkv; rw.q_col = -1; rw.k_col = 0; rw.v_col = Dkv;
+        rw.cs = layer_is_global(cfg, l) ? cs_g : cs_l;
+        rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
+        rw.vT = nullptr;
+        pop::launch_rope_write(rw, st);
+      }
+    }
+    POP_HIP(hipGetLastError());
+  }
+
+  // ---- boundary tokens at full depth (Sec. 3.3, boundary handling): they rode along through the
+  //      kept layers (identical to their decode step there) and continue alone through the rest.
+  if (a->mode == POP_MODE_POP) {
+    LayerCtx x{m, c, ws, &w, st};
+    pop::launch_gather_rows(h, at<int32_t>(ws, w.o_bnd_row), at<float>(ws, w.o_xb), B, d, st);
+    for (int l = a->l_keep + 1; l <= cfg.n_layers; ++l)
+      if (pop_status s = decode_layer(x, l, B, at<int32_t>(ws, w.o_bnd_pos), at<int32_t>(ws, w.o_bnd_slot), max_len))
+        return s;
+    if (pop_status s = lm_head(x, B, dev_logits)) return s;
+  }
+  return POP_OK;
+}
+
+pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_tokens, int32_t n_seqs, float* dev_logits,
+                           void* dev_workspace, size_t workspace_bytes, pop_stream stream) {
+  if (!m || !c || !host_tokens || !dev_logits) return fail(POP_EINVAL, "model / cache / tokens / logits is NULL");
+  const pop_config& cfg = m->cfg;
+  if (std::memcmp(&cfg, &c->cfg, sizeof cfg) != 0) return fail(POP_EINVAL, "cache was created for another config");
+  if (c->n_seqs < 1) return fail(POP_ESTATE, "no prefilled sequences in this cache");
+  if (n_seqs != c->n_seqs) return fail(POP_EINVAL, "n_seqs %d does not match the %d live sequences", n_seqs, c->n_seqs);
+  if (!aligned16(dev_logits)) return fail(POP_EALIGN, "dev_logits not 16-byte aligned");
+  if (!dev_workspace) return fail(POP_EINVAL, "dev_workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(dev_workspace) & 255) return fail(POP_EALIGN, "dev_workspace not 256-byte aligned");
+  const int B = n_seqs, P = cfg.page_size, maxp = c->max_pages;
+  const Workspace w = carve(cfg, B, B, maxp);
+  if (workspace_bytes < w.total) return fail(POP_ENOSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  std::vector<unsigned char> meta(w.meta_bytes, 0);
+  auto mi = [&](size_t off) { return reinterpret_cast<int32_t*>(meta.data() + off); };
+  int max_len = 0;
+  for (int b = 0; b < B; ++b) {
+    if (host_tokens[b] < 0 || host_tokens[b] >= cfg.vocab)
+      return fail(POP_EINVAL, "token %d of sequence %d is outside [0, %d)", host_tokens[b], b, cfg.vocab);
+    const int pos = c->seq_lens[b];
+    if (pos / P >= maxp || c->block_table[(size_t)b * maxp + pos / P] < 0)
+      return fail(POP_ENOSPACE, "sequence %d has no page for position %d", b, pos);
+    mi(w.o_tokens)[b] = host_tokens[b];
+    mi(w.o_bnd_pos)[b] = pos;
+    mi(w.o_bnd_slot)[b] = c->block_table[(size_t)b * maxp + pos / P] * P + pos % P;
+    max_len = std::max(max_len, pos + 1);
+    std::copy(c->block_table.begin() + (size_t)b * maxp, c->block_table.begin() + (size_t)(b + 1) * maxp,
+              mi(w.o_bt) + (size_t)b * maxp);
+  }
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  void* ws = dev_workspace;
+  POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
+  for (int b = 0; b < B; ++b) c->seq_lens[b] += 1;
+  LayerCtx x{m, c, ws, &w, st};
+  pop::launch_embed((const bf16_t*)m->w.embed, at<int32_t>(ws, w.o_tokens), nullptr, nullptr, at<float>(ws, w.o_xb),
+                    B, cfg.d_model, st);
+  for (int l = 1; l <= cfg.n_layers; ++l)
+    if (pop_status s = decode_layer(x, l, B, at<int32_t>(ws, w.o_bnd_pos), at<int32_t>(ws, w.o_bnd_slot), max_len))
+      return s;
+  return lm_head(x, B, dev_logits);
+}
+
+// ----------------------------------------------------------------------------------------- single steps
+pop_status pop_op_rmsnorm(const float* x, const float* gamma, void* out, int32_t rows, int32_t d, float eps,
+                          pop_stream stream) {
+  if (!x || !gamma || !out) return fail(POP_EINVAL, "NULL pointer");
+  if (rows < 0 || d < 8 || d % 8 || d > 8192) return fail(POP_ESHAPE, "rows %d / d %d not supported", rows, d);
+  if (!aligned16(x) || !aligned16(gamma) || !aligned16(out)) return fail(POP_EALIGN, "pointer not 16-byte aligned");
+  pop::launch_rmsnorm(const_cast<float*>(x), nullptr, nullptr, gamma, (bf16_t*)out, nullptr, rows, d, eps,
+                      reinterpret_cast<hipStream_t>(stream));
+  POP_HIP(hipGetLastError());
+  return POP_OK;
+}
+
+pop_status pop_op_gemm(const void* A, int64_t lda, const void* W, int64_t ldw, void* out, int64_t ldc, int32_t M,
+                       int32_t N, int32_t K, int32_t epilogue, int32_t act, pop_stream stream) {
+  if (!A || !W || !out) return fail(POP_EINVAL, "NULL pointer");
+  if (M < 0 || N < 0 || K < 1) return fail(POP_EINVAL, "bad sizes");
+  if (epilogue < 0 || epilogue > 3) return fail(POP_EINVAL, "unknown epilogue %d", epilogue);
+  if (K % 8 || lda % 8 || ldw % 8 || ldc % 4 || lda < K || ldw < K || ldc < N)
+    return fail(POP_ESHAPE, "K, lda, ldw must be multiples of 8 (ldc of 4) and strides must cover the rows");
+  if (!aligned16(A) || !aligned16(W) || !aligned16(out)) return fail(POP_EALIGN, "pointer not 16-byte aligned");
+  pop::GemmArgs g{};
+  g.A = (const bf16_t*)A; g.lda = lda; g.W = (const bf16_t*)W; g.ldw = ldw; g.out = out; g.ldc = ldc;
+  g.M = M; g.N = N; g.K = K; g.epilogue = epilogue; g.act = act; g.batch = 1;
+  hipError_t e = pop::launch_gemm(g, reinterpret_cast<hipStream_t>(stream));
+  if (e == hipErrorInvalidValue) return fail(POP_ESHAPE, "operand too large or misaligned for the GEMM kernel");
+  if (e != hipSuccess) return fail(POP_EHIP, "GEMM launch failed: %s", hipGetErrorString(e));
+  return POP_OK;
+}
+
+pop_status pop_op_gemv(const void* x, const void* W, void* out, int64_t ldo, int32_t M, int32_t N, int32_t K,
+                       int32_t epilogue, int32_t act, pop_stream stream) {
+  if (!x || !W || !out) return fail(POP_EINVAL, "NULL pointer");
+  if (M < 0 || M > 64 || N < 0 || K < 8 || K % 8) return fail(POP_ESHAPE, "bad sizes");
+  if (epilogue < 0 || epilogue > 2) return fail(POP_EINVAL, "unknown epilogue %d", epilogue);
+  if (!aligned16(x) || !aligned16(W) || !aligned16(out)) return fail(POP_EALIGN, "pointer not 16-byte aligned");
+  pop::launch_gemv((const bf16_t*)x, (const bf16_t*)W, out, M, N, K, ldo, epilogue, act,
+                   reinterpret_cast<hipStream_t>(stream));
+  POP_HIP(hipGetLastError());
+  return POP_OK;
+}
+
+namespace {
+struct RopeAttnWs {
+  size_t o_pos, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start, meta_bytes, o_cs, o_vT, total;
+  int Tp_max;
+};
+RopeAttnWs carve_rope_attn(int T, int B, int Hkv, int hd) {
+  RopeAttnWs w{};
+  size_t o = 0;
+  auto take = [&](size_t bytes) { const size_t a = o; o += round_up(bytes, 256); return a; };
+  w.Tp_max = (int)round_up((size_t)T + 63 * (size_t)B, 64);
+  w.o_pos = take(4 * (size_t)T);
+  w.o_cu = take(4 * ((size_t)B + 1));
+  w.o_vt_off = take(4 * (size_t)B);
+  w.o_t64_seq = take(4 * ((size_t)T / 64 + B));
+  w.o_t64_start = take(4 * ((size_t)T / 64 + B));
+  w.o_ta_seq = take(4 * ((size_t)T / 128 + B));
+  w.o_ta_start = take(4 * ((size_t)T / 128 + B));
+  w.meta_bytes = o;
+  w.o_cs = take(8 * (size_t)T * (hd / 2));
+  w.o_vT = take(2 * (size_t)Hkv * hd * w.Tp_max);
+  w.total = o;
+  return w;
+}
+}  // namespace
+
+size_t pop_op_rope_attention_workspace(int32_t T, int32_t n_seqs, int32_t n_kv_heads, int32_t head_dim) {
+  if (T < 1 || n_seqs < 1 || n_kv_heads < 1 || head_dim < 2) return 0;
+  return carve_rope_attn(T, n_seqs, n_kv_heads, head_dim).total;
+}
+
+pop_status pop_op_rope_attention(void* qkv, const int32_t* cu, int32_t B, int32_t Hq, int32_t Hkv, int32_t hd,
+                                 float rope_theta, int32_t window, void* out, void* workspace, size_t workspace_bytes,
+                                 pop_stream stream) {
+  if (!qkv || !cu || !out || !workspace) return fail(POP_EINVAL, "NULL pointer");
+  if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv || window < 0) return fail(POP_EINVAL, "bad head counts / window");
+  if (hd != 64 && hd != 128 && hd != 256) return fail(POP_ESHAPE, "head_dim %d is not one of 64, 128, 256", hd);
+  if (!aligned16(qkv) || !aligned16(out) || (reinterpret_cast<uintptr_t>(workspace) & 255))
+    return fail(POP_EALIGN, "pointer misaligned");
+  if (cu[0] != 0) return fail(POP_EINVAL, "cu_seqlens[0] != 0");
+  for (int b = 0; b < B; ++b)
+    if (cu[b + 1] <= cu[b]) return fail(POP_EINVAL, "sequence %d is empty", b);
+  const int T = cu[B];
+  const RopeAttnWs w = carve_rope_attn(T, B, Hkv, hd);
+  if (workspace_bytes < w.total) return fail(POP_ENOSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  std::vector<unsigned char> meta(w.meta_bytes, 0);
+  auto mi = [&](size_t off) { return reinterpret_cast<int32_t*>(meta.data() + off); };
+  std::copy(cu, cu + B + 1, mi(w.o_cu));
+  int n64 = 0, nta = 0, Tp = 0;
+  std::vector<std::pair<int, int>> atiles;
+  for (int b = 0; b < B; ++b) {
+    const int len = cu[b + 1] - cu[b];
+    for (int t = 0; t < len; ++t) mi(w.o_pos)[cu[b] + t] = t;
+    mi(w.o_vt_off)[b] = Tp;
+    Tp += (int)round_up(len, 64);
+    for (int p0 = 0; p0 < len; p0 += 64) { mi(w.o_t64_seq)[n64] = b; mi(w.o_t64_start)[n64++] = p0; }
+    for (int q0 = 0; q0 < len; q0 += 128) atiles.emplace_back(q0, b);
+  }
+  std::stable_sort(atiles.begin(), atiles.end(),
+                   [](const std::pair<int, int>& x, const std::pair<int, int>& y) { return x.first > y.first; });
+  for (auto& t : atiles) { mi(w.o_ta_seq)[nta] = t.second; mi(w.o_ta_start)[nta++] = t.first; }
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  POP_HIP(hipMemcpyAsync(workspace, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
+  const int Dq = Hq * hd, Dkv = Hkv * hd, ld = Dq + 2 * Dkv;
+  float2* cs = at<float2>(workspace, w.o_cs);
+  bf16_t* vT = at<bf16_t>(workspace, w.o_vT);
+  pop::launch_rope_table(at<int32_t>(workspace, w.o_pos), cs, T, hd, (double)rope_theta, st);
+  pop::RopeWriteArgs rw{};
+  rw.qkv = (bf16_t*)qkv; rw.ld = ld; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
+  rw.n_q_heads = Hq; rw.n_kv_heads = Hkv; rw.hd = hd; rw.cs = cs; rw.slot = nullptr;
+  rw.k_pool = nullptr; rw.v_pool = nullptr; rw.page_size = 1; rw.vT = vT; rw.Tp = Tp;
+  rw.cu_seqlens = at<int32_t>(workspace, w.o_cu); rw.vt_off = at<int32_t>(workspace, w.o_vt_off);
+  rw.tile_seq = at<int32_t>(workspace, w.o_t64_seq); rw.tile_start = at<int32_t>(workspace, w.o_t64_start);
+  rw.n_tiles = n64;
+  pop::launch_rope_write(rw, st);
+  pop::AttnPrefillArgs ap{};
+  ap.qkv = (const bf16_t*)qkv; ap.ld = ld; ap.q_col = 0; ap.k_col = Dq; ap.vT = vT; ap.Tp = Tp; ap.out = (bf16_t*)out;
+  ap.T = T; ap.n_q_heads = Hq; ap.n_kv_heads = Hkv; ap.hd = hd; ap.window = window;
+  ap.cu_seqlens = rw.cu_seqlens; ap.vt_off = rw.vt_off;
+  ap.tile_seq = at<int32_t>(workspace, w.o_ta_seq); ap.tile_start = at<int32_t>(workspace, w.o_ta_start);
+  ap.n_tiles = nta;
+  hipError_t e = pop::launch_attention_prefill(ap, st);
+  if (e != hipSuccess) return fail(POP_EHIP, "attention launch failed: %s", hipGetErrorString(e));
+  return POP_OK;
+}
+
+}  // extern "C"

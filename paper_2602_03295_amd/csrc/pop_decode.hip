@@ -1,0 +1,353 @@
+// Decode-step kernels: one row per sequence through a full layer against the paged KV cache.
+// They carry the boundary token of Sec. 3.3 ("Boundary Handling for the Last Input Token": x_N is
+// the first decode step with the full model) and pop_decode_step (Sec. 3.2, decode operator).
+// With M <= 8 rows every projection streams its weights once: these kernels are HBM-bound.
+#include "pop_device.h"
+#include "pop_kernels.h"
+
+namespace pop {
+
+namespace decode_impl {
+
+__device__ __forceinline__ float glu_act_f(float g, int act) {
+  if (act == 0) return g / (1.f + __expf(-g));
+  const float u = 0.7978845608028654f * (g + 0.044715f * g * g * g);
+  return 0.5f * g * (1.f + tanhf(u));
+}
+
+__device__ __forceinline__ void fma8(float (&acc), const uint4& w, const uint4& x) {
+  acc += bf16lo(w.x) * bf16lo(x.x) + bf16hi(w.x) * bf16hi(x.x) + bf16lo(w.y) * bf16lo(x.y) +
+         bf16hi(w.y) * bf16hi(x.y) + bf16lo(w.z) * bf16lo(x.z) + bf16hi(w.z) * bf16hi(x.z) +
+         bf16lo(w.w) * bf16lo(x.w) + bf16hi(w.w) * bf16hi(x.w);
+}
+
+// Each wave owns RW weight rows (for GLU: RW gate rows and the matching RW up rows) and all M batch
+// rows; lanes stride over K in 16-byte chunks; fp32 accumulation, wave reduction at the end.
+template <int M, int EPI>
+__global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W,
+                                                   void* __restrict__ out, int N, int K, long long ldo, int act) {
+  constexpr int RW = EPI == GEMV_GLU_BF16 ? 2 : 4;
+  constexpr int NR = EPI == GEMV_GLU_BF16 ? 2 * RW : RW;  // weight rows streamed per wave
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int n0 = (blockIdx.x * 4 + wave) * RW;
+  if (n0 >= N) return;
+  const bf16_t* wr[NR];
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    int row;
+    if (EPI == GEMV_GLU_BF16) row = (r < RW ? 0 : N) + min(n0 + (r % RW), N - 1);
+    else row = min(n0 + r, N - 1);
+    wr[r] = W + (size_t)row * K;
+  }
+  float acc[NR][M];
+#pragma unroll
+  for (int r = 0; r < NR; ++r)
+#pragma unroll
+    for (int m = 0; m < M; ++m) acc[r][m] = 0.f;
+  for (int k = lane * 8; k < K; k += 64 * 8) {
+    uint4 xv[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) xv[m] = *reinterpret_cast<const uint4*>(x + (size_t)m * K + k);
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      typedef __attribute__((__vector_size__(16))) unsigned int u32x4_t;
+      const u32x4_t wl = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wr[r] + k));
+      const uint4 wv = make_uint4(wl[0], wl[1], wl[2], wl[3]);
+#pragma unroll
+      for (int m = 0; m < M; ++m) fma8(acc[r][m], wv, xv[m]);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < NR; ++r)
+#pragma unroll
+    for (int m = 0; m < M; ++m) acc[r][m] = wave_sum(acc[r][m]);
+  if (lane != 0) return;
+#pragma unroll
+  for (int r = 0; r < RW; ++r) {
+    const int n = n0 + r;
+    if (n >= N) break;
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+      if (EPI == GEMV_GLU_BF16) {
+        reinterpret_cast<bf16_t*>(out)[(size_t)m * ldo + n] = f32_to_bf16(glu_act_f(acc[r][m], act) * acc[r + RW][m]);
+      } else {
+        float* o = reinterpret_cast<float*>(out) + (size_t)m * ldo + n;
+        *o = (EPI == GEMV_ADD_F32 ? *o : 0.f) + acc[r][m];
+      }
+    }
+  }
+}
+
+template <int M>
+void launch_gemv_m(const bf16_t* x, const bf16_t* W, void* out, int N, int K, long long ldo, int epi, int act,
+                   hipStream_t st) {
+  const int rw = epi == GEMV_GLU_BF16 ? 2 : 4;
+  const int blocks = (N + 4 * rw - 1) / (4 * rw);
+  switch (epi) {
+    case GEMV_STORE_F32:
+      hipLaunchKernelGGL((gemv_kernel<M, GEMV_STORE_F32>), dim3(blocks), dim3(256), 0, st, x, W, out, N, K, ldo, act);
+      break;
+    case GEMV_ADD_F32:
+      hipLaunchKernelGGL((gemv_kernel<M, GEMV_ADD_F32>), dim3(blocks), dim3(256), 0, st, x, W, out, N, K, ldo, act);
+      break;
+    default:
+      hipLaunchKernelGGL((gemv_kernel<M, GEMV_GLU_BF16>), dim3(blocks), dim3(256), 0, st, x, W, out, N, K, ldo, act);
+  }
+}
+
+}  // namespace decode_impl
+using namespace decode_impl;
+
+void launch_gemv(const bf16_t* x, const bf16_t* W, void* out, int M, int N, int K, int64_t ldo, int epilogue,
+                 int act, hipStream_t st) {
+  if (M <= 0 || N <= 0) return;
+  // rows are processed in groups of at most 8 (weights are re-streamed per group)
+  const size_t osz = epilogue == GEMV_GLU_BF16 ? 2 : 4;
+  for (int m0 = 0; m0 < M; m0 += 8) {
+    const int mm = M - m0 < 8 ? M - m0 : 8;
+    const bf16_t* xs = x + (size_t)m0 * K;
+    void* os = reinterpret_cast<char*>(out) + (size_t)m0 * ldo * osz;
+    if (mm == 1) launch_gemv_m<1>(xs, W, os, N, K, ldo, epilogue, act, st);
+    else if (mm == 2) launch_gemv_m<2>(xs, W, os, N, K, ldo, epilogue, act, st);
+    else if (mm <= 4) {
+      // pad to 4 rows by processing 2+2 / 2+1 splits would re-stream weights; use exact sizes instead
+      if (mm == 3) { launch_gemv_m<2>(xs, W, os, N, K, ldo, epilogue, act, st);
+                     launch_gemv_m<1>(xs + 2 * (size_t)K, W, reinterpret_cast<char*>(os) + 2 * ldo * osz, N, K, ldo, epilogue, act, st); }
+      else launch_gemv_m<4>(xs, W, os, N, K, ldo, epilogue, act, st);
+    } else if (mm == 8) launch_gemv_m<8>(xs, W, os, N, K, ldo, epilogue, act, st);
+    else {  // 5..7: 4 + remainder
+      launch_gemv_m<4>(xs, W, os, N, K, ldo, epilogue, act, st);
+      launch_gemv(xs + 4 * (size_t)K, W, reinterpret_cast<char*>(os) + 4 * ldo * osz, mm - 4, N, K, ldo, epilogue, act, st);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------- RoPE + append
+namespace decode_impl {
+__global__ __launch_bounds__(128) void rope_append_kernel(const float* __restrict__ qkv, int ld,
+                                                          bf16_t* __restrict__ q_out, int n_q_heads,
+                                                          int n_kv_heads, int hd, const int32_t* __restrict__ pos,
+                                                          const int32_t* __restrict__ slot,
+                                                          double neg2_over_hd_log2theta, bf16_t* __restrict__ k_pool,
+                                                          bf16_t* __restrict__ v_pool, int P) {
+  const int b = blockIdx.x, head = blockIdx.y;
+  const int half = hd >> 1;
+  const int i = threadIdx.x;
+  if (i >= half) return;
+  const float* row = qkv + (size_t)b * ld + (size_t)head * hd;
+  const int s = slot[b];
+  if (head < n_q_heads + n_kv_heads) {
+    const double ang = (double)pos[b] * exp2((double)i * neg2_over_hd_log2theta);
+    double sd, cd;
+    sincos(ang, &sd, &cd);
+    const float c = (float)cd, sn = (float)sd;
+    const float x = row[i], y = row[i + half];
+    const bf16_t lo = f32_to_bf16(x * c - y * sn), hi = f32_to_bf16(y * c + x * sn);
+    if (head < n_q_heads) {
+      bf16_t* o = q_out + ((size_t)b * n_q_heads + head) * hd;
+      o[i] = lo;
+      o[i + half] = hi;
+    } else {
+      const int hh = head - n_q_heads;
+      bf16_t* o = k_pool + (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
+      o[i] = lo;
+      o[i + half] = hi;
+    }
+  } else {
+    const int hh = head - n_q_heads - n_kv_heads;
+    bf16_t* o = v_pool + (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
+    o[i] = f32_to_bf16(row[i]);
+    o[i + half] = f32_to_bf16(row[i + half]);
+  }
+}
+}  // namespace decode_impl
+using namespace decode_impl;
+
+void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
+                        const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool, bf16_t* v_pool,
+                        int page_size, int B, hipStream_t st) {
+  if (B <= 0) return;
+  hipLaunchKernelGGL(rope_append_kernel, dim3(B, n_q_heads + 2 * n_kv_heads), dim3(128), 0, st, qkv, ld, q_out,
+                     n_q_heads, n_kv_heads, hd, pos, slot, -2.0 / (double)hd * log2(theta), k_pool, v_pool,
+                     page_size);
+}
+
+// ------------------------------------------------------------------------------------- decode attention
+namespace decode_impl {
+
+constexpr int KCH = 256;  // keys per work-group (one split)
+constexpr int GMAX = 8;   // query heads per KV head
+
+// grid (n_splits, Hkv, B), 256 threads.  Split s of sequence b covers keys lo + s*KCH .. +KCH-1,
+// lo = first visible key.  Writes the unnormalised partial output, its max and its sum.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a, float scale) {
+  constexpr int LPK = HD / 8;        // lanes per key (16-byte chunk each)
+  constexpr int KPI = 256 / LPK;     // keys per block iteration
+  __shared__ float sc[GMAX][KCH];
+  __shared__ float red[4][GMAX][HD];  // one partial per wave
+  __shared__ float stat[GMAX][2];
+
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int G = a.n_q_heads / a.n_kv_heads;
+  const int P = a.page_size;
+  const int qpos = a.pos[b];
+  const int lo = a.window > 0 ? max(0, qpos - a.window + 1) : 0;
+  const int k_first = lo + split * KCH;
+  const int n_keys = min(KCH, qpos + 1 - k_first);  // <= 0: this split is empty
+  const int tid = threadIdx.x;
+  const int li = tid % LPK, kslot = tid / LPK;
+  const int32_t* bt = a.block_table + (size_t)b * a.max_pages;
+  float* part = a.part + (((size_t)b * a.n_q_heads + (size_t)kvh * G) * a.n_splits + split) * (HD + 2);
+  const size_t part_head_stride = (size_t)a.n_splits * (HD + 2);
+
+  if (n_keys <= 0) {
+    for (int i = tid; i < G * (HD + 2); i += 256) {
+      const int g = i / (HD + 2), e = i % (HD + 2);
+      part[g * part_head_stride + e] = e == HD ? -INFINITY : 0.f;
+    }
+    return;
+  }
+
+  // ---- scores
+  float qv[GMAX][8];
+#pragma unroll
+  for (int g = 0; g < GMAX; ++g) {
+    if (g < G) {
+      const uint4 w = *reinterpret_cast<const uint4*>(a.q + ((size_t)b * a.n_q_heads + kvh * G + g) * HD + li * 8);
+      qv[g][0] = bf16lo(w.x); qv[g][1] = bf16hi(w.x); qv[g][2] = bf16lo(w.y); qv[g][3] = bf16hi(w.y);
+      qv[g][4] = bf16lo(w.z); qv[g][5] = bf16hi(w.z); qv[g][6] = bf16lo(w.w); qv[g][7] = bf16hi(w.w);
+    }
+  }
+  for (int kk = kslot; kk < KCH; kk += KPI) {
+    float s[GMAX];
+#pragma unroll
+    for (int g = 0; g < GMAX; ++g) s[g] = 0.f;
+    if (kk < n_keys) {
+      const int key = k_first + kk;
+      const int page = bt[key / P];
+      const uint4 w = *reinterpret_cast<const uint4*>(
+          a.k_pool + (((size_t)page * a.n_kv_heads + kvh) * P + (key % P)) * HD + li * 8);
+      const float kf[8] = {bf16lo(w.x), bf16hi(w.x), bf16lo(w.y), bf16hi(w.y),
+                           bf16lo(w.z), bf16hi(w.z), bf16lo(w.w), bf16hi(w.w)};
+#pragma unroll
+      for (int g = 0; g < GMAX; ++g)
+        if (g < G) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) s[g] += qv[g][e] * kf[e];
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < GMAX; ++g)
+      if (g < G) {
+#pragma unroll
+        for (int o = LPK / 2; o > 0; o >>= 1) s[g] += __shfl_xor(s[g], o, 64);
+        if (li == 0) sc[g][kk] = kk < n_keys ? s[g] * scale : -INFINITY;
+      }
+  }
+  __syncthreads();
+  // ---- per-head max and exp-sum (wave w handles heads w, w+4)
+  {
+    const int w = tid >> 6, lane = tid & 63;
+    for (int g = w; g < G; g += 4) {
+      float mx = -INFINITY;
+      for (int i = lane; i < KCH; i += 64) mx = fmaxf(mx, sc[g][i]);
+      mx = wave_max(mx);
+      float sum = 0.f;
+      for (int i = lane; i < KCH; i += 64) {
+        const float pv = __expf(sc[g][i] - mx);
+        sc[g][i] = pv;
+        sum += pv;
+      }
+      sum = wave_sum(sum);
+      if (lane == 0) { stat[g][0] = mx; stat[g][1] = sum; }
+    }
+  }
+  __syncthreads();
+  // ---- partial O = P V : thread owns 8 head-dim values, strides over keys
+  float acc[GMAX][8];
+#pragma unroll
+  for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+  for (int kk = kslot; kk < n_keys; kk += KPI) {
+    const int key = k_first + kk;
+    const int page = bt[key / P];
+    const uint4 w = *reinterpret_cast<const uint4*>(
+        a.v_pool + (((size_t)page * a.n_kv_heads + kvh) * P + (key % P)) * HD + li * 8);
+    const float vf[8] = {bf16lo(w.x), bf16hi(w.x), bf16lo(w.y), bf16hi(w.y),
+                         bf16lo(w.z), bf16hi(w.z), bf16lo(w.w), bf16hi(w.w)};
+#pragma unroll
+    for (int g = 0; g < GMAX; ++g)
+      if (g < G) {
+        const float pv = sc[g][kk];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] += pv * vf[e];
+      }
+  }
+  // lanes li, li + LPK, ... of a wave hold the same head-dim slice: add them, then add the 4 waves
+#pragma unroll
+  for (int g = 0; g < GMAX; ++g)
+    if (g < G) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float v = acc[g][e];
+#pragma unroll
+        for (int o = LPK; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
+        acc[g][e] = v;
+      }
+      if ((tid & 63) < LPK) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[tid >> 6][g][li * 8 + e] = acc[g][e];
+      }
+    }
+  __syncthreads();
+  for (int i = tid; i < G * HD; i += 256) {
+    const int g = i / HD, e = i % HD;
+    part[g * part_head_stride + e] = (red[0][g][e] + red[1][g][e]) + (red[2][g][e] + red[3][g][e]);
+  }
+  if (tid < G) {
+    part[tid * part_head_stride + HD] = stat[tid][0];
+    part[tid * part_head_stride + HD + 1] = stat[tid][1];
+  }
+}
+
+// grid (B * Hq), HD threads: merge the splits in index order.
+__global__ void attn_decode_combine_kernel(const float* __restrict__ part, bf16_t* __restrict__ out, int n_splits,
+                                           int hd) {
+  const size_t bh = blockIdx.x;
+  const int i = threadIdx.x;
+  const float* p = part + bh * n_splits * (hd + 2);
+  float mx = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, p[s * (hd + 2) + hd]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float m = p[s * (hd + 2) + hd];
+    const float w = m == -INFINITY ? 0.f : __expf(m - mx);
+    num += w * p[s * (hd + 2) + i];
+    den += w * p[s * (hd + 2) + hd + 1];
+  }
+  out[bh * hd + i] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+}
+
+template <int HD>
+void launch_decode_hd(const AttnDecodeArgs& a, hipStream_t st) {
+  const float scale = 1.f / sqrtf((float)HD);
+  hipLaunchKernelGGL(attn_decode_split_kernel<HD>, dim3(a.n_splits, a.n_kv_heads, a.B), dim3(256), 0, st, a, scale);
+  hipLaunchKernelGGL(attn_decode_combine_kernel, dim3(a.B * a.n_q_heads), dim3(HD), 0, st, a.part, a.out,
+                     a.n_splits, HD);
+}
+}  // namespace decode_impl
+using namespace decode_impl;
+
+void launch_attention_decode(const AttnDecodeArgs& a, hipStream_t st) {
+  if (a.B <= 0) return;
+  switch (a.hd) {
+    case 64: launch_decode_hd<64>(a, st); break;
+    case 128: launch_decode_hd<128>(a, st); break;
+    case 256: launch_decode_hd<256>(a, st); break;
+  }
+}
+
+}  // namespace pop

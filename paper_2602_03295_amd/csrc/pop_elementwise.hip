@@ -1,0 +1,246 @@
+// Bandwidth-bound steps of the POP prefill path for gfx950: embedding gather, RMSNorm (the LN of
+// Sec. 2.1), the RoPE angle table, and RoPE + KV-cache append (Sec. 2.1, K/V generation and cache
+// append; the same kernel serves the independent KV projections of Sec. 3.3).
+#include "pop_device.h"
+#include "pop_kernels.h"
+
+namespace pop {
+
+// ------------------------------------------------------------------------------------- embed
+__global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ table,
+                                                    const int32_t* __restrict__ tokens,
+                                                    const int32_t* __restrict__ row_src,
+                                                    const bf16_t* __restrict__ embeds,
+                                                    float* __restrict__ h, int d) {
+  const int t = blockIdx.x;
+  const int src = row_src ? row_src[t] : -1;
+  const bf16_t* row = src < 0 ? table + (size_t)tokens[t] * d : embeds + (size_t)src * d;
+  float* dst = h + (size_t)t * d;
+  for (int i = threadIdx.x * 8; i < d; i += 256 * 8) {
+    const uint4 v = *reinterpret_cast<const uint4*>(row + i);
+    float4 a = make_float4(bf16lo(v.x), bf16hi(v.x), bf16lo(v.y), bf16hi(v.y));
+    float4 b = make_float4(bf16lo(v.z), bf16hi(v.z), bf16lo(v.w), bf16hi(v.w));
+    *reinterpret_cast<float4*>(dst + i) = a;
+    *reinterpret_cast<float4*>(dst + i + 4) = b;
+  }
+}
+
+void launch_embed(const bf16_t* table, const int32_t* tokens, const int32_t* row_src,
+                  const bf16_t* embeds, float* h, int T, int d, hipStream_t st) {
+  if (T <= 0) return;
+  hipLaunchKernelGGL(embed_kernel, dim3(T), dim3(256), 0, st, table, tokens, row_src, embeds, h, d);
+}
+
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restrict__ src,
+                                                          const int32_t* __restrict__ idx,
+                                                          float* __restrict__ dst, int d) {
+  const float* s = src + (size_t)idx[blockIdx.x] * d;
+  float* o = dst + (size_t)blockIdx.x * d;
+  for (int i = threadIdx.x * 4; i < d; i += 256 * 4)
+    *reinterpret_cast<float4*>(o + i) = *reinterpret_cast<const float4*>(s + i);
+}
+
+void launch_gather_rows(const float* src, const int32_t* idx, float* dst, int rows, int d, hipStream_t st) {
+  if (rows <= 0) return;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(rows), dim3(256), 0, st, src, idx, dst, d);
+}
+
+// ------------------------------------------------------------------------------------- RMSNorm
+// One 256-thread block per row; the row stays in registers between the statistics and the scaling
+// (up to 8 float4 per thread, d <= 8192), so x is read from HBM once.
+constexpr int kNormMaxV = 8;
+
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ add1,
+                                                      const float* __restrict__ add2, GammaList gammas,
+                                                      int n_out, bf16_t* __restrict__ out, size_t out_stride,
+                                                      const int32_t* __restrict__ row_idx, int d, float eps) {
+  __shared__ float red[4];
+  const int t = blockIdx.x;
+  const size_t src_row = row_idx ? (size_t)row_idx[t] : (size_t)t;
+  float* xr = x + src_row * d;
+  float4 v[kNormMaxV];
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < kNormMaxV; ++j) {
+    const int i = (j * 256 + threadIdx.x) * 4;
+    if (i < d) {
+      float4 a = *reinterpret_cast<const float4*>(xr + i);
+      if (add1) {
+        const float4 b = *reinterpret_cast<const float4*>(add1 + src_row * d + i);
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+        if (add2) {
+          const float4 c = *reinterpret_cast<const float4*>(add2 + src_row * d + i);
+          a.x += c.x; a.y += c.y; a.z += c.z; a.w += c.w;
+        }
+        *reinterpret_cast<float4*>(xr + i) = a;
+      }
+      v[j] = a;
+      ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+    }
+  }
+  const float total = block_sum_256(ss, red);
+  const float rstd = rsqrtf(total / (float)d + eps);
+  for (int o = 0; o < n_out; ++o) {
+    const float* g = gammas.g[o];
+    bf16_t* orow = out + (size_t)o * out_stride + (size_t)t * d;
+#pragma unroll
+    for (int j = 0; j < kNormMaxV; ++j) {
+      const int i = (j * 256 + threadIdx.x) * 4;
+      if (i < d) {
+        const float4 gg = *reinterpret_cast<const float4*>(g + i);
+        uint2 p;
+        p.x = pack_bf16x2(v[j].x * rstd * gg.x, v[j].y * rstd * gg.y);
+        p.y = pack_bf16x2(v[j].z * rstd * gg.z, v[j].w * rstd * gg.w);
+        *reinterpret_cast<uint2*>(orow + i) = p;
+      }
+    }
+  }
+}
+
+void launch_rmsnorm(float* x, const float* add1, const float* add2, const float* gamma, bf16_t* out,
+                    const int32_t* row_idx, int rows, int d, float eps, hipStream_t st) {
+  if (rows <= 0) return;
+  GammaList gl{};
+  gl.g[0] = gamma;
+  hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(256), 0, st, x, add1, add2, gl, 1, out, (size_t)0,
+                     row_idx, d, eps);
+}
+
+void launch_rmsnorm_multi(const float* x, GammaList gammas, int n_out, bf16_t* out, size_t out_stride,
+                          int rows, int d, float eps, hipStream_t st) {
+  if (rows <= 0 || n_out <= 0) return;
+  hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(256), 0, st, const_cast<float*>(x),
+                     (const float*)nullptr, (const float*)nullptr, gammas, n_out, out, out_stride,
+                     (const int32_t*)nullptr, d, eps);
+}
+
+// ------------------------------------------------------------------------------------- RoPE table
+__global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restrict__ pos,
+                                                         float2* __restrict__ cs, int T, int half,
+                                                         double neg2_over_hd_log2theta) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= T * half) return;
+  const int t = i / half, f = i - t * half;
+  const double inv_freq = exp2((double)f * neg2_over_hd_log2theta);
+  const double ang = (double)pos[t] * inv_freq;
+  double s, c;
+  sincos(ang, &s, &c);
+  cs[i] = make_float2((float)c, (float)s);
+}
+
+void launch_rope_table(const int32_t* pos, float2* cs, int T, int hd, double theta, hipStream_t st) {
+  if (T <= 0) return;
+  const int half = hd / 2;
+  const int n = T * half;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, pos, cs, T, half,
+                     -2.0 / (double)hd * log2(theta));
+}
+
+// ------------------------------------------------------------------------------------- RoPE + cache append
+// grid = (tiles of 64 positions, heads); a block handles one head of one tile.
+//   q head: rotate in place.   k head: rotate in place + store to the K pool.
+//   v head: store to the V pool (+ transposed copy vT[h][i][col], zero beyond the sequence end).
+__global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a) {
+  __shared__ uint16_t tr[256 * 66];  // [hd][64 + 2] transposed V tile
+  const int tile = blockIdx.x;
+  const int b = a.tile_seq[tile];
+  const int p0 = a.tile_start[tile];
+  const int seq0 = a.cu_seqlens[b];
+  const int len = a.cu_seqlens[b + 1] - seq0;
+  const int hd = a.hd, half = hd >> 1;
+  int head = blockIdx.y;
+  const int nq = a.q_col >= 0 ? a.n_q_heads : 0;
+  const int P = a.page_size;
+
+  if (head < nq + a.n_kv_heads) {
+    // ---- rotate (q or k)
+    const bool is_k = head >= nq;
+    const int hh = is_k ? head - nq : head;
+    const int col = (is_k ? a.k_col : a.q_col) + hh * hd;
+    const int groups = half >> 3;  // 8 pairs per work item
+    for (int it = threadIdx.x; it < 64 * groups; it += 256) {
+      const int p = it / groups, g = it - p * groups;
+      if (p0 + p >= len) continue;
+      const size_t t = (size_t)seq0 + p0 + p;
+      bf16_t* row = a.qkv + t * a.ld + col;
+      const uint4 lo = *reinterpret_cast<const uint4*>(row + g * 8);
+      const uint4 hi = *reinterpret_cast<const uint4*>(row + half + g * 8);
+      const float2* cs = a.cs + t * half + g * 8;
+      const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+      uint32_t ol[4], oh[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
+        const float x0 = bf16lo(lw[e]), x1 = bf16hi(lw[e]);
+        const float y0 = bf16lo(hw[e]), y1 = bf16hi(hw[e]);
+        ol[e] = pack_bf16x2(x0 * c0.x - y0 * c0.y, x1 * c1.x - y1 * c1.y);
+        oh[e] = pack_bf16x2(y0 * c0.x + x0 * c0.y, y1 * c1.x + x1 * c1.y);
+      }
+      const uint4 vlo = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+      const uint4 vhi = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+      *reinterpret_cast<uint4*>(row + g * 8) = vlo;
+      *reinterpret_cast<uint4*>(row + half + g * 8) = vhi;
+      if (is_k && a.k_pool) {
+        const int s = a.slot[t];
+        bf16_t* dst = a.k_pool + (((size_t)(s / P) * a.n_kv_heads + hh) * P + (s % P)) * hd;
+        *reinterpret_cast<uint4*>(dst + g * 8) = vlo;
+        *reinterpret_cast<uint4*>(dst + half + g * 8) = vhi;
+      }
+    }
+    return;
+  }
+  // ---- v head
+  const int hh = head - nq - a.n_kv_heads;
+  const int col = a.v_col + hh * hd;
+  const int groups = hd >> 3;
+  for (int it = threadIdx.x; it < 64 * groups; it += 256) {
+    const int p = it / groups, g = it - p * groups;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (p0 + p < len) {
+      const size_t t = (size_t)seq0 + p0 + p;
+      v = *reinterpret_cast<const uint4*>(a.qkv + t * a.ld + col + g * 8);
+      if (a.v_pool) {
+        const int s = a.slot[t];
+        bf16_t* dst = a.v_pool + (((size_t)(s / P) * a.n_kv_heads + hh) * P + (s % P)) * hd;
+        *reinterpret_cast<uint4*>(dst + g * 8) = v;
+      }
+    }
+    if (a.vT) {
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        tr[(g * 8 + 2 * e) * 66 + p] = (uint16_t)(w[e] & 0xffff);
+        tr[(g * 8 + 2 * e + 1) * 66 + p] = (uint16_t)(w[e] >> 16);
+      }
+    }
+  }
+  if (!a.vT) return;
+  __syncthreads();
+  const size_t colbase = (size_t)a.vt_off[b] + p0;
+  for (int it = threadIdx.x; it < hd * 8; it += 256) {
+    const int i = it >> 3, c = it & 7;
+    const uint16_t* s = tr + i * 66 + c * 8;
+    uint4 o;
+    o.x = s[0] | ((uint32_t)s[1] << 16);
+    o.y = s[2] | ((uint32_t)s[3] << 16);
+    o.z = s[4] | ((uint32_t)s[5] << 16);
+    o.w = s[6] | ((uint32_t)s[7] << 16);
+    *reinterpret_cast<uint4*>(a.vT + ((size_t)hh * hd + i) * a.Tp + colbase + c * 8) = o;
+  }
+}
+
+void launch_rope_write(const RopeWriteArgs& a, hipStream_t st) {
+  if (a.n_tiles <= 0) return;
+  const int nq = a.q_col >= 0 ? a.n_q_heads : 0;
+  hipLaunchKernelGGL(rope_write_kernel, dim3(a.n_tiles, nq + 2 * a.n_kv_heads), dim3(256), 0, st, a);
+}
+
+}  // namespace pop

@@ -1,0 +1,141 @@
+// Internal launch interface of the gfx950 kernels behind the POP C ABI.
+// Every function enqueues on `st` and returns; pointers are device pointers unless said otherwise.
+// Shapes are validated by the callers in pop_api.cpp; launchers only assert what the kernel's
+// indexing relies on.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pop {
+
+typedef uint16_t bf16_t;  // raw bf16 bits in memory
+
+// ---------------------------------------------------------------------------------------------
+// Elementwise / bandwidth-bound steps (pop_elementwise.hip)
+// ---------------------------------------------------------------------------------------------
+// h[t,:] = row_src[t] < 0 ? table[tokens[t],:] : embeds[row_src[t],:]      (fp32 residual stream)
+void launch_embed(const bf16_t* table, const int32_t* tokens, const int32_t* row_src,
+                  const bf16_t* embeds, float* h, int T, int d, hipStream_t st);
+
+// out[t,:] = bf16( x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * gamma )   -- LN(.) of Sec. 2.1
+// If row_idx != nullptr the source row of output row t is row_idx[t] (gather).
+// If add1/add2 != nullptr they are first added into x (x is updated in place): this is how the
+// partial sums of a split-K projection reach the residual stream.
+void launch_rmsnorm(float* x, const float* add1, const float* add2, const float* gamma,
+                    bf16_t* out, const int32_t* row_idx, int rows, int d, float eps, hipStream_t st);
+
+// Same statistics, several scales: out[j][t,:] = bf16(x[t,:] * rstd[t] * gammas[j]), j < n_out <= 8.
+// Used by the K/V-only path of Sec. 3.3, where all pruned layers see the same hidden state.
+struct GammaList {
+  const float* g[8];
+};
+void launch_rmsnorm_multi(const float* x, GammaList gammas, int n_out, bf16_t* out, size_t out_stride,
+                          int rows, int d, float eps, hipStream_t st);
+
+// cs[t, i] = (cos, sin)(pos[t] * theta^(-2 i / hd)), i < hd/2, angle formed in fp64.
+void launch_rope_table(const int32_t* pos, float2* cs, int T, int hd, double theta, hipStream_t st);
+
+// Prefill RoPE + cache append for one layer.  Work is organised in tiles of 64 consecutive
+// positions of one sequence: tile i covers positions tile_start[i] .. +63 of sequence tile_seq[i].
+struct RopeWriteArgs {
+  bf16_t* qkv;            // [T, ld] rows q | k | v ; q and k are rotated in place (nullptr q part ok)
+  int ld;                 // row stride in elements
+  int q_col, k_col, v_col;  // first column of q / k / v inside a row (q_col < 0: no q heads)
+  int n_q_heads, n_kv_heads, hd;
+  const float2* cs;       // [T, hd/2]
+  const int32_t* slot;    // [T] cache slot of each packed token
+  const uint8_t* skip;    // [T] or nullptr: 1 = do not write this row's cache entry
+  bf16_t* k_pool;         // this layer's K pool [page][Hkv][P][hd]
+  bf16_t* v_pool;
+  int page_size;
+  bf16_t* vT;             // nullptr or [Hkv][hd][Tp]: transposed copy of V for the attention kernel
+  int Tp;
+  const int32_t* cu_seqlens;  // [B+1]
+  const int32_t* vt_off;      // [B] first column of each sequence in vT (multiple of 64)
+  const int32_t* tile_seq;    // [n_tiles]
+  const int32_t* tile_start;  // [n_tiles]
+  int n_tiles;
+};
+void launch_rope_write(const RopeWriteArgs& a, hipStream_t st);
+
+// ---------------------------------------------------------------------------------------------
+// bf16 MFMA GEMM (pop_gemm.hip):  C = A[M,K] * W[N,K]^T, fp32 accumulate
+// ---------------------------------------------------------------------------------------------
+enum GemmEpilogue {
+  EPI_STORE_BF16 = 0,  // out bf16 [M, ldc]
+  EPI_ADD_F32 = 1,     // out fp32 [M, ldc]: out += C           (residual update)
+  EPI_GLU_BF16 = 2,    // W is [2N, K] (gate rows then up rows); out bf16 [M, ldc] = act(gate) * up
+  EPI_STORE_F32 = 3    // out fp32 [M, ldc] = C
+};
+struct GemmArgs {
+  const bf16_t* A;   // [M, lda]
+  const bf16_t* W;   // [N, ldw]   (EPI_GLU: [2N, ldw])
+  void* out;
+  int M, N, K;
+  int64_t lda, ldw, ldc;
+  int epilogue;
+  int act;           // EPI_GLU only: 0 SiLU, 1 tanh-GELU
+  // batched form (the K/V-only path): batch b uses A + b*strideA, W_list[b], out + b*strideC elems
+  int batch;                 // 1 = plain
+  int64_t strideA, strideC;  // in elements
+  const bf16_t* const* W_list;  // DEVICE array of `batch` weight pointers, or nullptr for plain
+};
+// Returns hipSuccess or the launch error.  Requirements: K % 8 == 0, lda/ldw % 8 == 0,
+// A/W 16-byte aligned, ldc % 4 == 0, and every operand below 2^31 bytes.
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t st);
+
+// ---------------------------------------------------------------------------------------------
+// Causal GQA flash attention over packed variable-length sequences (pop_attention.hip)
+// ---------------------------------------------------------------------------------------------
+struct AttnPrefillArgs {
+  const bf16_t* qkv;  // rotated q and k inside [T, ld]
+  int ld, q_col, k_col;
+  const bf16_t* vT;   // [Hkv][hd][Tp]
+  int Tp;
+  bf16_t* out;        // [T, Hq*hd]
+  int T, n_q_heads, n_kv_heads, hd;
+  int window;         // 0 = global
+  const int32_t* cu_seqlens;
+  const int32_t* vt_off;
+  const int32_t* tile_seq;    // query tiles of 128 rows: sequence and first position
+  const int32_t* tile_start;
+  int n_tiles;
+};
+hipError_t launch_attention_prefill(const AttnPrefillArgs& a, hipStream_t st);
+
+// ---------------------------------------------------------------------------------------------
+// Decode-step kernels for the boundary rows (pop_decode.hip); rows = sequences, M <= 8 per launch
+// ---------------------------------------------------------------------------------------------
+enum GemvEpilogue { GEMV_STORE_F32 = 0, GEMV_ADD_F32 = 1, GEMV_GLU_BF16 = 2 };
+// out[m, n] (op)= sum_k x[m,k] * W[n,k], x bf16 [M, K] (M <= 8), W bf16 [N, K] ([2N, K] for GLU).
+void launch_gemv(const bf16_t* x, const bf16_t* W, void* out, int M, int N, int K, int64_t ldo,
+                 int epilogue, int act, hipStream_t st);
+
+// RoPE of one new token per sequence + cache append: qkv fp32 [B, ld] -> q bf16 [B, Hq*hd] rotated,
+// k (rotated) and v stored at slot[b].
+void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
+                        const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool,
+                        bf16_t* v_pool, int page_size, int B, hipStream_t st);
+
+// Attention of one query row per sequence over its paged cache entries 0..len-1 (len = pos + 1),
+// split over the key range; `part` holds the per-split partial results.
+struct AttnDecodeArgs {
+  const bf16_t* q;      // [B, Hq*hd]
+  const bf16_t* k_pool;
+  const bf16_t* v_pool;
+  const int32_t* block_table;  // [B, max_pages]
+  int max_pages, page_size;
+  const int32_t* pos;   // [B] position of the query token (attends 0..pos)
+  int window;
+  int B, n_q_heads, n_kv_heads, hd;
+  int n_splits;         // key range of every sequence is cut into n_splits equal chunks
+  int max_len;          // upper bound of pos+1 over the batch
+  float* part;          // [B, Hq, n_splits, hd + 2]
+  bf16_t* out;          // [B, Hq*hd]
+};
+void launch_attention_decode(const AttnDecodeArgs& a, hipStream_t st);
+
+// gather fp32 rows: dst[i,:] = src[idx[i],:]
+void launch_gather_rows(const float* src, const int32_t* idx, float* dst, int rows, int d, hipStream_t st);
+
+}  // namespace pop

@@ -1,0 +1,73 @@
+"""Helpers for the GPU parity tests: run the HIP path through the C ABI binding and fetch what it
+wrote, next to the oracle's result for the same seeded inputs."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import pop_oracle as O
+from paper_2602_03295_amd import synth
+
+TOL = 2e-2   # spec bound: per-tensor max|gpu - ref| / max|ref|, bf16 path vs the fp64 oracle
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    den = float(np.max(np.abs(ref)))
+    return float(np.max(np.abs(got.astype(np.float64) - ref))) / (den if den > 0 else 1.0)
+
+
+class GpuRun:
+    def __init__(self, pop, cfg, W, lens, reserve_pages=1, shuffle_seed=None, poison=None):
+        self.pop, self.cfg, self.lens = pop, cfg, list(lens)
+        self.dev_w = pop.upload_weights(cfg, W)
+        self.model = pop.Model(cfg, self.dev_w)
+        P = cfg["page_size"]
+        self.bt, self.n_pages = synth.make_block_table(self.lens, P, reserve_pages, shuffle_seed)
+        self.cache = pop.Cache(cfg, self.n_pages, len(lens), self.bt.shape[1], fill=poison)
+        self.cu = np.concatenate([[0], np.cumsum(self.lens)]).astype(np.int32)
+        self.ws = pop.alloc_workspace(cfg, int(self.cu[-1]), len(lens), self.bt.shape[1])
+
+    def prefill(self, tokens, l_keep, mode=0, embeds=None, embed_ranges=None):
+        logits = self.pop.pop_prefill(self.model, self.cache, tokens, self.cu, self.bt, l_keep, self.ws, mode=mode,
+                                      embeds=embeds, embed_ranges=embed_ranges)
+        torch.cuda.synchronize()
+        return None if logits is None else logits.cpu().numpy()
+
+    def decode(self, tokens):
+        logits = self.pop.pop_decode_step(self.model, self.cache, tokens, self.ws)
+        torch.cuda.synchronize()
+        return logits.cpu().numpy()
+
+    def kv(self, layer, b, length=None):
+        """K, V entries of sequence b in layer `layer` (0-based) as float arrays [len, Hkv, hd]."""
+        n = self.lens[b] if length is None else length
+        k = self.cache.gather(layer, 0, self.bt[b], n).float().cpu().numpy()
+        v = self.cache.gather(layer, 1, self.bt[b], n).float().cpu().numpy()
+        return k, v
+
+
+def compare_with_oracle(run: GpuRun, W, tokens, l_keep, gpu_logits, embeds=None, embed_ranges=(), tol=TOL,
+                        lengths=None):
+    """Element-by-element comparison of every layer's K and V and of the logits, per sequence.
+    Returns the worst relative errors and the oracle's outputs."""
+    cfg = run.cfg
+    outs = O.pop_prefill_batch(cfg, W, tokens, run.cu, l_keep, embeds=embeds, embed_ranges=embed_ranges)
+    worst = {"k": 0.0, "v": 0.0, "logits": 0.0}
+    for b, (Kc, Vc, logits) in enumerate(outs):
+        for l in range(cfg["n_layers"]):
+            k, v = run.kv(l, b)
+            ek, ev = rel_err(k, Kc[l]), rel_err(v, Vc[l])
+            assert ek <= tol, f"K of layer {l + 1}, sequence {b}: rel err {ek:.4f} > {tol}"
+            assert ev <= tol, f"V of layer {l + 1}, sequence {b}: rel err {ev:.4f} > {tol}"
+            worst["k"], worst["v"] = max(worst["k"], ek), max(worst["v"], ev)
+        el = rel_err(gpu_logits[b], logits)
+        assert el <= tol, f"logits of sequence {b}: rel err {el:.4f} > {tol}"
+        worst["logits"] = max(worst["logits"], el)
+        # first generated token: identical argmax unless the oracle's own top-2 gap is inside the
+        # measured absolute error (then both answers are within tolerance of each other)
+        top = np.argsort(logits)[-2:]
+        gap = float(logits[top[1]] - logits[top[0]])
+        abs_err = float(np.max(np.abs(gpu_logits[b] - logits)))
+        if gap > 2 * abs_err:
+            assert int(np.argmax(gpu_logits[b])) == int(top[1]), f"argmax differs for sequence {b}"
+    return worst, outs

@@ -1,0 +1,137 @@
+"""Per-step parity on the GPU: each HIP kernel, called through the C ABI, against the oracle's
+same step on the same seeded inputs (bf16-rounded where the kernel takes bf16)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pop_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pop():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2602_03295_amd import pop as p
+    return p
+
+
+def bf16_round(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(a).float().to(torch.bfloat16)
+
+
+def rel(got, ref):
+    return float(np.max(np.abs(got.astype(np.float64) - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+
+
+@pytest.mark.parametrize("rows,d", [(1, 256), (37, 4096), (5, 3840), (300, 8192), (3, 264)])
+def test_rmsnorm(pop, rows, d):
+    rng = np.random.default_rng(rows * 7 + d)
+    x = rng.standard_normal((rows, d)).astype(np.float32) * 3
+    g = (1 + 0.1 * rng.standard_normal(d)).astype(np.float32)
+    out = pop.pop_op_rmsnorm(torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda(), 1e-5)
+    torch.cuda.synchronize()
+    ref = O.rmsnorm(x.astype(np.float64), g.astype(np.float64), 1e-5)
+    got = out.float().cpu().numpy()
+    assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-30)
+
+
+GEMM_SHAPES = [(128, 128, 64), (300, 200, 264), (1, 8, 8), (257, 513, 1000), (2048, 8192, 256), (515, 4100, 136),
+               (64, 96, 4096)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("epi", [0, 1, 3])
+def test_gemm(pop, M, N, K, epi):
+    rng = np.random.default_rng(M + 3 * N + 5 * K + epi)
+    A = bf16_round(rng.standard_normal((M, K)).astype(np.float32))
+    W = bf16_round(rng.standard_normal((N, K)).astype(np.float32))
+    ref = A.double().numpy() @ W.double().numpy().T
+    out = None
+    if epi == 1:
+        base = rng.standard_normal((M, N)).astype(np.float32)
+        out = torch.from_numpy(base).cuda()
+        ref = ref + base
+    got = pop.pop_op_gemm(A.cuda(), W.cuda(), epilogue=epi, out=out)
+    torch.cuda.synchronize()
+    got = got.float().cpu().numpy()
+    tol = 2.0 ** -8 if epi == 0 else 1e-5
+    assert rel(got, ref) <= tol, (rel(got, ref), tol)
+
+
+@pytest.mark.parametrize("M,N,K,act", [(200, 344, 256, 0), (2048, 4096, 128, 1), (130, 688, 256, 0), (33, 64, 72, 1)])
+def test_gemm_glu(pop, M, N, K, act):
+    rng = np.random.default_rng(M + N + K)
+    A = bf16_round(rng.standard_normal((M, K)).astype(np.float32) * 0.3)
+    W = bf16_round(rng.standard_normal((2 * N, K)).astype(np.float32) * 0.3)
+    Ad, Wd = A.double().numpy(), W.double().numpy()
+    ref = O.glu_act(Ad @ Wd[:N].T, act) * (Ad @ Wd[N:].T)
+    got = pop.pop_op_gemm(A.cuda(), W.cuda(), epilogue=2, act=act)
+    torch.cuda.synchronize()
+    assert got.shape == (M, N)
+    assert rel(got.float().cpu().numpy(), ref) <= 2.0 ** -7
+
+
+def test_gemm_strided_operands(pop):
+    """A and the output may be column slices of wider buffers (q inside a q|k|v row)."""
+    rng = np.random.default_rng(11)
+    buf = bf16_round(rng.standard_normal((200, 640)).astype(np.float32)).cuda()
+    W = bf16_round(rng.standard_normal((96, 256)).astype(np.float32)).cuda()
+    A = buf[:, 128:384]
+    out = torch.zeros(200, 256, dtype=torch.float32, device="cuda")
+    pop.pop_op_gemm(A, W, epilogue=3, out=out[:, 64:160])
+    torch.cuda.synchronize()
+    ref = A.double().cpu().numpy() @ W.double().cpu().numpy().T
+    assert rel(out[:, 64:160].cpu().numpy(), ref) <= 1e-5
+    assert float(out[:, :64].abs().max()) == 0 and float(out[:, 160:].abs().max()) == 0
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 7, 8, 11])
+@pytest.mark.parametrize("epi", [0, 1, 2])
+def test_gemv(pop, M, epi):
+    N, K = 1003 if epi != 2 else 1002, 688
+    rng = np.random.default_rng(M * 10 + epi)
+    x = bf16_round(rng.standard_normal((M, K)).astype(np.float32) * 0.3)
+    W = bf16_round(rng.standard_normal(((2 if epi == 2 else 1) * N, K)).astype(np.float32) * 0.3)
+    xd, Wd = x.double().numpy(), W.double().numpy()
+    out = None
+    if epi == 2:
+        ref = O.glu_act(xd @ Wd[:N].T, 0) * (xd @ Wd[N:].T)
+    else:
+        ref = xd @ Wd.T
+        if epi == 1:
+            base = rng.standard_normal((M, N)).astype(np.float32)
+            out = torch.from_numpy(base).cuda()
+            ref = ref + base
+    got = pop.pop_op_gemv(x.cuda(), W.cuda(), epilogue=epi, act=0, out=out)
+    torch.cuda.synchronize()
+    assert rel(got.float().cpu().numpy(), ref) <= (2.0 ** -7 if epi == 2 else 1e-5)
+
+
+@pytest.mark.parametrize("hd,hq,hkv", [(64, 4, 2), (128, 8, 2), (256, 2, 1)])
+@pytest.mark.parametrize("window", [0, 100])
+def test_rope_attention_varlen(pop, hd, hq, hkv, window):
+    lens = [200, 1, 329, 64, 129]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    T = int(cu[-1])
+    rng = np.random.default_rng(hd + window)
+    ld = (hq + 2 * hkv) * hd
+    qkv = bf16_round(rng.standard_normal((T, ld)).astype(np.float32))
+    theta = 10000.0
+    out = pop.pop_op_rope_attention(qkv.cuda(), cu, hq, hkv, hd, theta, window)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy()
+    q64 = qkv.double().numpy()
+    worst = 0.0
+    for b, n in enumerate(lens):
+        rows = q64[cu[b]:cu[b + 1]]
+        pos = np.arange(n)
+        q = O.rope(rows[:, :hq * hd].reshape(n, hq, hd), pos, theta)
+        k = O.rope(rows[:, hq * hd:(hq + hkv) * hd].reshape(n, hkv, hd), pos, theta)
+        v = rows[:, (hq + hkv) * hd:].reshape(n, hkv, hd)
+        ref = O.attention_rows(q, pos, k, v, window)
+        worst = max(worst, rel(got[cu[b]:cu[b + 1]], ref))
+    assert worst <= 2e-2, worst
