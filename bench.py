@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the POP pruned-prefill hot path on one MI355X.
+
+A "step" is one pop_prefill call: embed -> kept layers -> K/V-only projections of the pruned layers ->
+boundary token at full depth -> logits, on one batch of synthetic input that is already resident in
+HBM.  The workload is the Llama-3.1-8B shape with a 2048-token prompt (bf16 random weights), the
+headline value is prefill tokens/s at L_keep = 24; the same run also times L_keep in {32, 28, 20} and
+reports the speedup over full-depth (L_keep = 32) prefill.
+
+Prints ONE JSON line.  Extra objects:
+  roofline     -- the dominant kernel (gate|up projection GEMM with fused GLU): algorithmic flops per
+                  launch / average launch duration measured with HIP events inside the library on
+                  the launch stream, against the bf16 dense MFMA peak.
+  cpu_baseline -- the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def device_weights(cfg, seed, torch):
+    """Random N(0, 0.02) bf16 weights drawn directly on the GPU (input generation, not part of the
+    path): the 16 GB of the Llama shape never exist on the host."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    d, hd, f, v = cfg["d_model"], cfg["head_dim"], cfg["d_ffn"], cfg["vocab"]
+    dq, dkv = cfg["n_q_heads"] * hd, cfg["n_kv_heads"] * hd
+
+    def normal(*shape):
+        t = torch.empty(*shape, dtype=torch.float32, device="cuda").normal_(0.0, 0.02, generator=g)
+        return t.to(torch.bfloat16)
+
+    ones = lambda: torch.ones(d, dtype=torch.float32, device="cuda")
+    w = {"embed": normal(v, d), "lm_head": normal(v, d), "final_norm": ones(), "layers": []}
+    for _ in range(cfg["n_layers"]):
+        w["layers"].append({"norm_in": ones(), "wqkv": normal(dq + 2 * dkv, d), "wo": normal(d, dq),
+                            "norm_post": ones(), "w_gate_up": normal(2 * f, d), "w_down": normal(d, f)})
+    return w
+
+
+def algorithmic_flops(cfg, n, l_keep):
+    """Flops the method itself needs for one prompt of n tokens: kept layers on all rows that ride
+    through them, K/V-only projections for the pruned layers, causal attention (lower triangle),
+    and the boundary token's deep layers + LM head."""
+    d, hd, f, v, L = cfg["d_model"], cfg["head_dim"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"]
+    dq, dkv = cfg["n_q_heads"] * hd, cfg["n_kv_heads"] * hd
+    p_layer = d * (dq + 2 * dkv) + dq * d + 3 * d * f
+    p_kv = 2 * d * dkv
+    attn = 2 * n * n * dq                      # QK^T + PV over the causal half
+    body = n - 1
+    return (2 * body * (l_keep * p_layer + (L - l_keep) * p_kv) + l_keep * attn
+            + 2 * (L * p_layer + v * d))
+
+
+def cpu_baseline(cfg, n, l_keep):
+    """The oracle as it stands on a bounded sample: one kept layer, one K/V-only layer and one
+    boundary decode layer (+ LM head) at full width and full prompt length, scaled by layer counts."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import pop_oracle as O
+    from paper_2602_03295_amd import synth
+
+    small = dict(cfg, n_layers=2, vocab=4096)
+    W = synth.make_weights(small, seed=1234)
+    tokens = synth.make_tokens(small["vocab"], n, seed=1)
+    h = O.embed_rows(W, tokens, np.float64)
+    pos = np.arange(n - 1)
+    empty = np.zeros((0, cfg["n_kv_heads"], cfg["head_dim"]))
+    t0 = time.perf_counter()
+    x, K, V = O.kept_layer_rows(small, W["layers"][0], 1, h[:n - 1], pos, empty, empty)
+    t_kept = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    _, K2, V2 = O.kv_only_rows(small, W["layers"][1], 2, x, pos)
+    t_kv = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    O.decode_step(small, W, h[n - 1], [K, K2], [V, V2])
+    t_dec = time.perf_counter() - t0            # 2 layers + LM head of the reduced vocab
+    L = cfg["n_layers"]
+    total = l_keep * t_kept + (L - l_keep) * t_kv + (L / 2.0) * t_dec
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": n / total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": (f"fp64 numpy oracle, Llama-3.1-8B layer shape, {n} tokens: one kept layer "
+                       f"({t_kept:.2f} s), one K/V-only layer ({t_kv:.2f} s), one 2-layer boundary decode "
+                       f"step ({t_dec:.2f} s); scaled to {l_keep} kept + {L - l_keep} pruned layers and a "
+                       f"{L}-layer boundary step"),
+            "extrapolated_s_per_prompt": total}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="llama8b")
+    ap.add_argument("--seq-len", type=int, default=2048)
+    ap.add_argument("--l-keep", type=int, default=24)
+    ap.add_argument("--sweep", default="32,28,24,20")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2602_03295_amd import pop, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.get_config(args.config)
+    if args.layers:
+        cfg["n_layers"] = args.layers
+    L = cfg["n_layers"]
+    n = args.seq_len
+    sweep = sorted({min(int(x), L) for x in args.sweep.split(",")} | {min(args.l_keep, L), L}, reverse=True)
+    head = min(args.l_keep, L)
+
+    model = pop.Model(cfg, device_weights(cfg, 1234, torch))
+    bt, n_pages = synth.make_block_table([n], cfg["page_size"], reserve_pages=1)
+    cache = pop.Cache(cfg, n_pages, 1, bt.shape[1])
+    ws = pop.alloc_workspace(cfg, n, 1, bt.shape[1])
+    tokens = synth.make_tokens(cfg["vocab"], n, seed=1)
+    cu = np.array([0, n], dtype=np.int32)
+    logits = torch.empty(1, cfg["vocab"], dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(l_keep):
+        pop.pop_prefill(model, cache, tokens, cu, bt, l_keep, ws, logits=logits, stream=stream)
+
+    def timed(l_keep, steps, warmup):
+        for _ in range(warmup):
+            step(l_keep)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(steps):
+            step(l_keep)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return e0.elapsed_time(e1) / steps, wall
+
+    results = {}
+    for lk in sweep:
+        ms, wall = timed(lk, args.steps, args.warmup)
+        results[lk] = {"ms_per_step": ms, "wall_ms_per_step": wall, "tokens_per_s": n / (ms * 1e-3),
+                       "algorithmic_tflop": algorithmic_flops(cfg, n, lk) / 1e12,
+                       "end_to_end_frac_of_mfma_peak": algorithmic_flops(cfg, n, lk) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    full_ms = results[L]["ms_per_step"]
+    for lk in sweep:
+        results[lk]["speedup_vs_full_depth"] = full_ms / results[lk]["ms_per_step"]
+
+    # ---- per-step breakdown with HIP events inside the library, on the launch stream
+    pop.pop_timing_enable(model, True)
+    for _ in range(args.steps):
+        step(head)
+    torch.cuda.synchronize()
+    steps_t = pop.pop_timing_read(model)
+    pop.pop_timing_enable(model, False)
+    d, f = cfg["d_model"], cfg["d_ffn"]
+    gu = steps_t["gate_up_gemm"]
+    gu_ms = gu["ms"] / max(gu["launches"], 1)
+    gu_flops = 2.0 * n * d * 2 * f            # one launch: [n, d] x [2f, d]^T
+    achieved = gu_flops / (gu_ms * 1e-3) / 1e12 if gu_ms > 0 else 0.0
+    breakdown = {k: {"ms_per_launch": v["ms"] / max(v["launches"], 1), "launches_per_step": v["launches"] / args.steps,
+                     "ms_per_step": v["ms"] / args.steps} for k, v in steps_t.items() if v["launches"]}
+    hd = cfg["head_dim"]
+    dq, dkv = cfg["n_q_heads"] * hd, cfg["n_kv_heads"] * hd
+    gemm_flops = {"qkv_gemm": 2.0 * n * d * (dq + 2 * dkv), "o_gemm": 2.0 * n * dq * d,
+                  "gate_up_gemm": gu_flops, "down_gemm": 2.0 * n * f * d,
+                  "attention": 2.0 * n * n * dq}
+    for k, fl in gemm_flops.items():
+        if k in breakdown and breakdown[k]["ms_per_launch"] > 0:
+            breakdown[k]["tflops"] = fl / (breakdown[k]["ms_per_launch"] * 1e-3) / 1e12
+            breakdown[k]["frac_of_mfma_peak"] = breakdown[k]["tflops"] / PEAK_BF16_TFLOPS
+    if "norm" in breakdown:
+        nb = n * d * (4 + 2)
+        breakdown["norm"]["gb_per_s"] = nb / (breakdown["norm"]["ms_per_launch"] * 1e-3) / 1e9
+    if "rope_write" in breakdown:
+        rb = n * (dq + 2 * dkv) * 2 * 2 + n * dkv * 2
+        breakdown["rope_write"]["gb_per_s"] = rb / (breakdown["rope_write"]["ms_per_launch"] * 1e-3) / 1e9
+
+    out = {
+        "metric": "prefill tokens/s (POP pruned prefill, Llama-3.1-8B shape, 2K prompt) + speedup vs full-depth prefill",
+        "value": results[head]["tokens_per_s"],
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": results[head]["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.config} shape ({L} layers), batch 1, {n}-token prompt, L_keep={head}, "
+                               f"bf16 N(0,0.02) weights, paged KV cache (16-token pages)",
+                   "l_keep": head, "seq_len": n, "batch": 1},
+        "speedup_vs_full_depth": results[head]["speedup_vs_full_depth"],
+        "sweep": {str(k): v for k, v in results.items()},
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<256,256,2,2,GLU> (gate|up projection + GLU)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "flops_per_launch": gu_flops, "avg_launch_ms": gu_ms},
+        "breakdown": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, n, head)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -177,6 +177,32 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
                            float* dev_logits, void* dev_workspace, size_t workspace_bytes,
                            pop_stream stream);
 
+/*
+ * Optional per-step timing for benchmarks.  While enabled, pop_prefill brackets every launch of the
+ * steps below with HIP events on the caller's stream (this adds a little launch overhead, so whole-
+ * call latency should be measured with timing disabled).  pop_timing_read waits for the recorded
+ * events, adds the elapsed time and launch count of each step kind since the last read into
+ * ms_out[POP_N_STEPS] / launches_out[POP_N_STEPS] (HOST arrays) and clears the record.
+ * Step kinds follow the layer forward of Sec. 2.1 and the pruned-layer / boundary split of Sec. 3.3.
+ */
+enum {
+  POP_STEP_EMBED = 0,     /* embedding gather + RoPE tables                       */
+  POP_STEP_NORM = 1,      /* RMSNorm (both norms of a kept layer)                 */
+  POP_STEP_QKV_GEMM = 2,
+  POP_STEP_ROPE_WRITE = 3, /* RoPE + cache append (kept layers)                   */
+  POP_STEP_ATTENTION = 4,
+  POP_STEP_O_GEMM = 5,
+  POP_STEP_GATE_UP_GEMM = 6,
+  POP_STEP_DOWN_GEMM = 7,
+  POP_STEP_KV_ONLY_NORM = 8,  /* pruned layers: shared-statistics norm            */
+  POP_STEP_KV_ONLY_GEMM = 9,  /* pruned layers: batched K/V projection            */
+  POP_STEP_KV_ONLY_WRITE = 10, /* pruned layers: RoPE + cache append              */
+  POP_STEP_BOUNDARY = 11,     /* boundary rows: deep layers + final norm + LM head */
+  POP_N_STEPS = 12
+};
+pop_status pop_timing_enable(pop_model* m, int32_t enable);
+pop_status pop_timing_read(pop_model* m, float* ms_out, int32_t* launches_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -71,12 +71,51 @@ bool layer_is_global(const pop_config& c, int l /*1-based*/) {
 }
 }  // namespace
 
+struct TimedSpan {
+  int kind;
+  hipEvent_t start, stop;
+};
+
 struct pop_model {
   pop_config cfg;
   pop_weights w;
   std::vector<pop_layer_weights> layers;
   int Dq, Dkv, Dqkv;
+  // optional per-step timing (pop_timing_enable)
+  bool timing = false;
+  std::vector<TimedSpan> spans;      // recorded since the last read
+  std::vector<hipEvent_t> free_events;
+  hipEvent_t take_event() {
+    if (!free_events.empty()) {
+      hipEvent_t e = free_events.back();
+      free_events.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
 };
+
+namespace {
+// Records an event pair around the launches issued during its lifetime (only while timing is on).
+struct StepTimer {
+  pop_model* m;
+  hipStream_t st;
+  hipEvent_t stop = nullptr;
+  StepTimer(pop_model* model, hipStream_t stream, int kind) : m(model), st(stream) {
+    if (!m->timing) return;
+    hipEvent_t start = m->take_event();
+    stop = m->take_event();
+    if (!start || !stop) { stop = nullptr; return; }
+    (void)hipEventRecord(start, st);
+    m->spans.push_back(TimedSpan{kind, start, stop});
+  }
+  ~StepTimer() {
+    if (stop) (void)hipEventRecord(stop, st);
+  }
+};
+}  // namespace
 
 struct pop_cache {
   pop_config cfg;
@@ -310,7 +349,34 @@ pop_status pop_load_weights(const pop_config* cfg, const pop_weights* w, pop_mod
   return POP_OK;
 }
 
-void pop_free_model(pop_model* m) { delete m; }
+void pop_free_model(pop_model* m) {
+  if (!m) return;
+  for (auto& s : m->spans) { (void)hipEventDestroy(s.start); (void)hipEventDestroy(s.stop); }
+  for (auto e : m->free_events) (void)hipEventDestroy(e);
+  delete m;
+}
+
+pop_status pop_timing_enable(pop_model* m, int32_t enable) {
+  if (!m) return fail(POP_EINVAL, "model is NULL");
+  m->timing = enable != 0;
+  return POP_OK;
+}
+
+pop_status pop_timing_read(pop_model* m, float* ms_out, int32_t* launches_out) {
+  if (!m || !ms_out || !launches_out) return fail(POP_EINVAL, "model / output array is NULL");
+  for (int i = 0; i < POP_N_STEPS; ++i) { ms_out[i] = 0.f; launches_out[i] = 0; }
+  for (auto& s : m->spans) {
+    POP_HIP(hipEventSynchronize(s.stop));
+    float ms = 0.f;
+    POP_HIP(hipEventElapsedTime(&ms, s.start, s.stop));
+    ms_out[s.kind] += ms;
+    launches_out[s.kind] += 1;
+    m->free_events.push_back(s.start);
+    m->free_events.push_back(s.stop);
+  }
+  m->spans.clear();
+  return POP_OK;
+}
 
 size_t pop_cache_bytes(const pop_config* cfg, int32_t n_pages) {
   if (!cfg || n_pages < 1 || cfg->n_layers < 1 || cfg->n_kv_heads < 1 || cfg->head_dim < 1 || cfg->page_size < 1)
@@ -490,12 +556,15 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   float2* cs_g = at<float2>(ws, w.o_cs_g);
   float2* cs_l = at<float2>(ws, w.o_cs_l);
 
-  pop::launch_embed((const bf16_t*)m->w.embed, d_tokens, a->n_ranges > 0 ? d_row_src : nullptr,
-                    (const bf16_t*)a->embeds, h, T, d, st);
-  bool any_local = false;
-  for (int l = 1; l <= cfg.n_layers; ++l) any_local |= !layer_is_global(cfg, l);
-  pop::launch_rope_table(d_pos, cs_g, T, hd, (double)cfg.rope_theta, st);
-  if (any_local) pop::launch_rope_table(d_pos, cs_l, T, hd, (double)cfg.rope_theta_local, st);
+  {
+    StepTimer tm(m, st, POP_STEP_EMBED);
+    pop::launch_embed((const bf16_t*)m->w.embed, d_tokens, a->n_ranges > 0 ? d_row_src : nullptr,
+                      (const bf16_t*)a->embeds, h, T, d, st);
+    bool any_local = false;
+    for (int l = 1; l <= cfg.n_layers; ++l) any_local |= !layer_is_global(cfg, l);
+    pop::launch_rope_table(d_pos, cs_g, T, hd, (double)cfg.rope_theta, st);
+    if (any_local) pop::launch_rope_table(d_pos, cs_l, T, hd, (double)cfg.rope_theta_local, st);
+  }
   POP_HIP(hipGetLastError());
 
   pop::RopeWriteArgs rw{};
@@ -515,17 +584,26 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   for (int l = 1; l <= a->l_keep; ++l) {
     const pop_layer_weights& lw = m->layers[l - 1];
     const bool glob = layer_is_global(cfg, l);
-    pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_in, abuf, nullptr, T, d, cfg.rms_eps, st);
+    {
+      StepTimer tm(m, st, POP_STEP_NORM);
+      pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_in, abuf, nullptr, T, d, cfg.rms_eps, st);
+    }
     pop::GemmArgs g{};
     g.batch = 1;
     g.A = abuf; g.lda = d; g.W = (const bf16_t*)lw.wqkv; g.ldw = d; g.out = qkv; g.ldc = Dqkv;
     g.M = T; g.N = Dqkv; g.K = d; g.epilogue = pop::EPI_STORE_BF16;
-    if (pop_status s = gemm_or_fail(g, st, "QKV")) return s;
+    {
+      StepTimer tm(m, st, POP_STEP_QKV_GEMM);
+      if (pop_status s = gemm_or_fail(g, st, "QKV")) return s;
+    }
     rw.qkv = qkv; rw.ld = Dqkv; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
     rw.cs = glob ? cs_g : cs_l;
     rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
     rw.vT = vT;
-    pop::launch_rope_write(rw, st);
+    {
+      StepTimer tm(m, st, POP_STEP_ROPE_WRITE);
+      pop::launch_rope_write(rw, st);
+    }
     pop::AttnPrefillArgs ap{};
     ap.qkv = qkv; ap.ld = Dqkv; ap.q_col = 0; ap.k_col = Dq; ap.vT = vT; ap.Tp = Tp; ap.out = attn;
     ap.T = T; ap.n_q_heads = cfg.n_q_heads; ap.n_kv_heads = cfg.n_kv_heads; ap.hd = hd;
@@ -533,19 +611,32 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     ap.cu_seqlens = d_cu; ap.vt_off = d_vt_off;
     ap.tile_seq = at<int32_t>(ws, w.o_ta_seq); ap.tile_start = at<int32_t>(ws, w.o_ta_start); ap.n_tiles = n_ta;
     {
+      StepTimer tm(m, st, POP_STEP_ATTENTION);
       hipError_t e = pop::launch_attention_prefill(ap, st);
       if (e != hipSuccess) return fail(POP_EHIP, "attention launch failed: %s", hipGetErrorString(e));
     }
     g.A = attn; g.lda = Dq; g.W = (const bf16_t*)lw.wo; g.ldw = Dq; g.out = h; g.ldc = d;
     g.M = T; g.N = d; g.K = Dq; g.epilogue = pop::EPI_ADD_F32;
-    if (pop_status s = gemm_or_fail(g, st, "O")) return s;
-    pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_post, abuf, nullptr, T, d, cfg.rms_eps, st);
+    {
+      StepTimer tm(m, st, POP_STEP_O_GEMM);
+      if (pop_status s = gemm_or_fail(g, st, "O")) return s;
+    }
+    {
+      StepTimer tm(m, st, POP_STEP_NORM);
+      pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_post, abuf, nullptr, T, d, cfg.rms_eps, st);
+    }
     g.A = abuf; g.lda = d; g.W = (const bf16_t*)lw.w_gate_up; g.ldw = d; g.out = u; g.ldc = f;
     g.M = T; g.N = f; g.K = d; g.epilogue = pop::EPI_GLU_BF16; g.act = cfg.act;
-    if (pop_status s = gemm_or_fail(g, st, "gate/up")) return s;
+    {
+      StepTimer tm(m, st, POP_STEP_GATE_UP_GEMM);
+      if (pop_status s = gemm_or_fail(g, st, "gate/up")) return s;
+    }
     g.A = u; g.lda = f; g.W = (const bf16_t*)lw.w_down; g.ldw = f; g.out = h; g.ldc = d;
     g.M = T; g.N = d; g.K = f; g.epilogue = pop::EPI_ADD_F32;
-    if (pop_status s = gemm_or_fail(g, st, "down")) return s;
+    {
+      StepTimer tm(m, st, POP_STEP_DOWN_GEMM);
+      if (pop_status s = gemm_or_fail(g, st, "down")) return s;
+    }
   }
 
   // ---- pruned layers l_keep+1..L: independent KV projections of the frozen hidden state (Sec. 3.3)
@@ -557,13 +648,20 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       const int n = std::min(kKvChunk, cfg.n_layers - l0 + 1);
       pop::GammaList gl{};
       for (int j = 0; j < n; ++j) gl.g[j] = (const float*)m->layers[l0 - 1 + j].norm_in;
-      pop::launch_rmsnorm_multi(h, gl, n, a_multi, (size_t)T * d, T, d, cfg.rms_eps, st);
+      {
+        StepTimer tm(m, st, POP_STEP_KV_ONLY_NORM);
+        pop::launch_rmsnorm_multi(h, gl, n, a_multi, (size_t)T * d, T, d, cfg.rms_eps, st);
+      }
       pop::GemmArgs g{};
       g.A = a_multi; g.lda = d; g.W = nullptr; g.ldw = d; g.out = kv_out; g.ldc = 2 * Dkv;
       g.M = T; g.N = 2 * Dkv; g.K = d; g.epilogue = pop::EPI_STORE_BF16;
       g.batch = n; g.strideA = (long long)T * d; g.strideC = (long long)T * 2 * Dkv;
       g.W_list = wlist + (l0 - 1);
-      if (pop_status s = gemm_or_fail(g, st, "K/V-only")) return s;
+      {
+        StepTimer tm(m, st, POP_STEP_KV_ONLY_GEMM);
+        if (pop_status s = gemm_or_fail(g, st, "K/V-only")) return s;
+      }
+      StepTimer tmw(m, st, POP_STEP_KV_ONLY_WRITE);
       for (int j = 0; j < n; ++j) {
         const int l = l0 + j;
         rw.qkv = kv_out + (size_t)j * T * 2 * Dkv; rw.ld = 2 * Dkv; rw.q_col = -1; rw.k_col = 0; rw.v_col = Dkv;
@@ -579,6 +677,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   // ---- boundary tokens at full depth (Sec. 3.3, boundary handling): they rode along through the
   //      kept layers (identical to their decode step there) and continue alone through the rest.
   if (a->mode == POP_MODE_POP) {
+    StepTimer tm(m, st, POP_STEP_BOUNDARY);
     LayerCtx x{m, c, ws, &w, st};
     pop::launch_gather_rows(h, at<int32_t>(ws, w.o_bnd_row), at<float>(ws, w.o_xb), B, d, st);
     for (int l = a->l_keep + 1; l <= cfg.n_layers; ++l)

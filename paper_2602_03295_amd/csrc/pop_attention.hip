@@ -91,18 +91,20 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
     const int c = (lane & 7) ^ (row & 7);
     offV[j] = (uint32_t)((((long long)kvh * HD + row) * a.Tp + a.vt_off[b] + c * 8) * 2);
   }
+  // The key offset goes into the per-lane offset (not the scalar one) so that rows beyond the end of
+  // the buffer are range-checked and read as zero.
   auto issue = [&](int it, int stage) {
     const int j0 = j_begin + it * BKV;
     unsigned char* sk = smem + stage * STAGE;
     unsigned char* sv = sk + K_BYTES;
 #pragma unroll
     for (int j = 0; j < K_LOADS; ++j)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rK, (lds_ptr_t)(sk + (j * 4 + wave) * 1024), 16, offK[j],
-                                               j0 * a.ld * 2, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rK, (lds_ptr_t)(sk + (j * 4 + wave) * 1024), 16,
+                                               offK[j] + (uint32_t)(j0 * a.ld * 2), 0, 0, 0);
 #pragma unroll
     for (int j = 0; j < V_LOADS; ++j)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rV, (lds_ptr_t)(sv + (j * 4 + wave) * 1024), 16, offV[j],
-                                               j0 * 2, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rV, (lds_ptr_t)(sv + (j * 4 + wave) * 1024), 16,
+                                               offV[j] + (uint32_t)(j0 * 2), 0, 0, 0);
   };
 
   // ---- Q fragments (B operand: lane = query row, 8 consecutive head-dim values per step)

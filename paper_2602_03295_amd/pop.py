@@ -87,7 +87,12 @@ lib.pop_op_rope_attention_workspace.restype = C.c_size_t
 lib.pop_op_rope_attention.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float,
                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 
-EXPORTED = ["pop_last_error", "pop_version", "pop_load_weights", "pop_free_model", "pop_cache_bytes",
+lib.pop_timing_enable.argtypes = [C.c_void_p, C.c_int32]
+lib.pop_timing_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), _i32p]
+STEP_NAMES = ["embed", "norm", "qkv_gemm", "rope_write", "attention", "o_gemm", "gate_up_gemm", "down_gemm",
+              "kv_only_norm", "kv_only_gemm", "kv_only_write", "boundary"]
+
+EXPORTED = ["pop_timing_enable", "pop_timing_read", "pop_last_error", "pop_version", "pop_load_weights", "pop_free_model", "pop_cache_bytes",
             "pop_workspace_bytes", "pop_cache_create", "pop_cache_destroy", "pop_cache_n_seqs",
             "pop_cache_seq_lens", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_op_rmsnorm",
             "pop_op_gemm", "pop_op_gemv", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
@@ -119,6 +124,18 @@ def _stream(stream) -> int:
             return 0      # host-only calls (argument errors are reported before any launch)
         stream = torch.cuda.current_stream()
     return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def pop_timing_enable(model: "Model", enable: bool) -> None:
+    _check(lib.pop_timing_enable(model.handle, 1 if enable else 0))
+
+
+def pop_timing_read(model: "Model") -> Dict[str, Dict[str, float]]:
+    """Elapsed GPU time and launch count per step kind since the last read (waits for the events)."""
+    ms = (C.c_float * len(STEP_NAMES))()
+    n = (C.c_int32 * len(STEP_NAMES))()
+    _check(lib.pop_timing_read(model.handle, ms, n))
+    return {name: {"ms": float(ms[i]), "launches": int(n[i])} for i, name in enumerate(STEP_NAMES)}
 
 
 def pop_version() -> str:

@@ -39,7 +39,7 @@ def test_rmsnorm(pop, rows, d):
     assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-30)
 
 
-GEMM_SHAPES = [(128, 128, 64), (300, 200, 264), (1, 8, 8), (257, 513, 1000), (2048, 8192, 256), (515, 4100, 136),
+GEMM_SHAPES = [(128, 128, 64), (300, 200, 264), (1, 8, 8), (257, 516, 1000), (2048, 8192, 256), (515, 4100, 136),
                (64, 96, 4096)]
 
 
