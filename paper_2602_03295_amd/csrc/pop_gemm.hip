@@ -8,15 +8,25 @@
 //   * Tiles are staged global -> LDS with buffer_load_dwordx4 ... lds (no VGPR round trip); rows
 //     beyond M / N are out of range of the buffer descriptor and read as zero, so ragged edges need
 //     no branches in the main loop.
-//   * LDS rows are 64 bf16 (128 B).  Chunk c of row r is stored at chunk position c ^ (r & 7), which
-//     makes the ds_read_b128 operand fetches bank-conflict free.  The permutation is applied on the
-//     global side (each lane picks the chunk that belongs at its LDS position).
-//   * Two LDS stages; the loads of K-step k+1 are issued right after the barrier that publishes
-//     K-step k, so they overlap its MFMA work.
+//   * LDS rows are 64 bf16 (128 B).  Chunk c of row r is stored at chunk position c ^ ((r >> 1) & 7).
+//     gfx950's LDS serves a ds_read_b128 sixteen lanes (256 B, 64 banks) per cycle; sixteen
+//     consecutive rows are eight 256-byte bank lines, and the key makes the two rows of a line plus
+//     the eight lines land on sixteen different 16-byte positions: conflict free (measured:
+//     SQ_LDS_BANK_CONFLICT 50 % of SQ_LDS_IDX_ACTIVE with the key r & 7, which collides rows r and
+//     r + 8).  The permutation is applied on the global side (each lane picks the chunk that belongs
+//     at its LDS position).
+//   * STAGES LDS stages (2 for 256x256 tiles, 3 for 256x128): the loads of K-step k+STAGES-1 are
+//     issued right after the barrier that publishes K-step k, so they overlap MFMA work; with 3
+//     stages two K-steps of loads are in flight, which covers L2-miss latency.
+//   * Tile shape is chosen per problem so that the number of tiles fills 256 CUs evenly (at M = 2048
+//     a 256x256 tiling of the gate|up projection leaves the last of 3.5 rounds half empty, 256x128
+//     gives exactly 7 rounds).
 //   * The MFMA is issued with W as the first operand, so a lane ends up with 4 consecutive output
 //     columns of one row: epilogues use 8/16-byte accesses.
 //   * Work-group ids are remapped so that the groups that run together on one XCD (ids equal mod 8)
 //     work on neighbouring M tiles of the same W tile and share it through that XCD's L2.
+#include <cstdlib>
+
 #include "pop_device.h"
 #include "pop_kernels.h"
 
@@ -41,13 +51,14 @@ struct GemmParams {
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-__device__ __forceinline__ float glu_act(float g, int act) {
-  if (act == 0) return g / (1.f + __expf(-g));
-  const float u = 0.7978845608028654f * (g + 0.044715f * g * g * g);
-  return 0.5f * g * (1.f + tanhf(u));
+// SiLU: g * sigmoid(g); tanh-GELU: 0.5 g (1 + tanh(u)) = g * sigmoid(2u), u = sqrt(2/pi) (g + 0.044715 g^3).
+// Both are g / (1 + 2^(-g (k0 + k1 g^2))): one v_exp_f32 and one v_rcp_f32, constants chosen per
+// activation (SiLU: k0 = log2(e), k1 = 0; GELU: k0 = 2 sqrt(2/pi) log2(e), k1 = 0.044715 k0).
+__device__ __forceinline__ float glu_act(float g, float k0, float k1) {
+  return g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-g * (k0 + k1 * g * g)));
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the buffer-resource builtins exist in the device pass only
   constexpr int NW = WGM * WGN;
@@ -88,8 +99,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
       __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(W), 0, w_bytes, 0x00020000);
 
   // ---- per-lane global offsets of the chunks this lane stages (K offset added per step)
+  static_assert(NW % 2 == 0, "the swizzle key of a staged row must not depend on the load index");
   const int lr = lane >> 3;         // row inside an 8-row group
-  const int lc = (lane & 7) ^ lr;   // logical chunk that belongs at this lane's LDS position
+  // logical chunk that belongs at this lane's LDS position: key = (tile row >> 1) & 7, and the tile
+  // row is (j * NW + wave) * 8 + lr with NW even, so the key is ((wave & 1) << 2) | (lr >> 1)
+  const int lc = (lane & 7) ^ (((wave & 1) << 2) | (lr >> 1));
   uint32_t offA[LA], offB[LB];
 #pragma unroll
   for (int j = 0; j < LA; ++j) {
@@ -114,24 +128,70 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     offB[j] = ok ? (uint32_t)(((long long)wrow * p.ldw + lc * 8) * 2) : kOOB;
   }
 
-  // tail_mask: bit 31 set on lanes whose chunk lies beyond K in the last (partial) K-step, which
-  // pushes their offset out of range so they stage zeros.
-  auto issue = [&](int kt, int stage, uint32_t tail_mask) {
+  // K-step t is staged by LA + LB wave-loads, spread over the STEPS = BK/16 MFMA sub-steps of the
+  // K-step before it (LPS per sub-step).  tail_mask has bit 31 set on lanes whose chunk lies beyond K (or for a K-step beyond
+  // the last one): that pushes the offset out of range and the lane stages zeros.
+  constexpr int STEPS = BK / 16;
+  constexpr int LOADS = LA + LB;
+  constexpr int LPS = (LOADS + STEPS - 1) / STEPS;  // loads per slice
+  auto issue_one = [&](int q, int kt, unsigned char* stage_base, uint32_t tail_mask) {
+    if (q >= LOADS) return;
     const int k0 = kt * BK;
-    unsigned char* sa = smem + stage * STAGE;
+    unsigned char* sa = stage_base;
     unsigned char* sb = sa + A_BYTES;
+    if (q < LA)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(sa + (q * NW + wave) * 1024), 16,
+                                               offA[q] | tail_mask, k0 * 2, 0, 0);
+    else
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rW, (lds_ptr_t)(sb + ((q - LA) * NW + wave) * 1024), 16,
+                                               offB[q - LA] | tail_mask, k0 * 2, 0, 0);
+  };
+  auto issue = [&](int kt, int stage, uint32_t tail_mask) {
 #pragma unroll
-    for (int j = 0; j < LA; ++j)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(sa + (j * NW + wave) * 1024), 16,
-                                               offA[j] | tail_mask, k0 * 2, 0, 0);
-#pragma unroll
-    for (int j = 0; j < LB; ++j)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rW, (lds_ptr_t)(sb + (j * NW + wave) * 1024), 16,
-                                               offB[j] | tail_mask, k0 * 2, 0, 0);
+    for (int q = 0; q < LOADS; ++q) issue_one(q, kt, smem + stage * STAGE, tail_mask);
   };
   const int nk = (p.K + BK - 1) / BK;
   const int nk_full = p.K / BK;  // K-steps that need no tail mask
   const uint32_t last_mask = (nk_full * BK + lc * 8 < p.K) ? 0u : kOOB;
+
+  // L2 prefetch.  The work-groups that run together on one XCD share their W tile (same tn, eight
+  // consecutive tm) and their A tile (same tm, four tn), and all of them walk K in step, so an L2
+  // miss of one is a miss of all: every staged line then pays HBM latency, which bounds the loading
+  // rate.  Each K-step every wave therefore touches (4-byte DMA load into a scratch line of LDS) a
+  // few cache lines PF_DIST K-steps ahead: wave 0 one eighth of the W tile's rows (slice tm % 8),
+  // waves 1 and 2 one quarter of the A tile's rows (slice tn % 4).  Together the sharers cover both
+  // tiles, and the real loads later hit in L2.
+  constexpr int PF_DIST = STAGES + 1;
+  unsigned char* pf_scratch = smem + STAGES * STAGE;
+  uint32_t pf_off;
+  {
+    const int l32 = lane & 31;
+    if (wave == 0) {
+      const int jn = (tm & 7) * (BN / 8) + (lane % (BN / 8));   // row of the LDS B tile
+      int wrow; bool ok = lane < BN / 8;
+      if (EPI == EPI_GLU_BF16) {
+        const int w2 = jn / WTN, r = jn % WTN;
+        const int oc = n0 + w2 * (WTN / 2) + (r % (WTN / 2));
+        ok = ok && oc < p.N;
+        wrow = (r >= WTN / 2 ? p.N : 0) + oc;
+      } else {
+        wrow = n0 + jn;
+        ok = ok && wrow < p.N;
+      }
+      pf_off = ok ? (uint32_t)((long long)wrow * p.ldw * 2) : kOOB;
+    } else if (wave <= 2) {
+      const int row = m0 + (tn & 3) * (BM / 4) + (wave - 1) * 32 + l32;
+      const bool ok = lane < 32 && (wave - 1) * 32 + l32 < BM / 4 && row < p.M;
+      pf_off = ok ? (uint32_t)((long long)row * p.lda * 2) : kOOB;
+    } else {
+      pf_off = kOOB;
+    }
+  }
+  auto prefetch = [&](int kt) {   // one DMA load per wave; lanes beyond K or beyond the tile are masked
+    const uint32_t off = (kt * BK < p.K) ? pf_off : kOOB;
+    if (wave == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rW, (lds_ptr_t)pf_scratch, 4, off, kt * BK * 2, 0, 0);
+    else __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(pf_scratch + 256), 4, off, kt * BK * 2, 0, 0);
+  };
 
   floatx16_t acc[NB][MB];
 #pragma unroll
@@ -141,42 +201,92 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // LDS read offsets: row (lane & 31) of a 32-row block, chunk (2*ks + lane/32) ^ (row & 7)
+  // LDS read offsets: row (lane & 31) of a 32-row block, chunk (2*ks + lane/32) ^ ((row >> 1) & 7)
   const int frag_row = lane & 31;
   const int frag_hi = lane >> 5;
   const int a_base = (wm * WTM + frag_row) * 128;
   const int b_base = (wn * WTN + frag_row) * 128;
 
-  if (nk_full > 0) issue(0, 0, 0u); else issue(0, 0, last_mask);
+  static_assert(STAGES == 2 || STAGES == 3, "2 or 3 LDS stages");
+  static_assert(LOADS + 2 < 64, "vmcnt is a 6-bit counter");
+#pragma unroll
+  for (int t = 0; t < STAGES - 1; ++t)
+    if (t < nk) issue(t, t, t < nk_full ? 0u : last_mask);
+  int stage = 0;                  // stage that holds K-step kt
+  int fill = (STAGES - 1) % STAGES;  // stage the next issued K-step goes to
   for (int kt = 0; kt < nk; ++kt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    if (kt + 1 < nk_full) issue(kt + 1, (kt + 1) & 1, 0u);
-    else if (kt + 1 < nk) issue(kt + 1, (kt + 1) & 1, last_mask);
-    const unsigned char* sa = smem + (kt & 1) * STAGE;
-    const unsigned char* sb = sa + A_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int pc = ((2 * ks + frag_hi) ^ (frag_row & 7)) * 16;
-      bf16x8_t af[MB], bfr[NB];
-#pragma unroll
-      for (int j = 0; j < MB; ++j)
-        af[j] = *reinterpret_cast<const bf16x8_t*>(sa + a_base + j * 32 * 128 + pc);
-#pragma unroll
-      for (int i = 0; i < NB; ++i)
-        bfr[i] = *reinterpret_cast<const bf16x8_t*>(sb + b_base + i * 32 * 128 + pc);
-#pragma unroll
-      for (int i = 0; i < NB; ++i)
-#pragma unroll
-        for (int j = 0; j < MB; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[i], af[j], acc[i][j], 0, 0, 0);
+    // Wait until K-step kt has landed.  Loads return in order, so it is enough to bound how many
+    // younger ones may still be in flight.  Every iteration issues exactly LOADS staging loads (masked
+    // beyond the last K-step) followed by one prefetch load, so behind K-step kt's loads there are:
+    // 2 stages: the previous iteration's prefetch; 3 stages: prefetch, LOADS, prefetch.  The first
+    // iterations have fewer; waiting for more than necessary there is harmless.
+    if (STAGES == 2) {
+      if (kt > 0) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+      if (kt >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS + 2) : "memory");
+      else if (kt == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
+    __builtin_amdgcn_s_barrier();
+    // K-step to prefetch during this one (branch-free: beyond the end every lane is masked off)
+    const int tp = kt + STAGES - 1;
+    const uint32_t pmask = tp < nk_full ? 0u : (tp < nk ? last_mask : kOOB);
+    unsigned char* fill_base = smem + fill * STAGE;
+    const unsigned char* sa = smem + stage * STAGE;
+    stage = stage + 1 == STAGES ? 0 : stage + 1;
+    fill = fill + 1 == STAGES ? 0 : fill + 1;
+    const unsigned char* sb = sa + A_BYTES;
+    // Operand fetches are software pipelined (the fragments of sub-step ks+1 are requested while the
+    // MFMAs of sub-step ks run), and every sub-step is cut into G groups of MFMAs; each group also
+    // carries one slice of the next K-step's global loads and a share of the LDS reads.  Scheduling
+    // barriers pin that order: a wave that issues its global loads in one burst sits in the memory
+    // pipeline's issue queue (measured: about 27 cycles per 1 KB wave-load per CU) while its MFMAs
+    // could run, which serialises loading and matrix work.
+    bf16x8_t af[2][MB], bfr[2][NB];
+    constexpr int READS = MB + NB, MFMAS = MB * NB;
+    constexpr int G = MFMAS >= 4 ? 4 : 1;            // groups per sub-step
+    constexpr int MPG = MFMAS / G;                    // MFMAs per group
+    constexpr int RPG = (READS + G - 1) / G;          // LDS reads per group
+    constexpr int LPG = (LPS + G - 1) / G;            // global loads per group
+    static_assert(MFMAS % G == 0, "MFMAs must split evenly into groups");
+    auto load_frag = [&](int ks, int buf, int r) {    // r-th fragment read of sub-step ks
+      const int pc = ((2 * ks + frag_hi) ^ ((frag_row >> 1) & 7)) * 16;
+      if (r < NB) bfr[buf][r] = *reinterpret_cast<const bf16x8_t*>(sb + b_base + r * 32 * 128 + pc);
+      else af[buf][r - NB] = *reinterpret_cast<const bf16x8_t*>(sa + a_base + (r - NB) * 32 * 128 + pc);
+    };
+#pragma unroll
+    for (int r = 0; r < READS; ++r) load_frag(0, 0, r);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < STEPS; ++ks) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (ks + 1 < STEPS) {
+#pragma unroll
+          for (int r = g * RPG; r < (g + 1) * RPG && r < READS; ++r) load_frag(ks + 1, (ks + 1) & 1, r);
+        }
+#pragma unroll
+        for (int q = g * LPG; q < (g + 1) * LPG && q < LPS; ++q) issue_one(ks * LPS + q, tp, fill_base, pmask);
+#pragma unroll
+        for (int e = g * MPG; e < (g + 1) * MPG; ++e) {
+          const int i = e / MB, j = e % MB;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][i], af[ks & 1][j], acc[i][j], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    prefetch(kt + PF_DIST);
   }
+  // masked staging loads and prefetches of the last iterations still target this group's LDS
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- epilogue.  acc[i][j][v]: row m = .. + j*32 + (lane&31); column block i, columns
   //      (v/4)*8 + (lane>>5)*4 + (v%4) inside it: 4 consecutive columns per (v/4).
   const int m_lane = m0 + wm * WTM + frag_row;
   if (EPI == EPI_GLU_BF16) {
+    const float act_k0 = p.act == 0 ? 1.4426950408889634f : 2.302208198f;
+    const float act_k1 = p.act == 0 ? 0.f : 0.1029432396f;
     bf16_t* out = reinterpret_cast<bf16_t*>(p.out) + (long long)z * p.strideC;
 #pragma unroll
     for (int i = 0; i < NB / 2; ++i)
@@ -189,7 +299,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
           const int n = n0 + wn * (WTN / 2) + i * 32 + g * 8 + frag_hi * 4;
           float r[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) r[e] = glu_act(acc[i][j][g * 4 + e], p.act) * acc[i + NB / 2][j][g * 4 + e];
+          for (int e = 0; e < 4; ++e) r[e] = glu_act(acc[i][j][g * 4 + e], act_k0, act_k1) * acc[i + NB / 2][j][g * 4 + e];
           bf16_t* o = out + (long long)m * p.ldc + n;
           if (n + 3 < p.N) {
             uint2 pk;
@@ -251,10 +361,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #endif
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int EPI>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
   constexpr int BN_OUT = EPI == EPI_GLU_BF16 ? BN / 2 : BN;
-  constexpr int smem = 2 * (BM + BN) * BK * 2;
+  constexpr int smem = STAGES * (BM + BN) * BK * 2 + 1024;  // stages + prefetch scratch
+  static_assert(smem <= 160 * 1024, "LDS budget of a gfx950 CU");
   GemmParams p;
   p.A = g.A; p.W = g.W; p.out = g.out;
   p.M = g.M; p.N = g.N; p.K = g.K;
@@ -266,26 +377,55 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
   p.W_list = g.batch > 1 || g.W_list ? g.W_list : nullptr;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WGM, WGN, EPI>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int total = p.tiles_m * p.tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, EPI>), dim3(grid, 1, g.batch > 0 ? g.batch : 1),
+  hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI>), dim3(grid, 1, g.batch > 0 ? g.batch : 1),
                      dim3(64 * WGM * WGN), smem, st, p);
   return hipGetLastError();
 }
 
+// Tile choice: minimise the estimated time on the critical path,
+//     ceil(tiles / 256 CUs) * tile area * relative cost per flop of that configuration.
+// The relative costs are measured on MI355X at the Llama-3.1-8B projection shapes (256x256 tiles
+// move the fewest operand bytes per flop and are the fastest per flop; smaller tiles only win when
+// they fill the chip better).
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& g, hipStream_t st) {
-  // Large tiles when there is enough work to fill 256 CUs with them, smaller ones otherwise.
   const long long batch = g.batch > 0 ? g.batch : 1;
-  const long long out_cols = EPI == EPI_GLU_BF16 ? 2LL * g.N : g.N;
-  const long long big_tiles = ((g.M + 255) / 256) * ((out_cols + 255) / 256) * batch;
-  if (big_tiles >= 256) return launch_cfg<256, 256, 2, 2, EPI>(g, st);
-  return launch_cfg<128, 128, 2, 2, EPI>(g, st);
+  const long long cols = EPI == EPI_GLU_BF16 ? 2LL * g.N : g.N;  // W rows consumed
+  auto cost = [&](long long bm, long long bn, double rel) {
+    const long long tiles = ((g.M + bm - 1) / bm) * ((cols + bn - 1) / bn) * batch;
+    return (double)(((tiles + 255) / 256) * bm * bn) * rel;
+  };
+  // POP_GEMM_TILE=1..5 forces one configuration (tile-shape experiments); unset or 0 = automatic
+  static const int forced = [] {
+    const char* e = getenv("POP_GEMM_TILE");
+    return e ? atoi(e) : 0;
+  }();
+  int pick = forced;
+  if (pick < 1 || pick > 5 || (pick == 5 && EPI == EPI_GLU_BF16)) {
+    const double c1 = cost(256, 256, 1.00), c3 = cost(256, 128, 1.25), c4 = cost(128, 128, 1.40);
+    const double c5 = EPI == EPI_GLU_BF16 ? 1e300 : cost(256, 192, 1.08);
+    pick = 1;
+    double best = c1;
+    if (c5 < best) { best = c5; pick = 5; }
+    if (c3 < best) { best = c3; pick = 3; }
+    if (c4 < best) { best = c4; pick = 4; }
+  }
+  switch (pick) {
+    case 2: return launch_cfg<256, 256, 2, 4, 2, EPI>(g, st);
+    case 3: return launch_cfg<256, 128, 2, 2, 3, EPI>(g, st);
+    case 4: return launch_cfg<128, 128, 2, 2, 2, EPI>(g, st);
+    case 5:
+      if constexpr (EPI != EPI_GLU_BF16) return launch_cfg<256, 192, 2, 2, 2, EPI>(g, st);
+      [[fallthrough]];
+    default: return launch_cfg<256, 256, 2, 2, 2, EPI>(g, st);
+  }
 }
 
 }  // namespace gemm_impl
