@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--sweep", default="32,28,24,20")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel (calibrates the FETCH_SIZE / "
+                         "WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -154,6 +157,13 @@ def main():
         wall = (time.perf_counter() - t0) * 1e3 / steps
         return e0.elapsed_time(e1) / steps, wall
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     results = {}
     for lk in sweep:
         ms, wall = timed(lk, args.steps, args.warmup)
@@ -176,6 +186,9 @@ def main():
     gu_ms = gu["ms"] / max(gu["launches"], 1)
     gu_flops = 2.0 * n * d * 2 * f            # one launch: [n, d] x [2f, d]^T
     achieved = gu_flops / (gu_ms * 1e-3) / 1e12 if gu_ms > 0 else 0.0
+    # HBM bytes per launch of that kernel, from the committed rocprofv3 --pmc runs (FETCH_SIZE x 2.0 +
+    # WRITE_SIZE x 1.0, calibrated with a 1 GiB copy); only valid for the workload they were taken on
+    traffic = (377003 * 2.0 + 66942) * 1024 if (args.config == "llama8b" and n == 2048 and not args.layers) else None
     breakdown = {k: {"ms_per_launch": v["ms"] / max(v["launches"], 1), "launches_per_step": v["launches"] / args.steps,
                      "ms_per_step": v["ms"] / args.steps} for k, v in steps_t.items() if v["launches"]}
     hd = cfg["head_dim"]
@@ -207,9 +220,10 @@ def main():
                    "l_keep": head, "seq_len": n, "batch": 1},
         "speedup_vs_full_depth": results[head]["speedup_vs_full_depth"],
         "sweep": {str(k): v for k, v in results.items()},
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<256,256,2,2,GLU> (gate|up projection + GLU)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<256,256,2x2 waves,2 stages,GLU> (gate|up projection + GLU)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "traffic_source": "profiles/gate_up_gemm_llama8b_2k_pmc.md" if traffic else None,
                      "flops_per_launch": gu_flops, "avg_launch_ms": gu_ms},
         "breakdown": breakdown,
     }
