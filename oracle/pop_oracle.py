@@ -113,10 +113,18 @@ def attention_rows(q: np.ndarray, q_pos: np.ndarray, K: np.ndarray, V: np.ndarra
     return out.reshape(n, hq * hd)
 
 
+def _to_numpy(a) -> np.ndarray:
+    """Input adapter: numpy arrays pass through; torch CPU tensors (bf16 ones are widened to fp32,
+    which is exact) are viewed as numpy."""
+    if hasattr(a, "numpy"):
+        if str(getattr(a, "dtype", "")) == "torch.bfloat16":
+            a = a.float()
+        return a.numpy()
+    return np.asarray(a)
+
+
 def _w(lw: Dict, name: str, dtype) -> np.ndarray:
-    a = lw[name]
-    a = a.numpy() if hasattr(a, "numpy") else np.asarray(a)
-    return a.astype(dtype, copy=False)
+    return _to_numpy(lw[name]).astype(dtype, copy=False)
 
 
 # ----------------------------------------------------------------------------- layer bodies
@@ -165,14 +173,16 @@ def embed_rows(W: Dict, tokens: np.ndarray, dtype, embeds: Optional[np.ndarray] 
                embed_ranges: Sequence[Tuple[int, int]] = ()) -> np.ndarray:
     """h[t] = E[token[t]]; positions inside a (first_pos, count) range take the next rows of
     `embeds` instead (visual tokens enter the backbone as ready-made hidden states)."""
+    idx = np.asarray(tokens, dtype=np.int64)
     E = W["embed"]
-    E = E.numpy() if hasattr(E, "numpy") else np.asarray(E)
-    h = E[np.asarray(tokens, dtype=np.int64)].astype(dtype)
+    if hasattr(E, "numpy"):                      # torch table: gather first, then widen
+        import torch
+        h = _to_numpy(E[torch.as_tensor(idx)]).astype(dtype)
+    else:
+        h = np.asarray(E)[idx].astype(dtype)
     o = 0
     for first, count in embed_ranges:
-        e = embeds[o:o + count]
-        e = e.numpy() if hasattr(e, "numpy") else np.asarray(e)
-        h[first:first + count] = e.astype(dtype)
+        h[first:first + count] = _to_numpy(embeds[o:o + count]).astype(dtype)
         o += count
     return h
 

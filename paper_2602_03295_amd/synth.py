@@ -103,6 +103,36 @@ def make_weights(cfg: Dict, seed: int = 1234, std: float = 0.02) -> Dict:
     return w
 
 
+def make_weights_on_gpu(cfg: Dict, seed: int = 1234, std: float = 0.02):
+    """Same shapes and distribution as make_weights, drawn with the GPU generator (the 8 billion
+    draws of a full-depth model take seconds there).  Returns (device dict in the layout the GPU
+    library takes: bf16, wqkv = q|k|v rows, w_gate_up = gate|up rows; host dict in the oracle's layout:
+    bf16 torch CPU tensors that share no storage with the device copy).  Values are identical on both
+    sides.  Requires a GPU."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    d, hd = cfg["d_model"], cfg["head_dim"]
+    dq, dkv, f, v = cfg["n_q_heads"] * hd, cfg["n_kv_heads"] * hd, cfg["d_ffn"], cfg["vocab"]
+
+    def normal(*shape):
+        t = torch.empty(*shape, dtype=torch.float32, device="cuda").normal_(0.0, std, generator=g)
+        return t.to(torch.bfloat16)
+
+    ones_d = lambda: torch.ones(d, dtype=torch.float32, device="cuda")
+    ones_h = lambda: torch.ones(d, dtype=torch.float32)
+    dev = {"embed": normal(v, d), "lm_head": normal(v, d), "final_norm": ones_d(), "layers": []}
+    host = {"embed": dev["embed"].cpu(), "lm_head": dev["lm_head"].cpu(), "final_norm": ones_h(), "layers": []}
+    for _ in range(cfg["n_layers"]):
+        lw = {"norm_in": ones_d(), "wqkv": normal(dq + 2 * dkv, d), "wo": normal(d, dq), "norm_post": ones_d(),
+              "w_gate_up": normal(2 * f, d), "w_down": normal(d, f)}
+        dev["layers"].append(lw)
+        qkv, gu = lw["wqkv"].cpu(), lw["w_gate_up"].cpu()
+        host["layers"].append({"norm_in": ones_h(), "wq": qkv[:dq], "wk": qkv[dq:dq + dkv], "wv": qkv[dq + dkv:],
+                               "wo": lw["wo"].cpu(), "norm_post": ones_h(), "w_gate": gu[:f], "w_up": gu[f:],
+                               "w_down": lw["w_down"].cpu()})
+    return dev, host
+
+
 def randomize_norms(w: Dict, cfg: Dict, seed: int = 99) -> None:
     """Replace the all-ones norm scales by 1 + N(0, 0.1) draws (tests that must notice a norm
     scale applied in the wrong place)."""

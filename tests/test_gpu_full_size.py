@@ -1,0 +1,97 @@
+"""Parity at the workloads' real widths and lengths, in the launch configuration bench.py times.
+
+The oracle (fp64 numpy) needs about two seconds per kept layer at 2048 tokens on the GPU machine's host,
+so the Llama-3.1-8B shape is compared at FULL depth and full vocabulary; the other shapes run at full
+width and length-scale with a reduced layer count chosen so that kept, pruned, local and global
+layers all occur.  Weights are drawn on the GPU (seconds instead of minutes) and copied to the host
+for the oracle; both sides see identical bf16 values."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pop_oracle as O
+from paper_2602_03295_amd import synth
+from tests.gpu_util import TOL, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pop():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2602_03295_amd import pop as p
+    return p
+
+
+def run_and_compare(pop, cfg, lens, l_keep, tokens, embeds=None, embed_ranges=None, seed=1234, reserve=1):
+    dev, host = synth.make_weights_on_gpu(cfg, seed=seed)
+    model = pop.Model(cfg, dev)
+    P = cfg["page_size"]
+    bt, n_pages = synth.make_block_table(lens, P, reserve)
+    cache = pop.Cache(cfg, n_pages, len(lens), bt.shape[1], fill=float("nan"))
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    ws = pop.alloc_workspace(cfg, int(cu[-1]), len(lens), bt.shape[1])
+    dev_emb = None if embeds is None else embeds.to(torch.bfloat16).cuda()
+    logits = pop.pop_prefill(model, cache, tokens, cu, bt, l_keep, ws, embeds=dev_emb, embed_ranges=embed_ranges)
+    torch.cuda.synchronize()
+    logits = logits.cpu().numpy()
+    slots = O.slot_map(cu, bt, P)
+    assert np.array_equal(pop.pop_slot_map(cu, bt, P, n_pages), slots)
+    outs = O.pop_prefill_batch(cfg, host, tokens, cu, l_keep,
+                               embeds=None if embeds is None else embeds.numpy(),
+                               embed_ranges=embed_ranges or ())
+    worst = {"k": 0.0, "v": 0.0, "logits": 0.0}
+    for b, (Kc, Vc, ref) in enumerate(outs):
+        for l in range(cfg["n_layers"]):
+            k = cache.gather(l, 0, bt[b], lens[b]).float().cpu().numpy()
+            v = cache.gather(l, 1, bt[b], lens[b]).float().cpu().numpy()
+            ek, ev = rel_err(k, Kc[l]), rel_err(v, Vc[l])
+            assert ek <= TOL and ev <= TOL, f"layer {l + 1} seq {b}: K {ek:.4f} V {ev:.4f}"
+            worst["k"], worst["v"] = max(worst["k"], ek), max(worst["v"], ev)
+        el = rel_err(logits[b], ref)
+        assert el <= TOL, f"logits seq {b}: {el:.4f}"
+        worst["logits"] = max(worst["logits"], el)
+        top = np.argsort(ref)[-2:]
+        gap, abs_err = float(ref[top[1]] - ref[top[0]]), float(np.max(np.abs(logits[b] - ref)))
+        print(f"seq {b}: oracle top-2 gap {gap:.4f}, max abs logit err {abs_err:.4f}, "
+              f"argmax gpu {int(np.argmax(logits[b]))} oracle {int(top[1])}")
+        if gap > 2 * abs_err:
+            assert int(np.argmax(logits[b])) == int(top[1])
+    print("worst rel err", worst)
+    return worst
+
+
+def test_llama8b_2k_full_depth_lkeep24(pop):
+    """The benchmark workload itself: 32 layers, vocab 128256, 2048 tokens, L_keep = 24."""
+    cfg = synth.get_config("llama8b")
+    tokens = synth.make_tokens(cfg["vocab"], 2048, seed=1)
+    run_and_compare(pop, cfg, [2048], 24, tokens)
+
+
+def test_llama8b_ragged_batch_paged_reduced_depth(pop):
+    """Ragged packed batch with 16-token pages at the Llama width: 8 prompts, lengths ~ U[512, 4096]
+    (seed 7), 3 layers (2 kept + 1 pruned)."""
+    cfg = synth.get_config("llama8b", n_layers=3, vocab=8192)
+    lens = synth.make_lengths(8, 512, 4096, seed=7)
+    tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=1)
+    print("lengths", lens)
+    run_and_compare(pop, cfg, lens, 2, tokens)
+
+
+def test_qwen3vl_shape_visual_rows_reduced_depth(pop):
+    """Qwen3-VL-8B-style backbone width, 6144 positions of which 64..4159 are supplied hidden states."""
+    cfg = synth.get_config("qwen3vl8b", n_layers=3, vocab=8192)
+    n = 6144
+    tokens = synth.make_tokens(cfg["vocab"], n, seed=1)
+    emb = synth.make_visual_embeds(4096, cfg["d_model"], seed=2)
+    run_and_compare(pop, cfg, [n], 2, tokens, embeds=emb, embed_ranges=[(0, 64, 4096)])
+
+
+def test_gemma12b_shape_local_global_reduced(pop):
+    """Gemma-3-12B-style width (d 3840, 16/8 heads of 256, GeGLU 15360, window 1024, every 6th layer
+    global) at 7 layers (5 local + 1 global kept, 1 local pruned) and 4096 tokens."""
+    cfg = synth.get_config("gemma12b", n_layers=7, vocab=8192)
+    n = 4096
+    tokens = synth.make_tokens(cfg["vocab"], n, seed=1)
+    run_and_compare(pop, cfg, [n], 6, tokens)
