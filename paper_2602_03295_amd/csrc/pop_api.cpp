@@ -591,7 +591,9 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     pop::GemmArgs g{};
     g.batch = 1;
     g.A = abuf; g.lda = d; g.W = (const bf16_t*)lw.wqkv; g.ldw = d; g.out = qkv; g.ldc = Dqkv;
-    g.M = T; g.N = Dqkv; g.K = d; g.epilogue = pop::EPI_STORE_BF16;
+    // q, k, v leave the GEMM as fp16: they only feed the RoPE/append and attention kernels, and fp16
+    // keeps three more mantissa bits than bf16 for the score contraction (the cache itself is bf16)
+    g.M = T; g.N = Dqkv; g.K = d; g.epilogue = pop::EPI_STORE_F16;
     {
       StepTimer tm(m, st, POP_STEP_QKV_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "QKV")) return s;
@@ -600,6 +602,8 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     rw.cs = glob ? cs_g : cs_l;
     rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
     rw.vT = vT;
+    rw.fp16_inplace = 1;
+    rw.fp16_input = 1;
     {
       StepTimer tm(m, st, POP_STEP_ROPE_WRITE);
       pop::launch_rope_write(rw, st);
@@ -668,6 +672,8 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
         rw.cs = layer_is_global(cfg, l) ? cs_g : cs_l;
         rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
         rw.vT = nullptr;
+        rw.fp16_inplace = 0;
+        rw.fp16_input = 0;
         pop::launch_rope_write(rw, st);
       }
     }
@@ -746,7 +752,7 @@ pop_status pop_op_gemm(const void* A, int64_t lda, const void* W, int64_t ldw, v
                        int32_t N, int32_t K, int32_t epilogue, int32_t act, pop_stream stream) {
   if (!A || !W || !out) return fail(POP_EINVAL, "NULL pointer");
   if (M < 0 || N < 0 || K < 1) return fail(POP_EINVAL, "bad sizes");
-  if (epilogue < 0 || epilogue > 3) return fail(POP_EINVAL, "unknown epilogue %d", epilogue);
+  if (epilogue < 0 || epilogue > 3) return fail(POP_EINVAL, "unknown epilogue %d", epilogue);  // fp16 output is internal
   if (K % 8 || lda % 8 || ldw % 8 || ldc % 4 || lda < K || ldw < K || ldc < N)
     return fail(POP_ESHAPE, "K, lda, ldw must be multiples of 8 (ldc of 4) and strides must cover the rows");
   if (!aligned16(A) || !aligned16(W) || !aligned16(out)) return fail(POP_EALIGN, "pointer not 16-byte aligned");
@@ -840,7 +846,7 @@ pop_status pop_op_rope_attention(void* qkv, const int32_t* cu, int32_t B, int32_
   pop::RopeWriteArgs rw{};
   rw.qkv = (bf16_t*)qkv; rw.ld = ld; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
   rw.n_q_heads = Hq; rw.n_kv_heads = Hkv; rw.hd = hd; rw.cs = cs; rw.slot = nullptr;
-  rw.k_pool = nullptr; rw.v_pool = nullptr; rw.page_size = 1; rw.vT = vT; rw.Tp = Tp;
+  rw.k_pool = nullptr; rw.v_pool = nullptr; rw.page_size = 1; rw.vT = vT; rw.Tp = Tp; rw.fp16_inplace = 1;
   rw.cu_seqlens = at<int32_t>(workspace, w.o_cu); rw.vt_off = at<int32_t>(workspace, w.o_vt_off);
   rw.tile_seq = at<int32_t>(workspace, w.o_t64_seq); rw.tile_start = at<int32_t>(workspace, w.o_t64_start);
   rw.n_tiles = n64;

@@ -4,7 +4,13 @@
 // One work-group = 128 query rows of one query head; 4 waves x 32 rows.  Keys/values stream through
 // LDS in tiles of 64, staged with buffer_load ... lds and double buffered.
 //
-// MFMA arrangement (v_mfma_f32_32x32x16_bf16, D = A * B with A rows / B columns spread over lanes):
+// Inside this kernel Q, K, V and P are fp16 (the RoPE/append kernel hands over fp16 copies; the cache
+// itself stays bf16): with random-like V the softmax average shrinks signal and rounding noise alike, so
+// the relative error of the output equals that of the individual probabilities, and bf16's 8-bit
+// mantissa in q, k and P was the largest error source of a whole layer.  P <= 1 and saturating
+// conversions keep fp16's range safe.
+//
+// MFMA arrangement (v_mfma_f32_32x32x16_f16, D = A * B with A rows / B columns spread over lanes):
 //   S^T = K * Q^T   : A = K tile rows (keys), B = Q rows.  A lane then owns ONE query row (lane & 31)
 //                     and 16 keys per 32-key block, so the softmax row reductions are in-lane plus a
 //                     single exchange with lane ^ 32.
@@ -12,7 +18,7 @@
 //                     accumulator registers 8G..8G+7 of a block are exactly the B operand of the
 //                     G-th 16-key step, because the keys are fed to the first MFMA in the permuted
 //                     order key(i) below; no cross-lane data movement is needed for P.
-// Softmax is computed in fp32 with exp2 and running max / sum (online softmax); P is rounded to bf16
+// Softmax is computed in fp32 with exp2 and running max / sum (online softmax); P is rounded to fp16
 // for the second MFMA, O accumulates in fp32.
 #include "pop_device.h"
 #include "pop_kernels.h"
@@ -108,11 +114,11 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
   };
 
   // ---- Q fragments (B operand: lane = query row, 8 consecutive head-dim values per step)
-  bf16x8_t qf[KS];
+  f16x8_t qf[KS];
   {
     const bf16_t* qp = a.qkv + ((long long)seq0 + (qvalid ? qrow : 0)) * a.ld + a.q_col + head * HD + h * 8;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8_t*>(qp + ks * 16);
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const f16x8_t*>(qp + ks * 16);
   }
 
   floatx16_t o[OB];
@@ -153,8 +159,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
       const int pc = ((2 * ks + h) ^ k_sw) * 16;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sk + k_frag + kb * 32 * K_ROW_BYTES + pc);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
+        const f16x8_t kf = *reinterpret_cast<const f16x8_t*>(sk + k_frag + kb * 32 * K_ROW_BYTES + pc);
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[ks], s[kb], 0, 0, 0);
       }
     }
     // register v of block kb on lane-half h holds key j0 + kb*32 + 16*(v/8) + 8*h + (v%8)
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);  // m_run = -inf -> 0
     float psum = 0.f;
-    bf16x8_t pf[2][2];
+    f16x8_t pf[2][2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -189,7 +195,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
         for (int e = 0; e < 8; ++e) {
           const float pv = __builtin_amdgcn_exp2f(s[kb][g * 8 + e] * scale_log2 - m_use);
           psum += pv;
-          pf[kb][g][e] = static_cast<__bf16>(pv);
+          pf[kb][g][e] = static_cast<_Float16>(pv);
         }
     l_run = l_run * alpha + psum;
     m_run = m_new;
@@ -205,8 +211,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
         const int pc = ((4 * kb + 2 * g + h) ^ v_sw) * 16;
 #pragma unroll
         for (int i = 0; i < OB; ++i) {
-          const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(sv + v_frag + i * 32 * 128 + pc);
-          o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][g], o[i], 0, 0, 0);
+          const f16x8_t vf = *reinterpret_cast<const f16x8_t*>(sv + v_frag + i * 32 * 128 + pc);
+          o[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[kb][g], o[i], 0, 0, 0);
         }
       }
   }

@@ -147,7 +147,7 @@ void launch_rope_table(const int32_t* pos, float2* cs, int T, int hd, double the
 // ------------------------------------------------------------------------------------- RoPE + cache append
 // grid = (tiles of 64 positions, heads); a block handles one head of one tile.
 //   q head: rotate in place.   k head: rotate in place + store to the K pool.
-//   v head: store to the V pool (+ transposed copy vT[h][i][col], zero beyond the sequence end).
+//   v head: store to the V pool (+ transposed fp16 copy vT[h][i][col], zero beyond the sequence end).
 __global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a) {
   __shared__ uint16_t tr[256 * 66];  // [hd][64 + 2] transposed V tile
   const int tile = blockIdx.x;
@@ -175,19 +175,25 @@ __global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a) {
       const uint4 hi = *reinterpret_cast<const uint4*>(row + half + g * 8);
       const float2* cs = a.cs + t * half + g * 8;
       const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
-      uint32_t ol[4], oh[4];
+      uint32_t ol[4], oh[4], fl[4], fh[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
-        const float x0 = bf16lo(lw[e]), x1 = bf16hi(lw[e]);
-        const float y0 = bf16lo(hw[e]), y1 = bf16hi(hw[e]);
-        ol[e] = pack_bf16x2(x0 * c0.x - y0 * c0.y, x1 * c1.x - y1 * c1.y);
-        oh[e] = pack_bf16x2(y0 * c0.x + x0 * c0.y, y1 * c1.x + x1 * c1.y);
+        const float x0 = a.fp16_input ? f16lo(lw[e]) : bf16lo(lw[e]), x1 = a.fp16_input ? f16hi(lw[e]) : bf16hi(lw[e]);
+        const float y0 = a.fp16_input ? f16lo(hw[e]) : bf16lo(hw[e]), y1 = a.fp16_input ? f16hi(hw[e]) : bf16hi(hw[e]);
+        const float r0 = x0 * c0.x - y0 * c0.y, r1 = x1 * c1.x - y1 * c1.y;
+        const float r2 = y0 * c0.x + x0 * c0.y, r3 = y1 * c1.x + x1 * c1.y;
+        ol[e] = pack_bf16x2(r0, r1);
+        oh[e] = pack_bf16x2(r2, r3);
+        fl[e] = pack_f16x2(r0, r1);
+        fh[e] = pack_f16x2(r2, r3);
       }
       const uint4 vlo = make_uint4(ol[0], ol[1], ol[2], ol[3]);
       const uint4 vhi = make_uint4(oh[0], oh[1], oh[2], oh[3]);
-      *reinterpret_cast<uint4*>(row + g * 8) = vlo;
-      *reinterpret_cast<uint4*>(row + half + g * 8) = vhi;
+      // in place: fp16 when the attention kernel is the consumer (three more mantissa bits than bf16
+      // for the score contraction), bf16 otherwise; the cache entry is always bf16
+      *reinterpret_cast<uint4*>(row + g * 8) = a.fp16_inplace ? make_uint4(fl[0], fl[1], fl[2], fl[3]) : vlo;
+      *reinterpret_cast<uint4*>(row + half + g * 8) = a.fp16_inplace ? make_uint4(fh[0], fh[1], fh[2], fh[3]) : vhi;
       if (is_k && a.k_pool) {
         const int s = a.slot[t];
         bf16_t* dst = a.k_pool + (((size_t)(s / P) * a.n_kv_heads + hh) * P + (s % P)) * hd;
@@ -210,15 +216,21 @@ __global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a) {
       if (a.v_pool) {
         const int s = a.slot[t];
         bf16_t* dst = a.v_pool + (((size_t)(s / P) * a.n_kv_heads + hh) * P + (s % P)) * hd;
-        *reinterpret_cast<uint4*>(dst + g * 8) = v;
+        uint4 vb = v;   // the cache entry is bf16
+        if (a.fp16_input) {
+          vb.x = pack_bf16x2(f16lo(v.x), f16hi(v.x)); vb.y = pack_bf16x2(f16lo(v.y), f16hi(v.y));
+          vb.z = pack_bf16x2(f16lo(v.z), f16hi(v.z)); vb.w = pack_bf16x2(f16lo(v.w), f16hi(v.w));
+        }
+        *reinterpret_cast<uint4*>(dst + g * 8) = vb;
       }
     }
     if (a.vT) {
+      // the transposed copy is fp16 (bf16 -> fp16 is exact inside fp16's range; saturates outside)
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        tr[(g * 8 + 2 * e) * 66 + p] = (uint16_t)(w[e] & 0xffff);
-        tr[(g * 8 + 2 * e + 1) * 66 + p] = (uint16_t)(w[e] >> 16);
+        tr[(g * 8 + 2 * e) * 66 + p] = a.fp16_input ? (uint16_t)(w[e] & 0xffff) : f32_to_f16_sat(bf16lo(w[e]));
+        tr[(g * 8 + 2 * e + 1) * 66 + p] = a.fp16_input ? (uint16_t)(w[e] >> 16) : f32_to_f16_sat(bf16hi(w[e]));
       }
     }
   }

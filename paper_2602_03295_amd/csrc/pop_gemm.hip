@@ -326,18 +326,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
           if (n >= p.N) continue;
           const float r0 = acc[i][j][g * 4 + 0], r1 = acc[i][j][g * 4 + 1];
           const float r2 = acc[i][j][g * 4 + 2], r3 = acc[i][j][g * 4 + 3];
-          if (EPI == EPI_STORE_BF16) {
+          if (EPI == EPI_STORE_BF16 || EPI == EPI_STORE_F16) {
             bf16_t* o = reinterpret_cast<bf16_t*>(p.out) + (long long)z * p.strideC + (long long)m * p.ldc + n;
             if (n + 3 < p.N) {
               uint2 pk;
-              pk.x = pack_bf16x2(r0, r1);
-              pk.y = pack_bf16x2(r2, r3);
+              pk.x = EPI == EPI_STORE_F16 ? pack_f16x2(r0, r1) : pack_bf16x2(r0, r1);
+              pk.y = EPI == EPI_STORE_F16 ? pack_f16x2(r2, r3) : pack_bf16x2(r2, r3);
               *reinterpret_cast<uint2*>(o) = pk;
             } else {
               const float r[4] = {r0, r1, r2, r3};
 #pragma unroll
               for (int e = 0; e < 4; ++e)
-                if (n + e < p.N) o[e] = f32_to_bf16(r[e]);
+                if (n + e < p.N) o[e] = EPI == EPI_STORE_F16 ? f32_to_f16_sat(r[e]) : f32_to_bf16(r[e]);
             }
           } else {
             float* o = reinterpret_cast<float*>(p.out) + (long long)z * p.strideC + (long long)m * p.ldc + n;
@@ -445,6 +445,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
     case EPI_ADD_F32: return launch_epi<EPI_ADD_F32>(g, st);
     case EPI_GLU_BF16: return launch_epi<EPI_GLU_BF16>(g, st);
     case EPI_STORE_F32: return launch_epi<EPI_STORE_F32>(g, st);
+    case EPI_STORE_F16: return launch_epi<EPI_STORE_F16>(g, st);
   }
   return hipErrorInvalidValue;
 }

@@ -38,17 +38,18 @@ void launch_rope_table(const int32_t* pos, float2* cs, int T, int hd, double the
 // Prefill RoPE + cache append for one layer.  Work is organised in tiles of 64 consecutive
 // positions of one sequence: tile i covers positions tile_start[i] .. +63 of sequence tile_seq[i].
 struct RopeWriteArgs {
-  bf16_t* qkv;            // [T, ld] rows q | k | v ; q and k are rotated in place (nullptr q part ok)
+  bf16_t* qkv;            // [T, ld] rows q | k | v ; q and k are rotated in place
+  int fp16_input;         // 1: qkv holds fp16 (EPI_STORE_F16 output), 0: bf16
   int ld;                 // row stride in elements
   int q_col, k_col, v_col;  // first column of q / k / v inside a row (q_col < 0: no q heads)
   int n_q_heads, n_kv_heads, hd;
   const float2* cs;       // [T, hd/2]
   const int32_t* slot;    // [T] cache slot of each packed token
-  const uint8_t* skip;    // [T] or nullptr: 1 = do not write this row's cache entry
   bf16_t* k_pool;         // this layer's K pool [page][Hkv][P][hd]
   bf16_t* v_pool;
   int page_size;
-  bf16_t* vT;             // nullptr or [Hkv][hd][Tp]: transposed copy of V for the attention kernel
+  int fp16_inplace;       // 1: rotated q and k are written back as fp16 (consumer = attention kernel)
+  bf16_t* vT;             // nullptr or [Hkv][hd][Tp]: transposed fp16 copy of V for the attention kernel
   int Tp;
   const int32_t* cu_seqlens;  // [B+1]
   const int32_t* vt_off;      // [B] first column of each sequence in vT (multiple of 64)
@@ -65,7 +66,8 @@ enum GemmEpilogue {
   EPI_STORE_BF16 = 0,  // out bf16 [M, ldc]
   EPI_ADD_F32 = 1,     // out fp32 [M, ldc]: out += C           (residual update)
   EPI_GLU_BF16 = 2,    // W is [2N, K] (gate rows then up rows); out bf16 [M, ldc] = act(gate) * up
-  EPI_STORE_F32 = 3    // out fp32 [M, ldc] = C
+  EPI_STORE_F32 = 3,   // out fp32 [M, ldc] = C
+  EPI_STORE_F16 = 4    // out fp16 [M, ldc] = C (saturating), for outputs that stay inside the library
 };
 struct GemmArgs {
   const bf16_t* A;   // [M, lda]
@@ -88,11 +90,11 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st);
 // Causal GQA flash attention over packed variable-length sequences (pop_attention.hip)
 // ---------------------------------------------------------------------------------------------
 struct AttnPrefillArgs {
-  const bf16_t* qkv;  // rotated q and k inside [T, ld]
+  const bf16_t* qkv;  // rotated q and k inside [T, ld], as fp16 (written by launch_rope_write with fp16_inplace)
   int ld, q_col, k_col;
-  const bf16_t* vT;   // [Hkv][hd][Tp]
+  const bf16_t* vT;   // [Hkv][hd][Tp] fp16
   int Tp;
-  bf16_t* out;        // [T, Hq*hd]
+  bf16_t* out;        // [T, Hq*hd] bf16
   int T, n_q_heads, n_kv_heads, hd;
   int window;         // 0 = global
   const int32_t* cu_seqlens;

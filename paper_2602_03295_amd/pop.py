@@ -187,7 +187,7 @@ class Model:
         _check(lib.pop_load_weights(C.byref(self.c_cfg), C.byref(w), C.byref(self.handle)))
 
     def __del__(self):
-        if getattr(self, "handle", None):
+        if getattr(self, "handle", None) and lib is not None:
             lib.pop_free_model(self.handle)
             self.handle = None
 
@@ -233,7 +233,7 @@ class Cache:
         return lib.pop_cache_n_seqs(self.handle)
 
     def __del__(self):
-        if getattr(self, "handle", None):
+        if getattr(self, "handle", None) and lib is not None:
             lib.pop_cache_destroy(self.handle)
             self.handle = None
 
