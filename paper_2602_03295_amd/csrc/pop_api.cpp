@@ -161,7 +161,7 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.nt64_max = T / 64 + B;
   w.nta_max = T / 128 + B;
   const long long max_len = (long long)maxp * c.page_size;
-  w.n_splits_max = (int)std::max<long long>(1, (max_len + 255) / 256);
+  w.n_splits_max = (int)std::max<long long>(1, (max_len + pop::kDecodeKeysPerSplit - 1) / pop::kDecodeKeysPerSplit);
   size_t o = 0;
   auto take = [&](size_t bytes) {
     const size_t at = o;
@@ -281,7 +281,7 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   ad.n_kv_heads = c.n_kv_heads;
   ad.hd = c.head_dim;
   const int span = ad.window > 0 ? std::min(max_len, ad.window) : max_len;
-  ad.n_splits = std::max(1, (span + 255) / 256);
+  ad.n_splits = std::max(1, (span + pop::kDecodeKeysPerSplit - 1) / pop::kDecodeKeysPerSplit);
   ad.max_len = max_len;
   ad.part = at<float>(x.ws, x.w->o_part);
   ad.out = attnb;

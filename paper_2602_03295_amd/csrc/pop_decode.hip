@@ -176,7 +176,7 @@ void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, 
 // ------------------------------------------------------------------------------------- decode attention
 namespace decode_impl {
 
-constexpr int KCH = 256;  // keys per work-group (one split)
+constexpr int KCH = kDecodeKeysPerSplit;  // keys per work-group (one split)
 constexpr int GMAX = 8;   // query heads per KV head
 
 // grid (n_splits, Hkv, B), 256 threads.  Split s of sequence b covers keys lo + s*KCH .. +KCH-1,

@@ -44,7 +44,8 @@ struct GemmParams {
   int M, N, K;           // N = output columns (for GLU: columns of the result, W has 2N rows)
   int lda, ldw, ldc;     // elements
   int act;
-  int tiles_m, tiles_n;  // per batch
+  int tiles_m, tiles_n;  // per batch, of this launch
+  int n_tile0;           // first column tile of this launch (a GEMM may be split into two launches)
   long long strideA, strideC;
   const bf16_t* const* W_list;
 };
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   const int tm = logical % p.tiles_m, tn = logical / p.tiles_m;
   const int m0 = tm * BM;
   constexpr int BN_OUT = EPI == EPI_GLU_BF16 ? BN / 2 : BN;
-  const int n0 = tn * BN_OUT;  // first output column of the tile
+  const int n0 = (p.n_tile0 + tn) * BN_OUT;  // first output column of the tile
 
   const int z = blockIdx.z;
   const bf16_t* A = p.A + (long long)z * p.strideA;
@@ -362,7 +363,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 }
 
 template <int BM, int BN, int WGM, int WGN, int STAGES, int EPI>
-hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
+hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_tiles = -1) {
   constexpr int BN_OUT = EPI == EPI_GLU_BF16 ? BN / 2 : BN;
   constexpr int smem = STAGES * (BM + BN) * BK * 2 + 1024;  // stages + prefetch scratch
   static_assert(smem <= 160 * 1024, "LDS budget of a gfx950 CU");
@@ -372,7 +373,9 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
   p.lda = (int)g.lda; p.ldw = (int)g.ldw; p.ldc = (int)g.ldc;
   p.act = g.act;
   p.tiles_m = (g.M + BM - 1) / BM;
-  p.tiles_n = (g.N + BN_OUT - 1) / BN_OUT;
+  p.tiles_n = n_tiles >= 0 ? n_tiles : (g.N + BN_OUT - 1) / BN_OUT;
+  p.n_tile0 = n_tile0;
+  if (p.tiles_n <= 0) return hipSuccess;
   p.strideA = g.strideA; p.strideC = g.strideC;
   p.W_list = g.batch > 1 || g.W_list ? g.W_list : nullptr;
   static bool attr_set = false;  // per instantiation
@@ -424,8 +427,28 @@ hipError_t launch_epi(const GemmArgs& g, hipStream_t st) {
     case 5:
       if constexpr (EPI != EPI_GLU_BF16) return launch_cfg<256, 192, 2, 2, 2, EPI>(g, st);
       [[fallthrough]];
-    default: return launch_cfg<256, 256, 2, 2, 2, EPI>(g, st);
+    default: break;
   }
+  // 256x256 tiles.  If they leave the last round of 256 work-groups partly empty, the column tiles
+  // of that last round are computed by a second launch with 128x256 tiles (twice as many, half as
+  // long): at M = 2048 the gate|up projection has 896 tiles = 3.5 rounds, i.e. 3 rounds of 256x256
+  // plus one round of 128x256 instead of four rounds.
+  const int tiles_m = (g.M + 255) / 256;
+  const int tiles_n = (int)((cols + 255) / 256);
+  const long long total = (long long)tiles_m * tiles_n * batch;
+  const long long rem = total % 256;
+  static const bool no_split = getenv("POP_GEMM_NOSPLIT") != nullptr;
+  if (forced == 0 && !no_split && batch == 1 && total > 256 && rem > 0 && rem <= 128 && g.M > 128) {
+    const int tail_cols = (int)((rem + tiles_m - 1) / tiles_m);   // column tiles moved to the second launch
+    const int head_cols = tiles_n - tail_cols;
+    // only worth it when the second launch fills the chip better than the partial round did
+    if (head_cols > 0 && (long long)tail_cols * ((g.M + 127) / 128) <= 256) {
+      hipError_t e = launch_cfg<256, 256, 2, 2, 2, EPI>(g, st, 0, head_cols);
+      if (e != hipSuccess) return e;
+      return launch_cfg<128, 256, 2, 2, 2, EPI>(g, st, head_cols, tail_cols);
+    }
+  }
+  return launch_cfg<256, 256, 2, 2, 2, EPI>(g, st);
 }
 
 }  // namespace gemm_impl

@@ -119,6 +119,10 @@ void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, 
                         const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool,
                         bf16_t* v_pool, int page_size, int B, hipStream_t st);
 
+// Keys per split of the decode attention: small enough that a 2K-token context already gives every
+// CU a work-group (len / 64 splits x KV heads x sequences).
+constexpr int kDecodeKeysPerSplit = 64;
+
 // Attention of one query row per sequence over its paged cache entries 0..len-1 (len = pos + 1),
 // split over the key range; `part` holds the per-split partial results.
 struct AttnDecodeArgs {
@@ -130,7 +134,7 @@ struct AttnDecodeArgs {
   const int32_t* pos;   // [B] position of the query token (attends 0..pos)
   int window;
   int B, n_q_heads, n_kv_heads, hd;
-  int n_splits;         // key range of every sequence is cut into n_splits equal chunks
+  int n_splits;         // splits of kDecodeKeysPerSplit keys that cover the longest visible key range
   int max_len;          // upper bound of pos+1 over the batch
   float* part;          // [B, Hq, n_splits, hd + 2]
   bf16_t* out;          // [B, Hq*hd]
