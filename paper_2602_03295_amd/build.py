@@ -11,6 +11,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpop.so")
 SOURCES = ["pop_api.cpp", "pop_elementwise.hip", "pop_gemm.hip", "pop_attention.hip", "pop_decode.hip"]
+# Per-file extras.  The attention kernel post-processes its MFMA accumulators with vector ALU ops
+# (softmax, rescaling); keeping them in architectural VGPRs (VGPR-form MFMA) avoids an
+# AGPR<->VGPR copy of every accumulator in every key tile.  The GEMM keeps the default (AGPR
+# accumulators): it needs all 512 registers.
+EXTRA_FLAGS = {"pop_attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
@@ -29,7 +34,7 @@ def build(verbose: bool = True) -> str:
 
     def compile_one(src: str) -> str:
         obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc(), *FLAGS, "-I", CSRC, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc(), *FLAGS, *EXTRA_FLAGS.get(src, []), "-I", CSRC, "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")

@@ -143,7 +143,7 @@ constexpr int kKvChunk = 8;  // pruned layers projected per batched GEMM
 struct Workspace {
   // int32 meta (one upload per call)
   size_t meta_bytes;
-  size_t o_tokens, o_row_src, o_pos, o_slot, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start,
+  size_t o_tokens, o_row_src, o_pos, o_slot, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start, o_ta_start2,
       o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_wlist;
   // device buffers
   size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_a_multi, o_kv_out;
@@ -178,6 +178,7 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_t64_start = take(4 * (size_t)w.nt64_max);
   w.o_ta_seq = take(4 * (size_t)w.nta_max);
   w.o_ta_start = take(4 * (size_t)w.nta_max);
+  w.o_ta_start2 = take(4 * (size_t)w.nta_max);
   w.o_bnd_row = take(4 * (size_t)B);
   w.o_bnd_pos = take(4 * (size_t)B);
   w.o_bnd_slot = take(4 * (size_t)B);
@@ -239,6 +240,31 @@ pop_status slot_map_impl(const int32_t* cu, int n_seqs, const int32_t* bt, int m
         slots[cu[b] + t] = bt[(size_t)b * maxp + t / P] * P + (int)(t % P);
   }
   return POP_OK;
+}
+
+// Work list of the prefill attention kernel.  A work-group processes one or two query tiles of 128
+// rows of one sequence: the k-th latest tile (most keys) is paired with the k-th earliest (fewest),
+// so every work-group of a sequence sees the same number of key tiles and the causal triangle is
+// balanced.  Longer sequences (more work per pair) come first.  Returns the number of entries.
+int build_attention_work(const int32_t* cu, int B, int32_t* seq_out, int32_t* start_out, int32_t* start2_out) {
+  struct Item { int work, seq, a, b; };
+  std::vector<Item> items;
+  for (int b = 0; b < B; ++b) {
+    const int len = cu[b + 1] - cu[b];
+    const int nt = (len + 127) / 128;
+    for (int k = 0; k < (nt + 1) / 2; ++k) {
+      const int heavy = nt - 1 - k, light = k;
+      items.push_back(Item{heavy == light ? heavy + 1 : nt + 1, b, heavy * 128, heavy == light ? -1 : light * 128});
+    }
+  }
+  std::stable_sort(items.begin(), items.end(), [](const Item& x, const Item& y) { return x.work > y.work; });
+  int n = 0;
+  for (const Item& it : items) {
+    seq_out[n] = it.seq;
+    start_out[n] = it.a;
+    start2_out[n++] = it.b;
+  }
+  return n;
 }
 
 struct LayerCtx {
@@ -497,7 +523,6 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   std::copy(slots.begin(), slots.end(), mi(w.o_slot));
   std::copy(a->cu_seqlens, a->cu_seqlens + B + 1, mi(w.o_cu));
   int n_t64 = 0, n_ta = 0, Tp = 0, max_len = 0;
-  std::vector<std::pair<int, int>> atiles;  // (start, seq)
   for (int b = 0; b < B; ++b) {
     const int s0 = a->cu_seqlens[b], len = a->cu_seqlens[b + 1] - s0;
     max_len = std::max(max_len, len);
@@ -508,19 +533,12 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       mi(w.o_t64_seq)[n_t64] = b;
       mi(w.o_t64_start)[n_t64++] = p0;
     }
-    for (int q0 = 0; q0 < len; q0 += 128) atiles.emplace_back(q0, b);
     mi(w.o_bnd_row)[b] = s0 + len - 1;
     mi(w.o_bnd_pos)[b] = len - 1;
     mi(w.o_bnd_slot)[b] = slots[s0 + len - 1];
     std::copy(a->block_table + (size_t)b * maxp, a->block_table + (size_t)(b + 1) * maxp, mi(w.o_bt) + (size_t)b * maxp);
   }
-  // heaviest query tiles (latest rows) first
-  std::stable_sort(atiles.begin(), atiles.end(),
-                   [](const std::pair<int, int>& x, const std::pair<int, int>& y) { return x.first > y.first; });
-  for (auto& t : atiles) {
-    mi(w.o_ta_seq)[n_ta] = t.second;
-    mi(w.o_ta_start)[n_ta++] = t.first;
-  }
+  n_ta = build_attention_work(a->cu_seqlens, B, mi(w.o_ta_seq), mi(w.o_ta_start), mi(w.o_ta_start2));
   {
     const bf16_t** wl = reinterpret_cast<const bf16_t**>(meta.data() + w.o_wlist);
     for (int l = 0; l < cfg.n_layers; ++l)
@@ -613,7 +631,8 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     ap.T = T; ap.n_q_heads = cfg.n_q_heads; ap.n_kv_heads = cfg.n_kv_heads; ap.hd = hd;
     ap.window = glob ? 0 : cfg.sliding_window;
     ap.cu_seqlens = d_cu; ap.vt_off = d_vt_off;
-    ap.tile_seq = at<int32_t>(ws, w.o_ta_seq); ap.tile_start = at<int32_t>(ws, w.o_ta_start); ap.n_tiles = n_ta;
+    ap.tile_seq = at<int32_t>(ws, w.o_ta_seq); ap.tile_start = at<int32_t>(ws, w.o_ta_start);
+    ap.tile_start2 = at<int32_t>(ws, w.o_ta_start2); ap.n_tiles = n_ta;
     {
       StepTimer tm(m, st, POP_STEP_ATTENTION);
       hipError_t e = pop::launch_attention_prefill(ap, st);
@@ -779,7 +798,7 @@ pop_status pop_op_gemv(const void* x, const void* W, void* out, int64_t ldo, int
 
 namespace {
 struct RopeAttnWs {
-  size_t o_pos, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start, meta_bytes, o_cs, o_vT, total;
+  size_t o_pos, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start, o_ta_start2, meta_bytes, o_cs, o_vT, total;
   int Tp_max;
 };
 RopeAttnWs carve_rope_attn(int T, int B, int Hkv, int hd) {
@@ -794,6 +813,7 @@ RopeAttnWs carve_rope_attn(int T, int B, int Hkv, int hd) {
   w.o_t64_start = take(4 * ((size_t)T / 64 + B));
   w.o_ta_seq = take(4 * ((size_t)T / 128 + B));
   w.o_ta_start = take(4 * ((size_t)T / 128 + B));
+  w.o_ta_start2 = take(4 * ((size_t)T / 128 + B));
   w.meta_bytes = o;
   w.o_cs = take(8 * (size_t)T * (hd / 2));
   w.o_vT = take(2 * (size_t)Hkv * hd * w.Tp_max);
@@ -825,18 +845,14 @@ pop_status pop_op_rope_attention(void* qkv, const int32_t* cu, int32_t B, int32_
   auto mi = [&](size_t off) { return reinterpret_cast<int32_t*>(meta.data() + off); };
   std::copy(cu, cu + B + 1, mi(w.o_cu));
   int n64 = 0, nta = 0, Tp = 0;
-  std::vector<std::pair<int, int>> atiles;
   for (int b = 0; b < B; ++b) {
     const int len = cu[b + 1] - cu[b];
     for (int t = 0; t < len; ++t) mi(w.o_pos)[cu[b] + t] = t;
     mi(w.o_vt_off)[b] = Tp;
     Tp += (int)round_up(len, 64);
     for (int p0 = 0; p0 < len; p0 += 64) { mi(w.o_t64_seq)[n64] = b; mi(w.o_t64_start)[n64++] = p0; }
-    for (int q0 = 0; q0 < len; q0 += 128) atiles.emplace_back(q0, b);
   }
-  std::stable_sort(atiles.begin(), atiles.end(),
-                   [](const std::pair<int, int>& x, const std::pair<int, int>& y) { return x.first > y.first; });
-  for (auto& t : atiles) { mi(w.o_ta_seq)[nta] = t.second; mi(w.o_ta_start)[nta++] = t.first; }
+  nta = build_attention_work(cu, B, mi(w.o_ta_seq), mi(w.o_ta_start), mi(w.o_ta_start2));
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   POP_HIP(hipMemcpyAsync(workspace, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
   const int Dq = Hq * hd, Dkv = Hkv * hd, ld = Dq + 2 * Dkv;
@@ -856,6 +872,7 @@ pop_status pop_op_rope_attention(void* qkv, const int32_t* cu, int32_t B, int32_
   ap.T = T; ap.n_q_heads = Hq; ap.n_kv_heads = Hkv; ap.hd = hd; ap.window = window;
   ap.cu_seqlens = rw.cu_seqlens; ap.vt_off = rw.vt_off;
   ap.tile_seq = at<int32_t>(workspace, w.o_ta_seq); ap.tile_start = at<int32_t>(workspace, w.o_ta_start);
+  ap.tile_start2 = at<int32_t>(workspace, w.o_ta_start2);
   ap.n_tiles = nta;
   hipError_t e = pop::launch_attention_prefill(ap, st);
   if (e != hipSuccess) return fail(POP_EHIP, "attention launch failed: %s", hipGetErrorString(e));

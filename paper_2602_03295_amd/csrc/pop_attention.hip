@@ -1,7 +1,8 @@
 // Causal grouped-query flash attention for the prompt body (the Attn block of Sec. 2.1 applied to
 // all body rows of a kept layer at once), packed variable-length sequences, optional sliding window.
 //
-// One work-group = 128 query rows of one query head; 4 waves x 32 rows.  Keys/values stream through
+// One work-group = one or two tiles of 128 query rows of one query head (a late tile paired with an
+// early one, which balances the causal triangle); 4 waves x 32 rows.  Keys/values stream through
 // LDS in tiles of 64, staged with buffer_load ... lds and double buffered.
 //
 // Inside this kernel Q, K, V and P are fp16 (the RoPE/append kernel hands over fp16 copies; the cache
@@ -37,9 +38,15 @@ __device__ __forceinline__ int key_of_row(int i) {
   const int a = i >> 3, hb = (i >> 2) & 1, r = i & 3;
   return 16 * (a >> 1) + 8 * hb + 4 * (a & 1) + r;
 }
-// LDS swizzle of the K tile: the 8 rows a ds_read_b128 phase touches (see key_of_row) get 8 distinct
-// values.
-__device__ __forceinline__ int k_swz(int row) { return (row & 3) | (((row >> 3) & 1) << 2); }
+// LDS swizzle of the K tile.  gfx950 serves a ds_read_b128 sixteen lanes (256 B = all 64 banks) per
+// cycle, and the sixteen lanes of a phase read the sixteen rows of an aligned group (key_of_row
+// permutes inside such a group).  Rows of >= 256 B each fill whole bank lines, so the sixteen rows need
+// sixteen different chunk positions: key = row & 15.  128-byte rows (head_dim 64) share a bank line in
+// pairs: key = (row >> 1) & 7 (the row's parity already selects the half line).
+template <int ROW_BYTES>
+__device__ __forceinline__ int k_swz(int row) {
+  return ROW_BYTES >= 256 ? (row & 15) : ((row >> 1) & 7);
+}
 
 template <int HD>
 __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, float scale_log2) {
@@ -60,12 +67,16 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
   const int head = blockIdx.y;
   const int kvh = head / (a.n_q_heads / a.n_kv_heads);
   const int b = a.tile_seq[tile];
-  const int q0 = a.tile_start[tile];
   const int seq0 = a.cu_seqlens[b];
   const int len = a.cu_seqlens[b + 1] - seq0;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int h = lane >> 5;
+  // one or two query tiles per work-group (a late and an early tile of the same sequence)
+  for (int part = 0; part < 2; ++part) {
+  const int q0 = part == 0 ? a.tile_start[tile] : a.tile_start2[tile];
+  if (q0 < 0) break;
+  if (part == 1) __builtin_amdgcn_s_barrier();  // everyone is done with the first tile's LDS stages
   const int qrow = q0 + wave * 32 + (lane & 31);  // position of this lane's query row
   const bool qvalid = qrow < len;
 
@@ -88,13 +99,13 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
   for (int j = 0; j < K_LOADS; ++j) {
     const int row = (j * 4 + wave) * K_RPL + lane / K_CPR;
     const int pchunk = lane % K_CPR;
-    const int c = pchunk ^ k_swz(row);
+    const int c = pchunk ^ k_swz<K_ROW_BYTES>(row);
     offK[j] = (uint32_t)((((long long)seq0 + row) * a.ld + a.k_col + kvh * HD + c * 8) * 2);
   }
 #pragma unroll
   for (int j = 0; j < V_LOADS; ++j) {
     const int row = (j * 4 + wave) * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ (row & 7);
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
     offV[j] = (uint32_t)((((long long)kvh * HD + row) * a.Tp + a.vt_off[b] + c * 8) * 2);
   }
   // The key offset goes into the per-lane offset (not the scalar one) so that rows beyond the end of
@@ -131,9 +142,9 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
   // LDS fragment addresses
   const int krow = key_of_row(lane & 31);
   const int k_frag = krow * K_ROW_BYTES;
-  const int k_sw = k_swz(krow);  // same for krow + 32 (bits 0,1,3 unchanged)
+  const int k_sw = k_swz<K_ROW_BYTES>(krow);  // same for krow + 32 (only bits 0..3 of the row are used)
   const int v_frag = (lane & 31) * 128;
-  const int v_sw = lane & 7;
+  const int v_sw = ((lane & 31) >> 1) & 7;
 
   const int wave_last = q0 + wave * 32 + 31;  // last query position this wave owns
 
@@ -199,10 +210,12 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
         }
     l_run = l_run * alpha + psum;
     m_run = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {  // the running max moved for some row of this wave
 #pragma unroll
-    for (int i = 0; i < OB; ++i)
+      for (int i = 0; i < OB; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
+        for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
+    }
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -219,7 +232,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
 
   // ---- normalise and store: lane owns query row qrow, head-dim i*32 + (v/4)*8 + 4h + v%4
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (!qvalid) return;
+  if (!qvalid) continue;
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   bf16_t* op = a.out + ((long long)seq0 + qrow) * ((long long)a.n_q_heads * HD) + head * HD;
 #pragma unroll
@@ -231,6 +244,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
       pk.y = pack_bf16x2(o[i][g * 4 + 2] * inv, o[i][g * 4 + 3] * inv);
       *reinterpret_cast<uint2*>(op + i * 32 + g * 8 + h * 4) = pk;
     }
+  }  // part
 #endif
 }
 

@@ -99,8 +99,9 @@ struct AttnPrefillArgs {
   int window;         // 0 = global
   const int32_t* cu_seqlens;
   const int32_t* vt_off;
-  const int32_t* tile_seq;    // query tiles of 128 rows: sequence and first position
-  const int32_t* tile_start;
+  const int32_t* tile_seq;    // work list: sequence, first position of a 128-row query tile, and
+  const int32_t* tile_start;  // first position of a second tile of the same sequence (or -1)
+  const int32_t* tile_start2;
   int n_tiles;
 };
 hipError_t launch_attention_prefill(const AttnPrefillArgs& a, hipStream_t st);
