@@ -215,19 +215,42 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     if (t < nk) issue(t, t, t < nk_full ? 0u : last_mask);
   int stage = 0;                  // stage that holds K-step kt
   int fill = (STAGES - 1) % STAGES;  // stage the next issued K-step goes to
+  // The K loop is rotated by one sub-step: the MFMAs of the last sub-step of K-step kt-1 are issued
+  // after the barrier of K-step kt, from fragments that are already in registers, so the matrix
+  // pipe has work while the first fragments of the new stage travel from LDS.  Sub-step s of a
+  // K-step uses fragment buffer s & 1 (STEPS is even); the buffer of the "previous last sub-step"
+  // starts as zeros, which makes the first iteration's MFMAs add nothing.
+  static_assert(STEPS % 2 == 0, "fragment buffer parity must repeat every K-step");
+  bf16x8_t af[2][MB], bfr[2][NB];
+#pragma unroll
+  for (int j = 0; j < MB; ++j)
+#pragma unroll
+    for (int v = 0; v < 8; ++v) af[1][j][v] = (__bf16)0.f;
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int v = 0; v < 8; ++v) bfr[1][i][v] = (__bf16)0.f;
+  constexpr int READS = MB + NB, MFMAS = MB * NB;
+  constexpr int G = MFMAS >= 4 ? 4 : 1;            // groups per sub-step
+  constexpr int MPG = MFMAS / G;                    // MFMAs per group
+  constexpr int RPG = (READS + G - 1) / G;          // LDS reads per group
+  constexpr int LPG = (LPS + G - 1) / G;            // global loads per group
+  static_assert(MFMAS % G == 0, "MFMAs must split evenly into groups");
   for (int kt = 0; kt < nk; ++kt) {
     // Wait until K-step kt has landed.  Loads return in order, so it is enough to bound how many
     // younger ones may still be in flight.  Every iteration issues exactly LOADS staging loads (masked
     // beyond the last K-step) followed by one prefetch load, so behind K-step kt's loads there are:
     // 2 stages: the previous iteration's prefetch; 3 stages: prefetch, LOADS, prefetch.  The first
     // iterations have fewer; waiting for more than necessary there is harmless.
+    // The fragment reads of the previous K-step must also have completed before any wave refills
+    // the stage they came from (lgkmcnt).
     if (STAGES == 2) {
-      if (kt > 0) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
-      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (kt > 0) asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     } else {
-      if (kt >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS + 2) : "memory");
-      else if (kt == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS) : "memory");
-      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (kt >= 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(LOADS + 2) : "memory");
+      else if (kt == 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(LOADS) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     }
     __builtin_amdgcn_s_barrier();
     // K-step to prefetch during this one (branch-free: beyond the end every lane is masked off)
@@ -238,46 +261,40 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     stage = stage + 1 == STAGES ? 0 : stage + 1;
     fill = fill + 1 == STAGES ? 0 : fill + 1;
     const unsigned char* sb = sa + A_BYTES;
-    // Operand fetches are software pipelined (the fragments of sub-step ks+1 are requested while the
-    // MFMAs of sub-step ks run), and every sub-step is cut into G groups of MFMAs; each group also
-    // carries one slice of the next K-step's global loads and a share of the LDS reads.  Scheduling
-    // barriers pin that order: a wave that issues its global loads in one burst sits in the memory
-    // pipeline's issue queue (measured: about 27 cycles per 1 KB wave-load per CU) while its MFMAs
-    // could run, which serialises loading and matrix work.
-    bf16x8_t af[2][MB], bfr[2][NB];
-    constexpr int READS = MB + NB, MFMAS = MB * NB;
-    constexpr int G = MFMAS >= 4 ? 4 : 1;            // groups per sub-step
-    constexpr int MPG = MFMAS / G;                    // MFMAs per group
-    constexpr int RPG = (READS + G - 1) / G;          // LDS reads per group
-    constexpr int LPG = (LPS + G - 1) / G;            // global loads per group
-    static_assert(MFMAS % G == 0, "MFMAs must split evenly into groups");
+    // Every slot is cut into G groups; a group carries a share of the LDS reads of sub-step `slot`,
+    // one slice of the next K-step's global loads, and MPG MFMAs of the sub-step before it.
+    // Scheduling barriers pin that order: a wave that issues its global loads in one burst sits in
+    // the memory pipeline's issue queue while its MFMAs could run.
     auto load_frag = [&](int ks, int buf, int r) {    // r-th fragment read of sub-step ks
       const int pc = ((2 * ks + frag_hi) ^ ((frag_row >> 1) & 7)) * 16;
       if (r < NB) bfr[buf][r] = *reinterpret_cast<const bf16x8_t*>(sb + b_base + r * 32 * 128 + pc);
       else af[buf][r - NB] = *reinterpret_cast<const bf16x8_t*>(sa + a_base + (r - NB) * 32 * 128 + pc);
     };
-#pragma unroll
-    for (int r = 0; r < READS; ++r) load_frag(0, 0, r);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < STEPS; ++ks) {
+    for (int slot = 0; slot < STEPS; ++slot) {
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        if (ks + 1 < STEPS) {
 #pragma unroll
-          for (int r = g * RPG; r < (g + 1) * RPG && r < READS; ++r) load_frag(ks + 1, (ks + 1) & 1, r);
-        }
+        for (int r = g * RPG; r < (g + 1) * RPG && r < READS; ++r) load_frag(slot, slot & 1, r);
 #pragma unroll
-        for (int q = g * LPG; q < (g + 1) * LPG && q < LPS; ++q) issue_one(ks * LPS + q, tp, fill_base, pmask);
+        for (int q = g * LPG; q < (g + 1) * LPG && q < LPS; ++q) issue_one(slot * LPS + q, tp, fill_base, pmask);
 #pragma unroll
         for (int e = g * MPG; e < (g + 1) * MPG; ++e) {
           const int i = e / MB, j = e % MB;
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][i], af[ks & 1][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[(slot + 1) & 1][i], af[(slot + 1) & 1][j],
+                                                              acc[i][j], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     prefetch(kt + PF_DIST);
+  }
+  // last sub-step of the last K-step
+#pragma unroll
+  for (int e = 0; e < MFMAS; ++e) {
+    const int i = e / MB, j = e % MB;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[(STEPS - 1) & 1][i], af[(STEPS - 1) & 1][j], acc[i][j], 0, 0, 0);
   }
   // masked staging loads and prefetches of the last iterations still target this group's LDS
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -56,6 +56,7 @@ def run_and_compare(pop, cfg, lens, l_keep, tokens, embeds=None, embed_ranges=No
                                embed_ranges=embed_ranges or ())
     worst = {"k": 0.0, "v": 0.0, "logits": 0.0}
     for b, (Kc, Vc, ref) in enumerate(outs):
+        per_layer = []
         for l in range(cfg["n_layers"]):
             k = cache.gather(l, 0, bt[b], lens[b]).float().cpu().numpy()
             v = cache.gather(l, 1, bt[b], lens[b]).float().cpu().numpy()
@@ -63,6 +64,8 @@ def run_and_compare(pop, cfg, lens, l_keep, tokens, embeds=None, embed_ranges=No
             tol = depth_tol(l + 1)
             assert ek <= tol and ev <= tol, f"layer {l + 1} seq {b}: K {ek:.4f} V {ev:.4f} (bound {tol:.4f})"
             worst["k"], worst["v"] = max(worst["k"], ek), max(worst["v"], ev)
+            per_layer.append(f"{l + 1}:{100 * ek:.2f}/{100 * ev:.2f}")
+        print(f"seq {b} K/V rel err in % per layer:", " ".join(per_layer))
         el = rel_err(logits[b], ref)
         assert el <= depth_tol(cfg["n_layers"] + 1), f"logits seq {b}: {el:.4f}"
         worst["logits"] = max(worst["logits"], el)
