@@ -21,6 +21,8 @@
 //                     order key(i) below; no cross-lane data movement is needed for P.
 // Softmax is computed in fp32 with exp2 and running max / sum (online softmax); P is rounded to fp16
 // for the second MFMA, O accumulates in fp32.
+#include <type_traits>
+
 #include "pop_device.h"
 #include "pop_kernels.h"
 
@@ -59,7 +61,11 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
   constexpr int K_BYTES = BKV * K_ROW_BYTES;
   constexpr int V_BYTES = HD * BKV * 2;  // V^T tile: HD rows of 64 keys (128 B)
   constexpr int STAGE = K_BYTES + V_BYTES;
+  constexpr int NST = HD <= 128 ? 3 : 2;   // LDS ring: K and V^T tiles are requested NST-1 iterations ahead
+  constexpr int DPF = NST - 1;
+  constexpr uint32_t kOOB = 0x80000000u;   // pushes a byte offset out of range: the lane stages zeros
   constexpr int K_LOADS = K_BYTES / 1024 / 4, V_LOADS = V_BYTES / 1024 / 4;  // per wave
+  constexpr int LPI = K_LOADS + V_LOADS;   // wave-loads per iteration
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -110,18 +116,30 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
   }
   // The key offset goes into the per-lane offset (not the scalar one) so that rows beyond the end of
   // the buffer are range-checked and read as zero.
-  auto issue = [&](int it, int stage) {
+  // Key tile `it` of this query tile goes to ring slot it % NST.  Tiles beyond the key range are
+  // requested with every lane out of range (zeros are staged), so that each iteration issues the same
+  // number of loads and the vmcnt bookkeeping below stays uniform.
+  auto issue_k1 = [&](int j, int it) {
     const int j0 = j_begin + it * BKV;
-    unsigned char* sk = smem + stage * STAGE;
-    unsigned char* sv = sk + K_BYTES;
+    unsigned char* sk = smem + (it % NST) * STAGE;
+    const uint32_t mask = it < n_kv ? 0u : kOOB;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rK, (lds_ptr_t)(sk + (j * 4 + wave) * 1024), 16,
+                                             (offK[j] + (uint32_t)(j0 * a.ld * 2)) | mask, 0, 0, 0);
+  };
+  auto issue_v1 = [&](int j, int it) {
+    const int j0 = j_begin + it * BKV;
+    unsigned char* sv = smem + (it % NST) * STAGE + K_BYTES;
+    const uint32_t mask = it < n_kv ? 0u : kOOB;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rV, (lds_ptr_t)(sv + (j * 4 + wave) * 1024), 16,
+                                             (offV[j] + (uint32_t)(j0 * 2)) | mask, 0, 0, 0);
+  };
+  auto issue_k = [&](int it) {
 #pragma unroll
-    for (int j = 0; j < K_LOADS; ++j)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rK, (lds_ptr_t)(sk + (j * 4 + wave) * 1024), 16,
-                                               offK[j] + (uint32_t)(j0 * a.ld * 2), 0, 0, 0);
+    for (int j = 0; j < K_LOADS; ++j) issue_k1(j, it);
+  };
+  auto issue_v = [&](int it) {
 #pragma unroll
-    for (int j = 0; j < V_LOADS; ++j)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rV, (lds_ptr_t)(sv + (j * 4 + wave) * 1024), 16,
-                                               offV[j] + (uint32_t)(j0 * 2), 0, 0, 0);
+    for (int j = 0; j < V_LOADS; ++j) issue_v1(j, it);
   };
 
   // ---- Q fragments (B operand: lane = query row, 8 consecutive head-dim values per step)
@@ -146,36 +164,74 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
   const int v_frag = (lane & 31) * 128;
   const int v_sw = ((lane & 31) >> 1) & 7;
 
-  const int wave_last = q0 + wave * 32 + 31;  // last query position this wave owns
+  const int wave_first = q0 + wave * 32;       // first / last query position this wave owns
+  const int wave_last = wave_first + 31;
 
-  if (n_kv > 0) issue(0, 0);
-  for (int it = 0; it < n_kv; ++it) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // The key loop is software pipelined so that the matrix pipe and the vector ALU work at the same
+  // time inside one wave: iteration t runs the softmax of key tile t on the vector ALU and, sprinkled
+  // between its instructions, the MFMAs of O^T += V^T P^T for tile t-1 and of S^T = K Q^T for tile
+  // t+1.  The MFMAs of an iteration are cut into 32 slots, one per exponential.  LDS stage (t+1)&1
+  // holds K of tile t+1 and V^T of tile t-1 during iteration t; K of tile t+2 and V^T of tile t are
+  // requested at its start into the other stage, whose contents were consumed in iteration t-1.
+  constexpr int PVN = 4 * OB;          // MFMAs of one O update, index (kb*2+g)*OB + i
+  constexpr int SN = 2 * KS;           // MFMAs of one S tile, index ks*2 + kb
+  constexpr int NM = PVN + SN;
+  constexpr int DIST = 4;              // fragment reads run this many MFMAs ahead
+  constexpr bool UNROLL2 = HD <= 128;  // head_dim 256 has no registers to spare for the unrolled form
+  // S^T of tile t lives in sbuf[t & 1] and the packed fp16 P^T of tile t in pbuf[t & 1]; the loop is
+  // unrolled by two so that these indices are compile-time constants (no register copies).
+  floatx16_t sbuf[2][2];
+  uint32_t pbuf[2][2][2][4];
+  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+  typedef float float2_t __attribute__((ext_vector_type(2)));
+  const floatx16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  auto body = [&](int t, auto par_c, auto has_pv_c, auto has_s_c) {
+    constexpr int PAR = decltype(par_c)::value;   // t & 1
+    constexpr bool HAS_PV = decltype(has_pv_c)::value, HAS_S = decltype(has_s_c)::value;
+    floatx16_t(&s_cur)[2] = sbuf[PAR];
+    floatx16_t(&s_next)[2] = sbuf[PAR ^ 1];
+    uint32_t(&pw)[2][2][4] = pbuf[PAR];
+    uint32_t(&pw_prev)[2][2][4] = pbuf[PAR ^ 1];
+    constexpr int LO = HAS_PV ? 0 : PVN, HI = HAS_S ? NM : PVN, CNT = HI - LO;
+    constexpr int PRE = CNT >= 8 ? 4 : 0;   // MFMAs issued before the softmax proper
+    // K of tile t+1 and V^T of tile t-1 were requested DPF iterations ago; the loads of the
+    // iterations in between may still be in flight (loads return in order).
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DPF - 1) * LPI) : "memory");
     __builtin_amdgcn_s_barrier();
-    if (it + 1 < n_kv) issue(it + 1, (it + 1) & 1);
-    const int j0 = j_begin + it * BKV;
-    if (j0 > wave_last) continue;  // tile entirely above this wave's diagonal (uniform per wave)
-    if (a.window > 0 && j0 + BKV - 1 < q0 + wave * 32 - a.window + 1) continue;  // entirely outside the window
-    const unsigned char* sk = smem + (it & 1) * STAGE;
-    const unsigned char* sv = sk + K_BYTES;
+    const unsigned char* sk = smem + ((t + 1) % NST) * STAGE;
+    const unsigned char* sv = smem + ((t + NST - 1) % NST) * STAGE + K_BYTES;
+    const int j0 = j_begin + t * BKV;
+    const int tk = t + 1 + DPF, tv = t - 1 + DPF;   // tiles requested during this iteration
 
-    // ---- S^T = K Q^T for 2 blocks of 32 keys
-    floatx16_t s[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int pc = ((2 * ks + h) ^ k_sw) * 16;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const f16x8_t kf = *reinterpret_cast<const f16x8_t*>(sk + k_frag + kb * 32 * K_ROW_BYTES + pc);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[ks], s[kb], 0, 0, 0);
+    f16x8_t fr[NM];
+    auto frag_read = [&](int idx) {
+      if (idx < PVN) {
+        const int kb = idx / (2 * OB), g = (idx / OB) % 2, i = idx % OB;
+        const int pc = ((4 * kb + 2 * g + h) ^ v_sw) * 16;
+        fr[idx] = *reinterpret_cast<const f16x8_t*>(sv + v_frag + i * 32 * 128 + pc);
+      } else {
+        const int j = idx - PVN, ks = j / 2, kb = j % 2;
+        const int pc = ((2 * ks + h) ^ k_sw) * 16;
+        fr[idx] = *reinterpret_cast<const f16x8_t*>(sk + k_frag + kb * 32 * K_ROW_BYTES + pc);
       }
-    }
+    };
+    auto do_mfma = [&](int idx) {
+      if (idx < PVN) {
+        const int kb = idx / (2 * OB), g = (idx / OB) % 2, i = idx % OB;
+        const uint4 w4 = make_uint4(pw_prev[kb][g][0], pw_prev[kb][g][1], pw_prev[kb][g][2], pw_prev[kb][g][3]);
+        o[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[idx], __builtin_bit_cast(f16x8_t, w4), o[i], 0, 0, 0);
+      } else {
+        const int j = idx - PVN, ks = j / 2, kb = j % 2;
+        s_next[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[idx], qf[ks], ks == 0 ? zero16 : s_next[kb], 0, 0, 0);
+      }
+    };
+#pragma unroll
+    for (int idx = LO; idx < LO + DIST && idx < HI; ++idx) frag_read(idx);
+
+    // ---- mask (diagonal / window-edge tiles only), row maximum
     // register v of block kb on lane-half h holds key j0 + kb*32 + 16*(v/8) + 8*h + (v%8)
-    const bool need_mask = (j0 + BKV - 1 > q0 + wave * 32) || (a.window > 0 && j0 < wave_last - a.window + 1);
+    const bool need_mask = (j0 + BKV - 1 > wave_first) || (a.window > 0 && j0 < wave_last - a.window + 1);
     if (need_mask) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
@@ -184,30 +240,61 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
           const int key = j0 + kb * 32 + 16 * (v >> 3) + 8 * h + (v & 7);
           bool ok = key <= qrow;
           if (a.window > 0) ok = ok && (key > qrow - a.window);
-          if (!ok) s[kb][v] = -INFINITY;
+          if (!ok) s_cur[kb][v] = -INFINITY;
         }
     }
     float mx = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_cur[kb][v]);
+    // the other half of the row lives in lane ^ 32; the exchange goes through the LDS crossbar, and
+    // the first MFMAs of the iteration are issued while it is under way
+    const float mx_other = __shfl_xor(mx, 32, 64);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int idx = LO + DIST; idx < LO + DIST + PRE; ++idx)
+      if (idx < HI) frag_read(idx);
+#pragma unroll
+    for (int idx = LO; idx < LO + PRE; ++idx) do_mfma(idx);
+    __builtin_amdgcn_sched_barrier(0);
+    mx = fmaxf(mx, mx_other);
     const float m_new = fmaxf(m_run, mx * scale_log2);
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);  // m_run = -inf -> 0
-    float psum = 0.f;
-    f16x8_t pf[2][2];
+    float psum = 0.f, pv_even = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int slot = 0; slot < 32; ++slot) {
+      const int lo = LO + PRE + slot * (CNT - PRE) / 32, hi = LO + PRE + (slot + 1) * (CNT - PRE) / 32;
 #pragma unroll
-      for (int g = 0; g < 2; ++g)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float pv = __builtin_amdgcn_exp2f(s[kb][g * 8 + e] * scale_log2 - m_use);
-          psum += pv;
-          pf[kb][g][e] = static_cast<_Float16>(pv);
+      for (int idx = lo + DIST; idx < hi + DIST; ++idx)
+        if (idx < HI) frag_read(idx);
+      if (slot % (32 / LPI) == 0) {   // one global load every few slots
+        const int q = slot / (32 / LPI);
+        if (q < K_LOADS) issue_k1(q, tk);
+        else issue_v1(q - K_LOADS, tv);
+      }
+      {
+        const int kb = slot >> 4, v = slot & 15;
+        const float pv = __builtin_amdgcn_exp2f(s_cur[kb][v] * scale_log2 - m_use);
+        psum += pv;
+        if (v & 1) {
+          // 0 <= P <= 1: plain round-to-nearest packing, no saturation needed
+          const float2_t pp = {pv_even, pv};
+          pw[kb][v >> 3][(v & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, half2_t));
+          // keep the softmax arithmetic inside its slot (otherwise it is sunk below the loop's
+          // last branch, behind all MFMAs, and nothing overlaps)
+          asm volatile("" : "+v"(pw[kb][v >> 3][(v & 7) >> 1]), "+v"(psum));
+        } else {
+          pv_even = pv;
+          asm volatile("" : "+v"(pv_even), "+v"(psum));
         }
+      }
+#pragma unroll
+      for (int idx = lo; idx < hi; ++idx) do_mfma(idx);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     l_run = l_run * alpha + psum;
     m_run = m_new;
     if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {  // the running max moved for some row of this wave
@@ -216,18 +303,84 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
     }
-    // ---- O^T += V^T P^T
+    if (!UNROLL2) {   // single-parity form: move the results to where the next iteration expects them
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < 2; ++kb) {
+        if (HAS_S) s_cur[kb] = s_next[kb];
 #pragma unroll
-      for (int g = 0; g < 2; ++g) {
-        const int pc = ((4 * kb + 2 * g + h) ^ v_sw) * 16;
+        for (int g = 0; g < 2; ++g)
 #pragma unroll
-        for (int i = 0; i < OB; ++i) {
-          const f16x8_t vf = *reinterpret_cast<const f16x8_t*>(sv + v_frag + i * 32 * 128 + pc);
-          o[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[kb][g], o[i], 0, 0, 0);
-        }
+          for (int e = 0; e < 4; ++e) pw_prev[kb][g][e] = pw[kb][g][e];
       }
+    }
+  };
+  using std::true_type;
+  using std::false_type;
+
+  if (n_kv > 0) {
+    // prologue: request K of tiles 0..DPF and V^T of tiles 0..DPF-2, then S of tile 0
+    issue_k(0);
+#pragma unroll
+    for (int i = 1; i <= DPF; ++i) issue_k(i);
+#pragma unroll
+    for (int i = 0; i <= DPF - 2; ++i) issue_v(i);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DPF * K_LOADS + (DPF - 1) * V_LOADS) : "memory");
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int pc = ((2 * ks + h) ^ k_sw) * 16;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const f16x8_t kf = *reinterpret_cast<const f16x8_t*>(smem + k_frag + kb * 32 * K_ROW_BYTES + pc);
+        sbuf[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[ks], ks == 0 ? zero16 : sbuf[0][kb], 0, 0, 0);
+      }
+    }
+    // O update of the last tile (all remaining loads are masked ones; drain them before the ring is reused)
+    auto last_pv = [&](auto par_c) {
+      constexpr int PAR = decltype(par_c)::value;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      const unsigned char* sv = smem + ((n_kv - 1) % NST) * STAGE + K_BYTES;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          const int pc = ((4 * kb + 2 * g + h) ^ v_sw) * 16;
+          const uint4 w4 = make_uint4(pbuf[PAR][kb][g][0], pbuf[PAR][kb][g][1], pbuf[PAR][kb][g][2], pbuf[PAR][kb][g][3]);
+#pragma unroll
+          for (int i = 0; i < OB; ++i) {
+            const f16x8_t vf = *reinterpret_cast<const f16x8_t*>(sv + v_frag + i * 32 * 128 + pc);
+            o[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, __builtin_bit_cast(f16x8_t, w4), o[i], 0, 0, 0);
+          }
+        }
+    };
+    typedef std::integral_constant<int, 0> P0;
+    typedef std::integral_constant<int, 1> P1;
+    if (n_kv == 1) {
+      body(0, P0{}, false_type{}, false_type{});
+      if (UNROLL2) last_pv(P0{});
+      else last_pv(P1{});
+    } else if (!UNROLL2) {
+      body(0, P0{}, false_type{}, true_type{});
+      for (int t = 1; t < n_kv - 1; ++t) body(t, P0{}, true_type{}, true_type{});
+      body(n_kv - 1, P0{}, true_type{}, false_type{});
+      last_pv(P1{});
+    } else {
+      body(0, P0{}, false_type{}, true_type{});
+      int t = 1;
+      for (; t + 1 < n_kv - 1; t += 2) {
+        body(t, P1{}, true_type{}, true_type{});
+        body(t + 1, P0{}, true_type{}, true_type{});
+      }
+      if (t < n_kv - 1) {   // one more middle tile, then the last one has even parity
+        body(t, P1{}, true_type{}, true_type{});
+        body(t + 1, P0{}, true_type{}, false_type{});
+        last_pv(P0{});
+      } else {
+        body(t, P1{}, true_type{}, false_type{});
+        last_pv(P1{});
+      }
+    }
   }
 
   // ---- normalise and store: lane owns query row qrow, head-dim i*32 + (v/4)*8 + 4h + v%4
@@ -250,7 +403,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
 
 template <int HD>
 hipError_t launch_hd(const AttnPrefillArgs& a, hipStream_t st) {
-  constexpr int smem = 2 * (BKV * HD * 2 + HD * BKV * 2);
+  constexpr int smem = (HD <= 128 ? 3 : 2) * (BKV * HD * 2 + HD * BKV * 2);
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_prefill_kernel<HD>),
