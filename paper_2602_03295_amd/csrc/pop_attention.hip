@@ -186,6 +186,26 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
   typedef float float2_t __attribute__((ext_vector_type(2)));
   const floatx16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
+  // mask of a diagonal / window-edge tile: register v of block kb on lane-half h holds key
+  // j0 + kb*32 + 16*(v/8) + 8*h + (v%8)
+  auto mask_tile = [&](floatx16_t(&sv_)[2], int j0) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = j0 + kb * 32 + 16 * (v >> 3) + 8 * h + (v & 7);
+        bool ok = key <= qrow;
+        if (a.window > 0) ok = ok && (key > qrow - a.window);
+        if (!ok) sv_[kb][v] = -INFINITY;
+      }
+  };
+  auto tile_needs_mask = [&](int j0) {
+    return (j0 + BKV - 1 > wave_first) || (a.window > 0 && j0 < wave_last - a.window + 1);
+  };
+  // row maximum of the tile the next iteration works on: this lane's half (mx_part) and the other
+  // half of the row (mx_other, lane ^ 32, fetched through the LDS crossbar)
+  float mx_part = -INFINITY, mx_other = -INFINITY;
+
   auto body = [&](int t, auto par_c, auto has_pv_c, auto has_s_c) {
     constexpr int PAR = decltype(par_c)::value;   // t & 1
     constexpr bool HAS_PV = decltype(has_pv_c)::value, HAS_S = decltype(has_s_c)::value;
@@ -193,106 +213,113 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
     floatx16_t(&s_next)[2] = sbuf[PAR ^ 1];
     uint32_t(&pw)[2][2][4] = pbuf[PAR];
     uint32_t(&pw_prev)[2][2][4] = pbuf[PAR ^ 1];
-    constexpr int LO = HAS_PV ? 0 : PVN, HI = HAS_S ? NM : PVN, CNT = HI - LO;
-    constexpr int PRE = CNT >= 8 ? 4 : 0;   // MFMAs issued before the softmax proper
+    // MFMAs of this iteration in issue order: S^T of tile t+1 (slots 0..15), then the O update with
+    // tile t-1 (slots 16..31).  Once S^T is complete its row maximum is formed in the later slots, so
+    // the next iteration starts its exponentials at once.
+    constexpr int NS = HAS_S ? SN : 0, NP = HAS_PV ? PVN : 0, CNT = NS + NP;
     // K of tile t+1 and V^T of tile t-1 were requested DPF iterations ago; the loads of the
     // iterations in between may still be in flight (loads return in order).
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DPF - 1) * LPI) : "memory");
     __builtin_amdgcn_s_barrier();
     const unsigned char* sk = smem + ((t + 1) % NST) * STAGE;
     const unsigned char* sv = smem + ((t + NST - 1) % NST) * STAGE + K_BYTES;
-    const int j0 = j_begin + t * BKV;
     const int tk = t + 1 + DPF, tv = t - 1 + DPF;   // tiles requested during this iteration
 
-    f16x8_t fr[NM];
-    auto frag_read = [&](int idx) {
-      if (idx < PVN) {
+    f16x8_t fr[SN + PVN];
+    auto frag_read = [&](int n) {          // n-th MFMA of this iteration
+      if (n < NS) {
+        const int ks = n / 2, kb = n % 2;
+        const int pc = ((2 * ks + h) ^ k_sw) * 16;
+        fr[n] = *reinterpret_cast<const f16x8_t*>(sk + k_frag + kb * 32 * K_ROW_BYTES + pc);
+      } else {
+        const int idx = n - NS;
         const int kb = idx / (2 * OB), g = (idx / OB) % 2, i = idx % OB;
         const int pc = ((4 * kb + 2 * g + h) ^ v_sw) * 16;
-        fr[idx] = *reinterpret_cast<const f16x8_t*>(sv + v_frag + i * 32 * 128 + pc);
-      } else {
-        const int j = idx - PVN, ks = j / 2, kb = j % 2;
-        const int pc = ((2 * ks + h) ^ k_sw) * 16;
-        fr[idx] = *reinterpret_cast<const f16x8_t*>(sk + k_frag + kb * 32 * K_ROW_BYTES + pc);
+        fr[n] = *reinterpret_cast<const f16x8_t*>(sv + v_frag + i * 32 * 128 + pc);
       }
     };
-    auto do_mfma = [&](int idx) {
-      if (idx < PVN) {
+    auto do_mfma = [&](int n) {
+      if (n < NS) {
+        const int ks = n / 2, kb = n % 2;
+        s_next[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[n], qf[ks], ks == 0 ? zero16 : s_next[kb], 0, 0, 0);
+      } else {
+        const int idx = n - NS;
         const int kb = idx / (2 * OB), g = (idx / OB) % 2, i = idx % OB;
         const uint4 w4 = make_uint4(pw_prev[kb][g][0], pw_prev[kb][g][1], pw_prev[kb][g][2], pw_prev[kb][g][3]);
-        o[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[idx], __builtin_bit_cast(f16x8_t, w4), o[i], 0, 0, 0);
-      } else {
-        const int j = idx - PVN, ks = j / 2, kb = j % 2;
-        s_next[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[idx], qf[ks], ks == 0 ? zero16 : s_next[kb], 0, 0, 0);
+        o[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fr[n], __builtin_bit_cast(f16x8_t, w4), o[i], 0, 0, 0);
       }
     };
+    auto first_of = [](int slot) {   // MFMAs issued before `slot`
+      const int s1 = slot < 16 ? slot : 16, s2 = slot < 16 ? 0 : slot - 16;
+      return s1 * NS / 16 + s2 * NP / 16;
+    };
 #pragma unroll
-    for (int idx = LO; idx < LO + DIST && idx < HI; ++idx) frag_read(idx);
+    for (int n = 0; n < DIST && n < CNT; ++n) frag_read(n);
 
-    // ---- mask (diagonal / window-edge tiles only), row maximum
-    // register v of block kb on lane-half h holds key j0 + kb*32 + 16*(v/8) + 8*h + (v%8)
-    const bool need_mask = (j0 + BKV - 1 > wave_first) || (a.window > 0 && j0 < wave_last - a.window + 1);
-    if (need_mask) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = j0 + kb * 32 + 16 * (v >> 3) + 8 * h + (v & 7);
-          bool ok = key <= qrow;
-          if (a.window > 0) ok = ok && (key > qrow - a.window);
-          if (!ok) s_cur[kb][v] = -INFINITY;
-        }
-    }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_cur[kb][v]);
-    // the other half of the row lives in lane ^ 32; the exchange goes through the LDS crossbar, and
-    // the first MFMAs of the iteration are issued while it is under way
-    const float mx_other = __shfl_xor(mx, 32, 64);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int idx = LO + DIST; idx < LO + DIST + PRE; ++idx)
-      if (idx < HI) frag_read(idx);
-#pragma unroll
-    for (int idx = LO; idx < LO + PRE; ++idx) do_mfma(idx);
-    __builtin_amdgcn_sched_barrier(0);
-    mx = fmaxf(mx, mx_other);
+    const float mx = fmaxf(mx_part, mx_other);
     const float m_new = fmaxf(m_run, mx * scale_log2);
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);  // m_run = -inf -> 0
-    float psum = 0.f, pv_even = 0.f;
+    float psum = 0.f;
+    // the exponentials are skewed over the slots (argument two slots ahead, exp one slot ahead, sum
+    // and packing in the slot itself) so that consecutive vector instructions do not wait on each other
+    float xa[32], ea[32];
+    xa[0] = s_cur[0][0] * scale_log2 - m_use;
+    xa[1] = s_cur[0][1] * scale_log2 - m_use;
+    ea[0] = __builtin_amdgcn_exp2f(xa[0]);
+    float mxa = -INFINITY, mxb = -INFINITY;   // two chains of the next tile's row maximum
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int slot = 0; slot < 32; ++slot) {
-      const int lo = LO + PRE + slot * (CNT - PRE) / 32, hi = LO + PRE + (slot + 1) * (CNT - PRE) / 32;
+      const int lo = first_of(slot), hi = first_of(slot + 1);
 #pragma unroll
-      for (int idx = lo + DIST; idx < hi + DIST; ++idx)
-        if (idx < HI) frag_read(idx);
+      for (int n = lo + DIST; n < hi + DIST; ++n)
+        if (n < CNT) frag_read(n);
       if (slot % (32 / LPI) == 0) {   // one global load every few slots
         const int q = slot / (32 / LPI);
         if (q < K_LOADS) issue_k1(q, tk);
         else issue_v1(q - K_LOADS, tv);
       }
+      if (slot + 2 < 32) {
+        xa[slot + 2] = s_cur[(slot + 2) >> 4][(slot + 2) & 15] * scale_log2 - m_use;
+        asm volatile("" : "+v"(xa[slot + 2]));
+      }
+      if (slot + 1 < 32) {
+        ea[slot + 1] = __builtin_amdgcn_exp2f(xa[slot + 1]);
+        asm volatile("" : "+v"(ea[slot + 1]));
+      }
       {
         const int kb = slot >> 4, v = slot & 15;
-        const float pv = __builtin_amdgcn_exp2f(s_cur[kb][v] * scale_log2 - m_use);
-        psum += pv;
+        psum += ea[slot];
         if (v & 1) {
           // 0 <= P <= 1: plain round-to-nearest packing, no saturation needed
-          const float2_t pp = {pv_even, pv};
+          const float2_t pp = {ea[slot - 1], ea[slot]};
           pw[kb][v >> 3][(v & 7) >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, half2_t));
           // keep the softmax arithmetic inside its slot (otherwise it is sunk below the loop's
           // last branch, behind all MFMAs, and nothing overlaps)
           asm volatile("" : "+v"(pw[kb][v >> 3][(v & 7) >> 1]), "+v"(psum));
         } else {
-          pv_even = pv;
-          asm volatile("" : "+v"(pv_even), "+v"(psum));
+          asm volatile("" : "+v"(psum));
+        }
+      }
+      if (HAS_S) {
+        if (slot == 18) {
+          const int j0n = j_begin + (t + 1) * BKV;
+          if (tile_needs_mask(j0n)) mask_tile(s_next, j0n);
+        }
+        if (slot >= 20 && slot < 28) {   // 4 values per slot, two independent chains
+          const int kb = (slot - 20) >> 2, v0 = ((slot - 20) & 3) * 4;
+          mxa = fmaxf(fmaxf(mxa, s_next[kb][v0]), s_next[kb][v0 + 1]);
+          mxb = fmaxf(fmaxf(mxb, s_next[kb][v0 + 2]), s_next[kb][v0 + 3]);
+          asm volatile("" : "+v"(mxa), "+v"(mxb));
+        }
+        if (slot == 28) {
+          mx_part = fmaxf(mxa, mxb);
+          mx_other = __shfl_xor(mx_part, 32, 64);
         }
       }
 #pragma unroll
-      for (int idx = lo; idx < hi; ++idx) do_mfma(idx);
+      for (int n = lo; n < hi; ++n) do_mfma(n);
       __builtin_amdgcn_sched_barrier(0);
     }
     l_run = l_run * alpha + psum;
@@ -335,6 +362,12 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
         sbuf[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, qf[ks], ks == 0 ? zero16 : sbuf[0][kb], 0, 0, 0);
       }
     }
+    if (tile_needs_mask(j_begin)) mask_tile(sbuf[0], j_begin);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mx_part = fmaxf(mx_part, sbuf[0][kb][v]);
+    mx_other = __shfl_xor(mx_part, 32, 64);
     // O update of the last tile (all remaining loads are masked ones; drain them before the ring is reused)
     auto last_pv = [&](auto par_c) {
       constexpr int PAR = decltype(par_c)::value;
