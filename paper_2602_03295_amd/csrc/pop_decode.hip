@@ -23,11 +23,13 @@ __device__ __forceinline__ void fma8(float (&acc), const uint4& w, const uint4& 
 
 // Each wave owns RW weight rows (for GLU: RW gate rows and the matching RW up rows) and all M batch
 // rows; lanes stride over K in 16-byte chunks; fp32 accumulation, wave reduction at the end.
-template <int M, int EPI>
+// The K loop is unrolled by U with all weight loads of an unrolled step issued before the first
+// multiply: with one row per step a wave has too few bytes in flight to cover HBM latency.
+template <int M, int EPI, int RW, int U>
 __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W,
                                                    void* __restrict__ out, int N, int K, long long ldo, int act) {
-  constexpr int RW = EPI == GEMV_GLU_BF16 ? 2 : 4;
   constexpr int NR = EPI == GEMV_GLU_BF16 ? 2 * RW : RW;  // weight rows streamed per wave
+  typedef __attribute__((__vector_size__(16))) unsigned int u32x4_t;
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int n0 = (blockIdx.x * 4 + wave) * RW;
@@ -45,13 +47,33 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x,
   for (int r = 0; r < NR; ++r)
 #pragma unroll
     for (int m = 0; m < M; ++m) acc[r][m] = 0.f;
-  for (int k = lane * 8; k < K; k += 64 * 8) {
+  int k = lane * 8;
+  for (; k + (U - 1) * 512 < K; k += U * 512) {
+    u32x4_t wl[U][NR];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int r = 0; r < NR; ++r)
+        wl[u][r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wr[r] + k + u * 512));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      uint4 xv[M];
+#pragma unroll
+      for (int m = 0; m < M; ++m) xv[m] = *reinterpret_cast<const uint4*>(x + (size_t)m * K + k + u * 512);
+#pragma unroll
+      for (int r = 0; r < NR; ++r) {
+        const uint4 wv = make_uint4(wl[u][r][0], wl[u][r][1], wl[u][r][2], wl[u][r][3]);
+#pragma unroll
+        for (int m = 0; m < M; ++m) fma8(acc[r][m], wv, xv[m]);
+      }
+    }
+  }
+  for (; k < K; k += 512) {
     uint4 xv[M];
 #pragma unroll
     for (int m = 0; m < M; ++m) xv[m] = *reinterpret_cast<const uint4*>(x + (size_t)m * K + k);
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
-      typedef __attribute__((__vector_size__(16))) unsigned int u32x4_t;
       const u32x4_t wl = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wr[r] + k));
       const uint4 wv = make_uint4(wl[0], wl[1], wl[2], wl[3]);
 #pragma unroll
@@ -79,20 +101,36 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x,
   }
 }
 
+template <int M, int EPI, int RW, int U>
+void launch_gemv_cfg(const bf16_t* x, const bf16_t* W, void* out, int N, int K, long long ldo, int act, hipStream_t st) {
+  const int blocks = (N + 4 * RW - 1) / (4 * RW);
+  hipLaunchKernelGGL((gemv_kernel<M, EPI, RW, U>), dim3(blocks), dim3(256), 0, st, x, W, out, N, K, ldo, act);
+}
+
+// Rows per wave and unroll depth: few batch rows leave registers for deep unrolling; a small N gets
+// two rows per wave so that the launch still has several waves per SIMD.
+template <int M, int EPI>
+void launch_gemv_me(const bf16_t* x, const bf16_t* W, void* out, int N, int K, long long ldo, int act, hipStream_t st) {
+  if (EPI == GEMV_GLU_BF16) {
+    if (M <= 2) launch_gemv_cfg<M, EPI, 2, 4>(x, W, out, N, K, ldo, act, st);
+    else launch_gemv_cfg<M, EPI, 2, 1>(x, W, out, N, K, ldo, act, st);
+  } else if (M <= 2) {
+    if (N <= 8192) launch_gemv_cfg<M, EPI, 2, 4>(x, W, out, N, K, ldo, act, st);
+    else launch_gemv_cfg<M, EPI, 4, 4>(x, W, out, N, K, ldo, act, st);
+  } else if (M <= 4) {
+    launch_gemv_cfg<M, EPI, 4, 2>(x, W, out, N, K, ldo, act, st);
+  } else {
+    launch_gemv_cfg<M, EPI, 4, 1>(x, W, out, N, K, ldo, act, st);
+  }
+}
+
 template <int M>
 void launch_gemv_m(const bf16_t* x, const bf16_t* W, void* out, int N, int K, long long ldo, int epi, int act,
                    hipStream_t st) {
-  const int rw = epi == GEMV_GLU_BF16 ? 2 : 4;
-  const int blocks = (N + 4 * rw - 1) / (4 * rw);
   switch (epi) {
-    case GEMV_STORE_F32:
-      hipLaunchKernelGGL((gemv_kernel<M, GEMV_STORE_F32>), dim3(blocks), dim3(256), 0, st, x, W, out, N, K, ldo, act);
-      break;
-    case GEMV_ADD_F32:
-      hipLaunchKernelGGL((gemv_kernel<M, GEMV_ADD_F32>), dim3(blocks), dim3(256), 0, st, x, W, out, N, K, ldo, act);
-      break;
-    default:
-      hipLaunchKernelGGL((gemv_kernel<M, GEMV_GLU_BF16>), dim3(blocks), dim3(256), 0, st, x, W, out, N, K, ldo, act);
+    case GEMV_STORE_F32: launch_gemv_me<M, GEMV_STORE_F32>(x, W, out, N, K, ldo, act, st); break;
+    case GEMV_ADD_F32: launch_gemv_me<M, GEMV_ADD_F32>(x, W, out, N, K, ldo, act, st); break;
+    default: launch_gemv_me<M, GEMV_GLU_BF16>(x, W, out, N, K, ldo, act, st);
   }
 }
 
@@ -220,15 +258,30 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
       qv[g][4] = bf16lo(w.z); qv[g][5] = bf16hi(w.z); qv[g][6] = bf16lo(w.w); qv[g][7] = bf16hi(w.w);
     }
   }
-  for (int kk = kslot; kk < KCH; kk += KPI) {
-    float s[GMAX];
+  // this thread's K and V chunks of the split are requested up front (one memory round trip)
+  constexpr int NIT = KCH / KPI;
+  uint4 kw[NIT], vw[NIT];
 #pragma unroll
-    for (int g = 0; g < GMAX; ++g) s[g] = 0.f;
+  for (int it = 0; it < NIT; ++it) {
+    const int kk = kslot + it * KPI;
+    kw[it] = make_uint4(0, 0, 0, 0);
+    vw[it] = make_uint4(0, 0, 0, 0);
     if (kk < n_keys) {
       const int key = k_first + kk;
       const int page = bt[key / P];
-      const uint4 w = *reinterpret_cast<const uint4*>(
-          a.k_pool + (((size_t)page * a.n_kv_heads + kvh) * P + (key % P)) * HD + li * 8);
+      const size_t off = (((size_t)page * a.n_kv_heads + kvh) * P + (key % P)) * HD + li * 8;
+      kw[it] = *reinterpret_cast<const uint4*>(a.k_pool + off);
+      vw[it] = *reinterpret_cast<const uint4*>(a.v_pool + off);
+    }
+  }
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int kk = kslot + it * KPI;
+    float s[GMAX];
+#pragma unroll
+    for (int g = 0; g < GMAX; ++g) s[g] = 0.f;
+    {
+      const uint4 w = kw[it];
       const float kf[8] = {bf16lo(w.x), bf16hi(w.x), bf16lo(w.y), bf16hi(w.y),
                            bf16lo(w.z), bf16hi(w.z), bf16lo(w.w), bf16hi(w.w)};
 #pragma unroll
@@ -271,11 +324,11 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
   for (int g = 0; g < GMAX; ++g)
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-  for (int kk = kslot; kk < n_keys; kk += KPI) {
-    const int key = k_first + kk;
-    const int page = bt[key / P];
-    const uint4 w = *reinterpret_cast<const uint4*>(
-        a.v_pool + (((size_t)page * a.n_kv_heads + kvh) * P + (key % P)) * HD + li * 8);
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int kk = kslot + it * KPI;
+    if (kk >= n_keys) continue;
+    const uint4 w = vw[it];
     const float vf[8] = {bf16lo(w.x), bf16hi(w.x), bf16lo(w.y), bf16hi(w.y),
                          bf16lo(w.z), bf16hi(w.z), bf16lo(w.w), bf16hi(w.w)};
 #pragma unroll
@@ -313,29 +366,47 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
   }
 }
 
-// grid (B * Hq), HD threads: merge the splits in index order.
-__global__ void attn_decode_combine_kernel(const float* __restrict__ part, bf16_t* __restrict__ out, int n_splits,
-                                           int hd) {
+// grid (B * Hq), 256 threads: thread (grp, i) sums head-dim element i over the splits s = grp, grp + NG, ..
+// (NG = 256 / hd groups), the groups are then added in index order: a fixed summation order.
+__global__ __launch_bounds__(256) void attn_decode_combine_kernel(const float* __restrict__ part,
+                                                                  bf16_t* __restrict__ out, int n_splits, int hd) {
+  __shared__ float red_m[4];
+  __shared__ float red_num[4][256];
+  __shared__ float red_den[4];
   const size_t bh = blockIdx.x;
-  const int i = threadIdx.x;
-  const float* p = part + bh * n_splits * (hd + 2);
+  const int tid = threadIdx.x;
+  const int stride = hd + 2;
+  const float* p = part + bh * n_splits * stride;
   float mx = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) mx = fmaxf(mx, p[s * (hd + 2) + hd]);
+  for (int s = tid; s < n_splits; s += 256) mx = fmaxf(mx, p[s * stride + hd]);
+  mx = wave_max(mx);
+  if ((tid & 63) == 0) red_m[tid >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+  const int ng = 256 / hd, grp = tid / hd, i = tid % hd;
   float num = 0.f, den = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const float m = p[s * (hd + 2) + hd];
+#pragma unroll 4
+  for (int s = grp; s < n_splits; s += ng) {
+    const float m = p[s * stride + hd];
     const float w = m == -INFINITY ? 0.f : __expf(m - mx);
-    num += w * p[s * (hd + 2) + i];
-    den += w * p[s * (hd + 2) + hd + 1];
+    num += w * p[s * stride + i];
+    den += w * p[s * stride + hd + 1];
   }
-  out[bh * hd + i] = f32_to_bf16(den > 0.f ? num / den : 0.f);
+  red_num[grp][i] = num;
+  if (i == 0) red_den[grp] = den;
+  __syncthreads();
+  if (tid < hd) {
+    float n = red_num[0][tid], d = red_den[0];
+    for (int g = 1; g < ng; ++g) { n += red_num[g][tid]; d += red_den[g]; }
+    out[bh * hd + tid] = f32_to_bf16(d > 0.f ? n / d : 0.f);
+  }
 }
 
 template <int HD>
 void launch_decode_hd(const AttnDecodeArgs& a, hipStream_t st) {
   const float scale = 1.f / sqrtf((float)HD);
   hipLaunchKernelGGL(attn_decode_split_kernel<HD>, dim3(a.n_splits, a.n_kv_heads, a.B), dim3(256), 0, st, a, scale);
-  hipLaunchKernelGGL(attn_decode_combine_kernel, dim3(a.B * a.n_q_heads), dim3(HD), 0, st, a.part, a.out,
+  hipLaunchKernelGGL(attn_decode_combine_kernel, dim3(a.B * a.n_q_heads), dim3(256), 0, st, a.part, a.out,
                      a.n_splits, HD);
 }
 }  // namespace decode_impl
