@@ -188,7 +188,7 @@ def main():
     achieved = gu_flops / (gu_ms * 1e-3) / 1e12 if gu_ms > 0 else 0.0
     # HBM bytes per launch of that kernel, from the committed rocprofv3 --pmc runs (FETCH_SIZE x 2.0 +
     # WRITE_SIZE x 1.0, calibrated with a 1 GiB copy); only valid for the workload they were taken on
-    traffic = (377003 * 2.0 + 66942) * 1024 if (args.config == "llama8b" and n == 2048 and not args.layers) else None
+    traffic = ((295111 + 82025) * 2.0 + (57563 + 8192)) * 1024 if (args.config == "llama8b" and n == 2048 and not args.layers) else None
     breakdown = {k: {"ms_per_launch": v["ms"] / max(v["launches"], 1), "launches_per_step": v["launches"] / args.steps,
                      "ms_per_step": v["ms"] / args.steps} for k, v in steps_t.items() if v["launches"]}
     hd = cfg["head_dim"]
@@ -220,7 +220,7 @@ def main():
                    "l_keep": head, "seq_len": n, "batch": 1},
         "speedup_vs_full_depth": results[head]["speedup_vs_full_depth"],
         "sweep": {str(k): v for k, v in results.items()},
-        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<256,256,2x2 waves,2 stages,GLU> (gate|up projection + GLU)",
+        "roofline": {"bound": "mfma", "kernel": "gate|up projection + GLU: gemm_kernel<256,256,2x2 waves,2 stages,GLU> for the full rounds + gemm_kernel<128,256,...,GLU> for the last half round (both launches timed together)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "traffic_source": "profiles/gate_up_gemm_llama8b_2k_pmc.md" if traffic else None,
