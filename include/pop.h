@@ -21,6 +21,11 @@
  *              pop_free_model / pop_cache_destroy.  HOST pointers are read during the call only.
  *   Layout     All matrices are row-major [out_features, in_features] (the contraction index is
  *              contiguous), elements bf16.  Norm scales are fp32 [d_model].
+ *   Precision  POP_DTYPE_BF16 is the production path (bf16 weights and cache, fp32 accumulation
+ *              and residual stream, MFMA kernels).  POP_DTYPE_F32 runs every step in fp32 with fp32
+ *              weights, embedding rows and cache entries (wherever this header says bf16, read
+ *              fp32); it is a slow checking path for small models: sequences of at most 15000
+ *              tokens (POP_EUNSUPPORTED beyond).
  *   Errors     Every call returns a pop_status.  Argument errors are detected on the host before
  *              anything is enqueued and leave cache contents and lengths unchanged;
  *              pop_last_error() then returns a message (thread-local, static storage).
@@ -51,7 +56,7 @@ typedef enum {
   POP_ENOSPACE = -4,     /* not enough pages, page-table columns, workspace or pool bytes          */
   POP_ESTATE = -5,       /* e.g. decode on a sequence that was never prefilled                     */
   POP_EHIP = -6,         /* a HIP runtime call or launch failed                                    */
-  POP_EUNSUPPORTED = -7  /* valid request the build does not implement (e.g. fp32 weights)         */
+  POP_EUNSUPPORTED = -7  /* valid request the build does not implement (e.g. fp32 beyond 15000 tokens)*/
 } pop_status;
 
 /* Message of the last failing call on this thread ("" if none).  Never freed by the caller. */
@@ -65,7 +70,7 @@ enum { POP_ACT_SILU = 0, POP_ACT_GELU_TANH = 1 };
 /* Model shape (Sec. 2.1: L layers, hidden size d, GQA attention block + gated FFN block). */
 typedef struct {
   int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
-  int32_t dtype;           /* POP_DTYPE_*; only POP_DTYPE_BF16 is implemented                      */
+  int32_t dtype;           /* POP_DTYPE_* (see Precision above)                                    */
   int32_t act;             /* POP_ACT_*: FFN = (act(m Wg^T) * (m Wu^T)) Wd^T                       */
   float rms_eps;           /* LN(x) = x * rsqrt(mean(x^2) + rms_eps) * gamma                       */
   float rope_theta;        /* RoPE base of global-attention layers                                 */
@@ -96,7 +101,7 @@ typedef struct {
  * Host-only, enqueues nothing, allocates no device memory.
  * Errors: POP_EINVAL (NULL, non-positive sizes, Hq % Hkv != 0), POP_ESHAPE (head_dim not in
  * {64,128,256}, d_model or d_ffn not a multiple of 8, page_size not a power of two in 1..256),
- * POP_EALIGN, POP_EUNSUPPORTED (dtype).
+ * POP_EALIGN.
  */
 pop_status pop_load_weights(const pop_config* cfg, const pop_weights* w, pop_model** out);
 void pop_free_model(pop_model* m);

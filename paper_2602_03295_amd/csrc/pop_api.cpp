@@ -51,7 +51,6 @@ pop_status check_config(const pop_config* c) {
                                                  c->n_q_heads, c->n_kv_heads);
   if (c->n_q_heads / c->n_kv_heads > 8) return fail(POP_ESHAPE, "more than 8 query heads per KV head");
   if (c->dtype != POP_DTYPE_BF16 && c->dtype != POP_DTYPE_F32) return fail(POP_EINVAL, "unknown dtype %d", c->dtype);
-  if (c->dtype != POP_DTYPE_BF16) return fail(POP_EUNSUPPORTED, "only bf16 weights are implemented");
   if (c->act != POP_ACT_SILU && c->act != POP_ACT_GELU_TANH) return fail(POP_EINVAL, "unknown activation %d", c->act);
   if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256)
     return fail(POP_ESHAPE, "head_dim %d is not one of 64, 128, 256", c->head_dim);
@@ -119,7 +118,7 @@ struct StepTimer {
 
 struct pop_cache {
   pop_config cfg;
-  bf16_t* pool;
+  bf16_t* pool;                      // fp32 configs: the same bytes viewed as float (see k_pool_f32)
   size_t bytes;
   int n_pages, max_seqs, max_pages;
   int n_seqs;                        // live sequences
@@ -133,6 +132,8 @@ struct pop_cache {
   }
   bf16_t* k_pool(int l0) const { return pool + (size_t)l0 * layer_stride(); }
   bf16_t* v_pool(int l0) const { return k_pool(l0) + pool_stride(); }
+  float* k_pool_f32(int l0) const { return reinterpret_cast<float*>(pool) + (size_t)l0 * layer_stride(); }
+  float* v_pool_f32(int l0) const { return k_pool_f32(l0) + pool_stride(); }
 };
 
 // ----------------------------------------------------------------------------------------- workspace
@@ -332,6 +333,211 @@ pop_status lm_head(const LayerCtx& x, int B, float* dev_logits) {
   return POP_OK;
 }
 
+// ------------------------------------------------------------------------------- fp32 instantiation
+struct WorkspaceF32 {
+  size_t meta_bytes;
+  size_t o_tokens, o_row_src, o_pos, o_slot, o_row_seq, o_bnd_row, o_bnd_pos, o_bnd_slot, o_bnd_seq, o_bt;
+  size_t o_h, o_a, o_qkv, o_attn, o_u, o_xb, o_ab, o_qkvb, o_attnb, o_ub;
+  size_t total;
+};
+
+WorkspaceF32 carve_f32(const pop_config& c, int T, int B, int maxp) {
+  WorkspaceF32 w{};
+  const size_t d = c.d_model, hd = c.head_dim, f = c.d_ffn;
+  const size_t Dq = (size_t)c.n_q_heads * hd, Dkv = (size_t)c.n_kv_heads * hd, Dqkv = Dq + 2 * Dkv;
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = o;
+    o += round_up(bytes, 256);
+    return at;
+  };
+  w.o_tokens = take(4 * (size_t)T);
+  w.o_row_src = take(4 * (size_t)T);
+  w.o_pos = take(4 * (size_t)T);
+  w.o_slot = take(4 * (size_t)T);
+  w.o_row_seq = take(4 * (size_t)T);
+  w.o_bnd_row = take(4 * (size_t)B);
+  w.o_bnd_pos = take(4 * (size_t)B);
+  w.o_bnd_slot = take(4 * (size_t)B);
+  w.o_bnd_seq = take(4 * (size_t)B);
+  w.o_bt = take(4 * (size_t)B * maxp);
+  w.meta_bytes = o;
+  w.o_h = take(4 * (size_t)T * d);
+  w.o_a = take(4 * (size_t)T * d);
+  w.o_qkv = take(4 * (size_t)T * Dqkv);
+  w.o_attn = take(4 * (size_t)T * Dq);
+  w.o_u = take(4 * (size_t)T * f);
+  w.o_xb = take(4 * (size_t)B * d);
+  w.o_ab = take(4 * (size_t)B * d);
+  w.o_qkvb = take(4 * (size_t)B * Dqkv);
+  w.o_attnb = take(4 * (size_t)B * Dq);
+  w.o_ub = take(4 * (size_t)B * f);
+  w.total = o;
+  return w;
+}
+
+struct CtxF32 {
+  const pop_model* m;
+  pop_cache* c;
+  void* ws;
+  const WorkspaceF32* w;
+  hipStream_t st;
+};
+
+// One layer of Sec. 2.1 for `rows` rows of x (fp32 [rows, d], updated in place); a / qkv / attn / u are
+// scratch of matching height.  row_seq / pos / slot are device arrays [rows].
+pop_status layer_f32(const CtxF32& x, int l /*1-based*/, int rows, float* xh, float* a, float* qkv, float* attn, float* u,
+                     const int32_t* row_seq, const int32_t* pos, const int32_t* slot, int max_len) {
+  const pop_config& c = x.m->cfg;
+  const pop_layer_weights& lw = x.m->layers[l - 1];
+  const int d = c.d_model, f = c.d_ffn, hd = c.head_dim, Dq = x.m->Dq, Dkv = x.m->Dkv, Dqkv = x.m->Dqkv;
+  const bool glob = layer_is_global(c, l);
+  namespace F = pop::f32;
+  F::launch_rmsnorm(xh, (const float*)lw.norm_in, a, nullptr, rows, d, c.rms_eps, x.st);
+  F::launch_gemm(a, d, (const float*)lw.wqkv, d, qkv, Dqkv, rows, Dqkv, d, F::EPI_STORE, 0, x.st);
+  F::launch_rope_write(qkv, Dqkv, 0, Dq, Dq + Dkv, c.n_q_heads, c.n_kv_heads, hd, pos, slot,
+                       glob ? (double)c.rope_theta : (double)c.rope_theta_local, x.c->k_pool_f32(l - 1),
+                       x.c->v_pool_f32(l - 1), c.page_size, rows, x.st);
+  hipError_t e = F::launch_attention(qkv, Dqkv, 0, attn, row_seq, pos, x.c->k_pool_f32(l - 1), x.c->v_pool_f32(l - 1),
+                                     at<int32_t>(x.ws, x.w->o_bt), x.c->max_pages, c.page_size,
+                                     glob ? 0 : c.sliding_window, rows, c.n_q_heads, c.n_kv_heads, hd, max_len, x.st);
+  if (e != hipSuccess) return fail(POP_EHIP, "fp32 attention launch failed: %s", hipGetErrorString(e));
+  F::launch_gemm(attn, Dq, (const float*)lw.wo, Dq, xh, d, rows, d, Dq, F::EPI_ADD, 0, x.st);
+  F::launch_rmsnorm(xh, (const float*)lw.norm_post, a, nullptr, rows, d, c.rms_eps, x.st);
+  F::launch_gemm(a, d, (const float*)lw.w_gate_up, d, u, f, rows, f, d, F::EPI_GLU, c.act, x.st);
+  F::launch_gemm(u, f, (const float*)lw.w_down, f, xh, d, rows, d, f, F::EPI_ADD, 0, x.st);
+  POP_HIP(hipGetLastError());
+  return POP_OK;
+}
+
+pop_status lm_head_f32(const CtxF32& x, int B, float* dev_logits) {
+  const pop_config& c = x.m->cfg;
+  namespace F = pop::f32;
+  float* xb = at<float>(x.ws, x.w->o_xb);
+  float* ab = at<float>(x.ws, x.w->o_ab);
+  F::launch_rmsnorm(xb, (const float*)x.m->w.final_norm, ab, nullptr, B, c.d_model, c.rms_eps, x.st);
+  F::launch_gemm(ab, c.d_model, (const float*)x.m->w.lm_head, c.d_model, dev_logits, c.vocab, B, c.vocab, c.d_model,
+                 F::EPI_STORE, 0, x.st);
+  POP_HIP(hipGetLastError());
+  return POP_OK;
+}
+
+// pop_prefill for an fp32 model; arguments are already validated (slots, row_src computed by the caller)
+pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, float* dev_logits, void* ws,
+                       size_t workspace_bytes, hipStream_t st, const std::vector<int32_t>& slots,
+                       const std::vector<int32_t>& row_src) {
+  const pop_config& cfg = m->cfg;
+  const int B = a->n_seqs, maxp = c->max_pages, T = a->cu_seqlens[B];
+  const WorkspaceF32 w = carve_f32(cfg, T, B, maxp);
+  if (workspace_bytes < w.total)
+    return fail(POP_ENOSPACE, "workspace has %zu bytes, %zu needed for %d tokens in %d sequences", workspace_bytes,
+                w.total, T, B);
+  std::vector<unsigned char> meta(w.meta_bytes, 0);
+  auto mi = [&](size_t off) { return reinterpret_cast<int32_t*>(meta.data() + off); };
+  std::copy(a->tokens, a->tokens + T, mi(w.o_tokens));
+  std::copy(row_src.begin(), row_src.end(), mi(w.o_row_src));
+  std::copy(slots.begin(), slots.end(), mi(w.o_slot));
+  int max_len = 0;
+  for (int b = 0; b < B; ++b) {
+    const int s0 = a->cu_seqlens[b], len = a->cu_seqlens[b + 1] - s0;
+    max_len = std::max(max_len, len);
+    for (int t = 0; t < len; ++t) {
+      mi(w.o_pos)[s0 + t] = t;
+      mi(w.o_row_seq)[s0 + t] = b;
+    }
+    mi(w.o_bnd_row)[b] = s0 + len - 1;
+    mi(w.o_bnd_pos)[b] = len - 1;
+    mi(w.o_bnd_slot)[b] = slots[s0 + len - 1];
+    mi(w.o_bnd_seq)[b] = b;
+    std::copy(a->block_table + (size_t)b * maxp, a->block_table + (size_t)(b + 1) * maxp, mi(w.o_bt) + (size_t)b * maxp);
+  }
+  if (max_len > pop::f32::kMaxContext)
+    return fail(POP_EUNSUPPORTED, "the fp32 path holds one row of scores in LDS: sequences up to %d tokens",
+                pop::f32::kMaxContext);
+  POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
+  c->n_seqs = B;
+  std::fill(c->seq_lens.begin(), c->seq_lens.end(), 0);
+  std::fill(c->block_table.begin(), c->block_table.end(), -1);
+  for (int b = 0; b < B; ++b) {
+    c->seq_lens[b] = a->cu_seqlens[b + 1] - a->cu_seqlens[b];
+    std::copy(a->block_table + (size_t)b * maxp, a->block_table + (size_t)(b + 1) * maxp,
+              c->block_table.begin() + (size_t)b * maxp);
+  }
+  namespace F = pop::f32;
+  const int d = cfg.d_model, hd = cfg.head_dim, Dq = m->Dq, Dkv = m->Dkv;
+  float* h = at<float>(ws, w.o_h);
+  float* abuf = at<float>(ws, w.o_a);
+  float* qkv = at<float>(ws, w.o_qkv);
+  float* attn = at<float>(ws, w.o_attn);
+  float* u = at<float>(ws, w.o_u);
+  const int32_t* d_pos = at<int32_t>(ws, w.o_pos);
+  const int32_t* d_slot = at<int32_t>(ws, w.o_slot);
+  CtxF32 x{m, c, ws, &w, st};
+  F::launch_embed((const float*)m->w.embed, at<int32_t>(ws, w.o_tokens),
+                  a->n_ranges > 0 ? at<int32_t>(ws, w.o_row_src) : nullptr, (const float*)a->embeds, h, T, d, st);
+  // kept layers 1..l_keep over all rows (Sec. 2.1)
+  for (int l = 1; l <= a->l_keep; ++l)
+    if (pop_status s = layer_f32(x, l, T, h, abuf, qkv, attn, u, at<int32_t>(ws, w.o_row_seq), d_pos, d_slot, max_len))
+      return s;
+  // pruned layers: K/V from the layer's own norm scale, W^K, W^V and RoPE; h is not modified (Sec. 3.3)
+  for (int l = a->l_keep + 1; l <= cfg.n_layers; ++l) {
+    const pop_layer_weights& lw = m->layers[l - 1];
+    F::launch_rmsnorm(h, (const float*)lw.norm_in, abuf, nullptr, T, d, cfg.rms_eps, st);
+    F::launch_gemm(abuf, d, (const float*)lw.wqkv + (size_t)Dq * d, d, qkv, 2 * Dkv, T, 2 * Dkv, d, F::EPI_STORE, 0, st);
+    F::launch_rope_write(qkv, 2 * Dkv, -1, 0, Dkv, cfg.n_q_heads, cfg.n_kv_heads, hd, d_pos, d_slot,
+                         layer_is_global(cfg, l) ? (double)cfg.rope_theta : (double)cfg.rope_theta_local,
+                         c->k_pool_f32(l - 1), c->v_pool_f32(l - 1), cfg.page_size, T, st);
+  }
+  POP_HIP(hipGetLastError());
+  // boundary rows at full depth (Sec. 3.3, boundary handling)
+  if (a->mode == POP_MODE_POP) {
+    float* xb = at<float>(ws, w.o_xb);
+    pop::launch_gather_rows(h, at<int32_t>(ws, w.o_bnd_row), xb, B, d, st);
+    for (int l = a->l_keep + 1; l <= cfg.n_layers; ++l)
+      if (pop_status s = layer_f32(x, l, B, xb, at<float>(ws, w.o_ab), at<float>(ws, w.o_qkvb), at<float>(ws, w.o_attnb),
+                                   at<float>(ws, w.o_ub), at<int32_t>(ws, w.o_bnd_seq), at<int32_t>(ws, w.o_bnd_pos),
+                                   at<int32_t>(ws, w.o_bnd_slot), max_len))
+        return s;
+    if (pop_status s = lm_head_f32(x, B, dev_logits)) return s;
+  }
+  return POP_OK;
+}
+
+pop_status decode_step_f32(pop_model* m, pop_cache* c, const int32_t* host_tokens, int B, float* dev_logits, void* ws,
+                           size_t workspace_bytes, hipStream_t st) {
+  const pop_config& cfg = m->cfg;
+  const int P = cfg.page_size, maxp = c->max_pages;
+  const WorkspaceF32 w = carve_f32(cfg, B, B, maxp);
+  if (workspace_bytes < w.total) return fail(POP_ENOSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  std::vector<unsigned char> meta(w.meta_bytes, 0);
+  auto mi = [&](size_t off) { return reinterpret_cast<int32_t*>(meta.data() + off); };
+  int max_len = 0;
+  for (int b = 0; b < B; ++b) {
+    const int pos = c->seq_lens[b];
+    mi(w.o_tokens)[b] = host_tokens[b];
+    mi(w.o_bnd_pos)[b] = pos;
+    mi(w.o_bnd_slot)[b] = c->block_table[(size_t)b * maxp + pos / P] * P + pos % P;
+    mi(w.o_bnd_seq)[b] = b;
+    max_len = std::max(max_len, pos + 1);
+    std::copy(c->block_table.begin() + (size_t)b * maxp, c->block_table.begin() + (size_t)(b + 1) * maxp,
+              mi(w.o_bt) + (size_t)b * maxp);
+  }
+  if (max_len > pop::f32::kMaxContext)
+    return fail(POP_EUNSUPPORTED, "the fp32 path holds one row of scores in LDS: sequences up to %d tokens",
+                pop::f32::kMaxContext);
+  POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
+  for (int b = 0; b < B; ++b) c->seq_lens[b] += 1;
+  CtxF32 x{m, c, ws, &w, st};
+  float* xb = at<float>(ws, w.o_xb);
+  pop::f32::launch_embed((const float*)m->w.embed, at<int32_t>(ws, w.o_tokens), nullptr, nullptr, xb, B, cfg.d_model, st);
+  for (int l = 1; l <= cfg.n_layers; ++l)
+    if (pop_status s = layer_f32(x, l, B, xb, at<float>(ws, w.o_ab), at<float>(ws, w.o_qkvb), at<float>(ws, w.o_attnb),
+                                 at<float>(ws, w.o_ub), at<int32_t>(ws, w.o_bnd_seq), at<int32_t>(ws, w.o_bnd_pos),
+                                 at<int32_t>(ws, w.o_bnd_slot), max_len))
+      return s;
+  return lm_head_f32(x, B, dev_logits);
+}
+
 pop_status gemm_or_fail(const pop::GemmArgs& g, hipStream_t st, const char* what) {
   hipError_t e = pop::launch_gemm(g, st);
   if (e != hipSuccess) return fail(POP_EHIP, "%s GEMM launch failed: %s", what, hipGetErrorString(e));
@@ -407,11 +613,13 @@ pop_status pop_timing_read(pop_model* m, float* ms_out, int32_t* launches_out) {
 size_t pop_cache_bytes(const pop_config* cfg, int32_t n_pages) {
   if (!cfg || n_pages < 1 || cfg->n_layers < 1 || cfg->n_kv_heads < 1 || cfg->head_dim < 1 || cfg->page_size < 1)
     return 0;
-  return (size_t)cfg->n_layers * 2 * n_pages * cfg->n_kv_heads * cfg->page_size * cfg->head_dim * sizeof(bf16_t);
+  const size_t esz = cfg->dtype == POP_DTYPE_F32 ? sizeof(float) : sizeof(bf16_t);
+  return (size_t)cfg->n_layers * 2 * n_pages * cfg->n_kv_heads * cfg->page_size * cfg->head_dim * esz;
 }
 
 size_t pop_workspace_bytes(const pop_config* cfg, int32_t max_tokens, int32_t max_seqs, int32_t max_pages_per_seq) {
   if (check_config(cfg) != POP_OK || max_tokens < 1 || max_seqs < 1 || max_pages_per_seq < 1) return 0;
+  if (cfg->dtype == POP_DTYPE_F32) return carve_f32(*cfg, max_tokens, max_seqs, max_pages_per_seq).total;
   return carve(*cfg, max_tokens, max_seqs, max_pages_per_seq).total;
 }
 
@@ -507,6 +715,9 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       }
     }
   }
+  if (cfg.dtype == POP_DTYPE_F32)
+    return prefill_f32(m, c, a, dev_logits, dev_workspace, workspace_bytes, reinterpret_cast<hipStream_t>(stream), slots,
+                       row_src);
   const Workspace w = carve(cfg, T, B, maxp);
   if (workspace_bytes < w.total)
     return fail(POP_ENOSPACE, "workspace has %zu bytes, %zu needed for %d tokens in %d sequences", workspace_bytes,
@@ -724,6 +935,16 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
   if (!dev_workspace) return fail(POP_EINVAL, "dev_workspace is NULL");
   if (reinterpret_cast<uintptr_t>(dev_workspace) & 255) return fail(POP_EALIGN, "dev_workspace not 256-byte aligned");
   const int B = n_seqs, P = cfg.page_size, maxp = c->max_pages;
+  for (int b = 0; b < B; ++b) {
+    if (host_tokens[b] < 0 || host_tokens[b] >= cfg.vocab)
+      return fail(POP_EINVAL, "token %d of sequence %d is outside [0, %d)", host_tokens[b], b, cfg.vocab);
+    const int pos = c->seq_lens[b];
+    if (pos / P >= maxp || c->block_table[(size_t)b * maxp + pos / P] < 0)
+      return fail(POP_ENOSPACE, "sequence %d has no page for position %d", b, pos);
+  }
+  if (cfg.dtype == POP_DTYPE_F32)
+    return decode_step_f32(m, c, host_tokens, B, dev_logits, dev_workspace, workspace_bytes,
+                           reinterpret_cast<hipStream_t>(stream));
   const Workspace w = carve(cfg, B, B, maxp);
   if (workspace_bytes < w.total) return fail(POP_ENOSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
   std::vector<unsigned char> meta(w.meta_bytes, 0);

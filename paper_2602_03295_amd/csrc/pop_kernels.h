@@ -142,6 +142,31 @@ struct AttnDecodeArgs {
 };
 void launch_attention_decode(const AttnDecodeArgs& a, hipStream_t st);
 
+// ---------------------------------------------------------------------------------------------
+// fp32 instantiation of every step (pop_f32.hip): fp32 weights, activations and cache entries
+// ---------------------------------------------------------------------------------------------
+namespace f32 {
+constexpr int kMaxContext = 15000;  // scores of one query row are held in LDS
+enum { EPI_STORE = 0, EPI_ADD = 1, EPI_GLU = 2 };
+void launch_embed(const float* table, const int32_t* tokens, const int32_t* row_src, const float* embeds, float* h,
+                  int T, int d, hipStream_t st);
+// out[t,:] = LN(x[row_idx ? row_idx[t] : t, :])
+void launch_rmsnorm(const float* x, const float* gamma, float* out, const int32_t* row_idx, int rows, int d, float eps,
+                    hipStream_t st);
+// out (op)= A[M,K] W[N,K]^T ; EPI_GLU: W is [2N,K] (gate rows, then up rows)
+void launch_gemm(const float* A, int lda, const float* W, int ldw, float* out, int ldc, int M, int N, int K, int epi,
+                 int act, hipStream_t st);
+// rotate q (unless q_col < 0) and k of `rows` rows in place, append k, v at slot[row]
+void launch_rope_write(float* qkv, int ld, int q_col, int k_col, int v_col, int n_q_heads, int n_kv_heads, int hd,
+                       const int32_t* pos, const int32_t* slot, double theta, float* k_pool, float* v_pool, int P,
+                       int rows, hipStream_t st);
+// out[r, :] = Attn of row r (sequence row_seq[r], position row_pos[r]) over its cache entries
+hipError_t launch_attention(const float* q, int ldq, int q_col, float* out, const int32_t* row_seq,
+                            const int32_t* row_pos, const float* k_pool, const float* v_pool,
+                            const int32_t* block_table, int max_pages, int P, int window, int rows, int n_q_heads,
+                            int n_kv_heads, int hd, int max_len, hipStream_t st);
+}  // namespace f32
+
 // gather fp32 rows: dst[i,:] = src[idx[i],:]
 void launch_gather_rows(const float* src, const int32_t* idx, float* dst, int rows, int d, hipStream_t st);
 

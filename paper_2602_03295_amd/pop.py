@@ -24,6 +24,7 @@ POP_OK = 0
 STATUS_NAMES = {0: "POP_OK", -1: "POP_EINVAL", -2: "POP_ESHAPE", -3: "POP_EALIGN", -4: "POP_ENOSPACE",
                 -5: "POP_ESTATE", -6: "POP_EHIP", -7: "POP_EUNSUPPORTED"}
 MODE_POP, MODE_BODY_ONLY = 0, 1
+DTYPE_F32, DTYPE_BF16 = 0, 1
 EPI_STORE_BF16, EPI_ADD_F32, EPI_GLU_BF16, EPI_STORE_F32 = 0, 1, 2, 3
 
 
@@ -153,9 +154,10 @@ def pop_slot_map(cu_seqlens, block_table, page_size: int, n_pages: int) -> np.nd
 
 def upload_weights(cfg: Dict, W: Dict, device="cuda") -> Dict:
     """Host weights (separate wq/wk/wv and w_gate/w_up, fp32 holding bf16 values) -> the device
-    layout of pop.h (wqkv rows q|k|v, w_gate_up rows gate|up, bf16; norm scales fp32)."""
-    bf = lambda t: t.to(torch.bfloat16).to(device).contiguous()
+    layout of pop.h (wqkv rows q|k|v, w_gate_up rows gate|up, bf16; norm scales fp32).  For an fp32
+    config the matrices stay fp32."""
     f32 = lambda t: t.to(torch.float32).to(device).contiguous()
+    bf = f32 if cfg["dtype"] == DTYPE_F32 else (lambda t: t.to(torch.bfloat16).to(device).contiguous())
     out = {"embed": bf(W["embed"]), "final_norm": f32(W["final_norm"]), "lm_head": bf(W["lm_head"]), "layers": []}
     for lw in W["layers"]:
         out["layers"].append({
@@ -203,7 +205,10 @@ class Cache:
         nbytes = lib.pop_cache_bytes(C.byref(self.c_cfg), n_pages)
         if nbytes == 0:
             raise PopError(-1, "pop_cache_bytes returned 0 (bad config or page count)")
-        self.pool = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=device)
+        if cfg["dtype"] == DTYPE_F32:
+            self.pool = torch.empty(nbytes // 4, dtype=torch.float32, device=device)
+        else:
+            self.pool = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=device)
         if fill is not None:
             self.pool.fill_(fill)
         self.handle = C.c_void_p()

@@ -1,0 +1,99 @@
+"""The fp32 instantiation of the path (configs[0] is stated in fp32): same schedule, every step in
+fp32 with fp32 weights and cache, compared with the fp64 oracle at max relative error 1e-4 per
+tensor.  At this tolerance a wrong index, a dropped term or a misplaced scale cannot hide behind
+bf16 rounding."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pop_oracle as O
+from paper_2602_03295_amd import synth
+from tests.gpu_util import GpuRun, compare_with_oracle, rel_err
+
+pytestmark = pytest.mark.gpu
+TOL32 = 1e-5   # the stated bar for this config is 1e-4; measured errors are about 1e-6
+
+
+@pytest.fixture(scope="module")
+def pop():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2602_03295_amd import pop as p
+    return p
+
+
+@pytest.mark.parametrize("l_keep", [5, 0, 8, 1])
+def test_config0_fp32(pop, l_keep):
+    """configs[0] as stated: 8 layers, d 256, 4/2 heads of 64, FFN 688, vocab 1024, fp32 N(0, 0.02)
+    weights (seed 1234), one prompt of 128 uniform-random tokens (seed 1), L_keep = 5 (and the
+    degenerate depths)."""
+    cfg = synth.get_config("tiny")
+    assert cfg["dtype"] == synth.DTYPE_F32
+    W = synth.make_weights(cfg, seed=1234)
+    tokens = synth.make_tokens(cfg["vocab"], 128, seed=1)
+    run = GpuRun(pop, cfg, W, [128], poison=float("nan"))
+    logits = run.prefill(tokens, l_keep)
+    worst, _ = compare_with_oracle(run, W, tokens, l_keep, logits, tol=TOL32)
+    print("config 0 fp32, l_keep", l_keep, worst)
+
+
+def test_fp32_ragged_batch_shuffled_pages_norm_scales(pop):
+    cfg = synth.get_config("tiny", n_layers=4)
+    W = synth.make_weights(cfg, seed=7)
+    synth.randomize_norms(W, cfg)
+    lens = [129, 1, 64, 200, 2]
+    tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=3)
+    run = GpuRun(pop, cfg, W, lens, shuffle_seed=4, poison=float("nan"))
+    logits = run.prefill(tokens, 2)
+    worst, _ = compare_with_oracle(run, W, tokens, 2, logits, tol=TOL32)
+    print("fp32 ragged", worst)
+
+
+def test_fp32_window_gelu_local_theta(pop):
+    """Sliding-window local layers with their own RoPE base, every 3rd layer global, tanh-GELU."""
+    cfg = synth.get_config("tiny", n_layers=6, sliding_window=24, global_every=3, rope_theta_local=100.0,
+                           act=synth.ACT_GELU_TANH, rms_eps=1e-6)
+    W = synth.make_weights(cfg, seed=11)
+    synth.randomize_norms(W, cfg)
+    lens = [90, 37]
+    tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=5)
+    run = GpuRun(pop, cfg, W, lens, poison=float("nan"))
+    logits = run.prefill(tokens, 4)
+    worst, _ = compare_with_oracle(run, W, tokens, 4, logits, tol=TOL32)
+    print("fp32 window/gelu", worst)
+
+
+def test_fp32_body_only_then_decode_equals_pop_mode(pop):
+    """Boundary token = body prefill + one full-depth decode step (Sec. 3.3, boundary handling)."""
+    cfg = synth.get_config("tiny", n_layers=5)
+    W = synth.make_weights(cfg, seed=13)
+    lens = [50, 17]
+    tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=6)
+    fused = GpuRun(pop, cfg, W, lens)
+    l_fused = fused.prefill(tokens, 3)
+    cu = fused.cu
+    body_lens = [n - 1 for n in lens]
+    body_tokens = np.concatenate([tokens[cu[b]:cu[b + 1] - 1] for b in range(len(lens))])
+    last = np.array([tokens[cu[b + 1] - 1] for b in range(len(lens))], dtype=np.int32)
+    split = GpuRun(pop, cfg, W, body_lens, reserve_pages=1)
+    split.prefill(body_tokens, 3, mode=pop.MODE_BODY_ONLY)
+    l_split = split.decode(last)
+    assert rel_err(l_split, l_fused.astype(np.float64)) <= TOL32
+    for l in range(cfg["n_layers"]):
+        for b in range(len(lens)):
+            k1, v1 = fused.kv(l, b)
+            k2, v2 = split.kv(l, b, length=lens[b])
+            assert rel_err(k2, k1.astype(np.float64)) <= TOL32 and rel_err(v2, v1.astype(np.float64)) <= TOL32
+
+
+def test_fp32_visual_rows_override(pop):
+    cfg = synth.get_config("tiny", n_layers=3)
+    W = synth.make_weights(cfg, seed=17)
+    n = 96
+    tokens = synth.make_tokens(cfg["vocab"], n, seed=8)
+    emb = synth.make_visual_embeds(40, cfg["d_model"], seed=2, as_bf16=False) * 0.05
+    ranges = [(0, 10, 40)]
+    run = GpuRun(pop, cfg, W, [n])
+    logits = run.prefill(tokens, 2, embeds=emb.to(torch.float32).cuda(), embed_ranges=ranges)
+    worst, _ = compare_with_oracle(run, W, tokens, 2, logits, embeds=emb.numpy(), embed_ranges=ranges, tol=TOL32)
+    print("fp32 visual", worst)

@@ -102,7 +102,7 @@ def test_slot_map_errors():
 
 @pytest.mark.parametrize("kw,status", [
     ({"n_layers": 0}, -1), ({"n_q_heads": 3}, -1), ({"head_dim": 48}, -2), ({"d_model": 260}, -2),
-    ({"page_size": 12}, -2), ({"dtype": synth.DTYPE_F32}, -7), ({"act": 5}, -1), ({"rope_theta": 0.0}, -1),
+    ({"page_size": 12}, -2), ({"dtype": 7}, -1), ({"act": 5}, -1), ({"rope_theta": 0.0}, -1),
     ({"n_q_heads": 32, "n_kv_heads": 2}, -2),
 ])
 def test_load_weights_rejects_bad_configs(kw, status):
