@@ -244,6 +244,30 @@ def pop_prefill(cfg: Dict, W: Dict, tokens: np.ndarray, l_keep: int, dtype=np.fl
     return Kc, Vc, logits
 
 
+def greedy_generate(cfg: Dict, W: Dict, tokens: np.ndarray, l_keep: int, n_new: int, eos: int = -1,
+                    dtype=np.float64, forced: Optional[Sequence[int]] = None):
+    """POP prefill of the prompt, then n_new greedy tokens with the full model (Sec. 3.2: prefill
+    followed by the decode loop; Sec. 3.3: the decode stage keeps every layer).  Token s is the
+    argmax (lowest index on ties) of the logits of step s; step 0 is the boundary token's.  Once a
+    sequence has produced `eos` every later token is `eos`.  With `forced`, token s fed to step
+    s+1 is forced[s] instead of the argmax (the argmax is still what is returned).
+    Returns (tokens [n_new] int64, logits [n_new, V], Kc, Vc)."""
+    Kc, Vc, logits = pop_prefill(cfg, W, tokens, l_keep, dtype)
+    out, all_logits = [], []
+    done = False
+    for s in range(n_new):
+        tok = eos if done else int(np.argmax(logits))
+        out.append(tok)
+        all_logits.append(logits)
+        if tok == eos and eos >= 0:
+            done = True
+        if s + 1 < n_new:
+            feed = tok if forced is None else int(forced[s])
+            h = embed_rows(W, np.array([feed]), dtype)[0]
+            logits, Kc, Vc = decode_step(cfg, W, h, Kc, Vc)
+    return np.asarray(out, dtype=np.int64), np.stack(all_logits), Kc, Vc
+
+
 def full_prefill(cfg: Dict, W: Dict, tokens: np.ndarray, dtype=np.float64,
                  embeds: Optional[np.ndarray] = None, embed_ranges: Sequence[Tuple[int, int]] = ()):
     """The unpruned model's ordinary prefill of all N rows at once (every layer kept, no

@@ -11,12 +11,16 @@ import math
 from functools import lru_cache
 
 
-def brute_force_pop(cfg, W, tokens, l_keep):
-    """Returns (K, V, logits) with K[l][t][head][i] python floats (l 0-based layer index)."""
+def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None):
+    """Returns (K, V, logits) with K[l][t][head][i] python floats (l 0-based layer index).
+    `tokens` may extend beyond the prompt (first n_prompt entries): later tokens are decode steps and,
+    like the last prompt token, run every layer in full (Sec. 3.2: decoding keeps the full model).
+    logits are those of the last given token."""
     L, d = cfg["n_layers"], cfg["d_model"]
     Hq, Hkv, hd, f = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"]
     eps = cfg["rms_eps"]
     N = len(tokens)
+    n_prompt = N if n_prompt is None else n_prompt
     tl = lambda a: a.tolist()
     E = tl(W["embed"])
     lay = [{k: tl(v) for k, v in lw.items()} for lw in W["layers"]]
@@ -51,7 +55,7 @@ def brute_force_pop(cfg, W, tokens, l_keep):
     def runs_full(l, t):
         """Does token t run layer l (1-based) in full?  The body is pruned beyond l_keep, the last
         prompt token never is."""
-        return l <= l_keep or t == N - 1
+        return l <= l_keep or t >= n_prompt - 1
 
     @lru_cache(maxsize=None)
     def x_in(l, t):

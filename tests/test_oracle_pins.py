@@ -377,3 +377,56 @@ def test_argument_errors():
         O.pop_prefill(cfg, w, np.array([], dtype=np.int32), 2)
     with pytest.raises(ValueError):
         O.pop_prefill(cfg, w, np.array([1, 2], dtype=np.int32), cfg["n_layers"] + 1)
+
+
+# ------------------------------------------------------------------ greedy generation (Sec. 3.2)
+@pytest.mark.parametrize("l_keep", [0, 1, 2])
+def test_greedy_generation_matches_brute_force_recomputation(l_keep):
+    """Every generated token is recomputed from scratch by the scalar brute force: prompt body pruned
+    beyond l_keep, the last prompt token and all generated tokens at full depth."""
+    cfg = micro_cfg()
+    w = weights(cfg)
+    prompt = synth.make_tokens(cfg["vocab"], 6, seed=4)
+    n_new = 4
+    toks, logits, Kc, Vc = O.greedy_generate(cfg, w, prompt, l_keep, n_new)
+    seq = prompt.tolist()
+    for s in range(n_new):
+        Kb, Vb, lb = brute_force_pop(cfg, w, seq, l_keep, n_prompt=len(prompt))
+        np.testing.assert_allclose(logits[s], np.array(lb), rtol=1e-9, atol=1e-11)
+        assert int(np.argmax(lb)) == int(toks[s])
+        seq.append(int(toks[s]))
+    # the cache after generation holds the prompt and the first n_new - 1 generated tokens
+    Kb, Vb, _ = brute_force_pop(cfg, w, seq[:-1], l_keep, n_prompt=len(prompt))
+    np.testing.assert_allclose(stack(Kc), np.array(Kb), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(stack(Vc), np.array(Vb), rtol=1e-9, atol=1e-11)
+
+
+def test_greedy_generation_unpruned_equals_repeated_full_forward():
+    cfg = small_cfg()
+    w = weights(cfg)
+    prompt = synth.make_tokens(cfg["vocab"], 9, seed=5)
+    toks, logits, _, _ = O.greedy_generate(cfg, w, prompt, cfg["n_layers"], 5)
+    seq = prompt.copy()
+    for s in range(5):
+        _, _, ref = O.full_prefill(cfg, w, seq)
+        np.testing.assert_allclose(logits[s], ref, rtol=1e-9, atol=1e-11)
+        assert int(np.argmax(ref)) == int(toks[s])
+        seq = np.append(seq, toks[s])
+
+
+def test_greedy_generation_eos_and_forcing():
+    cfg = small_cfg()
+    w = weights(cfg)
+    prompt = synth.make_tokens(cfg["vocab"], 7, seed=6)
+    free, _, _, _ = O.greedy_generate(cfg, w, prompt, 2, 6)
+    # declaring the third generated token the end-of-sequence id freezes the tail
+    eos = int(free[2])
+    stopped, _, _, _ = O.greedy_generate(cfg, w, prompt, 2, 6, eos=eos)
+    first = list(free).index(eos)
+    assert list(stopped[:first + 1]) == list(free[:first + 1]) and all(t == eos for t in stopped[first:])
+    # forcing the model's own choices changes nothing; forcing others changes the continuation's inputs
+    same, l_same, _, _ = O.greedy_generate(cfg, w, prompt, 2, 6, forced=list(free))
+    assert list(same) == list(free)
+    other = [(int(t) + 1) % cfg["vocab"] for t in free]
+    _, l_other, _, _ = O.greedy_generate(cfg, w, prompt, 2, 6, forced=other)
+    assert np.allclose(l_other[0], l_same[0]) and not np.allclose(l_other[1], l_same[1])
