@@ -107,6 +107,8 @@ def main():
     ap.add_argument("--l-keep", type=int, default=24)
     ap.add_argument("--sweep", default="32,28,24,20")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ttft-sweep", action="store_true",
+                    help="skip the batch-8 time-to-first-token sweep over prompt lengths (Table 2's shape)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (calibrates the FETCH_SIZE / "
@@ -227,6 +229,36 @@ def main():
                      "flops_per_launch": gu_flops, "avg_launch_ms": gu_ms},
         "breakdown": breakdown,
     }
+    if not args.no_ttft_sweep:
+        # time to first token of a batch of 8 equal-length prompts, pruned (last third of the layers
+        # skipped for the body, the paper's static policy) against full depth: the shape of the paper's
+        # TTFT table; its numbers are another machine's and are not compared
+        del ws
+        lk = (2 * L) // 3
+        sweep8 = {}
+        for plen in (32, 128, 512, 2048):
+            lens = [plen] * 8
+            bt8, n_pages8 = synth.make_block_table(lens, cfg["page_size"], reserve_pages=1)
+            cache8 = pop.Cache(cfg, n_pages8, 8, bt8.shape[1])
+            ws8 = pop.alloc_workspace(cfg, 8 * plen, 8, bt8.shape[1])
+            tok8 = synth.make_tokens(cfg["vocab"], 8 * plen, seed=2)
+            cu8 = np.arange(9, dtype=np.int32) * plen
+            lg8 = torch.empty(8, cfg["vocab"], dtype=torch.float32, device="cuda")
+            res = {}
+            for k in (L, lk):
+                for _ in range(2):
+                    pop.pop_prefill(model, cache8, tok8, cu8, bt8, k, ws8, logits=lg8, stream=stream)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(5):
+                    pop.pop_prefill(model, cache8, tok8, cu8, bt8, k, ws8, logits=lg8, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                res[k] = e0.elapsed_time(e1) / 5
+            sweep8[str(plen)] = {"ttft_ms_full": res[L], "ttft_ms_pruned": res[lk], "speedup": res[L] / res[lk]}
+            del cache8, ws8, lg8
+        out["ttft_sweep"] = {"batch": 8, "l_keep": lk, "n_layers": L, "by_prompt_length": sweep8}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, n, head)
     print(json.dumps(out))

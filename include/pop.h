@@ -183,6 +183,28 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
                            pop_stream stream);
 
 /*
+ * Greedy generation (Sec. 3.2: prefill, then the decode loop with the full model): pop_prefill in
+ * POP_MODE_POP, then max_new_tokens tokens per sequence.  Token 0 is the index of the largest
+ * boundary-token logit (lowest index on ties); token s > 0 is chosen the same way from the logits
+ * of a decode step on token s-1.  Once a sequence has produced eos_token (>= 0; pass -1 for none)
+ * all its later tokens are eos_token (its steps are still computed, so all sequences stay in
+ * step).  Everything is enqueued without a host synchronisation: tokens are chosen and fed back on
+ * the device.
+ *   dev_tokens_out DEVICE int32 [n_seqs, max_new_tokens]
+ *   dev_logits     DEVICE fp32 [n_seqs, vocab]: scratch for every step; holds the last step's logits
+ *   dev_workspace  at least pop_generate_workspace_bytes(cfg, T, n_seqs, max_pages_per_seq, max_new_tokens)
+ * The block table must assign pages for positions up to len_b + max_new_tokens - 2.  Afterwards the
+ * cache holds len_b + max_new_tokens - 1 entries per sequence (the last chosen token is not fed).
+ * Errors as pop_prefill, plus POP_EINVAL (max_new_tokens < 1, mode not POP_MODE_POP, eos_token >=
+ * vocab) and POP_ENOSPACE (pages for the generated tokens, workspace); all before any launch.
+ */
+size_t pop_generate_workspace_bytes(const pop_config* cfg, int32_t max_tokens, int32_t max_seqs,
+                                    int32_t max_pages_per_seq, int32_t max_new_tokens);
+pop_status pop_generate(pop_model* m, pop_cache* c, const pop_prefill_args* args, int32_t max_new_tokens,
+                        int32_t eos_token, int32_t* dev_tokens_out, float* dev_logits, void* dev_workspace,
+                        size_t workspace_bytes, pop_stream stream);
+
+/*
  * Optional per-step timing for benchmarks.  While enabled, pop_prefill brackets every launch of the
  * steps below with HIP events on the caller's stream (this adds a little launch overhead, so whole-
  * call latency should be measured with timing disabled).  pop_timing_read waits for the recorded

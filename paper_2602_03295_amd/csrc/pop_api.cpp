@@ -976,6 +976,94 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
   return lm_head(x, B, dev_logits);
 }
 
+// ----------------------------------------------------------------------------------------- generation
+size_t pop_generate_workspace_bytes(const pop_config* cfg, int32_t max_tokens, int32_t max_seqs,
+                                    int32_t max_pages_per_seq, int32_t max_new_tokens) {
+  const size_t base = pop_workspace_bytes(cfg, max_tokens, max_seqs, max_pages_per_seq);
+  if (base == 0 || max_new_tokens < 1) return 0;
+  return base + round_up(4 * (size_t)max_seqs * (2 * (size_t)max_new_tokens + 1), 256);
+}
+
+pop_status pop_generate(pop_model* m, pop_cache* c, const pop_prefill_args* a, int32_t max_new_tokens, int32_t eos_token,
+                        int32_t* dev_tokens_out, float* dev_logits, void* dev_workspace, size_t workspace_bytes,
+                        pop_stream stream) {
+  if (!m || !c || !a) return fail(POP_EINVAL, "model / cache / args is NULL");
+  if (!dev_tokens_out || !dev_logits) return fail(POP_EINVAL, "dev_tokens_out / dev_logits is NULL");
+  if (max_new_tokens < 1) return fail(POP_EINVAL, "max_new_tokens %d < 1", max_new_tokens);
+  if (a->mode != POP_MODE_POP) return fail(POP_EINVAL, "generation needs POP_MODE_POP (the boundary token's logits)");
+  const pop_config& cfg = m->cfg;
+  if (eos_token >= cfg.vocab) return fail(POP_EINVAL, "eos_token %d outside the vocabulary", eos_token);
+  if (!a->cu_seqlens || !a->block_table) return fail(POP_EINVAL, "cu_seqlens / block_table is NULL");
+  if (a->n_seqs < 1 || a->n_seqs > c->max_seqs)
+    return fail(POP_EINVAL, "n_seqs %d outside [1, %d]", a->n_seqs, c->max_seqs);
+  const int B = a->n_seqs, P = cfg.page_size, maxp = c->max_pages, n_new = max_new_tokens;
+  // pages for the prompt and for the n_new - 1 generated tokens that are fed back
+  if (pop_status st = slot_map_impl(a->cu_seqlens, B, a->block_table, maxp, P, c->n_pages, nullptr, n_new - 1)) return st;
+  const int T = a->cu_seqlens[B];
+  const size_t base = pop_workspace_bytes(&cfg, T, B, maxp);
+  const size_t need = pop_generate_workspace_bytes(&cfg, T, B, maxp, n_new);
+  if (base == 0) return fail(POP_EINVAL, "bad config");
+  if (workspace_bytes < need)
+    return fail(POP_ENOSPACE, "workspace has %zu bytes, %zu needed to generate %d tokens", workspace_bytes, need, n_new);
+  if (cfg.dtype == POP_DTYPE_F32)
+    for (int b = 0; b < B; ++b)
+      if (a->cu_seqlens[b + 1] - a->cu_seqlens[b] + n_new > pop::f32::kMaxContext)
+        return fail(POP_EUNSUPPORTED, "the fp32 path supports sequences up to %d tokens", pop::f32::kMaxContext);
+  if (pop_status st = pop_prefill(m, c, a, dev_logits, dev_workspace, base, stream)) return st;
+
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  // positions and slots of the fed-back tokens, step-major: entry (s, b) is generated token s of sequence b
+  std::vector<int32_t> gmeta((size_t)B * (2 * (size_t)n_new + 1), 0);
+  int32_t* g_pos = gmeta.data();
+  int32_t* g_slot = g_pos + (size_t)B * n_new;
+  int max_len = 0;
+  for (int b = 0; b < B; ++b) {
+    const int len = a->cu_seqlens[b + 1] - a->cu_seqlens[b];
+    max_len = std::max(max_len, len);
+    for (int s = 0; s + 1 < n_new; ++s) {
+      const int pos = len + s;
+      g_pos[(size_t)s * B + b] = pos;
+      g_slot[(size_t)s * B + b] = a->block_table[(size_t)b * maxp + pos / P] * P + pos % P;
+    }
+  }
+  char* gbase = reinterpret_cast<char*>(dev_workspace) + base;
+  POP_HIP(hipMemcpyAsync(gbase, gmeta.data(), gmeta.size() * 4, hipMemcpyHostToDevice, st));
+  const int32_t* d_gpos = reinterpret_cast<const int32_t*>(gbase);
+  const int32_t* d_gslot = d_gpos + (size_t)B * n_new;
+  int32_t* d_tok = reinterpret_cast<int32_t*>(gbase) + 2 * (size_t)B * n_new;
+  void* ws = dev_workspace;
+  pop::launch_argmax(dev_logits, cfg.vocab, d_tok, dev_tokens_out, n_new, 0, eos_token, B, st);
+  if (cfg.dtype == POP_DTYPE_F32) {
+    const WorkspaceF32 w = carve_f32(cfg, T, B, maxp);
+    CtxF32 x{m, c, ws, &w, st};
+    float* xb = at<float>(ws, w.o_xb);
+    for (int s = 1; s < n_new; ++s) {
+      pop::f32::launch_embed((const float*)m->w.embed, d_tok, nullptr, nullptr, xb, B, cfg.d_model, st);
+      for (int l = 1; l <= cfg.n_layers; ++l)
+        if (pop_status e = layer_f32(x, l, B, xb, at<float>(ws, w.o_ab), at<float>(ws, w.o_qkvb), at<float>(ws, w.o_attnb),
+                                     at<float>(ws, w.o_ub), at<int32_t>(ws, w.o_bnd_seq), d_gpos + (size_t)(s - 1) * B,
+                                     d_gslot + (size_t)(s - 1) * B, max_len + s))
+          return e;
+      if (pop_status e = lm_head_f32(x, B, dev_logits)) return e;
+      pop::launch_argmax(dev_logits, cfg.vocab, d_tok, dev_tokens_out, n_new, s, eos_token, B, st);
+    }
+  } else {
+    const Workspace w = carve(cfg, T, B, maxp);
+    LayerCtx x{m, c, ws, &w, st};
+    for (int s = 1; s < n_new; ++s) {
+      pop::launch_embed((const bf16_t*)m->w.embed, d_tok, nullptr, nullptr, at<float>(ws, w.o_xb), B, cfg.d_model, st);
+      for (int l = 1; l <= cfg.n_layers; ++l)
+        if (pop_status e = decode_layer(x, l, B, d_gpos + (size_t)(s - 1) * B, d_gslot + (size_t)(s - 1) * B, max_len + s))
+          return e;
+      if (pop_status e = lm_head(x, B, dev_logits)) return e;
+      pop::launch_argmax(dev_logits, cfg.vocab, d_tok, dev_tokens_out, n_new, s, eos_token, B, st);
+    }
+  }
+  POP_HIP(hipGetLastError());
+  for (int b = 0; b < B; ++b) c->seq_lens[b] += n_new - 1;
+  return POP_OK;
+}
+
 // ----------------------------------------------------------------------------------------- single steps
 pop_status pop_op_rmsnorm(const float* x, const float* gamma, void* out, int32_t rows, int32_t d, float eps,
                           pop_stream stream) {

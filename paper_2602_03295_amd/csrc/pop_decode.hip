@@ -412,6 +412,49 @@ void launch_decode_hd(const AttnDecodeArgs& a, hipStream_t st) {
 }  // namespace decode_impl
 using namespace decode_impl;
 
+// ------------------------------------------------------------------------------------- greedy choice
+namespace decode_impl {
+// tok[b] = (step > 0 and tok[b] == eos and eos >= 0) ? eos : argmax_v logits[b, v]  (lowest index on ties),
+// and out[b * out_stride + step] = tok[b].  One work-group of 1024 threads per sequence.
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int vocab,
+                                                      int32_t* __restrict__ tok, int32_t* __restrict__ out,
+                                                      int out_stride, int step, int eos) {
+  __shared__ float bv[16];
+  __shared__ int bi[16];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const float* row = logits + (size_t)b * vocab;
+  float best = -INFINITY;
+  int idx = 0x7fffffff;
+  for (int v = tid; v < vocab; v += 1024) {
+    const float x = row[v];
+    if (x > best) { best = x; idx = v; }   // ascending v: the first maximum of this thread is kept
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, 64);
+    const int oi = __shfl_xor(idx, o, 64);
+    if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+  }
+  if ((tid & 63) == 0) { bv[tid >> 6] = best; bi[tid >> 6] = idx; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < 16; ++w)
+      if (bv[w] > best || (bv[w] == best && bi[w] < idx)) { best = bv[w]; idx = bi[w]; }
+    if (idx == 0x7fffffff) idx = 0;   // a row without any finite maximum
+    if (step > 0 && eos >= 0 && tok[b] == eos) idx = eos;
+    tok[b] = idx;
+    out[(size_t)b * out_stride + step] = idx;
+  }
+}
+}  // namespace decode_impl
+
+void launch_argmax(const float* logits, int vocab, int32_t* tok, int32_t* out, int out_stride, int step, int eos,
+                   int B, hipStream_t st) {
+  if (B <= 0) return;
+  hipLaunchKernelGGL(decode_impl::argmax_kernel, dim3(B), dim3(1024), 0, st, logits, vocab, tok, out, out_stride, step,
+                     eos);
+}
+
 void launch_attention_decode(const AttnDecodeArgs& a, hipStream_t st) {
   if (a.B <= 0) return;
   switch (a.hd) {

@@ -167,6 +167,12 @@ hipError_t launch_attention(const float* q, int ldq, int q_col, float* out, cons
                             int n_kv_heads, int hd, int max_len, hipStream_t st);
 }  // namespace f32
 
+// Greedy choice of the next token of every sequence from fp32 logits [B, vocab]: tok[b] (device, in/out)
+// becomes the index of the largest logit (lowest index on ties), or stays `eos` once it was `eos`
+// (step > 0, eos >= 0); the choice is also stored at out[b * out_stride + step].
+void launch_argmax(const float* logits, int vocab, int32_t* tok, int32_t* out, int out_stride, int step, int eos,
+                   int B, hipStream_t st);
+
 // gather fp32 rows: dst[i,:] = src[idx[i],:]
 void launch_gather_rows(const float* src, const int32_t* idx, float* dst, int rows, int d, hipStream_t st);
 

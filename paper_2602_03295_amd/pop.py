@@ -78,6 +78,10 @@ lib.pop_prefill.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(pop_prefill_args),
                             C.c_size_t, C.c_void_p]
 lib.pop_decode_step.argtypes = [C.c_void_p, C.c_void_p, _i32p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                 C.c_void_p]
+lib.pop_generate_workspace_bytes.argtypes = [C.POINTER(pop_config), C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+lib.pop_generate_workspace_bytes.restype = C.c_size_t
+lib.pop_generate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(pop_prefill_args), C.c_int32, C.c_int32, C.c_void_p,
+                             C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 lib.pop_op_rmsnorm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p]
 lib.pop_op_gemm.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                             C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
@@ -95,7 +99,8 @@ STEP_NAMES = ["embed", "norm", "qkv_gemm", "rope_write", "attention", "o_gemm", 
 
 EXPORTED = ["pop_timing_enable", "pop_timing_read", "pop_last_error", "pop_version", "pop_load_weights", "pop_free_model", "pop_cache_bytes",
             "pop_workspace_bytes", "pop_cache_create", "pop_cache_destroy", "pop_cache_n_seqs",
-            "pop_cache_seq_lens", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_op_rmsnorm",
+            "pop_cache_seq_lens", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_generate",
+            "pop_generate_workspace_bytes", "pop_op_rmsnorm",
             "pop_op_gemm", "pop_op_gemv", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
 
 
@@ -281,6 +286,32 @@ def pop_decode_step(model: Model, cache: Cache, tokens, workspace: torch.Tensor,
     _check(lib.pop_decode_step(model.handle, cache.handle, _ptr(tok), len(tok), logits.data_ptr(),
                                workspace.data_ptr(), workspace.numel(), _stream(stream)))
     return logits
+
+
+def alloc_generate_workspace(cfg: Dict, max_tokens: int, max_seqs: int, max_pages_per_seq: int, max_new_tokens: int,
+                             device="cuda") -> torch.Tensor:
+    c = make_config(cfg)
+    n = lib.pop_generate_workspace_bytes(C.byref(c), max_tokens, max_seqs, max_pages_per_seq, max_new_tokens)
+    if n == 0:
+        raise PopError(-1, "pop_generate_workspace_bytes returned 0")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def pop_generate(model: Model, cache: Cache, tokens, cu_seqlens, block_table, l_keep: int, max_new_tokens: int,
+                 workspace: torch.Tensor, eos_token: int = -1, logits: Optional[torch.Tensor] = None,
+                 stream=None):
+    """Returns (generated tokens int32 [n_seqs, max_new_tokens] on the device, last step's logits)."""
+    tok, cu, bt = _i32(tokens), _i32(cu_seqlens), _i32(block_table)
+    n_seqs = len(cu) - 1
+    dev = workspace.device if workspace is not None else "cpu"
+    if logits is None:
+        logits = torch.empty(max(n_seqs, 1), model.cfg["vocab"], dtype=torch.float32, device=dev)
+    out = torch.empty(max(n_seqs, 1), max(max_new_tokens, 1), dtype=torch.int32, device=dev)
+    a = pop_prefill_args(_ptr(tok), _ptr(cu), n_seqs, _ptr(bt), None, None, 0, l_keep, MODE_POP)
+    _check(lib.pop_generate(model.handle, cache.handle, C.byref(a), max_new_tokens, eos_token, out.data_ptr(),
+                            logits.data_ptr(), workspace.data_ptr() if workspace is not None else None,
+                            0 if workspace is None else workspace.numel(), _stream(stream)))
+    return out, logits
 
 
 # ------------------------------------------------------------------------------------ single steps

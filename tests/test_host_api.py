@@ -196,3 +196,34 @@ def test_decode_step_state_errors():
     assert pop.lib.pop_decode_step(m, cache, None, 1, FAKE, FAKE, 1 << 30, None) == -1
     pop.lib.pop_cache_destroy(cache)
     pop.lib.pop_free_model(m)
+
+
+def test_generate_argument_errors():
+    """pop_generate rejects bad requests on the host, before anything is enqueued."""
+    cfg = bf16_cfg()
+    tokens = synth.make_tokens(cfg["vocab"], 27, seed=1)
+    bt, n_pages = synth.make_block_table([20, 7], 16, reserve_pages=1)   # room for positions < 48 and < 32
+    cu = np.array([0, 20, 27], dtype=np.int32)
+    tok, bt_ = (np.ascontiguousarray(np.asarray(x, dtype=np.int32)) for x in (tokens, bt))
+    p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    c_cfg0 = pop.make_config(cfg)
+    base = pop.lib.pop_workspace_bytes(C.byref(c_cfg0), 27, 2, bt.shape[1])
+    need = pop.lib.pop_generate_workspace_bytes(C.byref(c_cfg0), 27, 2, bt.shape[1], 4)
+    assert 0 < base < need
+    assert pop.lib.pop_generate_workspace_bytes(C.byref(c_cfg0), 27, 2, bt.shape[1], 0) == 0
+    cases = [
+        (dict(n_new=0), -1), (dict(n_new=200), -4), (dict(eos=cfg["vocab"]), -1), (dict(ws_bytes=base), -4),
+        (dict(mode=1), -1), (dict(out=None), -1), (dict(logits=None), -1), (dict(n_new=27), -4),
+    ]
+    for kw, want in cases:
+        args = dict(n_new=4, eos=-1, ws_bytes=1 << 34, mode=0, out=FAKE, logits=FAKE)
+        args.update(kw)
+        st, m, c_cfg, keep = fake_model(cfg)
+        st, cache = fake_cache(c_cfg, n_pages, 4, bt.shape[1])
+        a = pop.pop_prefill_args(p(tok), p(cu), 2, p(bt_), None, None, 0, 5, args["mode"])
+        st = pop.lib.pop_generate(m, cache, C.byref(a), args["n_new"], args["eos"], args["out"], args["logits"], FAKE,
+                                  args["ws_bytes"], None)
+        assert st == want, (kw, st, err())
+        assert pop.lib.pop_cache_n_seqs(cache) == 0 and err()
+        pop.lib.pop_cache_destroy(cache)
+        pop.lib.pop_free_model(m)
