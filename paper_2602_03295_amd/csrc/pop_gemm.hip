@@ -26,6 +26,7 @@
 //   * Work-group ids are remapped so that the groups that run together on one XCD (ids equal mod 8)
 //     work on neighbouring M tiles of the same W tile and share it through that XCD's L2.
 #include <cstdlib>
+#include <type_traits>
 
 #include "pop_device.h"
 #include "pop_kernels.h"
@@ -59,7 +60,10 @@ __device__ __forceinline__ float glu_act(float g, float k0, float k1) {
   return g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-g * (k0 + k1 * g * g)));
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, int EPI>
+// KFULL: K is a multiple of BK.  Then no lane ever needs a tail mask and the main loop carries no
+// vector-ALU instruction besides the MFMAs (address arithmetic is loop invariant or scalar): vector
+// ALU instructions share the issue port with the MFMAs and every one of them delays the next MFMA.
+template <int BM, int BN, int WGM, int WGN, int STAGES, int EPI, bool KFULL>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the buffer-resource builtins exist in the device pass only
   constexpr int NW = WGM * WGN;
@@ -135,23 +139,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   constexpr int STEPS = BK / 16;
   constexpr int LOADS = LA + LB;
   constexpr int LPS = (LOADS + STEPS - 1) / STEPS;  // loads per slice
+  const int nk = (p.K + BK - 1) / BK;
+  // KFULL: a K-step beyond the last one re-stages the last one (into a stage nobody reads any more),
+  // which keeps the number of loads per iteration uniform without a per-lane mask.
   auto issue_one = [&](int q, int kt, unsigned char* stage_base, uint32_t tail_mask) {
     if (q >= LOADS) return;
-    const int k0 = kt * BK;
+    const int k0 = (KFULL ? min(kt, nk - 1) : kt) * BK;
     unsigned char* sa = stage_base;
     unsigned char* sb = sa + A_BYTES;
     if (q < LA)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(sa + (q * NW + wave) * 1024), 16,
-                                               offA[q] | tail_mask, k0 * 2, 0, 0);
+                                               KFULL ? offA[q] : (offA[q] | tail_mask), k0 * 2, 0, 0);
     else
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rW, (lds_ptr_t)(sb + ((q - LA) * NW + wave) * 1024), 16,
-                                               offB[q - LA] | tail_mask, k0 * 2, 0, 0);
+                                               KFULL ? offB[q - LA] : (offB[q - LA] | tail_mask), k0 * 2, 0, 0);
   };
   auto issue = [&](int kt, int stage, uint32_t tail_mask) {
 #pragma unroll
     for (int q = 0; q < LOADS; ++q) issue_one(q, kt, smem + stage * STAGE, tail_mask);
   };
-  const int nk = (p.K + BK - 1) / BK;
   const int nk_full = p.K / BK;  // K-steps that need no tail mask
   const uint32_t last_mask = (nk_full * BK + lc * 8 < p.K) ? 0u : kOOB;
 
@@ -189,9 +195,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     }
   }
   auto prefetch = [&](int kt) {   // one DMA load per wave; lanes beyond K or beyond the tile are masked
-    const uint32_t off = (kt * BK < p.K) ? pf_off : kOOB;
-    if (wave == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rW, (lds_ptr_t)pf_scratch, 4, off, kt * BK * 2, 0, 0);
-    else __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(pf_scratch + 256), 4, off, kt * BK * 2, 0, 0);
+    const uint32_t off = KFULL ? pf_off : ((kt * BK < p.K) ? pf_off : kOOB);
+    const int kk = KFULL ? min(kt, nk - 1) : kt;
+    if (wave == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rW, (lds_ptr_t)pf_scratch, 4, off, kk * BK * 2, 0, 0);
+    else __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(pf_scratch + 256), 4, off, kk * BK * 2, 0, 0);
   };
 
   floatx16_t acc[NB][MB];
@@ -213,8 +220,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #pragma unroll
   for (int t = 0; t < STAGES - 1; ++t)
     if (t < nk) issue(t, t, t < nk_full ? 0u : last_mask);
-  int stage = 0;                  // stage that holds K-step kt
-  int fill = (STAGES - 1) % STAGES;  // stage the next issued K-step goes to
   // The K loop is rotated by one sub-step: the MFMAs of the last sub-step of K-step kt-1 are issued
   // after the barrier of K-step kt, from fragments that are already in registers, so the matrix
   // pipe has work while the first fragments of the new stage travel from LDS.  Sub-step s of a
@@ -236,7 +241,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   constexpr int RPG = (READS + G - 1) / G;          // LDS reads per group
   constexpr int LPG = (LPS + G - 1) / G;            // global loads per group
   static_assert(MFMAS % G == 0, "MFMAs must split evenly into groups");
-  for (int kt = 0; kt < nk; ++kt) {
+  // One K-step; the stage that holds it and the stage refilled meanwhile are compile-time constants
+  // (the loop below is unrolled by STAGES), so LDS addresses are loop-invariant registers + immediates.
+  auto kstep = [&](int kt, auto stage_c, auto fill_c) {
+    constexpr int stage = decltype(stage_c)::value, fill = decltype(fill_c)::value;
     // Wait until K-step kt has landed.  Loads return in order, so it is enough to bound how many
     // younger ones may still be in flight.  Every iteration issues exactly LOADS staging loads (masked
     // beyond the last K-step) followed by one prefetch load, so behind K-step kt's loads there are:
@@ -255,11 +263,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     __builtin_amdgcn_s_barrier();
     // K-step to prefetch during this one (branch-free: beyond the end every lane is masked off)
     const int tp = kt + STAGES - 1;
-    const uint32_t pmask = tp < nk_full ? 0u : (tp < nk ? last_mask : kOOB);
+    const uint32_t pmask = KFULL ? 0u : (tp < nk_full ? 0u : (tp < nk ? last_mask : kOOB));
     unsigned char* fill_base = smem + fill * STAGE;
     const unsigned char* sa = smem + stage * STAGE;
-    stage = stage + 1 == STAGES ? 0 : stage + 1;
-    fill = fill + 1 == STAGES ? 0 : fill + 1;
     const unsigned char* sb = sa + A_BYTES;
     // Every slot is cut into G groups; a group carries a share of the LDS reads of sub-step `slot`,
     // one slice of the next K-step's global loads, and MPG MFMAs of the sub-step before it.
@@ -289,6 +295,27 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
       }
     }
     prefetch(kt + PF_DIST);
+  };
+  {
+    typedef std::integral_constant<int, 0> S0;
+    typedef std::integral_constant<int, 1> S1;
+    typedef std::integral_constant<int, 2> S2;
+    int kt = 0;
+    if constexpr (STAGES == 2) {
+      for (; kt + 1 < nk; kt += 2) {
+        kstep(kt, S0{}, S1{});
+        kstep(kt + 1, S1{}, S0{});
+      }
+      if (kt < nk) kstep(kt, S0{}, S1{});
+    } else {
+      for (; kt + 2 < nk; kt += 3) {
+        kstep(kt, S0{}, S2{});
+        kstep(kt + 1, S1{}, S0{});
+        kstep(kt + 2, S2{}, S1{});
+      }
+      if (kt < nk) kstep(kt, S0{}, S2{});
+      if (kt + 1 < nk) kstep(kt + 1, S1{}, S0{});
+    }
   }
   // last sub-step of the last K-step
 #pragma unroll
@@ -397,15 +424,21 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_
   p.W_list = g.batch > 1 || g.W_list ? g.W_list : nullptr;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI, true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int total = p.tiles_m * p.tiles_n;
   const int grid = ((total + 7) / 8) * 8;
-  hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI>), dim3(grid, 1, g.batch > 0 ? g.batch : 1),
-                     dim3(64 * WGM * WGN), smem, st, p);
+  const dim3 grid3(grid, 1, g.batch > 0 ? g.batch : 1), block3(64 * WGM * WGN);
+  if (g.K % BK == 0)
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI, true>), grid3, block3, smem, st, p);
+  else
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI, false>), grid3, block3, smem, st, p);
   return hipGetLastError();
 }
 
