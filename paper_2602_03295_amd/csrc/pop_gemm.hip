@@ -81,7 +81,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   const int per_xcd = (total + 7) >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (logical >= total) return;
-  const int tm = logical % p.tiles_m, tn = logical / p.tiles_m;
+  // Tiles are numbered in bands of 8 row tiles: inside a band the row tile runs fastest, then the
+  // column tile.  The 32 CUs of an XCD then work on 8 row tiles x 4 column tiles at a time whatever M
+  // is (each W tile is shared by 8 of them, each A tile by 4), which is what their L2 can hold.
+  int tm, tn;
+  {
+    const int band = logical / (8 * p.tiles_n);
+    const int rows = min(8, p.tiles_m - band * 8);     // the last band may be narrower
+    const int r = logical - band * 8 * p.tiles_n;
+    tn = r / rows;
+    tm = band * 8 + r % rows;
+  }
   const int m0 = tm * BM;
   constexpr int BN_OUT = EPI == EPI_GLU_BF16 ? BN / 2 : BN;
   const int n0 = (p.n_tile0 + tn) * BN_OUT;  // first output column of the tile
