@@ -68,7 +68,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the buffer-resource builtins exist in the device pass only
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
-  constexpr int MB = WTM / 32, NB = WTN / 32;
+  constexpr int MB = WTM / 16, NB = WTN / 16;   // 16x16 output blocks of a wave tile
   constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // wave-loads per stage and wave
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/wave mismatch");
   static_assert(EPI != EPI_GLU_BF16 || NB % 2 == 0, "GLU needs an even number of column blocks");
@@ -143,10 +143,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     offB[j] = ok ? (uint32_t)(((long long)wrow * p.ldw + lc * 8) * 2) : kOOB;
   }
 
-  // K-step t is staged by LA + LB wave-loads, spread over the STEPS = BK/16 MFMA sub-steps of the
+  // K-step t is staged by LA + LB wave-loads, spread over the STEPS = BK/32 MFMA sub-steps of the
   // K-step before it (LPS per sub-step).  tail_mask has bit 31 set on lanes whose chunk lies beyond K (or for a K-step beyond
   // the last one): that pushes the offset out of range and the lane stages zeros.
-  constexpr int STEPS = BK / 16;
+  constexpr int STEPS = BK / 32;
   constexpr int LOADS = LA + LB;
   constexpr int LPS = (LOADS + STEPS - 1) / STEPS;  // loads per slice
   const int nk = (p.K + BK - 1) / BK;
@@ -211,17 +211,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     else __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(pf_scratch + 256), 4, off, kk * BK * 2, 0, 0);
   };
 
-  floatx16_t acc[NB][MB];
+  // v_mfma_f32_16x16x32_bf16: D[16 x 16] += A[16 x 32] B[32 x 16].  Lane l supplies row l % 16 of A
+  // (here: a W row = output column) and column l % 16 of B (an activation row = output row), 8
+  // consecutive k each starting at 8 (l / 16), and receives rows 4 (l / 16) .. +3 of column l % 16.
+  // The 16x16 shape is used instead of 32x32x16 for its smaller accumulator traffic per flop.
+  floatx4_t acc[NB][MB];
 #pragma unroll
   for (int i = 0; i < NB; ++i)
 #pragma unroll
     for (int j = 0; j < MB; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
 
-  // LDS read offsets: row (lane & 31) of a 32-row block, chunk (2*ks + lane/32) ^ ((row >> 1) & 7)
-  const int frag_row = lane & 31;
-  const int frag_hi = lane >> 5;
+  // LDS read offsets: row (lane & 15) of a 16-row block, chunk (4*ks + lane/16) ^ ((row >> 1) & 7)
+  const int frag_row = lane & 15;
+  const int frag_hi = lane >> 4;
   const int a_base = (wm * WTM + frag_row) * 128;
   const int b_base = (wn * WTN + frag_row) * 128;
 
@@ -230,7 +234,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #pragma unroll
   for (int t = 0; t < STAGES - 1; ++t)
     if (t < nk) issue(t, t, t < nk_full ? 0u : last_mask);
-  // The K loop is rotated by one sub-step: the MFMAs of the last sub-step of K-step kt-1 are issued
+  // The K loop is rotated by one (32-wide) sub-step: the MFMAs of the last sub-step of K-step kt-1 are issued
   // after the barrier of K-step kt, from fragments that are already in registers, so the matrix
   // pipe has work while the first fragments of the new stage travel from LDS.  Sub-step s of a
   // K-step uses fragment buffer s & 1 (STEPS is even); the buffer of the "previous last sub-step"
@@ -246,7 +250,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #pragma unroll
     for (int v = 0; v < 8; ++v) bfr[1][i][v] = (__bf16)0.f;
   constexpr int READS = MB + NB, MFMAS = MB * NB;
-  constexpr int G = MFMAS >= 4 ? 4 : 1;            // groups per sub-step
+  constexpr int G = NB;                             // groups per sub-step: one W block with all A blocks
   constexpr int MPG = MFMAS / G;                    // MFMAs per group
   constexpr int RPG = (READS + G - 1) / G;          // LDS reads per group
   constexpr int LPG = (LPS + G - 1) / G;            // global loads per group
@@ -282,9 +286,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     // Scheduling barriers pin that order: a wave that issues its global loads in one burst sits in
     // the memory pipeline's issue queue while its MFMAs could run.
     auto load_frag = [&](int ks, int buf, int r) {    // r-th fragment read of sub-step ks
-      const int pc = ((2 * ks + frag_hi) ^ ((frag_row >> 1) & 7)) * 16;
-      if (r < NB) bfr[buf][r] = *reinterpret_cast<const bf16x8_t*>(sb + b_base + r * 32 * 128 + pc);
-      else af[buf][r - NB] = *reinterpret_cast<const bf16x8_t*>(sa + a_base + (r - NB) * 32 * 128 + pc);
+      const int pc = ((4 * ks + frag_hi) ^ ((frag_row >> 1) & 7)) * 16;
+      if (r < NB) bfr[buf][r] = *reinterpret_cast<const bf16x8_t*>(sb + b_base + r * 16 * 128 + pc);
+      else af[buf][r - NB] = *reinterpret_cast<const bf16x8_t*>(sa + a_base + (r - NB) * 16 * 128 + pc);
     };
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -298,7 +302,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #pragma unroll
         for (int e = g * MPG; e < (g + 1) * MPG; ++e) {
           const int i = e / MB, j = e % MB;
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[(slot + 1) & 1][i], af[(slot + 1) & 1][j],
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[(slot + 1) & 1][i], af[(slot + 1) & 1][j],
                                                               acc[i][j], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -331,13 +335,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #pragma unroll
   for (int e = 0; e < MFMAS; ++e) {
     const int i = e / MB, j = e % MB;
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[(STEPS - 1) & 1][i], af[(STEPS - 1) & 1][j], acc[i][j], 0, 0, 0);
+    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[(STEPS - 1) & 1][i], af[(STEPS - 1) & 1][j], acc[i][j], 0, 0, 0);
   }
   // masked staging loads and prefetches of the last iterations still target this group's LDS
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-  // ---- epilogue.  acc[i][j][v]: row m = .. + j*32 + (lane&31); column block i, columns
-  //      (v/4)*8 + (lane>>5)*4 + (v%4) inside it: 4 consecutive columns per (v/4).
+  // ---- epilogue.  acc[i][j][v]: row m = .. + j*16 + (lane & 15); column block i, columns
+  //      4 (lane >> 4) + v inside it: 4 consecutive columns per lane.
   const int m_lane = m0 + wm * WTM + frag_row;
   if (EPI == EPI_GLU_BF16) {
     const float act_k0 = p.act == 0 ? 1.4426950408889634f : 2.302208198f;
@@ -347,14 +351,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     for (int i = 0; i < NB / 2; ++i)
 #pragma unroll
       for (int j = 0; j < MB; ++j) {
-        const int m = m_lane + j * 32;
+        const int m = m_lane + j * 16;
         if (m >= p.M) continue;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = n0 + wn * (WTN / 2) + i * 32 + g * 8 + frag_hi * 4;
+        {
+          const int n = n0 + wn * (WTN / 2) + i * 16 + frag_hi * 4;
           float r[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) r[e] = glu_act(acc[i][j][g * 4 + e], act_k0, act_k1) * acc[i + NB / 2][j][g * 4 + e];
+          for (int e = 0; e < 4; ++e) r[e] = glu_act(acc[i][j][e], act_k0, act_k1) * acc[i + NB / 2][j][e];
           bf16_t* o = out + (long long)m * p.ldc + n;
           if (n + 3 < p.N) {
             uint2 pk;
@@ -373,14 +376,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     for (int i = 0; i < NB; ++i)
 #pragma unroll
       for (int j = 0; j < MB; ++j) {
-        const int m = m_lane + j * 32;
+        const int m = m_lane + j * 16;
         if (m >= p.M) continue;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = n0 + wn * WTN + i * 32 + g * 8 + frag_hi * 4;
+        {
+          const int n = n0 + wn * WTN + i * 16 + frag_hi * 4;
           if (n >= p.N) continue;
-          const float r0 = acc[i][j][g * 4 + 0], r1 = acc[i][j][g * 4 + 1];
-          const float r2 = acc[i][j][g * 4 + 2], r3 = acc[i][j][g * 4 + 3];
+          const float r0 = acc[i][j][0], r1 = acc[i][j][1];
+          const float r2 = acc[i][j][2], r3 = acc[i][j][3];
           if (EPI == EPI_STORE_BF16 || EPI == EPI_STORE_F16) {
             bf16_t* o = reinterpret_cast<bf16_t*>(p.out) + (long long)z * p.strideC + (long long)m * p.ldc + n;
             if (n + 3 < p.N) {
