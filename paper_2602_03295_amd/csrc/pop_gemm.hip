@@ -250,7 +250,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #pragma unroll
     for (int v = 0; v < 8; ++v) bfr[1][i][v] = (__bf16)0.f;
   constexpr int READS = MB + NB, MFMAS = MB * NB;
-  constexpr int G = NB;                             // groups per sub-step: one W block with all A blocks
+  constexpr int G = MB % 2 == 0 ? 2 * NB : NB;      // groups per sub-step: half a W block's MFMAs (64 cycles) each
   constexpr int MPG = MFMAS / G;                    // MFMAs per group
   constexpr int RPG = (READS + G - 1) / G;          // LDS reads per group
   constexpr int LPG = (LPS + G - 1) / G;            // global loads per group
