@@ -347,10 +347,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     const float act_k0 = p.act == 0 ? 1.4426950408889634f : 2.302208198f;
     const float act_k1 = p.act == 0 ? 0.f : 0.1029432396f;
     bf16_t* out = reinterpret_cast<bf16_t*>(p.out) + (long long)z * p.strideC;
+    // rows outer, column blocks inner: the stores that complete one 128-byte line of a row follow
+    // each other directly
 #pragma unroll
-    for (int i = 0; i < NB / 2; ++i)
+    for (int j = 0; j < MB; ++j)
 #pragma unroll
-      for (int j = 0; j < MB; ++j) {
+      for (int i = 0; i < NB / 2; ++i) {
         const int m = m_lane + j * 16;
         if (m >= p.M) continue;
         {
@@ -373,9 +375,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
       }
   } else {
 #pragma unroll
-    for (int i = 0; i < NB; ++i)
+    for (int j = 0; j < MB; ++j)
 #pragma unroll
-      for (int j = 0; j < MB; ++j) {
+      for (int i = 0; i < NB; ++i) {
         const int m = m_lane + j * 16;
         if (m >= p.M) continue;
         {
