@@ -112,3 +112,46 @@ def test_gemma12b_shape_local_global_reduced(pop):
     n = 4096
     tokens = synth.make_tokens(cfg["vocab"], n, seed=1)
     run_and_compare(pop, cfg, [n], 6, tokens)
+
+
+def test_llama8b_32k_context_sampled_rows(pop):
+    """Long-context shape (one 32768-token prompt at the Llama width): the oracle cannot afford the
+    full quadratic attention, so layer 1's K/V are compared for every position and layer 1's
+    attention + FFN are checked through layer 2's K/V on sampled rows, which the oracle computes one
+    row at a time from the definitions (each sampled row attends to all earlier keys)."""
+    cfg = synth.get_config("llama8b", n_layers=2, vocab=8192)
+    n = 32768
+    tokens = synth.make_tokens(cfg["vocab"], n, seed=1)
+    dev, host = synth.make_weights_on_gpu(cfg, seed=1234)
+    model = pop.Model(cfg, dev)
+    P = cfg["page_size"]
+    bt, n_pages = synth.make_block_table([n], P, 1)
+    cache = pop.Cache(cfg, n_pages, 1, bt.shape[1], fill=float("nan"))
+    ws = pop.alloc_workspace(cfg, n, 1, bt.shape[1])
+    pop.pop_prefill(model, cache, tokens, [0, n], bt, 1, ws)      # layer 1 kept, layer 2 pruned
+    torch.cuda.synchronize()
+    pos = np.arange(n)
+    h0 = O.embed_rows(host, tokens, np.float64)
+    lw1, lw2 = host["layers"]
+    K1, V1 = O.project_kv(cfg, lw1, 1, h0, pos)
+    k = cache.gather(0, 0, bt[0], n).float().cpu().numpy()
+    v = cache.gather(0, 1, bt[0], n).float().cpu().numpy()
+    e1 = (rel_err(k, K1), rel_err(v, V1))
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, 4095, 4096, 16383, 16384, n - 2, n - 1],
+                                     rng.integers(0, n, 20)]))
+    hq, hd = cfg["n_q_heads"], cfg["head_dim"]
+    dt = np.float64
+    x = h0[rows]
+    a = O.rmsnorm(x, O._w(lw1, "norm_in", dt), cfg["rms_eps"])
+    q = O.rope((a @ O._w(lw1, "wq", dt).T).reshape(-1, hq, hd), rows, cfg["rope_theta"])
+    o = O.attention_rows(q, rows, K1, V1, 0)
+    y = x + o @ O._w(lw1, "wo", dt).T
+    m = O.rmsnorm(y, O._w(lw1, "norm_post", dt), cfg["rms_eps"])
+    x1 = y + (O.glu_act(m @ O._w(lw1, "w_gate", dt).T, cfg["act"]) * (m @ O._w(lw1, "w_up", dt).T)) @ O._w(lw1, "w_down", dt).T
+    K2, V2 = O.project_kv(cfg, lw2, 2, x1, rows)
+    k2 = cache.gather(1, 0, bt[0], n).float().cpu().numpy()[rows]
+    v2 = cache.gather(1, 1, bt[0], n).float().cpu().numpy()[rows]
+    e2 = (rel_err(k2, K2), rel_err(v2, V2))
+    print("32K context: layer 1 K/V rel err", e1, "layer 2 K/V on", len(rows), "sampled rows", e2)
+    assert max(e1) <= TOL and max(e2) <= TOL
