@@ -4,7 +4,9 @@
 //
 // Design (MI355X):
 //   * Both operands have the contraction index contiguous, so a 16-byte chunk is exactly the 8 bf16
-//     values one lane feeds to v_mfma_f32_32x32x16_bf16.
+//     values one lane feeds to v_mfma_f32_16x16x32_bf16.  That shape is used rather than 32x32x16:
+//     same operand bytes per flop, a quarter of the accumulator registers read and written per
+//     instruction, and measurably higher sustained clocks under the power limit.
 //   * Tiles are staged global -> LDS with buffer_load_dwordx4 ... lds (no VGPR round trip); rows
 //     beyond M / N are out of range of the buffer descriptor and read as zero, so ragged edges need
 //     no branches in the main loop.
@@ -16,15 +18,19 @@
 //     r + 8).  The permutation is applied on the global side (each lane picks the chunk that belongs
 //     at its LDS position).
 //   * STAGES LDS stages (2 for 256x256 tiles, 3 for 256x128): the loads of K-step k+STAGES-1 are
-//     issued right after the barrier that publishes K-step k, so they overlap MFMA work; with 3
-//     stages two K-steps of loads are in flight, which covers L2-miss latency.
-//   * Tile shape is chosen per problem so that the number of tiles fills 256 CUs evenly (at M = 2048
-//     a 256x256 tiling of the gate|up projection leaves the last of 3.5 rounds half empty, 256x128
-//     gives exactly 7 rounds).
+//     issued after the barrier that publishes K-step k, spread over the K-step between groups of
+//     four MFMAs, so they overlap MFMA work.  Every K-step each wave also touches a few cache lines
+//     several K-steps ahead (a share of the tiles its XCD neighbours will stage), which turns the
+//     staging loads into L2 hits.
+//   * The main loop is software pipelined by one 32-wide sub-step and rotated so that MFMAs with
+//     operands already in registers follow the barrier; when K is a multiple of 64 it contains no
+//     vector-ALU instruction besides the MFMAs (they share an issue port).
+//   * Tile shape is chosen per problem so that the number of tiles fills 256 CUs evenly; a partly
+//     filled last round of 256x256 tiles is computed by a second launch with 128x256 tiles.
 //   * The MFMA is issued with W as the first operand, so a lane ends up with 4 consecutive output
 //     columns of one row: epilogues use 8/16-byte accesses.
-//   * Work-group ids are remapped so that the groups that run together on one XCD (ids equal mod 8)
-//     work on neighbouring M tiles of the same W tile and share it through that XCD's L2.
+//   * Work-group ids are remapped so that the 32 groups that run together on one XCD (ids equal mod
+//     8) work on 8 row tiles x 4 column tiles and share them through that XCD's L2.
 #include <cstdlib>
 #include <type_traits>
 
