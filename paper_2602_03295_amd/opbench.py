@@ -1,10 +1,13 @@
 """Per-kernel micro-benchmarks through the C ABI's single-step entry points (include/pop_ops.h).
 
     python -m paper_2602_03295_amd.opbench gemm [qkv|o|gate_up|down ...] [--m 2048] [--iters 20]
+                                                [--shape N K] [--vendor]
     python -m paper_2602_03295_amd.opbench attention [--tokens 8192] [--heads 32] [--kv-heads 8]
                                                      [--head-dim 128] [--window 0] [--iters 10]
 
-Shapes default to the Llama-3.1-8B projection shapes.  Inputs are seeded random numbers; the timed
+Shapes default to the Llama-3.1-8B projection shapes; `--shape N K` times one plain-store GEMM of
+that size instead, and `--vendor` times the same shapes through torch.matmul (hipBLASLt), without
+the fused epilogues, as the comparison the counter summaries quote.  Inputs are seeded random numbers; the timed
 region is `iters` back-to-back calls between two events on the launch stream.  Also the program that
 the counter summaries under profiles/ were collected on (rocprofv3 --pmc ... -- python3 -m ...).
 """
@@ -37,17 +40,26 @@ def _time(fn, iters):
     return e0.elapsed_time(e1) / iters
 
 
-def bench_gemm(names, m, iters):
+def bench_gemm(names, m, iters, shape=None, vendor=False):
     gen = torch.Generator(device="cuda").manual_seed(1)
+    shapes = dict(GEMM_SHAPES)
+    if shape is not None:
+        names = ["custom"]
+        shapes["custom"] = (shape[0], shape[1], pop.EPI_STORE_BF16)
     for name in names:
-        n, k, epi = GEMM_SHAPES[name]
+        n, k, epi = shapes[name]
         a = torch.randn(m, k, device="cuda", generator=gen).to(torch.bfloat16)
         rows = 2 * n if epi == pop.EPI_GLU_BF16 else n
         w = (torch.randn(rows, k, device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
         out = torch.zeros(m, n, dtype=torch.float32 if epi == pop.EPI_ADD_F32 else torch.bfloat16, device="cuda")
-        ms = _time(lambda: pop.pop_op_gemm(a, w, epilogue=epi, out=out), iters)
+        if vendor:
+            c = torch.empty(m, rows, dtype=torch.bfloat16, device="cuda")
+            wt = w.t()
+            ms = _time(lambda: torch.matmul(a, wt, out=c), iters)
+        else:
+            ms = _time(lambda: pop.pop_op_gemm(a, w, epilogue=epi, out=out), iters)
         flops = 2.0 * m * k * rows
-        print(f"gemm {name:8s} M={m} N={n} K={k} epilogue={epi}: {ms * 1e3:8.1f} us  "
+        print(f"{'torch.matmul' if vendor else 'gemm'} {name:8s} M={m} N={n} K={k} epilogue={epi}: {ms * 1e3:8.1f} us  "
               f"{flops / ms / 1e9:7.1f} TFLOP/s ({flops / ms / 1e9 / 2500 * 100:4.1f} % of 2.5 PFLOP/s)", flush=True)
 
 
@@ -73,6 +85,8 @@ def main(argv=None):
     g.add_argument("names", nargs="*", default=list(GEMM_SHAPES))
     g.add_argument("--m", type=int, default=2048)
     g.add_argument("--iters", type=int, default=20)
+    g.add_argument("--shape", type=int, nargs=2, metavar=("N", "K"))
+    g.add_argument("--vendor", action="store_true")
     a = sub.add_parser("attention")
     a.add_argument("--tokens", type=int, default=8192)
     a.add_argument("--heads", type=int, default=32)
@@ -84,7 +98,7 @@ def main(argv=None):
     if not torch.cuda.is_available():
         sys.exit("opbench needs a GPU")
     if args.what == "gemm":
-        bench_gemm(args.names, args.m, args.iters)
+        bench_gemm(args.names, args.m, args.iters, args.shape, args.vendor)
     else:
         bench_attention(args.tokens, args.heads, args.kv_heads, args.head_dim, args.window, args.iters)
 
