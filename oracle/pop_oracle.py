@@ -15,6 +15,11 @@ What follows what:
                               ("Boundary Handling for the Last Input Token").
   * `decode_step`          -- Sec. 3.2, the decode operator: one token through all L layers,
                               appending its K/V and producing next-token logits.
+  * `skip_set_prefill`     -- Sec. 2.2 (identity through every layer of a general S_skip) applied
+                              to the prefill stage only, with the switches of the ablation study
+                              (Sec. 4.4): independent KV projections on/off, boundary handling
+                              on/off.  `decode_step_at` is the decode operator on the cache this
+                              leaves (entries may be missing for a layer's prompt body).
   * `slot_map`             -- where entry t of sequence b lives in a paged cache (the paper's
                               cache append is a plain concatenation; paging is the serving
                               layout used by the workloads here).
@@ -34,6 +39,15 @@ Readings of points the paper leaves open (each is listed in the design notes as 
     rope_theta_local and the sliding window.
   * The boundary token runs every layer normally: its own K/V in deep layers come from its true
     layer input, and it attends to the projected body entries plus its own.
+  * General S_skip: a pruned layer l projects K/V from its own input x_l, which is the output of
+    the nearest kept layer below it (the embedding if there is none); pruned layers that follow
+    each other share that input, pruned layers separated by a kept layer do not.
+  * Without independent KV projections a pruned layer holds no entries for the prompt body:
+    positions keep their absolute values (RoPE of the last prompt token still uses N-1), the
+    entries of earlier positions are simply absent from that layer's attention.
+  * Without boundary handling the last prompt token is one more body row, and the first
+    generated token comes from the final norm and LM head applied to the pruned model's output
+    for that row.
 
 Parity pins for every function here live in tests/test_oracle_pins.py (brute force on a
 2-layer / 8-token model, a composition of torch library routines for L_keep = L, closed forms
@@ -87,16 +101,16 @@ def layer_theta_window(cfg: Dict, l: int) -> Tuple[float, int]:
 
 
 def attention_rows(q: np.ndarray, q_pos: np.ndarray, K: np.ndarray, V: np.ndarray,
-                   window: int) -> np.ndarray:
+                   window: int, k_pos: Optional[np.ndarray] = None) -> np.ndarray:
     """Attn of Sec. 2.1 for query rows q [n, Hq, hd] at positions q_pos against cache entries
-    K, V [m, Hkv, hd] at positions 0..m-1.  Row t sees j <= q_pos[t] (and j > q_pos[t] - window
-    when window > 0).  Returns [n, Hq * hd]."""
+    K, V [m, Hkv, hd] at positions k_pos (0..m-1 if not given).  Row t sees the entries at
+    positions j <= q_pos[t] (and j > q_pos[t] - window when window > 0).  Returns [n, Hq * hd]."""
     n, hq, hd = q.shape
     m, hkv, _ = K.shape
     group = hq // hkv
     if n == 0:
         return np.zeros((0, hq * hd), dtype=q.dtype)
-    j = np.arange(m)[None, :]
+    j = (np.arange(m) if k_pos is None else np.asarray(k_pos))[None, :]
     allowed = j <= q_pos[:, None]
     if window > 0:
         allowed &= j > (q_pos[:, None] - window)
@@ -141,10 +155,10 @@ def project_kv(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray):
 
 
 def kept_layer_rows(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray,
-                    K_past: np.ndarray, V_past: np.ndarray):
+                    K_past: np.ndarray, V_past: np.ndarray, past_pos: Optional[np.ndarray] = None):
     """One full layer (Sec. 2.1) for rows x [n, d] at positions pos, given the cache entries of
-    earlier positions K_past, V_past [m, Hkv, hd] with m == pos[0].  The rows' own K/V are
-    appended first, attention then runs on the updated cache.
+    earlier positions K_past, V_past [m, Hkv, hd] (positions past_pos; 0..m-1 with m == pos[0] if
+    not given).  The rows' own K/V are appended first, attention then runs on the updated cache.
     Returns (x_next [n, d], K_current, V_current)."""
     dt = x.dtype
     hq, hd = cfg["n_q_heads"], cfg["head_dim"]
@@ -154,7 +168,8 @@ def kept_layer_rows(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray,
     k_new, v_new = project_kv(cfg, lw, l, x, pos)
     K_cur = np.concatenate([K_past, k_new], axis=0)
     V_cur = np.concatenate([V_past, v_new], axis=0)
-    o = attention_rows(q, pos, K_cur, V_cur, window)
+    cur_pos = None if past_pos is None else np.concatenate([np.asarray(past_pos, dtype=np.int64), pos])
+    o = attention_rows(q, pos, K_cur, V_cur, window, cur_pos)
     y = x + o @ _w(lw, "wo", dt).T
     m = rmsnorm(y, _w(lw, "norm_post", dt), cfg["rms_eps"])
     ffn = (glu_act(m @ _w(lw, "w_gate", dt).T, cfg["act"]) * (m @ _w(lw, "w_up", dt).T)) \
@@ -242,6 +257,69 @@ def pop_prefill(cfg: Dict, W: Dict, tokens: np.ndarray, l_keep: int, dtype=np.fl
     Kc, Vc, _ = body_prefill(cfg, W, h[:n - 1], l_keep)
     logits, Kc, Vc = decode_step(cfg, W, h[n - 1], Kc, Vc)
     return Kc, Vc, logits
+
+
+# ----------------------------------------------------------------------------- general skip sets
+def skip_set_body(cfg: Dict, W: Dict, h: np.ndarray, skip: Sequence[int], kv_projection: bool = True):
+    """Prefill of body rows h [n, d] (positions 0..n-1) with the layers of `skip` (1-based) pruned:
+    x_{l+1} = x_l for l in S_skip (Sec. 2.2), every other layer in full (Sec. 2.1).  A pruned layer
+    stores the independent KV projections of its own input x_l (Sec. 3.3) or, with
+    kv_projection=False, nothing at all (the ablation without KV projections, Sec. 4.4).
+    Returns (cache, x): cache[l-1] = (positions, K, V) with K, V [m, Hkv, hd]; m = 0 for a pruned
+    layer without projections."""
+    L, hkv, hd = cfg["n_layers"], cfg["n_kv_heads"], cfg["head_dim"]
+    skip = set(int(l) for l in skip)
+    if any(l < 1 or l > L for l in skip):
+        raise ValueError("skip set outside 1..L")
+    n = h.shape[0]
+    pos = np.arange(n)
+    empty = np.zeros((0, hkv, hd), dtype=h.dtype)
+    cache = []
+    x = h
+    for l in range(1, L + 1):
+        lw = W["layers"][l - 1]
+        if l not in skip:
+            x, K, V = kept_layer_rows(cfg, lw, l, x, pos, empty, empty)
+            cache.append((pos, K, V))
+        elif kv_projection:
+            x, K, V = kv_only_rows(cfg, lw, l, x, pos)
+            cache.append((pos, K, V))
+        else:
+            cache.append((pos[:0], empty, empty))
+    return cache, x
+
+
+def decode_step_at(cfg: Dict, W: Dict, h_tok: np.ndarray, position: int, cache):
+    """The decode operator (Sec. 3.2) for one token at absolute position `position` against a
+    cache whose layers may lack entries: every layer in full, attention over whatever entries the
+    layer holds plus the token's own.  Returns (logits [V], cache with the token appended)."""
+    x = h_tok[None, :]
+    pos = np.array([position])
+    new = []
+    for l in range(1, cfg["n_layers"] + 1):
+        kp, K, V = cache[l - 1]
+        x, K2, V2 = kept_layer_rows(cfg, W["layers"][l - 1], l, x, pos, K, V, kp)
+        new.append((np.concatenate([np.asarray(kp, dtype=np.int64), pos]), K2, V2))
+    return lm_head_logits(cfg, W, x)[0], new
+
+
+def skip_set_prefill(cfg: Dict, W: Dict, tokens: np.ndarray, skip: Sequence[int],
+                     kv_projection: bool = True, boundary: bool = True, dtype=np.float64):
+    """Prefill-only pruning with a general skip set and the ablation switches (Sec. 2.2, 3.3,
+    4.4).  boundary=True: x_{1:N-1} through the pruned model, x_N through the full model as the
+    first decode step.  boundary=False: all N rows through the pruned model, logits from the last
+    row's pruned output.  Returns (cache, logits) with cache[l-1] = (positions, K, V)."""
+    n = len(tokens)
+    if n < 1:
+        raise ValueError("empty prompt")
+    h = embed_rows(W, tokens, dtype)
+    if boundary:
+        cache, _ = skip_set_body(cfg, W, h[:n - 1], skip, kv_projection)
+        logits, cache = decode_step_at(cfg, W, h[n - 1], n - 1, cache)
+    else:
+        cache, x = skip_set_body(cfg, W, h, skip, kv_projection)
+        logits = lm_head_logits(cfg, W, x[-1:])[0]
+    return cache, logits
 
 
 def greedy_generate(cfg: Dict, W: Dict, tokens: np.ndarray, l_keep: int, n_new: int, eos: int = -1,

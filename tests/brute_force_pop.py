@@ -11,11 +11,15 @@ import math
 from functools import lru_cache
 
 
-def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None):
+def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_projection=True, boundary=True):
     """Returns (K, V, logits) with K[l][t][head][i] python floats (l 0-based layer index).
     `tokens` may extend beyond the prompt (first n_prompt entries): later tokens are decode steps and,
     like the last prompt token, run every layer in full (Sec. 3.2: decoding keeps the full model).
-    logits are those of the last given token."""
+    logits are those of the last given token.
+    `skip` (a set of 1-based layers, Sec. 2.2) replaces the deep block l_keep+1..L as the pruned set.
+    kv_projection=False: a pruned layer keeps no entry for a pruned token (K[l][t] is None and the
+    entry is absent from attention); boundary=False: the last prompt token is pruned like the
+    others (the two ablations of Sec. 4.4)."""
     L, d = cfg["n_layers"], cfg["d_model"]
     Hq, Hkv, hd, f = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"]
     eps = cfg["rms_eps"]
@@ -52,10 +56,16 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None):
             return g / (1.0 + math.exp(-g))
         return 0.5 * g * (1.0 + math.tanh(math.sqrt(2.0 / math.pi) * (g + 0.044715 * g * g * g)))
 
+    pruned_layers = set(range(l_keep + 1, L + 1)) if skip is None else set(skip)
+    n_pruned_tokens = n_prompt - 1 if boundary else n_prompt
+
     def runs_full(l, t):
-        """Does token t run layer l (1-based) in full?  The body is pruned beyond l_keep, the last
-        prompt token never is."""
-        return l <= l_keep or t >= n_prompt - 1
+        """Does token t run layer l (1-based) in full?  The body is pruned in the layers of the skip
+        set; the last prompt token (with boundary handling) and generated tokens never are."""
+        return l not in pruned_layers or t >= n_pruned_tokens
+
+    def has_entry(l, t):
+        return kv_projection or runs_full(l, t)
 
     @lru_cache(maxsize=None)
     def x_in(l, t):
@@ -92,7 +102,7 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None):
             q = rot(qf[i * hd:(i + 1) * hd], t, theta)
             g = i // (Hq // Hkv)
             js = [j for j in range(t + 1)
-                  if is_global(l) or j > t - cfg["sliding_window"]]
+                  if (is_global(l) or j > t - cfg["sliding_window"]) and has_entry(l, j)]
             sc = [sum(a_ * b_ for a_, b_ in zip(q, key(l, j)[g])) / math.sqrt(hd) for j in js]
             mx = max(sc)
             ex = [math.exp(s - mx) for s in sc]
@@ -105,7 +115,7 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None):
         u = [act(g_) * u_ for g_, u_ in zip(gate, up)]
         return tuple(yi + di for yi, di in zip(y, matvec(p["w_down"], u)))
 
-    K = [[[list(h) for h in key(l, t)] for t in range(N)] for l in range(1, L + 1)]
-    V = [[[list(h) for h in val(l, t)] for t in range(N)] for l in range(1, L + 1)]
+    K = [[[list(h) for h in key(l, t)] if has_entry(l, t) else None for t in range(N)] for l in range(1, L + 1)]
+    V = [[[list(h) for h in val(l, t)] if has_entry(l, t) else None for t in range(N)] for l in range(1, L + 1)]
     logits = matvec(lm, norm(x_in(L + 1, N - 1), fin))
     return K, V, logits

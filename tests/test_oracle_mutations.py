@@ -42,16 +42,16 @@ def _rms_no_gamma(x, g, eps):
     return O_rms(x, np.ones_like(g), eps)
 
 
-def _attn_wrong_group(q, q_pos, K, V, window):
-    return O_attn(q[:, ::-1], q_pos, K, V, window)
+def _attn_wrong_group(q, q_pos, K, V, window, k_pos=None):
+    return O_attn(q[:, ::-1], q_pos, K, V, window, k_pos)
 
 
-def _attn_no_self(q, q_pos, K, V, window):
-    return O_attn(q, np.maximum(q_pos - 1, 0), K, V, window)
+def _attn_no_self(q, q_pos, K, V, window, k_pos=None):
+    return O_attn(q, np.maximum(q_pos - 1, 0), K, V, window, k_pos)
 
 
-def _attn_window_off_by_one(q, q_pos, K, V, window):
-    return O_attn(q, q_pos, K, V, window + 1 if window else 0)
+def _attn_window_off_by_one(q, q_pos, K, V, window, k_pos=None):
+    return O_attn(q, q_pos, K, V, window + 1 if window else 0, k_pos)
 
 
 def _kv_only_changes_x(cfg, lw, l, x, pos):
@@ -92,3 +92,53 @@ def test_planted_boundary_mistakes_are_caught(monkeypatch):
         return Kc, Vc, O.lm_head_logits(cfg, W, x[-1:])[0]
     monkeypatch.setattr(O, "pop_prefill", pruned_boundary)
     assert not pin_holds()
+
+
+# ------------------------------------------------------------------ general skip sets and switches
+def skip_pin_holds(skip=(1, 3), kv_projection=True, boundary=True, **cfg_kw):
+    cfg = micro_cfg(n_layers=4, **cfg_kw)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 7, seed=5)
+    Kb, Vb, lb = brute_force_pop(cfg, w, tokens.tolist(), 0, skip=skip, kv_projection=kv_projection, boundary=boundary)
+    cache, logits = O.skip_set_prefill(cfg, w, tokens, skip, kv_projection, boundary)
+    for l, (kp, K, V) in enumerate(cache):
+        present = [t for t in range(7) if Kb[l][t] is not None]
+        if list(kp) != present:
+            return False
+        if present and not (np.allclose(K, np.array([Kb[l][t] for t in present]), rtol=1e-9, atol=1e-11)
+                            and np.allclose(V, np.array([Vb[l][t] for t in present]), rtol=1e-9, atol=1e-11)):
+            return False
+    return bool(np.allclose(logits, np.array(lb), rtol=1e-9, atol=1e-11))
+
+
+def test_planted_skip_set_mistakes_are_caught(monkeypatch):
+    assert skip_pin_holds() and skip_pin_holds(kv_projection=False) and skip_pin_holds(boundary=False)
+    real_body, real_decode = O.skip_set_body, O.decode_step_at
+
+    def frozen_input(cfg, W, h, skip, kv_projection=True):
+        """every pruned layer projects the embeddings instead of its own input"""
+        cache, x = real_body(cfg, W, h, skip, kv_projection)
+        if kv_projection:
+            for l in skip:
+                _, K, V = O.kv_only_rows(cfg, W["layers"][l - 1], l, h, np.arange(h.shape[0]))
+                cache[l - 1] = (cache[l - 1][0], K, V)
+        return cache, x
+    monkeypatch.setattr(O, "skip_set_body", frozen_input)
+    assert not skip_pin_holds()
+    monkeypatch.setattr(O, "skip_set_body", real_body)
+
+    def relative_position(cfg, W, h_tok, position, cache):
+        """the token's position taken as the number of entries of the first layer"""
+        return real_decode(cfg, W, h_tok, len(cache[0][0]), cache)
+    monkeypatch.setattr(O, "decode_step_at", relative_position)
+    assert not skip_pin_holds(skip=(1, 3), kv_projection=False)
+    monkeypatch.setattr(O, "decode_step_at", real_decode)
+
+    def attends_missing(q, q_pos, K, V, window, k_pos=None):
+        """entry positions ignored: the window of a local layer then cuts the wrong entries"""
+        return O_attn(q, q_pos, K, V, window, None)
+    local = dict(sliding_window=3, global_every=4, rope_theta_local=50.0)
+    assert skip_pin_holds(skip=(2,), kv_projection=False, **local)
+    monkeypatch.setattr(O, "attention_rows", attends_missing)
+    with np.errstate(all="ignore"):
+        assert not skip_pin_holds(skip=(2,), kv_projection=False, **local)

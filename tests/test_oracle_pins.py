@@ -430,3 +430,132 @@ def test_greedy_generation_eos_and_forcing():
     other = [(int(t) + 1) % cfg["vocab"] for t in free]
     _, l_other, _, _ = O.greedy_generate(cfg, w, prompt, 2, 6, forced=other)
     assert np.allclose(l_other[0], l_same[0]) and not np.allclose(l_other[1], l_same[1])
+
+
+# ------------------------------------------------------------------ general skip sets, ablation switches
+def _cache_matches_brute_force(cache, Kb, Vb):
+    """cache[l] = (positions, K, V) against brute-force K[l][t] (None where no entry exists)."""
+    for l, (kp, K, V) in enumerate(cache):
+        present = [t for t in range(len(Kb[l])) if Kb[l][t] is not None]
+        assert list(kp) == present, f"layer {l + 1}: entries at {list(kp)}, expected {present}"
+        if present:
+            np.testing.assert_allclose(K, np.array([Kb[l][t] for t in present]), rtol=1e-10, atol=1e-12)
+            np.testing.assert_allclose(V, np.array([Vb[l][t] for t in present]), rtol=1e-10, atol=1e-12)
+
+
+SKIP_SETS = {"deep": (3, 4), "shallow": (1,), "interleaved": (2, 4), "mixed": (1, 3), "none": (), "all": (1, 2, 3, 4)}
+
+
+@pytest.mark.parametrize("which", list(SKIP_SETS))
+@pytest.mark.parametrize("kv_projection,boundary", [(True, True), (False, True), (True, False), (False, False)])
+def test_skip_set_prefill_matches_brute_force(which, kv_projection, boundary):
+    """Sec. 2.2 (identity through S_skip) in prefill only, independent KV projections and boundary
+    handling of Sec. 3.3 switched on and off as in the ablation study (Sec. 4.4): scalar
+    recomputation from the definitions on a 4-layer / 7-token model with a sliding-window layer."""
+    cfg = micro_cfg(n_layers=4, sliding_window=4, global_every=2, rope_theta_local=50.0)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 7, seed=5)
+    skip = SKIP_SETS[which]
+    Kb, Vb, lb = brute_force_pop(cfg, w, tokens.tolist(), 0, skip=skip, kv_projection=kv_projection,
+                                 boundary=boundary)
+    cache, logits = O.skip_set_prefill(cfg, w, tokens, skip, kv_projection, boundary)
+    _cache_matches_brute_force(cache, Kb, Vb)
+    np.testing.assert_allclose(logits, np.array(lb), rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("kv_projection", [True, False])
+def test_decode_after_skip_set_prefill_matches_brute_force(kv_projection):
+    """Decoding keeps every layer (Sec. 3.2, 3.3) whatever was pruned in prefill: two decode steps after
+    an interleaved-pruned prefill, against the scalar recomputation of all nine tokens."""
+    cfg = micro_cfg(n_layers=3)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 9, seed=6)
+    n_prompt = 7
+    cache, _ = O.skip_set_prefill(cfg, w, tokens[:n_prompt], (1, 3), kv_projection)
+    for t in range(n_prompt, 9):
+        logits, cache = O.decode_step_at(cfg, w, O.embed_rows(w, tokens[t:t + 1], np.float64)[0], t, cache)
+    Kb, Vb, lb = brute_force_pop(cfg, w, tokens.tolist(), 0, n_prompt=n_prompt, skip=(1, 3),
+                                 kv_projection=kv_projection)
+    _cache_matches_brute_force(cache, Kb, Vb)
+    np.testing.assert_allclose(logits, np.array(lb), rtol=1e-10, atol=1e-12)
+
+
+def test_deep_skip_set_is_pop_prefill_and_empty_skip_set_is_library_prefill():
+    """S_skip = {L_keep+1..L} with both switches on is POP itself (Sec. 3.3); S_skip = {} is the unpruned
+    model, which the composition of torch library routines pins."""
+    cfg = small_cfg()
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 12, seed=2)
+    Kc, Vc, logits = O.pop_prefill(cfg, w, tokens, 2)
+    cache, lg = O.skip_set_prefill(cfg, w, tokens, (3, 4))
+    np.testing.assert_allclose(stack([c[1] for c in cache]), stack(Kc), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(stack([c[2] for c in cache]), stack(Vc), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(lg, logits, rtol=1e-12, atol=1e-14)
+    Kt, Vt, lt = torch_reference_prefill(cfg, w, tokens)
+    cache, lg = O.skip_set_prefill(cfg, w, tokens, ())
+    np.testing.assert_allclose(stack([c[1] for c in cache]), Kt, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(stack([c[2] for c in cache]), Vt, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(lg, lt, rtol=1e-9, atol=1e-11)
+
+
+def test_no_kv_projection_boundary_token_sees_only_itself():
+    """Without KV projections a pruned layer's attention for the last prompt token runs over a single
+    entry, so its output is that entry's value vector whatever the scores are (softmax of one element):
+    a one-layer model with that layer pruned has the closed form
+    y = x + W_O repeat(v(x)),  out = y + FFN(LN(y)),  written here with torch library calls."""
+    cfg = micro_cfg(n_layers=1)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 6, seed=8)
+    cache, logits = O.skip_set_prefill(cfg, w, tokens, (1,), kv_projection=False)
+    assert list(cache[0][0]) == [5]
+    lw = w["layers"][0]
+    dt = torch.float64
+    x = w["embed"].to(dt)[int(tokens[-1])]
+    a = F.rms_norm(x, (cfg["d_model"],), lw["norm_in"].to(dt), cfg["rms_eps"])
+    v = F.linear(a, lw["wv"].to(dt)).view(cfg["n_kv_heads"], cfg["head_dim"])
+    o = v.repeat_interleave(cfg["n_q_heads"] // cfg["n_kv_heads"], dim=0).reshape(-1)
+    y = x + F.linear(o, lw["wo"].to(dt))
+    m = F.rms_norm(y, (cfg["d_model"],), lw["norm_post"].to(dt), cfg["rms_eps"])
+    out = y + F.linear(F.silu(F.linear(m, lw["w_gate"].to(dt))) * F.linear(m, lw["w_up"].to(dt)), lw["w_down"].to(dt))
+    ref = F.linear(F.rms_norm(out, (cfg["d_model"],), w["final_norm"].to(dt), cfg["rms_eps"]), w["lm_head"].to(dt))
+    np.testing.assert_allclose(logits, ref.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(cache[0][2][0], v.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_no_boundary_handling_all_layers_pruned_is_lm_head_of_embedding():
+    """Every layer pruned and no boundary handling: the last token's hidden state is its embedding
+    (Sec. 2.2, identity), so the logits are the LM head of the normed embedding row."""
+    cfg = small_cfg()
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 5, seed=9)
+    _, logits = O.skip_set_prefill(cfg, w, tokens, (1, 2, 3, 4), boundary=False)
+    dt = torch.float64
+    e = w["embed"].to(dt)[int(tokens[-1])]
+    ref = F.linear(F.rms_norm(e, (cfg["d_model"],), w["final_norm"].to(dt), cfg["rms_eps"]), w["lm_head"].to(dt))
+    np.testing.assert_allclose(logits, ref.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_interleaved_pruned_layers_project_different_inputs():
+    """Pruned layers separated by a kept layer see different inputs: layer 1 projects the embeddings,
+    layer 3 the output of layer 2 (Sec. 2.2: x_{l+1} = x_l only across the pruned layer itself)."""
+    cfg = small_cfg()
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 10, seed=4)
+    cache, _ = O.skip_set_prefill(cfg, w, tokens, (1, 3))
+    dt = torch.float64
+    e = w["embed"].to(dt)[torch.as_tensor(tokens[:-1], dtype=torch.long)]
+    lw = w["layers"][0]
+    v1 = F.linear(F.rms_norm(e, (cfg["d_model"],), lw["norm_in"].to(dt), cfg["rms_eps"]), lw["wv"].to(dt))
+    np.testing.assert_allclose(cache[0][2][:-1].reshape(9, -1), v1.numpy(), rtol=1e-10, atol=1e-12)
+    # layer 2 is kept and its input is the embedding: its K/V equal those of an unpruned model whose first
+    # layer is an exact identity (both of its residual branches zeroed)
+    w_id = copy.deepcopy(w)
+    w_id["layers"][0]["wo"] = torch.zeros_like(w_id["layers"][0]["wo"])
+    w_id["layers"][0]["w_down"] = torch.zeros_like(w_id["layers"][0]["w_down"])
+    Kt, Vt, _ = torch_reference_prefill(cfg, w_id, tokens[:-1])
+    np.testing.assert_allclose(cache[1][1][:-1], Kt[1], rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(cache[1][2][:-1], Vt[1], rtol=1e-9, atol=1e-11)
+    # layer 3 projects the output of layer 2, which differs from the embedding
+    lw3 = w["layers"][2]
+    v3_from_e = F.linear(F.rms_norm(e, (cfg["d_model"],), lw3["norm_in"].to(dt), cfg["rms_eps"]), lw3["wv"].to(dt))
+    assert np.max(np.abs(cache[2][2][:-1].reshape(9, -1) - v3_from_e.numpy())) > 1e-3
