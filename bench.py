@@ -109,6 +109,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ttft-sweep", action="store_true",
                     help="skip the batch-8 time-to-first-token sweep over prompt lengths (Table 2's shape)")
+    ap.add_argument("--no-ablation-sweep", action="store_true",
+                    help="skip timing the layer-selection variants and switches of the paper's ablation study")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (calibrates the FETCH_SIZE / "
@@ -229,6 +231,34 @@ def main():
                      "flops_per_launch": gu_flops, "avg_launch_ms": gu_ms},
         "breakdown": breakdown,
     }
+    if not args.no_ablation_sweep:
+        # the prefill variants of the paper's ablation study (Sec. 4.4), a third of the layers pruned in
+        # each: which layers (deep block = the method, first third, every third layer) and the two switches.
+        # Only their time is measured here; what they do to accuracy needs trained weights.
+        third = L - (2 * L) // 3
+        variants = {
+            "deep (the method)": dict(skip_layers=list(range(L - third + 1, L + 1))),
+            "shallow": dict(skip_layers=list(range(1, third + 1))),
+            "interleaved": dict(skip_layers=list(range(3, L + 1, 3))),
+            "deep, no KV projections": dict(skip_layers=list(range(L - third + 1, L + 1)), no_kv_projection=True),
+            "deep, no boundary handling": dict(skip_layers=list(range(L - third + 1, L + 1)), mode=pop.MODE_NO_BOUNDARY),
+        }
+        abl = {}
+        for name, kw in variants.items():
+            def run_variant():
+                pop.pop_prefill(model, cache, tokens, cu, bt, 0, ws, logits=logits, stream=stream, **kw)
+            for _ in range(2):
+                run_variant()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(5):
+                run_variant()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            abl[name] = {"pruned_layers": len(kw["skip_layers"]), "ms_per_prompt": ms, "speedup_vs_full_depth": full_ms / ms}
+        out["ablation_timing"] = abl
     if not args.no_ttft_sweep:
         # time to first token of a batch of 8 equal-length prompts, pruned (last third of the layers
         # skipped for the body, the paper's static policy) against full depth: the shape of the paper's

@@ -149,23 +149,45 @@ typedef struct {
   const int32_t* embed_ranges; /* HOST [n_ranges][3] = (seq, first_pos, count), rows of `embeds`
                                   consumed in this order; ranges must not overlap                   */
   int32_t n_ranges;
-  int32_t l_keep;              /* 0 .. n_layers: layers 1..l_keep are kept for the body             */
+  int32_t l_keep;              /* 0 .. n_layers: layers 1..l_keep are kept for the body, the deep
+                                  block l_keep+1..L is pruned (ignored when skip_layers is given)   */
   int32_t mode;                /* POP_MODE_POP: the last token of each sequence is the boundary token:
                                   full depth, logits returned.
-                                  POP_MODE_BODY_ONLY: every given token is a body token (pruned
-                                  beyond l_keep); no logits.  pop_decode_step on the next token then
-                                  completes the same computation.                                   */
+                                  POP_MODE_BODY_ONLY: every given token is a body token (pruned in
+                                  the pruned layers); no logits.  pop_decode_step on the next token
+                                  then completes the same computation.
+                                  POP_MODE_NO_BOUNDARY (ablation, Sec. 4.4): every given token is a
+                                  body token and the logits are the final norm and LM head of the
+                                  pruned model's output for each sequence's last token.             */
+  /* The fields below may be left zero: zero means the method as published. */
+  const int32_t* skip_layers;  /* HOST [n_skip] or NULL.  A general skip set (Sec. 2.2), applied to
+                                  the body tokens of the prefill only: 1-based layer indices,
+                                  strictly increasing.  A pruned layer passes its input on unchanged
+                                  and stores the K/V projections of that input (Sec. 3.3), so pruned
+                                  layers separated by a kept layer project different hidden states.
+                                  NULL: the deep block given by l_keep.  Non-NULL with n_skip = 0:
+                                  nothing is pruned.                                                */
+  int32_t n_skip;
+  int32_t no_kv_projection;    /* 1 (ablation, Sec. 4.4): pruned layers store nothing for body
+                                  tokens; the boundary token and every later token then see, in
+                                  those layers, only the entries from the first full-depth token on
+                                  (positions stay absolute).  0: independent KV projections.        */
 } pop_prefill_args;
-enum { POP_MODE_POP = 0, POP_MODE_BODY_ONLY = 1 };
+enum { POP_MODE_POP = 0, POP_MODE_BODY_ONLY = 1, POP_MODE_NO_BOUNDARY = 2 };
 
 /*
  * Pruned prefill (Sec. 3.3).  Starts sequences 0..n_seqs-1 from empty (a cache that was in use is
  * reset), writes the K/V entries of all n_layers layers for every given token and, in POP mode, the
  * boundary tokens' next-token logits.
  *   dev_logits   DEVICE fp32 [n_seqs, vocab]; may be NULL in POP_MODE_BODY_ONLY.
+ * With no_kv_projection the cache pages of a pruned layer keep whatever they held at the body
+ * positions; the cache object remembers that those entries do not exist, and pop_decode_step /
+ * pop_generate honour it until the next pop_prefill.
  *   dev_workspace DEVICE scratch of at least pop_workspace_bytes(cfg, T, n_seqs, max_pages_per_seq).
- * Errors (all before any launch): POP_EINVAL (NULL, l_keep outside [0, L], n_seqs < 1 or above the
- * cache's max_seqs, an empty sequence, token id outside [0, vocab), bad embed range), POP_ENOSPACE
+ * Errors (all before any launch): POP_EINVAL (NULL, l_keep outside [0, L], skip_layers not strictly
+ * increasing or outside [1, L], n_skip without skip_layers, unknown mode or switch value, n_seqs < 1
+ * or above the cache's max_seqs, an empty sequence, token id outside [0, vocab), bad embed range),
+ * POP_ENOSPACE
  * (pages, workspace), POP_EALIGN.  POP_EHIP if a launch fails.
  */
 pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* args, float* dev_logits,
@@ -184,7 +206,7 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
 
 /*
  * Greedy generation (Sec. 3.2: prefill, then the decode loop with the full model): pop_prefill in
- * POP_MODE_POP, then max_new_tokens tokens per sequence.  Token 0 is the index of the largest
+ * POP_MODE_POP (or POP_MODE_NO_BOUNDARY), then max_new_tokens tokens per sequence.  Token 0 is the index of the largest
  * boundary-token logit (lowest index on ties); token s > 0 is chosen the same way from the logits
  * of a decode step on token s-1.  Once a sequence has produced eos_token (>= 0; pass -1 for none)
  * all its later tokens are eos_token (its steps are still computed, so all sequences stay in
@@ -195,7 +217,7 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
  *   dev_workspace  at least pop_generate_workspace_bytes(cfg, T, n_seqs, max_pages_per_seq, max_new_tokens)
  * The block table must assign pages for positions up to len_b + max_new_tokens - 2.  Afterwards the
  * cache holds len_b + max_new_tokens - 1 entries per sequence (the last chosen token is not fed).
- * Errors as pop_prefill, plus POP_EINVAL (max_new_tokens < 1, mode not POP_MODE_POP, eos_token >=
+ * Errors as pop_prefill, plus POP_EINVAL (max_new_tokens < 1, POP_MODE_BODY_ONLY, eos_token >=
  * vocab) and POP_ENOSPACE (pages for the generated tokens, workspace); all before any launch.
  */
 size_t pop_generate_workspace_bytes(const pop_config* cfg, int32_t max_tokens, int32_t max_seqs,

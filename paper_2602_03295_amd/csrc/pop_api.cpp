@@ -124,6 +124,10 @@ struct pop_cache {
   int n_seqs;                        // live sequences
   std::vector<int32_t> seq_lens;     // [max_seqs]
   std::vector<int32_t> block_table;  // [max_seqs][max_pages]
+  // First position that has an entry, per layer and sequence: 0 unless the layer was pruned without
+  // KV projections in the prefill, in which case nothing exists below the first full-depth token.
+  std::vector<int32_t> kv_first;     // [n_layers][max_seqs]
+  bool any_kv_first = false;
   size_t layer_stride() const {      // elements between the K pools of consecutive layers
     return 2 * pool_stride();
   }
@@ -145,7 +149,7 @@ struct Workspace {
   // int32 meta (one upload per call)
   size_t meta_bytes;
   size_t o_tokens, o_row_src, o_pos, o_slot, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start, o_ta_start2,
-      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_wlist;
+      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_wlist, o_kv_first;
   // device buffers
   size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_a_multi, o_kv_out;
   size_t o_xb, o_ab, o_qkvb, o_qb, o_attnb, o_ub, o_part;
@@ -185,6 +189,7 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_bnd_slot = take(4 * (size_t)B);
   w.o_bt = take(4 * (size_t)B * maxp);
   w.o_wlist = take(8 * (size_t)c.n_layers);
+  w.o_kv_first = take(4 * (size_t)c.n_layers * B);
   w.meta_bytes = o;
   w.o_h = take(4 * (size_t)T * d);
   w.o_a = take(2 * (size_t)T * d);
@@ -274,7 +279,58 @@ struct LayerCtx {
   void* ws;
   const Workspace* w;
   hipStream_t st;
+  const int32_t* kv_first = nullptr;  // DEVICE [n_layers][B] or nullptr (every layer holds every position)
 };
+
+// The prefill's pruning, resolved from the arguments (Sec. 2.2: a skip set; Sec. 3.3: applied to the
+// body tokens of the prefill only).
+struct PrunePlan {
+  std::vector<char> pruned;  // [n_layers + 2], 1-based
+  bool kv_projection;        // pruned layers store independent KV projections of the body
+  int n_pruned;
+};
+
+pop_status make_plan(const pop_config& cfg, const pop_prefill_args* a, PrunePlan* plan) {
+  const int L = cfg.n_layers;
+  if (a->mode != POP_MODE_POP && a->mode != POP_MODE_BODY_ONLY && a->mode != POP_MODE_NO_BOUNDARY)
+    return fail(POP_EINVAL, "unknown mode %d", a->mode);
+  if (a->no_kv_projection != 0 && a->no_kv_projection != 1)
+    return fail(POP_EINVAL, "no_kv_projection must be 0 or 1, got %d", a->no_kv_projection);
+  plan->pruned.assign((size_t)L + 2, 0);
+  plan->kv_projection = a->no_kv_projection == 0;
+  plan->n_pruned = 0;
+  if (a->skip_layers) {
+    if (a->n_skip < 0 || a->n_skip > L) return fail(POP_EINVAL, "n_skip %d outside [0, %d]", a->n_skip, L);
+    for (int i = 0; i < a->n_skip; ++i) {
+      const int l = a->skip_layers[i];
+      if (l < 1 || l > L) return fail(POP_EINVAL, "skip_layers[%d] = %d outside [1, %d]", i, l, L);
+      if (i > 0 && l <= a->skip_layers[i - 1])
+        return fail(POP_EINVAL, "skip_layers must be strictly increasing (entry %d)", i);
+      plan->pruned[l] = 1;
+    }
+    plan->n_pruned = a->n_skip;
+  } else {
+    if (a->n_skip != 0) return fail(POP_EINVAL, "n_skip %d given without skip_layers", a->n_skip);
+    if (a->l_keep < 0 || a->l_keep > L) return fail(POP_EINVAL, "l_keep %d outside [0, %d]", a->l_keep, L);
+    for (int l = a->l_keep + 1; l <= L; ++l) plan->pruned[l] = 1;
+    plan->n_pruned = L - a->l_keep;
+  }
+  return POP_OK;
+}
+
+// Records which positions exist per layer after this prefill and writes the device copy [L][B].
+void record_kv_first(pop_cache* c, const pop_prefill_args* a, const PrunePlan& plan, int32_t* meta_out) {
+  const int L = c->cfg.n_layers, B = a->n_seqs;
+  std::fill(c->kv_first.begin(), c->kv_first.end(), 0);
+  c->any_kv_first = !plan.kv_projection && plan.n_pruned > 0;
+  for (int l = 1; l <= L; ++l)
+    for (int b = 0; b < B; ++b) {
+      const int len = a->cu_seqlens[b + 1] - a->cu_seqlens[b];
+      const int first = (plan.pruned[l] && !plan.kv_projection) ? len - (a->mode == POP_MODE_POP ? 1 : 0) : 0;
+      c->kv_first[(size_t)(l - 1) * c->max_seqs + b] = first;
+      meta_out[(size_t)(l - 1) * B + b] = first;
+    }
+}
 
 // One decode-style layer for B rows held in xb (fp32 [B, d]); pos/slot are device arrays [B].
 pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32_t* pos, const int32_t* slot,
@@ -302,6 +358,7 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   ad.max_pages = x.c->max_pages;
   ad.page_size = c.page_size;
   ad.pos = pos;
+  ad.kv_first = x.kv_first ? x.kv_first + (size_t)(l - 1) * B : nullptr;
   ad.window = glob ? 0 : c.sliding_window;
   ad.B = B;
   ad.n_q_heads = c.n_q_heads;
@@ -336,7 +393,7 @@ pop_status lm_head(const LayerCtx& x, int B, float* dev_logits) {
 // ------------------------------------------------------------------------------- fp32 instantiation
 struct WorkspaceF32 {
   size_t meta_bytes;
-  size_t o_tokens, o_row_src, o_pos, o_slot, o_row_seq, o_bnd_row, o_bnd_pos, o_bnd_slot, o_bnd_seq, o_bt;
+  size_t o_tokens, o_row_src, o_pos, o_slot, o_row_seq, o_bnd_row, o_bnd_pos, o_bnd_slot, o_bnd_seq, o_bt, o_kv_first;
   size_t o_h, o_a, o_qkv, o_attn, o_u, o_xb, o_ab, o_qkvb, o_attnb, o_ub;
   size_t total;
 };
@@ -361,6 +418,7 @@ WorkspaceF32 carve_f32(const pop_config& c, int T, int B, int maxp) {
   w.o_bnd_slot = take(4 * (size_t)B);
   w.o_bnd_seq = take(4 * (size_t)B);
   w.o_bt = take(4 * (size_t)B * maxp);
+  w.o_kv_first = take(4 * (size_t)c.n_layers * B);
   w.meta_bytes = o;
   w.o_h = take(4 * (size_t)T * d);
   w.o_a = take(4 * (size_t)T * d);
@@ -382,6 +440,8 @@ struct CtxF32 {
   void* ws;
   const WorkspaceF32* w;
   hipStream_t st;
+  const int32_t* kv_first = nullptr;  // DEVICE [n_layers][B] or nullptr
+  int B = 0;                          // sequences (row stride of kv_first)
 };
 
 // One layer of Sec. 2.1 for `rows` rows of x (fp32 [rows, d], updated in place); a / qkv / attn / u are
@@ -400,7 +460,9 @@ pop_status layer_f32(const CtxF32& x, int l /*1-based*/, int rows, float* xh, fl
                        x.c->v_pool_f32(l - 1), c.page_size, rows, x.st);
   hipError_t e = F::launch_attention(qkv, Dqkv, 0, attn, row_seq, pos, x.c->k_pool_f32(l - 1), x.c->v_pool_f32(l - 1),
                                      at<int32_t>(x.ws, x.w->o_bt), x.c->max_pages, c.page_size,
-                                     glob ? 0 : c.sliding_window, rows, c.n_q_heads, c.n_kv_heads, hd, max_len, x.st);
+                                     glob ? 0 : c.sliding_window,
+                                     x.kv_first ? x.kv_first + (size_t)(l - 1) * x.B : nullptr, rows, c.n_q_heads,
+                                     c.n_kv_heads, hd, max_len, x.st);
   if (e != hipSuccess) return fail(POP_EHIP, "fp32 attention launch failed: %s", hipGetErrorString(e));
   F::launch_gemm(attn, Dq, (const float*)lw.wo, Dq, xh, d, rows, d, Dq, F::EPI_ADD, 0, x.st);
   F::launch_rmsnorm(xh, (const float*)lw.norm_post, a, nullptr, rows, d, c.rms_eps, x.st);
@@ -423,8 +485,8 @@ pop_status lm_head_f32(const CtxF32& x, int B, float* dev_logits) {
 }
 
 // pop_prefill for an fp32 model; arguments are already validated (slots, row_src computed by the caller)
-pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, float* dev_logits, void* ws,
-                       size_t workspace_bytes, hipStream_t st, const std::vector<int32_t>& slots,
+pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, const PrunePlan& plan, float* dev_logits,
+                       void* ws, size_t workspace_bytes, hipStream_t st, const std::vector<int32_t>& slots,
                        const std::vector<int32_t>& row_src) {
   const pop_config& cfg = m->cfg;
   const int B = a->n_seqs, maxp = c->max_pages, T = a->cu_seqlens[B];
@@ -454,6 +516,7 @@ pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   if (max_len > pop::f32::kMaxContext)
     return fail(POP_EUNSUPPORTED, "the fp32 path holds one row of scores in LDS: sequences up to %d tokens",
                 pop::f32::kMaxContext);
+  record_kv_first(c, a, plan, mi(w.o_kv_first));
   POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
   c->n_seqs = B;
   std::fill(c->seq_lens.begin(), c->seq_lens.end(), 0);
@@ -473,33 +536,54 @@ pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   const int32_t* d_pos = at<int32_t>(ws, w.o_pos);
   const int32_t* d_slot = at<int32_t>(ws, w.o_slot);
   CtxF32 x{m, c, ws, &w, st};
+  x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;
+  x.B = B;
   F::launch_embed((const float*)m->w.embed, at<int32_t>(ws, w.o_tokens),
                   a->n_ranges > 0 ? at<int32_t>(ws, w.o_row_src) : nullptr, (const float*)a->embeds, h, T, d, st);
-  // kept layers 1..l_keep over all rows (Sec. 2.1)
-  for (int l = 1; l <= a->l_keep; ++l)
-    if (pop_status s = layer_f32(x, l, T, h, abuf, qkv, attn, u, at<int32_t>(ws, w.o_row_seq), d_pos, d_slot, max_len))
-      return s;
-  // pruned layers: K/V from the layer's own norm scale, W^K, W^V and RoPE; h is not modified (Sec. 3.3)
-  for (int l = a->l_keep + 1; l <= cfg.n_layers; ++l) {
-    const pop_layer_weights& lw = m->layers[l - 1];
-    F::launch_rmsnorm(h, (const float*)lw.norm_in, abuf, nullptr, T, d, cfg.rms_eps, st);
-    F::launch_gemm(abuf, d, (const float*)lw.wqkv + (size_t)Dq * d, d, qkv, 2 * Dkv, T, 2 * Dkv, d, F::EPI_STORE, 0, st);
-    F::launch_rope_write(qkv, 2 * Dkv, -1, 0, Dkv, cfg.n_q_heads, cfg.n_kv_heads, hd, d_pos, d_slot,
-                         layer_is_global(cfg, l) ? (double)cfg.rope_theta : (double)cfg.rope_theta_local,
-                         c->k_pool_f32(l - 1), c->v_pool_f32(l - 1), cfg.page_size, T, st);
-  }
-  POP_HIP(hipGetLastError());
-  // boundary rows at full depth (Sec. 3.3, boundary handling)
-  if (a->mode == POP_MODE_POP) {
-    float* xb = at<float>(ws, w.o_xb);
-    pop::launch_gather_rows(h, at<int32_t>(ws, w.o_bnd_row), xb, B, d, st);
-    for (int l = a->l_keep + 1; l <= cfg.n_layers; ++l)
-      if (pop_status s = layer_f32(x, l, B, xb, at<float>(ws, w.o_ab), at<float>(ws, w.o_qkvb), at<float>(ws, w.o_attnb),
-                                   at<float>(ws, w.o_ub), at<int32_t>(ws, w.o_bnd_seq), at<int32_t>(ws, w.o_bnd_pos),
-                                   at<int32_t>(ws, w.o_bnd_slot), max_len))
+  // Layers in order.  A kept layer runs over all rows (Sec. 2.1).  A run of pruned layers leaves h alone
+  // (Sec. 2.2) and stores each layer's K/V projection of it with the layer's own norm scale, W^K, W^V and
+  // RoPE (Sec. 3.3); the boundary rows, which are never pruned, leave h for that run and pass its layers
+  // in full against the cache (Sec. 3.3, boundary handling), then return to their rows of h.
+  float* xb = at<float>(ws, w.o_xb);
+  const int32_t* bnd_row = at<int32_t>(ws, w.o_bnd_row);
+  const bool boundary = a->mode == POP_MODE_POP;
+  for (int l = 1; l <= cfg.n_layers;) {
+    if (!plan.pruned[l]) {
+      if (pop_status s = layer_f32(x, l, T, h, abuf, qkv, attn, u, at<int32_t>(ws, w.o_row_seq), d_pos, d_slot, max_len))
         return s;
+      ++l;
+      continue;
+    }
+    int r = l;
+    while (plan.pruned[r + 1]) ++r;
+    if (plan.kv_projection)
+      for (int j = l; j <= r; ++j) {
+        const pop_layer_weights& lw = m->layers[j - 1];
+        F::launch_rmsnorm(h, (const float*)lw.norm_in, abuf, nullptr, T, d, cfg.rms_eps, st);
+        F::launch_gemm(abuf, d, (const float*)lw.wqkv + (size_t)Dq * d, d, qkv, 2 * Dkv, T, 2 * Dkv, d, F::EPI_STORE, 0, st);
+        F::launch_rope_write(qkv, 2 * Dkv, -1, 0, Dkv, cfg.n_q_heads, cfg.n_kv_heads, hd, d_pos, d_slot,
+                             layer_is_global(cfg, j) ? (double)cfg.rope_theta : (double)cfg.rope_theta_local,
+                             c->k_pool_f32(j - 1), c->v_pool_f32(j - 1), cfg.page_size, T, st);
+      }
+    POP_HIP(hipGetLastError());
+    if (boundary) {
+      pop::launch_gather_rows(h, bnd_row, xb, B, d, st);
+      for (int j = l; j <= r; ++j)
+        if (pop_status s = layer_f32(x, j, B, xb, at<float>(ws, w.o_ab), at<float>(ws, w.o_qkvb), at<float>(ws, w.o_attnb),
+                                     at<float>(ws, w.o_ub), at<int32_t>(ws, w.o_bnd_seq), at<int32_t>(ws, w.o_bnd_pos),
+                                     at<int32_t>(ws, w.o_bnd_slot), max_len))
+          return s;
+      pop::launch_scatter_rows(xb, bnd_row, h, B, d, st);
+    }
+    l = r + 1;
+  }
+  // logits of each sequence's last row: the boundary token's (full depth), or, without boundary handling,
+  // the pruned model's output for it
+  if (a->mode != POP_MODE_BODY_ONLY) {
+    pop::launch_gather_rows(h, bnd_row, xb, B, d, st);
     if (pop_status s = lm_head_f32(x, B, dev_logits)) return s;
   }
+  POP_HIP(hipGetLastError());
   return POP_OK;
 }
 
@@ -521,6 +605,7 @@ pop_status decode_step_f32(pop_model* m, pop_cache* c, const int32_t* host_token
     max_len = std::max(max_len, pos + 1);
     std::copy(c->block_table.begin() + (size_t)b * maxp, c->block_table.begin() + (size_t)(b + 1) * maxp,
               mi(w.o_bt) + (size_t)b * maxp);
+    for (int l = 0; l < cfg.n_layers; ++l) mi(w.o_kv_first)[(size_t)l * B + b] = c->kv_first[(size_t)l * c->max_seqs + b];
   }
   if (max_len > pop::f32::kMaxContext)
     return fail(POP_EUNSUPPORTED, "the fp32 path holds one row of scores in LDS: sequences up to %d tokens",
@@ -528,6 +613,8 @@ pop_status decode_step_f32(pop_model* m, pop_cache* c, const int32_t* host_token
   POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
   for (int b = 0; b < B; ++b) c->seq_lens[b] += 1;
   CtxF32 x{m, c, ws, &w, st};
+  x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;
+  x.B = B;
   float* xb = at<float>(ws, w.o_xb);
   pop::f32::launch_embed((const float*)m->w.embed, at<int32_t>(ws, w.o_tokens), nullptr, nullptr, xb, B, cfg.d_model, st);
   for (int l = 1; l <= cfg.n_layers; ++l)
@@ -645,6 +732,7 @@ pop_status pop_cache_create(const pop_config* cfg, void* dev_pool, size_t bytes,
   c->n_seqs = 0;
   c->seq_lens.assign(max_seqs, 0);
   c->block_table.assign((size_t)max_seqs * max_pages_per_seq, -1);
+  c->kv_first.assign((size_t)cfg->n_layers * max_seqs, 0);
   *out = c;
   return POP_OK;
 }
@@ -675,10 +763,9 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   if (!a->tokens || !a->cu_seqlens || !a->block_table) return fail(POP_EINVAL, "tokens / cu_seqlens / block_table is NULL");
   if (a->n_seqs < 1 || a->n_seqs > c->max_seqs)
     return fail(POP_EINVAL, "n_seqs %d outside [1, %d]", a->n_seqs, c->max_seqs);
-  if (a->l_keep < 0 || a->l_keep > cfg.n_layers)
-    return fail(POP_EINVAL, "l_keep %d outside [0, %d]", a->l_keep, cfg.n_layers);
-  if (a->mode != POP_MODE_POP && a->mode != POP_MODE_BODY_ONLY) return fail(POP_EINVAL, "unknown mode %d", a->mode);
-  if (a->mode == POP_MODE_POP && !dev_logits) return fail(POP_EINVAL, "dev_logits is NULL");
+  PrunePlan plan;
+  if (pop_status ps = make_plan(cfg, a, &plan)) return ps;
+  if (a->mode != POP_MODE_BODY_ONLY && !dev_logits) return fail(POP_EINVAL, "dev_logits is NULL");
   if (dev_logits && !aligned16(dev_logits)) return fail(POP_EALIGN, "dev_logits not 16-byte aligned");
   if (!dev_workspace) return fail(POP_EINVAL, "dev_workspace is NULL");
   if (reinterpret_cast<uintptr_t>(dev_workspace) & 255) return fail(POP_EALIGN, "dev_workspace not 256-byte aligned");
@@ -716,8 +803,8 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     }
   }
   if (cfg.dtype == POP_DTYPE_F32)
-    return prefill_f32(m, c, a, dev_logits, dev_workspace, workspace_bytes, reinterpret_cast<hipStream_t>(stream), slots,
-                       row_src);
+    return prefill_f32(m, c, a, plan, dev_logits, dev_workspace, workspace_bytes, reinterpret_cast<hipStream_t>(stream),
+                       slots, row_src);
   const Workspace w = carve(cfg, T, B, maxp);
   if (workspace_bytes < w.total)
     return fail(POP_ENOSPACE, "workspace has %zu bytes, %zu needed for %d tokens in %d sequences", workspace_bytes,
@@ -755,6 +842,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     for (int l = 0; l < cfg.n_layers; ++l)
       wl[l] = reinterpret_cast<const bf16_t*>(m->layers[l].wqkv) + (size_t)Dq * d;  // rows W^K | W^V
   }
+  record_kv_first(c, a, plan, mi(w.o_kv_first));
 
   // ------------------------------------------------------------------ launches
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -809,8 +897,8 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   rw.tile_start = at<int32_t>(ws, w.o_t64_start);
   rw.n_tiles = n_t64;
 
-  // ---- kept layers 1..l_keep over all given rows (Sec. 2.1)
-  for (int l = 1; l <= a->l_keep; ++l) {
+  // ---- a kept layer over all given rows (Sec. 2.1)
+  auto kept_layer = [&](int l) -> pop_status {
     const pop_layer_weights& lw = m->layers[l - 1];
     const bool glob = layer_is_global(cfg, l);
     {
@@ -871,15 +959,17 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       StepTimer tm(m, st, POP_STEP_DOWN_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "down")) return s;
     }
-  }
+    return POP_OK;
+  };
 
-  // ---- pruned layers l_keep+1..L: independent KV projections of the frozen hidden state (Sec. 3.3)
-  {
-    bf16_t* a_multi = at<bf16_t>(ws, w.o_a_multi);
-    bf16_t* kv_out = at<bf16_t>(ws, w.o_kv_out);
-    const bf16_t* const* wlist = at<const bf16_t*>(ws, w.o_wlist);
-    for (int l0 = a->l_keep + 1; l0 <= cfg.n_layers; l0 += kKvChunk) {
-      const int n = std::min(kKvChunk, cfg.n_layers - l0 + 1);
+  // ---- a run l0..l1 of pruned layers: independent KV projections of the hidden state the run leaves
+  //      unchanged (Sec. 2.2, Sec. 3.3); the layers of a run share one normalisation pass and one batched GEMM
+  bf16_t* a_multi = at<bf16_t>(ws, w.o_a_multi);
+  bf16_t* kv_out = at<bf16_t>(ws, w.o_kv_out);
+  const bf16_t* const* wlist = at<const bf16_t*>(ws, w.o_wlist);
+  auto kv_only_run = [&](int first, int last) -> pop_status {
+    for (int l0 = first; l0 <= last; l0 += kKvChunk) {
+      const int n = std::min(kKvChunk, last - l0 + 1);
       pop::GammaList gl{};
       for (int j = 0; j < n; ++j) gl.g[j] = (const float*)m->layers[l0 - 1 + j].norm_in;
       {
@@ -908,17 +998,48 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       }
     }
     POP_HIP(hipGetLastError());
-  }
+    return POP_OK;
+  };
 
-  // ---- boundary tokens at full depth (Sec. 3.3, boundary handling): they rode along through the
-  //      kept layers (identical to their decode step there) and continue alone through the rest.
-  if (a->mode == POP_MODE_POP) {
+  // ---- layers in order.  The boundary tokens (Sec. 3.3, boundary handling) are rows of h through kept
+  //      layers (identical to their decode step there); through a run of pruned layers they leave h, pass
+  //      the run's layers in full against the cache, and return to their rows if a kept layer follows.
+  LayerCtx x{m, c, ws, &w, st};
+  x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;
+  const bool boundary = a->mode == POP_MODE_POP;
+  const int32_t* bnd_row = at<int32_t>(ws, w.o_bnd_row);
+  float* xb = at<float>(ws, w.o_xb);
+  bool rows_in_xb = false;   // the boundary rows' current state is in xb rather than in h
+  for (int l = 1; l <= cfg.n_layers;) {
+    if (!plan.pruned[l]) {
+      if (rows_in_xb) {
+        StepTimer tm(m, st, POP_STEP_BOUNDARY);
+        pop::launch_scatter_rows(xb, bnd_row, h, B, d, st);
+        rows_in_xb = false;
+      }
+      if (pop_status s = kept_layer(l)) return s;
+      ++l;
+      continue;
+    }
+    int r = l;
+    while (plan.pruned[r + 1]) ++r;
+    if (plan.kv_projection)
+      if (pop_status s = kv_only_run(l, r)) return s;
+    if (boundary) {
+      StepTimer tm(m, st, POP_STEP_BOUNDARY);
+      pop::launch_gather_rows(h, bnd_row, xb, B, d, st);
+      rows_in_xb = true;
+      for (int j = l; j <= r; ++j)
+        if (pop_status s = decode_layer(x, j, B, at<int32_t>(ws, w.o_bnd_pos), at<int32_t>(ws, w.o_bnd_slot), max_len))
+          return s;
+    }
+    l = r + 1;
+  }
+  // ---- logits of each sequence's last row: the boundary token's, or (no boundary handling) the pruned
+  //      model's output for it
+  if (a->mode != POP_MODE_BODY_ONLY) {
     StepTimer tm(m, st, POP_STEP_BOUNDARY);
-    LayerCtx x{m, c, ws, &w, st};
-    pop::launch_gather_rows(h, at<int32_t>(ws, w.o_bnd_row), at<float>(ws, w.o_xb), B, d, st);
-    for (int l = a->l_keep + 1; l <= cfg.n_layers; ++l)
-      if (pop_status s = decode_layer(x, l, B, at<int32_t>(ws, w.o_bnd_pos), at<int32_t>(ws, w.o_bnd_slot), max_len))
-        return s;
+    if (!rows_in_xb) pop::launch_gather_rows(h, bnd_row, xb, B, d, st);
     if (pop_status s = lm_head(x, B, dev_logits)) return s;
   }
   return POP_OK;
@@ -962,12 +1083,14 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
     max_len = std::max(max_len, pos + 1);
     std::copy(c->block_table.begin() + (size_t)b * maxp, c->block_table.begin() + (size_t)(b + 1) * maxp,
               mi(w.o_bt) + (size_t)b * maxp);
+    for (int l = 0; l < cfg.n_layers; ++l) mi(w.o_kv_first)[(size_t)l * B + b] = c->kv_first[(size_t)l * c->max_seqs + b];
   }
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   void* ws = dev_workspace;
   POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
   for (int b = 0; b < B; ++b) c->seq_lens[b] += 1;
   LayerCtx x{m, c, ws, &w, st};
+  x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;
   pop::launch_embed((const bf16_t*)m->w.embed, at<int32_t>(ws, w.o_tokens), nullptr, nullptr, at<float>(ws, w.o_xb),
                     B, cfg.d_model, st);
   for (int l = 1; l <= cfg.n_layers; ++l)
@@ -990,7 +1113,8 @@ pop_status pop_generate(pop_model* m, pop_cache* c, const pop_prefill_args* a, i
   if (!m || !c || !a) return fail(POP_EINVAL, "model / cache / args is NULL");
   if (!dev_tokens_out || !dev_logits) return fail(POP_EINVAL, "dev_tokens_out / dev_logits is NULL");
   if (max_new_tokens < 1) return fail(POP_EINVAL, "max_new_tokens %d < 1", max_new_tokens);
-  if (a->mode != POP_MODE_POP) return fail(POP_EINVAL, "generation needs POP_MODE_POP (the boundary token's logits)");
+  if (a->mode != POP_MODE_POP && a->mode != POP_MODE_NO_BOUNDARY)
+    return fail(POP_EINVAL, "generation needs the last prompt token's logits (POP_MODE_POP or POP_MODE_NO_BOUNDARY)");
   const pop_config& cfg = m->cfg;
   if (eos_token >= cfg.vocab) return fail(POP_EINVAL, "eos_token %d outside the vocabulary", eos_token);
   if (!a->cu_seqlens || !a->block_table) return fail(POP_EINVAL, "cu_seqlens / block_table is NULL");
@@ -1036,6 +1160,8 @@ pop_status pop_generate(pop_model* m, pop_cache* c, const pop_prefill_args* a, i
   if (cfg.dtype == POP_DTYPE_F32) {
     const WorkspaceF32 w = carve_f32(cfg, T, B, maxp);
     CtxF32 x{m, c, ws, &w, st};
+    x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;   // uploaded by the prefill
+    x.B = B;
     float* xb = at<float>(ws, w.o_xb);
     for (int s = 1; s < n_new; ++s) {
       pop::f32::launch_embed((const float*)m->w.embed, d_tok, nullptr, nullptr, xb, B, cfg.d_model, st);
@@ -1050,6 +1176,7 @@ pop_status pop_generate(pop_model* m, pop_cache* c, const pop_prefill_args* a, i
   } else {
     const Workspace w = carve(cfg, T, B, maxp);
     LayerCtx x{m, c, ws, &w, st};
+    x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;   // uploaded by the prefill
     for (int s = 1; s < n_new; ++s) {
       pop::launch_embed((const bf16_t*)m->w.embed, d_tok, nullptr, nullptr, at<float>(ws, w.o_xb), B, cfg.d_model, st);
       for (int l = 1; l <= cfg.n_layers; ++l)

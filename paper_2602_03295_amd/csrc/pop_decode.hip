@@ -218,7 +218,7 @@ constexpr int KCH = kDecodeKeysPerSplit;  // keys per work-group (one split)
 constexpr int GMAX = 8;   // query heads per KV head
 
 // grid (n_splits, Hkv, B), 256 threads.  Split s of sequence b covers keys lo + s*KCH .. +KCH-1,
-// lo = first visible key.  Writes the unnormalised partial output, its max and its sum.
+// lo = first visible key (window start, or the first position the layer holds an entry for).  Writes the unnormalised partial output, its max and its sum.
 template <int HD>
 __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a, float scale) {
   constexpr int LPK = HD / 8;        // lanes per key (16-byte chunk each)
@@ -231,7 +231,8 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
   const int G = a.n_q_heads / a.n_kv_heads;
   const int P = a.page_size;
   const int qpos = a.pos[b];
-  const int lo = a.window > 0 ? max(0, qpos - a.window + 1) : 0;
+  int lo = a.window > 0 ? max(0, qpos - a.window + 1) : 0;
+  if (a.kv_first) lo = max(lo, min(a.kv_first[b], qpos));   // the query token's own entry always exists
   const int k_first = lo + split * KCH;
   const int n_keys = min(KCH, qpos + 1 - k_first);  // <= 0: this split is empty
   const int tid = threadIdx.x;

@@ -45,6 +45,20 @@ void launch_gather_rows(const float* src, const int32_t* idx, float* dst, int ro
   hipLaunchKernelGGL(gather_rows_kernel, dim3(rows), dim3(256), 0, st, src, idx, dst, d);
 }
 
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const float* __restrict__ src,
+                                                           const int32_t* __restrict__ idx,
+                                                           float* __restrict__ dst, int d) {
+  const float* s = src + (size_t)blockIdx.x * d;
+  float* o = dst + (size_t)idx[blockIdx.x] * d;
+  for (int i = threadIdx.x * 4; i < d; i += 256 * 4)
+    *reinterpret_cast<float4*>(o + i) = *reinterpret_cast<const float4*>(s + i);
+}
+
+void launch_scatter_rows(const float* src, const int32_t* idx, float* dst, int rows, int d, hipStream_t st) {
+  if (rows <= 0) return;
+  hipLaunchKernelGGL(scatter_rows_kernel, dim3(rows), dim3(256), 0, st, src, idx, dst, d);
+}
+
 // ------------------------------------------------------------------------------------- RMSNorm
 // One 256-thread block per row; the row stays in registers between the statistics and the scaling
 // (up to 8 float4 per thread, d <= 8192), so x is read from HBM once.

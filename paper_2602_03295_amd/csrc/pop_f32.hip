@@ -145,21 +145,24 @@ __global__ void rope_write_kernel(float* __restrict__ qkv, int ld, int q_col, in
 }
 
 // Attn of Sec. 2.1 for one (row, query head) per work-group against the paged cache of the row's
-// sequence: keys lo..pos with lo = max(0, pos - window + 1) (window > 0) or 0.  Scores live in LDS.
+// sequence: keys lo..pos with lo = max(0, pos - window + 1) (window > 0) or 0, and not below the
+// first position the layer holds an entry for (kv_first[sequence], if given).  Scores live in LDS.
 __global__ __launch_bounds__(256) void attention_kernel(const float* __restrict__ q, int ldq, int q_col,
                                                         float* __restrict__ out, const int32_t* __restrict__ row_seq,
                                                         const int32_t* __restrict__ row_pos,
                                                         const float* __restrict__ k_pool,
                                                         const float* __restrict__ v_pool,
                                                         const int32_t* __restrict__ block_table, int max_pages, int P,
-                                                        int window, int n_q_heads, int n_kv_heads, int hd, float scale) {
+                                                        int window, const int32_t* __restrict__ kv_first,
+                                                        int n_q_heads, int n_kv_heads, int hd, float scale) {
   extern __shared__ float smem[];
   __shared__ float red[4];
   float* qs = smem;        // [hd]
   float* sc = smem + hd;   // [n keys]
   const int r = blockIdx.x, head = blockIdx.y, tid = threadIdx.x;
   const int b = row_seq[r], pos = row_pos[r];
-  const int lo = window > 0 ? max(0, pos - window + 1) : 0;
+  int lo = window > 0 ? max(0, pos - window + 1) : 0;
+  if (kv_first) lo = max(lo, min(kv_first[b], pos));   // the row's own entry always exists
   const int n = pos - lo + 1;
   const int kvh = head / (n_q_heads / n_kv_heads);
   const int32_t* bt = block_table + (size_t)b * max_pages;
@@ -237,13 +240,13 @@ void launch_rope_write(float* qkv, int ld, int q_col, int k_col, int v_col, int 
 
 hipError_t launch_attention(const float* q, int ldq, int q_col, float* out, const int32_t* row_seq,
                             const int32_t* row_pos, const float* k_pool, const float* v_pool,
-                            const int32_t* block_table, int max_pages, int P, int window, int rows, int n_q_heads,
+                            const int32_t* block_table, int max_pages, int P, int window, const int32_t* kv_first, int rows, int n_q_heads,
                             int n_kv_heads, int hd, int max_len, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
   const size_t smem = ((size_t)hd + (size_t)max_len) * sizeof(float);
   if (max_len > kMaxContext) return hipErrorInvalidValue;
   hipLaunchKernelGGL(impl::attention_kernel, dim3(rows, n_q_heads), dim3(256), smem, st, q, ldq, q_col, out, row_seq,
-                     row_pos, k_pool, v_pool, block_table, max_pages, P, window, n_q_heads, n_kv_heads, hd,
+                     row_pos, k_pool, v_pool, block_table, max_pages, P, window, kv_first, n_q_heads, n_kv_heads, hd,
                      1.f / sqrtf((float)hd));
   return hipGetLastError();
 }

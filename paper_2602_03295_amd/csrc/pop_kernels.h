@@ -133,6 +133,8 @@ struct AttnDecodeArgs {
   const int32_t* block_table;  // [B, max_pages]
   int max_pages, page_size;
   const int32_t* pos;   // [B] position of the query token (attends 0..pos)
+  const int32_t* kv_first;  // [B] first position that has an entry in this layer's cache, or nullptr (= 0):
+                            // a layer pruned without KV projections holds nothing for the prompt body
   int window;
   int B, n_q_heads, n_kv_heads, hd;
   int n_splits;         // splits of kDecodeKeysPerSplit keys that cover the longest visible key range
@@ -161,10 +163,11 @@ void launch_rope_write(float* qkv, int ld, int q_col, int k_col, int v_col, int 
                        const int32_t* pos, const int32_t* slot, double theta, float* k_pool, float* v_pool, int P,
                        int rows, hipStream_t st);
 // out[r, :] = Attn of row r (sequence row_seq[r], position row_pos[r]) over its cache entries
+// kv_first: per sequence, first position that has a cache entry in this layer (nullptr = 0)
 hipError_t launch_attention(const float* q, int ldq, int q_col, float* out, const int32_t* row_seq,
                             const int32_t* row_pos, const float* k_pool, const float* v_pool,
-                            const int32_t* block_table, int max_pages, int P, int window, int rows, int n_q_heads,
-                            int n_kv_heads, int hd, int max_len, hipStream_t st);
+                            const int32_t* block_table, int max_pages, int P, int window, const int32_t* kv_first,
+                            int rows, int n_q_heads, int n_kv_heads, int hd, int max_len, hipStream_t st);
 }  // namespace f32
 
 // Greedy choice of the next token of every sequence from fp32 logits [B, vocab]: tok[b] (device, in/out)
@@ -175,5 +178,7 @@ void launch_argmax(const float* logits, int vocab, int32_t* tok, int32_t* out, i
 
 // gather fp32 rows: dst[i,:] = src[idx[i],:]
 void launch_gather_rows(const float* src, const int32_t* idx, float* dst, int rows, int d, hipStream_t st);
+// dst[idx[r], :] = src[r, :] (fp32 rows of width d; idx must not repeat)
+void launch_scatter_rows(const float* src, const int32_t* idx, float* dst, int rows, int d, hipStream_t st);
 
 }  // namespace pop

@@ -23,7 +23,7 @@ lib = C.CDLL(LIB_PATH)
 POP_OK = 0
 STATUS_NAMES = {0: "POP_OK", -1: "POP_EINVAL", -2: "POP_ESHAPE", -3: "POP_EALIGN", -4: "POP_ENOSPACE",
                 -5: "POP_ESTATE", -6: "POP_EHIP", -7: "POP_EUNSUPPORTED"}
-MODE_POP, MODE_BODY_ONLY = 0, 1
+MODE_POP, MODE_BODY_ONLY, MODE_NO_BOUNDARY = 0, 1, 2
 DTYPE_F32, DTYPE_BF16 = 0, 1
 EPI_STORE_BF16, EPI_ADD_F32, EPI_GLU_BF16, EPI_STORE_F32 = 0, 1, 2, 3
 
@@ -54,7 +54,8 @@ class pop_prefill_args(C.Structure):
     _fields_ = [("tokens", C.POINTER(C.c_int32)), ("cu_seqlens", C.POINTER(C.c_int32)), ("n_seqs", C.c_int32),
                 ("block_table", C.POINTER(C.c_int32)), ("embeds", C.c_void_p),
                 ("embed_ranges", C.POINTER(C.c_int32)), ("n_ranges", C.c_int32), ("l_keep", C.c_int32),
-                ("mode", C.c_int32)]
+                ("mode", C.c_int32), ("skip_layers", C.POINTER(C.c_int32)), ("n_skip", C.c_int32),
+                ("no_kv_projection", C.c_int32)]
 
 
 _i32p = C.POINTER(C.c_int32)
@@ -262,15 +263,18 @@ def alloc_workspace(cfg: Dict, max_tokens: int, max_seqs: int, max_pages_per_seq
 
 def pop_prefill(model: Model, cache: Cache, tokens, cu_seqlens, block_table, l_keep: int, workspace: torch.Tensor,
                 mode: int = MODE_POP, logits: Optional[torch.Tensor] = None, embeds: Optional[torch.Tensor] = None,
-                embed_ranges=None, stream=None) -> Optional[torch.Tensor]:
+                embed_ranges=None, stream=None, skip_layers=None, no_kv_projection: bool = False) -> Optional[torch.Tensor]:
+    """skip_layers: 1-based layer indices (a general skip set; None = the deep block beyond l_keep)."""
     tok, cu, bt = _i32(tokens), _i32(cu_seqlens), _i32(block_table)
     n_seqs = len(cu) - 1
-    if logits is None and mode == MODE_POP:
+    skip = None if skip_layers is None else _i32(list(skip_layers) + [0])[:len(skip_layers)]   # non-NULL even if empty
+    if logits is None and mode != MODE_BODY_ONLY:
         logits = torch.empty(max(n_seqs, 1), model.cfg["vocab"], dtype=torch.float32, device=workspace.device)
     rng = None if embed_ranges is None else _i32(embed_ranges).reshape(-1, 3)
     a = pop_prefill_args(_ptr(tok), _ptr(cu), n_seqs, _ptr(bt),
                          None if embeds is None else embeds.data_ptr(), _ptr(rng),
-                         0 if rng is None else len(rng), l_keep, mode)
+                         0 if rng is None else len(rng), l_keep, mode, _ptr(skip), 0 if skip is None else len(skip),
+                         1 if no_kv_projection else 0)
     _check(lib.pop_prefill(model.handle, cache.handle, C.byref(a),
                            None if logits is None else logits.data_ptr(),
                            workspace.data_ptr() if workspace is not None else None,
@@ -299,7 +303,7 @@ def alloc_generate_workspace(cfg: Dict, max_tokens: int, max_seqs: int, max_page
 
 def pop_generate(model: Model, cache: Cache, tokens, cu_seqlens, block_table, l_keep: int, max_new_tokens: int,
                  workspace: torch.Tensor, eos_token: int = -1, logits: Optional[torch.Tensor] = None,
-                 stream=None):
+                 stream=None, mode: int = MODE_POP, skip_layers=None, no_kv_projection: bool = False):
     """Returns (generated tokens int32 [n_seqs, max_new_tokens] on the device, last step's logits)."""
     tok, cu, bt = _i32(tokens), _i32(cu_seqlens), _i32(block_table)
     n_seqs = len(cu) - 1
@@ -307,7 +311,9 @@ def pop_generate(model: Model, cache: Cache, tokens, cu_seqlens, block_table, l_
     if logits is None:
         logits = torch.empty(max(n_seqs, 1), model.cfg["vocab"], dtype=torch.float32, device=dev)
     out = torch.empty(max(n_seqs, 1), max(max_new_tokens, 1), dtype=torch.int32, device=dev)
-    a = pop_prefill_args(_ptr(tok), _ptr(cu), n_seqs, _ptr(bt), None, None, 0, l_keep, MODE_POP)
+    skip = None if skip_layers is None else _i32(list(skip_layers) + [0])[:len(skip_layers)]
+    a = pop_prefill_args(_ptr(tok), _ptr(cu), n_seqs, _ptr(bt), None, None, 0, l_keep, mode, _ptr(skip),
+                         0 if skip is None else len(skip), 1 if no_kv_projection else 0)
     _check(lib.pop_generate(model.handle, cache.handle, C.byref(a), max_new_tokens, eos_token, out.data_ptr(),
                             logits.data_ptr(), workspace.data_ptr() if workspace is not None else None,
                             0 if workspace is None else workspace.numel(), _stream(stream)))

@@ -172,7 +172,7 @@ def test_prefill_argument_errors_leave_cache_untouched():
     cases = [
         (dict(l_keep=9), -1), (dict(l_keep=-1), -1), (dict(cu=[0, 30, 30]), -1), (dict(cu=[0, 40, 30]), -1),
         (dict(tokens=np.r_[tokens[:5], 1024, tokens[6:]]), -1), (dict(tokens=np.r_[tokens[:5], -1, tokens[6:]]), -1),
-        (dict(ws_bytes=1024), -4), (dict(bt=bt[:, :1]), -4), (dict(logits=None), -1), (dict(mode=2), -1),
+        (dict(ws_bytes=1024), -4), (dict(bt=bt[:, :1]), -4), (dict(logits=None), -1), (dict(mode=3), -1),
         (dict(max_seqs=1), -1), (dict(ranges=[[0, 25, 10]], embeds=FAKE), -1),
         (dict(ranges=[[0, 2, 3], [0, 4, 2]], embeds=FAKE), -1), (dict(ranges=[[0, 2, 3]]), -1),
         (dict(n_pages=2), -1),
@@ -224,6 +224,35 @@ def test_generate_argument_errors():
         st = pop.lib.pop_generate(m, cache, C.byref(a), args["n_new"], args["eos"], args["out"], args["logits"], FAKE,
                                   args["ws_bytes"], None)
         assert st == want, (kw, st, err())
+        assert pop.lib.pop_cache_n_seqs(cache) == 0 and err()
+        pop.lib.pop_cache_destroy(cache)
+        pop.lib.pop_free_model(m)
+
+
+def test_skip_set_and_switch_argument_errors():
+    """A malformed skip set, an unknown mode or switch value is refused on the host before any launch."""
+    cfg = bf16_cfg()
+    L = cfg["n_layers"]
+    tokens = synth.make_tokens(cfg["vocab"], 27, seed=1)
+    bt, n_pages = synth.make_block_table([20, 7], 16, reserve_pages=1)
+    cu = np.array([0, 20, 27], dtype=np.int32)
+    tok, bt_ = (np.ascontiguousarray(np.asarray(x, dtype=np.int32)) for x in (tokens, bt))
+    p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    bad = [
+        dict(skip=[0, 2]), dict(skip=[2, 2]), dict(skip=[3, 2]), dict(skip=[L + 1]), dict(skip=[1], n_skip=-1),
+        dict(skip=list(range(1, L + 1)), n_skip=L + 1), dict(skip=None, n_skip=2), dict(no_kv=2), dict(no_kv=-1),
+        dict(mode=3), dict(mode=2, logits=None),
+    ]
+    for kw in bad:
+        st, m, c_cfg, keep = fake_model(cfg)
+        st, cache = fake_cache(c_cfg, n_pages, 4, bt.shape[1])
+        skip = kw.get("skip")
+        arr = None if skip is None else np.ascontiguousarray(np.asarray(skip, dtype=np.int32))
+        a = pop.pop_prefill_args(p(tok), p(cu), 2, p(bt_), None, None, 0, 5, kw.get("mode", 0),
+                                 None if arr is None else p(arr), kw.get("n_skip", 0 if skip is None else len(skip)),
+                                 kw.get("no_kv", 0))
+        st = pop.lib.pop_prefill(m, cache, C.byref(a), kw.get("logits", FAKE), FAKE, 1 << 34, None)
+        assert st == -1, (kw, st, err())
         assert pop.lib.pop_cache_n_seqs(cache) == 0 and err()
         pop.lib.pop_cache_destroy(cache)
         pop.lib.pop_free_model(m)
