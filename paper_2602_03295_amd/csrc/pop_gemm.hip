@@ -31,6 +31,7 @@
 //     columns of one row: epilogues use 8/16-byte accesses.
 //   * Work-group ids are remapped so that the 32 groups that run together on one XCD (ids equal mod
 //     8) work on 8 row tiles x 4 column tiles and share them through that XCD's L2.
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 
@@ -463,37 +464,53 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_
 }
 
 // Tile choice: minimise the estimated time on the critical path,
-//     ceil(tiles / 256 CUs) * tile area * relative cost per flop of that configuration.
-// The relative costs are measured on MI355X at the Llama-3.1-8B projection shapes (256x256 tiles
-// move the fewest operand bytes per flop and are the fastest per flop; smaller tiles only win when
-// they fill the chip better).
+//     rounds * K-steps * max(latency floor of a K-step, work-groups per CU * compute time of a K-step),
+//     rounds = ceil(tiles / (256 CUs * work-groups per CU)).
+// The compute time of a K-step is tile area * a relative cost per flop measured on MI355X at the
+// Llama-3.1-8B projection shapes (256x256 tiles move the fewest operand bytes per flop and are the
+// fastest per flop; smaller tiles only win when they fill the chip better).  The floor is what a
+// K-step takes when the work-group only waits for its loads (0.55 us with 2 stages, about half with
+// 3): with few rows (short prompts) a projection is weight streaming, every configuration runs at
+// its floor, and the small tiles win because more work-groups, several per CU, have loads in flight.
+struct TileCfg { int id, bm, bn; double rel; int occ; double floor_us; };
+constexpr TileCfg kTileCfgs[] = {
+    {1, 256, 256, 1.00, 1, 0.55}, {5, 256, 192, 1.08, 1, 0.55}, {3, 256, 128, 1.25, 1, 0.30},
+    {4, 128, 128, 1.40, 2, 0.55}, {7, 128, 64, 1.75, 2, 0.30},  {8, 64, 128, 1.67, 2, 0.30},
+    {6, 64, 64, 2.09, 3, 0.27},
+};
+
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& g, hipStream_t st) {
   const long long batch = g.batch > 0 ? g.batch : 1;
   const long long cols = EPI == EPI_GLU_BF16 ? 2LL * g.N : g.N;  // W rows consumed
-  auto cost = [&](long long bm, long long bn, double rel) {
-    const long long tiles = ((g.M + bm - 1) / bm) * ((cols + bn - 1) / bn) * batch;
-    return (double)(((tiles + 255) / 256) * bm * bn) * rel;
+  auto cost = [&](const TileCfg& c) {
+    const long long tiles = ((g.M + c.bm - 1) / c.bm) * ((cols + c.bn - 1) / c.bn) * batch;
+    const double kstep_us = (double)c.bm * c.bn * c.rel * (1.54 / 65536.0);   // 256x256: 1.54 us
+    const long long rounds = (tiles + 256LL * c.occ - 1) / (256LL * c.occ);
+    const long long share = std::min<long long>(c.occ, (tiles + 255) / 256);
+    return (double)rounds * (double)((g.K + BK - 1) / BK) * std::max(c.floor_us, (double)share * kstep_us);
   };
-  // POP_GEMM_TILE=1..5 forces one configuration (tile-shape experiments); unset or 0 = automatic
+  // POP_GEMM_TILE=1..8 forces one configuration (tile-shape experiments); unset or 0 = automatic
   static const int forced = [] {
     const char* e = getenv("POP_GEMM_TILE");
     return e ? atoi(e) : 0;
   }();
   int pick = forced;
-  if (pick < 1 || pick > 5 || (pick == 5 && EPI == EPI_GLU_BF16)) {
-    const double c1 = cost(256, 256, 1.00), c3 = cost(256, 128, 1.25), c4 = cost(128, 128, 1.40);
-    const double c5 = EPI == EPI_GLU_BF16 ? 1e300 : cost(256, 192, 1.08);
-    pick = 1;
-    double best = c1;
-    if (c5 < best) { best = c5; pick = 5; }
-    if (c3 < best) { best = c3; pick = 3; }
-    if (c4 < best) { best = c4; pick = 4; }
+  if (pick < 1 || pick > 8 || (pick == 5 && EPI == EPI_GLU_BF16)) {
+    double best = 1e300;
+    for (const TileCfg& c : kTileCfgs) {      // ordered by area: ties go to the larger tile
+      if (c.id == 5 && EPI == EPI_GLU_BF16) continue;
+      const double t = cost(c);
+      if (t < best) { best = t; pick = c.id; }
+    }
   }
   switch (pick) {
     case 2: return launch_cfg<256, 256, 2, 4, 2, EPI>(g, st);
     case 3: return launch_cfg<256, 128, 2, 2, 3, EPI>(g, st);
     case 4: return launch_cfg<128, 128, 2, 2, 2, EPI>(g, st);
+    case 6: return launch_cfg<64, 64, 2, 2, 3, EPI>(g, st);
+    case 7: return launch_cfg<128, 64, 2, 2, 3, EPI>(g, st);
+    case 8: return launch_cfg<64, 128, 2, 2, 3, EPI>(g, st);
     case 5:
       if constexpr (EPI != EPI_GLU_BF16) return launch_cfg<256, 192, 2, 2, 2, EPI>(g, st);
       [[fallthrough]];
