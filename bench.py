@@ -63,6 +63,56 @@ def algorithmic_flops(cfg, n, l_keep):
             + 2 * (L * p_layer + v * d))
 
 
+def algorithmic_flops_batch(cfg, lens, l_keep):
+    """The same count for a ragged batch and for models with sliding-window layers (a local layer's
+    attention covers the window only)."""
+    d, hd, f, v, L = cfg["d_model"], cfg["head_dim"], cfg["d_ffn"], cfg["vocab"], cfg["n_layers"]
+    dq, dkv = cfg["n_q_heads"] * hd, cfg["n_kv_heads"] * hd
+    p_layer = d * (dq + 2 * dkv) + dq * d + 3 * d * f
+    p_kv = 2 * d * dkv
+    W, ge = cfg.get("sliding_window", 0), cfg.get("global_every", 0)
+    total = 0.0
+    for n in lens:
+        attn = 0.0
+        for l in range(1, l_keep + 1):
+            local = W > 0 and ge > 0 and l % ge != 0 and n > W
+            attn += 4.0 * dq * (n * W - W * W / 2.0) if local else 2.0 * n * n * dq
+        total += 2.0 * (n - 1) * (l_keep * p_layer + (L - l_keep) * p_kv) + attn + 2.0 * (L * p_layer + v * d)
+    return total
+
+
+def time_workload(pop, synth, torch, np, model, cfg, lens, l_keep, embeds=None, embed_ranges=None, iters=3):
+    """Latency of pop_prefill at full depth and at l_keep for one batch (inputs resident in HBM)."""
+    L = cfg["n_layers"]
+    bt, n_pages = synth.make_block_table(lens, cfg["page_size"], reserve_pages=1)
+    cache = pop.Cache(cfg, n_pages, len(lens), bt.shape[1])
+    T = int(sum(lens))
+    ws = pop.alloc_workspace(cfg, T, len(lens), bt.shape[1])
+    tokens = synth.make_tokens(cfg["vocab"], T, seed=1)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    logits = torch.empty(len(lens), cfg["vocab"], dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    res = {}
+    for k in (L, l_keep):
+        def run():
+            pop.pop_prefill(model, cache, tokens, cu, bt, k, ws, logits=logits, embeds=embeds,
+                            embed_ranges=embed_ranges, stream=stream)
+        run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(iters):
+            run()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        res[k] = e0.elapsed_time(e1) / iters
+    fl = algorithmic_flops_batch(cfg, lens, l_keep)
+    return {"tokens": T, "sequences": len(lens), "l_keep": l_keep, "n_layers": L,
+            "ms_full_depth": res[L], "ms_pruned": res[l_keep], "speedup_vs_full_depth": res[L] / res[l_keep],
+            "tokens_per_s": T / (res[l_keep] * 1e-3), "algorithmic_tflop": fl / 1e12,
+            "end_to_end_frac_of_mfma_peak": fl / (res[l_keep] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+
+
 def cpu_baseline(cfg, n, l_keep):
     """The oracle as it stands on a bounded sample: one kept layer, one K/V-only layer and one
     boundary decode layer (+ LM head) at full width and full prompt length, scaled by layer counts."""
@@ -111,6 +161,8 @@ def main():
                     help="skip the batch-8 time-to-first-token sweep over prompt lengths (Table 2's shape)")
     ap.add_argument("--no-ablation-sweep", action="store_true",
                     help="skip timing the layer-selection variants and switches of the paper's ablation study")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the ragged batch of 8 and the Qwen3-VL-style and Gemma-3-style shapes")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (calibrates the FETCH_SIZE / "
@@ -289,6 +341,29 @@ def main():
             sweep8[str(plen)] = {"ttft_ms_full": res[L], "ttft_ms_pruned": res[lk], "speedup": res[L] / res[lk]}
             del cache8, ws8, lg8
         out["ttft_sweep"] = {"batch": 8, "l_keep": lk, "n_layers": L, "by_prompt_length": sweep8}
+    if not args.no_other_workloads and args.config == "llama8b" and not args.layers:
+        # the other workloads the method is stated on (all synthetic, same recipe): throughput only
+        other = {}
+        lens = synth.make_lengths(8, 512, 4096, seed=7)
+        w8 = time_workload(pop, synth, torch, np, model, cfg, lens, 24)
+        w8["lengths"] = [int(x) for x in lens]
+        other["llama8b shape, 8 ragged prompts of U[512,4096] tokens, L_keep=24"] = w8
+        del model, cache
+        torch.cuda.empty_cache()
+        qcfg = synth.get_config("qwen3vl8b")
+        qmodel = pop.Model(qcfg, device_weights(qcfg, 1234, torch))
+        vis = torch.empty(4096, qcfg["d_model"], dtype=torch.float32, device="cuda").normal_(0.0, 1.0).to(torch.bfloat16)
+        other["qwen3-vl-8b-style shape, 6144 positions (64..4159 supplied as hidden states), L_keep=26"] = \
+            time_workload(pop, synth, torch, np, qmodel, qcfg, [6144], 26, embeds=vis, embed_ranges=[(0, 64, 4096)])
+        del qmodel, vis
+        torch.cuda.empty_cache()
+        gcfg = synth.get_config("gemma12b")
+        gmodel = pop.Model(gcfg, device_weights(gcfg, 1234, torch))
+        other["gemma-3-12b-style shape (head_dim 256, GeGLU, 5 local : 1 global, window 1024), 16384 tokens, L_keep=34"] = \
+            time_workload(pop, synth, torch, np, gmodel, gcfg, [16384], 34, iters=2)
+        del gmodel
+        torch.cuda.empty_cache()
+        out["other_workloads"] = other
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, n, head)
     print(json.dumps(out))
