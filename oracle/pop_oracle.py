@@ -260,11 +260,16 @@ def pop_prefill(cfg: Dict, W: Dict, tokens: np.ndarray, l_keep: int, dtype=np.fl
 
 
 # ----------------------------------------------------------------------------- general skip sets
-def skip_set_body(cfg: Dict, W: Dict, h: np.ndarray, skip: Sequence[int], kv_projection: bool = True):
+def skip_set_body(cfg: Dict, W: Dict, h: np.ndarray, skip: Sequence[int], kv_projection: bool = True,
+                  first_reader: Optional[int] = None):
     """Prefill of body rows h [n, d] (positions 0..n-1) with the layers of `skip` (1-based) pruned:
     x_{l+1} = x_l for l in S_skip (Sec. 2.2), every other layer in full (Sec. 2.1).  A pruned layer
     stores the independent KV projections of its own input x_l (Sec. 3.3) or, with
     kv_projection=False, nothing at all (the ablation without KV projections, Sec. 4.4).
+    With first_reader = p (the position of the first token that will run the full model on this
+    cache), a pruned sliding-window layer stores only the projections that such a token can see:
+    positions j > p - W.  Every later token is further right, so nothing that is ever read is
+    missing and no logit changes (the windowed-write option; Sec. 2.1 attention with a window).
     Returns (cache, x): cache[l-1] = (positions, K, V) with K, V [m, Hkv, hd]; m = 0 for a pruned
     layer without projections."""
     L, hkv, hd = cfg["n_layers"], cfg["n_kv_heads"], cfg["head_dim"]
@@ -282,8 +287,12 @@ def skip_set_body(cfg: Dict, W: Dict, h: np.ndarray, skip: Sequence[int], kv_pro
             x, K, V = kept_layer_rows(cfg, lw, l, x, pos, empty, empty)
             cache.append((pos, K, V))
         elif kv_projection:
-            x, K, V = kv_only_rows(cfg, lw, l, x, pos)
-            cache.append((pos, K, V))
+            _, window = layer_theta_window(cfg, l)
+            first = 0
+            if first_reader is not None and window > 0:
+                first = min(n, max(0, first_reader - window + 1))
+            _, K, V = kv_only_rows(cfg, lw, l, x[first:], pos[first:])
+            cache.append((pos[first:], K, V))
         else:
             cache.append((pos[:0], empty, empty))
     return cache, x
@@ -304,20 +313,23 @@ def decode_step_at(cfg: Dict, W: Dict, h_tok: np.ndarray, position: int, cache):
 
 
 def skip_set_prefill(cfg: Dict, W: Dict, tokens: np.ndarray, skip: Sequence[int],
-                     kv_projection: bool = True, boundary: bool = True, dtype=np.float64):
+                     kv_projection: bool = True, boundary: bool = True, dtype=np.float64,
+                     window_kv_writes: bool = False):
     """Prefill-only pruning with a general skip set and the ablation switches (Sec. 2.2, 3.3,
     4.4).  boundary=True: x_{1:N-1} through the pruned model, x_N through the full model as the
     first decode step.  boundary=False: all N rows through the pruned model, logits from the last
-    row's pruned output.  Returns (cache, logits) with cache[l-1] = (positions, K, V)."""
+    row's pruned output.  window_kv_writes: pruned sliding-window layers keep only the entries the
+    first full-depth token (position N-1 with boundary handling, N without) can still see.
+    Returns (cache, logits) with cache[l-1] = (positions, K, V)."""
     n = len(tokens)
     if n < 1:
         raise ValueError("empty prompt")
     h = embed_rows(W, tokens, dtype)
     if boundary:
-        cache, _ = skip_set_body(cfg, W, h[:n - 1], skip, kv_projection)
+        cache, _ = skip_set_body(cfg, W, h[:n - 1], skip, kv_projection, n - 1 if window_kv_writes else None)
         logits, cache = decode_step_at(cfg, W, h[n - 1], n - 1, cache)
     else:
-        cache, x = skip_set_body(cfg, W, h, skip, kv_projection)
+        cache, x = skip_set_body(cfg, W, h, skip, kv_projection, n if window_kv_writes else None)
         logits = lm_head_logits(cfg, W, x[-1:])[0]
     return cache, logits
 

@@ -11,7 +11,8 @@ import math
 from functools import lru_cache
 
 
-def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_projection=True, boundary=True):
+def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_projection=True, boundary=True,
+                    window_kv_writes=False):
     """Returns (K, V, logits) with K[l][t][head][i] python floats (l 0-based layer index).
     `tokens` may extend beyond the prompt (first n_prompt entries): later tokens are decode steps and,
     like the last prompt token, run every layer in full (Sec. 3.2: decoding keeps the full model).
@@ -19,7 +20,8 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_project
     `skip` (a set of 1-based layers, Sec. 2.2) replaces the deep block l_keep+1..L as the pruned set.
     kv_projection=False: a pruned layer keeps no entry for a pruned token (K[l][t] is None and the
     entry is absent from attention); boundary=False: the last prompt token is pruned like the
-    others (the two ablations of Sec. 4.4)."""
+    others (the two ablations of Sec. 4.4).  window_kv_writes: a pruned sliding-window layer keeps the
+    entry of a pruned token only if the first unpruned token is within the window of it."""
     L, d = cfg["n_layers"], cfg["d_model"]
     Hq, Hkv, hd, f = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"]
     eps = cfg["rms_eps"]
@@ -65,7 +67,13 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_project
         return l not in pruned_layers or t >= n_pruned_tokens
 
     def has_entry(l, t):
-        return kv_projection or runs_full(l, t)
+        if runs_full(l, t):
+            return True
+        if not kv_projection:
+            return False
+        if window_kv_writes and not is_global(l):
+            return t > n_pruned_tokens - cfg["sliding_window"]     # visible from position n_pruned_tokens
+        return True
 
     @lru_cache(maxsize=None)
     def x_in(l, t):

@@ -115,9 +115,9 @@ def test_planted_skip_set_mistakes_are_caught(monkeypatch):
     assert skip_pin_holds() and skip_pin_holds(kv_projection=False) and skip_pin_holds(boundary=False)
     real_body, real_decode = O.skip_set_body, O.decode_step_at
 
-    def frozen_input(cfg, W, h, skip, kv_projection=True):
+    def frozen_input(cfg, W, h, skip, kv_projection=True, first_reader=None):
         """every pruned layer projects the embeddings instead of its own input"""
-        cache, x = real_body(cfg, W, h, skip, kv_projection)
+        cache, x = real_body(cfg, W, h, skip, kv_projection, first_reader)
         if kv_projection:
             for l in skip:
                 _, K, V = O.kv_only_rows(cfg, W["layers"][l - 1], l, h, np.arange(h.shape[0]))
@@ -142,3 +142,23 @@ def test_planted_skip_set_mistakes_are_caught(monkeypatch):
     monkeypatch.setattr(O, "attention_rows", attends_missing)
     with np.errstate(all="ignore"):
         assert not skip_pin_holds(skip=(2,), kv_projection=False, **local)
+
+
+def test_planted_window_write_mistake_is_caught(monkeypatch):
+    """Dropping one entry too many from a pruned sliding-window layer changes what the first full-depth token
+    sees; the scalar recomputation must notice."""
+    cfg = micro_cfg(n_layers=3, sliding_window=3, global_every=3, rope_theta_local=50.0)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 8, seed=12)
+
+    def holds():
+        Kb, Vb, lb = brute_force_pop(cfg, w, tokens.tolist(), 0, skip=(2,), window_kv_writes=True)
+        cache, logits = O.skip_set_prefill(cfg, w, tokens, (2,), window_kv_writes=True)
+        present = [t for t in range(8) if Kb[1][t] is not None]
+        return list(cache[1][0]) == present and bool(np.allclose(logits, np.array(lb), rtol=1e-9, atol=1e-11))
+
+    assert holds()
+    real_body = O.skip_set_body
+    monkeypatch.setattr(O, "skip_set_body",
+                        lambda c, W, h, skip, kv=True, fr=None: real_body(c, W, h, skip, kv, None if fr is None else fr + 1))
+    assert not holds()

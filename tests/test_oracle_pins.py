@@ -559,3 +559,33 @@ def test_interleaved_pruned_layers_project_different_inputs():
     lw3 = w["layers"][2]
     v3_from_e = F.linear(F.rms_norm(e, (cfg["d_model"],), lw3["norm_in"].to(dt), cfg["rms_eps"]), lw3["wv"].to(dt))
     assert np.max(np.abs(cache[2][2][:-1].reshape(9, -1) - v3_from_e.numpy())) > 1e-3
+
+
+@pytest.mark.parametrize("boundary", [True, False])
+def test_windowed_kv_writes_drop_only_entries_nobody_reads(boundary):
+    """A pruned sliding-window layer needs no entry left of the first full-depth token's window (Sec. 2.1:
+    a local layer's token sees the W most recent positions): with those entries dropped the surviving ones,
+    the prefill logits and the logits of later decode steps are those of the ordinary run, and the scalar
+    recomputation (which simply leaves the entries out of attention) agrees."""
+    cfg = micro_cfg(n_layers=4, sliding_window=3, global_every=2, rope_theta_local=50.0)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 10, seed=11)
+    n_prompt, skip = 8, (1, 3, 4)          # layers 1 and 3 are local, 4 is global
+    full, lg_full = O.skip_set_prefill(cfg, w, tokens[:n_prompt], skip, True, boundary)
+    win, lg_win = O.skip_set_prefill(cfg, w, tokens[:n_prompt], skip, True, boundary, window_kv_writes=True)
+    np.testing.assert_allclose(lg_win, lg_full, rtol=1e-12, atol=1e-14)
+    first_reader = n_prompt - 1 if boundary else n_prompt
+    for l in (1, 3):
+        kept = list(win[l - 1][0])
+        assert kept == [p for p in full[l - 1][0] if p > first_reader - cfg["sliding_window"] or p >= first_reader]
+        assert len(kept) < len(full[l - 1][0])
+    assert list(win[3][0]) == list(full[3][0])         # the global pruned layer keeps everything
+    for t in range(n_prompt, 10):
+        h = O.embed_rows(w, tokens[t:t + 1], np.float64)[0]
+        a, full = O.decode_step_at(cfg, w, h, t, full)
+        b, win = O.decode_step_at(cfg, w, h, t, win)
+        np.testing.assert_allclose(b, a, rtol=1e-12, atol=1e-14)
+    Kb, Vb, lb = brute_force_pop(cfg, w, tokens.tolist(), 0, n_prompt=n_prompt, skip=skip, boundary=boundary,
+                                 window_kv_writes=True)
+    _cache_matches_brute_force(win, Kb, Vb)
+    np.testing.assert_allclose(b, np.array(lb), rtol=1e-10, atol=1e-12)
