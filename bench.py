@@ -81,7 +81,8 @@ def algorithmic_flops_batch(cfg, lens, l_keep):
     return total
 
 
-def time_workload(pop, synth, torch, np, model, cfg, lens, l_keep, embeds=None, embed_ranges=None, iters=3):
+def time_workload(pop, synth, torch, np, model, cfg, lens, l_keep, embeds=None, embed_ranges=None, iters=3,
+                  also_window_kv_writes=False):
     """Latency of pop_prefill at full depth and at l_keep for one batch (inputs resident in HBM)."""
     L = cfg["n_layers"]
     bt, n_pages = synth.make_block_table(lens, cfg["page_size"], reserve_pages=1)
@@ -93,10 +94,10 @@ def time_workload(pop, synth, torch, np, model, cfg, lens, l_keep, embeds=None, 
     logits = torch.empty(len(lens), cfg["vocab"], dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
     res = {}
-    for k in (L, l_keep):
+    for k in (L, l_keep) + (("windowed",) if also_window_kv_writes else ()):
         def run():
-            pop.pop_prefill(model, cache, tokens, cu, bt, k, ws, logits=logits, embeds=embeds,
-                            embed_ranges=embed_ranges, stream=stream)
+            pop.pop_prefill(model, cache, tokens, cu, bt, l_keep if k == "windowed" else k, ws, logits=logits,
+                            embeds=embeds, embed_ranges=embed_ranges, stream=stream, window_kv_writes=k == "windowed")
         run()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -107,7 +108,12 @@ def time_workload(pop, synth, torch, np, model, cfg, lens, l_keep, embeds=None, 
         torch.cuda.synchronize()
         res[k] = e0.elapsed_time(e1) / iters
     fl = algorithmic_flops_batch(cfg, lens, l_keep)
-    return {"tokens": T, "sequences": len(lens), "l_keep": l_keep, "n_layers": L,
+    extra = {}
+    if also_window_kv_writes:
+        # pruned sliding-window layers store only the entries a later token can see (at most W rows each)
+        extra = {"ms_pruned_window_kv_writes": res["windowed"],
+                 "speedup_vs_full_depth_window_kv_writes": res[L] / res["windowed"]}
+    return {**extra, "tokens": T, "sequences": len(lens), "l_keep": l_keep, "n_layers": L,
             "ms_full_depth": res[L], "ms_pruned": res[l_keep], "speedup_vs_full_depth": res[L] / res[l_keep],
             "tokens_per_s": T / (res[l_keep] * 1e-3), "algorithmic_tflop": fl / 1e12,
             "end_to_end_frac_of_mfma_peak": fl / (res[l_keep] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
@@ -360,7 +366,7 @@ def main():
         gcfg = synth.get_config("gemma12b")
         gmodel = pop.Model(gcfg, device_weights(gcfg, 1234, torch))
         other["gemma-3-12b-style shape (head_dim 256, GeGLU, 5 local : 1 global, window 1024), 16384 tokens, L_keep=34"] = \
-            time_workload(pop, synth, torch, np, gmodel, gcfg, [16384], 34, iters=2)
+            time_workload(pop, synth, torch, np, gmodel, gcfg, [16384], 34, iters=2, also_window_kv_writes=True)
         del gmodel
         torch.cuda.empty_cache()
         out["other_workloads"] = other

@@ -172,6 +172,12 @@ typedef struct {
                                   tokens; the boundary token and every later token then see, in
                                   those layers, only the entries from the first full-depth token on
                                   (positions stay absolute).  0: independent KV projections.        */
+  int32_t window_kv_writes;    /* 1: a pruned sliding-window layer stores only the body entries that the
+                                  first full-depth token (position len-1 in POP_MODE_POP, len
+                                  otherwise) can still see, i.e. positions > that position - W; later
+                                  tokens see even less of the body, so no result changes and the
+                                  K/V-only projection of such a layer shrinks to at most W rows per
+                                  sequence.  The other slots keep what they held.  0: all entries.   */
 } pop_prefill_args;
 enum { POP_MODE_POP = 0, POP_MODE_BODY_ONLY = 1, POP_MODE_NO_BOUNDARY = 2 };
 

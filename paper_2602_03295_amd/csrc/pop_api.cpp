@@ -149,9 +149,10 @@ struct Workspace {
   // int32 meta (one upload per call)
   size_t meta_bytes;
   size_t o_tokens, o_row_src, o_pos, o_slot, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start, o_ta_start2,
-      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_wlist, o_kv_first;
+      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_kv_first, o_wl_full, o_wl_tail, o_tr_row, o_tr_pos, o_tr_slot,
+      o_tr_cu, o_tr_t64_seq, o_tr_t64_start;
   // device buffers
-  size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_a_multi, o_kv_out;
+  size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_cs_tail, o_a_multi, o_kv_out;
   size_t o_xb, o_ab, o_qkvb, o_qb, o_attnb, o_ub, o_part;
   size_t total;
   int Tp_max, nt64_max, nta_max, n_splits_max;
@@ -188,8 +189,15 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_bnd_pos = take(4 * (size_t)B);
   w.o_bnd_slot = take(4 * (size_t)B);
   w.o_bt = take(4 * (size_t)B * maxp);
-  w.o_wlist = take(8 * (size_t)c.n_layers);
   w.o_kv_first = take(4 * (size_t)c.n_layers * B);
+  w.o_wl_full = take(8 * (size_t)c.n_layers);
+  w.o_wl_tail = take(8 * (size_t)c.n_layers);
+  w.o_tr_row = take(4 * (size_t)T);
+  w.o_tr_pos = take(4 * (size_t)T);
+  w.o_tr_slot = take(4 * (size_t)T);
+  w.o_tr_cu = take(4 * ((size_t)B + 1));
+  w.o_tr_t64_seq = take(4 * (size_t)w.nt64_max);
+  w.o_tr_t64_start = take(4 * (size_t)w.nt64_max);
   w.meta_bytes = o;
   w.o_h = take(4 * (size_t)T * d);
   w.o_a = take(2 * (size_t)T * d);
@@ -199,6 +207,7 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_vT = take(2 * Dkv * (size_t)w.Tp_max);
   w.o_cs_g = take(8 * (size_t)T * (hd / 2));
   w.o_cs_l = take(8 * (size_t)T * (hd / 2));
+  w.o_cs_tail = c.sliding_window > 0 ? take(8 * (size_t)T * (hd / 2)) : o;
   const size_t rc = std::min(kKvChunk, c.n_layers);
   w.o_a_multi = take(2 * rc * (size_t)T * d);
   w.o_kv_out = take(2 * rc * (size_t)T * 2 * Dkv);
@@ -287,8 +296,41 @@ struct LayerCtx {
 struct PrunePlan {
   std::vector<char> pruned;  // [n_layers + 2], 1-based
   bool kv_projection;        // pruned layers store independent KV projections of the body
+  bool window_writes;        // pruned sliding-window layers store only what a later token can see
   int n_pruned;
 };
+
+// Tail rows of every sequence that a pruned sliding-window layer still has to store (window_kv_writes):
+// positions first_b .. len_b - 1 with first_b = max(0, p0 - W + 1), p0 the position of the first token that
+// runs the full model on this cache.  Packed like the prompt itself.
+struct TailRows {
+  std::vector<int32_t> row, pos, slot, cu, t64_seq, t64_start;
+  int n = 0;
+};
+
+TailRows tail_rows(const pop_config& cfg, const pop_prefill_args* a, const std::vector<int32_t>& slots) {
+  TailRows t;
+  const int B = a->n_seqs, W = cfg.sliding_window;
+  t.cu.push_back(0);
+  for (int b = 0; b < B; ++b) {
+    const int s0 = a->cu_seqlens[b], len = a->cu_seqlens[b + 1] - s0;
+    const int p0 = a->mode == POP_MODE_POP ? len - 1 : len;
+    const int first = std::min(len, std::max(0, p0 - W + 1));
+    for (int p = first; p < len; ++p) {
+      t.row.push_back(s0 + p);
+      t.pos.push_back(p);
+      t.slot.push_back(slots[(size_t)s0 + p]);
+    }
+    const int cnt = len - first;
+    for (int q0 = 0; q0 < cnt; q0 += 64) {
+      t.t64_seq.push_back(b);
+      t.t64_start.push_back(q0);
+    }
+    t.cu.push_back(t.cu.back() + cnt);
+  }
+  t.n = t.cu.back();
+  return t;
+}
 
 pop_status make_plan(const pop_config& cfg, const pop_prefill_args* a, PrunePlan* plan) {
   const int L = cfg.n_layers;
@@ -297,7 +339,10 @@ pop_status make_plan(const pop_config& cfg, const pop_prefill_args* a, PrunePlan
   if (a->no_kv_projection != 0 && a->no_kv_projection != 1)
     return fail(POP_EINVAL, "no_kv_projection must be 0 or 1, got %d", a->no_kv_projection);
   plan->pruned.assign((size_t)L + 2, 0);
+  if (a->window_kv_writes != 0 && a->window_kv_writes != 1)
+    return fail(POP_EINVAL, "window_kv_writes must be 0 or 1, got %d", a->window_kv_writes);
   plan->kv_projection = a->no_kv_projection == 0;
+  plan->window_writes = a->window_kv_writes == 1 && cfg.sliding_window > 0 && cfg.global_every > 0;
   plan->n_pruned = 0;
   if (a->skip_layers) {
     if (a->n_skip < 0 || a->n_skip > L) return fail(POP_EINVAL, "n_skip %d outside [0, %d]", a->n_skip, L);
@@ -393,7 +438,8 @@ pop_status lm_head(const LayerCtx& x, int B, float* dev_logits) {
 // ------------------------------------------------------------------------------- fp32 instantiation
 struct WorkspaceF32 {
   size_t meta_bytes;
-  size_t o_tokens, o_row_src, o_pos, o_slot, o_row_seq, o_bnd_row, o_bnd_pos, o_bnd_slot, o_bnd_seq, o_bt, o_kv_first;
+  size_t o_tokens, o_row_src, o_pos, o_slot, o_row_seq, o_bnd_row, o_bnd_pos, o_bnd_slot, o_bnd_seq, o_bt, o_kv_first, o_tr_row, o_tr_pos,
+      o_tr_slot;
   size_t o_h, o_a, o_qkv, o_attn, o_u, o_xb, o_ab, o_qkvb, o_attnb, o_ub;
   size_t total;
 };
@@ -419,6 +465,9 @@ WorkspaceF32 carve_f32(const pop_config& c, int T, int B, int maxp) {
   w.o_bnd_seq = take(4 * (size_t)B);
   w.o_bt = take(4 * (size_t)B * maxp);
   w.o_kv_first = take(4 * (size_t)c.n_layers * B);
+  w.o_tr_row = take(4 * (size_t)T);
+  w.o_tr_pos = take(4 * (size_t)T);
+  w.o_tr_slot = take(4 * (size_t)T);
   w.meta_bytes = o;
   w.o_h = take(4 * (size_t)T * d);
   w.o_a = take(4 * (size_t)T * d);
@@ -517,6 +566,13 @@ pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, co
     return fail(POP_EUNSUPPORTED, "the fp32 path holds one row of scores in LDS: sequences up to %d tokens",
                 pop::f32::kMaxContext);
   record_kv_first(c, a, plan, mi(w.o_kv_first));
+  TailRows tr;
+  if (plan.window_writes) {
+    tr = tail_rows(cfg, a, slots);
+    std::copy(tr.row.begin(), tr.row.end(), mi(w.o_tr_row));
+    std::copy(tr.pos.begin(), tr.pos.end(), mi(w.o_tr_pos));
+    std::copy(tr.slot.begin(), tr.slot.end(), mi(w.o_tr_slot));
+  }
   POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
   c->n_seqs = B;
   std::fill(c->seq_lens.begin(), c->seq_lens.end(), 0);
@@ -559,11 +615,17 @@ pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, co
     if (plan.kv_projection)
       for (int j = l; j <= r; ++j) {
         const pop_layer_weights& lw = m->layers[j - 1];
-        F::launch_rmsnorm(h, (const float*)lw.norm_in, abuf, nullptr, T, d, cfg.rms_eps, st);
-        F::launch_gemm(abuf, d, (const float*)lw.wqkv + (size_t)Dq * d, d, qkv, 2 * Dkv, T, 2 * Dkv, d, F::EPI_STORE, 0, st);
-        F::launch_rope_write(qkv, 2 * Dkv, -1, 0, Dkv, cfg.n_q_heads, cfg.n_kv_heads, hd, d_pos, d_slot,
+        // a sliding-window layer may store only the tail rows a later token can see (window_kv_writes)
+        const bool tail = plan.window_writes && !layer_is_global(cfg, j);
+        const int rows = tail ? tr.n : T;
+        F::launch_rmsnorm(h, (const float*)lw.norm_in, abuf, tail ? at<int32_t>(ws, w.o_tr_row) : nullptr, rows, d,
+                          cfg.rms_eps, st);
+        F::launch_gemm(abuf, d, (const float*)lw.wqkv + (size_t)Dq * d, d, qkv, 2 * Dkv, rows, 2 * Dkv, d, F::EPI_STORE, 0,
+                       st);
+        F::launch_rope_write(qkv, 2 * Dkv, -1, 0, Dkv, cfg.n_q_heads, cfg.n_kv_heads, hd,
+                             tail ? at<int32_t>(ws, w.o_tr_pos) : d_pos, tail ? at<int32_t>(ws, w.o_tr_slot) : d_slot,
                              layer_is_global(cfg, j) ? (double)cfg.rope_theta : (double)cfg.rope_theta_local,
-                             c->k_pool_f32(j - 1), c->v_pool_f32(j - 1), cfg.page_size, T, st);
+                             c->k_pool_f32(j - 1), c->v_pool_f32(j - 1), cfg.page_size, rows, st);
       }
     POP_HIP(hipGetLastError());
     if (boundary) {
@@ -837,12 +899,35 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     std::copy(a->block_table + (size_t)b * maxp, a->block_table + (size_t)(b + 1) * maxp, mi(w.o_bt) + (size_t)b * maxp);
   }
   n_ta = build_attention_work(a->cu_seqlens, B, mi(w.o_ta_seq), mi(w.o_ta_start), mi(w.o_ta_start2));
-  {
-    const bf16_t** wl = reinterpret_cast<const bf16_t**>(meta.data() + w.o_wlist);
-    for (int l = 0; l < cfg.n_layers; ++l)
-      wl[l] = reinterpret_cast<const bf16_t*>(m->layers[l].wqkv) + (size_t)Dq * d;  // rows W^K | W^V
-  }
   record_kv_first(c, a, plan, mi(w.o_kv_first));
+  // Pruned layers in two lists: those that store an entry for every row, and (window_kv_writes) the
+  // sliding-window ones that store the tail rows only.  A run of consecutive pruned layers is a range of each.
+  std::vector<int> full_layers, tail_layers;
+  {
+    const bf16_t** wf = reinterpret_cast<const bf16_t**>(meta.data() + w.o_wl_full);
+    const bf16_t** wt = reinterpret_cast<const bf16_t**>(meta.data() + w.o_wl_tail);
+    for (int l = 1; l <= cfg.n_layers; ++l) {
+      if (!plan.pruned[l]) continue;
+      const bf16_t* wkv = reinterpret_cast<const bf16_t*>(m->layers[l - 1].wqkv) + (size_t)Dq * d;
+      if (plan.window_writes && !layer_is_global(cfg, l)) {
+        wt[tail_layers.size()] = wkv;
+        tail_layers.push_back(l);
+      } else {
+        wf[full_layers.size()] = wkv;
+        full_layers.push_back(l);
+      }
+    }
+  }
+  TailRows tr;
+  if (!tail_layers.empty()) {
+    tr = tail_rows(cfg, a, slots);
+    std::copy(tr.row.begin(), tr.row.end(), mi(w.o_tr_row));
+    std::copy(tr.pos.begin(), tr.pos.end(), mi(w.o_tr_pos));
+    std::copy(tr.slot.begin(), tr.slot.end(), mi(w.o_tr_slot));
+    std::copy(tr.cu.begin(), tr.cu.end(), mi(w.o_tr_cu));
+    std::copy(tr.t64_seq.begin(), tr.t64_seq.end(), mi(w.o_tr_t64_seq));
+    std::copy(tr.t64_start.begin(), tr.t64_start.end(), mi(w.o_tr_t64_start));
+  }
 
   // ------------------------------------------------------------------ launches
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -881,6 +966,9 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     for (int l = 1; l <= cfg.n_layers; ++l) any_local |= !layer_is_global(cfg, l);
     pop::launch_rope_table(d_pos, cs_g, T, hd, (double)cfg.rope_theta, st);
     if (any_local) pop::launch_rope_table(d_pos, cs_l, T, hd, (double)cfg.rope_theta_local, st);
+    if (tr.n > 0)
+      pop::launch_rope_table(at<int32_t>(ws, w.o_tr_pos), at<float2>(ws, w.o_cs_tail), tr.n, hd,
+                             (double)cfg.rope_theta_local, st);
   }
   POP_HIP(hipGetLastError());
 
@@ -962,43 +1050,66 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     return POP_OK;
   };
 
-  // ---- a run l0..l1 of pruned layers: independent KV projections of the hidden state the run leaves
-  //      unchanged (Sec. 2.2, Sec. 3.3); the layers of a run share one normalisation pass and one batched GEMM
+  // ---- a run first..last of pruned layers: independent KV projections of the hidden state the run leaves
+  //      unchanged (Sec. 2.2, Sec. 3.3); layers that share their rows share one normalisation pass and one
+  //      batched GEMM (chunks of kKvChunk).  `tail`: only the tail rows of every sequence, gathered.
   bf16_t* a_multi = at<bf16_t>(ws, w.o_a_multi);
   bf16_t* kv_out = at<bf16_t>(ws, w.o_kv_out);
-  const bf16_t* const* wlist = at<const bf16_t*>(ws, w.o_wlist);
-  auto kv_only_run = [&](int first, int last) -> pop_status {
-    for (int l0 = first; l0 <= last; l0 += kKvChunk) {
-      const int n = std::min(kKvChunk, last - l0 + 1);
+  auto kv_only_layers = [&](const std::vector<int>& layers, int i0, int i1, const bf16_t* const* d_wlist,
+                            bool tail) -> pop_status {
+    const int rows = tail ? tr.n : T;
+    if (rows <= 0) return POP_OK;
+    pop::RopeWriteArgs rk = rw;
+    if (tail) {
+      rk.slot = at<int32_t>(ws, w.o_tr_slot);
+      rk.cu_seqlens = at<int32_t>(ws, w.o_tr_cu);
+      rk.tile_seq = at<int32_t>(ws, w.o_tr_t64_seq);
+      rk.tile_start = at<int32_t>(ws, w.o_tr_t64_start);
+      rk.n_tiles = (int)tr.t64_seq.size();
+    }
+    for (int c0 = i0; c0 < i1; c0 += kKvChunk) {
+      const int n = std::min(kKvChunk, i1 - c0);
       pop::GammaList gl{};
-      for (int j = 0; j < n; ++j) gl.g[j] = (const float*)m->layers[l0 - 1 + j].norm_in;
+      for (int j = 0; j < n; ++j) gl.g[j] = (const float*)m->layers[layers[c0 + j] - 1].norm_in;
       {
         StepTimer tm(m, st, POP_STEP_KV_ONLY_NORM);
-        pop::launch_rmsnorm_multi(h, gl, n, a_multi, (size_t)T * d, T, d, cfg.rms_eps, st);
+        pop::launch_rmsnorm_multi(h, gl, n, a_multi, (size_t)rows * d, rows, d, cfg.rms_eps, st,
+                                  tail ? at<int32_t>(ws, w.o_tr_row) : nullptr);
       }
       pop::GemmArgs g{};
       g.A = a_multi; g.lda = d; g.W = nullptr; g.ldw = d; g.out = kv_out; g.ldc = 2 * Dkv;
-      g.M = T; g.N = 2 * Dkv; g.K = d; g.epilogue = pop::EPI_STORE_BF16;
-      g.batch = n; g.strideA = (long long)T * d; g.strideC = (long long)T * 2 * Dkv;
-      g.W_list = wlist + (l0 - 1);
+      g.M = rows; g.N = 2 * Dkv; g.K = d; g.epilogue = pop::EPI_STORE_BF16;
+      g.batch = n; g.strideA = (long long)rows * d; g.strideC = (long long)rows * 2 * Dkv;
+      g.W_list = d_wlist + c0;
       {
         StepTimer tm(m, st, POP_STEP_KV_ONLY_GEMM);
         if (pop_status s = gemm_or_fail(g, st, "K/V-only")) return s;
       }
       StepTimer tmw(m, st, POP_STEP_KV_ONLY_WRITE);
       for (int j = 0; j < n; ++j) {
-        const int l = l0 + j;
-        rw.qkv = kv_out + (size_t)j * T * 2 * Dkv; rw.ld = 2 * Dkv; rw.q_col = -1; rw.k_col = 0; rw.v_col = Dkv;
-        rw.cs = layer_is_global(cfg, l) ? cs_g : cs_l;
-        rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
-        rw.vT = nullptr;
-        rw.fp16_inplace = 0;
-        rw.fp16_input = 0;
-        pop::launch_rope_write(rw, st);
+        const int l = layers[c0 + j];
+        rk.qkv = kv_out + (size_t)j * rows * 2 * Dkv; rk.ld = 2 * Dkv; rk.q_col = -1; rk.k_col = 0; rk.v_col = Dkv;
+        rk.cs = tail ? at<float2>(ws, w.o_cs_tail) : (layer_is_global(cfg, l) ? cs_g : cs_l);
+        rk.k_pool = c->k_pool(l - 1); rk.v_pool = c->v_pool(l - 1);
+        rk.vT = nullptr;
+        rk.fp16_inplace = 0;
+        rk.fp16_input = 0;
+        pop::launch_rope_write(rk, st);
       }
     }
     POP_HIP(hipGetLastError());
     return POP_OK;
+  };
+  auto kv_only_run = [&](int first, int last) -> pop_status {
+    auto range = [&](const std::vector<int>& v, int& i0, int& i1) {
+      i0 = (int)(std::lower_bound(v.begin(), v.end(), first) - v.begin());
+      i1 = (int)(std::upper_bound(v.begin(), v.end(), last) - v.begin());
+    };
+    int i0, i1;
+    range(full_layers, i0, i1);
+    if (pop_status s = kv_only_layers(full_layers, i0, i1, at<const bf16_t*>(ws, w.o_wl_full), false)) return s;
+    range(tail_layers, i0, i1);
+    return kv_only_layers(tail_layers, i0, i1, at<const bf16_t*>(ws, w.o_wl_tail), true);
   };
 
   // ---- layers in order.  The boundary tokens (Sec. 3.3, boundary handling) are rows of h through kept

@@ -129,11 +129,11 @@ void launch_rmsnorm(float* x, const float* add1, const float* add2, const float*
 }
 
 void launch_rmsnorm_multi(const float* x, GammaList gammas, int n_out, bf16_t* out, size_t out_stride,
-                          int rows, int d, float eps, hipStream_t st) {
+                          int rows, int d, float eps, hipStream_t st, const int32_t* row_idx) {
   if (rows <= 0 || n_out <= 0) return;
   hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(256), 0, st, const_cast<float*>(x),
                      (const float*)nullptr, (const float*)nullptr, gammas, n_out, out, out_stride,
-                     (const int32_t*)nullptr, d, eps);
+                     row_idx, d, eps);
 }
 
 // ------------------------------------------------------------------------------------- RoPE table

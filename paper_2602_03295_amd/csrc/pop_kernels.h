@@ -30,7 +30,7 @@ struct GammaList {
   const float* g[8];
 };
 void launch_rmsnorm_multi(const float* x, GammaList gammas, int n_out, bf16_t* out, size_t out_stride,
-                          int rows, int d, float eps, hipStream_t st);
+                          int rows, int d, float eps, hipStream_t st, const int32_t* row_idx = nullptr);
 
 // cs[t, i] = (cos, sin)(pos[t] * theta^(-2 i / hd)), i < hd/2, angle formed in fp64.
 void launch_rope_table(const int32_t* pos, float2* cs, int T, int hd, double theta, hipStream_t st);

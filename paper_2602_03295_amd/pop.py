@@ -55,7 +55,7 @@ class pop_prefill_args(C.Structure):
                 ("block_table", C.POINTER(C.c_int32)), ("embeds", C.c_void_p),
                 ("embed_ranges", C.POINTER(C.c_int32)), ("n_ranges", C.c_int32), ("l_keep", C.c_int32),
                 ("mode", C.c_int32), ("skip_layers", C.POINTER(C.c_int32)), ("n_skip", C.c_int32),
-                ("no_kv_projection", C.c_int32)]
+                ("no_kv_projection", C.c_int32), ("window_kv_writes", C.c_int32)]
 
 
 _i32p = C.POINTER(C.c_int32)
@@ -263,7 +263,8 @@ def alloc_workspace(cfg: Dict, max_tokens: int, max_seqs: int, max_pages_per_seq
 
 def pop_prefill(model: Model, cache: Cache, tokens, cu_seqlens, block_table, l_keep: int, workspace: torch.Tensor,
                 mode: int = MODE_POP, logits: Optional[torch.Tensor] = None, embeds: Optional[torch.Tensor] = None,
-                embed_ranges=None, stream=None, skip_layers=None, no_kv_projection: bool = False) -> Optional[torch.Tensor]:
+                embed_ranges=None, stream=None, skip_layers=None, no_kv_projection: bool = False,
+                window_kv_writes: bool = False) -> Optional[torch.Tensor]:
     """skip_layers: 1-based layer indices (a general skip set; None = the deep block beyond l_keep)."""
     tok, cu, bt = _i32(tokens), _i32(cu_seqlens), _i32(block_table)
     n_seqs = len(cu) - 1
@@ -274,7 +275,7 @@ def pop_prefill(model: Model, cache: Cache, tokens, cu_seqlens, block_table, l_k
     a = pop_prefill_args(_ptr(tok), _ptr(cu), n_seqs, _ptr(bt),
                          None if embeds is None else embeds.data_ptr(), _ptr(rng),
                          0 if rng is None else len(rng), l_keep, mode, _ptr(skip), 0 if skip is None else len(skip),
-                         1 if no_kv_projection else 0)
+                         1 if no_kv_projection else 0, 1 if window_kv_writes else 0)
     _check(lib.pop_prefill(model.handle, cache.handle, C.byref(a),
                            None if logits is None else logits.data_ptr(),
                            workspace.data_ptr() if workspace is not None else None,

@@ -22,16 +22,19 @@ def pop():
     return p
 
 
-def check_against_oracle(pop, cfg, W, lens, tokens, skip, kv_projection, boundary, tol, n_decode=0, seed=0):
+def check_against_oracle(pop, cfg, W, lens, tokens, skip, kv_projection, boundary, tol, n_decode=0, seed=0,
+                         window_kv_writes=False):
     """Prefill (and n_decode teacher-forced decode steps) on the GPU and in the oracle, compared per
     sequence: entries that exist element by element, positions without an entry still holding the
     sentinel the pool was filled with, logits of the prefill and of every decode step."""
     run = GpuRun(pop, cfg, W, lens, reserve_pages=2, shuffle_seed=3, poison=SENTINEL)
     mode = pop.MODE_POP if boundary else pop.MODE_NO_BOUNDARY
-    logits = run.prefill(tokens, 0, mode=mode, skip_layers=list(skip), no_kv_projection=not kv_projection)
+    logits = run.prefill(tokens, 0, mode=mode, skip_layers=list(skip), no_kv_projection=not kv_projection,
+                         window_kv_writes=window_kv_writes)
     caches, ref_logits = [], []
     for b in range(len(lens)):
-        c, lg = O.skip_set_prefill(cfg, W, tokens[run.cu[b]:run.cu[b + 1]], skip, kv_projection, boundary)
+        c, lg = O.skip_set_prefill(cfg, W, tokens[run.cu[b]:run.cu[b + 1]], skip, kv_projection, boundary,
+                                   window_kv_writes=window_kv_writes)
         caches.append(c)
         ref_logits.append(lg)
     worst = 0.0
@@ -155,3 +158,40 @@ def test_generate_without_boundary_handling(pop):
             if s + 1 < n_new:
                 h = O.embed_rows(W, got[b, s:s + 1], np.float64)[0]
                 lg, cache = O.decode_step_at(cfg, W, h, lens[b] + s, cache)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("boundary", [True, False])
+def test_windowed_kv_writes(pop, dtype, boundary):
+    """Pruned sliding-window layers store only the entries the first full-depth token can see; the pruned
+    global layer stores all.  Entries, untouched slots, prefill logits and the logits of decode steps that
+    walk the window across the end of the prompt are compared with the oracle."""
+    cfg = synth.get_config("tiny", n_layers=6, sliding_window=24, global_every=3, rope_theta_local=100.0)
+    if dtype == "bf16":
+        cfg["dtype"] = synth.DTYPE_BF16
+    W = synth.make_weights(cfg, seed=31)
+    synth.randomize_norms(W, cfg)
+    lens = [150, 10, 70, 24, 25]            # longer than, shorter than and equal to the window (+-1)
+    tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=9)
+    tol = TOL32 if dtype == "fp32" else TOL
+    worst = check_against_oracle(pop, cfg, W, lens, tokens, (2, 4, 5, 6), True, boundary, tol, n_decode=4, seed=2,
+                                 window_kv_writes=True)
+    print("windowed writes", dtype, boundary, f"{worst:.2e}")
+
+
+def test_windowed_kv_writes_change_no_logit(pop):
+    """Same prompt with and without windowed writes: bit-identical logits in the prefill and in later decode
+    steps (nothing that is read has changed)."""
+    cfg = synth.get_config("tiny", dtype=synth.DTYPE_BF16, n_layers=6, sliding_window=32, global_every=2)
+    W = synth.make_weights(cfg, seed=32)
+    lens = [200, 90]
+    tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=10)
+    outs = []
+    for flag in (False, True):
+        run = GpuRun(pop, cfg, W, lens, reserve_pages=2, poison=0.0)
+        lg = [run.prefill(tokens, 3, window_kv_writes=flag)]
+        for s in range(3):
+            lg.append(run.decode(np.array([5 + s, 9 + s], dtype=np.int32)))
+        outs.append(lg)
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)

@@ -241,7 +241,7 @@ def test_skip_set_and_switch_argument_errors():
     bad = [
         dict(skip=[0, 2]), dict(skip=[2, 2]), dict(skip=[3, 2]), dict(skip=[L + 1]), dict(skip=[1], n_skip=-1),
         dict(skip=list(range(1, L + 1)), n_skip=L + 1), dict(skip=None, n_skip=2), dict(no_kv=2), dict(no_kv=-1),
-        dict(mode=3), dict(mode=2, logits=None),
+        dict(mode=3), dict(mode=2, logits=None), dict(window=2), dict(window=-1),
     ]
     for kw in bad:
         st, m, c_cfg, keep = fake_model(cfg)
@@ -250,7 +250,7 @@ def test_skip_set_and_switch_argument_errors():
         arr = None if skip is None else np.ascontiguousarray(np.asarray(skip, dtype=np.int32))
         a = pop.pop_prefill_args(p(tok), p(cu), 2, p(bt_), None, None, 0, 5, kw.get("mode", 0),
                                  None if arr is None else p(arr), kw.get("n_skip", 0 if skip is None else len(skip)),
-                                 kw.get("no_kv", 0))
+                                 kw.get("no_kv", 0), kw.get("window", 0))
         st = pop.lib.pop_prefill(m, cache, C.byref(a), kw.get("logits", FAKE), FAKE, 1 << 34, None)
         assert st == -1, (kw, st, err())
         assert pop.lib.pop_cache_n_seqs(cache) == 0 and err()
