@@ -35,6 +35,10 @@ Readings of points the paper leaves open (each is listed in the design notes as 
     j > t - W; query head i reads KV head i // (Hq / Hkv); softmax with the row maximum
     subtracted.
   * FFN is gated: (act(m Wg^T) * (m Wu^T)) Wd^T with act = SiLU or tanh-GELU.  No biases.
+  * Optional per-head QK-norm (not in the paper; the Qwen3- and Gemma-3-style backbones it is
+    evaluated on have it): if a layer carries "q_norm" / "k_norm" scales [hd], every query / key
+    head is RMS-normalised over head_dim with that scale (same eps) before RoPE, in kept layers
+    and in the pruned layers' key projection alike.
   * Layer l (1-based) is global iff global_every == 0 or l % global_every == 0; local layers use
     rope_theta_local and the sliding window.
   * The boundary token runs every layer normally: its own K/V in deep layers come from its true
@@ -149,7 +153,10 @@ def project_kv(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray):
     hkv, hd = cfg["n_kv_heads"], cfg["head_dim"]
     theta, _ = layer_theta_window(cfg, l)
     a = rmsnorm(x, _w(lw, "norm_in", dt), cfg["rms_eps"])
-    k = rope((a @ _w(lw, "wk", dt).T).reshape(-1, hkv, hd), pos, theta)
+    k = (a @ _w(lw, "wk", dt).T).reshape(-1, hkv, hd)
+    if "k_norm" in lw:
+        k = rmsnorm(k, _w(lw, "k_norm", dt), cfg["rms_eps"])
+    k = rope(k, pos, theta)
     v = (a @ _w(lw, "wv", dt).T).reshape(-1, hkv, hd)
     return k, v
 
@@ -164,7 +171,10 @@ def kept_layer_rows(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray,
     hq, hd = cfg["n_q_heads"], cfg["head_dim"]
     theta, window = layer_theta_window(cfg, l)
     a = rmsnorm(x, _w(lw, "norm_in", dt), cfg["rms_eps"])
-    q = rope((a @ _w(lw, "wq", dt).T).reshape(-1, hq, hd), pos, theta)
+    q = (a @ _w(lw, "wq", dt).T).reshape(-1, hq, hd)
+    if "q_norm" in lw:
+        q = rmsnorm(q, _w(lw, "q_norm", dt), cfg["rms_eps"])
+    q = rope(q, pos, theta)
     k_new, v_new = project_kv(cfg, lw, l, x, pos)
     K_cur = np.concatenate([K_past, k_new], axis=0)
     V_cur = np.concatenate([V_past, v_new], axis=0)

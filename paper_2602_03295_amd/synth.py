@@ -149,6 +149,17 @@ def randomize_norms(w: Dict, cfg: Dict, seed: int = 99) -> None:
         lw["norm_post"] = draw(2 * l + 2)
 
 
+def add_qk_norms(w: Dict, cfg: Dict, seed: int = 77) -> None:
+    """Per-head QK-norm scales [head_dim] for every layer, 1 + N(0, 0.1) draws (Qwen3- / Gemma-3-style
+    backbones normalise every query and key head before RoPE)."""
+    bf = cfg["dtype"] == DTYPE_BF16
+    hd = cfg["head_dim"]
+    for l, lw in enumerate(w["layers"]):
+        for j, name in enumerate(("q_norm", "k_norm")):
+            t = 1.0 + _normal((hd,), seed, 2 * l + j, 0.1, False)
+            lw[name] = t.to(torch.bfloat16).to(torch.float32) if bf else t
+
+
 def make_tokens(vocab: int, n: int, seed: int = 1) -> np.ndarray:
     g = torch.Generator(device="cpu")
     g.manual_seed(seed)

@@ -90,7 +90,10 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_project
         theta = cfg["rope_theta"] if is_global(l) else cfg["rope_theta_local"]
         a = norm(x_in(l, t), lay[l - 1]["norm_in"])
         k = matvec(lay[l - 1]["wk"], a)
-        return tuple(tuple(rot(k[h * hd:(h + 1) * hd], t, theta)) for h in range(Hkv))
+        heads = [k[h * hd:(h + 1) * hd] for h in range(Hkv)]
+        if "k_norm" in lay[l - 1]:                         # per-head QK-norm, before the rotation
+            heads = [norm(hv, lay[l - 1]["k_norm"]) for hv in heads]
+        return tuple(tuple(rot(hv, t, theta)) for hv in heads)
 
     @lru_cache(maxsize=None)
     def val(l, t):
@@ -107,7 +110,10 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_project
         qf = matvec(p["wq"], a)
         o = []
         for i in range(Hq):
-            q = rot(qf[i * hd:(i + 1) * hd], t, theta)
+            qh = qf[i * hd:(i + 1) * hd]
+            if "q_norm" in p:
+                qh = norm(qh, p["q_norm"])
+            q = rot(qh, t, theta)
             g = i // (Hq // Hkv)
             js = [j for j in range(t + 1)
                   if (is_global(l) or j > t - cfg["sliding_window"]) and has_entry(l, j)]

@@ -589,3 +589,47 @@ def test_windowed_kv_writes_drop_only_entries_nobody_reads(boundary):
                                  window_kv_writes=True)
     _cache_matches_brute_force(win, Kb, Vb)
     np.testing.assert_allclose(b, np.array(lb), rtol=1e-10, atol=1e-12)
+
+
+# ------------------------------------------------------------------ per-head QK-norm (family extra)
+@pytest.mark.parametrize("skip", [(), (2,), (1, 3)])
+def test_qk_norm_matches_brute_force(skip):
+    """Every query and key head RMS-normalised over head_dim before RoPE, in kept layers, in the pruned layers'
+    key projection and in decode steps: scalar recomputation."""
+    cfg = micro_cfg(n_layers=3, sliding_window=4, global_every=3, rope_theta_local=50.0)
+    w = weights(cfg)
+    synth.add_qk_norms(w, cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 8, seed=13)
+    Kb, Vb, lb = brute_force_pop(cfg, w, tokens.tolist(), 0, n_prompt=7, skip=skip)
+    cache, _ = O.skip_set_prefill(cfg, w, tokens[:7], skip)
+    logits, cache = O.decode_step_at(cfg, w, O.embed_rows(w, tokens[7:8], np.float64)[0], 7, cache)
+    _cache_matches_brute_force(cache, Kb, Vb)
+    np.testing.assert_allclose(logits, np.array(lb), rtol=1e-10, atol=1e-12)
+
+
+def test_qk_norm_invariances():
+    """With QK-norm the layer does not depend on the scale of a head's rows of W_Q or W_K (the normalisation
+    removes it, up to eps), and stored keys have RMS 1 over head_dim when the scale is all ones; without
+    QK-norm the same rescaling changes the logits."""
+    cfg = small_cfg(rms_eps=1e-12)
+    w = weights(cfg)
+    for lw in w["layers"]:
+        lw["q_norm"] = torch.ones(cfg["head_dim"])
+        lw["k_norm"] = torch.ones(cfg["head_dim"])
+    tokens = synth.make_tokens(cfg["vocab"], 9, seed=14)
+    Kc, Vc, logits = O.pop_prefill(cfg, w, tokens, 2)
+    np.testing.assert_allclose(np.sqrt(np.mean(np.stack(Kc) ** 2, axis=-1)), 1.0, rtol=1e-9)
+    w2 = copy.deepcopy(w)
+    hd = cfg["head_dim"]
+    for lw in w2["layers"]:
+        lw["wq"][:hd] *= 4.0            # first query head (powers of two: exact in the fp32 weight tensors)
+        lw["wk"][hd:2 * hd] *= 0.25     # second key head
+    K2, V2, logits2 = O.pop_prefill(cfg, w2, tokens, 2)
+    np.testing.assert_allclose(logits2, logits, rtol=1e-8, atol=1e-10)
+    np.testing.assert_allclose(np.stack(K2), np.stack(Kc), rtol=1e-8, atol=1e-10)
+    for lw in w2["layers"]:
+        del lw["q_norm"], lw["k_norm"]
+    w3 = copy.deepcopy(w)
+    for lw in w3["layers"]:
+        del lw["q_norm"], lw["k_norm"]
+    assert np.max(np.abs(O.pop_prefill(cfg, w2, tokens, 2)[2] - O.pop_prefill(cfg, w3, tokens, 2)[2])) > 1e-3
