@@ -87,6 +87,12 @@ typedef struct {
   const void* norm_post; /* DEVICE fp32 [d]                 norm in front of the FFN block         */
   const void* w_gate_up; /* DEVICE bf16 [2 f, d]            rows ordered gate | up                 */
   const void* w_down;    /* DEVICE bf16 [d, f]                                                     */
+  /* Optional per-head QK-norm (a family extra, not part of the method; both NULL = off, both or
+     neither): every query head is RMS-normalised over head_dim with scale q_norm, every key head with
+     k_norm (same rms_eps), before RoPE; in kept layers, in the pruned layers' key projection and in
+     decode steps alike. */
+  const void* q_norm;    /* DEVICE fp32 [head_dim] or NULL                                         */
+  const void* k_norm;    /* DEVICE fp32 [head_dim] or NULL                                         */
 } pop_layer_weights;
 
 typedef struct {
@@ -101,7 +107,7 @@ typedef struct {
  * Host-only, enqueues nothing, allocates no device memory.
  * Errors: POP_EINVAL (NULL, non-positive sizes, Hq % Hkv != 0), POP_ESHAPE (head_dim not in
  * {64,128,256}, d_model or d_ffn not a multiple of 8, page_size not a power of two in 1..256),
- * POP_EALIGN.
+ * POP_EALIGN; POP_EINVAL also if a layer has only one of q_norm / k_norm.
  */
 pop_status pop_load_weights(const pop_config* cfg, const pop_weights* w, pop_model** out);
 void pop_free_model(pop_model* m);

@@ -394,7 +394,8 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   pop::launch_gemv(ab, (const bf16_t*)lw.wqkv, qkvb, B, Dqkv, d, Dqkv, pop::GEMV_STORE_F32, 0, x.st);
   pop::launch_rope_append(qkvb, Dqkv, qb, c.n_q_heads, c.n_kv_heads, c.head_dim, pos, slot,
                           glob ? (double)c.rope_theta : (double)c.rope_theta_local, x.c->k_pool(l - 1),
-                          x.c->v_pool(l - 1), c.page_size, B, x.st);
+                          x.c->v_pool(l - 1), c.page_size, B, x.st, (const float*)lw.q_norm, (const float*)lw.k_norm,
+                          c.rms_eps);
   pop::AttnDecodeArgs ad{};
   ad.q = qb;
   ad.k_pool = x.c->k_pool(l - 1);
@@ -506,7 +507,8 @@ pop_status layer_f32(const CtxF32& x, int l /*1-based*/, int rows, float* xh, fl
   F::launch_gemm(a, d, (const float*)lw.wqkv, d, qkv, Dqkv, rows, Dqkv, d, F::EPI_STORE, 0, x.st);
   F::launch_rope_write(qkv, Dqkv, 0, Dq, Dq + Dkv, c.n_q_heads, c.n_kv_heads, hd, pos, slot,
                        glob ? (double)c.rope_theta : (double)c.rope_theta_local, x.c->k_pool_f32(l - 1),
-                       x.c->v_pool_f32(l - 1), c.page_size, rows, x.st);
+                       x.c->v_pool_f32(l - 1), c.page_size, rows, x.st, (const float*)lw.q_norm, (const float*)lw.k_norm,
+                       c.rms_eps);
   hipError_t e = F::launch_attention(qkv, Dqkv, 0, attn, row_seq, pos, x.c->k_pool_f32(l - 1), x.c->v_pool_f32(l - 1),
                                      at<int32_t>(x.ws, x.w->o_bt), x.c->max_pages, c.page_size,
                                      glob ? 0 : c.sliding_window,
@@ -625,7 +627,8 @@ pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, co
         F::launch_rope_write(qkv, 2 * Dkv, -1, 0, Dkv, cfg.n_q_heads, cfg.n_kv_heads, hd,
                              tail ? at<int32_t>(ws, w.o_tr_pos) : d_pos, tail ? at<int32_t>(ws, w.o_tr_slot) : d_slot,
                              layer_is_global(cfg, j) ? (double)cfg.rope_theta : (double)cfg.rope_theta_local,
-                             c->k_pool_f32(j - 1), c->v_pool_f32(j - 1), cfg.page_size, rows, st);
+                             c->k_pool_f32(j - 1), c->v_pool_f32(j - 1), cfg.page_size, rows, st, nullptr,
+                             (const float*)lw.k_norm, cfg.rms_eps);
       }
     POP_HIP(hipGetLastError());
     if (boundary) {
@@ -715,6 +718,10 @@ pop_status pop_load_weights(const pop_config* cfg, const pop_weights* w, pop_mod
     for (const void* p : ps) {
       if (!p) return fail(POP_EINVAL, "layer %d has a NULL weight pointer", l + 1);
       if (!aligned16(p)) return fail(POP_EALIGN, "layer %d has a weight pointer that is not 16-byte aligned", l + 1);
+    if ((lw.q_norm == nullptr) != (lw.k_norm == nullptr))
+      return fail(POP_EINVAL, "layer %d has only one of q_norm / k_norm", l + 1);
+    if (!aligned16(lw.q_norm) || !aligned16(lw.k_norm))
+      return fail(POP_EALIGN, "layer %d has a QK-norm scale that is not 16-byte aligned", l + 1);
     }
   }
   pop_model* m = new (std::nothrow) pop_model();
@@ -1005,6 +1012,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     }
     rw.qkv = qkv; rw.ld = Dqkv; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
     rw.cs = glob ? cs_g : cs_l;
+    rw.q_gamma = (const float*)lw.q_norm; rw.k_gamma = (const float*)lw.k_norm; rw.qk_eps = cfg.rms_eps;
     rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
     rw.vT = vT;
     rw.fp16_inplace = 1;
@@ -1090,6 +1098,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
         const int l = layers[c0 + j];
         rk.qkv = kv_out + (size_t)j * rows * 2 * Dkv; rk.ld = 2 * Dkv; rk.q_col = -1; rk.k_col = 0; rk.v_col = Dkv;
         rk.cs = tail ? at<float2>(ws, w.o_cs_tail) : (layer_is_global(cfg, l) ? cs_g : cs_l);
+        rk.q_gamma = nullptr; rk.k_gamma = (const float*)m->layers[l - 1].k_norm; rk.qk_eps = cfg.rms_eps;
         rk.k_pool = c->k_pool(l - 1); rk.v_pool = c->v_pool(l - 1);
         rk.vT = nullptr;
         rk.fp16_inplace = 0;

@@ -168,19 +168,34 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float* __restric
                                                           int n_kv_heads, int hd, const int32_t* __restrict__ pos,
                                                           const int32_t* __restrict__ slot,
                                                           double neg2_over_hd_log2theta, bf16_t* __restrict__ k_pool,
-                                                          bf16_t* __restrict__ v_pool, int P) {
+                                                          bf16_t* __restrict__ v_pool, int P,
+                                                          const float* __restrict__ q_gamma,
+                                                          const float* __restrict__ k_gamma, float qk_eps) {
+  __shared__ float red[2];
   const int b = blockIdx.x, head = blockIdx.y;
   const int half = hd >> 1;
   const int i = threadIdx.x;
-  if (i >= half) return;
   const float* row = qkv + (size_t)b * ld + (size_t)head * hd;
   const int s = slot[b];
+  // per-head QK-norm (uniform over the block): RMS over the head's hd values, before the rotation
+  const float* gamma = head < n_q_heads ? q_gamma : (head < n_q_heads + n_kv_heads ? k_gamma : nullptr);
+  float x = i < half ? row[i] : 0.f, y = i < half ? row[i + half] : 0.f;
+  if (gamma) {
+    const float ss = wave_sum(x * x + y * y);
+    if ((i & 63) == 0) red[i >> 6] = ss;
+    __syncthreads();
+    const float rstd = 1.0f / sqrtf((red[0] + red[1]) / (float)hd + qk_eps);
+    if (i < half) {
+      x *= rstd * gamma[i];
+      y *= rstd * gamma[i + half];
+    }
+  }
+  if (i >= half) return;
   if (head < n_q_heads + n_kv_heads) {
     const double ang = (double)pos[b] * exp2((double)i * neg2_over_hd_log2theta);
     double sd, cd;
     sincos(ang, &sd, &cd);
     const float c = (float)cd, sn = (float)sd;
-    const float x = row[i], y = row[i + half];
     const bf16_t lo = f32_to_bf16(x * c - y * sn), hi = f32_to_bf16(y * c + x * sn);
     if (head < n_q_heads) {
       bf16_t* o = q_out + ((size_t)b * n_q_heads + head) * hd;
@@ -204,11 +219,12 @@ using namespace decode_impl;
 
 void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
                         const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool, bf16_t* v_pool,
-                        int page_size, int B, hipStream_t st) {
+                        int page_size, int B, hipStream_t st, const float* q_gamma, const float* k_gamma,
+                        float qk_eps) {
   if (B <= 0) return;
   hipLaunchKernelGGL(rope_append_kernel, dim3(B, n_q_heads + 2 * n_kv_heads), dim3(128), 0, st, qkv, ld, q_out,
                      n_q_heads, n_kv_heads, hd, pos, slot, -2.0 / (double)hd * log2(theta), k_pool, v_pool,
-                     page_size);
+                     page_size, q_gamma, k_gamma, qk_eps);
 }
 
 // ------------------------------------------------------------------------------------- decode attention

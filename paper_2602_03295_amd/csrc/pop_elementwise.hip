@@ -161,6 +161,8 @@ void launch_rope_table(const int32_t* pos, float2* cs, int T, int hd, double the
 // ------------------------------------------------------------------------------------- RoPE + cache append
 // grid = (tiles of 64 positions, heads); a block handles one head of one tile.
 //   q head: rotate in place.   k head: rotate in place + store to the K pool.
+//   With q_gamma / k_gamma the head is first RMS-normalised over its hd values (per-head QK-norm); the
+//   threads that share a head row are neighbouring lanes and add their sums of squares by shuffles.
 //   v head: store to the V pool (+ transposed fp16 copy vT[h][i][col], zero beyond the sequence end).
 __global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a) {
   __shared__ uint16_t tr[256 * 66];  // [hd][64 + 2] transposed V tile
@@ -179,22 +181,44 @@ __global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a) {
     const bool is_k = head >= nq;
     const int hh = is_k ? head - nq : head;
     const int col = (is_k ? a.k_col : a.q_col) + hh * hd;
-    const int groups = half >> 3;  // 8 pairs per work item
+    const int groups = half >> 3;  // 8 pairs per work item; 64 * groups is a multiple of 256 for hd >= 64
+    const float* gamma = is_k ? a.k_gamma : a.q_gamma;
     for (int it = threadIdx.x; it < 64 * groups; it += 256) {
       const int p = it / groups, g = it - p * groups;
-      if (p0 + p >= len) continue;
-      const size_t t = (size_t)seq0 + p0 + p;
+      const bool valid = p0 + p < len;
+      const size_t t = (size_t)seq0 + p0 + (valid ? p : 0);
       bf16_t* row = a.qkv + t * a.ld + col;
-      const uint4 lo = *reinterpret_cast<const uint4*>(row + g * 8);
-      const uint4 hi = *reinterpret_cast<const uint4*>(row + half + g * 8);
+      const uint4 lo = valid ? *reinterpret_cast<const uint4*>(row + g * 8) : make_uint4(0, 0, 0, 0);
+      const uint4 hi = valid ? *reinterpret_cast<const uint4*>(row + half + g * 8) : make_uint4(0, 0, 0, 0);
       const float2* cs = a.cs + t * half + g * 8;
       const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+      float xs[8], ys[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        xs[2 * e] = a.fp16_input ? f16lo(lw[e]) : bf16lo(lw[e]);
+        xs[2 * e + 1] = a.fp16_input ? f16hi(lw[e]) : bf16hi(lw[e]);
+        ys[2 * e] = a.fp16_input ? f16lo(hw[e]) : bf16lo(hw[e]);
+        ys[2 * e + 1] = a.fp16_input ? f16hi(hw[e]) : bf16hi(hw[e]);
+      }
+      if (gamma) {   // uniform over the block
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += xs[e] * xs[e] + ys[e] * ys[e];
+        for (int o = groups >> 1; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        const float rstd = 1.0f / sqrtf(ss / (float)hd + a.qk_eps);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          xs[e] *= rstd * gamma[g * 8 + e];
+          ys[e] *= rstd * gamma[half + g * 8 + e];
+        }
+      }
+      if (!valid) continue;
       uint32_t ol[4], oh[4], fl[4], fh[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
-        const float x0 = a.fp16_input ? f16lo(lw[e]) : bf16lo(lw[e]), x1 = a.fp16_input ? f16hi(lw[e]) : bf16hi(lw[e]);
-        const float y0 = a.fp16_input ? f16lo(hw[e]) : bf16lo(hw[e]), y1 = a.fp16_input ? f16hi(hw[e]) : bf16hi(hw[e]);
+        const float x0 = xs[2 * e], x1 = xs[2 * e + 1];
+        const float y0 = ys[2 * e], y1 = ys[2 * e + 1];
         const float r0 = x0 * c0.x - y0 * c0.y, r1 = x1 * c1.x - y1 * c1.y;
         const float r2 = y0 * c0.x + x0 * c0.y, r3 = y1 * c1.x + x1 * c1.y;
         ol[e] = pack_bf16x2(r0, r1);

@@ -107,26 +107,42 @@ __global__ __launch_bounds__(256) void gemm_kernel(const float* __restrict__ A, 
 }
 
 // RoPE (half-split pairs, angle formed in fp64) of the q and k heads of `rows` rows in place, and
-// append of k, v to the paged cache at slot[row].  grid (rows, Hq + 2 Hkv), hd/2 threads.
+// append of k, v to the paged cache at slot[row].  grid (rows, Hq + 2 Hkv), hd/2 threads rounded up to whole
+// waves.  With q_gamma / k_gamma every query / key head is RMS-normalised over hd first (per-head QK-norm).
 __global__ void rope_write_kernel(float* __restrict__ qkv, int ld, int q_col, int k_col, int v_col, int n_q_heads,
                                   int n_kv_heads, int hd, const int32_t* __restrict__ pos,
                                   const int32_t* __restrict__ slot, double neg2_over_hd_log2theta,
-                                  float* __restrict__ k_pool, float* __restrict__ v_pool, int P) {
+                                  float* __restrict__ k_pool, float* __restrict__ v_pool, int P,
+                                  const float* __restrict__ q_gamma, const float* __restrict__ k_gamma, float qk_eps) {
+  __shared__ float red[2];
   const int r = blockIdx.x, head = blockIdx.y;
   const int half = hd >> 1;
-  const int i = threadIdx.x;
-  if (i >= half) return;
+  const int i = threadIdx.x;      // whole waves: 64 or 128 threads, the first `half` of them work
+  const bool act = i < half;
   const int s = slot[r];
   float* row = qkv + (size_t)r * ld;
   if (head < n_q_heads + n_kv_heads) {
     const bool is_q = head < n_q_heads;
     if (is_q && q_col < 0) return;
     float* x = row + (is_q ? q_col + head * hd : k_col + (head - n_q_heads) * hd);
+    float a = act ? x[i] : 0.f, b = act ? x[i + half] : 0.f;
+    const float* gamma = is_q ? q_gamma : k_gamma;
+    if (gamma) {   // per-head QK-norm before the rotation (uniform over the block)
+      const float ss = wave_sum(a * a + b * b);
+      if ((i & 63) == 0) red[i >> 6] = ss;
+      __syncthreads();
+      const float tot = blockDim.x > 64 ? red[0] + red[1] : red[0];
+      const float rstd = 1.0f / sqrtf(tot / (float)hd + qk_eps);
+      if (act) {
+        a *= rstd * gamma[i];
+        b *= rstd * gamma[i + half];
+      }
+    }
+    if (!act) return;
     const double ang = (double)pos[r] * exp2((double)i * neg2_over_hd_log2theta);
     double sd, cd;
     sincos(ang, &sd, &cd);
     const float c = (float)cd, sn = (float)sd;
-    const float a = x[i], b = x[i + half];
     const float lo = a * c - b * sn, hi = b * c + a * sn;
     x[i] = lo;
     x[i + half] = hi;
@@ -136,6 +152,7 @@ __global__ void rope_write_kernel(float* __restrict__ qkv, int ld, int q_col, in
       o[i + half] = hi;
     }
   } else {
+    if (!act) return;
     const int hh = head - n_q_heads - n_kv_heads;
     const float* x = row + v_col + hh * hd;
     float* o = v_pool + (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
@@ -231,11 +248,11 @@ void launch_gemm(const float* A, int lda, const float* W, int ldw, float* out, i
 
 void launch_rope_write(float* qkv, int ld, int q_col, int k_col, int v_col, int n_q_heads, int n_kv_heads, int hd,
                        const int32_t* pos, const int32_t* slot, double theta, float* k_pool, float* v_pool, int P,
-                       int rows, hipStream_t st) {
+                       int rows, hipStream_t st, const float* q_gamma, const float* k_gamma, float qk_eps) {
   if (rows <= 0) return;
-  hipLaunchKernelGGL(impl::rope_write_kernel, dim3(rows, n_q_heads + 2 * n_kv_heads), dim3(hd / 2), 0, st, qkv, ld,
+  hipLaunchKernelGGL(impl::rope_write_kernel, dim3(rows, n_q_heads + 2 * n_kv_heads), dim3((hd / 2 + 63) / 64 * 64), 0, st, qkv, ld,
                      q_col, k_col, v_col, n_q_heads, n_kv_heads, hd, pos, slot, -2.0 / (double)hd * log2(theta), k_pool,
-                     v_pool, P);
+                     v_pool, P, q_gamma, k_gamma, qk_eps);
 }
 
 hipError_t launch_attention(const float* q, int ldq, int q_col, float* out, const int32_t* row_seq,

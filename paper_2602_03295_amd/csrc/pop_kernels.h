@@ -44,6 +44,9 @@ struct RopeWriteArgs {
   int q_col, k_col, v_col;  // first column of q / k / v inside a row (q_col < 0: no q heads)
   int n_q_heads, n_kv_heads, hd;
   const float2* cs;       // [T, hd/2]
+  const float* q_gamma;   // nullptr or [hd]: every query head is RMS-normalised over hd with this scale before RoPE
+  const float* k_gamma;   // the same for the key heads (per-head QK-norm)
+  float qk_eps;
   const int32_t* slot;    // [T] cache slot of each packed token
   bf16_t* k_pool;         // this layer's K pool [page][Hkv][P][hd]
   bf16_t* v_pool;
@@ -118,7 +121,8 @@ void launch_gemv(const bf16_t* x, const bf16_t* W, void* out, int M, int N, int 
 // k (rotated) and v stored at slot[b].
 void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
                         const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool,
-                        bf16_t* v_pool, int page_size, int B, hipStream_t st);
+                        bf16_t* v_pool, int page_size, int B, hipStream_t st, const float* q_gamma = nullptr,
+                        const float* k_gamma = nullptr, float qk_eps = 0.f);
 
 // Keys per split of the decode attention: small enough that a 2K-token context already gives every
 // CU a work-group (len / 64 splits x KV heads x sequences).
@@ -161,7 +165,8 @@ void launch_gemm(const float* A, int lda, const float* W, int ldw, float* out, i
 // rotate q (unless q_col < 0) and k of `rows` rows in place, append k, v at slot[row]
 void launch_rope_write(float* qkv, int ld, int q_col, int k_col, int v_col, int n_q_heads, int n_kv_heads, int hd,
                        const int32_t* pos, const int32_t* slot, double theta, float* k_pool, float* v_pool, int P,
-                       int rows, hipStream_t st);
+                       int rows, hipStream_t st, const float* q_gamma = nullptr, const float* k_gamma = nullptr,
+                       float qk_eps = 0.f);
 // out[r, :] = Attn of row r (sequence row_seq[r], position row_pos[r]) over its cache entries
 // kv_first: per sequence, first position that has a cache entry in this layer (nullptr = 0)
 hipError_t launch_attention(const float* q, int ldq, int q_col, float* out, const int32_t* row_seq,

@@ -42,7 +42,8 @@ class pop_config(C.Structure):
 
 
 class pop_layer_weights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("norm_in", "wqkv", "wo", "norm_post", "w_gate_up", "w_down")]
+    _fields_ = [(n, C.c_void_p) for n in ("norm_in", "wqkv", "wo", "norm_post", "w_gate_up", "w_down", "q_norm",
+                                          "k_norm")]
 
 
 class pop_weights(C.Structure):
@@ -174,6 +175,9 @@ def upload_weights(cfg: Dict, W: Dict, device="cuda") -> Dict:
             "w_gate_up": bf(torch.cat([lw["w_gate"], lw["w_up"]], dim=0)),
             "w_down": bf(lw["w_down"]),
         })
+        for name in ("q_norm", "k_norm"):       # optional per-head QK-norm scales
+            if name in lw:
+                out["layers"][-1][name] = f32(lw[name])
     return out
 
 
@@ -188,7 +192,7 @@ class Model:
         self._layers = (pop_layer_weights * max(n, 1))()
         for i, lw in enumerate(dev_weights["layers"]):
             for name, _ in pop_layer_weights._fields_:
-                setattr(self._layers[i], name, lw[name].data_ptr())
+                setattr(self._layers[i], name, lw[name].data_ptr() if name in lw else None)
         w = pop_weights(dev_weights["embed"].data_ptr(), dev_weights["final_norm"].data_ptr(),
                         dev_weights["lm_head"].data_ptr(), self._layers)
         self.handle = C.c_void_p()

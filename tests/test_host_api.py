@@ -256,3 +256,22 @@ def test_skip_set_and_switch_argument_errors():
         assert pop.lib.pop_cache_n_seqs(cache) == 0 and err()
         pop.lib.pop_cache_destroy(cache)
         pop.lib.pop_free_model(m)
+
+
+def test_qk_norm_pointers_come_in_pairs():
+    """A layer with only one of q_norm / k_norm, or a misaligned one, is refused by pop_load_weights."""
+    cfg = bf16_cfg()
+    c_cfg = pop.make_config(cfg)
+    for q, k, want in ((FAKE, None, -1), (None, FAKE, -1), (FAKE + 4, FAKE, -3), (None, None, 0), (FAKE, FAKE, 0)):
+        layers = (pop.pop_layer_weights * cfg["n_layers"])()
+        for i in range(cfg["n_layers"]):
+            for name, _ in pop.pop_layer_weights._fields_:
+                setattr(layers[i], name, FAKE)
+            layers[i].q_norm, layers[i].k_norm = FAKE, FAKE
+        layers[1].q_norm, layers[1].k_norm = q, k
+        w = pop.pop_weights(FAKE, FAKE, FAKE, layers)
+        h = C.c_void_p()
+        st = pop.lib.pop_load_weights(C.byref(c_cfg), C.byref(w), C.byref(h))
+        assert st == want, (q, k, st, err())
+        if st == 0:
+            pop.lib.pop_free_model(h)
