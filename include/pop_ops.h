@@ -26,6 +26,15 @@ pop_status pop_op_rmsnorm(const float* x, const float* gamma, void* out, int32_t
 pop_status pop_op_gemm(const void* A, int64_t lda, const void* W, int64_t ldw, void* out, int64_t ldc,
                        int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t act, pop_stream stream);
 
+/* The same projection with scratch memory that allows a deterministic split of K (few rows, long K: the
+ * projections of short prompts are weight streaming, and more work-groups stream faster).  The library
+ * decides whether and how far to split; parts are added in a fixed order, so results do not depend on
+ * timing.  epilogue 0, 1 or 3.  dev_scratch DEVICE, 16-byte aligned, scratch_bytes >= 32 M N allows the
+ * deepest split (8 parts of fp32 [M, N]); less only limits it. */
+pop_status pop_op_gemm_splitk(const void* A, int64_t lda, const void* W, int64_t ldw, void* out, int64_t ldc,
+                              int32_t M, int32_t N, int32_t K, int32_t epilogue, void* dev_scratch,
+                              size_t scratch_bytes, pop_stream stream);
+
 /* Same contraction for M <= 64 rows with the bandwidth-bound kernel of the boundary token
  * (Sec. 3.3, "Boundary Handling"): epilogue 0: out fp32 = C, 1: out fp32 += C, 2: GLU -> bf16.
  * Operands are dense (lda = ldw = K). */

@@ -153,7 +153,8 @@ struct Workspace {
       o_tr_cu, o_tr_t64_seq, o_tr_t64_start;
   // device buffers
   size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_cs_tail, o_a_multi, o_kv_out;
-  size_t o_xb, o_ab, o_qkvb, o_qb, o_attnb, o_ub, o_part;
+  size_t o_xb, o_ab, o_qkvb, o_qb, o_attnb, o_ub, o_part, o_splitk;
+  size_t splitk_bytes;
   size_t total;
   int Tp_max, nt64_max, nta_max, n_splits_max;
 };
@@ -218,6 +219,9 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_attnb = take(2 * (size_t)B * Dq);
   w.o_ub = take(2 * (size_t)B * f);
   w.o_part = take(4 * (size_t)B * c.n_q_heads * w.n_splits_max * (hd + 2));
+  // fp32 partial products of a projection whose K range is split (short prompts only)
+  w.splitk_bytes = T <= 512 ? 8 * 4 * (size_t)T * std::max(Dqkv, d) : 0;
+  w.o_splitk = take(w.splitk_bytes);
   w.total = o;
   return w;
 }
@@ -1006,6 +1010,8 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     // q, k, v leave the GEMM as fp16: they only feed the RoPE/append and attention kernels, and fp16
     // keeps three more mantissa bits than bf16 for the score contraction (the cache itself is bf16)
     g.M = T; g.N = Dqkv; g.K = d; g.epilogue = pop::EPI_STORE_F16;
+    g.splitk_ws = w.splitk_bytes ? at<float>(ws, w.o_splitk) : nullptr;
+    g.splitk_ws_bytes = w.splitk_bytes;
     {
       StepTimer tm(m, st, POP_STEP_QKV_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "QKV")) return s;
@@ -1334,6 +1340,26 @@ pop_status pop_op_gemm(const void* A, int64_t lda, const void* W, int64_t ldw, v
   pop::GemmArgs g{};
   g.A = (const bf16_t*)A; g.lda = lda; g.W = (const bf16_t*)W; g.ldw = ldw; g.out = out; g.ldc = ldc;
   g.M = M; g.N = N; g.K = K; g.epilogue = epilogue; g.act = act; g.batch = 1;
+  hipError_t e = pop::launch_gemm(g, reinterpret_cast<hipStream_t>(stream));
+  if (e == hipErrorInvalidValue) return fail(POP_ESHAPE, "operand too large or misaligned for the GEMM kernel");
+  if (e != hipSuccess) return fail(POP_EHIP, "GEMM launch failed: %s", hipGetErrorString(e));
+  return POP_OK;
+}
+
+pop_status pop_op_gemm_splitk(const void* A, int64_t lda, const void* W, int64_t ldw, void* out, int64_t ldc, int32_t M,
+                              int32_t N, int32_t K, int32_t epilogue, void* dev_scratch, size_t scratch_bytes,
+                              pop_stream stream) {
+  if (!A || !W || !out || !dev_scratch) return fail(POP_EINVAL, "NULL pointer");
+  if (M < 0 || N < 0 || K < 1) return fail(POP_EINVAL, "bad sizes");
+  if (epilogue != 0 && epilogue != 1 && epilogue != 3) return fail(POP_EINVAL, "epilogue %d cannot be split", epilogue);
+  if (K % 8 || lda % 8 || ldw % 8 || ldc % 4 || lda < K || ldw < K || ldc < N)
+    return fail(POP_ESHAPE, "K, lda, ldw must be multiples of 8 (ldc of 4) and strides must cover the rows");
+  if (!aligned16(A) || !aligned16(W) || !aligned16(out) || !aligned16(dev_scratch))
+    return fail(POP_EALIGN, "pointer not 16-byte aligned");
+  pop::GemmArgs g{};
+  g.A = (const bf16_t*)A; g.lda = lda; g.W = (const bf16_t*)W; g.ldw = ldw; g.out = out; g.ldc = ldc;
+  g.M = M; g.N = N; g.K = K; g.epilogue = epilogue; g.batch = 1;
+  g.splitk_ws = (float*)dev_scratch; g.splitk_ws_bytes = scratch_bytes;
   hipError_t e = pop::launch_gemm(g, reinterpret_cast<hipStream_t>(stream));
   if (e == hipErrorInvalidValue) return fail(POP_ESHAPE, "operand too large or misaligned for the GEMM kernel");
   if (e != hipSuccess) return fail(POP_EHIP, "GEMM launch failed: %s", hipGetErrorString(e));

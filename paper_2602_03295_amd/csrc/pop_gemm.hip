@@ -34,6 +34,7 @@
 #include <algorithm>
 #include <cstdlib>
 #include <type_traits>
+#include <utility>
 
 #include "pop_device.h"
 #include "pop_kernels.h"
@@ -54,7 +55,7 @@ struct GemmParams {
   int act;
   int tiles_m, tiles_n;  // per batch, of this launch
   int n_tile0;           // first column tile of this launch (a GEMM may be split into two launches)
-  long long strideA, strideC;
+  long long strideA, strideC, strideW;
   const bf16_t* const* W_list;
 };
 
@@ -65,6 +66,11 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 // activation (SiLU: k0 = log2(e), k1 = 0; GELU: k0 = 2 sqrt(2/pi) log2(e), k1 = 0.044715 k0).
 __device__ __forceinline__ float glu_act(float g, float k0, float k1) {
   return g * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-g * (k0 + k1 * g * g)));
+}
+
+template <typename F, int... I>
+__device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
 }
 
 // KFULL: K is a multiple of BK.  Then no lane ever needs a tail mask and the main loop carries no
@@ -105,7 +111,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 
   const int z = blockIdx.z;
   const bf16_t* A = p.A + (long long)z * p.strideA;
-  const bf16_t* W = p.W_list ? p.W_list[z] : p.W;
+  const bf16_t* W = p.W_list ? p.W_list[z] : p.W + (long long)z * p.strideW;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -236,11 +242,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   const int a_base = (wm * WTM + frag_row) * 128;
   const int b_base = (wn * WTN + frag_row) * 128;
 
-  static_assert(STAGES == 2 || STAGES == 3, "2 or 3 LDS stages");
-  static_assert(LOADS + 2 < 64, "vmcnt is a 6-bit counter");
+  static_assert(STAGES >= 2 && STAGES <= 8, "2 to 8 LDS stages");
+  static_assert(1 + (STAGES - 2) * (LOADS + 1) < 64, "vmcnt is a 6-bit counter");
 #pragma unroll
-  for (int t = 0; t < STAGES - 1; ++t)
+  for (int t = 0; t < STAGES - 1; ++t) {
+    // with 4 or more stages the waits below count on every prologue stage having been requested: a stage
+    // beyond the last K-step is requested masked (or re-stages the last K-step) and never read
     if (t < nk) issue(t, t, t < nk_full ? 0u : last_mask);
+    else if (STAGES >= 4) issue(t, t, kOOB);
+  }
   // The K loop is rotated by one (32-wide) sub-step: the MFMAs of the last sub-step of K-step kt-1 are issued
   // after the barrier of K-step kt, from fragments that are already in registers, so the matrix
   // pipe has work while the first fragments of the new stage travel from LDS.  Sub-step s of a
@@ -276,10 +286,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     if (STAGES == 2) {
       if (kt > 0) asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    } else {
+    } else if (STAGES == 3) {
       if (kt >= 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(LOADS + 2) : "memory");
       else if (kt == 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(LOADS) : "memory");
       else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    } else {
+      // General form: from K-step STAGES-1 on, behind K-step kt's loads there are its own iteration's
+      // prefetch and STAGES-2 whole iterations (LOADS + 1 each).  K-steps 0 .. STAGES-2 were requested in
+      // the prologue, stage by stage; behind K-step kt's loads there are at least the STAGES-2-kt stages
+      // requested after it (kt equals `stage` there).
+      constexpr int GENERAL = 1 + (STAGES - 2) * (LOADS + 1);
+      constexpr int EARLY = stage <= STAGES - 2 ? (STAGES - 2 - stage) * LOADS : 0;
+      if (kt >= STAGES - 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(GENERAL) : "memory");
+      else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(EARLY) : "memory");
     }
     __builtin_amdgcn_s_barrier();
     // K-step to prefetch during this one (branch-free: beyond the end every lane is masked off)
@@ -328,6 +347,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
         kstep(kt + 1, S1{}, S0{});
       }
       if (kt < nk) kstep(kt, S0{}, S1{});
+    } else if constexpr (STAGES >= 4) {
+      // unrolled by STAGES: instance I handles K-steps congruent to I, in stage I, refilling stage I - 1
+      auto one = [&](int base, auto idx) {
+        constexpr int I = decltype(idx)::value;
+        kstep(base + I, std::integral_constant<int, I>{}, std::integral_constant<int, (I + STAGES - 1) % STAGES>{});
+      };
+      for (; kt + STAGES - 1 < nk; kt += STAGES)
+        for_each_index([&](auto idx) { one(kt, idx); }, std::make_integer_sequence<int, STAGES>{});
+      for_each_index([&](auto idx) { if (kt + decltype(idx)::value < nk) one(kt, idx); },
+                     std::make_integer_sequence<int, STAGES>{});
     } else {
       for (; kt + 2 < nk; kt += 3) {
         kstep(kt, S0{}, S2{});
@@ -441,7 +470,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_
   p.tiles_n = n_tiles >= 0 ? n_tiles : (g.N + BN_OUT - 1) / BN_OUT;
   p.n_tile0 = n_tile0;
   if (p.tiles_n <= 0) return hipSuccess;
-  p.strideA = g.strideA; p.strideC = g.strideC;
+  p.strideA = g.strideA; p.strideC = g.strideC; p.strideW = g.W_list ? 0 : g.strideW;
   p.W_list = g.batch > 1 || g.W_list ? g.W_list : nullptr;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
@@ -476,27 +505,30 @@ struct TileCfg { int id, bm, bn; double rel; int occ; double floor_us; };
 constexpr TileCfg kTileCfgs[] = {
     {1, 256, 256, 1.00, 1, 0.55}, {5, 256, 192, 1.08, 1, 0.55}, {3, 256, 128, 1.25, 1, 0.30},
     {4, 128, 128, 1.40, 2, 0.55}, {7, 128, 64, 1.75, 2, 0.30},  {8, 64, 128, 1.67, 2, 0.30},
-    {6, 64, 64, 2.09, 3, 0.27},
+    {6, 64, 64, 2.09, 3, 0.27},   {9, 64, 64, 2.09, 1, 0.22},   // 9: six stages, one work-group per CU
 };
+
+// Estimated time (us) of configuration c for M rows, `cols` W rows, K, `batch` problems.
+inline double tile_cost_us(const TileCfg& c, long long M, long long cols, long long K, long long batch) {
+  const long long tiles = ((M + c.bm - 1) / c.bm) * ((cols + c.bn - 1) / c.bn) * batch;
+  const double kstep_us = (double)c.bm * c.bn * c.rel * (1.54 / 65536.0);   // 256x256: 1.54 us
+  const long long rounds = (tiles + 256LL * c.occ - 1) / (256LL * c.occ);
+  const long long share = std::min<long long>(c.occ, (tiles + 255) / 256);
+  return (double)rounds * (double)((K + BK - 1) / BK) * std::max(c.floor_us, (double)share * kstep_us);
+}
 
 template <int EPI>
 hipError_t launch_epi(const GemmArgs& g, hipStream_t st) {
   const long long batch = g.batch > 0 ? g.batch : 1;
   const long long cols = EPI == EPI_GLU_BF16 ? 2LL * g.N : g.N;  // W rows consumed
-  auto cost = [&](const TileCfg& c) {
-    const long long tiles = ((g.M + c.bm - 1) / c.bm) * ((cols + c.bn - 1) / c.bn) * batch;
-    const double kstep_us = (double)c.bm * c.bn * c.rel * (1.54 / 65536.0);   // 256x256: 1.54 us
-    const long long rounds = (tiles + 256LL * c.occ - 1) / (256LL * c.occ);
-    const long long share = std::min<long long>(c.occ, (tiles + 255) / 256);
-    return (double)rounds * (double)((g.K + BK - 1) / BK) * std::max(c.floor_us, (double)share * kstep_us);
-  };
-  // POP_GEMM_TILE=1..8 forces one configuration (tile-shape experiments); unset or 0 = automatic
+  auto cost = [&](const TileCfg& c) { return tile_cost_us(c, g.M, cols, g.K, batch); };
+  // POP_GEMM_TILE=1..9 forces one configuration (tile-shape experiments); unset or 0 = automatic
   static const int forced = [] {
     const char* e = getenv("POP_GEMM_TILE");
     return e ? atoi(e) : 0;
   }();
   int pick = forced;
-  if (pick < 1 || pick > 8 || (pick == 5 && EPI == EPI_GLU_BF16)) {
+  if (pick < 1 || pick > 9 || (pick == 5 && EPI == EPI_GLU_BF16)) {
     double best = 1e300;
     for (const TileCfg& c : kTileCfgs) {      // ordered by area: ties go to the larger tile
       if (c.id == 5 && EPI == EPI_GLU_BF16) continue;
@@ -511,6 +543,7 @@ hipError_t launch_epi(const GemmArgs& g, hipStream_t st) {
     case 6: return launch_cfg<64, 64, 2, 2, 3, EPI>(g, st);
     case 7: return launch_cfg<128, 64, 2, 2, 3, EPI>(g, st);
     case 8: return launch_cfg<64, 128, 2, 2, 3, EPI>(g, st);
+    case 9: return launch_cfg<64, 64, 2, 2, 6, EPI>(g, st);
     case 5:
       if constexpr (EPI != EPI_GLU_BF16) return launch_cfg<256, 192, 2, 2, 2, EPI>(g, st);
       [[fallthrough]];
@@ -541,6 +574,63 @@ hipError_t launch_epi(const GemmArgs& g, hipStream_t st) {
 }  // namespace gemm_impl
 using namespace gemm_impl;
 
+// ------------------------------------------------------------------------------------- split K
+namespace gemm_impl {
+// out = epilogue(parts[0] + parts[1] + ... + parts[S-1]), parts fp32 [S][M][N] dense, added in index order
+// (deterministic).  One thread per 4 consecutive columns.
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ parts, int S, long long part_stride,
+                                                            int M, int N, void* __restrict__ out, long long ldc) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int n4 = N >> 2;
+  if (idx >= (long long)M * n4) return;
+  const int m = (int)(idx / n4), n = (int)(idx % n4) * 4;
+  const float* p0 = parts + (long long)m * N + n;
+  float4 acc = *reinterpret_cast<const float4*>(p0);
+  for (int s = 1; s < S; ++s) {
+    const float4 v = *reinterpret_cast<const float4*>(p0 + (long long)s * part_stride);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  if (EPI == EPI_STORE_BF16 || EPI == EPI_STORE_F16) {
+    uint2 pk;
+    pk.x = EPI == EPI_STORE_F16 ? pack_f16x2(acc.x, acc.y) : pack_bf16x2(acc.x, acc.y);
+    pk.y = EPI == EPI_STORE_F16 ? pack_f16x2(acc.z, acc.w) : pack_bf16x2(acc.z, acc.w);
+    *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(out) + (long long)m * ldc + n) = pk;
+  } else {
+    float* o = reinterpret_cast<float*>(out) + (long long)m * ldc + n;
+    if (EPI == EPI_ADD_F32) {
+      const float4 old = *reinterpret_cast<const float4*>(o);
+      acc.x += old.x; acc.y += old.y; acc.z += old.z; acc.w += old.w;
+    }
+    *reinterpret_cast<float4*>(o) = acc;
+  }
+}
+
+// Number of K parts for this problem (1 = do not split).  Measured inside the model, where every layer's
+// weights come from HBM for the first time: with 256 rows the down projection (K = 14336, 256 work-groups
+// of 224 K-steps each) takes 75 us unsplit and 51 us in 8 parts; at K = 4096 (QKV, O) a split gains
+// nothing (the second kernel costs what the shorter loop saves), and from 1024 rows on the projections
+// are compute bound.  Hence: split only long K with few rows, as far as the scratch allows.
+inline int choose_split(const GemmArgs& g) {
+  if (!g.splitk_ws || g.batch > 1 || g.W_list || g.epilogue == EPI_GLU_BF16) return 1;
+  if (g.M > 512 || g.N % 4 || g.K % BK || (reinterpret_cast<uintptr_t>(g.splitk_ws) & 15)) return 1;
+  // POP_GEMM_SPLITK=S forces S parts where the problem allows it (experiments); unset or 0 = automatic
+  static const int forced = [] {
+    const char* e = getenv("POP_GEMM_SPLITK");
+    return e ? atoi(e) : 0;
+  }();
+  auto fits = [&](int S) {
+    return g.K % (S * BK) == 0 && g.K / (S * BK) >= 8 && (size_t)S * g.M * g.N * 4 <= g.splitk_ws_bytes;
+  };
+  if (forced == 1) return 1;
+  if (forced > 1) return fits(forced) ? forced : 1;
+  if (g.K < 8192 || g.M > 256) return 1;
+  for (int S = 8; S >= 2; S /= 2)
+    if (fits(S)) return S;
+  return 1;
+}
+}  // namespace gemm_impl
+
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.K <= 0 || g.K % 8 || g.lda % 8 || g.ldw % 8 || g.ldc % 4) return hipErrorInvalidValue;
@@ -550,6 +640,33 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   const long long w_rows = g.epilogue == EPI_GLU_BF16 ? 2LL * g.N : g.N;
   if (((long long)(g.M - 1) * g.lda + g.K) * 2 >= (1LL << 31) || ((w_rows - 1) * g.ldw + g.K) * 2 >= (1LL << 31))
     return hipErrorInvalidValue;
+  if (const int S = choose_split(g); S > 1) {
+    GemmArgs part = g;
+    part.K = g.K / S;
+    part.batch = S;
+    part.strideA = part.K;                 // part b starts b * K/S elements into every row of A and W
+    part.strideW = part.K;
+    part.W_list = nullptr;
+    part.out = g.splitk_ws;
+    part.ldc = g.N;
+    part.strideC = (int64_t)g.M * g.N;
+    part.epilogue = EPI_STORE_F32;
+    part.splitk_ws = nullptr;
+    if (hipError_t e = launch_epi<EPI_STORE_F32>(part, st); e != hipSuccess) return e;
+    const long long items = (long long)g.M * (g.N / 4);
+    const dim3 grid((unsigned)((items + 255) / 256));
+    switch (g.epilogue) {
+      case EPI_STORE_BF16:
+        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_STORE_BF16>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc); break;
+      case EPI_STORE_F16:
+        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_STORE_F16>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc); break;
+      case EPI_ADD_F32:
+        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_ADD_F32>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc); break;
+      default:
+        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_STORE_F32>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc); break;
+    }
+    return hipGetLastError();
+  }
   switch (g.epilogue) {
     case EPI_STORE_BF16: return launch_epi<EPI_STORE_BF16>(g, st);
     case EPI_ADD_F32: return launch_epi<EPI_ADD_F32>(g, st);

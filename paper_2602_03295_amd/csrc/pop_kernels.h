@@ -84,6 +84,12 @@ struct GemmArgs {
   int batch;                 // 1 = plain
   int64_t strideA, strideC;  // in elements
   const bf16_t* const* W_list;  // DEVICE array of `batch` weight pointers, or nullptr for plain
+  int64_t strideW;           // without W_list: batch b uses W + b*strideW elements
+  // Optional scratch for a deterministic split of K (few rows, long K: the projections of short prompts):
+  // the K range is cut into S parts that run as S times as many work-groups, each part writes its fp32
+  // partial product here, and a second kernel adds the parts in a fixed order and applies the epilogue.
+  float* splitk_ws;          // DEVICE, 16-byte aligned, or nullptr (never split)
+  size_t splitk_ws_bytes;
 };
 // Returns hipSuccess or the launch error.  Requirements: K % 8 == 0, lda/ldw % 8 == 0,
 // A/W 16-byte aligned, ldc % 4 == 0, and every operand below 2^31 bytes.

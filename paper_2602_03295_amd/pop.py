@@ -87,6 +87,8 @@ lib.pop_generate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(pop_prefill_args)
 lib.pop_op_rmsnorm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p]
 lib.pop_op_gemm.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                             C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+lib.pop_op_gemm_splitk.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
+                                   C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
 lib.pop_op_gemv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                             C.c_int32, C.c_int32, C.c_void_p]
 lib.pop_op_rope_attention_workspace.argtypes = [C.c_int32] * 4
@@ -103,7 +105,7 @@ EXPORTED = ["pop_timing_enable", "pop_timing_read", "pop_last_error", "pop_versi
             "pop_workspace_bytes", "pop_cache_create", "pop_cache_destroy", "pop_cache_n_seqs",
             "pop_cache_seq_lens", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_generate",
             "pop_generate_workspace_bytes", "pop_op_rmsnorm",
-            "pop_op_gemm", "pop_op_gemv", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
+            "pop_op_gemm", "pop_op_gemm_splitk", "pop_op_gemv", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
 
 
 def _check(status: int) -> None:
@@ -342,6 +344,19 @@ def pop_op_gemm(A: torch.Tensor, W: torch.Tensor, epilogue: int = EPI_STORE_BF16
         out = torch.zeros(M, N, dtype=dt, device=A.device)
     _check(lib.pop_op_gemm(A.data_ptr(), A.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(), out.stride(0),
                            M, N, K, epilogue, act, _stream(stream)))
+    return out
+
+
+def pop_op_gemm_splitk(A: torch.Tensor, W: torch.Tensor, epilogue: int = EPI_STORE_BF16,
+                       out: Optional[torch.Tensor] = None, scratch: Optional[torch.Tensor] = None, stream=None):
+    M, K = A.shape
+    N = W.shape[0]
+    if out is None:
+        out = torch.zeros(M, N, dtype=torch.bfloat16 if epilogue == EPI_STORE_BF16 else torch.float32, device=A.device)
+    if scratch is None:
+        scratch = torch.empty(max(32 * M * N, 256), dtype=torch.uint8, device=A.device)
+    _check(lib.pop_op_gemm_splitk(A.data_ptr(), A.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(), out.stride(0),
+                                  M, N, K, epilogue, scratch.data_ptr(), scratch.numel(), _stream(stream)))
     return out
 
 

@@ -155,3 +155,12 @@ def test_llama8b_32k_context_sampled_rows(pop):
     e2 = (rel_err(k2, K2), rel_err(v2, V2))
     print("32K context: layer 1 K/V rel err", e1, "layer 2 K/V on", len(rows), "sampled rows", e2)
     assert max(e1) <= TOL and max(e2) <= TOL
+
+
+def test_llama8b_short_prompts_small_tiles_and_split_k(pop):
+    """A batch of 8 short prompts at the Llama width (256 packed rows): the projections run with the small
+    GEMM tiles, and the down projection (K = 14336) with its K range split over more work-groups."""
+    cfg = synth.get_config("llama8b", n_layers=3, vocab=8192)
+    lens = [32, 7, 64, 1, 50, 33, 40, 29]
+    tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=3)
+    run_and_compare(pop, cfg, lens, 2, tokens)

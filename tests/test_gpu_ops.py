@@ -135,3 +135,47 @@ def test_rope_attention_varlen(pop, hd, hq, hkv, window):
         ref = O.attention_rows(q, pos, k, v, window)
         worst = max(worst, rel(got[cu[b]:cu[b + 1]], ref))
     assert worst <= 2e-2, worst
+
+
+@pytest.mark.parametrize("M,N,K", [(32, 4096, 4096), (256, 4096, 14336), (200, 6144, 4096), (512, 512, 1024), (7, 260, 8192)])
+@pytest.mark.parametrize("epi", [0, 1, 3])
+def test_gemm_split_k(pop, M, N, K, epi):
+    """Few rows and a long K: the K range may be split over more work-groups (fp32 partial products added in
+    a fixed order by a second kernel).  Same result as the definition, and bit-identical from run to run."""
+    rng = np.random.default_rng(M + 3 * N + 5 * K + epi)
+    A = bf16_round(rng.standard_normal((M, K)).astype(np.float32))
+    W = bf16_round(rng.standard_normal((N, K)).astype(np.float32))
+    ref = A.double().numpy() @ W.double().numpy().T
+    base = rng.standard_normal((M, N)).astype(np.float32)
+    if epi == 1:
+        ref = ref + base
+    outs = []
+    for _ in range(2):
+        out = torch.from_numpy(base.copy()).cuda() if epi == 1 else None
+        got = pop.pop_op_gemm_splitk(A.cuda(), W.cuda(), epilogue=epi, out=out)
+        torch.cuda.synchronize()
+        outs.append(got.float().cpu().numpy())
+    tol = 2.0 ** -8 if epi == 0 else 1e-5
+    assert rel(outs[0], ref) <= tol, (rel(outs[0], ref), tol)
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_gemm_split_k_small_scratch_and_strides(pop):
+    """Scratch too small for any split: the plain kernel runs.  Strided operands and output with a split."""
+    rng = np.random.default_rng(5)
+    A = bf16_round(rng.standard_normal((64, 8192)).astype(np.float32)).cuda()
+    W = bf16_round(rng.standard_normal((1024, 8192)).astype(np.float32)).cuda()
+    ref = A.double().cpu().numpy() @ W.double().cpu().numpy().T
+    tiny = torch.empty(256, dtype=torch.uint8, device="cuda")
+    got = pop.pop_op_gemm_splitk(A, W, epilogue=3, scratch=tiny)
+    torch.cuda.synchronize()
+    assert rel(got.cpu().numpy(), ref) <= 1e-5
+    out = torch.zeros(64, 2048, dtype=torch.float32, device="cuda")
+    wide_a = bf16_round(rng.standard_normal((64, 16384)).astype(np.float32)).cuda()
+    wide_w = bf16_round(rng.standard_normal((1024, 12288)).astype(np.float32)).cuda()
+    As, Ws = wide_a[:, 4096:12288], wide_w[:, 2048:10240]       # K = 8192 inside wider rows
+    pop.pop_op_gemm_splitk(As, Ws, epilogue=3, out=out[:, 512:1536])
+    torch.cuda.synchronize()
+    ref2 = As.double().cpu().numpy() @ Ws.double().cpu().numpy().T
+    assert rel(out[:, 512:1536].cpu().numpy(), ref2) <= 1e-5
+    assert float(out[:, :512].abs().max()) == 0 and float(out[:, 1536:].abs().max()) == 0
