@@ -220,7 +220,9 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_ub = take(2 * (size_t)B * f);
   w.o_part = take(4 * (size_t)B * c.n_q_heads * w.n_splits_max * (hd + 2));
   // fp32 partial products of a projection whose K range is split (short prompts only)
-  w.splitk_bytes = T <= 512 ? 8 * 4 * (size_t)T * std::max(Dqkv, d) : 0;
+  // (all packed rows of a short batch; otherwise the boundary rows, which are projected on their own)
+  const size_t split_rows = T <= 512 ? (size_t)T : (B <= 512 ? (size_t)B : 0);
+  w.splitk_bytes = 8 * 4 * split_rows * std::max(Dqkv, d);
   w.o_splitk = take(w.splitk_bytes);
   w.total = o;
   return w;
@@ -381,6 +383,38 @@ void record_kv_first(pop_cache* c, const pop_prefill_args* a, const PrunePlan& p
     }
 }
 
+// Projection of the B rows of a decode-style layer.  The GEMV kernel streams every weight row once per row
+// group and is the fastest form for one or a few rows; from kRowsForGemm rows on the tiled MFMA GEMM with
+// its small tiles (and the split of a long K) reads the weights faster than the GEMV kernel's 8-row form.
+constexpr int kRowsForGemmDefault = 5;
+int rows_for_gemm() {
+  static const int v = [] {
+    const char* e = getenv("POP_DECODE_GEMM_ROWS");   // experiments: 0 = never
+    const int n = e ? atoi(e) : kRowsForGemmDefault;
+    return n <= 0 ? 1 << 30 : n;
+  }();
+  return v;
+}
+
+pop_status few_rows_projection(const LayerCtx& x, const bf16_t* in, const void* W, void* out, int B, int N, int K,
+                               int ldo, int gemv_epi, int act) {
+  if (B < rows_for_gemm()) {
+    pop::launch_gemv(in, (const bf16_t*)W, out, B, N, K, ldo, gemv_epi, act, x.st);
+    return POP_OK;
+  }
+  pop::GemmArgs g{};
+  g.batch = 1;
+  g.A = in; g.lda = K; g.W = (const bf16_t*)W; g.ldw = K; g.out = out; g.ldc = ldo;
+  g.M = B; g.N = N; g.K = K; g.act = act;
+  g.epilogue = gemv_epi == pop::GEMV_STORE_F32 ? pop::EPI_STORE_F32
+               : gemv_epi == pop::GEMV_ADD_F32 ? pop::EPI_ADD_F32 : pop::EPI_GLU_BF16;
+  g.splitk_ws = x.w->splitk_bytes ? at<float>(x.ws, x.w->o_splitk) : nullptr;
+  g.splitk_ws_bytes = x.w->splitk_bytes;
+  hipError_t e = pop::launch_gemm(g, x.st);
+  if (e != hipSuccess) return fail(POP_EHIP, "projection launch failed: %s", hipGetErrorString(e));
+  return POP_OK;
+}
+
 // One decode-style layer for B rows held in xb (fp32 [B, d]); pos/slot are device arrays [B].
 pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32_t* pos, const int32_t* slot,
                         int max_len) {
@@ -395,7 +429,7 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   bf16_t* ub = at<bf16_t>(x.ws, x.w->o_ub);
   const bool glob = layer_is_global(c, l);
   pop::launch_rmsnorm(xb, nullptr, nullptr, (const float*)lw.norm_in, ab, nullptr, B, d, c.rms_eps, x.st);
-  pop::launch_gemv(ab, (const bf16_t*)lw.wqkv, qkvb, B, Dqkv, d, Dqkv, pop::GEMV_STORE_F32, 0, x.st);
+  if (pop_status s = few_rows_projection(x, ab, lw.wqkv, qkvb, B, Dqkv, d, Dqkv, pop::GEMV_STORE_F32, 0)) return s;
   pop::launch_rope_append(qkvb, Dqkv, qb, c.n_q_heads, c.n_kv_heads, c.head_dim, pos, slot,
                           glob ? (double)c.rope_theta : (double)c.rope_theta_local, x.c->k_pool(l - 1),
                           x.c->v_pool(l - 1), c.page_size, B, x.st, (const float*)lw.q_norm, (const float*)lw.k_norm,
@@ -420,10 +454,10 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   ad.part = at<float>(x.ws, x.w->o_part);
   ad.out = attnb;
   pop::launch_attention_decode(ad, x.st);
-  pop::launch_gemv(attnb, (const bf16_t*)lw.wo, xb, B, d, Dq, d, pop::GEMV_ADD_F32, 0, x.st);
+  if (pop_status s = few_rows_projection(x, attnb, lw.wo, xb, B, d, Dq, d, pop::GEMV_ADD_F32, 0)) return s;
   pop::launch_rmsnorm(xb, nullptr, nullptr, (const float*)lw.norm_post, ab, nullptr, B, d, c.rms_eps, x.st);
-  pop::launch_gemv(ab, (const bf16_t*)lw.w_gate_up, ub, B, f, d, f, pop::GEMV_GLU_BF16, c.act, x.st);
-  pop::launch_gemv(ub, (const bf16_t*)lw.w_down, xb, B, d, f, d, pop::GEMV_ADD_F32, 0, x.st);
+  if (pop_status s = few_rows_projection(x, ab, lw.w_gate_up, ub, B, f, d, f, pop::GEMV_GLU_BF16, c.act)) return s;
+  if (pop_status s = few_rows_projection(x, ub, lw.w_down, xb, B, d, f, d, pop::GEMV_ADD_F32, 0)) return s;
   POP_HIP(hipGetLastError());
   return POP_OK;
 }
