@@ -1143,6 +1143,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
         rk.vT = nullptr;
         rk.fp16_inplace = 0;
         rk.fp16_input = 0;
+        rk.cache_only = 1;
         pop::launch_rope_write(rk, st);
       }
     }

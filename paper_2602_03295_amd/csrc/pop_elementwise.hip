@@ -1,6 +1,7 @@
 // Bandwidth-bound steps of the POP prefill path for gfx950: embedding gather, RMSNorm (the LN of
 // Sec. 2.1), the RoPE angle table, and RoPE + KV-cache append (Sec. 2.1, K/V generation and cache
 // append; the same kernel serves the independent KV projections of Sec. 3.3).
+#include <algorithm>
 #include "pop_device.h"
 #include "pop_kernels.h"
 
@@ -159,12 +160,12 @@ void launch_rope_table(const int32_t* pos, float2* cs, int T, int hd, double the
 }
 
 // ------------------------------------------------------------------------------------- RoPE + cache append
-// grid = (tiles of 64 positions, heads); a block handles one head of one tile.
+// grid = (tiles of 64 positions, blocks of 1 to 4 q/k heads followed by one block per v head).
 //   q head: rotate in place.   k head: rotate in place + store to the K pool.
 //   With q_gamma / k_gamma the head is first RMS-normalised over its hd values (per-head QK-norm); the
 //   threads that share a head row are neighbouring lanes and add their sums of squares by shuffles.
 //   v head: store to the V pool (+ transposed fp16 copy vT[h][i][col], zero beyond the sequence end).
-__global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a) {
+__global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a, int heads_per_block) {
   __shared__ uint16_t tr[256 * 66];  // [hd][64 + 2] transposed V tile
   const int tile = blockIdx.x;
   const int b = a.tile_seq[tile];
@@ -172,77 +173,90 @@ __global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a) {
   const int seq0 = a.cu_seqlens[b];
   const int len = a.cu_seqlens[b + 1] - seq0;
   const int hd = a.hd, half = hd >> 1;
-  int head = blockIdx.y;
   const int nq = a.q_col >= 0 ? a.n_q_heads : 0;
   const int P = a.page_size;
+  const int n_rot = nq + a.n_kv_heads;                               // heads that are rotated
+  const int n_rot_blocks = (n_rot + heads_per_block - 1) / heads_per_block;
 
-  if (head < nq + a.n_kv_heads) {
-    // ---- rotate (q or k)
-    const bool is_k = head >= nq;
-    const int hh = is_k ? head - nq : head;
-    const int col = (is_k ? a.k_col : a.q_col) + hh * hd;
+  if ((int)blockIdx.y < n_rot_blocks) {
+    // ---- rotate (q or k): a block takes heads_per_block heads of its 64 positions, so that a thread's
+    //      cos/sin values (as many bytes as a head's data) are read once for all of them
+    const int head0 = blockIdx.y * heads_per_block;
+    const int head1 = min(head0 + heads_per_block, n_rot);
     const int groups = half >> 3;  // 8 pairs per work item; 64 * groups is a multiple of 256 for hd >= 64
-    const float* gamma = is_k ? a.k_gamma : a.q_gamma;
     for (int it = threadIdx.x; it < 64 * groups; it += 256) {
       const int p = it / groups, g = it - p * groups;
       const bool valid = p0 + p < len;
       const size_t t = (size_t)seq0 + p0 + (valid ? p : 0);
-      bf16_t* row = a.qkv + t * a.ld + col;
-      const uint4 lo = valid ? *reinterpret_cast<const uint4*>(row + g * 8) : make_uint4(0, 0, 0, 0);
-      const uint4 hi = valid ? *reinterpret_cast<const uint4*>(row + half + g * 8) : make_uint4(0, 0, 0, 0);
-      const float2* cs = a.cs + t * half + g * 8;
-      const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
-      float xs[8], ys[8];
+      float2 cs[8];
+      {
+        const float2* csp = a.cs + t * half + g * 8;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        xs[2 * e] = a.fp16_input ? f16lo(lw[e]) : bf16lo(lw[e]);
-        xs[2 * e + 1] = a.fp16_input ? f16hi(lw[e]) : bf16hi(lw[e]);
-        ys[2 * e] = a.fp16_input ? f16lo(hw[e]) : bf16lo(hw[e]);
-        ys[2 * e + 1] = a.fp16_input ? f16hi(hw[e]) : bf16hi(hw[e]);
+        for (int e = 0; e < 8; ++e) cs[e] = csp[e];
       }
-      if (gamma) {   // uniform over the block
-        float ss = 0.f;
+      const int s = (a.k_pool && valid) ? a.slot[t] : 0;
+      for (int head = head0; head < head1; ++head) {
+        const bool is_k = head >= nq;
+        const int hh = is_k ? head - nq : head;
+        const int col = (is_k ? a.k_col : a.q_col) + hh * hd;
+        const float* gamma = is_k ? a.k_gamma : a.q_gamma;
+        bf16_t* row = a.qkv + t * a.ld + col;
+        const uint4 lo = valid ? *reinterpret_cast<const uint4*>(row + g * 8) : make_uint4(0, 0, 0, 0);
+        const uint4 hi = valid ? *reinterpret_cast<const uint4*>(row + half + g * 8) : make_uint4(0, 0, 0, 0);
+        const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+        float xs[8], ys[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) ss += xs[e] * xs[e] + ys[e] * ys[e];
-        for (int o = groups >> 1; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
-        const float rstd = 1.0f / sqrtf(ss / (float)hd + a.qk_eps);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          xs[e] *= rstd * gamma[g * 8 + e];
-          ys[e] *= rstd * gamma[half + g * 8 + e];
+        for (int e = 0; e < 4; ++e) {
+          xs[2 * e] = a.fp16_input ? f16lo(lw[e]) : bf16lo(lw[e]);
+          xs[2 * e + 1] = a.fp16_input ? f16hi(lw[e]) : bf16hi(lw[e]);
+          ys[2 * e] = a.fp16_input ? f16lo(hw[e]) : bf16lo(hw[e]);
+          ys[2 * e + 1] = a.fp16_input ? f16hi(hw[e]) : bf16hi(hw[e]);
         }
-      }
-      if (!valid) continue;
-      uint32_t ol[4], oh[4], fl[4], fh[4];
+        if (gamma) {   // uniform over the block
+          float ss = 0.f;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
-        const float x0 = xs[2 * e], x1 = xs[2 * e + 1];
-        const float y0 = ys[2 * e], y1 = ys[2 * e + 1];
-        const float r0 = x0 * c0.x - y0 * c0.y, r1 = x1 * c1.x - y1 * c1.y;
-        const float r2 = y0 * c0.x + x0 * c0.y, r3 = y1 * c1.x + x1 * c1.y;
-        ol[e] = pack_bf16x2(r0, r1);
-        oh[e] = pack_bf16x2(r2, r3);
-        fl[e] = pack_f16x2(r0, r1);
-        fh[e] = pack_f16x2(r2, r3);
-      }
-      const uint4 vlo = make_uint4(ol[0], ol[1], ol[2], ol[3]);
-      const uint4 vhi = make_uint4(oh[0], oh[1], oh[2], oh[3]);
-      // in place: fp16 when the attention kernel is the consumer (three more mantissa bits than bf16
-      // for the score contraction), bf16 otherwise; the cache entry is always bf16
-      *reinterpret_cast<uint4*>(row + g * 8) = a.fp16_inplace ? make_uint4(fl[0], fl[1], fl[2], fl[3]) : vlo;
-      *reinterpret_cast<uint4*>(row + half + g * 8) = a.fp16_inplace ? make_uint4(fh[0], fh[1], fh[2], fh[3]) : vhi;
-      if (is_k && a.k_pool) {
-        const int s = a.slot[t];
-        bf16_t* dst = a.k_pool + (((size_t)(s / P) * a.n_kv_heads + hh) * P + (s % P)) * hd;
-        *reinterpret_cast<uint4*>(dst + g * 8) = vlo;
-        *reinterpret_cast<uint4*>(dst + half + g * 8) = vhi;
+          for (int e = 0; e < 8; ++e) ss += xs[e] * xs[e] + ys[e] * ys[e];
+          for (int o = groups >> 1; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+          const float rstd = 1.0f / sqrtf(ss / (float)hd + a.qk_eps);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            xs[e] *= rstd * gamma[g * 8 + e];
+            ys[e] *= rstd * gamma[half + g * 8 + e];
+          }
+        }
+        if (!valid) continue;
+        uint32_t ol[4], oh[4], fl[4], fh[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
+          const float x0 = xs[2 * e], x1 = xs[2 * e + 1];
+          const float y0 = ys[2 * e], y1 = ys[2 * e + 1];
+          const float r0 = x0 * c0.x - y0 * c0.y, r1 = x1 * c1.x - y1 * c1.y;
+          const float r2 = y0 * c0.x + x0 * c0.y, r3 = y1 * c1.x + x1 * c1.y;
+          ol[e] = pack_bf16x2(r0, r1);
+          oh[e] = pack_bf16x2(r2, r3);
+          fl[e] = pack_f16x2(r0, r1);
+          fh[e] = pack_f16x2(r2, r3);
+        }
+        const uint4 vlo = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+        const uint4 vhi = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+        // in place: fp16 when the attention kernel is the consumer (three more mantissa bits than bf16
+        // for the score contraction), bf16 otherwise; the cache entry is always bf16
+        if (!a.cache_only) {
+          *reinterpret_cast<uint4*>(row + g * 8) = a.fp16_inplace ? make_uint4(fl[0], fl[1], fl[2], fl[3]) : vlo;
+          *reinterpret_cast<uint4*>(row + half + g * 8) = a.fp16_inplace ? make_uint4(fh[0], fh[1], fh[2], fh[3]) : vhi;
+        }
+        if (is_k && a.k_pool) {
+          bf16_t* dst = a.k_pool + (((size_t)(s / P) * a.n_kv_heads + hh) * P + (s % P)) * hd;
+          *reinterpret_cast<uint4*>(dst + g * 8) = vlo;
+          *reinterpret_cast<uint4*>(dst + half + g * 8) = vhi;
+        }
       }
     }
     return;
   }
   // ---- v head
-  const int hh = head - nq - a.n_kv_heads;
+  const int hh = blockIdx.y - n_rot_blocks;
   const int col = a.v_col + hh * hd;
   const int groups = hd >> 3;
   for (int it = threadIdx.x; it < 64 * groups; it += 256) {
@@ -290,7 +304,11 @@ __global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a) {
 void launch_rope_write(const RopeWriteArgs& a, hipStream_t st) {
   if (a.n_tiles <= 0) return;
   const int nq = a.q_col >= 0 ? a.n_q_heads : 0;
-  hipLaunchKernelGGL(rope_write_kernel, dim3(a.n_tiles, nq + 2 * a.n_kv_heads), dim3(256), 0, st, a);
+  // several heads per block once there are enough blocks to fill the chip a few times over
+  const int n_rot = nq + a.n_kv_heads;
+  const int hpb = std::max(1, std::min(4, (int)((long long)a.n_tiles * n_rot / 2048)));
+  const int n_rot_blocks = (n_rot + hpb - 1) / hpb;
+  hipLaunchKernelGGL(rope_write_kernel, dim3(a.n_tiles, n_rot_blocks + a.n_kv_heads), dim3(256), 0, st, a, hpb);
 }
 
 }  // namespace pop

@@ -52,6 +52,7 @@ struct RopeWriteArgs {
   bf16_t* v_pool;
   int page_size;
   int fp16_inplace;       // 1: rotated q and k are written back as fp16 (consumer = attention kernel)
+  int cache_only;         // 1: rotated k goes to the cache only, qkv is left as it is (K/V-only projection)
   bf16_t* vT;             // nullptr or [Hkv][hd][Tp]: transposed fp16 copy of V for the attention kernel
   int Tp;
   const int32_t* cu_seqlens;  // [B+1]
