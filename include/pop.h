@@ -106,8 +106,8 @@ typedef struct {
  * Validates the shape and records the weight pointers (borrowed: they must outlive the model).
  * Host-only, enqueues nothing, allocates no device memory.
  * Errors: POP_EINVAL (NULL, non-positive sizes, Hq % Hkv != 0), POP_ESHAPE (head_dim not in
- * {64,128,256}, d_model or d_ffn not a multiple of 8, page_size not a power of two in 1..256),
- * POP_EALIGN; POP_EINVAL also if a layer has only one of q_norm / k_norm.
+ * {64,128,256}, d_model or d_ffn not a multiple of 8, page_size not a power of two in 1..256, a bf16
+ * weight matrix of 2 GiB or more), POP_EALIGN; POP_EINVAL also if a layer has only one of q_norm / k_norm.
  */
 pop_status pop_load_weights(const pop_config* cfg, const pop_weights* w, pop_model** out);
 void pop_free_model(pop_model* m);

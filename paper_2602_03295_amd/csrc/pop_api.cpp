@@ -756,11 +756,19 @@ pop_status pop_load_weights(const pop_config* cfg, const pop_weights* w, pop_mod
     for (const void* p : ps) {
       if (!p) return fail(POP_EINVAL, "layer %d has a NULL weight pointer", l + 1);
       if (!aligned16(p)) return fail(POP_EALIGN, "layer %d has a weight pointer that is not 16-byte aligned", l + 1);
+    }
     if ((lw.q_norm == nullptr) != (lw.k_norm == nullptr))
       return fail(POP_EINVAL, "layer %d has only one of q_norm / k_norm", l + 1);
     if (!aligned16(lw.q_norm) || !aligned16(lw.k_norm))
       return fail(POP_EALIGN, "layer %d has a QK-norm scale that is not 16-byte aligned", l + 1);
-    }
+  }
+  if (cfg->dtype == POP_DTYPE_BF16) {
+    // the bf16 kernels address a matrix through a buffer descriptor with 31-bit byte offsets
+    const long long d = cfg->d_model, rows = std::max<long long>(
+        std::max<long long>(cfg->vocab, 2LL * cfg->d_ffn), (long long)(cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim);
+    const long long inner = std::max<long long>(std::max<long long>(d, cfg->d_ffn), (long long)cfg->n_q_heads * cfg->head_dim);
+    if (rows * d * 2 >= (1LL << 31) || d * inner * 2 >= (1LL << 31))
+      return fail(POP_ESHAPE, "a weight matrix would reach 2 GiB");
   }
   pop_model* m = new (std::nothrow) pop_model();
   if (!m) return fail(POP_EINVAL, "out of host memory");

@@ -104,6 +104,7 @@ def test_slot_map_errors():
     ({"n_layers": 0}, -1), ({"n_q_heads": 3}, -1), ({"head_dim": 48}, -2), ({"d_model": 260}, -2),
     ({"page_size": 12}, -2), ({"dtype": 7}, -1), ({"act": 5}, -1), ({"rope_theta": 0.0}, -1),
     ({"n_q_heads": 32, "n_kv_heads": 2}, -2),
+    ({"vocab": 1 << 20, "d_model": 1024}, -2),     # the LM head would be 2 GiB
 ])
 def test_load_weights_rejects_bad_configs(kw, status):
     st, h, _, _ = fake_model(bf16_cfg(**kw))
