@@ -165,6 +165,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ttft-sweep", action="store_true",
                     help="skip the batch-8 time-to-first-token sweep over prompt lengths (Table 2's shape)")
+    ap.add_argument("--no-decode", action="store_true",
+                    help="skip timing generation (decode steps with the full model after the pruned prefill)")
     ap.add_argument("--no-ablation-sweep", action="store_true",
                     help="skip timing the layer-selection variants and switches of the paper's ablation study")
     ap.add_argument("--no-other-workloads", action="store_true",
@@ -317,6 +319,43 @@ def main():
             ms = e0.elapsed_time(e1) / 5
             abl[name] = {"pruned_layers": len(kw["skip_layers"]), "ms_per_prompt": ms, "speedup_vs_full_depth": full_ms / ms}
         out["ablation_timing"] = abl
+    if not args.no_decode:
+        # generation after the pruned prefill (Sec. 3.2: decode runs the full model on the cache the prefill
+        # left): time of pop_generate for 1 and for 33 new tokens; the difference is 32 decode steps.
+        # A decode step streams every weight once plus the cache: HBM-bound.
+        lk = (2 * L) // 3
+        new = 33
+        p_layer = d * (dq + 2 * dkv) + dq * d + 3 * d * f
+        gen = {}
+        for batch in (1, 8):
+            lens = [n] * batch
+            btg, n_pages_g = synth.make_block_table(lens, cfg["page_size"], reserve_pages=(new + 15) // 16 + 1)
+            cache_g = pop.Cache(cfg, n_pages_g, batch, btg.shape[1])
+            wsg = pop.alloc_generate_workspace(cfg, batch * n, batch, btg.shape[1], new)
+            tokg = synth.make_tokens(cfg["vocab"], batch * n, seed=3)
+            cug = np.arange(batch + 1, dtype=np.int32) * n
+            lgg = torch.empty(batch, cfg["vocab"], dtype=torch.float32, device="cuda")
+            t = {}
+            for n_new in (1, new):
+                for _ in range(2):
+                    pop.pop_generate(model, cache_g, tokg, cug, btg, lk, n_new, wsg, logits=lgg, stream=stream)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(3):
+                    pop.pop_generate(model, cache_g, tokg, cug, btg, lk, n_new, wsg, logits=lgg, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                t[n_new] = e0.elapsed_time(e1) / 3
+            step_ms = (t[new] - t[1]) / (new - 1)
+            step_bytes = 2.0 * (L * p_layer + cfg["vocab"] * d) + 2.0 * batch * (n + new / 2) * L * 2 * dkv
+            gen[f"batch {batch}"] = {"prompt_tokens": n, "l_keep": lk, "ttft_ms": t[1], "ms_for_33_tokens": t[new],
+                                     "decode_ms_per_step": step_ms, "decode_tokens_per_s": batch / (step_ms * 1e-3),
+                                     "decode_hbm_bytes_per_step": step_bytes,
+                                     "decode_hbm_gb_per_s": step_bytes / (step_ms * 1e-3) / 1e9,
+                                     "decode_frac_of_hbm_peak": step_bytes / (step_ms * 1e-3) / 8e12}
+            del cache_g, wsg, lgg
+        out["generation"] = gen
     if not args.no_ttft_sweep:
         # time to first token of a batch of 8 equal-length prompts, pruned (last third of the layers
         # skipped for the body, the paper's static policy) against full depth: the shape of the paper's

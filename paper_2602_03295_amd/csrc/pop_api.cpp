@@ -398,7 +398,7 @@ int rows_for_gemm() {
 
 pop_status few_rows_projection(const LayerCtx& x, const bf16_t* in, const void* W, void* out, int B, int N, int K,
                                int ldo, int gemv_epi, int act) {
-  if (B < rows_for_gemm()) {
+  if (B < rows_for_gemm() || ldo % 4) {   // (the tiled GEMM stores four columns at a time)
     pop::launch_gemv(in, (const bf16_t*)W, out, B, N, K, ldo, gemv_epi, act, x.st);
     return POP_OK;
   }
@@ -468,8 +468,9 @@ pop_status lm_head(const LayerCtx& x, int B, float* dev_logits) {
   bf16_t* ab = at<bf16_t>(x.ws, x.w->o_ab);
   pop::launch_rmsnorm(xb, nullptr, nullptr, (const float*)x.m->w.final_norm, ab, nullptr, B, c.d_model, c.rms_eps,
                       x.st);
-  pop::launch_gemv(ab, (const bf16_t*)x.m->w.lm_head, dev_logits, B, c.vocab, c.d_model, c.vocab,
-                   pop::GEMV_STORE_F32, 0, x.st);
+  if (pop_status s = few_rows_projection(x, ab, x.m->w.lm_head, dev_logits, B, c.vocab, c.d_model, c.vocab,
+                                         pop::GEMV_STORE_F32, 0))
+    return s;
   POP_HIP(hipGetLastError());
   return POP_OK;
 }

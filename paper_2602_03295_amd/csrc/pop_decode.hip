@@ -2,6 +2,8 @@
 // They carry the boundary token of Sec. 3.3 ("Boundary Handling for the Last Input Token": x_N is
 // the first decode step with the full model) and pop_decode_step (Sec. 3.2, decode operator).
 // With M <= 8 rows every projection streams its weights once: these kernels are HBM-bound.
+#include <type_traits>
+
 #include "pop_device.h"
 #include "pop_kernels.h"
 
@@ -235,17 +237,18 @@ constexpr int GMAX = 8;   // query heads per KV head
 
 // grid (n_splits, Hkv, B), 256 threads.  Split s of sequence b covers keys lo + s*KCH .. +KCH-1,
 // lo = first visible key (window start, or the first position the layer holds an entry for).  Writes the unnormalised partial output, its max and its sum.
-template <int HD>
+// GT: compile-time bound of the number of query heads per KV head (registers and loops are sized by it).
+template <int HD, int GT>
 __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a, float scale) {
   constexpr int LPK = HD / 8;        // lanes per key (16-byte chunk each)
   constexpr int KPI = 256 / LPK;     // keys per block iteration
-  __shared__ float sc[GMAX][KCH];
-  __shared__ float red[4][GMAX][HD];  // one partial per wave
-  __shared__ float stat[GMAX][2];
+  __shared__ float sc[GT][KCH];
+  __shared__ float red[4][GT][HD];  // one partial per wave
+  __shared__ float stat[GT][2];
 
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int G = a.n_q_heads / a.n_kv_heads;
-  const int P = a.page_size;
+  const int P = a.page_size, lgP = __ffs(P) - 1;   // page sizes are powers of two
   const int qpos = a.pos[b];
   int lo = a.window > 0 ? max(0, qpos - a.window + 1) : 0;
   if (a.kv_first) lo = max(lo, min(a.kv_first[b], qpos));   // the query token's own entry always exists
@@ -266,9 +269,9 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
   }
 
   // ---- scores
-  float qv[GMAX][8];
+  float qv[GT][8];
 #pragma unroll
-  for (int g = 0; g < GMAX; ++g) {
+  for (int g = 0; g < GT; ++g) {
     if (g < G) {
       const uint4 w = *reinterpret_cast<const uint4*>(a.q + ((size_t)b * a.n_q_heads + kvh * G + g) * HD + li * 8);
       qv[g][0] = bf16lo(w.x); qv[g][1] = bf16hi(w.x); qv[g][2] = bf16lo(w.y); qv[g][3] = bf16hi(w.y);
@@ -285,8 +288,8 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
     vw[it] = make_uint4(0, 0, 0, 0);
     if (kk < n_keys) {
       const int key = k_first + kk;
-      const int page = bt[key / P];
-      const size_t off = (((size_t)page * a.n_kv_heads + kvh) * P + (key % P)) * HD + li * 8;
+      const int page = bt[key >> lgP];
+      const size_t off = (((size_t)page * a.n_kv_heads + kvh) * P + (key & (P - 1))) * HD + li * 8;
       kw[it] = *reinterpret_cast<const uint4*>(a.k_pool + off);
       vw[it] = *reinterpret_cast<const uint4*>(a.v_pool + off);
     }
@@ -294,25 +297,26 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     const int kk = kslot + it * KPI;
-    float s[GMAX];
+    float s[GT];
 #pragma unroll
-    for (int g = 0; g < GMAX; ++g) s[g] = 0.f;
+    for (int g = 0; g < GT; ++g) s[g] = 0.f;
     {
       const uint4 w = kw[it];
       const float kf[8] = {bf16lo(w.x), bf16hi(w.x), bf16lo(w.y), bf16hi(w.y),
                            bf16lo(w.z), bf16hi(w.z), bf16lo(w.w), bf16hi(w.w)};
 #pragma unroll
-      for (int g = 0; g < GMAX; ++g)
+      for (int g = 0; g < GT; ++g)
         if (g < G) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) s[g] += qv[g][e] * kf[e];
         }
     }
 #pragma unroll
-    for (int g = 0; g < GMAX; ++g)
+    for (int g = 0; g < GT; ++g)
       if (g < G) {
-#pragma unroll
-        for (int o = LPK / 2; o > 0; o >>= 1) s[g] += __shfl_xor(s[g], o, 64);
+        // the LPK lanes of a key are an aligned group inside a row of 16 lanes (two rows at head_dim 256)
+        s[g] = group_sum<(LPK < 16 ? LPK : 16)>(s[g]);
+        if (LPK > 16) s[g] += __shfl_xor(s[g], 16, 64);
         if (li == 0) sc[g][kk] = kk < n_keys ? s[g] * scale : -INFINITY;
       }
   }
@@ -323,22 +327,22 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
     for (int g = w; g < G; g += 4) {
       float mx = -INFINITY;
       for (int i = lane; i < KCH; i += 64) mx = fmaxf(mx, sc[g][i]);
-      mx = wave_max(mx);
+      mx = wave_max_rows(mx);
       float sum = 0.f;
       for (int i = lane; i < KCH; i += 64) {
         const float pv = __expf(sc[g][i] - mx);
         sc[g][i] = pv;
         sum += pv;
       }
-      sum = wave_sum(sum);
+      sum = wave_sum_rows(sum);
       if (lane == 0) { stat[g][0] = mx; stat[g][1] = sum; }
     }
   }
   __syncthreads();
   // ---- partial O = P V : thread owns 8 head-dim values, strides over keys
-  float acc[GMAX][8];
+  float acc[GT][8];
 #pragma unroll
-  for (int g = 0; g < GMAX; ++g)
+  for (int g = 0; g < GT; ++g)
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
 #pragma unroll
@@ -349,29 +353,48 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
     const float vf[8] = {bf16lo(w.x), bf16hi(w.x), bf16lo(w.y), bf16hi(w.y),
                          bf16lo(w.z), bf16hi(w.z), bf16lo(w.w), bf16hi(w.w)};
 #pragma unroll
-    for (int g = 0; g < GMAX; ++g)
+    for (int g = 0; g < GT; ++g)
       if (g < G) {
         const float pv = sc[g][kk];
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[g][e] += pv * vf[e];
       }
   }
-  // lanes li, li + LPK, ... of a wave hold the same head-dim slice: add them, then add the 4 waves
+  // Lanes li, li + LPK, ... of a wave hold partial sums of the same head-dim slice.  They are added by a
+  // butterfly that halves the number of values a lane carries at every step (a lane sends the half its partner
+  // keeps), so the GT * 8 values cost GT * 8 * (1 - LPK / 64) exchanges instead of GT * 8 per step; at the end
+  // the lanes of the different rows hold different values, and all of them write.  Then the 4 waves are added.
+  {
+    constexpr int NV = GT * 8;
+    float v[NV];
 #pragma unroll
-  for (int g = 0; g < GMAX; ++g)
-    if (g < G) {
+    for (int g = 0; g < GT; ++g)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float v = acc[g][e];
+      for (int e = 0; e < 8; ++e) v[g * 8 + e] = acc[g][e];
+    const int lane = tid & 63;
+    int first = 0;   // index (g * 8 + e) of this lane's v[0]
+    auto fold = [&](auto n_c, int o) {
+      constexpr int H = decltype(n_c)::value / 2;
+      const bool upper = (lane & o) != 0;
 #pragma unroll
-        for (int o = LPK; o < 64; o <<= 1) v += __shfl_xor(v, o, 64);
-        acc[g][e] = v;
+      for (int i = 0; i < H; ++i) {
+        const float send = upper ? v[i] : v[i + H];
+        const float keep = upper ? v[i + H] : v[i];
+        v[i] = keep + __shfl_xor(send, o, 64);
       }
-      if ((tid & 63) < LPK) {
+      if (upper) first += H;
+    };
+    constexpr int N1 = NV, N2 = LPK <= 32 ? N1 / 2 : N1, N3 = LPK <= 16 ? N2 / 2 : N2, N4 = LPK <= 8 ? N3 / 2 : N3;
+    if constexpr (LPK <= 32) fold(std::integral_constant<int, N1>{}, 32);
+    if constexpr (LPK <= 16) fold(std::integral_constant<int, N2>{}, 16);
+    if constexpr (LPK <= 8) fold(std::integral_constant<int, N3>{}, 8);
+    static_assert(N4 >= 1, "a lane keeps at least one value");
 #pragma unroll
-        for (int e = 0; e < 8; ++e) red[tid >> 6][g][li * 8 + e] = acc[g][e];
-      }
+    for (int i = 0; i < N4; ++i) {
+      const int idx = first + i, g = idx >> 3, e = idx & 7;
+      if (g < G) red[tid >> 6][g][li * 8 + e] = v[i];
     }
+  }
   __syncthreads();
   for (int i = tid; i < G * HD; i += 256) {
     const int g = i / HD, e = i % HD;
@@ -422,7 +445,12 @@ __global__ __launch_bounds__(256) void attn_decode_combine_kernel(const float* _
 template <int HD>
 void launch_decode_hd(const AttnDecodeArgs& a, hipStream_t st) {
   const float scale = 1.f / sqrtf((float)HD);
-  hipLaunchKernelGGL(attn_decode_split_kernel<HD>, dim3(a.n_splits, a.n_kv_heads, a.B), dim3(256), 0, st, a, scale);
+  const dim3 grid(a.n_splits, a.n_kv_heads, a.B);
+  const int G = a.n_q_heads / a.n_kv_heads;
+  if (G <= 1) hipLaunchKernelGGL((attn_decode_split_kernel<HD, 1>), grid, dim3(256), 0, st, a, scale);
+  else if (G <= 2) hipLaunchKernelGGL((attn_decode_split_kernel<HD, 2>), grid, dim3(256), 0, st, a, scale);
+  else if (G <= 4) hipLaunchKernelGGL((attn_decode_split_kernel<HD, 4>), grid, dim3(256), 0, st, a, scale);
+  else hipLaunchKernelGGL((attn_decode_split_kernel<HD, GMAX>), grid, dim3(256), 0, st, a, scale);
   hipLaunchKernelGGL(attn_decode_combine_kernel, dim3(a.B * a.n_q_heads), dim3(256), 0, st, a.part, a.out,
                      a.n_splits, HD);
 }

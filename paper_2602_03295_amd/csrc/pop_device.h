@@ -46,4 +46,43 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Data-parallel-primitive moves inside a row of 16 lanes: no trip through LDS, unlike __shfl_xor.
+// CTRL: 0xB1 = quad_perm [1,0,3,2], 0x4E = quad_perm [2,3,0,1], 0x141 = row_half_mirror (lane i <-> 7 - i of
+// each 8), 0x140 = row_mirror (lane i <-> 15 - i of each 16).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+// Sum / maximum over each aligned group of N consecutive lanes (N = 2, 4, 8, 16); every lane of the group
+// receives the same bits.
+template <int N>
+__device__ __forceinline__ float group_sum(float v) {
+  static_assert(N == 2 || N == 4 || N == 8 || N == 16, "group inside a row of 16 lanes");
+  v += dpp_f32<0xB1>(v);
+  if (N >= 4) v += dpp_f32<0x4E>(v);
+  if (N >= 8) v += dpp_f32<0x141>(v);
+  if (N >= 16) v += dpp_f32<0x140>(v);
+  return v;
+}
+template <int N>
+__device__ __forceinline__ float group_max(float v) {
+  static_assert(N == 2 || N == 4 || N == 8 || N == 16, "group inside a row of 16 lanes");
+  v = fmaxf(v, dpp_f32<0xB1>(v));
+  if (N >= 4) v = fmaxf(v, dpp_f32<0x4E>(v));
+  if (N >= 8) v = fmaxf(v, dpp_f32<0x141>(v));
+  if (N >= 16) v = fmaxf(v, dpp_f32<0x140>(v));
+  return v;
+}
+// Whole-wave forms: the four steps inside the rows as above, the two across rows through __shfl_xor.
+__device__ __forceinline__ float wave_sum_rows(float v) {
+  v = group_sum<16>(v);
+  v += __shfl_xor(v, 16, 64);
+  return v + __shfl_xor(v, 32, 64);
+}
+__device__ __forceinline__ float wave_max_rows(float v) {
+  v = group_max<16>(v);
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  return fmaxf(v, __shfl_xor(v, 32, 64));
+}
+
 }  // namespace pop
