@@ -41,6 +41,13 @@ pop_status pop_op_gemm_splitk(const void* A, int64_t lda, const void* W, int64_t
 pop_status pop_op_gemv(const void* x, const void* W, void* out, int64_t ldo, int32_t M, int32_t N, int32_t K,
                        int32_t epilogue, int32_t act, pop_stream stream);
 
+/* The normalisation of Sec. 2.1 (the LN of the layer equations; RMSNorm here) fused into the same kernel:
+ * the rows of x are DEVICE fp32 [M, K], normalised as pop_op_rmsnorm does (same bits) and rounded to bf16
+ * before the contraction.  gamma DEVICE fp32 [K].  M <= 4, K <= 8192 and 2 M K + 16 M <= 49152 (the
+ * normalised rows are held in LDS); POP_ESHAPE otherwise. */
+pop_status pop_op_gemv_norm(const void* x, const void* gamma, float eps, const void* W, void* out, int64_t ldo,
+                            int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t act, pop_stream stream);
+
 /* RoPE on q and k followed by causal GQA attention (Sec. 2.1: K/V generation and Attn) over packed
  * sequences.  qkv DEVICE bf16 [T, (Hq + 2 Hkv) * hd], rows q | k | v, q and k are rotated IN PLACE;
  * out DEVICE bf16 [T, Hq * hd].  host_cu_seqlens HOST [n_seqs + 1].  window 0 = global.

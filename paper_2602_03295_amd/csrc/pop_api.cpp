@@ -415,6 +415,19 @@ pop_status few_rows_projection(const LayerCtx& x, const bf16_t* in, const void* 
   return POP_OK;
 }
 
+// The same for fp32 rows that are RMS-normalised first (Sec. 2.1): with a few rows the GEMV kernel normalises
+// them itself; otherwise the norm kernel writes bf16 rows to `normed` and the projection reads those.
+pop_status normed_few_rows_projection(const LayerCtx& x, float* rows, const float* gamma, bf16_t* normed, const void* W,
+                                      void* out, int B, int N, int K, int ldo, int gemv_epi, int act) {
+  const float eps = x.m->cfg.rms_eps;
+  if (B < rows_for_gemm() && pop::gemv_norm_supported(B, K)) {
+    pop::launch_gemv_norm(rows, gamma, eps, (const bf16_t*)W, out, B, N, K, ldo, gemv_epi, act, x.st);
+    return POP_OK;
+  }
+  pop::launch_rmsnorm(rows, nullptr, nullptr, gamma, normed, nullptr, B, K, eps, x.st);
+  return few_rows_projection(x, normed, W, out, B, N, K, ldo, gemv_epi, act);
+}
+
 // One decode-style layer for B rows held in xb (fp32 [B, d]); pos/slot are device arrays [B].
 pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32_t* pos, const int32_t* slot,
                         int max_len) {
@@ -428,8 +441,9 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   bf16_t* attnb = at<bf16_t>(x.ws, x.w->o_attnb);
   bf16_t* ub = at<bf16_t>(x.ws, x.w->o_ub);
   const bool glob = layer_is_global(c, l);
-  pop::launch_rmsnorm(xb, nullptr, nullptr, (const float*)lw.norm_in, ab, nullptr, B, d, c.rms_eps, x.st);
-  if (pop_status s = few_rows_projection(x, ab, lw.wqkv, qkvb, B, Dqkv, d, Dqkv, pop::GEMV_STORE_F32, 0)) return s;
+  if (pop_status s = normed_few_rows_projection(x, xb, (const float*)lw.norm_in, ab, lw.wqkv, qkvb, B, Dqkv, d, Dqkv,
+                                                pop::GEMV_STORE_F32, 0))
+    return s;
   pop::launch_rope_append(qkvb, Dqkv, qb, c.n_q_heads, c.n_kv_heads, c.head_dim, pos, slot,
                           glob ? (double)c.rope_theta : (double)c.rope_theta_local, x.c->k_pool(l - 1),
                           x.c->v_pool(l - 1), c.page_size, B, x.st, (const float*)lw.q_norm, (const float*)lw.k_norm,
@@ -455,8 +469,9 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   ad.out = attnb;
   pop::launch_attention_decode(ad, x.st);
   if (pop_status s = few_rows_projection(x, attnb, lw.wo, xb, B, d, Dq, d, pop::GEMV_ADD_F32, 0)) return s;
-  pop::launch_rmsnorm(xb, nullptr, nullptr, (const float*)lw.norm_post, ab, nullptr, B, d, c.rms_eps, x.st);
-  if (pop_status s = few_rows_projection(x, ab, lw.w_gate_up, ub, B, f, d, f, pop::GEMV_GLU_BF16, c.act)) return s;
+  if (pop_status s = normed_few_rows_projection(x, xb, (const float*)lw.norm_post, ab, lw.w_gate_up, ub, B, f, d, f,
+                                                pop::GEMV_GLU_BF16, c.act))
+    return s;
   if (pop_status s = few_rows_projection(x, ub, lw.w_down, xb, B, d, f, d, pop::GEMV_ADD_F32, 0)) return s;
   POP_HIP(hipGetLastError());
   return POP_OK;
@@ -466,10 +481,8 @@ pop_status lm_head(const LayerCtx& x, int B, float* dev_logits) {
   const pop_config& c = x.m->cfg;
   float* xb = at<float>(x.ws, x.w->o_xb);
   bf16_t* ab = at<bf16_t>(x.ws, x.w->o_ab);
-  pop::launch_rmsnorm(xb, nullptr, nullptr, (const float*)x.m->w.final_norm, ab, nullptr, B, c.d_model, c.rms_eps,
-                      x.st);
-  if (pop_status s = few_rows_projection(x, ab, x.m->w.lm_head, dev_logits, B, c.vocab, c.d_model, c.vocab,
-                                         pop::GEMV_STORE_F32, 0))
+  if (pop_status s = normed_few_rows_projection(x, xb, (const float*)x.m->w.final_norm, ab, x.m->w.lm_head, dev_logits,
+                                                B, c.vocab, c.d_model, c.vocab, pop::GEMV_STORE_F32, 0))
     return s;
   POP_HIP(hipGetLastError());
   return POP_OK;
@@ -1418,6 +1431,20 @@ pop_status pop_op_gemv(const void* x, const void* W, void* out, int64_t ldo, int
   if (!aligned16(x) || !aligned16(W) || !aligned16(out)) return fail(POP_EALIGN, "pointer not 16-byte aligned");
   pop::launch_gemv((const bf16_t*)x, (const bf16_t*)W, out, M, N, K, ldo, epilogue, act,
                    reinterpret_cast<hipStream_t>(stream));
+  POP_HIP(hipGetLastError());
+  return POP_OK;
+}
+
+pop_status pop_op_gemv_norm(const void* x, const void* gamma, float eps, const void* W, void* out, int64_t ldo,
+                            int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t act, pop_stream stream) {
+  if (!x || !gamma || !W || !out) return fail(POP_EINVAL, "NULL pointer");
+  if (M < 0 || N < 0 || K < 8 || K % 8) return fail(POP_ESHAPE, "bad sizes");
+  if (M > 0 && !pop::gemv_norm_supported(M, K)) return fail(POP_ESHAPE, "the fused form holds at most 4 rows of at most 48 KB in all");
+  if (epilogue < 0 || epilogue > 2) return fail(POP_EINVAL, "unknown epilogue %d", epilogue);
+  if (!aligned16(x) || !aligned16(gamma) || !aligned16(W) || !aligned16(out))
+    return fail(POP_EALIGN, "pointer not 16-byte aligned");
+  pop::launch_gemv_norm((const float*)x, (const float*)gamma, eps, (const bf16_t*)W, out, M, N, K, ldo, epilogue, act,
+                        reinterpret_cast<hipStream_t>(stream));
   POP_HIP(hipGetLastError());
   return POP_OK;
 }

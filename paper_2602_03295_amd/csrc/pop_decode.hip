@@ -27,15 +27,22 @@ __device__ __forceinline__ void fma8(float (&acc), const uint4& w, const uint4& 
 // rows; lanes stride over K in 16-byte chunks; fp32 accumulation, wave reduction at the end.
 // The K loop is unrolled by U with all weight loads of an unrolled step issued before the first
 // multiply: with one row per step a wave has too few bytes in flight to cover HBM latency.
-template <int M, int EPI, int RW, int U>
-__global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ W,
-                                                   void* __restrict__ out, int N, int K, long long ldo, int act) {
+// NORM: the M input rows are fp32 rows xf that are RMS-normalised first (Sec. 2.1, the LN of the layer
+// equations): every work-group computes the M normalised bf16 rows into LDS, with the thread layout, the
+// summation order and the roundings of rmsnorm_kernel (same bits), which saves the launch of that kernel
+// and the round trip of its output.
+template <int M, int EPI, int RW, int U, bool NORM>
+__global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x, const float* __restrict__ xf,
+                                                   const float* __restrict__ gamma, float eps,
+                                                   const bf16_t* __restrict__ W, void* __restrict__ out, int N, int K,
+                                                   long long ldo, int act) {
   constexpr int NR = EPI == GEMV_GLU_BF16 ? 2 * RW : RW;  // weight rows streamed per wave
   typedef __attribute__((__vector_size__(16))) unsigned int u32x4_t;
+  extern __shared__ __attribute__((aligned(16))) unsigned char gemv_smem[];   // NORM: bf16 [M][K], then float [M][4]
+  const bf16_t* xs = reinterpret_cast<const bf16_t*>(gemv_smem);
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int n0 = (blockIdx.x * 4 + wave) * RW;
-  if (n0 >= N) return;
   const bf16_t* wr[NR];
 #pragma unroll
   for (int r = 0; r < NR; ++r) {
@@ -44,24 +51,77 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x,
     else row = min(n0 + r, N - 1);
     wr[r] = W + (size_t)row * K;
   }
-  float acc[NR][M];
-#pragma unroll
-  for (int r = 0; r < NR; ++r)
-#pragma unroll
-    for (int m = 0; m < M; ++m) acc[r][m] = 0.f;
   int k = lane * 8;
-  for (; k + (U - 1) * 512 < K; k += U * 512) {
-    u32x4_t wl[U][NR];
+  // NORM: the weights of the first unrolled step are requested before the rows are normalised, so that
+  // they travel meanwhile
+  u32x4_t wl[U][NR];
+  bool preloaded = NORM && k + (U - 1) * 512 < K;
+  if (preloaded) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int r = 0; r < NR; ++r)
         wl[u][r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wr[r] + k + u * 512));
+  }
+  if (NORM) {
+    bf16_t* xw = reinterpret_cast<bf16_t*>(gemv_smem);
+    float* red = reinterpret_cast<float*>(gemv_smem + (size_t)M * K * 2);
+#pragma unroll 1
+    for (int m = 0; m < M; ++m) {
+      const float* xr = xf + (size_t)m * K;
+      float4 v[8];
+      float ss = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int i = (j * 256 + threadIdx.x) * 4;
+        if (i < K) {
+          v[j] = *reinterpret_cast<const float4*>(xr + i);
+          ss += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
+        }
+      }
+      ss = wave_sum(ss);
+      if ((threadIdx.x & 63) == 0) red[m * 4 + (threadIdx.x >> 6)] = ss;
+      __syncthreads();
+      const float total = red[m * 4] + red[m * 4 + 1] + red[m * 4 + 2] + red[m * 4 + 3];
+      const float rstd = rsqrtf(total / (float)K + eps);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int i = (j * 256 + threadIdx.x) * 4;
+        if (i < K) {
+          const float4 gg = *reinterpret_cast<const float4*>(gamma + i);
+          uint2 pk;
+          pk.x = pack_bf16x2(v[j].x * rstd * gg.x, v[j].y * rstd * gg.y);
+          pk.y = pack_bf16x2(v[j].z * rstd * gg.z, v[j].w * rstd * gg.w);
+          *reinterpret_cast<uint2*>(xw + (size_t)m * K + i) = pk;
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (n0 >= N) return;
+  auto x_chunk = [&](int m, int k) {
+    return NORM ? *reinterpret_cast<const uint4*>(xs + (size_t)m * K + k)
+                : *reinterpret_cast<const uint4*>(x + (size_t)m * K + k);
+  };
+  float acc[NR][M];
+#pragma unroll
+  for (int r = 0; r < NR; ++r)
+#pragma unroll
+    for (int m = 0; m < M; ++m) acc[r][m] = 0.f;
+  for (; k + (U - 1) * 512 < K; k += U * 512) {
+    if (!preloaded) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+          wl[u][r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wr[r] + k + u * 512));
+    }
+    preloaded = false;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       uint4 xv[M];
 #pragma unroll
-      for (int m = 0; m < M; ++m) xv[m] = *reinterpret_cast<const uint4*>(x + (size_t)m * K + k + u * 512);
+      for (int m = 0; m < M; ++m) xv[m] = x_chunk(m, k + u * 512);
 #pragma unroll
       for (int r = 0; r < NR; ++r) {
         const uint4 wv = make_uint4(wl[u][r][0], wl[u][r][1], wl[u][r][2], wl[u][r][3]);
@@ -73,11 +133,11 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x,
   for (; k < K; k += 512) {
     uint4 xv[M];
 #pragma unroll
-    for (int m = 0; m < M; ++m) xv[m] = *reinterpret_cast<const uint4*>(x + (size_t)m * K + k);
+    for (int m = 0; m < M; ++m) xv[m] = x_chunk(m, k);
 #pragma unroll
     for (int r = 0; r < NR; ++r) {
-      const u32x4_t wl = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wr[r] + k));
-      const uint4 wv = make_uint4(wl[0], wl[1], wl[2], wl[3]);
+      const u32x4_t wt = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wr[r] + k));
+      const uint4 wv = make_uint4(wt[0], wt[1], wt[2], wt[3]);
 #pragma unroll
       for (int m = 0; m < M; ++m) fma8(acc[r][m], wv, xv[m]);
     }
@@ -103,16 +163,29 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x,
   }
 }
 
+// The input of a projection: bf16 rows x, or (xf != nullptr) fp32 rows to be RMS-normalised with gamma / eps.
+struct GemvIn {
+  const bf16_t* x;
+  const float* xf;
+  const float* gamma;
+  float eps;
+};
+
 template <int M, int EPI, int RW, int U>
-void launch_gemv_cfg(const bf16_t* x, const bf16_t* W, void* out, int N, int K, long long ldo, int act, hipStream_t st) {
+void launch_gemv_cfg(const GemvIn& in, const bf16_t* W, void* out, int N, int K, long long ldo, int act, hipStream_t st) {
   const int blocks = (N + 4 * RW - 1) / (4 * RW);
-  hipLaunchKernelGGL((gemv_kernel<M, EPI, RW, U>), dim3(blocks), dim3(256), 0, st, x, W, out, N, K, ldo, act);
+  if (in.xf)
+    hipLaunchKernelGGL((gemv_kernel<M, EPI, RW, U, true>), dim3(blocks), dim3(256), (size_t)M * K * 2 + 16 * M, st,
+                       in.x, in.xf, in.gamma, in.eps, W, out, N, K, ldo, act);
+  else
+    hipLaunchKernelGGL((gemv_kernel<M, EPI, RW, U, false>), dim3(blocks), dim3(256), 0, st, in.x, in.xf, in.gamma,
+                       in.eps, W, out, N, K, ldo, act);
 }
 
 // Rows per wave and unroll depth: few batch rows leave registers for deep unrolling; a small N gets
 // two rows per wave so that the launch still has several waves per SIMD.
 template <int M, int EPI>
-void launch_gemv_me(const bf16_t* x, const bf16_t* W, void* out, int N, int K, long long ldo, int act, hipStream_t st) {
+void launch_gemv_me(const GemvIn& x, const bf16_t* W, void* out, int N, int K, long long ldo, int act, hipStream_t st) {
   if (EPI == GEMV_GLU_BF16) {
     if (M <= 2) launch_gemv_cfg<M, EPI, 2, 4>(x, W, out, N, K, ldo, act, st);
     else launch_gemv_cfg<M, EPI, 2, 1>(x, W, out, N, K, ldo, act, st);
@@ -127,7 +200,7 @@ void launch_gemv_me(const bf16_t* x, const bf16_t* W, void* out, int N, int K, l
 }
 
 template <int M>
-void launch_gemv_m(const bf16_t* x, const bf16_t* W, void* out, int N, int K, long long ldo, int epi, int act,
+void launch_gemv_m(const GemvIn& x, const bf16_t* W, void* out, int N, int K, long long ldo, int epi, int act,
                    hipStream_t st) {
   switch (epi) {
     case GEMV_STORE_F32: launch_gemv_me<M, GEMV_STORE_F32>(x, W, out, N, K, ldo, act, st); break;
@@ -136,31 +209,53 @@ void launch_gemv_m(const bf16_t* x, const bf16_t* W, void* out, int N, int K, lo
   }
 }
 
-}  // namespace decode_impl
-using namespace decode_impl;
+// rows m0 .. m0 + mm - 1 of the input
+GemvIn rows_from(const GemvIn& in, int m0, int K) {
+  GemvIn r = in;
+  if (r.xf) r.xf += (size_t)m0 * K;
+  else r.x += (size_t)m0 * K;
+  return r;
+}
 
-void launch_gemv(const bf16_t* x, const bf16_t* W, void* out, int M, int N, int K, int64_t ldo, int epilogue,
-                 int act, hipStream_t st) {
+void launch_gemv_in(const GemvIn& in, const bf16_t* W, void* out, int M, int N, int K, int64_t ldo, int epilogue,
+                    int act, hipStream_t st) {
   if (M <= 0 || N <= 0) return;
   // rows are processed in groups of at most 8 (weights are re-streamed per group)
   const size_t osz = epilogue == GEMV_GLU_BF16 ? 2 : 4;
   for (int m0 = 0; m0 < M; m0 += 8) {
     const int mm = M - m0 < 8 ? M - m0 : 8;
-    const bf16_t* xs = x + (size_t)m0 * K;
+    const GemvIn xs = rows_from(in, m0, K);
     void* os = reinterpret_cast<char*>(out) + (size_t)m0 * ldo * osz;
     if (mm == 1) launch_gemv_m<1>(xs, W, os, N, K, ldo, epilogue, act, st);
     else if (mm == 2) launch_gemv_m<2>(xs, W, os, N, K, ldo, epilogue, act, st);
     else if (mm <= 4) {
-      // pad to 4 rows by processing 2+2 / 2+1 splits would re-stream weights; use exact sizes instead
+      // 3 rows: 2 + 1 (exact sizes; padding to 4 would cost registers in the 2-row form's deep unrolling)
       if (mm == 3) { launch_gemv_m<2>(xs, W, os, N, K, ldo, epilogue, act, st);
-                     launch_gemv_m<1>(xs + 2 * (size_t)K, W, reinterpret_cast<char*>(os) + 2 * ldo * osz, N, K, ldo, epilogue, act, st); }
+                     launch_gemv_m<1>(rows_from(xs, 2, K), W, reinterpret_cast<char*>(os) + 2 * ldo * osz, N, K, ldo, epilogue, act, st); }
       else launch_gemv_m<4>(xs, W, os, N, K, ldo, epilogue, act, st);
     } else if (mm == 8) launch_gemv_m<8>(xs, W, os, N, K, ldo, epilogue, act, st);
     else {  // 5..7: 4 + remainder
       launch_gemv_m<4>(xs, W, os, N, K, ldo, epilogue, act, st);
-      launch_gemv(xs + 4 * (size_t)K, W, reinterpret_cast<char*>(os) + 4 * ldo * osz, mm - 4, N, K, ldo, epilogue, act, st);
+      launch_gemv_in(rows_from(xs, 4, K), W, reinterpret_cast<char*>(os) + 4 * ldo * osz, mm - 4, N, K, ldo, epilogue, act, st);
     }
   }
+}
+
+}  // namespace decode_impl
+using namespace decode_impl;
+
+void launch_gemv(const bf16_t* x, const bf16_t* W, void* out, int M, int N, int K, int64_t ldo, int epilogue,
+                 int act, hipStream_t st) {
+  launch_gemv_in(GemvIn{x, nullptr, nullptr, 0.f}, W, out, M, N, K, ldo, epilogue, act, st);
+}
+
+bool gemv_norm_supported(int M, int K) {
+  return M >= 1 && M <= 4 && K % 8 == 0 && K <= 8192 && (size_t)M * K * 2 + 16 * M <= 48 * 1024;
+}
+
+void launch_gemv_norm(const float* xf, const float* gamma, float eps, const bf16_t* W, void* out, int M, int N, int K,
+                      int64_t ldo, int epilogue, int act, hipStream_t st) {
+  launch_gemv_in(GemvIn{nullptr, xf, gamma, eps}, W, out, M, N, K, ldo, epilogue, act, st);
 }
 
 // ------------------------------------------------------------------------------------- RoPE + append

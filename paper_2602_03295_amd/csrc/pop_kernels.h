@@ -123,6 +123,12 @@ enum GemvEpilogue { GEMV_STORE_F32 = 0, GEMV_ADD_F32 = 1, GEMV_GLU_BF16 = 2 };
 // out[m, n] (op)= sum_k x[m,k] * W[n,k], x bf16 [M, K] (M <= 8), W bf16 [N, K] ([2N, K] for GLU).
 void launch_gemv(const bf16_t* x, const bf16_t* W, void* out, int M, int N, int K, int64_t ldo,
                  int epilogue, int act, hipStream_t st);
+// The same with the RMSNorm of the input fused in (Sec. 2.1): xf fp32 [M, K] is normalised with gamma / eps
+// inside the kernel (bit-identical to launch_rmsnorm followed by launch_gemv).  Only where
+// gemv_norm_supported(M, K): M <= 4 rows whose normalised copies fit 48 KB of LDS.
+bool gemv_norm_supported(int M, int K);
+void launch_gemv_norm(const float* xf, const float* gamma, float eps, const bf16_t* W, void* out, int M, int N, int K,
+                      int64_t ldo, int epilogue, int act, hipStream_t st);
 
 // RoPE of one new token per sequence + cache append: qkv fp32 [B, ld] -> q bf16 [B, Hq*hd] rotated,
 // k (rotated) and v stored at slot[b].

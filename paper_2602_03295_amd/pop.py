@@ -91,6 +91,8 @@ lib.pop_op_gemm_splitk.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
                                    C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
 lib.pop_op_gemv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                             C.c_int32, C.c_int32, C.c_void_p]
+lib.pop_op_gemv_norm.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                 C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
 lib.pop_op_rope_attention_workspace.argtypes = [C.c_int32] * 4
 lib.pop_op_rope_attention_workspace.restype = C.c_size_t
 lib.pop_op_rope_attention.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_float,
@@ -105,7 +107,7 @@ EXPORTED = ["pop_timing_enable", "pop_timing_read", "pop_last_error", "pop_versi
             "pop_workspace_bytes", "pop_cache_create", "pop_cache_destroy", "pop_cache_n_seqs",
             "pop_cache_seq_lens", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_generate",
             "pop_generate_workspace_bytes", "pop_op_rmsnorm",
-            "pop_op_gemm", "pop_op_gemm_splitk", "pop_op_gemv", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
+            "pop_op_gemm", "pop_op_gemm_splitk", "pop_op_gemv", "pop_op_gemv_norm", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
 
 
 def _check(status: int) -> None:
@@ -368,6 +370,18 @@ def pop_op_gemv(x: torch.Tensor, W: torch.Tensor, epilogue: int = 0, act: int = 
         out = torch.zeros(M, N, dtype=torch.bfloat16 if epilogue == 2 else torch.float32, device=x.device)
     _check(lib.pop_op_gemv(x.data_ptr(), W.data_ptr(), out.data_ptr(), out.stride(0), M, N, K, epilogue, act,
                            _stream(stream)))
+    return out
+
+
+def pop_op_gemv_norm(x: torch.Tensor, gamma: torch.Tensor, eps: float, W: torch.Tensor, epilogue: int = 0, act: int = 0,
+                     out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """x fp32 [M, K] is RMS-normalised (gamma, eps) inside the kernel, then contracted with W as pop_op_gemv does."""
+    M, K = x.shape
+    N = W.shape[0] // 2 if epilogue == 2 else W.shape[0]
+    if out is None:
+        out = torch.zeros(M, N, dtype=torch.bfloat16 if epilogue == 2 else torch.float32, device=x.device)
+    _check(lib.pop_op_gemv_norm(x.data_ptr(), gamma.data_ptr(), eps, W.data_ptr(), out.data_ptr(), out.stride(0),
+                                M, N, K, epilogue, act, _stream(stream)))
     return out
 
 

@@ -111,6 +111,29 @@ def test_gemv(pop, M, epi):
     assert rel(got.float().cpu().numpy(), ref) <= (2.0 ** -7 if epi == 2 else 1e-5)
 
 
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+@pytest.mark.parametrize("epi", [0, 2])
+def test_gemv_with_fused_rmsnorm(pop, M, epi):
+    """The few-row projection that normalises its fp32 input rows itself: against the oracle's RMSNorm
+    followed by the contraction, and bit for bit against the two separate kernels."""
+    N, K = 1003 if epi != 2 else 1002, 1384
+    rng = np.random.default_rng(100 + M * 10 + epi)
+    x = (rng.standard_normal((M, K)) * 2.5).astype(np.float32)
+    g = (1 + 0.1 * rng.standard_normal(K)).astype(np.float32)
+    W = bf16_round(rng.standard_normal(((2 if epi == 2 else 1) * N, K)).astype(np.float32) * 0.3)
+    xd, gd, Wd = torch.from_numpy(x).cuda(), torch.from_numpy(g).cuda(), W.cuda()
+    got = pop.pop_op_gemv_norm(xd, gd, 1e-5, Wd, epilogue=epi, act=0)
+    two = pop.pop_op_gemv(pop.pop_op_rmsnorm(xd, gd, 1e-5), Wd, epilogue=epi, act=0)
+    torch.cuda.synchronize()
+    assert torch.equal(got, two)
+    a = O.rmsnorm(x.astype(np.float64), g.astype(np.float64), 1e-5)
+    Wn = W.double().numpy()
+    ref = O.glu_act(a @ Wn[:N].T, 0) * (a @ Wn[N:].T) if epi == 2 else a @ Wn.T
+    assert rel(got.float().cpu().numpy(), ref) <= 2.0 ** -7     # the normalised rows are rounded to bf16
+    with pytest.raises(pop.PopError):
+        pop.pop_op_gemv_norm(torch.zeros(5, K, device="cuda"), gd, 1e-5, Wd, epilogue=epi)
+
+
 @pytest.mark.parametrize("hd,hq,hkv", [(64, 4, 2), (128, 8, 2), (256, 2, 1)])
 @pytest.mark.parametrize("window", [0, 100])
 def test_rope_attention_varlen(pop, hd, hq, hkv, window):
