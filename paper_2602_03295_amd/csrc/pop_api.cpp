@@ -295,6 +295,9 @@ struct LayerCtx {
   const Workspace* w;
   hipStream_t st;
   const int32_t* kv_first = nullptr;  // DEVICE [n_layers][B] or nullptr (every layer holds every position)
+  // The norm scale with which the bf16 scratch rows `ab` hold RMSNorm(xb), or nullptr when they do not: a split
+  // projection with a residual epilogue normalises its result for the next projection in its second kernel.
+  mutable const float* ab_gamma = nullptr;
 };
 
 // The prefill's pruning, resolved from the arguments (Sec. 2.2: a skip set; Sec. 3.3: applied to the
@@ -420,6 +423,8 @@ pop_status few_rows_projection(const LayerCtx& x, const bf16_t* in, const void* 
 pop_status normed_few_rows_projection(const LayerCtx& x, float* rows, const float* gamma, bf16_t* normed, const void* W,
                                       void* out, int B, int N, int K, int ldo, int gemv_epi, int act) {
   const float eps = x.m->cfg.rms_eps;
+  if (x.ab_gamma == gamma && gamma != nullptr)   // the previous projection's second kernel left them in `normed`
+    return few_rows_projection(x, normed, W, out, B, N, K, ldo, gemv_epi, act);
   if (B < rows_for_gemm() && pop::gemv_norm_supported(B, K)) {
     pop::launch_gemv_norm(rows, gamma, eps, (const bf16_t*)W, out, B, N, K, ldo, gemv_epi, act, x.st);
     return POP_OK;
@@ -428,9 +433,42 @@ pop_status normed_few_rows_projection(const LayerCtx& x, float* rows, const floa
   return few_rows_projection(x, normed, W, out, B, N, K, ldo, gemv_epi, act);
 }
 
+// xb += in W^T for the B rows of a decode-style layer.  With next_gamma the caller announces the norm scale of the
+// projection that follows: when this one runs as a split GEMM its second kernel then also writes
+// RMSNorm(xb; next_gamma) to ab (and records that in x.ab_gamma), which saves that projection's norm launch.
+pop_status residual_few_rows_projection(const LayerCtx& x, const bf16_t* in, const void* W, int B, int N, int K,
+                                        const float* next_gamma) {
+  float* xb = at<float>(x.ws, x.w->o_xb);
+  x.ab_gamma = nullptr;
+  if (B < rows_for_gemm() || N % 4) {
+    pop::launch_gemv(in, (const bf16_t*)W, xb, B, N, K, N, pop::GEMV_ADD_F32, 0, x.st);
+    return POP_OK;
+  }
+  pop::GemmArgs g{};
+  g.batch = 1;
+  g.A = in; g.lda = K; g.W = (const bf16_t*)W; g.ldw = K; g.out = xb; g.ldc = N;
+  g.M = B; g.N = N; g.K = K;
+  g.epilogue = pop::EPI_ADD_F32;
+  g.splitk_ws = x.w->splitk_bytes ? at<float>(x.ws, x.w->o_splitk) : nullptr;
+  g.splitk_ws_bytes = x.w->splitk_bytes;
+  int S = 1;
+  g.partials_only = next_gamma != nullptr && N <= 8192;
+  g.split_used = &S;
+  hipError_t e = pop::launch_gemm(g, x.st);
+  if (e != hipSuccess) return fail(POP_EHIP, "projection launch failed: %s", hipGetErrorString(e));
+  if (g.partials_only && S > 1) {
+    pop::launch_add_parts_rmsnorm(xb, g.splitk_ws, S, (size_t)B * N, next_gamma, at<bf16_t>(x.ws, x.w->o_ab), B, N,
+                                  x.m->cfg.rms_eps, x.st);
+    x.ab_gamma = next_gamma;
+  }
+  return POP_OK;
+}
+
 // One decode-style layer for B rows held in xb (fp32 [B, d]); pos/slot are device arrays [B].
+// next_gamma: norm scale of the projection that will read xb next (the next layer's input norm, the final norm),
+// or nullptr when something else happens to the rows first.
 pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32_t* pos, const int32_t* slot,
-                        int max_len) {
+                        int max_len, const float* next_gamma) {
   const pop_config& c = x.m->cfg;
   const pop_layer_weights& lw = x.m->layers[l - 1];
   const int d = c.d_model, f = c.d_ffn, Dq = x.m->Dq, Dqkv = x.m->Dqkv;
@@ -468,11 +506,11 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   ad.part = at<float>(x.ws, x.w->o_part);
   ad.out = attnb;
   pop::launch_attention_decode(ad, x.st);
-  if (pop_status s = few_rows_projection(x, attnb, lw.wo, xb, B, d, Dq, d, pop::GEMV_ADD_F32, 0)) return s;
+  if (pop_status s = residual_few_rows_projection(x, attnb, lw.wo, B, d, Dq, (const float*)lw.norm_post)) return s;
   if (pop_status s = normed_few_rows_projection(x, xb, (const float*)lw.norm_post, ab, lw.w_gate_up, ub, B, f, d, f,
                                                 pop::GEMV_GLU_BF16, c.act))
     return s;
-  if (pop_status s = few_rows_projection(x, ub, lw.w_down, xb, B, d, f, d, pop::GEMV_ADD_F32, 0)) return s;
+  if (pop_status s = residual_few_rows_projection(x, ub, lw.w_down, B, d, f, next_gamma)) return s;
   POP_HIP(hipGetLastError());
   return POP_OK;
 }
@@ -1211,10 +1249,15 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     if (boundary) {
       StepTimer tm(m, st, POP_STEP_BOUNDARY);
       pop::launch_gather_rows(h, bnd_row, xb, B, d, st);
+      x.ab_gamma = nullptr;
       rows_in_xb = true;
-      for (int j = l; j <= r; ++j)
-        if (pop_status s = decode_layer(x, j, B, at<int32_t>(ws, w.o_bnd_pos), at<int32_t>(ws, w.o_bnd_slot), max_len))
+      for (int j = l; j <= r; ++j) {
+        // what reads these rows next: the following layer of the run, the LM head, or (a kept layer follows) h
+        const float* next = j < r ? (const float*)m->layers[j].norm_in
+                            : (r == cfg.n_layers && a->mode != POP_MODE_BODY_ONLY ? (const float*)m->w.final_norm : nullptr);
+        if (pop_status s = decode_layer(x, j, B, at<int32_t>(ws, w.o_bnd_pos), at<int32_t>(ws, w.o_bnd_slot), max_len, next))
           return s;
+      }
     }
     l = r + 1;
   }
@@ -1222,7 +1265,10 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   //      model's output for it
   if (a->mode != POP_MODE_BODY_ONLY) {
     StepTimer tm(m, st, POP_STEP_BOUNDARY);
-    if (!rows_in_xb) pop::launch_gather_rows(h, bnd_row, xb, B, d, st);
+    if (!rows_in_xb) {
+      pop::launch_gather_rows(h, bnd_row, xb, B, d, st);
+      x.ab_gamma = nullptr;
+    }
     if (pop_status s = lm_head(x, B, dev_logits)) return s;
   }
   return POP_OK;
@@ -1276,9 +1322,11 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
   x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;
   pop::launch_embed((const bf16_t*)m->w.embed, at<int32_t>(ws, w.o_tokens), nullptr, nullptr, at<float>(ws, w.o_xb),
                     B, cfg.d_model, st);
-  for (int l = 1; l <= cfg.n_layers; ++l)
-    if (pop_status s = decode_layer(x, l, B, at<int32_t>(ws, w.o_bnd_pos), at<int32_t>(ws, w.o_bnd_slot), max_len))
+  for (int l = 1; l <= cfg.n_layers; ++l) {
+    const float* next = (const float*)(l < cfg.n_layers ? m->layers[l].norm_in : m->w.final_norm);
+    if (pop_status s = decode_layer(x, l, B, at<int32_t>(ws, w.o_bnd_pos), at<int32_t>(ws, w.o_bnd_slot), max_len, next))
       return s;
+  }
   return lm_head(x, B, dev_logits);
 }
 
@@ -1362,9 +1410,13 @@ pop_status pop_generate(pop_model* m, pop_cache* c, const pop_prefill_args* a, i
     x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;   // uploaded by the prefill
     for (int s = 1; s < n_new; ++s) {
       pop::launch_embed((const bf16_t*)m->w.embed, d_tok, nullptr, nullptr, at<float>(ws, w.o_xb), B, cfg.d_model, st);
-      for (int l = 1; l <= cfg.n_layers; ++l)
-        if (pop_status e = decode_layer(x, l, B, d_gpos + (size_t)(s - 1) * B, d_gslot + (size_t)(s - 1) * B, max_len + s))
+      x.ab_gamma = nullptr;
+      for (int l = 1; l <= cfg.n_layers; ++l) {
+        const float* next = (const float*)(l < cfg.n_layers ? m->layers[l].norm_in : m->w.final_norm);
+        if (pop_status e = decode_layer(x, l, B, d_gpos + (size_t)(s - 1) * B, d_gslot + (size_t)(s - 1) * B, max_len + s,
+                                        next))
           return e;
+      }
       if (pop_status e = lm_head(x, B, dev_logits)) return e;
       pop::launch_argmax(dev_logits, cfg.vocab, d_tok, dev_tokens_out, n_new, s, eos_token, B, st);
     }

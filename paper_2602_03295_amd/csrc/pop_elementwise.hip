@@ -129,6 +129,61 @@ void launch_rmsnorm(float* x, const float* add1, const float* add2, const float*
                      row_idx, d, eps);
 }
 
+// Same thread layout, summation order and roundings as rmsnorm_kernel; the parts are added in the order of
+// splitk_reduce_kernel (parts first, then the old value).
+__global__ __launch_bounds__(256) void add_parts_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ parts,
+                                                                int S, size_t part_stride,
+                                                                const float* __restrict__ gamma,
+                                                                bf16_t* __restrict__ out, int d, float eps) {
+  __shared__ float red[4];
+  const size_t row = blockIdx.x;
+  float* xr = x + row * d;
+  float4 v[kNormMaxV];
+  float ss = 0.f;
+#pragma unroll
+  for (int j = 0; j < kNormMaxV; ++j) {
+    const int i = (j * 256 + threadIdx.x) * 4;
+    if (i < d) {
+      const float* p0 = parts + row * d + i;
+      // all parts are requested before the first addition (S <= 8; few blocks run, so latency is what counts)
+      float4 q[8];
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+        if (s < S) q[s] = *reinterpret_cast<const float4*>(p0 + (size_t)s * part_stride);
+      const float4 old = *reinterpret_cast<const float4*>(xr + i);
+      float4 acc = q[0];
+#pragma unroll
+      for (int s = 1; s < 8; ++s)
+        if (s < S) { acc.x += q[s].x; acc.y += q[s].y; acc.z += q[s].z; acc.w += q[s].w; }
+      acc.x += old.x; acc.y += old.y; acc.z += old.z; acc.w += old.w;
+      *reinterpret_cast<float4*>(xr + i) = acc;
+      v[j] = acc;
+      ss += acc.x * acc.x + acc.y * acc.y + acc.z * acc.z + acc.w * acc.w;
+    }
+  }
+  const float total = block_sum_256(ss, red);
+  const float rstd = rsqrtf(total / (float)d + eps);
+  bf16_t* orow = out + row * d;
+#pragma unroll
+  for (int j = 0; j < kNormMaxV; ++j) {
+    const int i = (j * 256 + threadIdx.x) * 4;
+    if (i < d) {
+      const float4 gg = *reinterpret_cast<const float4*>(gamma + i);
+      uint2 p;
+      p.x = pack_bf16x2(v[j].x * rstd * gg.x, v[j].y * rstd * gg.y);
+      p.y = pack_bf16x2(v[j].z * rstd * gg.z, v[j].w * rstd * gg.w);
+      *reinterpret_cast<uint2*>(orow + i) = p;
+    }
+  }
+}
+
+void launch_add_parts_rmsnorm(float* x, const float* parts, int S, size_t part_stride, const float* gamma, bf16_t* out,
+                              int rows, int d, float eps, hipStream_t st) {
+  if (rows <= 0 || S < 1 || S > 8) return;
+  hipLaunchKernelGGL(add_parts_rmsnorm_kernel, dim3(rows), dim3(256), 0, st, x, parts, S, part_stride, gamma, out, d,
+                     eps);
+}
+
 void launch_rmsnorm_multi(const float* x, GammaList gammas, int n_out, bf16_t* out, size_t out_stride,
                           int rows, int d, float eps, hipStream_t st, const int32_t* row_idx) {
   if (rows <= 0 || n_out <= 0) return;

@@ -644,6 +644,7 @@ inline int choose_split(const GemmArgs& g) {
 }  // namespace gemm_impl
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
+  if (g.split_used) *g.split_used = 1;
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.K <= 0 || g.K % 8 || g.lda % 8 || g.ldw % 8 || g.ldc % 4) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.W) |
@@ -664,7 +665,13 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
     part.strideC = (int64_t)g.M * g.N;
     part.epilogue = EPI_STORE_F32;
     part.splitk_ws = nullptr;
+    part.partials_only = false;
+    part.split_used = nullptr;
     if (hipError_t e = launch_epi<EPI_STORE_F32>(part, st); e != hipSuccess) return e;
+    if (g.partials_only && g.split_used && S <= 8) {   // (the callers' second kernels take up to 8 parts)
+      *g.split_used = S;
+      return hipGetLastError();
+    }
     const long long items = (long long)g.M * (g.N / 4);
     const dim3 grid((unsigned)((items + 255) / 256));
     switch (g.epilogue) {

@@ -31,6 +31,12 @@ struct GammaList {
 };
 void launch_rmsnorm_multi(const float* x, GammaList gammas, int n_out, bf16_t* out, size_t out_stride,
                           int rows, int d, float eps, hipStream_t st, const int32_t* row_idx = nullptr);
+// x[r] += parts[0][r] + parts[1][r] + ... + parts[S-1][r] (fp32 [rows, d] each, part_stride elements apart, added
+// in index order), then out[r] = bf16(RMSNorm(x[r]; gamma, eps)): the second kernel of a split projection with a
+// residual epilogue and the normalisation that follows it (Sec. 2.1), in one launch.  d % 4 == 0, d <= 8192,
+// 1 <= S <= 8.
+void launch_add_parts_rmsnorm(float* x, const float* parts, int S, size_t part_stride, const float* gamma, bf16_t* out,
+                              int rows, int d, float eps, hipStream_t st);
 
 // cs[t, i] = (cos, sin)(pos[t] * theta^(-2 i / hd)), i < hd/2, angle formed in fp64.
 void launch_rope_table(const int32_t* pos, float2* cs, int T, int hd, double theta, hipStream_t st);
@@ -91,6 +97,11 @@ struct GemmArgs {
   // partial product here, and a second kernel adds the parts in a fixed order and applies the epilogue.
   float* splitk_ws;          // DEVICE, 16-byte aligned, or nullptr (never split)
   size_t splitk_ws_bytes;
+  // With partials_only a split launch stops after the partial products (fp32 [S][M][N] dense in splitk_ws) and
+  // leaves adding them and the epilogue to the caller; *split_used receives S (1: not split, or more than 8
+  // parts: epilogue applied as usual).
+  bool partials_only;
+  int* split_used;
 };
 // Returns hipSuccess or the launch error.  Requirements: K % 8 == 0, lda/ldw % 8 == 0,
 // A/W 16-byte aligned, ldc % 4 == 0, and every operand below 2^31 bytes.
