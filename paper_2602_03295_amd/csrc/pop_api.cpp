@@ -399,8 +399,12 @@ int rows_for_gemm() {
   return v;
 }
 
+// parts_out (optional): the caller can add partial products itself.  If the K range was split, *parts_out receives
+// the number of parts (fp32 [parts][B][N] dense at the split scratch of the workspace) and `out` is not written;
+// otherwise it receives 1.
 pop_status few_rows_projection(const LayerCtx& x, const bf16_t* in, const void* W, void* out, int B, int N, int K,
-                               int ldo, int gemv_epi, int act) {
+                               int ldo, int gemv_epi, int act, int* parts_out = nullptr) {
+  if (parts_out) *parts_out = 1;
   if (B < rows_for_gemm() || ldo % 4) {   // (the tiled GEMM stores four columns at a time)
     pop::launch_gemv(in, (const bf16_t*)W, out, B, N, K, ldo, gemv_epi, act, x.st);
     return POP_OK;
@@ -413,6 +417,8 @@ pop_status few_rows_projection(const LayerCtx& x, const bf16_t* in, const void* 
                : gemv_epi == pop::GEMV_ADD_F32 ? pop::EPI_ADD_F32 : pop::EPI_GLU_BF16;
   g.splitk_ws = x.w->splitk_bytes ? at<float>(x.ws, x.w->o_splitk) : nullptr;
   g.splitk_ws_bytes = x.w->splitk_bytes;
+  g.partials_only = parts_out != nullptr;
+  g.split_used = parts_out;
   hipError_t e = pop::launch_gemm(g, x.st);
   if (e != hipSuccess) return fail(POP_EHIP, "projection launch failed: %s", hipGetErrorString(e));
   return POP_OK;
@@ -421,16 +427,18 @@ pop_status few_rows_projection(const LayerCtx& x, const bf16_t* in, const void* 
 // The same for fp32 rows that are RMS-normalised first (Sec. 2.1): with a few rows the GEMV kernel normalises
 // them itself; otherwise the norm kernel writes bf16 rows to `normed` and the projection reads those.
 pop_status normed_few_rows_projection(const LayerCtx& x, float* rows, const float* gamma, bf16_t* normed, const void* W,
-                                      void* out, int B, int N, int K, int ldo, int gemv_epi, int act) {
+                                      void* out, int B, int N, int K, int ldo, int gemv_epi, int act,
+                                      int* parts_out = nullptr) {
+  if (parts_out) *parts_out = 1;
   const float eps = x.m->cfg.rms_eps;
   if (x.ab_gamma == gamma && gamma != nullptr)   // the previous projection's second kernel left them in `normed`
-    return few_rows_projection(x, normed, W, out, B, N, K, ldo, gemv_epi, act);
+    return few_rows_projection(x, normed, W, out, B, N, K, ldo, gemv_epi, act, parts_out);
   if (B < rows_for_gemm() && pop::gemv_norm_supported(B, K)) {
     pop::launch_gemv_norm(rows, gamma, eps, (const bf16_t*)W, out, B, N, K, ldo, gemv_epi, act, x.st);
     return POP_OK;
   }
   pop::launch_rmsnorm(rows, nullptr, nullptr, gamma, normed, nullptr, B, K, eps, x.st);
-  return few_rows_projection(x, normed, W, out, B, N, K, ldo, gemv_epi, act);
+  return few_rows_projection(x, normed, W, out, B, N, K, ldo, gemv_epi, act, parts_out);
 }
 
 // xb += in W^T for the B rows of a decode-style layer.  With next_gamma the caller announces the norm scale of the
@@ -479,13 +487,15 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   bf16_t* attnb = at<bf16_t>(x.ws, x.w->o_attnb);
   bf16_t* ub = at<bf16_t>(x.ws, x.w->o_ub);
   const bool glob = layer_is_global(c, l);
+  // (if the projection split its K range, the RoPE kernel adds the partial products itself)
+  int qkv_parts = 1;
   if (pop_status s = normed_few_rows_projection(x, xb, (const float*)lw.norm_in, ab, lw.wqkv, qkvb, B, Dqkv, d, Dqkv,
-                                                pop::GEMV_STORE_F32, 0))
+                                                pop::GEMV_STORE_F32, 0, &qkv_parts))
     return s;
-  pop::launch_rope_append(qkvb, Dqkv, qb, c.n_q_heads, c.n_kv_heads, c.head_dim, pos, slot,
+  pop::launch_rope_append(qkv_parts > 1 ? at<float>(x.ws, x.w->o_splitk) : qkvb, Dqkv, qb, c.n_q_heads, c.n_kv_heads, c.head_dim, pos, slot,
                           glob ? (double)c.rope_theta : (double)c.rope_theta_local, x.c->k_pool(l - 1),
                           x.c->v_pool(l - 1), c.page_size, B, x.st, (const float*)lw.q_norm, (const float*)lw.k_norm,
-                          c.rms_eps);
+                          c.rms_eps, qkv_parts, (size_t)B * Dqkv);
   pop::AttnDecodeArgs ad{};
   ad.q = qb;
   ad.k_pool = x.c->k_pool(l - 1);

@@ -267,7 +267,8 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float* __restric
                                                           double neg2_over_hd_log2theta, bf16_t* __restrict__ k_pool,
                                                           bf16_t* __restrict__ v_pool, int P,
                                                           const float* __restrict__ q_gamma,
-                                                          const float* __restrict__ k_gamma, float qk_eps) {
+                                                          const float* __restrict__ k_gamma, float qk_eps,
+                                                          int n_parts, size_t part_stride) {
   __shared__ float red[2];
   const int b = blockIdx.x, head = blockIdx.y;
   const int half = hd >> 1;
@@ -277,6 +278,11 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float* __restric
   // per-head QK-norm (uniform over the block): RMS over the head's hd values, before the rotation
   const float* gamma = head < n_q_heads ? q_gamma : (head < n_q_heads + n_kv_heads ? k_gamma : nullptr);
   float x = i < half ? row[i] : 0.f, y = i < half ? row[i + half] : 0.f;
+  for (int p = 1; p < n_parts; ++p)
+    if (i < half) {
+      x += row[p * part_stride + i];
+      y += row[p * part_stride + i + half];
+    }
   if (gamma) {
     const float ss = wave_sum(x * x + y * y);
     if ((i & 63) == 0) red[i >> 6] = ss;
@@ -307,8 +313,8 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float* __restric
   } else {
     const int hh = head - n_q_heads - n_kv_heads;
     bf16_t* o = v_pool + (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
-    o[i] = f32_to_bf16(row[i]);
-    o[i + half] = f32_to_bf16(row[i + half]);
+    o[i] = f32_to_bf16(x);
+    o[i + half] = f32_to_bf16(y);
   }
 }
 }  // namespace decode_impl
@@ -317,11 +323,11 @@ using namespace decode_impl;
 void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
                         const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool, bf16_t* v_pool,
                         int page_size, int B, hipStream_t st, const float* q_gamma, const float* k_gamma,
-                        float qk_eps) {
+                        float qk_eps, int n_parts, size_t part_stride) {
   if (B <= 0) return;
   hipLaunchKernelGGL(rope_append_kernel, dim3(B, n_q_heads + 2 * n_kv_heads), dim3(128), 0, st, qkv, ld, q_out,
                      n_q_heads, n_kv_heads, hd, pos, slot, -2.0 / (double)hd * log2(theta), k_pool, v_pool,
-                     page_size, q_gamma, k_gamma, qk_eps);
+                     page_size, q_gamma, k_gamma, qk_eps, n_parts, part_stride);
 }
 
 // ------------------------------------------------------------------------------------- decode attention

@@ -146,7 +146,9 @@ void launch_gemv_norm(const float* xf, const float* gamma, float eps, const bf16
 void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
                         const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool,
                         bf16_t* v_pool, int page_size, int B, hipStream_t st, const float* q_gamma = nullptr,
-                        const float* k_gamma = nullptr, float qk_eps = 0.f);
+                        const float* k_gamma = nullptr, float qk_eps = 0.f, int n_parts = 1, size_t part_stride = 0);
+// (n_parts > 1: qkv is given as that many fp32 partial products, part_stride elements apart, which are added in
+// index order first: the second kernel of a QKV projection whose K range was split)
 
 // Keys per split of the decode attention: small enough that a 2K-token context already gives every
 // CU a work-group (len / 64 splits x KV heads x sequences).
