@@ -128,6 +128,13 @@ struct pop_cache {
   // KV projections in the prefill, in which case nothing exists below the first full-depth token.
   std::vector<int32_t> kv_first;     // [n_layers][max_seqs]
   bool any_kv_first = false;
+  // Two pinned host buffers that the calls' metadata is copied to the device from, in turn (allocated at the
+  // first call that needs them).  A copy from pageable memory may still be reading its source after
+  // hipMemcpyAsync returns; these buffers outlive the call, and an event per buffer says when it is free again.
+  void* stage_host[2] = {nullptr, nullptr};
+  size_t stage_bytes[2] = {0, 0};
+  hipEvent_t stage_done[2] = {nullptr, nullptr};
+  unsigned stage_turn = 0;
   size_t layer_stride() const {      // elements between the K pools of consecutive layers
     return 2 * pool_stride();
   }
@@ -226,6 +233,36 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_splitk = take(w.splitk_bytes);
   w.total = o;
   return w;
+}
+
+// Copies `bytes` of host metadata to the device on the stream, through one of the cache's pinned buffers.
+pop_status upload_meta(pop_cache* c, void* dev_dst, const void* src, size_t bytes, hipStream_t st) {
+  if (bytes == 0) return POP_OK;
+  const unsigned k = c->stage_turn++ & 1;
+  if (c->stage_done[k]) POP_HIP(hipEventSynchronize(c->stage_done[k]));   // the buffer's previous copy has been read
+  if (c->stage_bytes[k] < bytes) {
+    if (c->stage_host[k]) (void)hipHostFree(c->stage_host[k]);
+    c->stage_host[k] = nullptr;
+    c->stage_bytes[k] = 0;
+    const size_t want = round_up(bytes, (size_t)1 << 16);
+    if (hipHostMalloc(&c->stage_host[k], want, hipHostMallocDefault) == hipSuccess) c->stage_bytes[k] = want;
+    else { c->stage_host[k] = nullptr; (void)hipGetLastError(); }
+  }
+  if (c->stage_host[k] && !c->stage_done[k] &&
+      hipEventCreateWithFlags(&c->stage_done[k], hipEventDisableTiming) != hipSuccess) {
+    c->stage_done[k] = nullptr;
+    (void)hipGetLastError();
+  }
+  if (!c->stage_host[k] || !c->stage_done[k]) {
+    // no pinned memory to be had: copy from the caller's buffer and wait until it has been read
+    POP_HIP(hipMemcpyAsync(dev_dst, src, bytes, hipMemcpyHostToDevice, st));
+    POP_HIP(hipStreamSynchronize(st));
+    return POP_OK;
+  }
+  std::memcpy(c->stage_host[k], src, bytes);
+  POP_HIP(hipMemcpyAsync(dev_dst, c->stage_host[k], bytes, hipMemcpyHostToDevice, st));
+  POP_HIP(hipEventRecord(c->stage_done[k], st));
+  return POP_OK;
 }
 
 template <typename T>
@@ -675,7 +712,7 @@ pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, co
     std::copy(tr.pos.begin(), tr.pos.end(), mi(w.o_tr_pos));
     std::copy(tr.slot.begin(), tr.slot.end(), mi(w.o_tr_slot));
   }
-  POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
+  if (pop_status us = upload_meta(c, ws, meta.data(), w.meta_bytes, st)) return us;
   c->n_seqs = B;
   std::fill(c->seq_lens.begin(), c->seq_lens.end(), 0);
   std::fill(c->block_table.begin(), c->block_table.end(), -1);
@@ -775,7 +812,7 @@ pop_status decode_step_f32(pop_model* m, pop_cache* c, const int32_t* host_token
   if (max_len > pop::f32::kMaxContext)
     return fail(POP_EUNSUPPORTED, "the fp32 path holds one row of scores in LDS: sequences up to %d tokens",
                 pop::f32::kMaxContext);
-  POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
+  if (pop_status us = upload_meta(c, ws, meta.data(), w.meta_bytes, st)) return us;
   for (int b = 0; b < B; ++b) c->seq_lens[b] += 1;
   CtxF32 x{m, c, ws, &w, st};
   x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;
@@ -914,7 +951,14 @@ pop_status pop_cache_create(const pop_config* cfg, void* dev_pool, size_t bytes,
   return POP_OK;
 }
 
-void pop_cache_destroy(pop_cache* c) { delete c; }
+void pop_cache_destroy(pop_cache* c) {
+  if (!c) return;
+  for (int k = 0; k < 2; ++k) {
+    if (c->stage_done[k]) { (void)hipEventSynchronize(c->stage_done[k]); (void)hipEventDestroy(c->stage_done[k]); }
+    if (c->stage_host[k]) (void)hipHostFree(c->stage_host[k]);
+  }
+  delete c;
+}
 
 int32_t pop_cache_n_seqs(const pop_cache* c) { return c ? c->n_seqs : 0; }
 
@@ -1047,7 +1091,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   // ------------------------------------------------------------------ launches
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   void* ws = dev_workspace;
-  POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
+  if (pop_status us = upload_meta(c, ws, meta.data(), w.meta_bytes, st)) return us;
   // sequences start from empty; record the new state now that nothing can fail on arguments
   c->n_seqs = B;
   std::fill(c->seq_lens.begin(), c->seq_lens.end(), 0);
@@ -1326,7 +1370,7 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
   }
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   void* ws = dev_workspace;
-  POP_HIP(hipMemcpyAsync(ws, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
+  if (pop_status us = upload_meta(c, ws, meta.data(), w.meta_bytes, st)) return us;
   for (int b = 0; b < B; ++b) c->seq_lens[b] += 1;
   LayerCtx x{m, c, ws, &w, st};
   x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;
@@ -1392,7 +1436,7 @@ pop_status pop_generate(pop_model* m, pop_cache* c, const pop_prefill_args* a, i
     }
   }
   char* gbase = reinterpret_cast<char*>(dev_workspace) + base;
-  POP_HIP(hipMemcpyAsync(gbase, gmeta.data(), gmeta.size() * 4, hipMemcpyHostToDevice, st));
+  if (pop_status us = upload_meta(c, gbase, gmeta.data(), gmeta.size() * 4, st)) return us;
   const int32_t* d_gpos = reinterpret_cast<const int32_t*>(gbase);
   const int32_t* d_gslot = d_gpos + (size_t)B * n_new;
   int32_t* d_tok = reinterpret_cast<int32_t*>(gbase) + 2 * (size_t)B * n_new;
@@ -1570,6 +1614,7 @@ pop_status pop_op_rope_attention(void* qkv, const int32_t* cu, int32_t B, int32_
   nta = build_attention_work(cu, B, mi(w.o_ta_seq), mi(w.o_ta_start), mi(w.o_ta_start2));
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   POP_HIP(hipMemcpyAsync(workspace, meta.data(), w.meta_bytes, hipMemcpyHostToDevice, st));
+  POP_HIP(hipStreamSynchronize(st));   // `meta` is pageable memory of this call: wait until it has been read
   const int Dq = Hq * hd, Dkv = Hkv * hd, ld = Dq + 2 * Dkv;
   float2* cs = at<float2>(workspace, w.o_cs);
   bf16_t* vT = at<bf16_t>(workspace, w.o_vT);
