@@ -17,8 +17,10 @@
  *
  * Conventions
  *   Memory     Every DEVICE pointer is caller-owned device memory (weights, cache pool, workspace,
- *              logits).  The library allocates small host structs only, released by the matching
- *              pop_free_model / pop_cache_destroy.  HOST pointers are read during the call only.
+ *              logits).  The library allocates no device memory: only small host structs and, per
+ *              cache, two pinned host buffers of the size of a call's int32 metadata (the calls copy
+ *              that to the device from there), released by the matching pop_free_model /
+ *              pop_cache_destroy.  HOST pointers are read during the call only.
  *   Layout     All matrices are row-major [out_features, in_features] (the contraction index is
  *              contiguous), elements bf16.  Norm scales are fp32 [d_model].
  *   Precision  POP_DTYPE_BF16 is the production path (bf16 weights and cache, fp32 accumulation
