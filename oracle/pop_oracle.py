@@ -162,10 +162,13 @@ def project_kv(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray):
 
 
 def kept_layer_rows(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray,
-                    K_past: np.ndarray, V_past: np.ndarray, past_pos: Optional[np.ndarray] = None):
+                    K_past: np.ndarray, V_past: np.ndarray, past_pos: Optional[np.ndarray] = None,
+                    gate: float = 1.0):
     """One full layer (Sec. 2.1) for rows x [n, d] at positions pos, given the cache entries of
     earlier positions K_past, V_past [m, Hkv, hd] (positions past_pos; 0..m-1 with m == pos[0] if
     not given).  The rows' own K/V are appended first, attention then runs on the updated cache.
+    `gate` is the layer's virtual gate g_l (Sec. 3.1): both residual branches, the attention output and
+    the FFN output, are multiplied by it; the layer's K/V do not depend on it.
     Returns (x_next [n, d], K_current, V_current)."""
     dt = x.dtype
     hq, hd = cfg["n_q_heads"], cfg["head_dim"]
@@ -180,11 +183,11 @@ def kept_layer_rows(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray,
     V_cur = np.concatenate([V_past, v_new], axis=0)
     cur_pos = None if past_pos is None else np.concatenate([np.asarray(past_pos, dtype=np.int64), pos])
     o = attention_rows(q, pos, K_cur, V_cur, window, cur_pos)
-    y = x + o @ _w(lw, "wo", dt).T
+    y = x + (o @ _w(lw, "wo", dt).T) * gate
     m = rmsnorm(y, _w(lw, "norm_post", dt), cfg["rms_eps"])
     ffn = (glu_act(m @ _w(lw, "w_gate", dt).T, cfg["act"]) * (m @ _w(lw, "w_up", dt).T)) \
         @ _w(lw, "w_down", dt).T
-    return y + ffn, K_cur, V_cur
+    return y + ffn * gate, K_cur, V_cur
 
 
 def kv_only_rows(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray):
@@ -218,9 +221,10 @@ def lm_head_logits(cfg: Dict, W: Dict, x: np.ndarray) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------- the operators
-def body_prefill(cfg: Dict, W: Dict, h: np.ndarray, l_keep: int):
+def body_prefill(cfg: Dict, W: Dict, h: np.ndarray, l_keep: int, gates: Optional[Sequence[float]] = None):
     """Pruned prefill of body rows h [n, d] (positions 0..n-1): layers 1..L_keep in full, layers
-    L_keep+1..L as KV-only projections of the last kept layer's output.
+    L_keep+1..L as KV-only projections of the last kept layer's output.  `gates` (per layer, default
+    all 1) are the prefill-stage virtual gates of Sec. 3.1 / 3.2 for the layers that run in full.
     Returns (Kc, Vc) lists over layers of [n, Hkv, hd], and the final body hidden state."""
     L, hkv, hd = cfg["n_layers"], cfg["n_kv_heads"], cfg["head_dim"]
     n = h.shape[0]
@@ -230,7 +234,8 @@ def body_prefill(cfg: Dict, W: Dict, h: np.ndarray, l_keep: int):
     x = h
     for l in range(1, L + 1):
         if l <= l_keep:
-            x, K, V = kept_layer_rows(cfg, W["layers"][l - 1], l, x, pos, empty, empty)
+            x, K, V = kept_layer_rows(cfg, W["layers"][l - 1], l, x, pos, empty, empty,
+                                      gate=1.0 if gates is None else float(gates[l - 1]))
         else:
             x, K, V = kv_only_rows(cfg, W["layers"][l - 1], l, x, pos)
         Kc.append(K)
@@ -238,16 +243,18 @@ def body_prefill(cfg: Dict, W: Dict, h: np.ndarray, l_keep: int):
     return Kc, Vc, x
 
 
-def decode_step(cfg: Dict, W: Dict, h_tok: np.ndarray, Kc: List[np.ndarray], Vc: List[np.ndarray]):
+def decode_step(cfg: Dict, W: Dict, h_tok: np.ndarray, Kc: List[np.ndarray], Vc: List[np.ndarray],
+                gates: Optional[Sequence[float]] = None):
     """One token (hidden row h_tok [d]) through the full model against the cache (Sec. 3.2, the
     decode operator).  Its position is the current cache length.  Appends to every layer's cache
-    and returns (logits [V], Kc, Vc)."""
+    and returns (logits [V], Kc, Vc).  `gates`: the decode-stage virtual gates (default all 1)."""
     L = cfg["n_layers"]
     x = h_tok[None, :]
     Kn, Vn = [], []
     for l in range(1, L + 1):
         pos = np.array([Kc[l - 1].shape[0]])
-        x, K, V = kept_layer_rows(cfg, W["layers"][l - 1], l, x, pos, Kc[l - 1], Vc[l - 1])
+        x, K, V = kept_layer_rows(cfg, W["layers"][l - 1], l, x, pos, Kc[l - 1], Vc[l - 1],
+                                  gate=1.0 if gates is None else float(gates[l - 1]))
         Kn.append(K)
         Vn.append(V)
     return lm_head_logits(cfg, W, x)[0], Kn, Vn
@@ -255,17 +262,21 @@ def decode_step(cfg: Dict, W: Dict, h_tok: np.ndarray, Kc: List[np.ndarray], Vc:
 
 def pop_prefill(cfg: Dict, W: Dict, tokens: np.ndarray, l_keep: int, dtype=np.float64,
                 embeds: Optional[np.ndarray] = None,
-                embed_ranges: Sequence[Tuple[int, int]] = ()):
+                embed_ranges: Sequence[Tuple[int, int]] = (),
+                gates_prefill: Optional[Sequence[float]] = None,
+                gates_decode: Optional[Sequence[float]] = None):
     """POP for one prompt x_{1:N} (Sec. 3.3): pruned prefill over x_{1:N-1}, then x_N as the first
-    decode step with the full model.  Returns (Kc, Vc, logits): per layer [N, Hkv, hd] and [V]."""
+    decode step with the full model.  Returns (Kc, Vc, logits): per layer [N, Hkv, hd] and [V].
+    With gates this is the stage-aware gated model of Sec. 3.2: the prefill operator runs x_{1:N-1} with
+    the gates g^prefill, the decode operator x_N (and later tokens) with g^decode."""
     if not 0 <= l_keep <= cfg["n_layers"]:
         raise ValueError("l_keep out of range")
     n = len(tokens)
     if n < 1:
         raise ValueError("empty prompt")
     h = embed_rows(W, tokens, dtype, embeds, embed_ranges)
-    Kc, Vc, _ = body_prefill(cfg, W, h[:n - 1], l_keep)
-    logits, Kc, Vc = decode_step(cfg, W, h[n - 1], Kc, Vc)
+    Kc, Vc, _ = body_prefill(cfg, W, h[:n - 1], l_keep, gates_prefill)
+    logits, Kc, Vc = decode_step(cfg, W, h[n - 1], Kc, Vc, gates_decode)
     return Kc, Vc, logits
 
 

@@ -12,7 +12,7 @@ from functools import lru_cache
 
 
 def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_projection=True, boundary=True,
-                    window_kv_writes=False):
+                    window_kv_writes=False, gates_prefill=None, gates_decode=None):
     """Returns (K, V, logits) with K[l][t][head][i] python floats (l 0-based layer index).
     `tokens` may extend beyond the prompt (first n_prompt entries): later tokens are decode steps and,
     like the last prompt token, run every layer in full (Sec. 3.2: decoding keeps the full model).
@@ -21,7 +21,10 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_project
     kv_projection=False: a pruned layer keeps no entry for a pruned token (K[l][t] is None and the
     entry is absent from attention); boundary=False: the last prompt token is pruned like the
     others (the two ablations of Sec. 4.4).  window_kv_writes: a pruned sliding-window layer keeps the
-    entry of a pruned token only if the first unpruned token is within the window of it."""
+    entry of a pruned token only if the first unpruned token is within the window of it.
+    gates_prefill / gates_decode (per layer): the virtual gates of Sec. 3.1 in their stage-aware form
+    (Sec. 3.2): a token of the prompt body multiplies both residual branches of layer l by
+    gates_prefill[l-1], the last prompt token and later tokens by gates_decode[l-1]."""
     L, d = cfg["n_layers"], cfg["d_model"]
     Hq, Hkv, hd, f = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"]
     eps = cfg["rms_eps"]
@@ -123,11 +126,13 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_project
             z = sum(ex)
             for c in range(hd):
                 o.append(sum(e / z * val(l, j)[g][c] for e, j in zip(ex, js)))
-        y = [xi + oi for xi, oi in zip(x, matvec(p["wo"], o))]
+        stage = gates_prefill if t < n_prompt - 1 else gates_decode
+        vg = 1.0 if stage is None else stage[l - 1]           # the virtual gate of this layer for this token
+        y = [xi + vg * oi for xi, oi in zip(x, matvec(p["wo"], o))]
         m = norm(y, p["norm_post"])
         gate, up = matvec(p["w_gate"], m), matvec(p["w_up"], m)
         u = [act(g_) * u_ for g_, u_ in zip(gate, up)]
-        return tuple(yi + di for yi, di in zip(y, matvec(p["w_down"], u)))
+        return tuple(yi + vg * di for yi, di in zip(y, matvec(p["w_down"], u)))
 
     K = [[[list(h) for h in key(l, t)] if has_entry(l, t) else None for t in range(N)] for l in range(1, L + 1)]
     V = [[[list(h) for h in val(l, t)] if has_entry(l, t) else None for t in range(N)] for l in range(1, L + 1)]

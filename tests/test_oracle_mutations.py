@@ -162,3 +162,49 @@ def test_planted_window_write_mistake_is_caught(monkeypatch):
     monkeypatch.setattr(O, "skip_set_body",
                         lambda c, W, h, skip, kv=True, fr=None: real_body(c, W, h, skip, kv, None if fr is None else fr + 1))
     assert not holds()
+
+
+# ------------------------------------------------------------------ virtual gates
+def gate_pin_holds():
+    cfg = micro_cfg(n_layers=3)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 7, seed=5)
+    gp, gd = [0.3, 1.0, 1.7], [1.2, 0.0, 0.6]
+    Kb, Vb, lb = brute_force_pop(cfg, w, tokens.tolist(), 3, gates_prefill=gp, gates_decode=gd)
+    Kc, Vc, logits = O.pop_prefill(cfg, w, tokens, 3, gates_prefill=gp, gates_decode=gd)
+    return (np.allclose(np.stack(Kc), np.array(Kb), rtol=1e-9, atol=1e-11)
+            and np.allclose(np.stack(Vc), np.array(Vb), rtol=1e-9, atol=1e-11)
+            and np.allclose(logits, np.array(lb), rtol=1e-9, atol=1e-11))
+
+
+def test_planted_gate_mistakes_are_caught(monkeypatch):
+    assert gate_pin_holds()
+    real = O.kept_layer_rows
+
+    def gate_on_attention_only(cfg, lw, l, x, pos, K_past, V_past, past_pos=None, gate=1.0):
+        # y = x + gate * attention as it should be, but the FFN branch is added without its gate
+        no_ffn = dict(lw)
+        no_ffn["w_down"] = lw["w_down"] * 0
+        y, K, V = real(cfg, no_ffn, l, x, pos, K_past, V_past, past_pos, gate)
+        dt = x.dtype
+        m = O.rmsnorm(y, O._w(lw, "norm_post", dt), cfg["rms_eps"])
+        ffn = (O.glu_act(m @ O._w(lw, "w_gate", dt).T, cfg["act"]) * (m @ O._w(lw, "w_up", dt).T)) \
+            @ O._w(lw, "w_down", dt).T
+        return y + ffn, K, V
+
+    def gate_scales_the_stream(cfg, lw, l, x, pos, K_past, V_past, past_pos=None, gate=1.0):
+        out, K, V = real(cfg, lw, l, x, pos, K_past, V_past, past_pos, 1.0)
+        return out * gate, K, V
+
+    def stages_swapped(cfg, W, tokens, l_keep, **kw):
+        kw["gates_prefill"], kw["gates_decode"] = kw.get("gates_decode"), kw.get("gates_prefill")
+        return real_pop(cfg, W, tokens, l_keep, **kw)
+
+    for wrong in (gate_on_attention_only, gate_scales_the_stream):
+        with monkeypatch.context() as mp:
+            mp.setattr(O, "kept_layer_rows", wrong)
+            assert not gate_pin_holds(), wrong.__name__
+    real_pop = O.pop_prefill
+    with monkeypatch.context() as mp:
+        mp.setattr(O, "pop_prefill", stages_swapped)
+        assert not gate_pin_holds()

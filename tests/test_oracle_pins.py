@@ -633,3 +633,60 @@ def test_qk_norm_invariances():
     for lw in w3["layers"]:
         del lw["q_norm"], lw["k_norm"]
     assert np.max(np.abs(O.pop_prefill(cfg, w2, tokens, 2)[2] - O.pop_prefill(cfg, w3, tokens, 2)[2])) > 1e-3
+
+
+# ------------------------------------------------------------------ virtual gates (Sec. 3.1, stage-aware: Sec. 3.2)
+@pytest.mark.parametrize("variant", ["silu_global", "gelu_window"])
+def test_stage_aware_gates_match_brute_force(variant):
+    """Every body token scales both residual branches of layer l by g^prefill_l, the last prompt token by
+    g^decode_l: against the scalar brute force, with and without pruned layers."""
+    cfg = micro_cfg(n_layers=3)
+    if variant == "gelu_window":
+        cfg.update(act=synth.ACT_GELU_TANH, sliding_window=3, global_every=2, rope_theta_local=50.0)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 7, seed=5)
+    gp, gd = [0.3, 1.0, 1.7], [1.2, 0.0, 0.6]
+    for l_keep in (3, 2):
+        Kb, Vb, lb = brute_force_pop(cfg, w, tokens.tolist(), l_keep, gates_prefill=gp, gates_decode=gd)
+        Kc, Vc, logits = O.pop_prefill(cfg, w, tokens, l_keep, gates_prefill=gp, gates_decode=gd)
+        np.testing.assert_allclose(stack(Kc), np.array(Kb), rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(stack(Vc), np.array(Vb), rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(logits, np.array(lb), rtol=1e-10, atol=1e-12)
+
+
+def test_gates_of_one_change_nothing_and_zero_prefill_gates_are_pop():
+    """Sec. 3.1: g = 1 is the original model; g = 0 makes x_{l+1} = x_l while the layer still writes the K/V
+    of its input.  Hence the full-depth prefill with prefill gates 0 on the deep layers leaves exactly the
+    cache and logits of POP with those layers pruned (decode gates stay 1: boundary handling)."""
+    cfg = small_cfg(n_layers=5)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 11, seed=12)
+    L, l_keep = 5, 3
+    K1, V1, l1 = O.pop_prefill(cfg, w, tokens, l_keep)
+    K2, V2, l2 = O.pop_prefill(cfg, w, tokens, l_keep, gates_prefill=[1.0] * L, gates_decode=[1.0] * L)
+    assert all(np.array_equal(a, b) for a, b in zip(K1 + V1, K2 + V2)) and np.array_equal(l1, l2)
+    K3, V3, l3 = O.pop_prefill(cfg, w, tokens, L, gates_prefill=[1.0] * l_keep + [0.0] * (L - l_keep))
+    np.testing.assert_allclose(stack(K3), stack(K1), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(stack(V3), stack(V1), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(l3, l1, rtol=1e-12, atol=1e-14)
+
+
+def test_all_gates_zero_is_lm_head_of_the_embedding_and_gates_are_stage_specific():
+    cfg = small_cfg()
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 9, seed=13)
+    L = cfg["n_layers"]
+    _, _, logits = O.pop_prefill(cfg, w, tokens, L, gates_prefill=[0.0] * L, gates_decode=[0.0] * L)
+    e = w["embed"][int(tokens[-1])].double().numpy()
+    ref = O.rmsnorm(e[None], w["final_norm"].double().numpy(), cfg["rms_eps"]) @ w["lm_head"].double().numpy().T
+    np.testing.assert_allclose(logits, ref[0], rtol=1e-12, atol=1e-14)
+    # a prefill gate moves the body's cache entries of later layers, not the entries of the gated layer itself;
+    # a decode gate moves nothing in the body's entries
+    K0, V0, _ = O.pop_prefill(cfg, w, tokens, L)
+    Kp, Vp, _ = O.pop_prefill(cfg, w, tokens, L, gates_prefill=[1.0, 0.5, 1.0, 1.0])
+    Kd, Vd, _ = O.pop_prefill(cfg, w, tokens, L, gates_decode=[1.0, 0.5, 1.0, 1.0])
+    n = len(tokens)
+    assert np.array_equal(Kp[1][:n - 1], K0[1][:n - 1]) and not np.allclose(Kp[2][:n - 1], K0[2][:n - 1])
+    assert np.array_equal(Kp[1][n - 1], K0[1][n - 1])          # the boundary token is a decode-stage token
+    assert all(np.array_equal(a[:n - 1], b[:n - 1]) for a, b in zip(Kd + Vd, K0 + V0))
+    assert not np.allclose(Kd[2][n - 1], K0[2][n - 1])
