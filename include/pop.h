@@ -186,6 +186,15 @@ typedef struct {
                                   tokens see even less of the body, so no result changes and the
                                   K/V-only projection of such a layer shrinks to at most W rows per
                                   sequence.  The other slots keep what they held.  0: all entries.   */
+  const float* gates;          /* HOST [n_layers] or NULL.  Prefill-stage virtual gates (Sec. 3.1 in the
+                                  stage-aware form of Sec. 3.2; the paper's tool for measuring layer
+                                  importance, not part of serving): a layer that runs in full multiplies
+                                  both of its residual branches, the attention output and the FFN
+                                  output, by gates[l-1]; its K/V entries do not depend on its own gate.
+                                  NULL: all 1.  Only with POP_MODE_BODY_ONLY or POP_MODE_NO_BOUNDARY,
+                                  where every given token is a prefill-stage token; the decode-stage
+                                  gates of the last prompt token and of later tokens go to
+                                  pop_decode_step_gated.                                              */
 } pop_prefill_args;
 enum { POP_MODE_POP = 0, POP_MODE_BODY_ONLY = 1, POP_MODE_NO_BOUNDARY = 2 };
 
@@ -199,7 +208,8 @@ enum { POP_MODE_POP = 0, POP_MODE_BODY_ONLY = 1, POP_MODE_NO_BOUNDARY = 2 };
  * pop_generate honour it until the next pop_prefill.
  *   dev_workspace DEVICE scratch of at least pop_workspace_bytes(cfg, T, n_seqs, max_pages_per_seq).
  * Errors (all before any launch): POP_EINVAL (NULL, l_keep outside [0, L], skip_layers not strictly
- * increasing or outside [1, L], n_skip without skip_layers, unknown mode or switch value, n_seqs < 1
+ * increasing or outside [1, L], n_skip without skip_layers, unknown mode or switch value, gates in
+ * POP_MODE_POP or a gate that is not finite, n_seqs < 1
  * or above the cache's max_seqs, an empty sequence, token id outside [0, vocab), bad embed range),
  * POP_ENOSPACE
  * (pages, workspace), POP_EALIGN.  POP_EHIP if a launch fails.
@@ -217,6 +227,12 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* args,
 pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_tokens, int32_t n_seqs,
                            float* dev_logits, void* dev_workspace, size_t workspace_bytes,
                            pop_stream stream);
+/* The same step with decode-stage virtual gates (Sec. 3.1 / 3.2, see pop_prefill_args.gates): layer l
+ * multiplies both of its residual branches by host_gates[l-1] (HOST [n_layers]; NULL = all 1, which is
+ * pop_decode_step).  POP_EINVAL also if a gate is not finite. */
+pop_status pop_decode_step_gated(pop_model* m, pop_cache* c, const int32_t* host_tokens, int32_t n_seqs,
+                                 const float* host_gates, float* dev_logits, void* dev_workspace,
+                                 size_t workspace_bytes, pop_stream stream);
 
 /*
  * Greedy generation (Sec. 3.2: prefill, then the decode loop with the full model): pop_prefill in

@@ -335,6 +335,8 @@ struct LayerCtx {
   // The norm scale with which the bf16 scratch rows `ab` hold RMSNorm(xb), or nullptr when they do not: a split
   // projection with a residual epilogue normalises its result for the next projection in its second kernel.
   mutable const float* ab_gamma = nullptr;
+  const float* gates = nullptr;       // HOST [n_layers] virtual gates of the stage this context runs, or nullptr
+  float gate(int l /*1-based*/) const { return gates ? gates[l - 1] : 1.f; }
 };
 
 // The prefill's pruning, resolved from the arguments (Sec. 2.2: a skip set; Sec. 3.3: applied to the
@@ -387,6 +389,13 @@ pop_status make_plan(const pop_config& cfg, const pop_prefill_args* a, PrunePlan
   plan->pruned.assign((size_t)L + 2, 0);
   if (a->window_kv_writes != 0 && a->window_kv_writes != 1)
     return fail(POP_EINVAL, "window_kv_writes must be 0 or 1, got %d", a->window_kv_writes);
+  if (a->gates) {
+    if (a->mode == POP_MODE_POP)
+      return fail(POP_EINVAL, "gates are prefill-stage gates: use POP_MODE_BODY_ONLY (and pop_decode_step_gated for "
+                              "the last token) or POP_MODE_NO_BOUNDARY");
+    for (int l = 0; l < L; ++l)
+      if (!std::isfinite(a->gates[l])) return fail(POP_EINVAL, "gates[%d] is not finite", l);
+  }
   plan->kv_projection = a->no_kv_projection == 0;
   plan->window_writes = a->window_kv_writes == 1 && cfg.sliding_window > 0 && cfg.global_every > 0;
   plan->n_pruned = 0;
@@ -482,11 +491,11 @@ pop_status normed_few_rows_projection(const LayerCtx& x, float* rows, const floa
 // projection that follows: when this one runs as a split GEMM its second kernel then also writes
 // RMSNorm(xb; next_gamma) to ab (and records that in x.ab_gamma), which saves that projection's norm launch.
 pop_status residual_few_rows_projection(const LayerCtx& x, const bf16_t* in, const void* W, int B, int N, int K,
-                                        const float* next_gamma) {
+                                        const float* next_gamma, float scale /* the layer's virtual gate */) {
   float* xb = at<float>(x.ws, x.w->o_xb);
   x.ab_gamma = nullptr;
   if (B < rows_for_gemm() || N % 4) {
-    pop::launch_gemv(in, (const bf16_t*)W, xb, B, N, K, N, pop::GEMV_ADD_F32, 0, x.st);
+    pop::launch_gemv(in, (const bf16_t*)W, xb, B, N, K, N, pop::GEMV_ADD_F32, 0, x.st, scale);
     return POP_OK;
   }
   pop::GemmArgs g{};
@@ -494,6 +503,8 @@ pop_status residual_few_rows_projection(const LayerCtx& x, const bf16_t* in, con
   g.A = in; g.lda = K; g.W = (const bf16_t*)W; g.ldw = K; g.out = xb; g.ldc = N;
   g.M = B; g.N = N; g.K = K;
   g.epilogue = pop::EPI_ADD_F32;
+  g.scaled = true;
+  g.scale = scale;
   g.splitk_ws = x.w->splitk_bytes ? at<float>(x.ws, x.w->o_splitk) : nullptr;
   g.splitk_ws_bytes = x.w->splitk_bytes;
   int S = 1;
@@ -503,7 +514,7 @@ pop_status residual_few_rows_projection(const LayerCtx& x, const bf16_t* in, con
   if (e != hipSuccess) return fail(POP_EHIP, "projection launch failed: %s", hipGetErrorString(e));
   if (g.partials_only && S > 1) {
     pop::launch_add_parts_rmsnorm(xb, g.splitk_ws, S, (size_t)B * N, next_gamma, at<bf16_t>(x.ws, x.w->o_ab), B, N,
-                                  x.m->cfg.rms_eps, x.st);
+                                  x.m->cfg.rms_eps, x.st, scale);
     x.ab_gamma = next_gamma;
   }
   return POP_OK;
@@ -553,11 +564,11 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   ad.part = at<float>(x.ws, x.w->o_part);
   ad.out = attnb;
   pop::launch_attention_decode(ad, x.st);
-  if (pop_status s = residual_few_rows_projection(x, attnb, lw.wo, B, d, Dq, (const float*)lw.norm_post)) return s;
+  if (pop_status s = residual_few_rows_projection(x, attnb, lw.wo, B, d, Dq, (const float*)lw.norm_post, x.gate(l))) return s;
   if (pop_status s = normed_few_rows_projection(x, xb, (const float*)lw.norm_post, ab, lw.w_gate_up, ub, B, f, d, f,
                                                 pop::GEMV_GLU_BF16, c.act))
     return s;
-  if (pop_status s = residual_few_rows_projection(x, ub, lw.w_down, B, d, f, next_gamma)) return s;
+  if (pop_status s = residual_few_rows_projection(x, ub, lw.w_down, B, d, f, next_gamma, x.gate(l))) return s;
   POP_HIP(hipGetLastError());
   return POP_OK;
 }
@@ -629,6 +640,8 @@ struct CtxF32 {
   hipStream_t st;
   const int32_t* kv_first = nullptr;  // DEVICE [n_layers][B] or nullptr
   int B = 0;                          // sequences (row stride of kv_first)
+  const float* gates = nullptr;       // HOST [n_layers] virtual gates of the stage this context runs, or nullptr
+  float gate(int l /*1-based*/) const { return gates ? gates[l - 1] : 1.f; }
 };
 
 // One layer of Sec. 2.1 for `rows` rows of x (fp32 [rows, d], updated in place); a / qkv / attn / u are
@@ -652,10 +665,10 @@ pop_status layer_f32(const CtxF32& x, int l /*1-based*/, int rows, float* xh, fl
                                      x.kv_first ? x.kv_first + (size_t)(l - 1) * x.B : nullptr, rows, c.n_q_heads,
                                      c.n_kv_heads, hd, max_len, x.st);
   if (e != hipSuccess) return fail(POP_EHIP, "fp32 attention launch failed: %s", hipGetErrorString(e));
-  F::launch_gemm(attn, Dq, (const float*)lw.wo, Dq, xh, d, rows, d, Dq, F::EPI_ADD, 0, x.st);
+  F::launch_gemm(attn, Dq, (const float*)lw.wo, Dq, xh, d, rows, d, Dq, F::EPI_ADD, 0, x.st, x.gate(l));
   F::launch_rmsnorm(xh, (const float*)lw.norm_post, a, nullptr, rows, d, c.rms_eps, x.st);
   F::launch_gemm(a, d, (const float*)lw.w_gate_up, d, u, f, rows, f, d, F::EPI_GLU, c.act, x.st);
-  F::launch_gemm(u, f, (const float*)lw.w_down, f, xh, d, rows, d, f, F::EPI_ADD, 0, x.st);
+  F::launch_gemm(u, f, (const float*)lw.w_down, f, xh, d, rows, d, f, F::EPI_ADD, 0, x.st, x.gate(l));
   POP_HIP(hipGetLastError());
   return POP_OK;
 }
@@ -733,6 +746,7 @@ pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, co
   CtxF32 x{m, c, ws, &w, st};
   x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;
   x.B = B;
+  x.gates = a->gates;
   F::launch_embed((const float*)m->w.embed, at<int32_t>(ws, w.o_tokens),
                   a->n_ranges > 0 ? at<int32_t>(ws, w.o_row_src) : nullptr, (const float*)a->embeds, h, T, d, st);
   // Layers in order.  A kept layer runs over all rows (Sec. 2.1).  A run of pruned layers leaves h alone
@@ -789,8 +803,8 @@ pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, co
   return POP_OK;
 }
 
-pop_status decode_step_f32(pop_model* m, pop_cache* c, const int32_t* host_tokens, int B, float* dev_logits, void* ws,
-                           size_t workspace_bytes, hipStream_t st) {
+pop_status decode_step_f32(pop_model* m, pop_cache* c, const int32_t* host_tokens, int B, const float* host_gates,
+                           float* dev_logits, void* ws, size_t workspace_bytes, hipStream_t st) {
   const pop_config& cfg = m->cfg;
   const int P = cfg.page_size, maxp = c->max_pages;
   const WorkspaceF32 w = carve_f32(cfg, B, B, maxp);
@@ -817,6 +831,7 @@ pop_status decode_step_f32(pop_model* m, pop_cache* c, const int32_t* host_token
   CtxF32 x{m, c, ws, &w, st};
   x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;
   x.B = B;
+  x.gates = host_gates;
   float* xb = at<float>(ws, w.o_xb);
   pop::f32::launch_embed((const float*)m->w.embed, at<int32_t>(ws, w.o_tokens), nullptr, nullptr, xb, B, cfg.d_model, st);
   for (int l = 1; l <= cfg.n_layers; ++l)
@@ -1189,6 +1204,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     }
     g.A = attn; g.lda = Dq; g.W = (const bf16_t*)lw.wo; g.ldw = Dq; g.out = h; g.ldc = d;
     g.M = T; g.N = d; g.K = Dq; g.epilogue = pop::EPI_ADD_F32;
+    g.scaled = a->gates != nullptr; g.scale = a->gates ? a->gates[l - 1] : 1.f;   // virtual gate of the layer
     {
       StepTimer tm(m, st, POP_STEP_O_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "O")) return s;
@@ -1205,6 +1221,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     }
     g.A = u; g.lda = f; g.W = (const bf16_t*)lw.w_down; g.ldw = f; g.out = h; g.ldc = d;
     g.M = T; g.N = d; g.K = f; g.epilogue = pop::EPI_ADD_F32;
+    g.scaled = a->gates != nullptr; g.scale = a->gates ? a->gates[l - 1] : 1.f;
     {
       StepTimer tm(m, st, POP_STEP_DOWN_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "down")) return s;
@@ -1330,8 +1347,17 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
 
 pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_tokens, int32_t n_seqs, float* dev_logits,
                            void* dev_workspace, size_t workspace_bytes, pop_stream stream) {
+  return pop_decode_step_gated(m, c, host_tokens, n_seqs, nullptr, dev_logits, dev_workspace, workspace_bytes, stream);
+}
+
+pop_status pop_decode_step_gated(pop_model* m, pop_cache* c, const int32_t* host_tokens, int32_t n_seqs,
+                                 const float* host_gates, float* dev_logits, void* dev_workspace,
+                                 size_t workspace_bytes, pop_stream stream) {
   if (!m || !c || !host_tokens || !dev_logits) return fail(POP_EINVAL, "model / cache / tokens / logits is NULL");
   const pop_config& cfg = m->cfg;
+  if (host_gates)
+    for (int l = 0; l < cfg.n_layers; ++l)
+      if (!std::isfinite(host_gates[l])) return fail(POP_EINVAL, "gates[%d] is not finite", l);
   if (std::memcmp(&cfg, &c->cfg, sizeof cfg) != 0) return fail(POP_EINVAL, "cache was created for another config");
   if (c->n_seqs < 1) return fail(POP_ESTATE, "no prefilled sequences in this cache");
   if (n_seqs != c->n_seqs) return fail(POP_EINVAL, "n_seqs %d does not match the %d live sequences", n_seqs, c->n_seqs);
@@ -1347,7 +1373,7 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
       return fail(POP_ENOSPACE, "sequence %d has no page for position %d", b, pos);
   }
   if (cfg.dtype == POP_DTYPE_F32)
-    return decode_step_f32(m, c, host_tokens, B, dev_logits, dev_workspace, workspace_bytes,
+    return decode_step_f32(m, c, host_tokens, B, host_gates, dev_logits, dev_workspace, workspace_bytes,
                            reinterpret_cast<hipStream_t>(stream));
   const Workspace w = carve(cfg, B, B, maxp);
   if (workspace_bytes < w.total) return fail(POP_ENOSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
@@ -1374,6 +1400,7 @@ pop_status pop_decode_step(pop_model* m, pop_cache* c, const int32_t* host_token
   for (int b = 0; b < B; ++b) c->seq_lens[b] += 1;
   LayerCtx x{m, c, ws, &w, st};
   x.kv_first = c->any_kv_first ? at<int32_t>(ws, w.o_kv_first) : nullptr;
+  x.gates = host_gates;
   pop::launch_embed((const bf16_t*)m->w.embed, at<int32_t>(ws, w.o_tokens), nullptr, nullptr, at<float>(ws, w.o_xb),
                     B, cfg.d_model, st);
   for (int l = 1; l <= cfg.n_layers; ++l) {

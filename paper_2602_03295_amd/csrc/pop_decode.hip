@@ -35,7 +35,7 @@ template <int M, int EPI, int RW, int U, bool NORM>
 __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x, const float* __restrict__ xf,
                                                    const float* __restrict__ gamma, float eps,
                                                    const bf16_t* __restrict__ W, void* __restrict__ out, int N, int K,
-                                                   long long ldo, int act) {
+                                                   long long ldo, int act, float scale /* ADD: out += scale * C */) {
   constexpr int NR = EPI == GEMV_GLU_BF16 ? 2 * RW : RW;  // weight rows streamed per wave
   typedef __attribute__((__vector_size__(16))) unsigned int u32x4_t;
   extern __shared__ __attribute__((aligned(16))) unsigned char gemv_smem[];   // NORM: bf16 [M][K], then float [M][4]
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x,
         reinterpret_cast<bf16_t*>(out)[(size_t)m * ldo + n] = f32_to_bf16(glu_act_f(acc[r][m], act) * acc[r + RW][m]);
       } else {
         float* o = reinterpret_cast<float*>(out) + (size_t)m * ldo + n;
-        *o = (EPI == GEMV_ADD_F32 ? *o : 0.f) + acc[r][m];
+        *o = EPI == GEMV_ADD_F32 ? *o + acc[r][m] * scale : acc[r][m];
       }
     }
   }
@@ -169,6 +169,7 @@ struct GemvIn {
   const float* xf;
   const float* gamma;
   float eps;
+  float scale;   // GEMV_ADD_F32: out += scale * C
 };
 
 template <int M, int EPI, int RW, int U>
@@ -176,10 +177,10 @@ void launch_gemv_cfg(const GemvIn& in, const bf16_t* W, void* out, int N, int K,
   const int blocks = (N + 4 * RW - 1) / (4 * RW);
   if (in.xf)
     hipLaunchKernelGGL((gemv_kernel<M, EPI, RW, U, true>), dim3(blocks), dim3(256), (size_t)M * K * 2 + 16 * M, st,
-                       in.x, in.xf, in.gamma, in.eps, W, out, N, K, ldo, act);
+                       in.x, in.xf, in.gamma, in.eps, W, out, N, K, ldo, act, in.scale);
   else
     hipLaunchKernelGGL((gemv_kernel<M, EPI, RW, U, false>), dim3(blocks), dim3(256), 0, st, in.x, in.xf, in.gamma,
-                       in.eps, W, out, N, K, ldo, act);
+                       in.eps, W, out, N, K, ldo, act, in.scale);
 }
 
 // Rows per wave and unroll depth: few batch rows leave registers for deep unrolling; a small N gets
@@ -245,8 +246,8 @@ void launch_gemv_in(const GemvIn& in, const bf16_t* W, void* out, int M, int N, 
 using namespace decode_impl;
 
 void launch_gemv(const bf16_t* x, const bf16_t* W, void* out, int M, int N, int K, int64_t ldo, int epilogue,
-                 int act, hipStream_t st) {
-  launch_gemv_in(GemvIn{x, nullptr, nullptr, 0.f}, W, out, M, N, K, ldo, epilogue, act, st);
+                 int act, hipStream_t st, float scale) {
+  launch_gemv_in(GemvIn{x, nullptr, nullptr, 0.f, scale}, W, out, M, N, K, ldo, epilogue, act, st);
 }
 
 bool gemv_norm_supported(int M, int K) {
@@ -255,7 +256,7 @@ bool gemv_norm_supported(int M, int K) {
 
 void launch_gemv_norm(const float* xf, const float* gamma, float eps, const bf16_t* W, void* out, int M, int N, int K,
                       int64_t ldo, int epilogue, int act, hipStream_t st) {
-  launch_gemv_in(GemvIn{nullptr, xf, gamma, eps}, W, out, M, N, K, ldo, epilogue, act, st);
+  launch_gemv_in(GemvIn{nullptr, xf, gamma, eps, 1.f}, W, out, M, N, K, ldo, epilogue, act, st);
 }
 
 // ------------------------------------------------------------------------------------- RoPE + append

@@ -134,7 +134,8 @@ void launch_rmsnorm(float* x, const float* add1, const float* add2, const float*
 __global__ __launch_bounds__(256) void add_parts_rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ parts,
                                                                 int S, size_t part_stride,
                                                                 const float* __restrict__ gamma,
-                                                                bf16_t* __restrict__ out, int d, float eps) {
+                                                                bf16_t* __restrict__ out, int d, float eps,
+                                                                float scale) {
   __shared__ float red[4];
   const size_t row = blockIdx.x;
   float* xr = x + row * d;
@@ -155,7 +156,8 @@ __global__ __launch_bounds__(256) void add_parts_rmsnorm_kernel(float* __restric
 #pragma unroll
       for (int s = 1; s < 8; ++s)
         if (s < S) { acc.x += q[s].x; acc.y += q[s].y; acc.z += q[s].z; acc.w += q[s].w; }
-      acc.x += old.x; acc.y += old.y; acc.z += old.z; acc.w += old.w;
+      acc.x = acc.x * scale + old.x; acc.y = acc.y * scale + old.y;
+      acc.z = acc.z * scale + old.z; acc.w = acc.w * scale + old.w;
       *reinterpret_cast<float4*>(xr + i) = acc;
       v[j] = acc;
       ss += acc.x * acc.x + acc.y * acc.y + acc.z * acc.z + acc.w * acc.w;
@@ -178,10 +180,10 @@ __global__ __launch_bounds__(256) void add_parts_rmsnorm_kernel(float* __restric
 }
 
 void launch_add_parts_rmsnorm(float* x, const float* parts, int S, size_t part_stride, const float* gamma, bf16_t* out,
-                              int rows, int d, float eps, hipStream_t st) {
+                              int rows, int d, float eps, hipStream_t st, float scale) {
   if (rows <= 0 || S < 1 || S > 8) return;
   hipLaunchKernelGGL(add_parts_rmsnorm_kernel, dim3(rows), dim3(256), 0, st, x, parts, S, part_stride, gamma, out, d,
-                     eps);
+                     eps, scale);
 }
 
 void launch_rmsnorm_multi(const float* x, GammaList gammas, int n_out, bf16_t* out, size_t out_stride,

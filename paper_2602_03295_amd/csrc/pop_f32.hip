@@ -50,7 +50,7 @@ __device__ __forceinline__ float glu_act(float g, int act) {
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_kernel(const float* __restrict__ A, int lda, const float* __restrict__ W,
                                                    int ldw, float* __restrict__ out, int ldc, int M, int N, int K,
-                                                   int act) {
+                                                   int act, float scale /* EPI 1: out += scale * C */) {
   constexpr int BT = 64, BKK = 16;
   __shared__ float sa[BKK][BT + 1], sw[BKK][BT + 1], su[EPI == 2 ? BKK : 1][BT + 1];
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const float* __restrict__ A, 
       if (n >= N) continue;
       float* o = out + (size_t)m * ldc + n;
       if (EPI == 0) *o = acc[i][j];
-      else if (EPI == 1) *o += acc[i][j];
+      else if (EPI == 1) *o += acc[i][j] * scale;
       else *o = glu_act(acc[i][j], act) * acu[i][j];
     }
   }
@@ -235,15 +235,15 @@ void launch_rmsnorm(const float* x, const float* gamma, float* out, const int32_
 }
 
 void launch_gemm(const float* A, int lda, const float* W, int ldw, float* out, int ldc, int M, int N, int K, int epi,
-                 int act, hipStream_t st) {
+                 int act, hipStream_t st, float scale) {
   if (M <= 0 || N <= 0) return;
   const dim3 grid((N + 63) / 64, (M + 63) / 64);
   if (epi == EPI_STORE)
-    hipLaunchKernelGGL((impl::gemm_kernel<0>), grid, dim3(256), 0, st, A, lda, W, ldw, out, ldc, M, N, K, act);
+    hipLaunchKernelGGL((impl::gemm_kernel<0>), grid, dim3(256), 0, st, A, lda, W, ldw, out, ldc, M, N, K, act, scale);
   else if (epi == EPI_ADD)
-    hipLaunchKernelGGL((impl::gemm_kernel<1>), grid, dim3(256), 0, st, A, lda, W, ldw, out, ldc, M, N, K, act);
+    hipLaunchKernelGGL((impl::gemm_kernel<1>), grid, dim3(256), 0, st, A, lda, W, ldw, out, ldc, M, N, K, act, scale);
   else
-    hipLaunchKernelGGL((impl::gemm_kernel<2>), grid, dim3(256), 0, st, A, lda, W, ldw, out, ldc, M, N, K, act);
+    hipLaunchKernelGGL((impl::gemm_kernel<2>), grid, dim3(256), 0, st, A, lda, W, ldw, out, ldc, M, N, K, act, scale);
 }
 
 void launch_rope_write(float* qkv, int ld, int q_col, int k_col, int v_col, int n_q_heads, int n_kv_heads, int hd,

@@ -57,6 +57,7 @@ struct GemmParams {
   int n_tile0;           // first column tile of this launch (a GEMM may be split into two launches)
   long long strideA, strideC, strideW;
   const bf16_t* const* W_list;
+  float scale;           // EPI_ADD_F32: out += scale * C
 };
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -437,12 +438,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
           const int m = m_lane + j * 16, n = n0 + wn * WTN + i * 16 + frag_hi * 4;
           float* o = outp + (long long)m * p.ldc + n;
           if (m < p.M && n + 3 < p.N) {
-            *reinterpret_cast<float4*>(o) = make_float4(acc[i][j][0] + old[c].x, acc[i][j][1] + old[c].y,
-                                                        acc[i][j][2] + old[c].z, acc[i][j][3] + old[c].w);
+            *reinterpret_cast<float4*>(o) = make_float4(acc[i][j][0] * p.scale + old[c].x, acc[i][j][1] * p.scale + old[c].y,
+                                                        acc[i][j][2] * p.scale + old[c].z, acc[i][j][3] * p.scale + old[c].w);
           } else if (m < p.M && n < p.N) {   // the last, partial group of four columns
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-              if (n + q < p.N) o[q] += acc[i][j][q];
+              if (n + q < p.N) o[q] += acc[i][j][q] * p.scale;
           }
         }
       }
@@ -504,6 +505,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_
   p.M = g.M; p.N = g.N; p.K = g.K;
   p.lda = (int)g.lda; p.ldw = (int)g.ldw; p.ldc = (int)g.ldc;
   p.act = g.act;
+  p.scale = residual_scale(g);
   p.tiles_m = (g.M + BM - 1) / BM;
   p.tiles_n = n_tiles >= 0 ? n_tiles : (g.N + BN_OUT - 1) / BN_OUT;
   p.n_tile0 = n_tile0;
@@ -618,7 +620,8 @@ namespace gemm_impl {
 // (deterministic).  One thread per 4 consecutive columns.
 template <int EPI>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ parts, int S, long long part_stride,
-                                                            int M, int N, void* __restrict__ out, long long ldc) {
+                                                            int M, int N, void* __restrict__ out, long long ldc,
+                                                            float scale /* EPI_ADD_F32: out += scale * sum */) {
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
   const int n4 = N >> 2;
   if (idx >= (long long)M * n4) return;
@@ -638,7 +641,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     float* o = reinterpret_cast<float*>(out) + (long long)m * ldc + n;
     if (EPI == EPI_ADD_F32) {
       const float4 old = *reinterpret_cast<const float4*>(o);
-      acc.x += old.x; acc.y += old.y; acc.z += old.z; acc.w += old.w;
+      acc.x = acc.x * scale + old.x; acc.y = acc.y * scale + old.y;
+      acc.z = acc.z * scale + old.z; acc.w = acc.w * scale + old.w;
     }
     *reinterpret_cast<float4*>(o) = acc;
   }
@@ -705,6 +709,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
     part.splitk_ws = nullptr;
     part.partials_only = false;
     part.split_used = nullptr;
+    part.scaled = false;
     if (hipError_t e = launch_epi<EPI_STORE_F32>(part, st); e != hipSuccess) return e;
     if (g.partials_only && g.split_used && S <= 8) {   // (the callers' second kernels take up to 8 parts)
       *g.split_used = S;
@@ -714,13 +719,13 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
     const dim3 grid((unsigned)((items + 255) / 256));
     switch (g.epilogue) {
       case EPI_STORE_BF16:
-        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_STORE_BF16>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc); break;
+        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_STORE_BF16>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc, residual_scale(g)); break;
       case EPI_STORE_F16:
-        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_STORE_F16>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc); break;
+        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_STORE_F16>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc, residual_scale(g)); break;
       case EPI_ADD_F32:
-        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_ADD_F32>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc); break;
+        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_ADD_F32>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc, residual_scale(g)); break;
       default:
-        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_STORE_F32>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc); break;
+        hipLaunchKernelGGL(splitk_reduce_kernel<EPI_STORE_F32>, grid, dim3(256), 0, st, g.splitk_ws, S, part.strideC, g.M, g.N, g.out, (long long)g.ldc, residual_scale(g)); break;
     }
     return hipGetLastError();
   }

@@ -36,7 +36,8 @@ void launch_rmsnorm_multi(const float* x, GammaList gammas, int n_out, bf16_t* o
 // residual epilogue and the normalisation that follows it (Sec. 2.1), in one launch.  d % 4 == 0, d <= 8192,
 // 1 <= S <= 8.
 void launch_add_parts_rmsnorm(float* x, const float* parts, int S, size_t part_stride, const float* gamma, bf16_t* out,
-                              int rows, int d, float eps, hipStream_t st);
+                              int rows, int d, float eps, hipStream_t st, float scale = 1.f);
+// (scale: the sum of the parts is multiplied by it before it is added to x)
 
 // cs[t, i] = (cos, sin)(pos[t] * theta^(-2 i / hd)), i < hd/2, angle formed in fp64.
 void launch_rope_table(const int32_t* pos, float2* cs, int T, int hd, double theta, hipStream_t st);
@@ -102,7 +103,12 @@ struct GemmArgs {
   // parts: epilogue applied as usual).
   bool partials_only;
   int* split_used;
+  // EPI_ADD_F32 with `scaled`: out += scale * C (the virtual gate of Sec. 3.1 on a residual branch); otherwise
+  // out += C.  A caller that adds partial products itself (partials_only) applies the scale there.
+  bool scaled;
+  float scale;
 };
+inline float residual_scale(const GemmArgs& g) { return g.scaled ? g.scale : 1.f; }
 // Returns hipSuccess or the launch error.  Requirements: K % 8 == 0, lda/ldw % 8 == 0,
 // A/W 16-byte aligned, ldc % 4 == 0, and every operand below 2^31 bytes.
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t st);
@@ -133,7 +139,7 @@ hipError_t launch_attention_prefill(const AttnPrefillArgs& a, hipStream_t st);
 enum GemvEpilogue { GEMV_STORE_F32 = 0, GEMV_ADD_F32 = 1, GEMV_GLU_BF16 = 2 };
 // out[m, n] (op)= sum_k x[m,k] * W[n,k], x bf16 [M, K] (M <= 8), W bf16 [N, K] ([2N, K] for GLU).
 void launch_gemv(const bf16_t* x, const bf16_t* W, void* out, int M, int N, int K, int64_t ldo,
-                 int epilogue, int act, hipStream_t st);
+                 int epilogue, int act, hipStream_t st, float scale = 1.f);   // GEMV_ADD_F32: out += scale * C
 // The same with the RMSNorm of the input fused in (Sec. 2.1): xf fp32 [M, K] is normalised with gamma / eps
 // inside the kernel (bit-identical to launch_rmsnorm followed by launch_gemv).  Only where
 // gemv_norm_supported(M, K): M <= 4 rows whose normalised copies fit 48 KB of LDS.
@@ -187,7 +193,7 @@ void launch_rmsnorm(const float* x, const float* gamma, float* out, const int32_
                     hipStream_t st);
 // out (op)= A[M,K] W[N,K]^T ; EPI_GLU: W is [2N,K] (gate rows, then up rows)
 void launch_gemm(const float* A, int lda, const float* W, int ldw, float* out, int ldc, int M, int N, int K, int epi,
-                 int act, hipStream_t st);
+                 int act, hipStream_t st, float scale = 1.f);   // EPI_ADD: out += scale * C
 // rotate q (unless q_col < 0) and k of `rows` rows in place, append k, v at slot[row]
 void launch_rope_write(float* qkv, int ld, int q_col, int k_col, int v_col, int n_q_heads, int n_kv_heads, int hd,
                        const int32_t* pos, const int32_t* slot, double theta, float* k_pool, float* v_pool, int P,

@@ -56,7 +56,8 @@ class pop_prefill_args(C.Structure):
                 ("block_table", C.POINTER(C.c_int32)), ("embeds", C.c_void_p),
                 ("embed_ranges", C.POINTER(C.c_int32)), ("n_ranges", C.c_int32), ("l_keep", C.c_int32),
                 ("mode", C.c_int32), ("skip_layers", C.POINTER(C.c_int32)), ("n_skip", C.c_int32),
-                ("no_kv_projection", C.c_int32), ("window_kv_writes", C.c_int32)]
+                ("no_kv_projection", C.c_int32), ("window_kv_writes", C.c_int32),
+                ("gates", C.POINTER(C.c_float))]
 
 
 _i32p = C.POINTER(C.c_int32)
@@ -80,6 +81,8 @@ lib.pop_prefill.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(pop_prefill_args),
                             C.c_size_t, C.c_void_p]
 lib.pop_decode_step.argtypes = [C.c_void_p, C.c_void_p, _i32p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t,
                                 C.c_void_p]
+lib.pop_decode_step_gated.argtypes = [C.c_void_p, C.c_void_p, _i32p, C.c_int32, C.POINTER(C.c_float), C.c_void_p,
+                                      C.c_void_p, C.c_size_t, C.c_void_p]
 lib.pop_generate_workspace_bytes.argtypes = [C.POINTER(pop_config), C.c_int32, C.c_int32, C.c_int32, C.c_int32]
 lib.pop_generate_workspace_bytes.restype = C.c_size_t
 lib.pop_generate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(pop_prefill_args), C.c_int32, C.c_int32, C.c_void_p,
@@ -105,7 +108,7 @@ STEP_NAMES = ["embed", "norm", "qkv_gemm", "rope_write", "attention", "o_gemm", 
 
 EXPORTED = ["pop_timing_enable", "pop_timing_read", "pop_last_error", "pop_version", "pop_load_weights", "pop_free_model", "pop_cache_bytes",
             "pop_workspace_bytes", "pop_cache_create", "pop_cache_destroy", "pop_cache_n_seqs",
-            "pop_cache_seq_lens", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_generate",
+            "pop_cache_seq_lens", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_decode_step_gated", "pop_generate",
             "pop_generate_workspace_bytes", "pop_op_rmsnorm",
             "pop_op_gemm", "pop_op_gemm_splitk", "pop_op_gemv", "pop_op_gemv_norm", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
 
@@ -124,6 +127,14 @@ def make_config(cfg: Dict) -> pop_config:
 
 def _i32(a) -> np.ndarray:
     return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _f32(a) -> Optional[np.ndarray]:
+    return None if a is None else np.ascontiguousarray(np.asarray(a, dtype=np.float32))
+
+
+def _fptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.POINTER(C.c_float))
 
 
 def _ptr(a: Optional[np.ndarray]):
@@ -272,18 +283,20 @@ def alloc_workspace(cfg: Dict, max_tokens: int, max_seqs: int, max_pages_per_seq
 def pop_prefill(model: Model, cache: Cache, tokens, cu_seqlens, block_table, l_keep: int, workspace: torch.Tensor,
                 mode: int = MODE_POP, logits: Optional[torch.Tensor] = None, embeds: Optional[torch.Tensor] = None,
                 embed_ranges=None, stream=None, skip_layers=None, no_kv_projection: bool = False,
-                window_kv_writes: bool = False) -> Optional[torch.Tensor]:
-    """skip_layers: 1-based layer indices (a general skip set; None = the deep block beyond l_keep)."""
+                window_kv_writes: bool = False, gates=None) -> Optional[torch.Tensor]:
+    """skip_layers: 1-based layer indices (a general skip set; None = the deep block beyond l_keep).
+    gates: per-layer prefill-stage virtual gates (only with MODE_BODY_ONLY / MODE_NO_BOUNDARY)."""
     tok, cu, bt = _i32(tokens), _i32(cu_seqlens), _i32(block_table)
     n_seqs = len(cu) - 1
     skip = None if skip_layers is None else _i32(list(skip_layers) + [0])[:len(skip_layers)]   # non-NULL even if empty
     if logits is None and mode != MODE_BODY_ONLY:
         logits = torch.empty(max(n_seqs, 1), model.cfg["vocab"], dtype=torch.float32, device=workspace.device)
     rng = None if embed_ranges is None else _i32(embed_ranges).reshape(-1, 3)
+    gts = _f32(gates)
     a = pop_prefill_args(_ptr(tok), _ptr(cu), n_seqs, _ptr(bt),
                          None if embeds is None else embeds.data_ptr(), _ptr(rng),
                          0 if rng is None else len(rng), l_keep, mode, _ptr(skip), 0 if skip is None else len(skip),
-                         1 if no_kv_projection else 0, 1 if window_kv_writes else 0)
+                         1 if no_kv_projection else 0, 1 if window_kv_writes else 0, _fptr(gts))
     _check(lib.pop_prefill(model.handle, cache.handle, C.byref(a),
                            None if logits is None else logits.data_ptr(),
                            workspace.data_ptr() if workspace is not None else None,
@@ -292,12 +305,18 @@ def pop_prefill(model: Model, cache: Cache, tokens, cu_seqlens, block_table, l_k
 
 
 def pop_decode_step(model: Model, cache: Cache, tokens, workspace: torch.Tensor,
-                    logits: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                    logits: Optional[torch.Tensor] = None, stream=None, gates=None) -> torch.Tensor:
+    """gates: per-layer decode-stage virtual gates (None = the plain step)."""
     tok = _i32(tokens)
     if logits is None:
         logits = torch.empty(len(tok), model.cfg["vocab"], dtype=torch.float32, device=workspace.device)
-    _check(lib.pop_decode_step(model.handle, cache.handle, _ptr(tok), len(tok), logits.data_ptr(),
-                               workspace.data_ptr(), workspace.numel(), _stream(stream)))
+    gts = _f32(gates)
+    if gts is None:
+        _check(lib.pop_decode_step(model.handle, cache.handle, _ptr(tok), len(tok), logits.data_ptr(),
+                                   workspace.data_ptr(), workspace.numel(), _stream(stream)))
+    else:
+        _check(lib.pop_decode_step_gated(model.handle, cache.handle, _ptr(tok), len(tok), _fptr(gts),
+                                         logits.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream)))
     return logits
 
 

@@ -28,15 +28,16 @@ class GpuRun:
         self.ws = pop.alloc_workspace(cfg, int(self.cu[-1]), len(lens), self.bt.shape[1])
 
     def prefill(self, tokens, l_keep, mode=0, embeds=None, embed_ranges=None, skip_layers=None, no_kv_projection=False,
-                window_kv_writes=False):
+                window_kv_writes=False, gates=None):
         logits = self.pop.pop_prefill(self.model, self.cache, tokens, self.cu, self.bt, l_keep, self.ws, mode=mode,
                                       embeds=embeds, embed_ranges=embed_ranges, skip_layers=skip_layers,
-                                      no_kv_projection=no_kv_projection, window_kv_writes=window_kv_writes)
+                                      no_kv_projection=no_kv_projection, window_kv_writes=window_kv_writes,
+                                      gates=gates)
         torch.cuda.synchronize()
         return None if logits is None else logits.cpu().numpy()
 
-    def decode(self, tokens):
-        logits = self.pop.pop_decode_step(self.model, self.cache, tokens, self.ws)
+    def decode(self, tokens, gates=None):
+        logits = self.pop.pop_decode_step(self.model, self.cache, tokens, self.ws, gates=gates)
         torch.cuda.synchronize()
         return logits.cpu().numpy()
 

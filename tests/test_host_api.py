@@ -259,6 +259,33 @@ def test_skip_set_and_switch_argument_errors():
         pop.lib.pop_free_model(m)
 
 
+def test_gate_argument_errors():
+    """Prefill-stage gates are refused in POP mode (the last token is a decode-stage token) and must be finite;
+    so must the decode-stage gates of pop_decode_step_gated."""
+    cfg = bf16_cfg()
+    L = cfg["n_layers"]
+    tokens = synth.make_tokens(cfg["vocab"], 27, seed=1)
+    bt, n_pages = synth.make_block_table([20, 7], 16, reserve_pages=1)
+    cu = np.array([0, 20, 27], dtype=np.int32)
+    tok, bt_ = (np.ascontiguousarray(np.asarray(x, dtype=np.int32)) for x in (tokens, bt))
+    p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    fp = lambda a: a.ctypes.data_as(C.POINTER(C.c_float))
+    ones = np.ones(L, dtype=np.float32)
+    bad_gate = ones.copy()
+    bad_gate[2] = np.inf
+    for mode, gates, expect in ((0, ones, "POP_MODE_BODY_ONLY"), (1, bad_gate, "gates[2]"), (2, bad_gate * np.nan, "gates[0]")):
+        st, m, c_cfg, keep = fake_model(cfg)
+        st, cache = fake_cache(c_cfg, n_pages, 4, bt.shape[1])
+        a = pop.pop_prefill_args(p(tok), p(cu), 2, p(bt_), None, None, 0, 5, mode, None, 0, 0, 0, fp(gates))
+        st = pop.lib.pop_prefill(m, cache, C.byref(a), FAKE, FAKE, 1 << 34, None)
+        assert st == -1 and expect in err(), (mode, st, err())
+        assert pop.lib.pop_cache_n_seqs(cache) == 0
+        st = pop.lib.pop_decode_step_gated(m, cache, p(tok), 2, fp(bad_gate), FAKE, FAKE, 1 << 34, None)
+        assert st == -1 and "gates[2]" in err()
+        pop.lib.pop_cache_destroy(cache)
+        pop.lib.pop_free_model(m)
+
+
 def test_qk_norm_pointers_come_in_pairs():
     """A layer with only one of q_norm / k_norm, or a misaligned one, is refused by pop_load_weights."""
     cfg = bf16_cfg()
