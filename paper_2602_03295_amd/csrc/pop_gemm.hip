@@ -473,20 +473,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
               for (int e = 0; e < 4; ++e)
                 if (n + e < p.N) o[e] = EPI == EPI_STORE_F16 ? f32_to_f16_sat(r[e]) : f32_to_bf16(r[e]);
             }
-          } else {
+          } else {   // EPI_STORE_F32
             float* o = reinterpret_cast<float*>(p.out) + (long long)z * p.strideC + (long long)m * p.ldc + n;
             if (n + 3 < p.N) {
-              float4 c = make_float4(r0, r1, r2, r3);
-              if (EPI == EPI_ADD_F32) {
-                const float4 old = *reinterpret_cast<const float4*>(o);
-                c.x += old.x; c.y += old.y; c.z += old.z; c.w += old.w;
-              }
-              *reinterpret_cast<float4*>(o) = c;
+              *reinterpret_cast<float4*>(o) = make_float4(r0, r1, r2, r3);
             } else {
               const float r[4] = {r0, r1, r2, r3};
 #pragma unroll
               for (int e = 0; e < 4; ++e)
-                if (n + e < p.N) o[e] = (EPI == EPI_ADD_F32 ? o[e] : 0.f) + r[e];
+                if (n + e < p.N) o[e] = r[e];
             }
           }
         }
