@@ -328,7 +328,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
         for (int q = g * LPG; q < (g + 1) * LPG && q < LPS; ++q) issue_one(slot * LPS + q, tp, fill_base, pmask);
 #pragma unroll
         for (int e = g * MPG; e < (g + 1) * MPG; ++e) {
-          const int i = e / MB, j = e % MB;
+          // W block by W block, the activation blocks forwards and backwards in turn: from one MFMA to the next
+          // only one of the two operands changes (measured 0.3 to 1.2 % faster than restarting at block 0:
+          // the clock under this load is set by power, and operand switching is part of it)
+          const int i = e / MB, j = (i & 1) ? MB - 1 - e % MB : e % MB;
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[(slot + 1) & 1][i], af[(slot + 1) & 1][j],
                                                               acc[i][j], 0, 0, 0);
         }
@@ -371,7 +374,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   // last sub-step of the last K-step
 #pragma unroll
   for (int e = 0; e < MFMAS; ++e) {
-    const int i = e / MB, j = e % MB;
+    const int i = e / MB, j = (i & 1) ? MB - 1 - e % MB : e % MB;
     acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[(STEPS - 1) & 1][i], af[(STEPS - 1) & 1][j], acc[i][j], 0, 0, 0);
   }
   // masked staging loads and prefetches of the last iterations still target this group's LDS
