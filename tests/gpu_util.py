@@ -16,7 +16,7 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.max(np.abs(got.astype(np.float64) - ref))) / (den if den > 0 else 1.0)
 
 
-class GpuRun:
+class DeviceRun:
     def __init__(self, pop, cfg, W, lens, reserve_pages=1, shuffle_seed=None, poison=None):
         self.pop, self.cfg, self.lens = pop, cfg, list(lens)
         self.dev_w = pop.upload_weights(cfg, W)
@@ -49,7 +49,7 @@ class GpuRun:
         return k, v
 
 
-def compare_with_oracle(run: GpuRun, W, tokens, l_keep, gpu_logits, embeds=None, embed_ranges=(), tol=TOL,
+def compare_with_oracle(run: DeviceRun, W, tokens, l_keep, gpu_logits, embeds=None, embed_ranges=(), tol=TOL,
                         lengths=None):
     """Element-by-element comparison of every layer's K and V and of the logits, per sequence.
     Returns the worst relative errors and the oracle's outputs."""

@@ -8,7 +8,7 @@ import torch
 
 from oracle import pop_oracle as O
 from paper_2602_03295_amd import synth
-from tests.gpu_util import GpuRun, compare_with_oracle, rel_err
+from tests.gpu_util import DeviceRun, compare_with_oracle, rel_err
 
 pytestmark = pytest.mark.gpu
 TOL32 = 1e-5   # the stated bar for this config is 1e-4; measured errors are about 1e-6
@@ -31,7 +31,7 @@ def test_config0_fp32(pop, l_keep):
     assert cfg["dtype"] == synth.DTYPE_F32
     W = synth.make_weights(cfg, seed=1234)
     tokens = synth.make_tokens(cfg["vocab"], 128, seed=1)
-    run = GpuRun(pop, cfg, W, [128], poison=float("nan"))
+    run = DeviceRun(pop, cfg, W, [128], poison=float("nan"))
     logits = run.prefill(tokens, l_keep)
     worst, _ = compare_with_oracle(run, W, tokens, l_keep, logits, tol=TOL32)
     print("config 0 fp32, l_keep", l_keep, worst)
@@ -43,7 +43,7 @@ def test_fp32_ragged_batch_shuffled_pages_norm_scales(pop):
     synth.randomize_norms(W, cfg)
     lens = [129, 1, 64, 200, 2]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=3)
-    run = GpuRun(pop, cfg, W, lens, shuffle_seed=4, poison=float("nan"))
+    run = DeviceRun(pop, cfg, W, lens, shuffle_seed=4, poison=float("nan"))
     logits = run.prefill(tokens, 2)
     worst, _ = compare_with_oracle(run, W, tokens, 2, logits, tol=TOL32)
     print("fp32 ragged", worst)
@@ -57,7 +57,7 @@ def test_fp32_window_gelu_local_theta(pop):
     synth.randomize_norms(W, cfg)
     lens = [90, 37]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=5)
-    run = GpuRun(pop, cfg, W, lens, poison=float("nan"))
+    run = DeviceRun(pop, cfg, W, lens, poison=float("nan"))
     logits = run.prefill(tokens, 4)
     worst, _ = compare_with_oracle(run, W, tokens, 4, logits, tol=TOL32)
     print("fp32 window/gelu", worst)
@@ -69,13 +69,13 @@ def test_fp32_body_only_then_decode_equals_pop_mode(pop):
     W = synth.make_weights(cfg, seed=13)
     lens = [50, 17]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=6)
-    fused = GpuRun(pop, cfg, W, lens)
+    fused = DeviceRun(pop, cfg, W, lens)
     l_fused = fused.prefill(tokens, 3)
     cu = fused.cu
     body_lens = [n - 1 for n in lens]
     body_tokens = np.concatenate([tokens[cu[b]:cu[b + 1] - 1] for b in range(len(lens))])
     last = np.array([tokens[cu[b + 1] - 1] for b in range(len(lens))], dtype=np.int32)
-    split = GpuRun(pop, cfg, W, body_lens, reserve_pages=1)
+    split = DeviceRun(pop, cfg, W, body_lens, reserve_pages=1)
     split.prefill(body_tokens, 3, mode=pop.MODE_BODY_ONLY)
     l_split = split.decode(last)
     assert rel_err(l_split, l_fused.astype(np.float64)) <= TOL32
@@ -93,7 +93,7 @@ def test_fp32_visual_rows_override(pop):
     tokens = synth.make_tokens(cfg["vocab"], n, seed=8)
     emb = synth.make_visual_embeds(40, cfg["d_model"], seed=2, as_bf16=False) * 0.05
     ranges = [(0, 10, 40)]
-    run = GpuRun(pop, cfg, W, [n])
+    run = DeviceRun(pop, cfg, W, [n])
     logits = run.prefill(tokens, 2, embeds=emb.to(torch.float32).cuda(), embed_ranges=ranges)
     worst, _ = compare_with_oracle(run, W, tokens, 2, logits, embeds=emb.numpy(), embed_ranges=ranges, tol=TOL32)
     print("fp32 visual", worst)

@@ -9,7 +9,7 @@ import torch
 
 from oracle import pop_oracle as O
 from paper_2602_03295_amd import synth
-from tests.gpu_util import TOL, GpuRun, rel_err
+from tests.gpu_util import TOL, DeviceRun, rel_err
 
 pytestmark = pytest.mark.gpu
 TOL32 = 1e-5
@@ -34,7 +34,7 @@ def gated_run(pop, cfg, W, lens, tokens, l_keep, gp, gd, n_decode=0, seed=0):
     """Body of every prompt with prefill gates gp, then its last token (and n_decode more, teacher-forced)
     with decode gates gd.  Returns (run, list over steps of logits [B, V])."""
     body = [n - 1 for n in lens]
-    run = GpuRun(pop, cfg, W, body, reserve_pages=2, shuffle_seed=5, poison=0.0)
+    run = DeviceRun(pop, cfg, W, body, reserve_pages=2, shuffle_seed=5, poison=0.0)
     cu_full = np.concatenate([[0], np.cumsum(lens)])
     body_tokens = np.concatenate([tokens[cu_full[b]:cu_full[b + 1] - 1] for b in range(len(lens))])
     run.prefill(body_tokens, l_keep, mode=pop.MODE_BODY_ONLY, gates=gp)
@@ -125,7 +125,7 @@ def test_stage_specific_gate_sensitivity_by_central_differences(pop):
         return float(np.sum(lse - rows[np.arange(len(rows)), future[:len(rows)]]))
 
     def loss_gpu(gp, gd):
-        run = GpuRun(pop, cfg, W, [n - 1], reserve_pages=2)
+        run = DeviceRun(pop, cfg, W, [n - 1], reserve_pages=2)
         run.prefill(tokens[:n - 1], L, mode=pop.MODE_BODY_ONLY, gates=gp)
         rows = [run.decode([int(tokens[n - 1])], gates=gd)[0]]
         for s in range(n_dec):

@@ -8,7 +8,7 @@ import torch
 
 from oracle import pop_oracle as O
 from paper_2602_03295_amd import synth
-from tests.gpu_util import TOL, GpuRun, compare_with_oracle, rel_err
+from tests.gpu_util import TOL, DeviceRun, compare_with_oracle, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -35,7 +35,7 @@ def test_tiny_config_single_prompt(pop, l_keep):
     W = synth.make_weights(cfg, seed=1234)
     synth.randomize_norms(W, cfg)
     tokens = synth.make_tokens(cfg["vocab"], 128, seed=1)
-    run = GpuRun(pop, cfg, W, [128], poison=float("nan"))
+    run = DeviceRun(pop, cfg, W, [128], poison=float("nan"))
     logits = run.prefill(tokens, l_keep)
     worst, _ = compare_with_oracle(run, W, tokens, l_keep, logits)
     print("tiny l_keep", l_keep, worst)
@@ -47,7 +47,7 @@ def test_slot_placement_is_exact_and_nothing_else_is_written(pop):
     lens = [70, 1, 33, 150]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=2)
     sentinel = -12345.0
-    run = GpuRun(pop, cfg, W, lens, reserve_pages=2, shuffle_seed=9, poison=sentinel)
+    run = DeviceRun(pop, cfg, W, lens, reserve_pages=2, shuffle_seed=9, poison=sentinel)
     run.prefill(tokens, 2)
     slots = O.slot_map(run.cu, run.bt, cfg["page_size"])
     assert np.array_equal(pop.pop_slot_map(run.cu, run.bt, cfg["page_size"], run.n_pages), slots)
@@ -68,13 +68,13 @@ def test_ragged_batch_paged_matches_oracle_and_single_runs(pop):
     synth.randomize_norms(W, cfg)
     lens = [129, 1, 64, 200, 2]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=3)
-    run = GpuRun(pop, cfg, W, lens, shuffle_seed=4, poison=float("nan"))
+    run = DeviceRun(pop, cfg, W, lens, shuffle_seed=4, poison=float("nan"))
     logits = run.prefill(tokens, 2)
     worst, _ = compare_with_oracle(run, W, tokens, 2, logits)
     print("ragged", worst)
     # the same sequence run alone gives the same bits (no cross-sequence leakage, deterministic)
     b = 3
-    solo = GpuRun(pop, cfg, W, [lens[b]])
+    solo = DeviceRun(pop, cfg, W, [lens[b]])
     l2 = solo.prefill(tokens[run.cu[b]:run.cu[b + 1]], 2)
     k1, v1 = run.kv(3, b)
     k2, v2 = solo.kv(3, 0)
@@ -88,11 +88,11 @@ def test_body_only_then_decode_step_equals_pop_mode(pop):
     W = synth.make_weights(cfg, seed=8)
     lens = [97, 40]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=4)
-    run = GpuRun(pop, cfg, W, lens, poison=float("nan"))
+    run = DeviceRun(pop, cfg, W, lens, poison=float("nan"))
     logits = run.prefill(tokens, 2)
     body_lens = [n - 1 for n in lens]
     body_tokens = np.concatenate([tokens[0:96], tokens[97:136]])
-    run2 = GpuRun(pop, cfg, W, body_lens, reserve_pages=1, poison=float("nan"))
+    run2 = DeviceRun(pop, cfg, W, body_lens, reserve_pages=1, poison=float("nan"))
     assert run2.prefill(body_tokens, 2, mode=pop.MODE_BODY_ONLY) is None
     l2 = run2.decode(np.array([tokens[96], tokens[136]]))
     assert run2.cache.seq_lens().tolist() == lens
@@ -121,7 +121,7 @@ def test_visual_embedding_override(pop):
     n = 150
     tokens = synth.make_tokens(cfg["vocab"], n, seed=5)
     emb = synth.make_visual_embeds(70, cfg["d_model"], seed=2) * 0.05
-    run = GpuRun(pop, cfg, W, [n], poison=float("nan"))
+    run = DeviceRun(pop, cfg, W, [n], poison=float("nan"))
     ranges = [(0, 10, 50), (0, 100, 20)]
     logits = run.prefill(tokens, 2, embeds=emb.to(torch.bfloat16).cuda(), embed_ranges=ranges)
     compare_with_oracle(run, W, tokens, 2, logits, embeds=emb.numpy(), embed_ranges=ranges)
@@ -137,7 +137,7 @@ def test_gemma_like_local_global_gelu(pop, hd, hq, hkv):
     synth.randomize_norms(W, cfg)
     lens = [260, 50]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=6)
-    run = GpuRun(pop, cfg, W, lens, poison=float("nan"))
+    run = DeviceRun(pop, cfg, W, lens, poison=float("nan"))
     logits = run.prefill(tokens, 4)
     worst, _ = compare_with_oracle(run, W, tokens, 4, logits)
     print("gemma-like", hd, worst)
@@ -147,7 +147,7 @@ def test_runs_are_bitwise_deterministic_and_cache_reuse_resets(pop):
     cfg = tiny_bf16(n_layers=3)
     W = synth.make_weights(cfg, seed=11)
     tokens = synth.make_tokens(cfg["vocab"], 300, seed=7)
-    run = GpuRun(pop, cfg, W, [300])
+    run = DeviceRun(pop, cfg, W, [300])
     l1 = run.prefill(tokens, 2)
     c1 = run.cache.pool.clone()
     l2 = run.prefill(tokens, 2)
@@ -167,7 +167,7 @@ def test_llama_width_reduced_depth(pop):
     W = synth.make_weights(cfg, seed=1234)
     n = 640
     tokens = synth.make_tokens(cfg["vocab"], n, seed=1)
-    run = GpuRun(pop, cfg, W, [n], poison=float("nan"))
+    run = DeviceRun(pop, cfg, W, [n], poison=float("nan"))
     logits = run.prefill(tokens, 2)
     worst, _ = compare_with_oracle(run, W, tokens, 2, logits)
     print("llama-width", worst)

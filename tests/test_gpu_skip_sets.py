@@ -7,7 +7,7 @@ import torch
 
 from oracle import pop_oracle as O
 from paper_2602_03295_amd import synth
-from tests.gpu_util import TOL, GpuRun, rel_err
+from tests.gpu_util import TOL, DeviceRun, rel_err
 
 pytestmark = pytest.mark.gpu
 TOL32 = 1e-5
@@ -27,7 +27,7 @@ def check_against_oracle(pop, cfg, W, lens, tokens, skip, kv_projection, boundar
     """Prefill (and n_decode teacher-forced decode steps) on the GPU and in the oracle, compared per
     sequence: entries that exist element by element, positions without an entry still holding the
     sentinel the pool was filled with, logits of the prefill and of every decode step."""
-    run = GpuRun(pop, cfg, W, lens, reserve_pages=2, shuffle_seed=3, poison=SENTINEL)
+    run = DeviceRun(pop, cfg, W, lens, reserve_pages=2, shuffle_seed=3, poison=SENTINEL)
     mode = pop.MODE_POP if boundary else pop.MODE_NO_BOUNDARY
     logits = run.prefill(tokens, 0, mode=mode, skip_layers=list(skip), no_kv_projection=not kv_projection,
                          window_kv_writes=window_kv_writes)
@@ -128,9 +128,9 @@ def test_deep_skip_set_equals_l_keep(pop):
     W = synth.make_weights(cfg, seed=24)
     lens = [200, 45]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=7)
-    a = GpuRun(pop, cfg, W, lens, poison=0.0)
+    a = DeviceRun(pop, cfg, W, lens, poison=0.0)
     la = a.prefill(tokens, 5)
-    b = GpuRun(pop, cfg, W, lens, poison=0.0)
+    b = DeviceRun(pop, cfg, W, lens, poison=0.0)
     lb = b.prefill(tokens, 0, skip_layers=[6, 7, 8])
     assert np.array_equal(la, lb)
     assert torch.equal(a.cache.pool, b.cache.pool)
@@ -144,7 +144,7 @@ def test_generate_without_boundary_handling(pop):
     lens = [40, 9]
     n_new = 4
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=8)
-    run = GpuRun(pop, cfg, W, lens, reserve_pages=2)
+    run = DeviceRun(pop, cfg, W, lens, reserve_pages=2)
     ws = pop.alloc_generate_workspace(cfg, sum(lens), len(lens), run.bt.shape[1], n_new)
     out, _ = pop.pop_generate(run.model, run.cache, tokens, run.cu, run.bt, 0, n_new, ws, mode=pop.MODE_NO_BOUNDARY,
                               skip_layers=[2, 4])
@@ -188,7 +188,7 @@ def test_windowed_kv_writes_change_no_logit(pop):
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=10)
     outs = []
     for flag in (False, True):
-        run = GpuRun(pop, cfg, W, lens, reserve_pages=2, poison=0.0)
+        run = DeviceRun(pop, cfg, W, lens, reserve_pages=2, poison=0.0)
         lg = [run.prefill(tokens, 3, window_kv_writes=flag)]
         for s in range(3):
             lg.append(run.decode(np.array([5 + s, 9 + s], dtype=np.int32)))
