@@ -157,3 +157,21 @@ def test_stage_specific_gate_sensitivity_by_central_differences(pop):
     print("(dL/dg)^2 prefill stage:", sens["ref"][0], " decode stage:", sens["ref"][1])
     assert np.max(np.abs(sens["gpu"] - sens["ref"])) <= 2e-3 * np.max(sens["ref"])
     assert not np.allclose(sens["ref"][0], sens["ref"][1], rtol=0.2)      # the two stages weigh the layers differently
+
+
+@pytest.mark.parametrize("dtype,tol", [(synth.DTYPE_F32, TOL32), (synth.DTYPE_BF16, TOL)])
+def test_gated_prefill_without_boundary_handling(pop, dtype, tol):
+    """POP_MODE_NO_BOUNDARY with gates: every token is a prefill-stage token and the logits are the final norm
+    and LM head of the gated, pruned model's output for the last one."""
+    cfg, W = model(dtype)
+    L, l_keep, n = cfg["n_layers"], 4, 37
+    gp = np.random.default_rng(9).uniform(0.2, 1.4, L).astype(np.float32)
+    tokens = synth.make_tokens(cfg["vocab"], n, seed=14)
+    run = DeviceRun(pop, cfg, W, [n])
+    logits = run.prefill(tokens, l_keep, mode=pop.MODE_NO_BOUNDARY, gates=gp)
+    h = O.embed_rows(W, tokens, np.float64)
+    Kc, Vc, x = O.body_prefill(cfg, W, h, l_keep, gates=gp)
+    assert rel_err(logits[0], O.lm_head_logits(cfg, W, x[-1:])[0]) <= tol
+    for l in range(L):
+        k, v = run.kv(l, 0)
+        assert rel_err(k, Kc[l]) <= tol and rel_err(v, Vc[l]) <= tol
