@@ -323,7 +323,7 @@ def main():
         # the prefill variants of the paper's ablation study (Sec. 4.4), a third of the layers pruned in
         # each: which layers (deep block = the method, first third, every third layer) and the two switches.
         # Only their time is measured here; what they do to accuracy needs trained weights.
-        third = L - (2 * L) // 3
+        third = L // 3          # the paper's ratio: 10 of 32 layers
         variants = {
             "deep (the method)": dict(skip_layers=list(range(L - third + 1, L + 1))),
             "shallow": dict(skip_layers=list(range(1, third + 1))),
@@ -351,7 +351,7 @@ def main():
         # generation after the pruned prefill (Sec. 3.2: decode runs the full model on the cache the prefill
         # left): time of pop_generate for 1 and for 33 new tokens; the difference is 32 decode steps.
         # A decode step streams every weight once plus the cache: HBM-bound.
-        lk = (2 * L) // 3
+        lk = synth.paper_l_keep(L)
         new = 33
         p_layer = d * (dq + 2 * dkv) + dq * d + 3 * d * f
         gen = {}
@@ -389,7 +389,7 @@ def main():
         # skipped for the body, the paper's static policy) against full depth: the shape of the paper's
         # TTFT table; its numbers are another machine's and are not compared
         del ws
-        lk = (2 * L) // 3
+        lk = synth.paper_l_keep(L)
         sweep8 = {}
         for plen in (32, 128, 512, 2048):
             lens = [plen] * 8

@@ -55,6 +55,12 @@ CONFIGS: Dict[str, Dict] = {
 }
 
 
+def paper_l_keep(n_layers: int) -> int:
+    """The paper's static policy (Sec. 3.3): the last third of the layers is pruned, floor(L / 3) of them,
+    which gives the ratios its main results table states (31.25 % at 32 layers, 33.3 % at 36 and 48)."""
+    return n_layers - n_layers // 3
+
+
 def get_config(name: str, **overrides) -> Dict:
     cfg = copy.deepcopy(CONFIGS[name])
     cfg.update(overrides)
