@@ -161,7 +161,7 @@ def main():
     ap.add_argument("--config", default="llama8b")
     ap.add_argument("--seq-len", type=int, default=2048)
     ap.add_argument("--l-keep", type=int, default=24)
-    ap.add_argument("--sweep", default="32,28,24,20")
+    ap.add_argument("--sweep", default="32,28,24,22,20")  # BASELINE sweep + the paper's own ratio (22 of 32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ttft-sweep", action="store_true",
                     help="skip the batch-8 time-to-first-token sweep over prompt lengths (Table 2's shape)")
@@ -256,7 +256,7 @@ def main():
     achieved = gu_flops / (gu_ms * 1e-3) / 1e12 if gu_ms > 0 else 0.0
     # HBM bytes per launch of that kernel, from the committed rocprofv3 --pmc runs (FETCH_SIZE x 2.0 +
     # WRITE_SIZE x 1.0, calibrated with a 1 GiB copy); only valid for the workload they were taken on
-    traffic = ((295126 + 65652) * 2.0 + (49152 + 8192)) * 1024 if (args.config == "llama8b" and n == 2048 and not args.layers) else None
+    traffic = ((295122 + 65652) * 2.0 + (49152 + 8192)) * 1024 if (args.config == "llama8b" and n == 2048 and not args.layers) else None
     breakdown = {k: {"ms_per_launch": v["ms"] / max(v["launches"], 1), "launches_per_step": v["launches"] / args.steps,
                      "ms_per_step": v["ms"] / args.steps} for k, v in steps_t.items() if v["launches"]}
     hd = cfg["head_dim"]
