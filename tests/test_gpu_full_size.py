@@ -164,3 +164,34 @@ def test_llama8b_short_prompts_small_tiles_and_split_k(pop):
     lens = [32, 7, 64, 1, 50, 33, 40, 29]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=3)
     run_and_compare(pop, cfg, lens, 2, tokens)
+
+
+def test_llama8b_width_virtual_gates_short_batch(pop):
+    """Virtual gates at the Llama width, 8 short prompts (247 packed body rows): the residual scale passes
+    through the split down projection's second kernel in the prefill and through the tiled-GEMM decode path
+    (8 rows) of the gated decode step."""
+    cfg = synth.get_config("llama8b", n_layers=3, vocab=8192)
+    L = cfg["n_layers"]
+    lens = [32, 7, 64, 2, 50, 33, 40, 27]
+    gp, gd = np.array([0.6, 1.3, 0.9], dtype=np.float32), np.array([1.1, 0.4, 1.0], dtype=np.float32)
+    tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=5)
+    dev, host = synth.make_weights_on_gpu(cfg, seed=1234)
+    model = pop.Model(cfg, dev)
+    body = [n - 1 for n in lens]
+    bt, n_pages = synth.make_block_table(body, cfg["page_size"], 1)
+    cache = pop.Cache(cfg, n_pages, len(lens), bt.shape[1], fill=float("nan"))
+    cu_full = np.concatenate([[0], np.cumsum(lens)])
+    cu = np.concatenate([[0], np.cumsum(body)]).astype(np.int32)
+    ws = pop.alloc_workspace(cfg, int(cu[-1]), len(lens), bt.shape[1])
+    body_tokens = np.concatenate([tokens[cu_full[b]:cu_full[b + 1] - 1] for b in range(len(lens))])
+    pop.pop_prefill(model, cache, body_tokens, cu, bt, L, ws, mode=pop.MODE_BODY_ONLY, gates=gp)
+    logits = pop.pop_decode_step(model, cache, [int(tokens[cu_full[b + 1] - 1]) for b in range(len(lens))], ws, gates=gd)
+    torch.cuda.synchronize()
+    logits = logits.cpu().numpy()
+    for b, n in enumerate(lens):
+        Kc, Vc, ref = O.pop_prefill(cfg, host, tokens[cu_full[b]:cu_full[b + 1]], L, gates_prefill=gp, gates_decode=gd)
+        assert rel_err(logits[b], ref) <= TOL, (b, rel_err(logits[b], ref))
+        for l in range(L):
+            k = cache.gather(l, 0, bt[b], n).float().cpu().numpy()
+            v = cache.gather(l, 1, bt[b], n).float().cpu().numpy()
+            assert rel_err(k, Kc[l]) <= TOL and rel_err(v, Vc[l]) <= TOL, (b, l)
