@@ -187,6 +187,19 @@ def test_prefill_argument_errors_leave_cache_untouched():
         assert err()
 
 
+def test_prompt_beyond_the_largest_activation_matrix_is_refused():
+    """Maximum size: the bf16 kernels address a matrix with 31-bit byte offsets, so a packed batch whose widest
+    activation matrix (T x d_ffn here) would reach 2 GiB is refused on the host, and one just below passes
+    the size checks as far as the workspace, which is too small here."""
+    cfg = bf16_cfg(d_model=512, d_ffn=14336, n_layers=2)
+    limit = (1 << 31) // (2 * cfg["d_ffn"])                 # first T that reaches 2 GiB: 74899
+    for T, ws_bytes, want, text in ((limit + 1, 1 << 40, -2, "2 GiB"), (limit - 1, 4096, -4, "workspace")):
+        tokens = np.zeros(T, dtype=np.int32)
+        bt, n_pages = synth.make_block_table([T], 16, reserve_pages=1)
+        st, n_live = prefill_status(cfg, tokens=tokens, cu=[0, T], bt=bt, l_keep=1, ws_bytes=ws_bytes, n_pages=n_pages)
+        assert st == want and text in err() and n_live == 0, (T, st, err())
+
+
 def test_decode_step_state_errors():
     cfg = bf16_cfg()
     st, m, c_cfg, keep = fake_model(cfg)
