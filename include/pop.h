@@ -247,8 +247,8 @@ pop_status pop_decode_step_gated(pop_model* m, pop_cache* c, const int32_t* host
  *   dev_workspace  at least pop_generate_workspace_bytes(cfg, T, n_seqs, max_pages_per_seq, max_new_tokens)
  * The block table must assign pages for positions up to len_b + max_new_tokens - 2.  Afterwards the
  * cache holds len_b + max_new_tokens - 1 entries per sequence (the last chosen token is not fed).
- * Errors as pop_prefill, plus POP_EINVAL (max_new_tokens < 1, POP_MODE_BODY_ONLY, eos_token >=
- * vocab) and POP_ENOSPACE (pages for the generated tokens, workspace); all before any launch.
+ * Errors as pop_prefill, plus POP_EINVAL (max_new_tokens < 1, POP_MODE_BODY_ONLY, gates given,
+ * eos_token >= vocab) and POP_ENOSPACE (pages for the generated tokens, workspace); all before any launch.
  */
 size_t pop_generate_workspace_bytes(const pop_config* cfg, int32_t max_tokens, int32_t max_seqs,
                                     int32_t max_pages_per_seq, int32_t max_new_tokens);

@@ -1427,6 +1427,7 @@ pop_status pop_generate(pop_model* m, pop_cache* c, const pop_prefill_args* a, i
   if (max_new_tokens < 1) return fail(POP_EINVAL, "max_new_tokens %d < 1", max_new_tokens);
   if (a->mode != POP_MODE_POP && a->mode != POP_MODE_NO_BOUNDARY)
     return fail(POP_EINVAL, "generation needs the last prompt token's logits (POP_MODE_POP or POP_MODE_NO_BOUNDARY)");
+  if (a->gates) return fail(POP_EINVAL, "virtual gates belong to pop_prefill / pop_decode_step_gated, not to generation");
   const pop_config& cfg = m->cfg;
   if (eos_token >= cfg.vocab) return fail(POP_EINVAL, "eos_token %d outside the vocabulary", eos_token);
   if (!a->cu_seqlens || !a->block_table) return fail(POP_EINVAL, "cu_seqlens / block_table is NULL");

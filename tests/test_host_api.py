@@ -295,6 +295,9 @@ def test_gate_argument_errors():
         assert pop.lib.pop_cache_n_seqs(cache) == 0
         st = pop.lib.pop_decode_step_gated(m, cache, p(tok), 2, fp(bad_gate), FAKE, FAKE, 1 << 34, None)
         assert st == -1 and "gates[2]" in err()
+        a2 = pop.pop_prefill_args(p(tok), p(cu), 2, p(bt_), None, None, 0, 5, 2, None, 0, 0, 0, fp(ones))
+        st = pop.lib.pop_generate(m, cache, C.byref(a2), 4, -1, FAKE, FAKE, FAKE, 1 << 34, None)
+        assert st == -1 and "generation" in err()
         pop.lib.pop_cache_destroy(cache)
         pop.lib.pop_free_model(m)
 
