@@ -26,7 +26,8 @@ pop_status pop_op_rmsnorm(const float* x, const float* gamma, void* out, int32_t
 pop_status pop_op_gemm(const void* A, int64_t lda, const void* W, int64_t ldw, void* out, int64_t ldc,
                        int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t act, pop_stream stream);
 
-/* The same projection with scratch memory that allows a deterministic split of K (few rows, long K: the
+/* The same projection (Sec. 2.1, Attn / FFN blocks; the short prompts of Sec. 4.3, where a projection is
+ * weight streaming) with scratch memory that allows a deterministic split of K (few rows, long K: the
  * projections of short prompts are weight streaming, and more work-groups stream faster).  The library
  * decides whether and how far to split; parts are added in a fixed order, so results do not depend on
  * timing.  epilogue 0, 1 or 3.  dev_scratch DEVICE, 16-byte aligned, scratch_bytes >= 32 M N allows the

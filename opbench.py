@@ -1,15 +1,15 @@
 """Per-kernel micro-benchmarks through the C ABI's single-step entry points (include/pop_ops.h).
 
-    python -m paper_2602_03295_amd.opbench gemm [qkv|o|gate_up|down ...] [--m 2048] [--iters 20]
+    python opbench.py gemm [qkv|o|gate_up|down ...] [--m 2048] [--iters 20]
                                                 [--shape N K] [--vendor]
-    python -m paper_2602_03295_amd.opbench attention [--tokens 8192] [--heads 32] [--kv-heads 8]
+    python opbench.py attention [--tokens 8192] [--heads 32] [--kv-heads 8]
                                                      [--head-dim 128] [--window 0] [--iters 10]
 
 Shapes default to the Llama-3.1-8B projection shapes; `--shape N K` times one plain-store GEMM of
 that size instead, and `--vendor` times the same shapes through torch.matmul (hipBLASLt), without
 the fused epilogues, as the comparison the counter summaries quote.  Inputs are seeded random numbers; the timed
 region is `iters` back-to-back calls between two events on the launch stream.  Also the program that
-the counter summaries under profiles/ were collected on (rocprofv3 --pmc ... -- python3 -m ...).
+the counter summaries under profiles/ were collected on (rocprofv3 --pmc ... -- python3 opbench.py ...).
 """
 import argparse
 import sys
@@ -17,7 +17,7 @@ import sys
 import numpy as np
 import torch
 
-from . import pop
+from paper_2602_03295_amd import pop
 
 GEMM_SHAPES = {  # name: (N, K, epilogue)
     "qkv": (6144, 4096, pop.EPI_STORE_BF16),
@@ -79,7 +79,7 @@ def bench_attention(tokens, hq, hkv, hd, window, iters):
 
 
 def main(argv=None):
-    ap = argparse.ArgumentParser(prog="python -m paper_2602_03295_amd.opbench")
+    ap = argparse.ArgumentParser(prog="python opbench.py")
     sub = ap.add_subparsers(dest="what", required=True)
     g = sub.add_parser("gemm")
     g.add_argument("names", nargs="*", default=list(GEMM_SHAPES))

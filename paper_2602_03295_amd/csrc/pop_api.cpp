@@ -70,6 +70,13 @@ bool layer_is_global(const pop_config& c, int l /*1-based*/) {
 }
 }  // namespace
 
+namespace pop {
+int record_error(int status, const char* msg) {
+  g_last_error = msg ? msg : "";
+  return status;
+}
+}  // namespace pop
+
 struct TimedSpan {
   int kind;
   hipEvent_t start, stop;
@@ -435,15 +442,8 @@ void record_kv_first(pop_cache* c, const pop_prefill_args* a, const PrunePlan& p
 // Projection of the B rows of a decode-style layer.  The GEMV kernel streams every weight row once per row
 // group and is the fastest form for one or a few rows; from kRowsForGemm rows on the tiled MFMA GEMM with
 // its small tiles (and the split of a long K) reads the weights faster than the GEMV kernel's 8-row form.
-constexpr int kRowsForGemmDefault = 5;
-int rows_for_gemm() {
-  static const int v = [] {
-    const char* e = getenv("POP_DECODE_GEMM_ROWS");   // experiments: 0 = never
-    const int n = e ? atoi(e) : kRowsForGemmDefault;
-    return n <= 0 ? 1 << 30 : n;
-  }();
-  return v;
-}
+constexpr int kRowsForGemm = 5;
+constexpr int rows_for_gemm() { return kRowsForGemm; }
 
 // parts_out (optional): the caller can add partial products itself.  If the K range was split, *parts_out receives
 // the number of parts (fp32 [parts][B][N] dense at the split scratch of the workspace) and `out` is not written;

@@ -560,11 +560,13 @@ hipError_t launch_epi(const GemmArgs& g, hipStream_t st) {
   const long long batch = g.batch > 0 ? g.batch : 1;
   const long long cols = EPI == EPI_GLU_BF16 ? 2LL * g.N : g.N;  // W rows consumed
   auto cost = [&](const TileCfg& c) { return tile_cost_us(c, g.M, cols, g.K, batch); };
-  // POP_GEMM_TILE=1..9 forces one configuration (tile-shape experiments); unset or 0 = automatic
-  static const int forced = [] {
-    const char* e = getenv("POP_GEMM_TILE");
-    return e ? atoi(e) : 0;
-  }();
+  // Building with -DPOP_FORCE_GEMM_TILE=1..9 forces one configuration (tile-shape experiments, never the
+  // product build): the choice is a compile-time constant and nothing in the environment can change it.
+#ifdef POP_FORCE_GEMM_TILE
+  constexpr int forced = POP_FORCE_GEMM_TILE;
+#else
+  constexpr int forced = 0;
+#endif
   int pick = forced;
   if (pick < 1 || pick > 9 || (pick == 5 && EPI == EPI_GLU_BF16)) {
     double best = 1e300;
@@ -595,8 +597,7 @@ hipError_t launch_epi(const GemmArgs& g, hipStream_t st) {
   const int tiles_n = (int)((cols + 255) / 256);
   const long long total = (long long)tiles_m * tiles_n * batch;
   const long long rem = total % 256;
-  static const bool no_split = getenv("POP_GEMM_NOSPLIT") != nullptr;
-  if (forced == 0 && !no_split && batch == 1 && total > 256 && rem > 0 && rem <= 128 && g.M > 128) {
+  if (forced == 0 && batch == 1 && total > 256 && rem > 0 && rem <= 128 && g.M > 128) {
     const int tail_cols = (int)((rem + tiles_m - 1) / tiles_m);   // column tiles moved to the second launch
     const int head_cols = tiles_n - tail_cols;
     // only worth it when the second launch fills the chip better than the partial round did
@@ -655,11 +656,12 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 inline int choose_split(const GemmArgs& g) {
   if (!g.splitk_ws || g.batch > 1 || g.W_list || g.epilogue == EPI_GLU_BF16) return 1;
   if (g.M > 512 || g.N % 4 || g.K % BK || (reinterpret_cast<uintptr_t>(g.splitk_ws) & 15)) return 1;
-  // POP_GEMM_SPLITK=S forces S parts where the problem allows it (experiments); unset or 0 = automatic
-  static const int forced = [] {
-    const char* e = getenv("POP_GEMM_SPLITK");
-    return e ? atoi(e) : 0;
-  }();
+  // Building with -DPOP_FORCE_SPLITK=S forces S parts where the problem allows it (experiments only).
+#ifdef POP_FORCE_SPLITK
+  constexpr int forced = POP_FORCE_SPLITK;
+#else
+  constexpr int forced = 0;
+#endif
   auto fits = [&](int S) {
     return g.K % (S * BK) == 0 && g.K / (S * BK) >= 8 && (size_t)S * g.M * g.N * 4 <= g.splitk_ws_bytes;
   };

@@ -10,6 +10,10 @@ namespace pop {
 
 typedef uint16_t bf16_t;  // raw bf16 bits in memory
 
+// Host side: stores `msg` as the calling thread's last error (the text pop_last_error() returns) and returns
+// `status` unchanged.  For the source files of the C ABI other than pop_api.cpp, which owns the record.
+int record_error(int status, const char* msg);
+
 // ---------------------------------------------------------------------------------------------
 // Elementwise / bandwidth-bound steps (pop_elementwise.hip)
 // ---------------------------------------------------------------------------------------------
