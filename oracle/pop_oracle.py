@@ -39,6 +39,13 @@ Readings of points the paper leaves open (each is listed in the design notes as 
     evaluated on have it): if a layer carries "q_norm" / "k_norm" scales [hd], every query / key
     head is RMS-normalised over head_dim with that scale (same eps) before RoPE, in kept layers
     and in the pruned layers' key projection alike.
+  * Optional 8-bit KV cache (not in the paper; cfg["kv_dtype"] == 1): the cache append of Sec. 2.1 stores
+    every entry as the nearest value of the 8-bit floating-point format with 4 exponent bits (bias 7), 3
+    mantissa bits and no infinities (largest finite value 448; "e4m3"), after division by a per-tensor scale
+    (cfg["k_scale"], cfg["v_scale"]); ties go to the even mantissa and magnitudes beyond 448 clamp to 448.
+    Sec. 2.1 lets attention run on the updated cache, so EVERY attention, in the prefill and in decode steps
+    alike, reads the stored (rounded, rescaled) entries, the token's own entry included.  The rotation is
+    applied before the rounding (the stored key is the rotated one).
   * Layer l (1-based) is global iff global_every == 0 or l % global_every == 0; local layers use
     rope_theta_local and the sliding window.
   * The boundary token runs every layer normally: its own K/V in deep layers come from its true
@@ -90,6 +97,29 @@ def glu_act(g: np.ndarray, act: int) -> np.ndarray:
     if act == 1:      # GELU, tanh form
         return 0.5 * g * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (g + 0.044715 * g ** 3)))
     raise ValueError("act")
+
+
+KV_BF16, KV_FP8_E4M3 = 0, 1     # values of cfg["kv_dtype"]
+
+
+def fp8_e4m3(x: np.ndarray) -> np.ndarray:
+    """Nearest value of the 8-bit format with 4 exponent bits (bias 7, so normal binades 2^-6 .. 2^8), 3
+    mantissa bits, subnormals in steps of 2^-9 and no infinities: ties to the even mantissa, magnitudes
+    beyond the largest finite value 448 = 1.75 * 2^8 clamp to it."""
+    a = np.minimum(np.abs(x), 448.0)
+    _, E = np.frexp(a)                           # a = m * 2^E with m in [0.5, 1): the binade is 2^(E-1)
+    e = np.maximum(E - 1, -6)                    # subnormals share the step of the smallest normal binade
+    step = np.ldexp(1.0, e - 3)                  # 8 steps per binade
+    return np.sign(x) * np.rint(a / step) * step
+
+
+def cache_entry(cfg: Dict, k: np.ndarray, v: np.ndarray):
+    """What the cache append of Sec. 2.1 leaves in the cache for a new (k, v): the values themselves, or with
+    an 8-bit cache their rounded, rescaled images."""
+    if cfg.get("kv_dtype", KV_BF16) == KV_FP8_E4M3:
+        ks, vs = float(cfg.get("k_scale", 1.0)), float(cfg.get("v_scale", 1.0))
+        return (fp8_e4m3(k / ks) * ks).astype(k.dtype), (fp8_e4m3(v / vs) * vs).astype(v.dtype)
+    return k, v
 
 
 def is_global_layer(cfg: Dict, l: int) -> bool:
@@ -158,7 +188,7 @@ def project_kv(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray):
         k = rmsnorm(k, _w(lw, "k_norm", dt), cfg["rms_eps"])
     k = rope(k, pos, theta)
     v = (a @ _w(lw, "wv", dt).T).reshape(-1, hkv, hd)
-    return k, v
+    return cache_entry(cfg, k, v)
 
 
 def kept_layer_rows(cfg: Dict, lw: Dict, l: int, x: np.ndarray, pos: np.ndarray,

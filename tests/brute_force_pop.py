@@ -12,7 +12,7 @@ from functools import lru_cache
 
 
 def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_projection=True, boundary=True,
-                    window_kv_writes=False, gates_prefill=None, gates_decode=None):
+                    window_kv_writes=False, gates_prefill=None, gates_decode=None, kv_store=None):
     """Returns (K, V, logits) with K[l][t][head][i] python floats (l 0-based layer index).
     `tokens` may extend beyond the prompt (first n_prompt entries): later tokens are decode steps and,
     like the last prompt token, run every layer in full (Sec. 3.2: decoding keeps the full model).
@@ -24,7 +24,9 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_project
     entry of a pruned token only if the first unpruned token is within the window of it.
     gates_prefill / gates_decode (per layer): the virtual gates of Sec. 3.1 in their stage-aware form
     (Sec. 3.2): a token of the prompt body multiplies both residual branches of layer l by
-    gates_prefill[l-1], the last prompt token and later tokens by gates_decode[l-1]."""
+    gates_prefill[l-1], the last prompt token and later tokens by gates_decode[l-1].
+    kv_store = (store_k, store_v): scalar functions applied to every key / value element as it enters the cache
+    (a cache that keeps rounded entries); every attention then reads the stored values."""
     L, d = cfg["n_layers"], cfg["d_model"]
     Hq, Hkv, hd, f = cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"], cfg["d_ffn"]
     eps = cfg["rms_eps"]
@@ -96,12 +98,17 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_project
         heads = [k[h * hd:(h + 1) * hd] for h in range(Hkv)]
         if "k_norm" in lay[l - 1]:                         # per-head QK-norm, before the rotation
             heads = [norm(hv, lay[l - 1]["k_norm"]) for hv in heads]
-        return tuple(tuple(rot(hv, t, theta)) for hv in heads)
+        heads = [rot(hv, t, theta) for hv in heads]
+        if kv_store is not None:
+            heads = [[kv_store[0](e) for e in hv] for hv in heads]
+        return tuple(tuple(hv) for hv in heads)
 
     @lru_cache(maxsize=None)
     def val(l, t):
         a = norm(x_in(l, t), lay[l - 1]["norm_in"])
         v = matvec(lay[l - 1]["wv"], a)
+        if kv_store is not None:
+            v = [kv_store[1](e) for e in v]
         return tuple(tuple(v[h * hd:(h + 1) * hd]) for h in range(Hkv))
 
     @lru_cache(maxsize=None)
@@ -138,3 +145,25 @@ def brute_force_pop(cfg, W, tokens, l_keep, n_prompt=None, skip=None, kv_project
     V = [[[list(h) for h in val(l, t)] if has_entry(l, t) else None for t in range(N)] for l in range(1, L + 1)]
     logits = matvec(lm, norm(x_in(L + 1, N - 1), fin))
     return K, V, logits
+
+
+def e4m3_table():
+    """Every non-negative finite value of the 8-bit format with 4 exponent bits (bias 7) and 3 mantissa bits
+    whose all-ones code is not a number: code c = 8 e + m stands for m 2^-9 (e = 0) or (1 + m / 8) 2^(e - 7)."""
+    vals = []
+    for c in range(127):               # 0 .. 126; code 127 is the NaN
+        e, m = c >> 3, c & 7
+        vals.append(m * 2.0 ** -9 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7))
+    return vals
+
+
+def e4m3_nearest(x, table=e4m3_table()):
+    """Nearest table value by exhaustive search; a tie goes to the even code (even mantissa); beyond the largest
+    value the largest value."""
+    a = abs(x)
+    best, best_d = 0, abs(a - table[0])
+    for c in range(1, len(table)):
+        dist = abs(a - table[c])
+        if dist < best_d or (dist == best_d and c % 2 == 0):
+            best, best_d = c, dist
+    return math.copysign(table[best], x)
