@@ -81,31 +81,41 @@ def _normal(shape, seed: int, index: int, std: float, as_bf16: bool) -> torch.Te
     return t
 
 
-def make_weights(cfg: Dict, seed: int = 1234, std: float = 0.02) -> Dict:
-    """Random weights, all matrices stored [out, in].  Returns fp32 torch CPU tensors; for a bf16
-    config every value is exactly representable in bf16."""
+def make_layer_weights(cfg: Dict, l: int, seed: int = 1234, std: float = 0.02) -> Dict:
+    """The weights of layer l (0-based) alone, identical to make_weights(...)["layers"][l]: for models whose
+    layers are drawn, used and dropped one at a time."""
     bf = cfg["dtype"] == DTYPE_BF16
     d, hd = cfg["d_model"], cfg["head_dim"]
-    dq, dkv, f, v = cfg["n_q_heads"] * hd, cfg["n_kv_heads"] * hd, cfg["d_ffn"], cfg["vocab"]
+    dq, dkv, f = cfg["n_q_heads"] * hd, cfg["n_kv_heads"] * hd, cfg["d_ffn"]
+    b = 16 * (l + 1)
+    return {
+        "norm_in": torch.ones(d, dtype=torch.float32),
+        "wq": _normal((dq, d), seed, b + 0, std, bf),
+        "wk": _normal((dkv, d), seed, b + 1, std, bf),
+        "wv": _normal((dkv, d), seed, b + 2, std, bf),
+        "wo": _normal((d, dq), seed, b + 3, std, bf),
+        "norm_post": torch.ones(d, dtype=torch.float32),
+        "w_gate": _normal((f, d), seed, b + 4, std, bf),
+        "w_up": _normal((f, d), seed, b + 5, std, bf),
+        "w_down": _normal((d, f), seed, b + 6, std, bf),
+    }
+
+
+def make_weights(cfg: Dict, seed: int = 1234, std: float = 0.02, layers: bool = True) -> Dict:
+    """Random weights, all matrices stored [out, in].  Returns fp32 torch CPU tensors; for a bf16
+    config every value is exactly representable in bf16.  layers=False: embedding, LM head and final norm
+    only (the layers then come from make_layer_weights one at a time)."""
+    bf = cfg["dtype"] == DTYPE_BF16
+    d, v = cfg["d_model"], cfg["vocab"]
     w = {
         "embed": _normal((v, d), seed, 0, std, bf),
         "lm_head": _normal((v, d), seed, 1, std, bf),
         "final_norm": torch.ones(d, dtype=torch.float32),
         "layers": [],
     }
-    for l in range(cfg["n_layers"]):
-        b = 16 * (l + 1)
-        w["layers"].append({
-            "norm_in": torch.ones(d, dtype=torch.float32),
-            "wq": _normal((dq, d), seed, b + 0, std, bf),
-            "wk": _normal((dkv, d), seed, b + 1, std, bf),
-            "wv": _normal((dkv, d), seed, b + 2, std, bf),
-            "wo": _normal((d, dq), seed, b + 3, std, bf),
-            "norm_post": torch.ones(d, dtype=torch.float32),
-            "w_gate": _normal((f, d), seed, b + 4, std, bf),
-            "w_up": _normal((f, d), seed, b + 5, std, bf),
-            "w_down": _normal((d, f), seed, b + 6, std, bf),
-        })
+    if layers:
+        for l in range(cfg["n_layers"]):
+            w["layers"].append(make_layer_weights(cfg, l, seed, std))
     return w
 
 
