@@ -36,6 +36,20 @@ pop_status pop_op_gemm_splitk(const void* A, int64_t lda, const void* W, int64_t
                               int32_t M, int32_t N, int32_t K, int32_t epilogue, void* dev_scratch,
                               size_t scratch_bytes, pop_stream stream);
 
+/* pop_op_gemm_splitk for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the scratch is a fixed array of POP_STATIC_SCRATCH_BYTES
+ * in the library's device image, one copy per GPU, held until the process ends.  Same kernels, same split,
+ * same bits as pop_op_gemm_splitk with a scratch buffer of that size.  The call allocates nothing.
+ * Limit: 32 M N <= POP_STATIC_SCRATCH_BYTES (M N <= 524288, e.g. 64 rows x 8192 columns); POP_ENOSPACE beyond,
+ * before anything is enqueued.  All calls on one GPU share that GPU's array: calls that overlap in time on one
+ * GPU (different streams, different threads) race and must be serialised by the caller.  The array keeps the
+ * last call's partial products; every call overwrites what it reads, so nothing needs clearing.
+ * Other errors as pop_op_gemm_splitk; POP_EHIP if the array's address cannot be obtained. */
+#define POP_STATIC_SCRATCH_BYTES (16u << 20)
+size_t pop_static_scratch_bytes(void);
+pop_status pop_op_gemm_splitk_static(const void* A, int64_t lda, const void* W, int64_t ldw, void* out, int64_t ldc,
+                                     int32_t M, int32_t N, int32_t K, int32_t epilogue, pop_stream stream);
+
 /* Same contraction for M <= 64 rows with the bandwidth-bound kernel of the boundary token
  * (Sec. 3.3, "Boundary Handling"): epilogue 0: out fp32 = C, 1: out fp32 += C, 2: GLU -> bf16.
  * Operands are dense (lda = ldw = K). */

@@ -10,7 +10,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpop.so")
-SOURCES = ["pop_api.cpp", "pop_elementwise.hip", "pop_gemm.hip", "pop_attention.hip", "pop_decode.hip", "pop_f32.hip"]
+SOURCES = ["pop_api.cpp", "pop_elementwise.hip", "pop_gemm.hip", "pop_attention.hip", "pop_decode.hip", "pop_f32.hip",
+           "pop_static_scratch.hip"]
 # Per-file extras.  The attention kernel post-processes its MFMA accumulators with vector ALU ops
 # (softmax, rescaling); keeping them in architectural VGPRs (VGPR-form MFMA) avoids an
 # AGPR<->VGPR copy of every accumulator in every key tile.  The GEMM keeps the default (AGPR

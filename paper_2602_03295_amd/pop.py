@@ -92,6 +92,10 @@ lib.pop_op_gemm.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_vo
                             C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
 lib.pop_op_gemm_splitk.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                                    C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+lib.pop_static_scratch_bytes.argtypes = []
+lib.pop_static_scratch_bytes.restype = C.c_size_t
+lib.pop_op_gemm_splitk_static.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64,
+                                          C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
 lib.pop_op_gemv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                             C.c_int32, C.c_int32, C.c_void_p]
 lib.pop_op_gemv_norm.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
@@ -110,7 +114,7 @@ EXPORTED = ["pop_timing_enable", "pop_timing_read", "pop_last_error", "pop_versi
             "pop_workspace_bytes", "pop_cache_create", "pop_cache_destroy", "pop_cache_n_seqs",
             "pop_cache_seq_lens", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_decode_step_gated", "pop_generate",
             "pop_generate_workspace_bytes", "pop_op_rmsnorm",
-            "pop_op_gemm", "pop_op_gemm_splitk", "pop_op_gemv", "pop_op_gemv_norm", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
+            "pop_op_gemm", "pop_op_gemm_splitk", "pop_op_gemm_splitk_static", "pop_static_scratch_bytes", "pop_op_gemv", "pop_op_gemv_norm", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
 
 
 def _check(status: int) -> None:
@@ -378,6 +382,16 @@ def pop_op_gemm_splitk(A: torch.Tensor, W: torch.Tensor, epilogue: int = EPI_STO
         scratch = torch.empty(max(32 * M * N, 256), dtype=torch.uint8, device=A.device)
     _check(lib.pop_op_gemm_splitk(A.data_ptr(), A.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(), out.stride(0),
                                   M, N, K, epilogue, scratch.data_ptr(), scratch.numel(), _stream(stream)))
+    return out
+
+
+def pop_op_gemm_splitk_static(A: torch.Tensor, W: torch.Tensor, out: torch.Tensor, epilogue: int = EPI_STORE_BF16,
+                              stream=None) -> torch.Tensor:
+    """pop_op_gemm_splitk with the library's built-in scratch array; `out` is the caller's (nothing is allocated)."""
+    M, K = A.shape
+    N = W.shape[0]
+    _check(lib.pop_op_gemm_splitk_static(A.data_ptr(), A.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(),
+                                         out.stride(0), M, N, K, epilogue, _stream(stream)))
     return out
 
 
