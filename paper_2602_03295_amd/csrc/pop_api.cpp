@@ -163,7 +163,7 @@ struct Workspace {
   // int32 meta (one upload per call)
   size_t meta_bytes;
   size_t o_tokens, o_row_src, o_pos, o_slot, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start, o_ta_start2,
-      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_kv_first, o_wl_full, o_wl_tail, o_tr_row, o_tr_pos, o_tr_slot,
+      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_kv_first, o_wl_full, o_wl_tail, o_kvd_full, o_kvd_tail, o_tr_row, o_tr_pos, o_tr_slot,
       o_tr_cu, o_tr_t64_seq, o_tr_t64_start;
   // device buffers
   size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_cs_tail, o_a_multi, o_kv_out;
@@ -207,6 +207,8 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_kv_first = take(4 * (size_t)c.n_layers * B);
   w.o_wl_full = take(8 * (size_t)c.n_layers);
   w.o_wl_tail = take(8 * (size_t)c.n_layers);
+  w.o_kvd_full = take(sizeof(pop::KvDest) * (size_t)c.n_layers);
+  w.o_kvd_tail = take(sizeof(pop::KvDest) * (size_t)c.n_layers);
   w.o_tr_row = take(4 * (size_t)T);
   w.o_tr_pos = take(4 * (size_t)T);
   w.o_tr_slot = take(4 * (size_t)T);
@@ -1080,14 +1082,19 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   {
     const bf16_t** wf = reinterpret_cast<const bf16_t**>(meta.data() + w.o_wl_full);
     const bf16_t** wt = reinterpret_cast<const bf16_t**>(meta.data() + w.o_wl_tail);
+    // where each of these layers' entries go and which RoPE table it uses (device addresses inside the workspace)
+    pop::KvDest* df = reinterpret_cast<pop::KvDest*>(meta.data() + w.o_kvd_full);
+    pop::KvDest* dt = reinterpret_cast<pop::KvDest*>(meta.data() + w.o_kvd_tail);
     for (int l = 1; l <= cfg.n_layers; ++l) {
       if (!plan.pruned[l]) continue;
       const bf16_t* wkv = reinterpret_cast<const bf16_t*>(m->layers[l - 1].wqkv) + (size_t)Dq * d;
       if (plan.window_writes && !layer_is_global(cfg, l)) {
         wt[tail_layers.size()] = wkv;
+        dt[tail_layers.size()] = pop::KvDest{c->k_pool(l - 1), at<float2>(dev_workspace, w.o_cs_tail)};
         tail_layers.push_back(l);
       } else {
         wf[full_layers.size()] = wkv;
+        df[full_layers.size()] = pop::KvDest{c->k_pool(l - 1), at<float2>(dev_workspace, layer_is_global(cfg, l) ? w.o_cs_g : w.o_cs_l)};
         full_layers.push_back(l);
       }
     }
@@ -1235,7 +1242,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   bf16_t* a_multi = at<bf16_t>(ws, w.o_a_multi);
   bf16_t* kv_out = at<bf16_t>(ws, w.o_kv_out);
   auto kv_only_layers = [&](const std::vector<int>& layers, int i0, int i1, const bf16_t* const* d_wlist,
-                            bool tail) -> pop_status {
+                            const pop::KvDest* d_dest, bool tail) -> pop_status {
     const int rows = tail ? tr.n : T;
     if (rows <= 0) return POP_OK;
     pop::RopeWriteArgs rk = rw;
@@ -1260,10 +1267,24 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       g.M = rows; g.N = 2 * Dkv; g.K = d; g.epilogue = pop::EPI_STORE_BF16;
       g.batch = n; g.strideA = (long long)rows * d; g.strideC = (long long)rows * 2 * Dkv;
       g.W_list = d_wlist + c0;
+      // Straight into the paged cache (RoPE and the page scatter in the GEMM's epilogue) when the layers of the
+      // chunk have no per-head key norm (that needs a head's sum of squares first) and there are enough rows for
+      // the 256-row tiles of that epilogue to fill the chip; otherwise through kv_out and the append kernel.
+      bool fused = pop::gemm_kv_cache_supported(cfg.n_kv_heads, hd) &&
+                   (long long)((rows + 255) / 256) * ((2 * Dkv + 255) / 256) * n >= 128;
+      for (int j = 0; j < n; ++j) fused = fused && m->layers[layers[c0 + j] - 1].k_norm == nullptr;
+      if (fused) {
+        g.epilogue = pop::EPI_KV_CACHE;
+        g.kv_dest = d_dest + c0;
+        g.kv_slot = rk.slot;
+        g.kv_heads = cfg.n_kv_heads; g.kv_hd = hd; g.kv_page_size = P;
+        g.kv_pool_stride = (int64_t)c->pool_stride();
+      }
       {
         StepTimer tm(m, st, POP_STEP_KV_ONLY_GEMM);
         if (pop_status s = gemm_or_fail(g, st, "K/V-only")) return s;
       }
+      if (fused) continue;
       StepTimer tmw(m, st, POP_STEP_KV_ONLY_WRITE);
       for (int j = 0; j < n; ++j) {
         const int l = layers[c0 + j];
@@ -1288,9 +1309,12 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     };
     int i0, i1;
     range(full_layers, i0, i1);
-    if (pop_status s = kv_only_layers(full_layers, i0, i1, at<const bf16_t*>(ws, w.o_wl_full), false)) return s;
+    if (pop_status s = kv_only_layers(full_layers, i0, i1, at<const bf16_t*>(ws, w.o_wl_full),
+                                      at<const pop::KvDest>(ws, w.o_kvd_full), false))
+      return s;
     range(tail_layers, i0, i1);
-    return kv_only_layers(tail_layers, i0, i1, at<const bf16_t*>(ws, w.o_wl_tail), true);
+    return kv_only_layers(tail_layers, i0, i1, at<const bf16_t*>(ws, w.o_wl_tail),
+                          at<const pop::KvDest>(ws, w.o_kvd_tail), true);
   };
 
   // ---- layers in order.  The boundary tokens (Sec. 3.3, boundary handling) are rows of h through kept

@@ -437,13 +437,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnPrefillArgs a, fl
 template <int HD>
 hipError_t launch_hd(const AttnPrefillArgs& a, hipStream_t st) {
   constexpr int smem = (HD <= 128 ? 3 : 2) * (BKV * HD * 2 + HD * BKV * 2);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_prefill_kernel<HD>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per head size; the initialisation of a function-local static is thread-safe
+  static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_prefill_kernel<HD>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (attr_err != hipSuccess) return attr_err;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
   hipLaunchKernelGGL((attn_prefill_kernel<HD>), dim3(a.n_tiles, a.n_q_heads), dim3(256), smem, st, a, scale_log2);
   return hipGetLastError();

@@ -58,7 +58,18 @@ struct GemmParams {
   long long strideA, strideC, strideW;
   const bf16_t* const* W_list;
   float scale;           // EPI_ADD_F32: out += scale * C
+  // KV-cache epilogues
+  const KvDest* kv_dest;
+  const int32_t* kv_slot;
+  int kv_heads, kv_page;
+  long long kv_pool_stride;
 };
+
+// Template values of the KV-cache epilogue (EPI_KV_CACHE of the interface), one per head_dim: the offset between
+// the two halves of a head decides which accumulator registers are RoPE partners, so it must be a constant.
+constexpr int EPI_KV64 = 5, EPI_KV128 = 6, EPI_KV256 = 7;
+constexpr bool epi_is_kv(int e) { return e == EPI_KV64 || e == EPI_KV128 || e == EPI_KV256; }
+constexpr int epi_kv_hd(int e) { return e == EPI_KV64 ? 64 : e == EPI_KV128 ? 128 : 256; }
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
@@ -413,6 +424,60 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
           }
         }
       }
+  } else if (epi_is_kv(EPI)) {
+   if constexpr (epi_is_kv(EPI)) {   // (the indices below only exist for these instantiations)
+    // Independent KV projections (Sec. 3.3) straight into the paged cache.  The wave tile holds whole heads
+    // (WTN is a multiple of the head size): column block i of a head and block i + HB are the two halves of the
+    // same rotation pairs, in the same lane and register slot.  K columns are rotated in fp32 on the accumulators
+    // and rounded to bf16 once; V columns are rounded and stored.  Rows outer, blocks inner, low half then high
+    // half: the 8-byte stores of the four lanes that share a row complete 32 bytes, the blocks a 128-byte line.
+    constexpr int HD = epi_kv_hd(EPI), HB = HD / 32, HPW = WTN / HD;   // HB: 16-column blocks in half a head
+    static_assert(WTN % HD == 0, "a wave tile must hold whole heads");
+    const int Dkv = p.N >> 1;
+    const int n_wave = n0 + wn * WTN;                  // first column of the wave tile (wave-uniform)
+    if (n_wave < p.N) {
+      const bool is_k = n_wave < Dkv;                  // Dkv is a multiple of WTN (checked by the launcher)
+      const int head0 = (is_k ? n_wave : n_wave - Dkv) / HD;
+      const KvDest dst = p.kv_dest[z];
+      bf16_t* pool = dst.k_pool + (is_k ? 0 : p.kv_pool_stride);
+      const int P = p.kv_page;
+#pragma unroll
+      for (int j = 0; j < MB; ++j) {
+        const int m = m_lane + j * 16;
+        if (m >= p.M) continue;
+        const int s = p.kv_slot[m];
+        bf16_t* row = pool + (((long long)(s / P) * p.kv_heads + head0) * P + (s % P)) * HD + frag_hi * 4;
+        const float4* csr = reinterpret_cast<const float4*>(dst.cs + (long long)m * (HD / 2) + frag_hi * 4);
+#pragma unroll
+        for (int hw = 0; hw < HPW; ++hw) {
+          bf16_t* hrow = row + (long long)hw * P * HD;
+#pragma unroll
+          for (int ib = 0; ib < HB; ++ib) {
+            const int lo = hw * 2 * HB + ib, hi = lo + HB;
+            float a[4], b[4];
+            if (is_k) {
+              // (cos, sin) of the four pairs this lane holds: dims ib*16 + frag_hi*4 .. +3
+              const float4 c01 = csr[ib * 8], c23 = csr[ib * 8 + 1];
+              const float cc[4] = {c01.x, c01.z, c23.x, c23.z}, sn[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                a[e] = acc[lo][j][e] * cc[e] - acc[hi][j][e] * sn[e];
+                b[e] = acc[hi][j][e] * cc[e] + acc[lo][j][e] * sn[e];
+              }
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) { a[e] = acc[lo][j][e]; b[e] = acc[hi][j][e]; }
+            }
+            uint2 pa, pb;
+            pa.x = pack_bf16x2(a[0], a[1]); pa.y = pack_bf16x2(a[2], a[3]);
+            pb.x = pack_bf16x2(b[0], b[1]); pb.y = pack_bf16x2(b[2], b[3]);
+            *reinterpret_cast<uint2*>(hrow + ib * 16) = pa;
+            *reinterpret_cast<uint2*>(hrow + HD / 2 + ib * 16) = pb;
+          }
+        }
+      }
+    }
+   }
   } else if (EPI == EPI_ADD_F32) {
     // out += C.  The old values are requested sixteen 16x16 blocks at a time, without branches (a lane whose
     // four columns are not all inside reads the first element of the matrix instead), so that the loads
@@ -504,22 +569,23 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_
   p.lda = (int)g.lda; p.ldw = (int)g.ldw; p.ldc = (int)g.ldc;
   p.act = g.act;
   p.scale = residual_scale(g);
+  p.kv_dest = g.kv_dest; p.kv_slot = g.kv_slot; p.kv_heads = g.kv_heads; p.kv_page = g.kv_page_size;
+  p.kv_pool_stride = g.kv_pool_stride;
   p.tiles_m = (g.M + BM - 1) / BM;
   p.tiles_n = n_tiles >= 0 ? n_tiles : (g.N + BN_OUT - 1) / BN_OUT;
   p.n_tile0 = n_tile0;
   if (p.tiles_n <= 0) return hipSuccess;
   p.strideA = g.strideA; p.strideC = g.strideC; p.strideW = g.W_list ? 0 : g.strideW;
   p.W_list = g.batch > 1 || g.W_list ? g.W_list : nullptr;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
+  // once per instantiation; the initialisation of a function-local static is thread-safe
+  static const hipError_t attr_err = [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI, true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI, false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WGM, WGN, STAGES, EPI, false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  }();
+  if (attr_err != hipSuccess) return attr_err;
   const int total = p.tiles_m * p.tiles_n;
   const int grid = ((total + 7) / 8) * 8;
   const dim3 grid3(grid, 1, g.batch > 0 ? g.batch : 1), block3(64 * WGM * WGN);
@@ -654,7 +720,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // are compute bound.  Hence: split only long K with few rows, as far as the scratch allows, and any K when
 // the rows fit one 64-row tile and the launch would leave CUs idle.
 inline int choose_split(const GemmArgs& g) {
-  if (!g.splitk_ws || g.batch > 1 || g.W_list || g.epilogue == EPI_GLU_BF16) return 1;
+  if (!g.splitk_ws || g.batch > 1 || g.W_list || g.epilogue == EPI_GLU_BF16 || g.epilogue == EPI_KV_CACHE) return 1;
   if (g.M > 512 || g.N % 4 || g.K % BK || (reinterpret_cast<uintptr_t>(g.splitk_ws) & 15)) return 1;
   // Building with -DPOP_FORCE_SPLITK=S forces S parts where the problem allows it (experiments only).
 #ifdef POP_FORCE_SPLITK
@@ -690,7 +756,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.K <= 0 || g.K % 8 || g.lda % 8 || g.ldw % 8 || g.ldc % 4) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.W) |
-       reinterpret_cast<uintptr_t>(g.out)) & 15)
+       (g.epilogue == EPI_KV_CACHE ? 0 : reinterpret_cast<uintptr_t>(g.out))) & 15)
     return hipErrorInvalidValue;
   const long long w_rows = g.epilogue == EPI_GLU_BF16 ? 2LL * g.N : g.N;
   if (((long long)(g.M - 1) * g.lda + g.K) * 2 >= (1LL << 31) || ((w_rows - 1) * g.ldw + g.K) * 2 >= (1LL << 31))
@@ -735,8 +801,23 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
     case EPI_GLU_BF16: return launch_epi<EPI_GLU_BF16>(g, st);
     case EPI_STORE_F32: return launch_epi<EPI_STORE_F32>(g, st);
     case EPI_STORE_F16: return launch_epi<EPI_STORE_F16>(g, st);
+    case EPI_KV_CACHE:
+      // 256-column tiles whose wave tiles hold whole heads: 2 x 2 waves of 128 x 128 for head sizes 64 and 128,
+      // 4 x 1 waves of 64 x 256 for head size 256
+      if (!gemm_kv_cache_supported(g.kv_heads, g.kv_hd) || g.N != 2 * g.kv_heads * g.kv_hd || !g.kv_dest ||
+          !g.kv_slot || g.kv_page_size < 1)
+        return hipErrorInvalidValue;
+      if (g.kv_hd == 64) return launch_cfg<256, 256, 2, 2, 2, EPI_KV64>(g, st);
+      if (g.kv_hd == 128) return launch_cfg<256, 256, 2, 2, 2, EPI_KV128>(g, st);
+      return launch_cfg<256, 256, 4, 1, 2, EPI_KV256>(g, st);
   }
   return hipErrorInvalidValue;
+}
+
+bool gemm_kv_cache_supported(int n_kv_heads, int hd) {
+  if (hd != 64 && hd != 128 && hd != 256) return false;
+  const int wtn = hd == 256 ? 256 : 128;            // columns of a wave tile in the configurations above
+  return n_kv_heads > 0 && ((long long)n_kv_heads * hd) % wtn == 0;
 }
 
 }  // namespace pop

@@ -82,7 +82,17 @@ enum GemmEpilogue {
   EPI_ADD_F32 = 1,     // out fp32 [M, ldc]: out += C           (residual update)
   EPI_GLU_BF16 = 2,    // W is [2N, K] (gate rows then up rows); out bf16 [M, ldc] = act(gate) * up
   EPI_STORE_F32 = 3,   // out fp32 [M, ldc] = C
-  EPI_STORE_F16 = 4    // out fp16 [M, ldc] = C (saturating), for outputs that stay inside the library
+  EPI_STORE_F16 = 4,   // out fp16 [M, ldc] = C (saturating), for outputs that stay inside the library
+  // The independent KV projections of Sec. 3.3 written straight into the paged cache: W is [2 Dkv, K] (a layer's
+  // W^K rows, then its W^V rows, N = 2 Dkv); columns < Dkv are rotated (RoPE on the fp32 accumulators, the two
+  // halves of a head are registers of the same lane) and stored as bf16 at the row's slot of the K pool, the
+  // others at the same slot of the V pool.  Nothing else is written (out, ldc, strideC are ignored).
+  EPI_KV_CACHE = 5
+};
+// Per batch entry (= pruned layer) of an EPI_KV_CACHE launch: where its entries go and which RoPE table it uses.
+struct KvDest {
+  bf16_t* k_pool;      // the layer's K pool [page][Hkv][P][hd]; its V pool follows kv_pool_stride elements later
+  const float2* cs;    // [M, hd/2] (cos, sin) of every row's position with the layer's RoPE base
 };
 struct GemmArgs {
   const bf16_t* A;   // [M, lda]
@@ -111,7 +121,15 @@ struct GemmArgs {
   // out += C.  A caller that adds partial products itself (partials_only) applies the scale there.
   bool scaled;
   float scale;
+  // EPI_KV_CACHE only
+  const KvDest* kv_dest;     // DEVICE [batch]
+  const int32_t* kv_slot;    // DEVICE [M] cache slot of every row
+  int kv_heads, kv_hd, kv_page_size;
+  int64_t kv_pool_stride;    // elements from a layer's K pool to its V pool
 };
+// Whether launch_gemm can run EPI_KV_CACHE for this shape (otherwise the caller projects to a scratch matrix
+// and appends with launch_rope_write): head_dim 64 / 128 / 256 and whole heads per wave tile.
+bool gemm_kv_cache_supported(int n_kv_heads, int hd);
 inline float residual_scale(const GemmArgs& g) { return g.scaled ? g.scale : 1.f; }
 // Returns hipSuccess or the launch error.  Requirements: K % 8 == 0, lda/ldw % 8 == 0,
 // A/W 16-byte aligned, ldc % 4 == 0, and every operand below 2^31 bytes.
