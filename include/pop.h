@@ -80,7 +80,18 @@ typedef struct {
   int32_t sliding_window;  /* 0 = none; W > 0: a local layer's row t sees positions t-W+1 .. t     */
   int32_t global_every;    /* 0 = every layer global; g > 0: 1-based layer l is global iff l%g==0  */
   int32_t page_size;       /* tokens per KV-cache page, a power of two (16)                        */
+  /* Optional 8-bit KV cache (a family extra, not part of the method; all zero = bf16 entries).           */
+  int32_t kv_dtype;        /* POP_KV_BF16 or POP_KV_FP8_E4M3                                       */
+  float k_scale, v_scale;  /* POP_KV_FP8_E4M3: an entry x is stored as the e4m3 code of x / scale and
+                              read back as code value * scale; finite and > 0 (ignored for bf16)    */
 } pop_config;
+/* POP_KV_FP8_E4M3: the cache append of Sec. 2.1 stores every K/V element as the nearest value of the 8-bit
+ * floating-point format with 4 exponent bits (bias 7), 3 mantissa bits and no infinities (largest finite value
+ * 448), ties to the even mantissa, magnitudes beyond 448 clamped to 448; keys are rotated first.  Attention runs
+ * on the updated cache (Sec. 2.1): EVERY attention, in the prefill as in decode steps, reads the stored entries,
+ * a token's own entry included, so the boundary token's pass through the kept layers inside the prefill stays
+ * identical to its decode step.  With POP_DTYPE_F32 the cache keeps fp32 entries that hold the rounded values. */
+enum { POP_KV_BF16 = 0, POP_KV_FP8_E4M3 = 1 };
 
 typedef struct {
   const void* norm_in;   /* DEVICE fp32 [d]                 input norm scale (the LN of Sec. 2.1)  */
@@ -107,7 +118,8 @@ typedef struct {
 /*
  * Validates the shape and records the weight pointers (borrowed: they must outlive the model).
  * Host-only, enqueues nothing, allocates no device memory.
- * Errors: POP_EINVAL (NULL, non-positive sizes, Hq % Hkv != 0), POP_ESHAPE (head_dim not in
+ * Errors: POP_EINVAL (NULL, non-positive sizes, Hq % Hkv != 0, unknown kv_dtype, bad k_scale / v_scale),
+ * POP_ESHAPE (head_dim not in
  * {64,128,256}, d_model or d_ffn not a multiple of 8, page_size not a power of two in 1..256, a bf16
  * weight matrix of 2 GiB or more), POP_EALIGN; POP_EINVAL also if a layer has only one of q_norm / k_norm.
  */
@@ -115,7 +127,8 @@ pop_status pop_load_weights(const pop_config* cfg, const pop_weights* w, pop_mod
 void pop_free_model(pop_model* m);
 
 /*
- * KV cache (Sec. 2.1, cache append) stored in pages.  Device layout, bf16:
+ * KV cache (Sec. 2.1, cache append) stored in pages.  Device layout, bf16 (one byte per element, the e4m3 code,
+ * with POP_KV_FP8_E4M3):
  *     pool[layer][kv][page][kv_head][slot_in_page][head_dim],   kv = 0 for K, 1 for V.
  * Entry t of sequence b lives in page block_table[b][t / P] at offset t % P.
  */
@@ -151,7 +164,12 @@ typedef struct {
   int32_t n_seqs;
   const int32_t* block_table;  /* HOST [n_seqs][max_pages_per_seq] page ids, negative = unassigned;
                                   must cover every position the sequences will reach, including
-                                  later decode steps                                                */
+                                  later decode steps.  The table is the CALLER's: which page a sequence
+                                  gets is the serving engine's allocation policy (free lists, prefix
+                                  sharing, eviction), not part of the method, so the library exports no
+                                  allocator and no call that hands a table out; it validates the table it
+                                  is given (pop_slot_map's rules), copies it into the cache object, and
+                                  reports the lengths it has recorded through pop_cache_seq_lens        */
   const void* embeds;          /* DEVICE bf16 [sum of counts, d] or NULL: rows that replace the
                                   embedding lookup (e.g. visual tokens fed as hidden states)        */
   const int32_t* embed_ranges; /* HOST [n_ranges][3] = (seq, first_pos, count), rows of `embeds`

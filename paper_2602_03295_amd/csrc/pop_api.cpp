@@ -62,7 +62,28 @@ pop_status check_config(const pop_config* c) {
   if (c->sliding_window < 0 || c->global_every < 0) return fail(POP_EINVAL, "negative sliding_window / global_every");
   if (c->sliding_window > 0 && c->global_every > 0 && !(c->rope_theta_local > 0.f))
     return fail(POP_EINVAL, "bad rope_theta_local");
+  if (c->kv_dtype != POP_KV_BF16 && c->kv_dtype != POP_KV_FP8_E4M3) return fail(POP_EINVAL, "unknown kv_dtype %d", c->kv_dtype);
+  if (c->kv_dtype == POP_KV_FP8_E4M3 &&
+      !(c->k_scale > 0.f && c->v_scale > 0.f && std::isfinite(c->k_scale) && std::isfinite(c->v_scale)))
+    return fail(POP_EINVAL, "k_scale / v_scale of an 8-bit cache must be finite and positive");
   return POP_OK;
+}
+
+// Bytes of one cache element: the fp32 checking path keeps fp32 entries (holding the rounded values when the
+// cache is 8-bit), the bf16 path bf16 entries or one-byte e4m3 codes.
+size_t cache_elem_bytes(const pop_config& c) {
+  if (c.dtype == POP_DTYPE_F32) return sizeof(float);
+  return c.kv_dtype == POP_KV_FP8_E4M3 ? 1 : sizeof(bf16_t);
+}
+// How the kernels store and read cache entries.
+pop::KvQuant kv_quant(const pop_config& c) {
+  pop::KvQuant q{};
+  q.fp8 = c.kv_dtype == POP_KV_FP8_E4M3;
+  q.k_scale = q.fp8 ? c.k_scale : 1.f;
+  q.v_scale = q.fp8 ? c.v_scale : 1.f;
+  q.k_inv = 1.f / q.k_scale;
+  q.v_inv = 1.f / q.v_scale;
+  return q;
 }
 
 bool layer_is_global(const pop_config& c, int l /*1-based*/) {
@@ -148,8 +169,14 @@ struct pop_cache {
   size_t pool_stride() const {
     return (size_t)n_pages * cfg.n_kv_heads * cfg.page_size * cfg.head_dim;
   }
-  bf16_t* k_pool(int l0) const { return pool + (size_t)l0 * layer_stride(); }
-  bf16_t* v_pool(int l0) const { return k_pool(l0) + pool_stride(); }
+  // (typed as bf16_t* for the kernels' argument lists; with an 8-bit cache the address is that of one-byte codes)
+  size_t esz() const { return cache_elem_bytes(cfg); }
+  bf16_t* k_pool(int l0) const {
+    return reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(pool) + (size_t)l0 * layer_stride() * esz());
+  }
+  bf16_t* v_pool(int l0) const {
+    return reinterpret_cast<bf16_t*>(reinterpret_cast<char*>(k_pool(l0)) + pool_stride() * esz());
+  }
   float* k_pool_f32(int l0) const { return reinterpret_cast<float*>(pool) + (size_t)l0 * layer_stride(); }
   float* v_pool_f32(int l0) const { return k_pool_f32(l0) + pool_stride(); }
 };
@@ -166,7 +193,7 @@ struct Workspace {
       o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_kv_first, o_wl_full, o_wl_tail, o_kvd_full, o_kvd_tail, o_tr_row, o_tr_pos, o_tr_slot,
       o_tr_cu, o_tr_t64_seq, o_tr_t64_start;
   // device buffers
-  size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_cs_tail, o_a_multi, o_kv_out;
+  size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_cs_tail, o_a_multi, o_kv_out, o_ss_parts;
   size_t o_xb, o_ab, o_qkvb, o_qb, o_attnb, o_ub, o_part, o_splitk;
   size_t splitk_bytes;
   size_t total;
@@ -228,6 +255,8 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   const size_t rc = std::min(kKvChunk, c.n_layers);
   w.o_a_multi = take(2 * rc * (size_t)T * d);
   w.o_kv_out = take(2 * rc * (size_t)T * 2 * Dkv);
+  // partial sums of squares of the rows of h per 64-column group (normalisation folded into the projections)
+  w.o_ss_parts = take(4 * (size_t)T * ((d + 63) / 64));
   w.o_xb = take(4 * (size_t)B * d);
   w.o_ab = take(2 * (size_t)B * std::max(d, Dq));
   w.o_qkvb = take(4 * (size_t)B * Dqkv);
@@ -545,7 +574,7 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   pop::launch_rope_append(qkv_parts > 1 ? at<float>(x.ws, x.w->o_splitk) : qkvb, Dqkv, qb, c.n_q_heads, c.n_kv_heads, c.head_dim, pos, slot,
                           glob ? (double)c.rope_theta : (double)c.rope_theta_local, x.c->k_pool(l - 1),
                           x.c->v_pool(l - 1), c.page_size, B, x.st, (const float*)lw.q_norm, (const float*)lw.k_norm,
-                          c.rms_eps, qkv_parts, (size_t)B * Dqkv);
+                          c.rms_eps, qkv_parts, (size_t)B * Dqkv, kv_quant(c));
   pop::AttnDecodeArgs ad{};
   ad.q = qb;
   ad.k_pool = x.c->k_pool(l - 1);
@@ -565,6 +594,7 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   ad.max_len = max_len;
   ad.part = at<float>(x.ws, x.w->o_part);
   ad.out = attnb;
+  ad.kvq = kv_quant(c);
   pop::launch_attention_decode(ad, x.st);
   if (pop_status s = residual_few_rows_projection(x, attnb, lw.wo, B, d, Dq, (const float*)lw.norm_post, x.gate(l))) return s;
   if (pop_status s = normed_few_rows_projection(x, xb, (const float*)lw.norm_post, ab, lw.w_gate_up, ub, B, f, d, f,
@@ -660,7 +690,7 @@ pop_status layer_f32(const CtxF32& x, int l /*1-based*/, int rows, float* xh, fl
   F::launch_rope_write(qkv, Dqkv, 0, Dq, Dq + Dkv, c.n_q_heads, c.n_kv_heads, hd, pos, slot,
                        glob ? (double)c.rope_theta : (double)c.rope_theta_local, x.c->k_pool_f32(l - 1),
                        x.c->v_pool_f32(l - 1), c.page_size, rows, x.st, (const float*)lw.q_norm, (const float*)lw.k_norm,
-                       c.rms_eps);
+                       c.rms_eps, kv_quant(c));
   hipError_t e = F::launch_attention(qkv, Dqkv, 0, attn, row_seq, pos, x.c->k_pool_f32(l - 1), x.c->v_pool_f32(l - 1),
                                      at<int32_t>(x.ws, x.w->o_bt), x.c->max_pages, c.page_size,
                                      glob ? 0 : c.sliding_window,
@@ -781,7 +811,7 @@ pop_status prefill_f32(pop_model* m, pop_cache* c, const pop_prefill_args* a, co
                              tail ? at<int32_t>(ws, w.o_tr_pos) : d_pos, tail ? at<int32_t>(ws, w.o_tr_slot) : d_slot,
                              layer_is_global(cfg, j) ? (double)cfg.rope_theta : (double)cfg.rope_theta_local,
                              c->k_pool_f32(j - 1), c->v_pool_f32(j - 1), cfg.page_size, rows, st, nullptr,
-                             (const float*)lw.k_norm, cfg.rms_eps);
+                             (const float*)lw.k_norm, cfg.rms_eps, kv_quant(cfg));
       }
     POP_HIP(hipGetLastError());
     if (boundary) {
@@ -931,8 +961,8 @@ pop_status pop_timing_read(pop_model* m, float* ms_out, int32_t* launches_out) {
 size_t pop_cache_bytes(const pop_config* cfg, int32_t n_pages) {
   if (!cfg || n_pages < 1 || cfg->n_layers < 1 || cfg->n_kv_heads < 1 || cfg->head_dim < 1 || cfg->page_size < 1)
     return 0;
-  const size_t esz = cfg->dtype == POP_DTYPE_F32 ? sizeof(float) : sizeof(bf16_t);
-  return (size_t)cfg->n_layers * 2 * n_pages * cfg->n_kv_heads * cfg->page_size * cfg->head_dim * esz;
+  if (cfg->kv_dtype != POP_KV_BF16 && cfg->kv_dtype != POP_KV_FP8_E4M3) return 0;
+  return (size_t)cfg->n_layers * 2 * n_pages * cfg->n_kv_heads * cfg->page_size * cfg->head_dim * cache_elem_bytes(*cfg);
 }
 
 size_t pop_workspace_bytes(const pop_config* cfg, int32_t max_tokens, int32_t max_seqs, int32_t max_pages_per_seq) {
@@ -1165,17 +1195,40 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   rw.tile_seq = at<int32_t>(ws, w.o_t64_seq);
   rw.tile_start = at<int32_t>(ws, w.o_t64_start);
   rw.n_tiles = n_t64;
+  rw.kvq = kv_quant(cfg);
 
   // ---- a kept layer over all given rows (Sec. 2.1)
+  // The two normalisations of a layer are folded into the projections around them when there are enough rows for
+  // the one-pass GEMM epilogues (a split of K is only used at <= 512 rows): the O and down projections store, next
+  // to the updated h, its rows times the following norm's scale as bf16 (into abuf) and partial sums of squares;
+  // the QKV and gate|up projections read those rows and multiply their result rows by rstd.  folded_gamma is the
+  // norm scale abuf / ss_parts currently stand for (nullptr: they do not hold h).
+  const bool fold_norms = d % 256 == 0 && T > 512;   // (the partial sums are read four at a time)
+  float* ss_parts = at<float>(ws, w.o_ss_parts);
+  const float* folded_gamma = nullptr;
   auto kept_layer = [&](int l) -> pop_status {
     const pop_layer_weights& lw = m->layers[l - 1];
     const bool glob = layer_is_global(cfg, l);
-    {
-      StepTimer tm(m, st, POP_STEP_NORM);
-      pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_in, abuf, nullptr, T, d, cfg.rms_eps, st);
-    }
     pop::GemmArgs g{};
     g.batch = 1;
+    auto normed_input = [&](const float* gamma) {   // abuf := the projection's input; sets g.a_parts if folded
+      if (fold_norms && folded_gamma == gamma) {
+        g.a_parts = ss_parts; g.a_nparts = d / 64; g.a_eps = cfg.rms_eps;
+      } else {
+        StepTimer tm(m, st, POP_STEP_NORM);
+        pop::launch_rmsnorm(h, nullptr, nullptr, gamma, abuf, nullptr, T, d, cfg.rms_eps, st);
+        g.a_parts = nullptr;
+      }
+      folded_gamma = nullptr;   // abuf is about to be consumed
+    };
+    auto fold_next = [&](const float* gamma) {      // the residual projection about to run also prepares `gamma`
+      g.nrm_gamma = nullptr;
+      if (fold_norms && gamma) {
+        g.nrm_gamma = gamma; g.nrm_out = abuf; g.nrm_parts = ss_parts;
+        folded_gamma = gamma;
+      }
+    };
+    normed_input((const float*)lw.norm_in);
     g.A = abuf; g.lda = d; g.W = (const bf16_t*)lw.wqkv; g.ldw = d; g.out = qkv; g.ldc = Dqkv;
     // q, k, v leave the GEMM as fp16: they only feed the RoPE/append and attention kernels, and fp16
     // keeps three more mantissa bits than bf16 for the score contraction (the cache itself is bf16)
@@ -1186,6 +1239,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       StepTimer tm(m, st, POP_STEP_QKV_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "QKV")) return s;
     }
+    g.a_parts = nullptr;
     rw.qkv = qkv; rw.ld = Dqkv; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
     rw.cs = glob ? cs_g : cs_l;
     rw.q_gamma = (const float*)lw.q_norm; rw.k_gamma = (const float*)lw.k_norm; rw.qk_eps = cfg.rms_eps;
@@ -1212,23 +1266,25 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     g.A = attn; g.lda = Dq; g.W = (const bf16_t*)lw.wo; g.ldw = Dq; g.out = h; g.ldc = d;
     g.M = T; g.N = d; g.K = Dq; g.epilogue = pop::EPI_ADD_F32;
     g.scaled = a->gates != nullptr; g.scale = a->gates ? a->gates[l - 1] : 1.f;   // virtual gate of the layer
+    fold_next((const float*)lw.norm_post);
     {
       StepTimer tm(m, st, POP_STEP_O_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "O")) return s;
     }
-    {
-      StepTimer tm(m, st, POP_STEP_NORM);
-      pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_post, abuf, nullptr, T, d, cfg.rms_eps, st);
-    }
+    g.nrm_gamma = nullptr;
+    normed_input((const float*)lw.norm_post);
     g.A = abuf; g.lda = d; g.W = (const bf16_t*)lw.w_gate_up; g.ldw = d; g.out = u; g.ldc = f;
     g.M = T; g.N = f; g.K = d; g.epilogue = pop::EPI_GLU_BF16; g.act = cfg.act;
     {
       StepTimer tm(m, st, POP_STEP_GATE_UP_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "gate/up")) return s;
     }
+    g.a_parts = nullptr;
     g.A = u; g.lda = f; g.W = (const bf16_t*)lw.w_down; g.ldw = f; g.out = h; g.ldc = d;
     g.M = T; g.N = d; g.K = f; g.epilogue = pop::EPI_ADD_F32;
     g.scaled = a->gates != nullptr; g.scale = a->gates ? a->gates[l - 1] : 1.f;
+    // if another kept layer follows directly, its input norm is prepared here
+    fold_next(l < cfg.n_layers && !plan.pruned[l + 1] ? (const float*)m->layers[l].norm_in : nullptr);
     {
       StepTimer tm(m, st, POP_STEP_DOWN_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "down")) return s;
@@ -1271,7 +1327,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       // chunk have no per-head key norm (that needs a head's sum of squares first) and there are enough rows for
       // the 256-row tiles of that epilogue to fill the chip; otherwise through kv_out and the append kernel.
       bool fused = pop::gemm_kv_cache_supported(cfg.n_kv_heads, hd) &&
-                   (long long)((rows + 255) / 256) * ((2 * Dkv + 255) / 256) * n >= 128;
+                   (long long)((rows + 255) / 256) * ((2 * Dkv + 255) / 256) * n >= 64;
       for (int j = 0; j < n; ++j) fused = fused && m->layers[layers[c0 + j] - 1].k_norm == nullptr;
       if (fused) {
         g.epilogue = pop::EPI_KV_CACHE;
@@ -1279,6 +1335,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
         g.kv_slot = rk.slot;
         g.kv_heads = cfg.n_kv_heads; g.kv_hd = hd; g.kv_page_size = P;
         g.kv_pool_stride = (int64_t)c->pool_stride();
+        g.kvq = kv_quant(cfg);
       }
       {
         StepTimer tm(m, st, POP_STEP_KV_ONLY_GEMM);
@@ -1675,6 +1732,7 @@ pop_status pop_op_rope_attention(void* qkv, const int32_t* cu, int32_t B, int32_
   rw.qkv = (bf16_t*)qkv; rw.ld = ld; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
   rw.n_q_heads = Hq; rw.n_kv_heads = Hkv; rw.hd = hd; rw.cs = cs; rw.slot = nullptr;
   rw.k_pool = nullptr; rw.v_pool = nullptr; rw.page_size = 1; rw.vT = vT; rw.Tp = Tp; rw.fp16_inplace = 1;
+  rw.kvq = pop::KvQuant{0, 1.f, 1.f, 1.f, 1.f};
   rw.cu_seqlens = at<int32_t>(workspace, w.o_cu); rw.vt_off = at<int32_t>(workspace, w.o_vt_off);
   rw.tile_seq = at<int32_t>(workspace, w.o_t64_seq); rw.tile_start = at<int32_t>(workspace, w.o_t64_start);
   rw.n_tiles = n64;

@@ -269,7 +269,7 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float* __restric
                                                           bf16_t* __restrict__ v_pool, int P,
                                                           const float* __restrict__ q_gamma,
                                                           const float* __restrict__ k_gamma, float qk_eps,
-                                                          int n_parts, size_t part_stride) {
+                                                          int n_parts, size_t part_stride, KvQuant kvq) {
   __shared__ float red[2];
   const int b = blockIdx.x, head = blockIdx.y;
   const int half = hd >> 1;
@@ -300,22 +300,37 @@ __global__ __launch_bounds__(128) void rope_append_kernel(const float* __restric
     double sd, cd;
     sincos(ang, &sd, &cd);
     const float c = (float)cd, sn = (float)sd;
-    const bf16_t lo = f32_to_bf16(x * c - y * sn), hi = f32_to_bf16(y * c + x * sn);
+    const float rlo = x * c - y * sn, rhi = y * c + x * sn;
+    const bf16_t lo = f32_to_bf16(rlo), hi = f32_to_bf16(rhi);
     if (head < n_q_heads) {
       bf16_t* o = q_out + ((size_t)b * n_q_heads + head) * hd;
       o[i] = lo;
       o[i + half] = hi;
     } else {
       const int hh = head - n_q_heads;
-      bf16_t* o = k_pool + (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
-      o[i] = lo;
-      o[i + half] = hi;
+      const size_t eoff = (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
+      if (kvq.fp8) {     // one-byte e4m3 codes
+        unsigned char* o = reinterpret_cast<unsigned char*>(k_pool) + eoff;
+        o[i] = (unsigned char)e4m3_encode(rlo * kvq.k_inv);
+        o[i + half] = (unsigned char)e4m3_encode(rhi * kvq.k_inv);
+      } else {
+        bf16_t* o = k_pool + eoff;
+        o[i] = lo;
+        o[i + half] = hi;
+      }
     }
   } else {
     const int hh = head - n_q_heads - n_kv_heads;
-    bf16_t* o = v_pool + (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
-    o[i] = f32_to_bf16(x);
-    o[i + half] = f32_to_bf16(y);
+    const size_t eoff = (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
+    if (kvq.fp8) {
+      unsigned char* o = reinterpret_cast<unsigned char*>(v_pool) + eoff;
+      o[i] = (unsigned char)e4m3_encode(x * kvq.v_inv);
+      o[i + half] = (unsigned char)e4m3_encode(y * kvq.v_inv);
+    } else {
+      bf16_t* o = v_pool + eoff;
+      o[i] = f32_to_bf16(x);
+      o[i + half] = f32_to_bf16(y);
+    }
   }
 }
 }  // namespace decode_impl
@@ -324,11 +339,11 @@ using namespace decode_impl;
 void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
                         const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool, bf16_t* v_pool,
                         int page_size, int B, hipStream_t st, const float* q_gamma, const float* k_gamma,
-                        float qk_eps, int n_parts, size_t part_stride) {
+                        float qk_eps, int n_parts, size_t part_stride, KvQuant kvq) {
   if (B <= 0) return;
   hipLaunchKernelGGL(rope_append_kernel, dim3(B, n_q_heads + 2 * n_kv_heads), dim3(128), 0, st, qkv, ld, q_out,
                      n_q_heads, n_kv_heads, hd, pos, slot, -2.0 / (double)hd * log2(theta), k_pool, v_pool,
-                     page_size, q_gamma, k_gamma, qk_eps, n_parts, part_stride);
+                     page_size, q_gamma, k_gamma, qk_eps, n_parts, part_stride, kvq);
 }
 
 // ------------------------------------------------------------------------------------- decode attention
@@ -357,6 +372,7 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
   const int k_first = lo + split * KCH;
   const int n_keys = min(KCH, qpos + 1 - k_first);  // <= 0: this split is empty
   const int tid = threadIdx.x;
+  const bool fp8 = a.kvq.fp8 != 0;      // uniform: the pools hold one-byte e4m3 codes
   const int li = tid % LPK, kslot = tid / LPK;
   const int32_t* bt = a.block_table + (size_t)b * a.max_pages;
   float* part = a.part + (((size_t)b * a.n_q_heads + (size_t)kvh * G) * a.n_splits + split) * (HD + 2);
@@ -392,10 +408,27 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
       const int key = k_first + kk;
       const int page = bt[key >> lgP];
       const size_t off = (((size_t)page * a.n_kv_heads + kvh) * P + (key & (P - 1))) * HD + li * 8;
-      kw[it] = *reinterpret_cast<const uint4*>(a.k_pool + off);
-      vw[it] = *reinterpret_cast<const uint4*>(a.v_pool + off);
+      if (fp8) {   // 8 one-byte codes per chunk
+        const uint2 k8 = *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned char*>(a.k_pool) + off);
+        const uint2 v8 = *reinterpret_cast<const uint2*>(reinterpret_cast<const unsigned char*>(a.v_pool) + off);
+        kw[it].x = k8.x; kw[it].y = k8.y;
+        vw[it].x = v8.x; vw[it].y = v8.y;
+      } else {
+        kw[it] = *reinterpret_cast<const uint4*>(a.k_pool + off);
+        vw[it] = *reinterpret_cast<const uint4*>(a.v_pool + off);
+      }
     }
   }
+  // the 8 values of a chunk as floats: bf16 entries, or e4m3 codes times the tensor's scale
+  auto unpack8 = [&](const uint4& w, float* f, float scale8) {
+    if (fp8) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = e4m3_decode(((e < 4 ? w.x : w.y) >> (8 * (e & 3))) & 0xffu) * scale8;
+    } else {
+      f[0] = bf16lo(w.x); f[1] = bf16hi(w.x); f[2] = bf16lo(w.y); f[3] = bf16hi(w.y);
+      f[4] = bf16lo(w.z); f[5] = bf16hi(w.z); f[6] = bf16lo(w.w); f[7] = bf16hi(w.w);
+    }
+  };
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     const int kk = kslot + it * KPI;
@@ -403,9 +436,8 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
 #pragma unroll
     for (int g = 0; g < GT; ++g) s[g] = 0.f;
     {
-      const uint4 w = kw[it];
-      const float kf[8] = {bf16lo(w.x), bf16hi(w.x), bf16lo(w.y), bf16hi(w.y),
-                           bf16lo(w.z), bf16hi(w.z), bf16lo(w.w), bf16hi(w.w)};
+      float kf[8];
+      unpack8(kw[it], kf, a.kvq.k_scale);
 #pragma unroll
       for (int g = 0; g < GT; ++g)
         if (g < G) {
@@ -451,9 +483,8 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
   for (int it = 0; it < NIT; ++it) {
     const int kk = kslot + it * KPI;
     if (kk >= n_keys) continue;
-    const uint4 w = vw[it];
-    const float vf[8] = {bf16lo(w.x), bf16hi(w.x), bf16lo(w.y), bf16hi(w.y),
-                         bf16lo(w.z), bf16hi(w.z), bf16lo(w.w), bf16hi(w.w)};
+    float vf[8];
+    unpack8(vw[it], vf, a.kvq.v_scale);
 #pragma unroll
     for (int g = 0; g < GT; ++g)
       if (g < G) {

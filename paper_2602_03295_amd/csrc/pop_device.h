@@ -35,6 +35,39 @@ __device__ __forceinline__ float f16hi(uint32_t w) { return (float)__builtin_bit
 __device__ __forceinline__ float bf16lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
 __device__ __forceinline__ float bf16hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
 
+// 8-bit floating point with 4 exponent bits (bias 7), 3 mantissa bits, no infinities ("e4m3", largest finite value
+// 448, code 0x7f / 0xff = NaN), in software so that the rounding is the one written here whatever the hardware's
+// conversion instructions implement: nearest value, ties to the even mantissa, magnitudes beyond 448 clamp to 448
+// (a NaN input gives the NaN code).
+__device__ __forceinline__ uint32_t e4m3_encode(float x) {
+  const uint32_t bits = __builtin_bit_cast(uint32_t, x);
+  const uint32_t sign = (bits >> 24) & 0x80u;
+  float a = __builtin_fabsf(x);
+  if (!(a == a)) return sign | 0x7fu;
+  a = fminf(a, 448.f);
+  uint32_t code;
+  if (a < 0.015625f) {                       // below the smallest normal value 2^-6: steps of 2^-9
+    code = (uint32_t)__builtin_rintf(a * 512.f);          // 0 .. 8 (8 is the code of 2^-6 itself)
+  } else {
+    uint32_t u = __builtin_bit_cast(uint32_t, a);
+    u += 0x7ffffu + ((u >> 20) & 1u);        // round to nearest even at bit 20 (3 mantissa bits kept)
+    code = ((u >> 20) & 0x7ffu) - ((127u - 7u) << 3);     // exponent re-biased from 127 to 7, mantissa below it
+  }
+  return sign | code;
+}
+__device__ __forceinline__ float e4m3_decode(uint32_t c) {
+  const uint32_t mag = c & 0x7fu;
+  // normal: exponent field e = mag >> 3 (>= 1), value (1 + m / 8) 2^(e - 7); subnormal: m 2^-9
+  const float normal = __builtin_bit_cast(float, (mag << 20) + ((127u - 7u) << 23));
+  const float sub = (float)mag * 0.001953125f;
+  const float v = mag < 8u ? sub : normal;
+  return (c & 0x80u) ? -v : v;
+}
+// Four values -> four codes in one 32-bit word (element 0 in the low byte).
+__device__ __forceinline__ uint32_t e4m3_pack4(float a, float b, float c, float d) {
+  return e4m3_encode(a) | (e4m3_encode(b) << 8) | (e4m3_encode(c) << 16) | (e4m3_encode(d) << 24);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -32,6 +32,18 @@ void launch_embed(const bf16_t* table, const int32_t* tokens, const int32_t* row
   hipLaunchKernelGGL(embed_kernel, dim3(T), dim3(256), 0, st, table, tokens, row_src, embeds, h, d);
 }
 
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ dst, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+    dst[i] = make_uint4(0, 0, 0, 0);
+}
+
+void launch_fill_zero(void* dst, size_t bytes, hipStream_t st) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return;
+  const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 4096);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<uint4*>(dst), n16);
+}
+
 __global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restrict__ src,
                                                           const int32_t* __restrict__ idx,
                                                           float* __restrict__ dst, int d) {
@@ -283,30 +295,54 @@ __global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a, int he
         }
         if (!valid) continue;
         uint32_t ol[4], oh[4], fl[4], fh[4];
+        float rl[8], rh[8];     // rotated low / high halves
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const float2 c0 = cs[2 * e], c1 = cs[2 * e + 1];
           const float x0 = xs[2 * e], x1 = xs[2 * e + 1];
           const float y0 = ys[2 * e], y1 = ys[2 * e + 1];
-          const float r0 = x0 * c0.x - y0 * c0.y, r1 = x1 * c1.x - y1 * c1.y;
-          const float r2 = y0 * c0.x + x0 * c0.y, r3 = y1 * c1.x + x1 * c1.y;
-          ol[e] = pack_bf16x2(r0, r1);
-          oh[e] = pack_bf16x2(r2, r3);
-          fl[e] = pack_f16x2(r0, r1);
-          fh[e] = pack_f16x2(r2, r3);
+          rl[2 * e] = x0 * c0.x - y0 * c0.y; rl[2 * e + 1] = x1 * c1.x - y1 * c1.y;
+          rh[2 * e] = y0 * c0.x + x0 * c0.y; rh[2 * e + 1] = y1 * c1.x + x1 * c1.y;
+        }
+        const bool q8 = is_k && a.kvq.fp8;     // an 8-bit cache: the key is what its code stands for
+        uint2 cl = make_uint2(0, 0), ch = make_uint2(0, 0);
+        if (q8) {
+          cl.x = e4m3_pack4(rl[0] * a.kvq.k_inv, rl[1] * a.kvq.k_inv, rl[2] * a.kvq.k_inv, rl[3] * a.kvq.k_inv);
+          cl.y = e4m3_pack4(rl[4] * a.kvq.k_inv, rl[5] * a.kvq.k_inv, rl[6] * a.kvq.k_inv, rl[7] * a.kvq.k_inv);
+          ch.x = e4m3_pack4(rh[0] * a.kvq.k_inv, rh[1] * a.kvq.k_inv, rh[2] * a.kvq.k_inv, rh[3] * a.kvq.k_inv);
+          ch.y = e4m3_pack4(rh[4] * a.kvq.k_inv, rh[5] * a.kvq.k_inv, rh[6] * a.kvq.k_inv, rh[7] * a.kvq.k_inv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            rl[e] = e4m3_decode(((e < 4 ? cl.x : cl.y) >> (8 * (e & 3))) & 0xffu) * a.kvq.k_scale;
+            rh[e] = e4m3_decode(((e < 4 ? ch.x : ch.y) >> (8 * (e & 3))) & 0xffu) * a.kvq.k_scale;
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          ol[e] = pack_bf16x2(rl[2 * e], rl[2 * e + 1]);
+          oh[e] = pack_bf16x2(rh[2 * e], rh[2 * e + 1]);
+          fl[e] = pack_f16x2(rl[2 * e], rl[2 * e + 1]);
+          fh[e] = pack_f16x2(rh[2 * e], rh[2 * e + 1]);
         }
         const uint4 vlo = make_uint4(ol[0], ol[1], ol[2], ol[3]);
         const uint4 vhi = make_uint4(oh[0], oh[1], oh[2], oh[3]);
         // in place: fp16 when the attention kernel is the consumer (three more mantissa bits than bf16
-        // for the score contraction), bf16 otherwise; the cache entry is always bf16
+        // for the score contraction), bf16 otherwise; the cache entry is bf16 or an e4m3 code
         if (!a.cache_only) {
           *reinterpret_cast<uint4*>(row + g * 8) = a.fp16_inplace ? make_uint4(fl[0], fl[1], fl[2], fl[3]) : vlo;
           *reinterpret_cast<uint4*>(row + half + g * 8) = a.fp16_inplace ? make_uint4(fh[0], fh[1], fh[2], fh[3]) : vhi;
         }
         if (is_k && a.k_pool) {
-          bf16_t* dst = a.k_pool + (((size_t)(s / P) * a.n_kv_heads + hh) * P + (s % P)) * hd;
-          *reinterpret_cast<uint4*>(dst + g * 8) = vlo;
-          *reinterpret_cast<uint4*>(dst + half + g * 8) = vhi;
+          const size_t eoff = (((size_t)(s / P) * a.n_kv_heads + hh) * P + (s % P)) * hd;
+          if (a.kvq.fp8) {
+            unsigned char* dst = reinterpret_cast<unsigned char*>(a.k_pool) + eoff;
+            *reinterpret_cast<uint2*>(dst + g * 8) = cl;
+            *reinterpret_cast<uint2*>(dst + half + g * 8) = ch;
+          } else {
+            bf16_t* dst = a.k_pool + eoff;
+            *reinterpret_cast<uint4*>(dst + g * 8) = vlo;
+            *reinterpret_cast<uint4*>(dst + half + g * 8) = vhi;
+          }
         }
       }
     }
@@ -319,10 +355,33 @@ __global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a, int he
   for (int it = threadIdx.x; it < 64 * groups; it += 256) {
     const int p = it / groups, g = it - p * groups;
     uint4 v = make_uint4(0, 0, 0, 0);
+    bool v_is_f16 = a.fp16_input != 0;     // format of the 8 values in v (fp16 or bf16)
     if (p0 + p < len) {
       const size_t t = (size_t)seq0 + p0 + p;
       v = *reinterpret_cast<const uint4*>(a.qkv + t * a.ld + col + g * 8);
-      if (a.v_pool) {
+      if (a.kvq.fp8) {
+        // 8-bit cache: store the codes; what the attention kernel reads (vT) are the values they stand for
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        float f[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          f[2 * e] = (a.fp16_input ? f16lo(w[e]) : bf16lo(w[e])) * a.kvq.v_inv;
+          f[2 * e + 1] = (a.fp16_input ? f16hi(w[e]) : bf16hi(w[e])) * a.kvq.v_inv;
+        }
+        uint2 c;
+        c.x = e4m3_pack4(f[0], f[1], f[2], f[3]);
+        c.y = e4m3_pack4(f[4], f[5], f[6], f[7]);
+        if (a.v_pool) {
+          const int s = a.slot[t];
+          unsigned char* dst = reinterpret_cast<unsigned char*>(a.v_pool) +
+                               (((size_t)(s / P) * a.n_kv_heads + hh) * P + (s % P)) * hd;
+          *reinterpret_cast<uint2*>(dst + g * 8) = c;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = e4m3_decode(((e < 4 ? c.x : c.y) >> (8 * (e & 3))) & 0xffu) * a.kvq.v_scale;
+        v = make_uint4(pack_f16x2(f[0], f[1]), pack_f16x2(f[2], f[3]), pack_f16x2(f[4], f[5]), pack_f16x2(f[6], f[7]));
+        v_is_f16 = true;
+      } else if (a.v_pool) {
         const int s = a.slot[t];
         bf16_t* dst = a.v_pool + (((size_t)(s / P) * a.n_kv_heads + hh) * P + (s % P)) * hd;
         uint4 vb = v;   // the cache entry is bf16
@@ -338,8 +397,8 @@ __global__ __launch_bounds__(256) void rope_write_kernel(RopeWriteArgs a, int he
       const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        tr[(g * 8 + 2 * e) * 66 + p] = a.fp16_input ? (uint16_t)(w[e] & 0xffff) : f32_to_f16_sat(bf16lo(w[e]));
-        tr[(g * 8 + 2 * e + 1) * 66 + p] = a.fp16_input ? (uint16_t)(w[e] >> 16) : f32_to_f16_sat(bf16hi(w[e]));
+        tr[(g * 8 + 2 * e) * 66 + p] = v_is_f16 ? (uint16_t)(w[e] & 0xffff) : f32_to_f16_sat(bf16lo(w[e]));
+        tr[(g * 8 + 2 * e + 1) * 66 + p] = v_is_f16 ? (uint16_t)(w[e] >> 16) : f32_to_f16_sat(bf16hi(w[e]));
       }
     }
   }

@@ -113,7 +113,8 @@ __global__ void rope_write_kernel(float* __restrict__ qkv, int ld, int q_col, in
                                   int n_kv_heads, int hd, const int32_t* __restrict__ pos,
                                   const int32_t* __restrict__ slot, double neg2_over_hd_log2theta,
                                   float* __restrict__ k_pool, float* __restrict__ v_pool, int P,
-                                  const float* __restrict__ q_gamma, const float* __restrict__ k_gamma, float qk_eps) {
+                                  const float* __restrict__ q_gamma, const float* __restrict__ k_gamma, float qk_eps,
+                                  KvQuant kvq) {
   __shared__ float red[2];
   const int r = blockIdx.x, head = blockIdx.y;
   const int half = hd >> 1;
@@ -147,17 +148,18 @@ __global__ void rope_write_kernel(float* __restrict__ qkv, int ld, int q_col, in
     x[i] = lo;
     x[i + half] = hi;
     if (!is_q) {
+      // 8-bit cache: the fp32 entry holds the value of the e4m3 code the element rounds to
       float* o = k_pool + (((size_t)(s / P) * n_kv_heads + (head - n_q_heads)) * P + (s % P)) * hd;
-      o[i] = lo;
-      o[i + half] = hi;
+      o[i] = kvq.fp8 ? e4m3_decode(e4m3_encode(lo * kvq.k_inv)) * kvq.k_scale : lo;
+      o[i + half] = kvq.fp8 ? e4m3_decode(e4m3_encode(hi * kvq.k_inv)) * kvq.k_scale : hi;
     }
   } else {
     if (!act) return;
     const int hh = head - n_q_heads - n_kv_heads;
     const float* x = row + v_col + hh * hd;
     float* o = v_pool + (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
-    o[i] = x[i];
-    o[i + half] = x[i + half];
+    o[i] = kvq.fp8 ? e4m3_decode(e4m3_encode(x[i] * kvq.v_inv)) * kvq.v_scale : x[i];
+    o[i + half] = kvq.fp8 ? e4m3_decode(e4m3_encode(x[i + half] * kvq.v_inv)) * kvq.v_scale : x[i + half];
   }
 }
 
@@ -248,11 +250,11 @@ void launch_gemm(const float* A, int lda, const float* W, int ldw, float* out, i
 
 void launch_rope_write(float* qkv, int ld, int q_col, int k_col, int v_col, int n_q_heads, int n_kv_heads, int hd,
                        const int32_t* pos, const int32_t* slot, double theta, float* k_pool, float* v_pool, int P,
-                       int rows, hipStream_t st, const float* q_gamma, const float* k_gamma, float qk_eps) {
+                       int rows, hipStream_t st, const float* q_gamma, const float* k_gamma, float qk_eps, KvQuant kvq) {
   if (rows <= 0) return;
   hipLaunchKernelGGL(impl::rope_write_kernel, dim3(rows, n_q_heads + 2 * n_kv_heads), dim3((hd / 2 + 63) / 64 * 64), 0, st, qkv, ld,
                      q_col, k_col, v_col, n_q_heads, n_kv_heads, hd, pos, slot, -2.0 / (double)hd * log2(theta), k_pool,
-                     v_pool, P, q_gamma, k_gamma, qk_eps);
+                     v_pool, P, q_gamma, k_gamma, qk_eps, kvq);
 }
 
 hipError_t launch_attention(const float* q, int ldq, int q_col, float* out, const int32_t* row_seq,

@@ -63,6 +63,18 @@ struct GemmParams {
   const int32_t* kv_slot;
   int kv_heads, kv_page;
   long long kv_pool_stride;
+  KvQuant kvq;
+  // Normalisation folded into two neighbouring projections (LN of Sec. 2.1 as RMSNorm):
+  //   producer (EPI_ADD_F32): besides out += C it stores bf16(out_new * gamma) and, per row and 64-column group,
+  //   the sum of squares of out_new;
+  //   consumer (any storing epilogue): A holds such un-normalised rows, and every accumulator row is multiplied
+  //   by rstd = rsqrt(sum of the row's partial sums / K + eps) before the epilogue proper.
+  const float* nrm_gamma;   // producer: [N], nullptr = off
+  bf16_t* nrm_out;          // producer: [M, N]
+  float* nrm_parts;         // producer: [M, N / 64]
+  const float* a_parts;     // consumer: [M, a_nparts], nullptr = off
+  int a_nparts;
+  float a_eps;
 };
 
 // Template values of the KV-cache epilogue (EPI_KV_CACHE of the interface), one per head_dim: the offset between
@@ -263,6 +275,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     if (t < nk) issue(t, t, t < nk_full ? 0u : last_mask);
     else if (STAGES >= 4) issue(t, t, kOOB);
   }
+  // Consumer side of a folded normalisation: while the first stages travel, every thread adds the partial sums of
+  // squares of one of the tile's rows (fixed order) and leaves the row's rstd in LDS for the epilogue.
+  float* row_rstd = reinterpret_cast<float*>(smem + STAGES * STAGE + 1024);
+  if (p.a_parts) {
+    for (int r = threadIdx.x; r < BM; r += 64 * NW) {
+      const int row = m0 + r;
+      float ssum = 0.f;
+      if (row < p.M) {
+        const float4* pp = reinterpret_cast<const float4*>(p.a_parts + (long long)row * p.a_nparts);
+        for (int i = 0; i < (p.a_nparts >> 2); ++i) {
+          const float4 v = pp[i];
+          ssum += (v.x + v.y) + (v.z + v.w);
+        }
+      }
+      row_rstd[r] = rsqrtf(ssum / (float)p.K + p.a_eps);
+    }
+  }
   // The K loop is rotated by one (32-wide) sub-step: the MFMAs of the last sub-step of K-step kt-1 are issued
   // after the barrier of K-step kt, from fragments that are already in registers, so the matrix
   // pipe has work while the first fragments of the new stage travel from LDS.  Sub-step s of a
@@ -408,9 +437,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
         if (m >= p.M) continue;
         {
           const int n = n0 + wn * (WTN / 2) + i * 16 + frag_hi * 4;
+          const float rs = p.a_parts ? row_rstd[wm * WTM + j * 16 + frag_row] : 1.f;   // folded normalisation of A
           float r[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) r[e] = glu_act(acc[i][j][e], act_k0, act_k1) * acc[i + NB / 2][j][e];
+          for (int e = 0; e < 4; ++e) r[e] = glu_act(acc[i][j][e] * rs, act_k0, act_k1) * (acc[i + NB / 2][j][e] * rs);
           bf16_t* o = out + (long long)m * p.ldc + n;
           if (n + 3 < p.N) {
             uint2 pk;
@@ -439,18 +469,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
       const bool is_k = n_wave < Dkv;                  // Dkv is a multiple of WTN (checked by the launcher)
       const int head0 = (is_k ? n_wave : n_wave - Dkv) / HD;
       const KvDest dst = p.kv_dest[z];
-      bf16_t* pool = dst.k_pool + (is_k ? 0 : p.kv_pool_stride);
+      const bool fp8 = p.kvq.fp8 != 0;                 // one-byte e4m3 codes instead of bf16 entries
+      const long long esz = fp8 ? 1 : 2;
+      char* pool = reinterpret_cast<char*>(dst.k_pool) + (is_k ? 0 : p.kv_pool_stride) * esz;
+      const float inv = is_k ? p.kvq.k_inv : p.kvq.v_inv;
       const int P = p.kv_page;
 #pragma unroll
       for (int j = 0; j < MB; ++j) {
         const int m = m_lane + j * 16;
         if (m >= p.M) continue;
         const int s = p.kv_slot[m];
-        bf16_t* row = pool + (((long long)(s / P) * p.kv_heads + head0) * P + (s % P)) * HD + frag_hi * 4;
+        char* row = pool + ((((long long)(s / P) * p.kv_heads + head0) * P + (s % P)) * HD + frag_hi * 4) * esz;
         const float4* csr = reinterpret_cast<const float4*>(dst.cs + (long long)m * (HD / 2) + frag_hi * 4);
 #pragma unroll
         for (int hw = 0; hw < HPW; ++hw) {
-          bf16_t* hrow = row + (long long)hw * P * HD;
+          char* hrow = row + (long long)hw * P * HD * esz;
 #pragma unroll
           for (int ib = 0; ib < HB; ++ib) {
             const int lo = hw * 2 * HB + ib, hi = lo + HB;
@@ -468,11 +501,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #pragma unroll
               for (int e = 0; e < 4; ++e) { a[e] = acc[lo][j][e]; b[e] = acc[hi][j][e]; }
             }
-            uint2 pa, pb;
-            pa.x = pack_bf16x2(a[0], a[1]); pa.y = pack_bf16x2(a[2], a[3]);
-            pb.x = pack_bf16x2(b[0], b[1]); pb.y = pack_bf16x2(b[2], b[3]);
-            *reinterpret_cast<uint2*>(hrow + ib * 16) = pa;
-            *reinterpret_cast<uint2*>(hrow + HD / 2 + ib * 16) = pb;
+            if (fp8) {
+              *reinterpret_cast<uint32_t*>(hrow + ib * 16) = e4m3_pack4(a[0] * inv, a[1] * inv, a[2] * inv, a[3] * inv);
+              *reinterpret_cast<uint32_t*>(hrow + HD / 2 + ib * 16) = e4m3_pack4(b[0] * inv, b[1] * inv, b[2] * inv, b[3] * inv);
+            } else {
+              uint2 pa, pb;
+              pa.x = pack_bf16x2(a[0], a[1]); pa.y = pack_bf16x2(a[2], a[3]);
+              pb.x = pack_bf16x2(b[0], b[1]); pb.y = pack_bf16x2(b[2], b[3]);
+              *reinterpret_cast<uint2*>(hrow + (ib * 16) * 2) = pa;
+              *reinterpret_cast<uint2*>(hrow + (HD / 2 + ib * 16) * 2) = pb;
+            }
           }
         }
       }
@@ -485,6 +523,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     // next one is requested (one memory round trip per block; measured: 2 to 7 us per projection at 2048 rows).
     float* outp = reinterpret_cast<float*>(p.out) + (long long)z * p.strideC;
     constexpr int TOT = MB * NB, CH = 16;
+    // Producer side of a folded normalisation (N is then a multiple of 64, so every group of four columns is
+    // whole): the new rows times the next norm's scale go out as bf16, and each lane collects the squares of what
+    // it holds of every row.
+    const bool nrm = p.nrm_gamma != nullptr;
+    float ss[MB];
+#pragma unroll
+    for (int j = 0; j < MB; ++j) ss[j] = 0.f;
 #pragma unroll
     for (int c0 = 0; c0 < TOT; c0 += CH) {
       float4 old[CH];
@@ -506,13 +551,42 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
           const int m = m_lane + j * 16, n = n0 + wn * WTN + i * 16 + frag_hi * 4;
           float* o = outp + (long long)m * p.ldc + n;
           if (m < p.M && n + 3 < p.N) {
-            *reinterpret_cast<float4*>(o) = make_float4(acc[i][j][0] * p.scale + old[c].x, acc[i][j][1] * p.scale + old[c].y,
-                                                        acc[i][j][2] * p.scale + old[c].z, acc[i][j][3] * p.scale + old[c].w);
+            const float4 nv = make_float4(acc[i][j][0] * p.scale + old[c].x, acc[i][j][1] * p.scale + old[c].y,
+                                          acc[i][j][2] * p.scale + old[c].z, acc[i][j][3] * p.scale + old[c].w);
+            *reinterpret_cast<float4*>(o) = nv;
+            if (nrm) {
+              const float4 g = *reinterpret_cast<const float4*>(p.nrm_gamma + n);
+              uint2 pk;
+              pk.x = pack_bf16x2(nv.x * g.x, nv.y * g.y);
+              pk.y = pack_bf16x2(nv.z * g.z, nv.w * g.w);
+              *reinterpret_cast<uint2*>(p.nrm_out + (long long)m * p.N + n) = pk;
+              ss[j] += (nv.x * nv.x + nv.y * nv.y) + (nv.z * nv.z + nv.w * nv.w);
+            }
           } else if (m < p.M && n < p.N) {   // the last, partial group of four columns
 #pragma unroll
             for (int q = 0; q < 4; ++q)
               if (n + q < p.N) o[q] += acc[i][j][q] * p.scale;
           }
+        }
+      }
+    }
+    if (nrm) {
+      // the four lanes that share a row (same lane & 15) add up; the first of them stores the wave tile's sum as
+      // the partial of its first 64-column group (a 128-column wave tile fills its second group with zero)
+      static_assert(WTN % 64 == 0 || EPI != EPI_ADD_F32 || true, "");
+      const int parts_per_row = p.N >> 6;
+      const int part0 = (n0 + wn * WTN) >> 6;
+#pragma unroll
+      for (int j = 0; j < MB; ++j) {
+        float v = ss[j];
+        v += __shfl_xor(v, 16, 64);
+        v += __shfl_xor(v, 32, 64);
+        const int m = m_lane + j * 16;
+        if (frag_hi == 0 && m < p.M && n0 + wn * WTN < p.N) {
+          float* pp = p.nrm_parts + (long long)m * parts_per_row + part0;
+          pp[0] = v;
+#pragma unroll
+          for (int q = 1; q < WTN / 64; ++q) pp[q] = 0.f;
         }
       }
     }
@@ -526,8 +600,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
         {
           const int n = n0 + wn * WTN + i * 16 + frag_hi * 4;
           if (n >= p.N) continue;
-          const float r0 = acc[i][j][0], r1 = acc[i][j][1];
-          const float r2 = acc[i][j][2], r3 = acc[i][j][3];
+          const float rs = p.a_parts ? row_rstd[wm * WTM + j * 16 + frag_row] : 1.f;   // folded normalisation of A
+          const float r0 = acc[i][j][0] * rs, r1 = acc[i][j][1] * rs;
+          const float r2 = acc[i][j][2] * rs, r3 = acc[i][j][3] * rs;
           if (EPI == EPI_STORE_BF16 || EPI == EPI_STORE_F16) {
             bf16_t* o = reinterpret_cast<bf16_t*>(p.out) + (long long)z * p.strideC + (long long)m * p.ldc + n;
             if (n + 3 < p.N) {
@@ -561,7 +636,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 template <int BM, int BN, int WGM, int WGN, int STAGES, int EPI>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_tiles = -1) {
   constexpr int BN_OUT = EPI == EPI_GLU_BF16 ? BN / 2 : BN;
-  constexpr int smem = STAGES * (BM + BN) * BK * 2 + 1024;  // stages + prefetch scratch
+  constexpr int smem = STAGES * (BM + BN) * BK * 2 + 1024 + BM * 4;  // stages + prefetch scratch + per-row rstd
   static_assert(smem <= 160 * 1024, "LDS budget of a gfx950 CU");
   GemmParams p;
   p.A = g.A; p.W = g.W; p.out = g.out;
@@ -571,6 +646,9 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_
   p.scale = residual_scale(g);
   p.kv_dest = g.kv_dest; p.kv_slot = g.kv_slot; p.kv_heads = g.kv_heads; p.kv_page = g.kv_page_size;
   p.kv_pool_stride = g.kv_pool_stride;
+  p.kvq = g.kvq;
+  p.nrm_gamma = g.nrm_gamma; p.nrm_out = g.nrm_out; p.nrm_parts = g.nrm_parts;
+  p.a_parts = g.a_parts; p.a_nparts = g.a_nparts; p.a_eps = g.a_eps;
   p.tiles_m = (g.M + BM - 1) / BM;
   p.tiles_n = n_tiles >= 0 ? n_tiles : (g.N + BN_OUT - 1) / BN_OUT;
   p.n_tile0 = n_tile0;
@@ -638,6 +716,8 @@ hipError_t launch_epi(const GemmArgs& g, hipStream_t st) {
     double best = 1e300;
     for (const TileCfg& c : kTileCfgs) {      // ordered by area: ties go to the larger tile
       if (c.id == 5 && EPI == EPI_GLU_BF16) continue;
+      // a producer of a folded normalisation needs wave tiles of whole 64-column groups
+      if (g.nrm_gamma && (c.id == 5 || c.id == 6 || c.id == 7 || c.id == 9)) continue;
       const double t = cost(c);
       if (t < best) { best = t; pick = c.id; }
     }
@@ -721,6 +801,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // the rows fit one 64-row tile and the launch would leave CUs idle.
 inline int choose_split(const GemmArgs& g) {
   if (!g.splitk_ws || g.batch > 1 || g.W_list || g.epilogue == EPI_GLU_BF16 || g.epilogue == EPI_KV_CACHE) return 1;
+  if (g.nrm_gamma || g.a_parts) return 1;   // the folded normalisation lives in the one-pass epilogues
   if (g.M > 512 || g.N % 4 || g.K % BK || (reinterpret_cast<uintptr_t>(g.splitk_ws) & 15)) return 1;
   // Building with -DPOP_FORCE_SPLITK=S forces S parts where the problem allows it (experiments only).
 #ifdef POP_FORCE_SPLITK
@@ -757,6 +838,11 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   if (g.K <= 0 || g.K % 8 || g.lda % 8 || g.ldw % 8 || g.ldc % 4) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.W) |
        (g.epilogue == EPI_KV_CACHE ? 0 : reinterpret_cast<uintptr_t>(g.out))) & 15)
+    return hipErrorInvalidValue;
+  if (g.nrm_gamma && (g.epilogue != EPI_ADD_F32 || g.N % 64 || !g.nrm_out || !g.nrm_parts || g.batch > 1))
+    return hipErrorInvalidValue;
+  if (g.a_parts && (g.epilogue == EPI_ADD_F32 || g.epilogue == EPI_KV_CACHE || g.a_nparts < 4 || g.a_nparts % 4 ||
+                    g.batch > 1 || (reinterpret_cast<uintptr_t>(g.a_parts) & 15)))
     return hipErrorInvalidValue;
   const long long w_rows = g.epilogue == EPI_GLU_BF16 ? 2LL * g.N : g.N;
   if (((long long)(g.M - 1) * g.lda + g.K) * 2 >= (1LL << 31) || ((w_rows - 1) * g.ldw + g.K) * 2 >= (1LL << 31))

@@ -14,6 +14,13 @@ typedef uint16_t bf16_t;  // raw bf16 bits in memory
 // `status` unchanged.  For the source files of the C ABI other than pop_api.cpp, which owns the record.
 int record_error(int status, const char* msg);
 
+// How cache entries are stored: bf16 values, or (fp8) one-byte e4m3 codes of x * inv_scale that read back as
+// code value * scale.  Every kernel that appends to the cache or reads it takes one of these.
+struct KvQuant {
+  int fp8;
+  float k_scale, v_scale, k_inv, v_inv;
+};
+
 // ---------------------------------------------------------------------------------------------
 // Elementwise / bandwidth-bound steps (pop_elementwise.hip)
 // ---------------------------------------------------------------------------------------------
@@ -71,6 +78,9 @@ struct RopeWriteArgs {
   const int32_t* tile_seq;    // [n_tiles]
   const int32_t* tile_start;  // [n_tiles]
   int n_tiles;
+  // 8-bit cache: the pools take e4m3 codes, and what the attention kernel reads (the in-place fp16 k and vT) are
+  // the values those codes stand for, since every attention reads the stored entries
+  KvQuant kvq;
 };
 void launch_rope_write(const RopeWriteArgs& a, hipStream_t st);
 
@@ -87,7 +97,27 @@ enum GemmEpilogue {
   // W^K rows, then its W^V rows, N = 2 Dkv); columns < Dkv are rotated (RoPE on the fp32 accumulators, the two
   // halves of a head are registers of the same lane) and stored as bf16 at the row's slot of the K pool, the
   // others at the same slot of the V pool.  Nothing else is written (out, ldc, strideC are ignored).
-  EPI_KV_CACHE = 5
+  EPI_KV_CACHE = 5,
+  // The QKV projection of a kept layer with everything the RoPE / append kernel does folded into its epilogue
+  // (Sec. 2.1, K/V generation and cache append): W is the layer's [Dq + 2 Dkv, K] matrix (rows q | k | v); query
+  // and key heads are rotated on the fp32 accumulators, q and k go to the fp16 matrix the attention kernel reads,
+  // k and v to the paged cache, v also to the transposed fp16 copy.  See QkvRope.
+  EPI_QKV_ROPE = 6
+};
+// Destinations of an EPI_QKV_ROPE launch.
+struct QkvRope {
+  bf16_t* qk_out;          // fp16 [M, ld]: rotated q heads in columns 0 .. Dq-1, rotated k heads in Dq .. Dq+Dkv-1
+  int ld;
+  int n_q_heads, n_kv_heads, hd;
+  const float2* cs;        // [M, hd/2] (cos, sin) of every row's position
+  const int32_t* slot;     // [M] cache slot of every row
+  const int32_t* vt_col;   // [M] column of every row in vT
+  bf16_t* k_pool;          // this layer's pools [page][Hkv][P][hd] (one-byte codes with an 8-bit cache)
+  bf16_t* v_pool;
+  int page_size;
+  bf16_t* vT;              // fp16 [Hkv][hd][Tp]; columns that belong to no row must already be zero
+  long long Tp;
+  KvQuant kvq;
 };
 // Per batch entry (= pruned layer) of an EPI_KV_CACHE launch: where its entries go and which RoPE table it uses.
 struct KvDest {
@@ -126,7 +156,24 @@ struct GemmArgs {
   const int32_t* kv_slot;    // DEVICE [M] cache slot of every row
   int kv_heads, kv_hd, kv_page_size;
   int64_t kv_pool_stride;    // elements from a layer's K pool to its V pool
+  KvQuant kvq;               // bf16 entries or e4m3 codes
+  // The normalisation between two projections (LN of Sec. 2.1) folded into them instead of a kernel of its own.
+  // Producer, EPI_ADD_F32 with N % 64 == 0: besides out += C the kernel stores nrm_out = bf16(out_new * nrm_gamma)
+  // ([M, N] dense) and nrm_parts[m][N / 64] = sums of squares of out_new over 64-column groups.
+  // Consumer, a storing epilogue: A is such an un-normalised matrix (lda = K) and a_parts its partial sums
+  // ([M, a_nparts], a_nparts = K / 64, 16-byte aligned); every result row is multiplied by
+  // rsqrt(sum of the row's partials / K + a_eps).  Mathematically RMSNorm followed by the projection; the bf16
+  // rounding of A happens before instead of after the multiplication by rstd, which changes no error bound.
+  const float* nrm_gamma;
+  bf16_t* nrm_out;
+  float* nrm_parts;
+  const float* a_parts;
+  int a_nparts;
+  float a_eps;
+  QkvRope qr;                // EPI_QKV_ROPE only
 };
+// Whether launch_gemm can run EPI_QKV_ROPE for this shape: head_dim a multiple of 32.
+bool gemm_qkv_rope_supported(int hd);
 // Whether launch_gemm can run EPI_KV_CACHE for this shape (otherwise the caller projects to a scratch matrix
 // and appends with launch_rope_write): head_dim 64 / 128 / 256 and whole heads per wave tile.
 bool gemm_kv_cache_supported(int n_kv_heads, int hd);
@@ -174,7 +221,8 @@ void launch_gemv_norm(const float* xf, const float* gamma, float eps, const bf16
 void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
                         const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool,
                         bf16_t* v_pool, int page_size, int B, hipStream_t st, const float* q_gamma = nullptr,
-                        const float* k_gamma = nullptr, float qk_eps = 0.f, int n_parts = 1, size_t part_stride = 0);
+                        const float* k_gamma = nullptr, float qk_eps = 0.f, int n_parts = 1, size_t part_stride = 0,
+                        KvQuant kvq = KvQuant{0, 1.f, 1.f, 1.f, 1.f});
 // (n_parts > 1: qkv is given as that many fp32 partial products, part_stride elements apart, which are added in
 // index order first: the second kernel of a QKV projection whose K range was split)
 
@@ -199,6 +247,7 @@ struct AttnDecodeArgs {
   int max_len;          // upper bound of pos+1 over the batch
   float* part;          // [B, Hq, n_splits, hd + 2]
   bf16_t* out;          // [B, Hq*hd]
+  KvQuant kvq;          // bf16 entries or e4m3 codes in the pools
 };
 void launch_attention_decode(const AttnDecodeArgs& a, hipStream_t st);
 
@@ -220,7 +269,8 @@ void launch_gemm(const float* A, int lda, const float* W, int ldw, float* out, i
 void launch_rope_write(float* qkv, int ld, int q_col, int k_col, int v_col, int n_q_heads, int n_kv_heads, int hd,
                        const int32_t* pos, const int32_t* slot, double theta, float* k_pool, float* v_pool, int P,
                        int rows, hipStream_t st, const float* q_gamma = nullptr, const float* k_gamma = nullptr,
-                       float qk_eps = 0.f);
+                       float qk_eps = 0.f, KvQuant kvq = KvQuant{0, 1.f, 1.f, 1.f, 1.f});
+// (kvq.fp8: the fp32 entries stored are the values of the e4m3 codes, i.e. decode(encode(x * inv)) * scale)
 // out[r, :] = Attn of row r (sequence row_seq[r], position row_pos[r]) over its cache entries
 // kv_first: per sequence, first position that has a cache entry in this layer (nullptr = 0)
 hipError_t launch_attention(const float* q, int ldq, int q_col, float* out, const int32_t* row_seq,
@@ -234,6 +284,9 @@ hipError_t launch_attention(const float* q, int ldq, int q_col, float* out, cons
 // (step > 0, eos >= 0); the choice is also stored at out[b * out_stride + step].
 void launch_argmax(const float* logits, int vocab, int32_t* tok, int32_t* out, int out_stride, int step, int eos,
                    int B, hipStream_t st);
+
+// dst[0 .. bytes) = 0 (a kernel, so that it may sit in a captured graph; bytes a multiple of 16, dst 16-byte aligned)
+void launch_fill_zero(void* dst, size_t bytes, hipStream_t st);
 
 // gather fp32 rows: dst[i,:] = src[idx[i],:]
 void launch_gather_rows(const float* src, const int32_t* idx, float* dst, int rows, int d, hipStream_t st);

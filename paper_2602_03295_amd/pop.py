@@ -25,6 +25,7 @@ STATUS_NAMES = {0: "POP_OK", -1: "POP_EINVAL", -2: "POP_ESHAPE", -3: "POP_EALIGN
                 -5: "POP_ESTATE", -6: "POP_EHIP", -7: "POP_EUNSUPPORTED"}
 MODE_POP, MODE_BODY_ONLY, MODE_NO_BOUNDARY = 0, 1, 2
 DTYPE_F32, DTYPE_BF16 = 0, 1
+KV_BF16, KV_FP8_E4M3 = 0, 1
 EPI_STORE_BF16, EPI_ADD_F32, EPI_GLU_BF16, EPI_STORE_F32 = 0, 1, 2, 3
 
 
@@ -38,7 +39,8 @@ class pop_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim",
                                          "d_ffn", "vocab", "dtype", "act")] + \
                [("rms_eps", C.c_float), ("rope_theta", C.c_float), ("rope_theta_local", C.c_float),
-                ("sliding_window", C.c_int32), ("global_every", C.c_int32), ("page_size", C.c_int32)]
+                ("sliding_window", C.c_int32), ("global_every", C.c_int32), ("page_size", C.c_int32),
+                ("kv_dtype", C.c_int32), ("k_scale", C.c_float), ("v_scale", C.c_float)]
 
 
 class pop_layer_weights(C.Structure):
@@ -124,8 +126,9 @@ def _check(status: int) -> None:
 
 def make_config(cfg: Dict) -> pop_config:
     c = pop_config()
+    defaults = {"kv_dtype": KV_BF16, "k_scale": 1.0, "v_scale": 1.0}
     for name, _ in pop_config._fields_:
-        setattr(c, name, cfg[name])
+        setattr(c, name, cfg[name] if name in cfg else defaults[name])
     return c
 
 
@@ -234,28 +237,53 @@ class Cache:
         nbytes = lib.pop_cache_bytes(C.byref(self.c_cfg), n_pages)
         if nbytes == 0:
             raise PopError(-1, "pop_cache_bytes returned 0 (bad config or page count)")
+        self.fp8 = cfg.get("kv_dtype", KV_BF16) == KV_FP8_E4M3 and cfg["dtype"] != DTYPE_F32
         if cfg["dtype"] == DTYPE_F32:
             self.pool = torch.empty(nbytes // 4, dtype=torch.float32, device=device)
+        elif self.fp8:
+            self.pool = torch.empty(nbytes, dtype=torch.uint8, device=device)     # one e4m3 code per element
         else:
             self.pool = torch.empty(nbytes // 2, dtype=torch.bfloat16, device=device)
         if fill is not None:
-            self.pool.fill_(fill)
+            if self.fp8:
+                self.pool.view(torch.float8_e4m3fn).copy_(torch.full_like(self.pool, fill, dtype=torch.float32))
+            else:
+                self.pool.fill_(fill)
         self.handle = C.c_void_p()
         _check(lib.pop_cache_create(C.byref(self.c_cfg), self.pool.data_ptr(), nbytes, n_pages, max_seqs,
                                     max_pages_per_seq, C.byref(self.handle)))
 
     def view(self) -> torch.Tensor:
-        """[layer, kv, page, kv_head, slot_in_page, head_dim]"""
+        """[layer, kv, page, kv_head, slot_in_page, head_dim]; an 8-bit cache is returned as the float32 values its
+        codes stand for (code value times the tensor's scale)."""
+        c = self.cfg
+        shape = (c["n_layers"], 2, self.n_pages, c["n_kv_heads"], c["page_size"], c["head_dim"])
+        if self.fp8:
+            v = self.pool.view(torch.float8_e4m3fn).view(*shape).float()
+            v[:, 0] *= c["k_scale"]
+            v[:, 1] *= c["v_scale"]
+            return v
+        return self.pool.view(*shape)
+
+    def codes(self) -> torch.Tensor:
+        """The raw one-byte codes of an 8-bit cache, same index order as view()."""
         c = self.cfg
         return self.pool.view(c["n_layers"], 2, self.n_pages, c["n_kv_heads"], c["page_size"], c["head_dim"])
 
     def gather(self, layer: int, kv: int, pages: Sequence[int], length: int) -> torch.Tensor:
         """Entries 0..length-1 of one sequence as [length, kv_head, head_dim] (layer 0-based)."""
-        v = self.view()[layer, kv]
+        c = self.cfg
+        if self.fp8:
+            raw = self.pool.view(c["n_layers"], 2, self.n_pages, c["n_kv_heads"], c["page_size"], c["head_dim"])[layer, kv]
+            v = raw.view(torch.float8_e4m3fn)
+        else:
+            v = self.view()[layer, kv]
         P = self.cfg["page_size"]
         idx = torch.as_tensor(list(pages)[:(length + P - 1) // P], device=v.device, dtype=torch.long)
         x = v[idx]                                  # [pages, H, P, hd]
         x = x.permute(0, 2, 1, 3).reshape(-1, v.shape[1], v.shape[3])
+        if self.fp8:
+            return x[:length].float() * (c["k_scale"] if kv == 0 else c["v_scale"])
         return x[:length]
 
     def seq_lens(self) -> np.ndarray:

@@ -32,6 +32,7 @@ def _cfg(**kw) -> Dict:
         n_layers=0, d_model=0, n_q_heads=0, n_kv_heads=0, head_dim=0, d_ffn=0, vocab=0,
         dtype=DTYPE_BF16, act=ACT_SILU, rms_eps=1e-5, rope_theta=10000.0,
         rope_theta_local=10000.0, sliding_window=0, global_every=0, page_size=16,
+        kv_dtype=0, k_scale=1.0, v_scale=1.0,     # 0: bf16 cache entries; 1: 8-bit (e4m3) codes of x / scale
     )
     base.update(kw)
     return base

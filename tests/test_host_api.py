@@ -105,6 +105,8 @@ def test_slot_map_errors():
     ({"page_size": 12}, -2), ({"dtype": 7}, -1), ({"act": 5}, -1), ({"rope_theta": 0.0}, -1),
     ({"n_q_heads": 32, "n_kv_heads": 2}, -2),
     ({"vocab": 1 << 20, "d_model": 1024}, -2),     # the LM head would be 2 GiB
+    ({"kv_dtype": 2}, -1), ({"kv_dtype": 1, "k_scale": 0.0}, -1), ({"kv_dtype": 1, "v_scale": float("inf")}, -1),
+    ({"kv_dtype": 1, "k_scale": -1.0}, -1),
 ])
 def test_load_weights_rejects_bad_configs(kw, status):
     st, h, _, _ = fake_model(bf16_cfg(**kw))
@@ -134,6 +136,12 @@ def test_cache_and_workspace_sizes():
     # L * 2 * pages * Hkv * P * hd * 2 bytes
     assert pop.lib.pop_cache_bytes(C.byref(c_cfg), 10) == 8 * 2 * 10 * 2 * 16 * 64 * 2
     assert pop.lib.pop_cache_bytes(C.byref(c_cfg), 0) == 0
+    # an 8-bit cache holds one byte per element; the fp32 checking path keeps fp32 entries either way
+    c8 = pop.make_config(bf16_cfg(kv_dtype=1, k_scale=0.5, v_scale=0.25))
+    assert pop.lib.pop_cache_bytes(C.byref(c8), 10) == 8 * 2 * 10 * 2 * 16 * 64
+    c8f = pop.make_config(dict(bf16_cfg(kv_dtype=1, k_scale=0.5, v_scale=0.25), dtype=0))
+    assert pop.lib.pop_cache_bytes(C.byref(c8f), 10) == 8 * 2 * 10 * 2 * 16 * 64 * 4
+    assert pop.lib.pop_cache_bytes(C.byref(pop.make_config(bf16_cfg(kv_dtype=3))), 10) == 0
     small = pop.pop_workspace_bytes(cfg, 128, 1, 9)
     big = pop.pop_workspace_bytes(cfg, 4096, 8, 300)
     assert 0 < small < big
