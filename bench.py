@@ -11,7 +11,8 @@ Prints ONE JSON line.  Extra objects:
   roofline     -- the dominant kernel (gate|up projection GEMM with fused GLU): algorithmic flops per
                   launch / average launch duration measured with HIP events inside the library on
                   the launch stream, against the bf16 dense MFMA peak.
-  cpu_baseline -- the CPU oracle timed on a bounded sample of the same workload.
+  cpu_baseline -- the CPU oracle timed on the whole headline workload (same weights and tokens; under a minute
+                  on the machine's host cores), or with --cpu-baseline-sample on a bounded sample, scaled.
 """
 from __future__ import annotations
 
@@ -119,9 +120,46 @@ def time_workload(pop, synth, torch, np, model, cfg, lens, l_keep, embeds=None, 
             "end_to_end_frac_of_mfma_peak": fl / (res[l_keep] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
 
 
+def host_weights(cfg, dev_w):
+    """Host copies (bf16 torch CPU tensors in the oracle's layout) of the weights drawn on the GPU."""
+    hd = cfg["head_dim"]
+    dq, dkv, f = cfg["n_q_heads"] * hd, cfg["n_kv_heads"] * hd, cfg["d_ffn"]
+    host = {"embed": dev_w["embed"].cpu(), "lm_head": dev_w["lm_head"].cpu(), "final_norm": dev_w["final_norm"].cpu(),
+            "layers": []}
+    for lw in dev_w["layers"]:
+        qkv, gu = lw["wqkv"].cpu(), lw["w_gate_up"].cpu()
+        host["layers"].append({"norm_in": lw["norm_in"].cpu(), "wq": qkv[:dq], "wk": qkv[dq:dq + dkv], "wv": qkv[dq + dkv:],
+                               "wo": lw["wo"].cpu(), "norm_post": lw["norm_post"].cpu(), "w_gate": gu[:f], "w_up": gu[f:],
+                               "w_down": lw["w_down"].cpu()})
+    return host
+
+
+def cpu_baseline_full(cfg, dev_w, tokens, l_keep, gpu_logits):
+    """The oracle as it stands, timed on the WHOLE workload (every layer, full vocabulary, the same weights and
+    tokens the GPU just ran), on the host's cores.  Also returns how far the GPU's logits are from it."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import pop_oracle as O
+
+    host = host_weights(cfg, dev_w)
+    n = len(tokens)
+    t0 = time.perf_counter()
+    _, _, ref = O.pop_prefill(cfg, host, tokens, l_keep)
+    total = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    err = float(np.max(np.abs(gpu_logits - ref)) / np.max(np.abs(ref)))
+    return {"value": n / total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": (f"measured, not extrapolated: the fp64 numpy oracle on the whole workload ({cfg['n_layers']} layers, "
+                       f"vocabulary {cfg['vocab']}, {n} tokens, L_keep={l_keep}; same weights and tokens as the GPU run) "
+                       f"in {total:.1f} s"),
+            "seconds_per_prompt": total, "gpu_logits_rel_err_vs_oracle": err,
+            "argmax_gpu": int(np.argmax(gpu_logits)), "argmax_oracle": int(np.argmax(ref))}
+
+
 def cpu_baseline(cfg, n, l_keep):
     """The oracle as it stands on a bounded sample: one kept layer, one K/V-only layer and one
-    boundary decode layer (+ LM head) at full width and full prompt length, scaled by layer counts."""
+    boundary decode layer (+ LM head) at full width and full prompt length, scaled by layer counts.
+    (Used for workloads whose full oracle run would take many minutes; the headline workload is timed whole.)"""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import pop_oracle as O
@@ -163,6 +201,8 @@ def main():
     ap.add_argument("--l-keep", type=int, default=24)
     ap.add_argument("--sweep", default="32,28,24,22,20")  # BASELINE sweep + the paper's own ratio (22 of 32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-sample", action="store_true",
+                    help="time the oracle on one kept + one pruned + boundary layer and scale, instead of the whole workload")
     ap.add_argument("--no-ttft-sweep", action="store_true",
                     help="skip the batch-8 time-to-first-token sweep over prompt lengths (Table 2's shape)")
     ap.add_argument("--no-decode", action="store_true",
@@ -195,7 +235,8 @@ def main():
     sweep = sorted({min(int(x), L) for x in args.sweep.split(",")} | {min(args.l_keep, L), L}, reverse=True)
     head = min(args.l_keep, L)
 
-    model = pop.Model(cfg, device_weights(cfg, 1234, torch))
+    dev_w = device_weights(cfg, 1234, torch)
+    model = pop.Model(cfg, dev_w)
     bt, n_pages = synth.make_block_table([n], cfg["page_size"], reserve_pages=1)
     cache = pop.Cache(cfg, n_pages, 1, bt.shape[1])
     ws = pop.alloc_workspace(cfg, n, 1, bt.shape[1])
@@ -211,15 +252,19 @@ def main():
         for _ in range(warmup):
             step(l_keep)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        # exactly `steps` steps between two synchronisations; an event after every step gives each step's own
+        # latency (enqueue to stream idle, back to back), of which the median is reported
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         t0 = time.perf_counter()
-        e0.record(stream)
-        for _ in range(steps):
+        ev[0].record(stream)
+        for i in range(steps):
             step(l_keep)
-        e1.record(stream)
+            ev[i + 1].record(stream)
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3 / steps
-        return e0.elapsed_time(e1) / steps, wall
+        per = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+        median = per[steps // 2] if steps % 2 else 0.5 * (per[steps // 2 - 1] + per[steps // 2])
+        return median, wall, ev[0].elapsed_time(ev[steps]) / steps, per[0], per[-1]
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB
@@ -230,11 +275,16 @@ def main():
 
     results = {}
     for lk in sweep:
-        ms, wall = timed(lk, args.steps, args.warmup)
-        results[lk] = {"ms_per_step": ms, "wall_ms_per_step": wall, "tokens_per_s": n / (ms * 1e-3),
+        ms, wall, mean_ms, min_ms, max_ms = timed(lk, args.steps, args.warmup)
+        results[lk] = {"ms_per_step": ms, "ms_per_step_is": "median of the timed steps", "mean_ms_per_step": mean_ms,
+                       "min_ms_per_step": min_ms, "max_ms_per_step": max_ms,
+                       "wall_ms_per_step": wall, "tokens_per_s": n / (ms * 1e-3),
                        "algorithmic_tflop": algorithmic_flops(cfg, n, lk) / 1e12,
                        "end_to_end_frac_of_mfma_peak": algorithmic_flops(cfg, n, lk) / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
     full_ms = results[L]["ms_per_step"]
+    step(head)                   # the headline configuration's logits, for the comparison with the oracle below
+    torch.cuda.synchronize()
+    head_logits = logits[0].cpu().numpy()
     for lk in sweep:
         results[lk]["speedup_vs_full_depth"] = full_ms / results[lk]["ms_per_step"]
 
@@ -438,7 +488,9 @@ def main():
         torch.cuda.empty_cache()
         out["other_workloads"] = other
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, n, head)
+        # the headline workload is timed whole (under a minute on the machine's host); other shapes on a sample, scaled
+        whole = not args.cpu_baseline_sample and args.config == "llama8b" and n <= 2048
+        out["cpu_baseline"] = cpu_baseline_full(cfg, dev_w, tokens, head, head_logits) if whole else cpu_baseline(cfg, n, head)
     print(json.dumps(out))
 
 

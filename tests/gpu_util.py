@@ -74,3 +74,29 @@ def compare_with_oracle(run: DeviceRun, W, tokens, l_keep, gpu_logits, embeds=No
         if gap > 2 * abs_err:
             assert int(np.argmax(gpu_logits[b])) == int(top[1]), f"argmax differs for sequence {b}"
     return worst, outs
+
+
+def oracle_pop_prefill_with_progress(cfg, W, tokens, l_keep, embeds=None, embed_ranges=(), progress=None):
+    """O.pop_prefill for one prompt, driven layer by layer from here so that a long run (tens of layers at
+    thousands of tokens take minutes on the host) can report after every layer: the same oracle steps in the same
+    order (body rows through kept / K/V-only layers, then the last token as a full decode step), nothing else.
+    tests/test_oracle_pins.py checks that it returns exactly what O.pop_prefill returns."""
+    n = len(tokens)
+    h = O.embed_rows(W, tokens, np.float64, embeds, embed_ranges)
+    L, hkv, hd = cfg["n_layers"], cfg["n_kv_heads"], cfg["head_dim"]
+    pos = np.arange(n - 1)
+    empty = np.zeros((0, hkv, hd))
+    x, xl = h[:n - 1], h[n - 1][None, :]
+    Kc, Vc = [], []
+    for l in range(1, L + 1):
+        lw = W["layers"][l - 1]
+        if l <= l_keep:
+            x, K, V = O.kept_layer_rows(cfg, lw, l, x, pos, empty, empty)
+        else:
+            x, K, V = O.kv_only_rows(cfg, lw, l, x, pos)
+        xl, K, V = O.kept_layer_rows(cfg, lw, l, xl, np.array([n - 1]), K, V)
+        Kc.append(K)
+        Vc.append(V)
+        if progress is not None:
+            progress(l)
+    return Kc, Vc, O.lm_head_logits(cfg, W, xl)[0]

@@ -690,3 +690,20 @@ def test_all_gates_zero_is_lm_head_of_the_embedding_and_gates_are_stage_specific
     assert np.array_equal(Kp[1][n - 1], K0[1][n - 1])          # the boundary token is a decode-stage token
     assert all(np.array_equal(a[:n - 1], b[:n - 1]) for a, b in zip(Kd + Vd, K0 + V0))
     assert not np.allclose(Kd[2][n - 1], K0[2][n - 1])
+
+
+def test_layerwise_driver_of_the_gpu_tests_is_pop_prefill():
+    """The GPU tests drive the oracle layer by layer for long runs (to report progress); that driver must return
+    exactly what O.pop_prefill returns, also with supplied embedding rows and a sliding window."""
+    from tests.gpu_util import oracle_pop_prefill_with_progress
+    cfg = small_cfg(sliding_window=5, global_every=2, rope_theta_local=50.0)
+    w = weights(cfg)
+    tokens = synth.make_tokens(cfg["vocab"], 14, seed=9)
+    emb = synth.make_visual_embeds(4, cfg["d_model"], seed=2).numpy() * 0.1
+    seen = []
+    for l_keep in (0, 2, 4):
+        a = O.pop_prefill(cfg, w, tokens, l_keep, embeds=emb, embed_ranges=[(3, 4)])
+        b = oracle_pop_prefill_with_progress(cfg, w, tokens, l_keep, emb, [(3, 4)], progress=seen.append)
+        assert np.array_equal(a[2], b[2])
+        assert all(np.array_equal(x, y) for x, y in zip(a[0], b[0])) and all(np.array_equal(x, y) for x, y in zip(a[1], b[1]))
+    assert seen == [1, 2, 3, 4] * 3
