@@ -190,7 +190,7 @@ struct Workspace {
   // int32 meta (one upload per call)
   size_t meta_bytes;
   size_t o_tokens, o_row_src, o_pos, o_slot, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start, o_ta_start2,
-      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_kv_first, o_wl_full, o_wl_tail, o_kvd_full, o_kvd_tail, o_tr_row, o_tr_pos, o_tr_slot,
+      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_kv_first, o_wl_full, o_wl_tail, o_kvd_full, o_kvd_tail, o_vt_col, o_tr_row, o_tr_pos, o_tr_slot,
       o_tr_cu, o_tr_t64_seq, o_tr_t64_start;
   // device buffers
   size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_cs_tail, o_a_multi, o_kv_out, o_ss_parts;
@@ -236,6 +236,7 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_wl_tail = take(8 * (size_t)c.n_layers);
   w.o_kvd_full = take(sizeof(pop::KvDest) * (size_t)c.n_layers);
   w.o_kvd_tail = take(sizeof(pop::KvDest) * (size_t)c.n_layers);
+  w.o_vt_col = take(4 * (size_t)T);
   w.o_tr_row = take(4 * (size_t)T);
   w.o_tr_pos = take(4 * (size_t)T);
   w.o_tr_slot = take(4 * (size_t)T);
@@ -1092,7 +1093,10 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   for (int b = 0; b < B; ++b) {
     const int s0 = a->cu_seqlens[b], len = a->cu_seqlens[b + 1] - s0;
     max_len = std::max(max_len, len);
-    for (int t = 0; t < len; ++t) mi(w.o_pos)[s0 + t] = t;
+    for (int t = 0; t < len; ++t) {
+      mi(w.o_pos)[s0 + t] = t;
+      mi(w.o_vt_col)[s0 + t] = Tp + t;      // column of the row in the transposed V copy
+    }
     mi(w.o_vt_off)[b] = Tp;
     Tp += (int)round_up(len, 64);
     for (int p0 = 0; p0 < len; p0 += 64) {
@@ -1203,7 +1207,26 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   // to the updated h, its rows times the following norm's scale as bf16 (into abuf) and partial sums of squares;
   // the QKV and gate|up projections read those rows and multiply their result rows by rstd.  folded_gamma is the
   // norm scale abuf / ss_parts currently stand for (nullptr: they do not hold h).
+#ifdef POP_NO_FOLD_NORMS      // (experiments only: a build without the folding, for A/B timing)
+  const bool fold_norms = false;
+#else
   const bool fold_norms = d % 256 == 0 && T > 512;   // (the partial sums are read four at a time)
+#endif
+  // RoPE, the cache append and the transposed V copy in the QKV projection's epilogue instead of a kernel of their
+  // own: same row threshold (the epilogue belongs to the one-pass 256 x 192 tiles), layers without per-head QK-norm
+  // (that needs a head's sum of squares before the rotation).  The epilogue writes only the columns of vT that
+  // belong to a row; the padding up to a multiple of 64 columns per sequence, which the attention kernel reads and
+  // multiplies by zero weights, is cleared once per call.
+#ifdef POP_NO_QKV_ROPE_EPILOGUE
+  const bool qkv_epilogue = false;
+#else
+  const bool qkv_epilogue = T > 512 && pop::gemm_qkv_rope_supported(hd);
+#endif
+  if (qkv_epilogue) {
+    bool any = false;
+    for (int l = 1; l <= cfg.n_layers; ++l) any |= !plan.pruned[l] && !m->layers[l - 1].q_norm;
+    if (any) pop::launch_fill_zero(vT, 2 * (size_t)Dkv * (size_t)w.Tp_max, st);
+  }
   float* ss_parts = at<float>(ws, w.o_ss_parts);
   const float* folded_gamma = nullptr;
   auto kept_layer = [&](int l) -> pop_status {
@@ -1235,19 +1258,32 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     g.M = T; g.N = Dqkv; g.K = d; g.epilogue = pop::EPI_STORE_F16;
     g.splitk_ws = w.splitk_bytes ? at<float>(ws, w.o_splitk) : nullptr;
     g.splitk_ws_bytes = w.splitk_bytes;
+    const bool fused_append = qkv_epilogue && !lw.q_norm && !lw.k_norm;
+    if (fused_append) {
+      g.epilogue = pop::EPI_QKV_ROPE;
+      g.qr.qk_out = qkv; g.qr.ld = Dqkv;
+      g.qr.n_q_heads = cfg.n_q_heads; g.qr.n_kv_heads = cfg.n_kv_heads; g.qr.hd = hd;
+      g.qr.cs = glob ? cs_g : cs_l;
+      g.qr.slot = d_slot;
+      g.qr.vt_col = at<int32_t>(ws, w.o_vt_col);
+      g.qr.k_pool = c->k_pool(l - 1); g.qr.v_pool = c->v_pool(l - 1);
+      g.qr.page_size = P;
+      g.qr.vT = vT; g.qr.Tp = Tp;
+      g.qr.kvq = kv_quant(cfg);
+    }
     {
       StepTimer tm(m, st, POP_STEP_QKV_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "QKV")) return s;
     }
     g.a_parts = nullptr;
-    rw.qkv = qkv; rw.ld = Dqkv; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
-    rw.cs = glob ? cs_g : cs_l;
-    rw.q_gamma = (const float*)lw.q_norm; rw.k_gamma = (const float*)lw.k_norm; rw.qk_eps = cfg.rms_eps;
-    rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
-    rw.vT = vT;
-    rw.fp16_inplace = 1;
-    rw.fp16_input = 1;
-    {
+    if (!fused_append) {
+      rw.qkv = qkv; rw.ld = Dqkv; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
+      rw.cs = glob ? cs_g : cs_l;
+      rw.q_gamma = (const float*)lw.q_norm; rw.k_gamma = (const float*)lw.k_norm; rw.qk_eps = cfg.rms_eps;
+      rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
+      rw.vT = vT;
+      rw.fp16_inplace = 1;
+      rw.fp16_input = 1;
       StepTimer tm(m, st, POP_STEP_ROPE_WRITE);
       pop::launch_rope_write(rw, st);
     }

@@ -75,11 +75,30 @@ struct GemmParams {
   const float* a_parts;     // consumer: [M, a_nparts], nullptr = off
   int a_nparts;
   float a_eps;
+  QkvRope qr;               // EPI_QKV_ROPE
 };
+
+// EPI_QKV_ROPE: which rows of W a column tile stages.  The epilogue rotates pairs (x_i, x_{i + hd/2}) of a head
+// in-lane, so the two 16-column blocks that hold the halves of a pair must be blocks b and b + NB/2 of the same
+// wave tile whatever the tile width.  The output columns of the whole projection are therefore cut into "slots" of
+// two 16-row blocks of W: for a query or key head, 16 rows of its low half and the 16 partner rows of its high
+// half (hd / 32 slots per head; W's rows are ordered q | k | v, so query and key heads are simply heads
+// 0 .. Hq + Hkv - 1); for V, 32 consecutive rows.  A wave tile of NB blocks holds NB / 2 consecutive slots: its
+// first NB / 2 blocks their low blocks, the others their high blocks.  Returns the W row of row r16 of the low
+// (is_hi = 0) or high block of slot s, or -1 beyond the last slot.
+__device__ __forceinline__ int qkv_slot_w_row(int s, int is_hi, int r16, int hd, int n_rot_heads, int n_kv_heads) {
+  const int hb = hd >> 5;
+  const int n_rot = n_rot_heads * hb;
+  if (s < n_rot) return (s / hb) * hd + (s % hb) * 16 + is_hi * (hd >> 1) + r16;
+  const int j = s - n_rot;
+  if (j >= n_kv_heads * hb) return -1;
+  return n_rot_heads * hd + j * 32 + is_hi * 16 + r16;
+}
+
 
 // Template values of the KV-cache epilogue (EPI_KV_CACHE of the interface), one per head_dim: the offset between
 // the two halves of a head decides which accumulator registers are RoPE partners, so it must be a constant.
-constexpr int EPI_KV64 = 5, EPI_KV128 = 6, EPI_KV256 = 7;
+constexpr int EPI_KV64 = 1064, EPI_KV128 = 1128, EPI_KV256 = 1256;   // (apart from the interface's values)
 constexpr bool epi_is_kv(int e) { return e == EPI_KV64 || e == EPI_KV128 || e == EPI_KV256; }
 constexpr int epi_kv_hd(int e) { return e == EPI_KV64 ? 64 : e == EPI_KV128 ? 128 : 256; }
 
@@ -109,6 +128,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // wave-loads per stage and wave
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/wave mismatch");
   static_assert(EPI != EPI_GLU_BF16 || NB % 2 == 0, "GLU needs an even number of column blocks");
+  static_assert(EPI != EPI_QKV_ROPE || NB % 2 == 0, "rotation pairs need an even number of column blocks");
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -173,6 +193,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
       const int oc = n0 + w2 * (WTN / 2) + (r % (WTN / 2));
       ok = oc < p.N;
       wrow = up * p.N + oc;
+    } else if (EPI == EPI_QKV_ROPE) {
+      const int w2 = jn / WTN, r = jn % WTN, b = r >> 4;               // wave tile, block inside it
+      const int slot = ((p.n_tile0 + tn) * WGN + w2) * (NB / 2) + b % (NB / 2);
+      wrow = qkv_slot_w_row(slot, b / (NB / 2), r & 15, p.qr.hd, p.qr.n_q_heads + p.qr.n_kv_heads, p.qr.n_kv_heads);
+      ok = wrow >= 0;
     } else {
       wrow = n0 + jn;
       ok = wrow < p.N;
@@ -228,6 +253,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
         const int oc = n0 + w2 * (WTN / 2) + (r % (WTN / 2));
         ok = ok && oc < p.N;
         wrow = (r >= WTN / 2 ? p.N : 0) + oc;
+      } else if (EPI == EPI_QKV_ROPE) {
+        const int w2 = jn / WTN, r = jn % WTN, b = r >> 4;
+        const int slot = ((p.n_tile0 + tn) * WGN + w2) * (NB / 2) + b % (NB / 2);
+        wrow = qkv_slot_w_row(slot, b / (NB / 2), r & 15, p.qr.hd, p.qr.n_q_heads + p.qr.n_kv_heads, p.qr.n_kv_heads);
+        ok = ok && wrow >= 0;
       } else {
         wrow = n0 + jn;
         ok = ok && wrow < p.N;
@@ -283,10 +313,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
       const int row = m0 + r;
       float ssum = 0.f;
       if (row < p.M) {
+        // eight 16-byte loads are requested before the first addition (a loop of dependent loads would pay the
+        // memory latency once per load: measured 5 us per tile)
         const float4* pp = reinterpret_cast<const float4*>(p.a_parts + (long long)row * p.a_nparts);
-        for (int i = 0; i < (p.a_nparts >> 2); ++i) {
-          const float4 v = pp[i];
-          ssum += (v.x + v.y) + (v.z + v.w);
+        const int n4 = p.a_nparts >> 2;
+        for (int i0 = 0; i0 < n4; i0 += 8) {
+          float4 v[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) v[i] = pp[min(i0 + i, n4 - 1)];
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            if (i0 + i < n4) ssum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
         }
       }
       row_rstd[r] = rsqrtf(ssum / (float)p.K + p.a_eps);
@@ -516,6 +553,99 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
       }
     }
    }
+  } else if (EPI == EPI_QKV_ROPE) {
+   if constexpr (EPI == EPI_QKV_ROPE) {
+    // K/V generation and cache append of Sec. 2.1 on the accumulators.  Wave tile = NB / 2 slots (see
+    // qkv_slot_w_row): block sl holds 16 low-half dims of a head (or 16 V dims), block sl + NB / 2 the partner
+    // high-half dims (or the next 16 V dims), for the same rows, in the same lane and register slot.
+    constexpr int NS = NB / 2;
+    const QkvRope& q = p.qr;
+    const int hd = q.hd, half = hd >> 1, hb = hd >> 5;
+    const int n_rot = (q.n_q_heads + q.n_kv_heads) * hb, n_slots = n_rot + q.n_kv_heads * hb;
+    const int slot0 = ((p.n_tile0 + tn) * WGN + wn) * NS;
+    const int P = q.page_size;
+    const bool fp8 = q.kvq.fp8 != 0;
+    const long long esz = fp8 ? 1 : 2;
+#pragma unroll
+    for (int j = 0; j < MB; ++j) {
+      const int m = m_lane + j * 16;
+      if (m >= p.M) continue;
+      const float rs = p.a_parts ? row_rstd[wm * WTM + j * 16 + frag_row] : 1.f;   // folded normalisation of A
+      const int cslot = q.slot[m];
+      const long long page_base = (long long)(cslot / P) * q.n_kv_heads * P * hd + (long long)(cslot % P) * hd;
+      const float2* csm = q.cs + (long long)m * half;
+      const long long vcol = q.vt_col[m];
+#pragma unroll
+      for (int sl = 0; sl < NS; ++sl) {
+        const int s = slot0 + sl;                 // wave-uniform
+        if (s >= n_slots) continue;
+        float a[4], b[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { a[e] = acc[sl][j][e] * rs; b[e] = acc[sl + NS][j][e] * rs; }
+        if (s < n_rot) {
+          const int head = s / hb, d0 = (s % hb) * 16 + frag_hi * 4;       // dims d0 .. d0+3 and their partners
+          const float4 c01 = *reinterpret_cast<const float4*>(csm + d0), c23 = *reinterpret_cast<const float4*>(csm + d0 + 2);
+          const float cc[4] = {c01.x, c01.z, c23.x, c23.z}, sn[4] = {c01.y, c01.w, c23.y, c23.w};
+          float lo[4], hi[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            lo[e] = a[e] * cc[e] - b[e] * sn[e];
+            hi[e] = b[e] * cc[e] + a[e] * sn[e];
+          }
+          const bool is_k = head >= q.n_q_heads;
+          if (is_k) {
+            const int kh = head - q.n_q_heads;
+            char* dst = reinterpret_cast<char*>(q.k_pool) + (page_base + (long long)kh * P * hd + d0) * esz;
+            if (fp8) {
+              // an 8-bit cache: store the codes; the attention kernel gets the values they stand for
+              const uint32_t cl = e4m3_pack4(lo[0] * q.kvq.k_inv, lo[1] * q.kvq.k_inv, lo[2] * q.kvq.k_inv, lo[3] * q.kvq.k_inv);
+              const uint32_t ch = e4m3_pack4(hi[0] * q.kvq.k_inv, hi[1] * q.kvq.k_inv, hi[2] * q.kvq.k_inv, hi[3] * q.kvq.k_inv);
+              *reinterpret_cast<uint32_t*>(dst) = cl;
+              *reinterpret_cast<uint32_t*>(dst + half) = ch;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                lo[e] = e4m3_decode((cl >> (8 * e)) & 0xffu) * q.kvq.k_scale;
+                hi[e] = e4m3_decode((ch >> (8 * e)) & 0xffu) * q.kvq.k_scale;
+              }
+            } else {
+              *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
+              *reinterpret_cast<uint2*>(dst + half * 2) = make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
+            }
+          }
+          bf16_t* o = q.qk_out + (long long)m * q.ld + head * hd + d0;
+          *reinterpret_cast<uint2*>(o) = make_uint2(pack_f16x2(lo[0], lo[1]), pack_f16x2(lo[2], lo[3]));
+          *reinterpret_cast<uint2*>(o + half) = make_uint2(pack_f16x2(hi[0], hi[1]), pack_f16x2(hi[2], hi[3]));
+        } else {
+          // V: dims c0 .. c0+3 of kv head kh (block sl) and c0+16 .. c0+19 (block sl + NS)
+          const int vc = (s - n_rot) * 32 + frag_hi * 4;
+          const int kh = vc / hd, c0 = vc % hd;
+          char* dst = reinterpret_cast<char*>(q.v_pool) + (page_base + (long long)kh * P * hd + c0) * esz;
+          if (fp8) {
+            const uint32_t ca = e4m3_pack4(a[0] * q.kvq.v_inv, a[1] * q.kvq.v_inv, a[2] * q.kvq.v_inv, a[3] * q.kvq.v_inv);
+            const uint32_t cb = e4m3_pack4(b[0] * q.kvq.v_inv, b[1] * q.kvq.v_inv, b[2] * q.kvq.v_inv, b[3] * q.kvq.v_inv);
+            *reinterpret_cast<uint32_t*>(dst) = ca;
+            *reinterpret_cast<uint32_t*>(dst + 16) = cb;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              a[e] = e4m3_decode((ca >> (8 * e)) & 0xffu) * q.kvq.v_scale;
+              b[e] = e4m3_decode((cb >> (8 * e)) & 0xffu) * q.kvq.v_scale;
+            }
+          } else {
+            *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
+            *reinterpret_cast<uint2*>(dst + 32) = make_uint2(pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3]));
+          }
+          // transposed fp16 copy for the attention kernel: vT[kh][dim][column of this row]; the 16 lanes that
+          // share frag_hi hold 16 consecutive rows, i.e. 32 contiguous bytes of one dim
+          bf16_t* vt = q.vT + ((long long)kh * hd + c0) * q.Tp + vcol;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            vt[(long long)e * q.Tp] = f32_to_f16_sat(a[e]);
+            vt[(long long)(e + 16) * q.Tp] = f32_to_f16_sat(b[e]);
+          }
+        }
+      }
+    }
+   }
   } else if (EPI == EPI_ADD_F32) {
     // out += C.  The old values are requested sixteen 16x16 blocks at a time, without branches (a lane whose
     // four columns are not all inside reads the first element of the matrix instead), so that the loads
@@ -649,6 +779,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_
   p.kvq = g.kvq;
   p.nrm_gamma = g.nrm_gamma; p.nrm_out = g.nrm_out; p.nrm_parts = g.nrm_parts;
   p.a_parts = g.a_parts; p.a_nparts = g.a_nparts; p.a_eps = g.a_eps;
+  p.qr = g.qr;
   p.tiles_m = (g.M + BM - 1) / BM;
   p.tiles_n = n_tiles >= 0 ? n_tiles : (g.N + BN_OUT - 1) / BN_OUT;
   p.n_tile0 = n_tile0;
@@ -801,7 +932,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // the rows fit one 64-row tile and the launch would leave CUs idle.
 inline int choose_split(const GemmArgs& g) {
   if (!g.splitk_ws || g.batch > 1 || g.W_list || g.epilogue == EPI_GLU_BF16 || g.epilogue == EPI_KV_CACHE) return 1;
-  if (g.nrm_gamma || g.a_parts) return 1;   // the folded normalisation lives in the one-pass epilogues
+  if (g.nrm_gamma || g.a_parts || g.epilogue == EPI_QKV_ROPE) return 1;   // these live in the one-pass epilogues
   if (g.M > 512 || g.N % 4 || g.K % BK || (reinterpret_cast<uintptr_t>(g.splitk_ws) & 15)) return 1;
   // Building with -DPOP_FORCE_SPLITK=S forces S parts where the problem allows it (experiments only).
 #ifdef POP_FORCE_SPLITK
@@ -837,7 +968,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.K <= 0 || g.K % 8 || g.lda % 8 || g.ldw % 8 || g.ldc % 4) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.W) |
-       (g.epilogue == EPI_KV_CACHE ? 0 : reinterpret_cast<uintptr_t>(g.out))) & 15)
+       (g.epilogue == EPI_KV_CACHE || g.epilogue == EPI_QKV_ROPE ? 0 : reinterpret_cast<uintptr_t>(g.out))) & 15)
     return hipErrorInvalidValue;
   if (g.nrm_gamma && (g.epilogue != EPI_ADD_F32 || g.N % 64 || !g.nrm_out || !g.nrm_parts || g.batch > 1))
     return hipErrorInvalidValue;
@@ -896,9 +1027,20 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
       if (g.kv_hd == 64) return launch_cfg<256, 256, 2, 2, 2, EPI_KV64>(g, st);
       if (g.kv_hd == 128) return launch_cfg<256, 256, 2, 2, 2, EPI_KV128>(g, st);
       return launch_cfg<256, 256, 4, 1, 2, EPI_KV256>(g, st);
+    case EPI_QKV_ROPE: {
+      // 192-column tiles (six slots of 32 output columns each), 2 x 2 waves: the shape that puts the
+      // Llama-3.1-8B QKV projection at 2048 rows on the chip in one round
+      const QkvRope& q = g.qr;
+      if (!gemm_qkv_rope_supported(q.hd) || g.N != (q.n_q_heads + 2 * q.n_kv_heads) * q.hd || !q.qk_out || !q.cs ||
+          !q.slot || !q.vt_col || !q.k_pool || !q.v_pool || !q.vT || q.page_size < 1 || q.ld % 4)
+        return hipErrorInvalidValue;
+      return launch_cfg<256, 192, 2, 2, 2, EPI_QKV_ROPE>(g, st);
+    }
   }
   return hipErrorInvalidValue;
 }
+
+bool gemm_qkv_rope_supported(int hd) { return hd >= 32 && hd % 32 == 0; }
 
 bool gemm_kv_cache_supported(int n_kv_heads, int hd) {
   if (hd != 64 && hd != 128 && hd != 256) return false;

@@ -112,6 +112,9 @@ def main():
                     help="8-bit (e4m3) cache with these per-tensor scales, in both passes")
     ap.add_argument("--only", default="", help="comma-separated rounding points to enable instead of all of them "
                                                "(a, o, m, u, kv, lm): the contribution of one source")
+    ap.add_argument("--visual", type=int, nargs=2, metavar=("FIRST", "COUNT"), default=None,
+                    help="positions FIRST .. FIRST+COUNT-1 take supplied hidden-state rows ~ N(0, 1) (seed 2) instead "
+                         "of embedding rows, as in the Qwen3-VL-style workload")
     ap.add_argument("--weights-bf16", action="store_true", help="round the weights to bf16 (shapes stated in fp32)")
     args = ap.parse_args()
     over = {"n_layers": args.layers} if args.layers else {}
@@ -122,13 +125,17 @@ def main():
     cfg = synth.get_config(args.shape, **over)
     L, n, l_keep = cfg["n_layers"], args.tokens, args.l_keep
     assert 0 <= l_keep <= L and n >= 2
+    points = tuple(p for p in args.only.split(",") if p) or ALL_POINTS
+    assert all(p in ALL_POINTS for p in points), points
     out = args.out or os.path.join(os.path.dirname(os.path.abspath(__file__)),
                                    f"bf16_input_floor_{args.shape}_{n}_lkeep{l_keep}_of_{L}{'_kvfp8' if args.kv_fp8 else ''}{'_only_' + '_'.join(points) if args.only else ''}.txt")
     W = synth.make_weights(cfg, seed=args.seed, layers=False)
     tokens = synth.make_tokens(cfg["vocab"], n, seed=1)
-    h0 = O.embed_rows(W, tokens, np.float64)
-    points = tuple(p for p in args.only.split(",") if p) or ALL_POINTS
-    assert all(p in ALL_POINTS for p in points), points
+    if args.visual:
+        emb = synth.make_visual_embeds(args.visual[1], cfg["d_model"], seed=2).numpy()
+        h0 = O.embed_rows(W, tokens, np.float64, emb, [(args.visual[0], args.visual[1])])
+    else:
+        h0 = O.embed_rows(W, tokens, np.float64)
     hkv, hd = cfg["n_kv_heads"], cfg["head_dim"]
     empty = np.zeros((0, hkv, hd))
     body_pos, last_pos = np.arange(n - 1), np.array([n - 1])
