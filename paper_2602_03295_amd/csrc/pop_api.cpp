@@ -190,10 +190,10 @@ struct Workspace {
   // int32 meta (one upload per call)
   size_t meta_bytes;
   size_t o_tokens, o_row_src, o_pos, o_slot, o_cu, o_vt_off, o_t64_seq, o_t64_start, o_ta_seq, o_ta_start, o_ta_start2,
-      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_kv_first, o_wl_full, o_wl_tail, o_kvd_full, o_kvd_tail, o_vt_col, o_tr_row, o_tr_pos, o_tr_slot,
+      o_bnd_row, o_bnd_pos, o_bnd_slot, o_bt, o_kv_first, o_wl_full, o_wl_tail, o_kvd_full, o_kvd_tail, o_tr_row, o_tr_pos, o_tr_slot,
       o_tr_cu, o_tr_t64_seq, o_tr_t64_start;
   // device buffers
-  size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_cs_tail, o_a_multi, o_kv_out, o_ss_parts;
+  size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_cs_tail, o_a_multi, o_kv_out;
   size_t o_xb, o_ab, o_qkvb, o_qb, o_attnb, o_ub, o_part, o_splitk;
   size_t splitk_bytes;
   size_t total;
@@ -236,7 +236,6 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_wl_tail = take(8 * (size_t)c.n_layers);
   w.o_kvd_full = take(sizeof(pop::KvDest) * (size_t)c.n_layers);
   w.o_kvd_tail = take(sizeof(pop::KvDest) * (size_t)c.n_layers);
-  w.o_vt_col = take(4 * (size_t)T);
   w.o_tr_row = take(4 * (size_t)T);
   w.o_tr_pos = take(4 * (size_t)T);
   w.o_tr_slot = take(4 * (size_t)T);
@@ -256,8 +255,6 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   const size_t rc = std::min(kKvChunk, c.n_layers);
   w.o_a_multi = take(2 * rc * (size_t)T * d);
   w.o_kv_out = take(2 * rc * (size_t)T * 2 * Dkv);
-  // partial sums of squares of the rows of h per 64-column group (normalisation folded into the projections)
-  w.o_ss_parts = take(4 * (size_t)T * ((d + 63) / 64));
   w.o_xb = take(4 * (size_t)B * d);
   w.o_ab = take(2 * (size_t)B * std::max(d, Dq));
   w.o_qkvb = take(4 * (size_t)B * Dqkv);
@@ -1093,10 +1090,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   for (int b = 0; b < B; ++b) {
     const int s0 = a->cu_seqlens[b], len = a->cu_seqlens[b + 1] - s0;
     max_len = std::max(max_len, len);
-    for (int t = 0; t < len; ++t) {
-      mi(w.o_pos)[s0 + t] = t;
-      mi(w.o_vt_col)[s0 + t] = Tp + t;      // column of the row in the transposed V copy
-    }
+    for (int t = 0; t < len; ++t) mi(w.o_pos)[s0 + t] = t;
     mi(w.o_vt_off)[b] = Tp;
     Tp += (int)round_up(len, 64);
     for (int p0 = 0; p0 < len; p0 += 64) {
@@ -1202,88 +1196,33 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   rw.kvq = kv_quant(cfg);
 
   // ---- a kept layer over all given rows (Sec. 2.1)
-  // The two normalisations of a layer are folded into the projections around them when there are enough rows for
-  // the one-pass GEMM epilogues (a split of K is only used at <= 512 rows): the O and down projections store, next
-  // to the updated h, its rows times the following norm's scale as bf16 (into abuf) and partial sums of squares;
-  // the QKV and gate|up projections read those rows and multiply their result rows by rstd.  folded_gamma is the
-  // norm scale abuf / ss_parts currently stand for (nullptr: they do not hold h).
-#ifdef POP_NO_FOLD_NORMS      // (experiments only: a build without the folding, for A/B timing)
-  const bool fold_norms = false;
-#else
-  const bool fold_norms = d % 256 == 0 && T > 512;   // (the partial sums are read four at a time)
-#endif
-  // RoPE, the cache append and the transposed V copy in the QKV projection's epilogue instead of a kernel of their
-  // own: same row threshold (the epilogue belongs to the one-pass 256 x 192 tiles), layers without per-head QK-norm
-  // (that needs a head's sum of squares before the rotation).  The epilogue writes only the columns of vT that
-  // belong to a row; the padding up to a multiple of 64 columns per sequence, which the attention kernel reads and
-  // multiplies by zero weights, is cleared once per call.
-#ifdef POP_NO_QKV_ROPE_EPILOGUE
-  const bool qkv_epilogue = false;
-#else
-  const bool qkv_epilogue = T > 512 && pop::gemm_qkv_rope_supported(hd);
-#endif
-  if (qkv_epilogue) {
-    bool any = false;
-    for (int l = 1; l <= cfg.n_layers; ++l) any |= !plan.pruned[l] && !m->layers[l - 1].q_norm;
-    if (any) pop::launch_fill_zero(vT, 2 * (size_t)Dkv * (size_t)w.Tp_max, st);
-  }
-  float* ss_parts = at<float>(ws, w.o_ss_parts);
-  const float* folded_gamma = nullptr;
   auto kept_layer = [&](int l) -> pop_status {
     const pop_layer_weights& lw = m->layers[l - 1];
     const bool glob = layer_is_global(cfg, l);
+    {
+      StepTimer tm(m, st, POP_STEP_NORM);
+      pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_in, abuf, nullptr, T, d, cfg.rms_eps, st);
+    }
     pop::GemmArgs g{};
     g.batch = 1;
-    auto normed_input = [&](const float* gamma) {   // abuf := the projection's input; sets g.a_parts if folded
-      if (fold_norms && folded_gamma == gamma) {
-        g.a_parts = ss_parts; g.a_nparts = d / 64; g.a_eps = cfg.rms_eps;
-      } else {
-        StepTimer tm(m, st, POP_STEP_NORM);
-        pop::launch_rmsnorm(h, nullptr, nullptr, gamma, abuf, nullptr, T, d, cfg.rms_eps, st);
-        g.a_parts = nullptr;
-      }
-      folded_gamma = nullptr;   // abuf is about to be consumed
-    };
-    auto fold_next = [&](const float* gamma) {      // the residual projection about to run also prepares `gamma`
-      g.nrm_gamma = nullptr;
-      if (fold_norms && gamma) {
-        g.nrm_gamma = gamma; g.nrm_out = abuf; g.nrm_parts = ss_parts;
-        folded_gamma = gamma;
-      }
-    };
-    normed_input((const float*)lw.norm_in);
     g.A = abuf; g.lda = d; g.W = (const bf16_t*)lw.wqkv; g.ldw = d; g.out = qkv; g.ldc = Dqkv;
     // q, k, v leave the GEMM as fp16: they only feed the RoPE/append and attention kernels, and fp16
     // keeps three more mantissa bits than bf16 for the score contraction (the cache itself is bf16)
     g.M = T; g.N = Dqkv; g.K = d; g.epilogue = pop::EPI_STORE_F16;
     g.splitk_ws = w.splitk_bytes ? at<float>(ws, w.o_splitk) : nullptr;
     g.splitk_ws_bytes = w.splitk_bytes;
-    const bool fused_append = qkv_epilogue && !lw.q_norm && !lw.k_norm;
-    if (fused_append) {
-      g.epilogue = pop::EPI_QKV_ROPE;
-      g.qr.qk_out = qkv; g.qr.ld = Dqkv;
-      g.qr.n_q_heads = cfg.n_q_heads; g.qr.n_kv_heads = cfg.n_kv_heads; g.qr.hd = hd;
-      g.qr.cs = glob ? cs_g : cs_l;
-      g.qr.slot = d_slot;
-      g.qr.vt_col = at<int32_t>(ws, w.o_vt_col);
-      g.qr.k_pool = c->k_pool(l - 1); g.qr.v_pool = c->v_pool(l - 1);
-      g.qr.page_size = P;
-      g.qr.vT = vT; g.qr.Tp = Tp;
-      g.qr.kvq = kv_quant(cfg);
-    }
     {
       StepTimer tm(m, st, POP_STEP_QKV_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "QKV")) return s;
     }
-    g.a_parts = nullptr;
-    if (!fused_append) {
-      rw.qkv = qkv; rw.ld = Dqkv; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
-      rw.cs = glob ? cs_g : cs_l;
-      rw.q_gamma = (const float*)lw.q_norm; rw.k_gamma = (const float*)lw.k_norm; rw.qk_eps = cfg.rms_eps;
-      rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
-      rw.vT = vT;
-      rw.fp16_inplace = 1;
-      rw.fp16_input = 1;
+    rw.qkv = qkv; rw.ld = Dqkv; rw.q_col = 0; rw.k_col = Dq; rw.v_col = Dq + Dkv;
+    rw.cs = glob ? cs_g : cs_l;
+    rw.q_gamma = (const float*)lw.q_norm; rw.k_gamma = (const float*)lw.k_norm; rw.qk_eps = cfg.rms_eps;
+    rw.k_pool = c->k_pool(l - 1); rw.v_pool = c->v_pool(l - 1);
+    rw.vT = vT;
+    rw.fp16_inplace = 1;
+    rw.fp16_input = 1;
+    {
       StepTimer tm(m, st, POP_STEP_ROPE_WRITE);
       pop::launch_rope_write(rw, st);
     }
@@ -1302,25 +1241,23 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     g.A = attn; g.lda = Dq; g.W = (const bf16_t*)lw.wo; g.ldw = Dq; g.out = h; g.ldc = d;
     g.M = T; g.N = d; g.K = Dq; g.epilogue = pop::EPI_ADD_F32;
     g.scaled = a->gates != nullptr; g.scale = a->gates ? a->gates[l - 1] : 1.f;   // virtual gate of the layer
-    fold_next((const float*)lw.norm_post);
     {
       StepTimer tm(m, st, POP_STEP_O_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "O")) return s;
     }
-    g.nrm_gamma = nullptr;
-    normed_input((const float*)lw.norm_post);
+    {
+      StepTimer tm(m, st, POP_STEP_NORM);
+      pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_post, abuf, nullptr, T, d, cfg.rms_eps, st);
+    }
     g.A = abuf; g.lda = d; g.W = (const bf16_t*)lw.w_gate_up; g.ldw = d; g.out = u; g.ldc = f;
     g.M = T; g.N = f; g.K = d; g.epilogue = pop::EPI_GLU_BF16; g.act = cfg.act;
     {
       StepTimer tm(m, st, POP_STEP_GATE_UP_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "gate/up")) return s;
     }
-    g.a_parts = nullptr;
     g.A = u; g.lda = f; g.W = (const bf16_t*)lw.w_down; g.ldw = f; g.out = h; g.ldc = d;
     g.M = T; g.N = d; g.K = f; g.epilogue = pop::EPI_ADD_F32;
     g.scaled = a->gates != nullptr; g.scale = a->gates ? a->gates[l - 1] : 1.f;
-    // if another kept layer follows directly, its input norm is prepared here
-    fold_next(l < cfg.n_layers && !plan.pruned[l + 1] ? (const float*)m->layers[l].norm_in : nullptr);
     {
       StepTimer tm(m, st, POP_STEP_DOWN_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "down")) return s;

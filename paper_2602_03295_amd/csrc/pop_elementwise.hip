@@ -32,18 +32,6 @@ void launch_embed(const bf16_t* table, const int32_t* tokens, const int32_t* row
   hipLaunchKernelGGL(embed_kernel, dim3(T), dim3(256), 0, st, table, tokens, row_src, embeds, h, d);
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ dst, size_t n16) {
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
-    dst[i] = make_uint4(0, 0, 0, 0);
-}
-
-void launch_fill_zero(void* dst, size_t bytes, hipStream_t st) {
-  const size_t n16 = bytes / 16;
-  if (n16 == 0) return;
-  const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 4096);
-  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, reinterpret_cast<uint4*>(dst), n16);
-}
-
 __global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restrict__ src,
                                                           const int32_t* __restrict__ idx,
                                                           float* __restrict__ dst, int d) {

@@ -64,37 +64,7 @@ struct GemmParams {
   int kv_heads, kv_page;
   long long kv_pool_stride;
   KvQuant kvq;
-  // Normalisation folded into two neighbouring projections (LN of Sec. 2.1 as RMSNorm):
-  //   producer (EPI_ADD_F32): besides out += C it stores bf16(out_new * gamma) and, per row and 64-column group,
-  //   the sum of squares of out_new;
-  //   consumer (any storing epilogue): A holds such un-normalised rows, and every accumulator row is multiplied
-  //   by rstd = rsqrt(sum of the row's partial sums / K + eps) before the epilogue proper.
-  const float* nrm_gamma;   // producer: [N], nullptr = off
-  bf16_t* nrm_out;          // producer: [M, N]
-  float* nrm_parts;         // producer: [M, N / 64]
-  const float* a_parts;     // consumer: [M, a_nparts], nullptr = off
-  int a_nparts;
-  float a_eps;
-  QkvRope qr;               // EPI_QKV_ROPE
 };
-
-// EPI_QKV_ROPE: which rows of W a column tile stages.  The epilogue rotates pairs (x_i, x_{i + hd/2}) of a head
-// in-lane, so the two 16-column blocks that hold the halves of a pair must be blocks b and b + NB/2 of the same
-// wave tile whatever the tile width.  The output columns of the whole projection are therefore cut into "slots" of
-// two 16-row blocks of W: for a query or key head, 16 rows of its low half and the 16 partner rows of its high
-// half (hd / 32 slots per head; W's rows are ordered q | k | v, so query and key heads are simply heads
-// 0 .. Hq + Hkv - 1); for V, 32 consecutive rows.  A wave tile of NB blocks holds NB / 2 consecutive slots: its
-// first NB / 2 blocks their low blocks, the others their high blocks.  Returns the W row of row r16 of the low
-// (is_hi = 0) or high block of slot s, or -1 beyond the last slot.
-__device__ __forceinline__ int qkv_slot_w_row(int s, int is_hi, int r16, int hd, int n_rot_heads, int n_kv_heads) {
-  const int hb = hd >> 5;
-  const int n_rot = n_rot_heads * hb;
-  if (s < n_rot) return (s / hb) * hd + (s % hb) * 16 + is_hi * (hd >> 1) + r16;
-  const int j = s - n_rot;
-  if (j >= n_kv_heads * hb) return -1;
-  return n_rot_heads * hd + j * 32 + is_hi * 16 + r16;
-}
-
 
 // Template values of the KV-cache epilogue (EPI_KV_CACHE of the interface), one per head_dim: the offset between
 // the two halves of a head decides which accumulator registers are RoPE partners, so it must be a constant.
@@ -128,7 +98,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // wave-loads per stage and wave
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/wave mismatch");
   static_assert(EPI != EPI_GLU_BF16 || NB % 2 == 0, "GLU needs an even number of column blocks");
-  static_assert(EPI != EPI_QKV_ROPE || NB % 2 == 0, "rotation pairs need an even number of column blocks");
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -193,11 +162,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
       const int oc = n0 + w2 * (WTN / 2) + (r % (WTN / 2));
       ok = oc < p.N;
       wrow = up * p.N + oc;
-    } else if (EPI == EPI_QKV_ROPE) {
-      const int w2 = jn / WTN, r = jn % WTN, b = r >> 4;               // wave tile, block inside it
-      const int slot = ((p.n_tile0 + tn) * WGN + w2) * (NB / 2) + b % (NB / 2);
-      wrow = qkv_slot_w_row(slot, b / (NB / 2), r & 15, p.qr.hd, p.qr.n_q_heads + p.qr.n_kv_heads, p.qr.n_kv_heads);
-      ok = wrow >= 0;
     } else {
       wrow = n0 + jn;
       ok = wrow < p.N;
@@ -253,11 +217,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
         const int oc = n0 + w2 * (WTN / 2) + (r % (WTN / 2));
         ok = ok && oc < p.N;
         wrow = (r >= WTN / 2 ? p.N : 0) + oc;
-      } else if (EPI == EPI_QKV_ROPE) {
-        const int w2 = jn / WTN, r = jn % WTN, b = r >> 4;
-        const int slot = ((p.n_tile0 + tn) * WGN + w2) * (NB / 2) + b % (NB / 2);
-        wrow = qkv_slot_w_row(slot, b / (NB / 2), r & 15, p.qr.hd, p.qr.n_q_heads + p.qr.n_kv_heads, p.qr.n_kv_heads);
-        ok = ok && wrow >= 0;
       } else {
         wrow = n0 + jn;
         ok = ok && wrow < p.N;
@@ -304,30 +263,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     // beyond the last K-step is requested masked (or re-stages the last K-step) and never read
     if (t < nk) issue(t, t, t < nk_full ? 0u : last_mask);
     else if (STAGES >= 4) issue(t, t, kOOB);
-  }
-  // Consumer side of a folded normalisation: while the first stages travel, every thread adds the partial sums of
-  // squares of one of the tile's rows (fixed order) and leaves the row's rstd in LDS for the epilogue.
-  float* row_rstd = reinterpret_cast<float*>(smem + STAGES * STAGE + 1024);
-  if (p.a_parts) {
-    for (int r = threadIdx.x; r < BM; r += 64 * NW) {
-      const int row = m0 + r;
-      float ssum = 0.f;
-      if (row < p.M) {
-        // eight 16-byte loads are requested before the first addition (a loop of dependent loads would pay the
-        // memory latency once per load: measured 5 us per tile)
-        const float4* pp = reinterpret_cast<const float4*>(p.a_parts + (long long)row * p.a_nparts);
-        const int n4 = p.a_nparts >> 2;
-        for (int i0 = 0; i0 < n4; i0 += 8) {
-          float4 v[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) v[i] = pp[min(i0 + i, n4 - 1)];
-#pragma unroll
-          for (int i = 0; i < 8; ++i)
-            if (i0 + i < n4) ssum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-        }
-      }
-      row_rstd[r] = rsqrtf(ssum / (float)p.K + p.a_eps);
-    }
   }
   // The K loop is rotated by one (32-wide) sub-step: the MFMAs of the last sub-step of K-step kt-1 are issued
   // after the barrier of K-step kt, from fragments that are already in registers, so the matrix
@@ -474,10 +409,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
         if (m >= p.M) continue;
         {
           const int n = n0 + wn * (WTN / 2) + i * 16 + frag_hi * 4;
-          const float rs = p.a_parts ? row_rstd[wm * WTM + j * 16 + frag_row] : 1.f;   // folded normalisation of A
           float r[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) r[e] = glu_act(acc[i][j][e] * rs, act_k0, act_k1) * (acc[i + NB / 2][j][e] * rs);
+          for (int e = 0; e < 4; ++e) r[e] = glu_act(acc[i][j][e], act_k0, act_k1) * acc[i + NB / 2][j][e];
           bf16_t* o = out + (long long)m * p.ldc + n;
           if (n + 3 < p.N) {
             uint2 pk;
@@ -553,99 +487,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
       }
     }
    }
-  } else if (EPI == EPI_QKV_ROPE) {
-   if constexpr (EPI == EPI_QKV_ROPE) {
-    // K/V generation and cache append of Sec. 2.1 on the accumulators.  Wave tile = NB / 2 slots (see
-    // qkv_slot_w_row): block sl holds 16 low-half dims of a head (or 16 V dims), block sl + NB / 2 the partner
-    // high-half dims (or the next 16 V dims), for the same rows, in the same lane and register slot.
-    constexpr int NS = NB / 2;
-    const QkvRope& q = p.qr;
-    const int hd = q.hd, half = hd >> 1, hb = hd >> 5;
-    const int n_rot = (q.n_q_heads + q.n_kv_heads) * hb, n_slots = n_rot + q.n_kv_heads * hb;
-    const int slot0 = ((p.n_tile0 + tn) * WGN + wn) * NS;
-    const int P = q.page_size;
-    const bool fp8 = q.kvq.fp8 != 0;
-    const long long esz = fp8 ? 1 : 2;
-#pragma unroll
-    for (int j = 0; j < MB; ++j) {
-      const int m = m_lane + j * 16;
-      if (m >= p.M) continue;
-      const float rs = p.a_parts ? row_rstd[wm * WTM + j * 16 + frag_row] : 1.f;   // folded normalisation of A
-      const int cslot = q.slot[m];
-      const long long page_base = (long long)(cslot / P) * q.n_kv_heads * P * hd + (long long)(cslot % P) * hd;
-      const float2* csm = q.cs + (long long)m * half;
-      const long long vcol = q.vt_col[m];
-#pragma unroll
-      for (int sl = 0; sl < NS; ++sl) {
-        const int s = slot0 + sl;                 // wave-uniform
-        if (s >= n_slots) continue;
-        float a[4], b[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { a[e] = acc[sl][j][e] * rs; b[e] = acc[sl + NS][j][e] * rs; }
-        if (s < n_rot) {
-          const int head = s / hb, d0 = (s % hb) * 16 + frag_hi * 4;       // dims d0 .. d0+3 and their partners
-          const float4 c01 = *reinterpret_cast<const float4*>(csm + d0), c23 = *reinterpret_cast<const float4*>(csm + d0 + 2);
-          const float cc[4] = {c01.x, c01.z, c23.x, c23.z}, sn[4] = {c01.y, c01.w, c23.y, c23.w};
-          float lo[4], hi[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            lo[e] = a[e] * cc[e] - b[e] * sn[e];
-            hi[e] = b[e] * cc[e] + a[e] * sn[e];
-          }
-          const bool is_k = head >= q.n_q_heads;
-          if (is_k) {
-            const int kh = head - q.n_q_heads;
-            char* dst = reinterpret_cast<char*>(q.k_pool) + (page_base + (long long)kh * P * hd + d0) * esz;
-            if (fp8) {
-              // an 8-bit cache: store the codes; the attention kernel gets the values they stand for
-              const uint32_t cl = e4m3_pack4(lo[0] * q.kvq.k_inv, lo[1] * q.kvq.k_inv, lo[2] * q.kvq.k_inv, lo[3] * q.kvq.k_inv);
-              const uint32_t ch = e4m3_pack4(hi[0] * q.kvq.k_inv, hi[1] * q.kvq.k_inv, hi[2] * q.kvq.k_inv, hi[3] * q.kvq.k_inv);
-              *reinterpret_cast<uint32_t*>(dst) = cl;
-              *reinterpret_cast<uint32_t*>(dst + half) = ch;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                lo[e] = e4m3_decode((cl >> (8 * e)) & 0xffu) * q.kvq.k_scale;
-                hi[e] = e4m3_decode((ch >> (8 * e)) & 0xffu) * q.kvq.k_scale;
-              }
-            } else {
-              *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
-              *reinterpret_cast<uint2*>(dst + half * 2) = make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
-            }
-          }
-          bf16_t* o = q.qk_out + (long long)m * q.ld + head * hd + d0;
-          *reinterpret_cast<uint2*>(o) = make_uint2(pack_f16x2(lo[0], lo[1]), pack_f16x2(lo[2], lo[3]));
-          *reinterpret_cast<uint2*>(o + half) = make_uint2(pack_f16x2(hi[0], hi[1]), pack_f16x2(hi[2], hi[3]));
-        } else {
-          // V: dims c0 .. c0+3 of kv head kh (block sl) and c0+16 .. c0+19 (block sl + NS)
-          const int vc = (s - n_rot) * 32 + frag_hi * 4;
-          const int kh = vc / hd, c0 = vc % hd;
-          char* dst = reinterpret_cast<char*>(q.v_pool) + (page_base + (long long)kh * P * hd + c0) * esz;
-          if (fp8) {
-            const uint32_t ca = e4m3_pack4(a[0] * q.kvq.v_inv, a[1] * q.kvq.v_inv, a[2] * q.kvq.v_inv, a[3] * q.kvq.v_inv);
-            const uint32_t cb = e4m3_pack4(b[0] * q.kvq.v_inv, b[1] * q.kvq.v_inv, b[2] * q.kvq.v_inv, b[3] * q.kvq.v_inv);
-            *reinterpret_cast<uint32_t*>(dst) = ca;
-            *reinterpret_cast<uint32_t*>(dst + 16) = cb;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              a[e] = e4m3_decode((ca >> (8 * e)) & 0xffu) * q.kvq.v_scale;
-              b[e] = e4m3_decode((cb >> (8 * e)) & 0xffu) * q.kvq.v_scale;
-            }
-          } else {
-            *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
-            *reinterpret_cast<uint2*>(dst + 32) = make_uint2(pack_bf16x2(b[0], b[1]), pack_bf16x2(b[2], b[3]));
-          }
-          // transposed fp16 copy for the attention kernel: vT[kh][dim][column of this row]; the 16 lanes that
-          // share frag_hi hold 16 consecutive rows, i.e. 32 contiguous bytes of one dim
-          bf16_t* vt = q.vT + ((long long)kh * hd + c0) * q.Tp + vcol;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            vt[(long long)e * q.Tp] = f32_to_f16_sat(a[e]);
-            vt[(long long)(e + 16) * q.Tp] = f32_to_f16_sat(b[e]);
-          }
-        }
-      }
-    }
-   }
   } else if (EPI == EPI_ADD_F32) {
     // out += C.  The old values are requested sixteen 16x16 blocks at a time, without branches (a lane whose
     // four columns are not all inside reads the first element of the matrix instead), so that the loads
@@ -653,13 +494,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     // next one is requested (one memory round trip per block; measured: 2 to 7 us per projection at 2048 rows).
     float* outp = reinterpret_cast<float*>(p.out) + (long long)z * p.strideC;
     constexpr int TOT = MB * NB, CH = 16;
-    // Producer side of a folded normalisation (N is then a multiple of 64, so every group of four columns is
-    // whole): the new rows times the next norm's scale go out as bf16, and each lane collects the squares of what
-    // it holds of every row.
-    const bool nrm = p.nrm_gamma != nullptr;
-    float ss[MB];
-#pragma unroll
-    for (int j = 0; j < MB; ++j) ss[j] = 0.f;
 #pragma unroll
     for (int c0 = 0; c0 < TOT; c0 += CH) {
       float4 old[CH];
@@ -681,42 +515,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
           const int m = m_lane + j * 16, n = n0 + wn * WTN + i * 16 + frag_hi * 4;
           float* o = outp + (long long)m * p.ldc + n;
           if (m < p.M && n + 3 < p.N) {
-            const float4 nv = make_float4(acc[i][j][0] * p.scale + old[c].x, acc[i][j][1] * p.scale + old[c].y,
-                                          acc[i][j][2] * p.scale + old[c].z, acc[i][j][3] * p.scale + old[c].w);
-            *reinterpret_cast<float4*>(o) = nv;
-            if (nrm) {
-              const float4 g = *reinterpret_cast<const float4*>(p.nrm_gamma + n);
-              uint2 pk;
-              pk.x = pack_bf16x2(nv.x * g.x, nv.y * g.y);
-              pk.y = pack_bf16x2(nv.z * g.z, nv.w * g.w);
-              *reinterpret_cast<uint2*>(p.nrm_out + (long long)m * p.N + n) = pk;
-              ss[j] += (nv.x * nv.x + nv.y * nv.y) + (nv.z * nv.z + nv.w * nv.w);
-            }
+            *reinterpret_cast<float4*>(o) = make_float4(acc[i][j][0] * p.scale + old[c].x, acc[i][j][1] * p.scale + old[c].y,
+                                                        acc[i][j][2] * p.scale + old[c].z, acc[i][j][3] * p.scale + old[c].w);
           } else if (m < p.M && n < p.N) {   // the last, partial group of four columns
 #pragma unroll
             for (int q = 0; q < 4; ++q)
               if (n + q < p.N) o[q] += acc[i][j][q] * p.scale;
           }
-        }
-      }
-    }
-    if (nrm) {
-      // the four lanes that share a row (same lane & 15) add up; the first of them stores the wave tile's sum as
-      // the partial of its first 64-column group (a 128-column wave tile fills its second group with zero)
-      static_assert(WTN % 64 == 0 || EPI != EPI_ADD_F32 || true, "");
-      const int parts_per_row = p.N >> 6;
-      const int part0 = (n0 + wn * WTN) >> 6;
-#pragma unroll
-      for (int j = 0; j < MB; ++j) {
-        float v = ss[j];
-        v += __shfl_xor(v, 16, 64);
-        v += __shfl_xor(v, 32, 64);
-        const int m = m_lane + j * 16;
-        if (frag_hi == 0 && m < p.M && n0 + wn * WTN < p.N) {
-          float* pp = p.nrm_parts + (long long)m * parts_per_row + part0;
-          pp[0] = v;
-#pragma unroll
-          for (int q = 1; q < WTN / 64; ++q) pp[q] = 0.f;
         }
       }
     }
@@ -730,9 +535,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
         {
           const int n = n0 + wn * WTN + i * 16 + frag_hi * 4;
           if (n >= p.N) continue;
-          const float rs = p.a_parts ? row_rstd[wm * WTM + j * 16 + frag_row] : 1.f;   // folded normalisation of A
-          const float r0 = acc[i][j][0] * rs, r1 = acc[i][j][1] * rs;
-          const float r2 = acc[i][j][2] * rs, r3 = acc[i][j][3] * rs;
+          const float r0 = acc[i][j][0], r1 = acc[i][j][1];
+          const float r2 = acc[i][j][2], r3 = acc[i][j][3];
           if (EPI == EPI_STORE_BF16 || EPI == EPI_STORE_F16) {
             bf16_t* o = reinterpret_cast<bf16_t*>(p.out) + (long long)z * p.strideC + (long long)m * p.ldc + n;
             if (n + 3 < p.N) {
@@ -766,7 +570,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 template <int BM, int BN, int WGM, int WGN, int STAGES, int EPI>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_tiles = -1) {
   constexpr int BN_OUT = EPI == EPI_GLU_BF16 ? BN / 2 : BN;
-  constexpr int smem = STAGES * (BM + BN) * BK * 2 + 1024 + BM * 4;  // stages + prefetch scratch + per-row rstd
+  constexpr int smem = STAGES * (BM + BN) * BK * 2 + 1024;  // stages + prefetch scratch
   static_assert(smem <= 160 * 1024, "LDS budget of a gfx950 CU");
   GemmParams p;
   p.A = g.A; p.W = g.W; p.out = g.out;
@@ -777,9 +581,6 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_
   p.kv_dest = g.kv_dest; p.kv_slot = g.kv_slot; p.kv_heads = g.kv_heads; p.kv_page = g.kv_page_size;
   p.kv_pool_stride = g.kv_pool_stride;
   p.kvq = g.kvq;
-  p.nrm_gamma = g.nrm_gamma; p.nrm_out = g.nrm_out; p.nrm_parts = g.nrm_parts;
-  p.a_parts = g.a_parts; p.a_nparts = g.a_nparts; p.a_eps = g.a_eps;
-  p.qr = g.qr;
   p.tiles_m = (g.M + BM - 1) / BM;
   p.tiles_n = n_tiles >= 0 ? n_tiles : (g.N + BN_OUT - 1) / BN_OUT;
   p.n_tile0 = n_tile0;
@@ -847,8 +648,6 @@ hipError_t launch_epi(const GemmArgs& g, hipStream_t st) {
     double best = 1e300;
     for (const TileCfg& c : kTileCfgs) {      // ordered by area: ties go to the larger tile
       if (c.id == 5 && EPI == EPI_GLU_BF16) continue;
-      // a producer of a folded normalisation needs wave tiles of whole 64-column groups
-      if (g.nrm_gamma && (c.id == 5 || c.id == 6 || c.id == 7 || c.id == 9)) continue;
       const double t = cost(c);
       if (t < best) { best = t; pick = c.id; }
     }
@@ -932,7 +731,6 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // the rows fit one 64-row tile and the launch would leave CUs idle.
 inline int choose_split(const GemmArgs& g) {
   if (!g.splitk_ws || g.batch > 1 || g.W_list || g.epilogue == EPI_GLU_BF16 || g.epilogue == EPI_KV_CACHE) return 1;
-  if (g.nrm_gamma || g.a_parts || g.epilogue == EPI_QKV_ROPE) return 1;   // these live in the one-pass epilogues
   if (g.M > 512 || g.N % 4 || g.K % BK || (reinterpret_cast<uintptr_t>(g.splitk_ws) & 15)) return 1;
   // Building with -DPOP_FORCE_SPLITK=S forces S parts where the problem allows it (experiments only).
 #ifdef POP_FORCE_SPLITK
@@ -968,12 +766,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (g.K <= 0 || g.K % 8 || g.lda % 8 || g.ldw % 8 || g.ldc % 4) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(g.A) | reinterpret_cast<uintptr_t>(g.W) |
-       (g.epilogue == EPI_KV_CACHE || g.epilogue == EPI_QKV_ROPE ? 0 : reinterpret_cast<uintptr_t>(g.out))) & 15)
-    return hipErrorInvalidValue;
-  if (g.nrm_gamma && (g.epilogue != EPI_ADD_F32 || g.N % 64 || !g.nrm_out || !g.nrm_parts || g.batch > 1))
-    return hipErrorInvalidValue;
-  if (g.a_parts && (g.epilogue == EPI_ADD_F32 || g.epilogue == EPI_KV_CACHE || g.a_nparts < 4 || g.a_nparts % 4 ||
-                    g.batch > 1 || (reinterpret_cast<uintptr_t>(g.a_parts) & 15)))
+       (g.epilogue == EPI_KV_CACHE ? 0 : reinterpret_cast<uintptr_t>(g.out))) & 15)
     return hipErrorInvalidValue;
   const long long w_rows = g.epilogue == EPI_GLU_BF16 ? 2LL * g.N : g.N;
   if (((long long)(g.M - 1) * g.lda + g.K) * 2 >= (1LL << 31) || ((w_rows - 1) * g.ldw + g.K) * 2 >= (1LL << 31))
@@ -1027,20 +820,9 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
       if (g.kv_hd == 64) return launch_cfg<256, 256, 2, 2, 2, EPI_KV64>(g, st);
       if (g.kv_hd == 128) return launch_cfg<256, 256, 2, 2, 2, EPI_KV128>(g, st);
       return launch_cfg<256, 256, 4, 1, 2, EPI_KV256>(g, st);
-    case EPI_QKV_ROPE: {
-      // 192-column tiles (six slots of 32 output columns each), 2 x 2 waves: the shape that puts the
-      // Llama-3.1-8B QKV projection at 2048 rows on the chip in one round
-      const QkvRope& q = g.qr;
-      if (!gemm_qkv_rope_supported(q.hd) || g.N != (q.n_q_heads + 2 * q.n_kv_heads) * q.hd || !q.qk_out || !q.cs ||
-          !q.slot || !q.vt_col || !q.k_pool || !q.v_pool || !q.vT || q.page_size < 1 || q.ld % 4)
-        return hipErrorInvalidValue;
-      return launch_cfg<256, 192, 2, 2, 2, EPI_QKV_ROPE>(g, st);
-    }
   }
   return hipErrorInvalidValue;
 }
-
-bool gemm_qkv_rope_supported(int hd) { return hd >= 32 && hd % 32 == 0; }
 
 bool gemm_kv_cache_supported(int n_kv_heads, int hd) {
   if (hd != 64 && hd != 128 && hd != 256) return false;

@@ -97,27 +97,7 @@ enum GemmEpilogue {
   // W^K rows, then its W^V rows, N = 2 Dkv); columns < Dkv are rotated (RoPE on the fp32 accumulators, the two
   // halves of a head are registers of the same lane) and stored as bf16 at the row's slot of the K pool, the
   // others at the same slot of the V pool.  Nothing else is written (out, ldc, strideC are ignored).
-  EPI_KV_CACHE = 5,
-  // The QKV projection of a kept layer with everything the RoPE / append kernel does folded into its epilogue
-  // (Sec. 2.1, K/V generation and cache append): W is the layer's [Dq + 2 Dkv, K] matrix (rows q | k | v); query
-  // and key heads are rotated on the fp32 accumulators, q and k go to the fp16 matrix the attention kernel reads,
-  // k and v to the paged cache, v also to the transposed fp16 copy.  See QkvRope.
-  EPI_QKV_ROPE = 6
-};
-// Destinations of an EPI_QKV_ROPE launch.
-struct QkvRope {
-  bf16_t* qk_out;          // fp16 [M, ld]: rotated q heads in columns 0 .. Dq-1, rotated k heads in Dq .. Dq+Dkv-1
-  int ld;
-  int n_q_heads, n_kv_heads, hd;
-  const float2* cs;        // [M, hd/2] (cos, sin) of every row's position
-  const int32_t* slot;     // [M] cache slot of every row
-  const int32_t* vt_col;   // [M] column of every row in vT
-  bf16_t* k_pool;          // this layer's pools [page][Hkv][P][hd] (one-byte codes with an 8-bit cache)
-  bf16_t* v_pool;
-  int page_size;
-  bf16_t* vT;              // fp16 [Hkv][hd][Tp]; columns that belong to no row must already be zero
-  long long Tp;
-  KvQuant kvq;
+  EPI_KV_CACHE = 5
 };
 // Per batch entry (= pruned layer) of an EPI_KV_CACHE launch: where its entries go and which RoPE table it uses.
 struct KvDest {
@@ -157,23 +137,7 @@ struct GemmArgs {
   int kv_heads, kv_hd, kv_page_size;
   int64_t kv_pool_stride;    // elements from a layer's K pool to its V pool
   KvQuant kvq;               // bf16 entries or e4m3 codes
-  // The normalisation between two projections (LN of Sec. 2.1) folded into them instead of a kernel of its own.
-  // Producer, EPI_ADD_F32 with N % 64 == 0: besides out += C the kernel stores nrm_out = bf16(out_new * nrm_gamma)
-  // ([M, N] dense) and nrm_parts[m][N / 64] = sums of squares of out_new over 64-column groups.
-  // Consumer, a storing epilogue: A is such an un-normalised matrix (lda = K) and a_parts its partial sums
-  // ([M, a_nparts], a_nparts = K / 64, 16-byte aligned); every result row is multiplied by
-  // rsqrt(sum of the row's partials / K + a_eps).  Mathematically RMSNorm followed by the projection; the bf16
-  // rounding of A happens before instead of after the multiplication by rstd, which changes no error bound.
-  const float* nrm_gamma;
-  bf16_t* nrm_out;
-  float* nrm_parts;
-  const float* a_parts;
-  int a_nparts;
-  float a_eps;
-  QkvRope qr;                // EPI_QKV_ROPE only
 };
-// Whether launch_gemm can run EPI_QKV_ROPE for this shape: head_dim a multiple of 32.
-bool gemm_qkv_rope_supported(int hd);
 // Whether launch_gemm can run EPI_KV_CACHE for this shape (otherwise the caller projects to a scratch matrix
 // and appends with launch_rope_write): head_dim 64 / 128 / 256 and whole heads per wave tile.
 bool gemm_kv_cache_supported(int n_kv_heads, int hd);
@@ -284,9 +248,6 @@ hipError_t launch_attention(const float* q, int ldq, int q_col, float* out, cons
 // (step > 0, eos >= 0); the choice is also stored at out[b * out_stride + step].
 void launch_argmax(const float* logits, int vocab, int32_t* tok, int32_t* out, int out_stride, int step, int eos,
                    int B, hipStream_t st);
-
-// dst[0 .. bytes) = 0 (a kernel, so that it may sit in a captured graph; bytes a multiple of 16, dst 16-byte aligned)
-void launch_fill_zero(void* dst, size_t bytes, hipStream_t st);
 
 // gather fp32 rows: dst[i,:] = src[idx[i],:]
 void launch_gather_rows(const float* src, const int32_t* idx, float* dst, int rows, int d, hipStream_t st);
