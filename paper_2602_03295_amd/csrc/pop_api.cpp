@@ -186,6 +186,22 @@ namespace {
 
 constexpr int kKvChunk = 8;  // pruned layers projected per batched GEMM
 
+// Parts into which the down projection (K = d_ffn) of T prompt rows splits its K range.  With 256 x 256 tiles
+// the projection has ceil(T / 256) * ceil(d / 256) tiles; when that is half the chip or less, and K is long, as
+// many work-groups again per part run the tiles' K ranges side by side (measured at 2048 rows of the Llama-3.1-8B
+// shape: 128 tiles, 2 parts).  The parts are added in index order by the kernel that normalises the result for the
+// next layer, or by the split's own second kernel.  1 = no split (few rows use the automatic rule of the GEMM).
+int down_split_parts(int T, int d, int f) {
+#ifdef POP_NO_DOWN_SPLIT      // (experiments only: a build without it, for A/B timing)
+  return 1;
+#endif
+  if (T <= 512 || f < 8192) return 1;
+  const long long tiles = (long long)((T + 255) / 256) * ((d + 255) / 256);
+  int S = 1;
+  while (S < 8 && tiles * S * 2 <= 256 && f % (S * 2 * 64) == 0 && f / (S * 2 * 64) >= 8) S *= 2;
+  return S;
+}
+
 struct Workspace {
   // int32 meta (one upload per call)
   size_t meta_bytes;
@@ -266,6 +282,9 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   // (all packed rows of a short batch; otherwise the boundary rows, which are projected on their own)
   const size_t split_rows = T <= 512 ? (size_t)T : (B <= 512 ? (size_t)B : 0);
   w.splitk_bytes = 8 * 4 * split_rows * std::max(Dqkv, d);
+  // (or the parts of the down projection of a long prompt)
+  if (const int S = down_split_parts(T, (int)d, (int)f); S > 1)
+    w.splitk_bytes = std::max(w.splitk_bytes, 4 * (size_t)S * (size_t)T * d);
   w.o_splitk = take(w.splitk_bytes);
   w.total = o;
   return w;
@@ -1196,13 +1215,18 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   rw.kvq = kv_quant(cfg);
 
   // ---- a kept layer over all given rows (Sec. 2.1)
+  // abuf_gamma: the norm scale with which abuf already holds RMSNorm(h) (left there by the previous layer's down
+  // projection when its K range was split: the kernel that adds the parts to h normalises the sum on the way).
+  const float* abuf_gamma = nullptr;
+  const int down_parts = down_split_parts(T, d, f);
   auto kept_layer = [&](int l) -> pop_status {
     const pop_layer_weights& lw = m->layers[l - 1];
     const bool glob = layer_is_global(cfg, l);
-    {
+    if (abuf_gamma == nullptr || abuf_gamma != (const float*)lw.norm_in) {
       StepTimer tm(m, st, POP_STEP_NORM);
       pop::launch_rmsnorm(h, nullptr, nullptr, (const float*)lw.norm_in, abuf, nullptr, T, d, cfg.rms_eps, st);
     }
+    abuf_gamma = nullptr;
     pop::GemmArgs g{};
     g.batch = 1;
     g.A = abuf; g.lda = d; g.W = (const bf16_t*)lw.wqkv; g.ldw = d; g.out = qkv; g.ldc = Dqkv;
@@ -1258,9 +1282,22 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
     g.A = u; g.lda = f; g.W = (const bf16_t*)lw.w_down; g.ldw = f; g.out = h; g.ldc = d;
     g.M = T; g.N = d; g.K = f; g.epilogue = pop::EPI_ADD_F32;
     g.scaled = a->gates != nullptr; g.scale = a->gates ? a->gates[l - 1] : 1.f;
+    // If the K range is split and another kept layer follows directly, the kernel that adds the parts to h also
+    // writes that layer's normalised input (one pass over h instead of two).
+    const float* next_gamma = l < cfg.n_layers && !plan.pruned[l + 1] ? (const float*)m->layers[l].norm_in : nullptr;
+    int parts = 1;
+    g.force_split = down_parts;
+    g.partials_only = down_parts > 1 && next_gamma != nullptr && d % 4 == 0;
+    g.split_used = &parts;
     {
       StepTimer tm(m, st, POP_STEP_DOWN_GEMM);
       if (pop_status s = gemm_or_fail(g, st, "down")) return s;
+    }
+    if (g.partials_only && parts > 1) {
+      StepTimer tm(m, st, POP_STEP_NORM);
+      pop::launch_add_parts_rmsnorm(h, g.splitk_ws, parts, (size_t)T * d, next_gamma, abuf, T, d, cfg.rms_eps, st,
+                                    pop::residual_scale(g));
+      abuf_gamma = next_gamma;
     }
     return POP_OK;
   };

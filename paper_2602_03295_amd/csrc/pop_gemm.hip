@@ -731,7 +731,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 // the rows fit one 64-row tile and the launch would leave CUs idle.
 inline int choose_split(const GemmArgs& g) {
   if (!g.splitk_ws || g.batch > 1 || g.W_list || g.epilogue == EPI_GLU_BF16 || g.epilogue == EPI_KV_CACHE) return 1;
-  if (g.M > 512 || g.N % 4 || g.K % BK || (reinterpret_cast<uintptr_t>(g.splitk_ws) & 15)) return 1;
+  if (g.N % 4 || g.K % BK || (reinterpret_cast<uintptr_t>(g.splitk_ws) & 15)) return 1;
+  if (g.M > 512 && g.force_split <= 1) return 1;
   // Building with -DPOP_FORCE_SPLITK=S forces S parts where the problem allows it (experiments only).
 #ifdef POP_FORCE_SPLITK
   constexpr int forced = POP_FORCE_SPLITK;
@@ -743,6 +744,7 @@ inline int choose_split(const GemmArgs& g) {
   };
   if (forced == 1) return 1;
   if (forced > 1) return fits(forced) ? forced : 1;
+  if (g.force_split > 1 && g.force_split <= 8 && fits(g.force_split)) return g.force_split;
   if (g.M > 256) return 1;
   if (g.K >= 8192) {
     for (int S = 8; S >= 2; S /= 2)

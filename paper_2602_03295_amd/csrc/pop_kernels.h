@@ -127,6 +127,10 @@ struct GemmArgs {
   // parts: epilogue applied as usual).
   bool partials_only;
   int* split_used;
+  // > 1: split K into exactly this many parts whatever the automatic rule says (the caller has measured that it
+  // pays: a long-K projection whose 256 x 256 tiles would fill only a fraction of the chip), if the scratch and K
+  // allow it; otherwise the automatic rule applies.
+  int force_split;
   // EPI_ADD_F32 with `scaled`: out += scale * C (the virtual gate of Sec. 3.1 on a residual branch); otherwise
   // out += C.  A caller that adds partial products itself (partials_only) applies the scale there.
   bool scaled;
