@@ -306,7 +306,7 @@ def main():
     achieved = gu_flops / (gu_ms * 1e-3) / 1e12 if gu_ms > 0 else 0.0
     # HBM bytes per launch of that kernel, from the committed rocprofv3 --pmc runs (FETCH_SIZE x 2.0 +
     # WRITE_SIZE x 1.0, calibrated with a 1 GiB copy); only valid for the workload they were taken on
-    traffic = ((295122 + 65652) * 2.0 + (49152 + 8192)) * 1024 if (args.config == "llama8b" and n == 2048 and not args.layers) else None
+    traffic = ((295114 + 65660) * 2.0 + (49152 + 8192)) * 1024 if (args.config == "llama8b" and n == 2048 and not args.layers) else None
     breakdown = {k: {"ms_per_launch": v["ms"] / max(v["launches"], 1), "launches_per_step": v["launches"] / args.steps,
                      "ms_per_step": v["ms"] / args.steps} for k, v in steps_t.items() if v["launches"]}
     hd = cfg["head_dim"]
