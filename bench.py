@@ -321,6 +321,16 @@ def main():
     if "norm" in breakdown:
         nb = n * d * (4 + 2)
         breakdown["norm"]["gb_per_s"] = nb / (breakdown["norm"]["ms_per_launch"] * 1e-3) / 1e9
+    if "down_add_norm" in breakdown:
+        # parts of the down projection's K range (the library's rule: as many as make the 256 x 256 tiles fill the
+        # chip); the kernel reads the parts and h, writes h and the next layer's normalised rows
+        tiles = -(-n // 256) * -(-d // 256)
+        parts = 1
+        while parts < 8 and tiles * parts * 2 <= 256 and f % (parts * 2 * 64) == 0 and f // (parts * 2 * 64) >= 8:
+            parts *= 2
+        ab = n * d * (4 * parts + 4 + 4 + 2)
+        breakdown["down_add_norm"]["gb_per_s"] = ab / (breakdown["down_add_norm"]["ms_per_launch"] * 1e-3) / 1e9
+        breakdown["down_add_norm"]["k_parts"] = parts
     if "rope_write" in breakdown:
         rb = n * (dq + 2 * dkv) * 2 * 2 + n * dkv * 2
         breakdown["rope_write"]["gb_per_s"] = rb / (breakdown["rope_write"]["ms_per_launch"] * 1e-3) / 1e9
@@ -332,7 +342,7 @@ def main():
         if k in breakdown and "tflops" in breakdown[k]:
             per_step[k] = {"bound": "mfma", "achieved": breakdown[k]["tflops"], "peak": PEAK_BF16_TFLOPS,
                            "unit": "TFLOP/s", "frac": breakdown[k]["tflops"] / PEAK_BF16_TFLOPS}
-    for k in ("norm", "rope_write"):
+    for k in ("norm", "rope_write", "down_add_norm"):
         if k in breakdown and "gb_per_s" in breakdown[k]:
             per_step[k] = {"bound": "hbm", "achieved": breakdown[k]["gb_per_s"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                            "frac": breakdown[k]["gb_per_s"] / PEAK_HBM_GBS}

@@ -295,7 +295,9 @@ enum {
   POP_STEP_KV_ONLY_GEMM = 9,  /* pruned layers: batched K/V projection            */
   POP_STEP_KV_ONLY_WRITE = 10, /* pruned layers: RoPE + cache append              */
   POP_STEP_BOUNDARY = 11,     /* boundary rows: deep layers + final norm + LM head */
-  POP_N_STEPS = 12
+  POP_STEP_DOWN_ADD_NORM = 12, /* long prompts: adds the K parts of the down projection to the hidden state and
+                                  writes the next layer's normalised input (or only adds, after the last kept layer) */
+  POP_N_STEPS = 13
 };
 pop_status pop_timing_enable(pop_model* m, int32_t enable);
 pop_status pop_timing_read(pop_model* m, float* ms_out, int32_t* launches_out);

@@ -1294,7 +1294,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       if (pop_status s = gemm_or_fail(g, st, "down")) return s;
     }
     if (g.partials_only && parts > 1) {
-      StepTimer tm(m, st, POP_STEP_NORM);
+      StepTimer tm(m, st, POP_STEP_DOWN_ADD_NORM);
       pop::launch_add_parts_rmsnorm(h, g.splitk_ws, parts, (size_t)T * d, next_gamma, abuf, T, d, cfg.rms_eps, st,
                                     pop::residual_scale(g));
       abuf_gamma = next_gamma;
@@ -1334,10 +1334,12 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       g.batch = n; g.strideA = (long long)rows * d; g.strideC = (long long)rows * 2 * Dkv;
       g.W_list = d_wlist + c0;
       // Straight into the paged cache (RoPE and the page scatter in the GEMM's epilogue) when the layers of the
-      // chunk have no per-head key norm (that needs a head's sum of squares first) and there are enough rows for
-      // the 256-row tiles of that epilogue to fill the chip; otherwise through kv_out and the append kernel.
+      // chunk have no per-head key norm (that needs a head's sum of squares first) and the 256 x 256 tiles of that
+      // epilogue fill at least three quarters of the chip (one pruned layer of a 2048-token prompt is 64 tiles: the
+      // smaller tiles of the plain GEMM plus the append kernel are faster there); otherwise through kv_out and the
+      // append kernel.
       bool fused = pop::gemm_kv_cache_supported(cfg.n_kv_heads, hd) &&
-                   (long long)((rows + 255) / 256) * ((2 * Dkv + 255) / 256) * n >= 64;
+                   (long long)((rows + 255) / 256) * ((2 * Dkv + 255) / 256) * n >= 192;
       for (int j = 0; j < n; ++j) fused = fused && m->layers[layers[c0 + j] - 1].k_norm == nullptr;
       if (fused) {
         g.epilogue = pop::EPI_KV_CACHE;

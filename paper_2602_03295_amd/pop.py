@@ -110,7 +110,7 @@ lib.pop_op_rope_attention.argtypes = [C.c_void_p, _i32p, C.c_int32, C.c_int32, C
 lib.pop_timing_enable.argtypes = [C.c_void_p, C.c_int32]
 lib.pop_timing_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), _i32p]
 STEP_NAMES = ["embed", "norm", "qkv_gemm", "rope_write", "attention", "o_gemm", "gate_up_gemm", "down_gemm",
-              "kv_only_norm", "kv_only_gemm", "kv_only_write", "boundary"]
+              "kv_only_norm", "kv_only_gemm", "kv_only_write", "boundary", "down_add_norm"]
 
 EXPORTED = ["pop_timing_enable", "pop_timing_read", "pop_last_error", "pop_version", "pop_load_weights", "pop_free_model", "pop_cache_bytes",
             "pop_workspace_bytes", "pop_cache_create", "pop_cache_destroy", "pop_cache_n_seqs",

@@ -307,8 +307,10 @@ def test_gemma12b_shape_16384_tokens_sampled_rows(pop, kind):
         logits2 = pop.pop_prefill(model, cache2, tokens, [0, n], bt, 1, ws, window_kv_writes=True).cpu().numpy()[0]
         torch.cuda.synchronize()
         # (the windowed layer projects 1024 rows instead of 16384: the same arithmetic per entry, but the library may
-        #  pick another of its two K/V-only routes for so few rows, whose roundings differ in the last bit)
-        assert rel_err(logits2, logits.astype(np.float64)) <= 1e-3
+        #  pick another of its two K/V-only routes for so few rows: one rotates the fp32 accumulator and rounds once,
+        #  the other rounds the projection to bf16, rotates and rounds again, so entries differ by up to a bf16 step,
+        #  2^-8 relative, and the logits that read 1024 such entries are held to twice that)
+        assert rel_err(logits2, logits.astype(np.float64)) <= 2.0 ** -7
         kw = cache2.gather(1, 0, bt[0], n).float().cpu().numpy()
         vw = cache2.gather(1, 1, bt[0], n).float().cpu().numpy()
         first = (n - 1) - W_ + 1                  # the boundary token at position n - 1 sees positions > n - 1 - W
