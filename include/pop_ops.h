@@ -26,19 +26,6 @@ pop_status pop_op_rmsnorm(const float* x, const float* gamma, void* out, int32_t
 pop_status pop_op_gemm(const void* A, int64_t lda, const void* W, int64_t ldw, void* out, int64_t ldc,
                        int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t act, pop_stream stream);
 
-/* Weight layout for the long-prompt projections (Sec. 2.1, Attn / FFN blocks): W [rows, ldw] row-major ->
- * `out`, rows * K bf16, in blocks of 16 rows x 32 k of 1 KB each, block (r, c) at ((r * K / 32) + c) * 1 KB,
- * inside a block the 16 bytes of lane l = 16 * (k chunk) + row are W[16 r + l % 16][32 c + 8 (l / 16) .. + 7]:
- * what one lane of a wave feeds to a 16 x 16 x 32 matrix instruction, so that a wave fetches an operand with one
- * contiguous 1 KB load and W need not pass through LDS.  rows % 16 == 0, K % 32 == 0, ldw % 8 == 0; W, out DEVICE,
- * 16-byte aligned, not overlapping.  POP_ESHAPE / POP_EALIGN / POP_EINVAL before anything is enqueued. */
-pop_status pop_op_pack_w(const void* W, int64_t ldw, int32_t rows, int32_t K, void* out, pop_stream stream);
-
-/* pop_op_gemm with W in the layout of pop_op_pack_w (of all its rows: 2N for epilogue 2).  K % 64 == 0,
- * N % 16 == 0; otherwise as pop_op_gemm. */
-pop_status pop_op_gemm_packed(const void* A, int64_t lda, const void* Wp, void* out, int64_t ldc,
-                              int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t act, pop_stream stream);
-
 /* The same projection (Sec. 2.1, Attn / FFN blocks; the short prompts of Sec. 4.3, where a projection is
  * weight streaming) with scratch memory that allows a deterministic split of K (few rows, long K: the
  * projections of short prompts are weight streaming, and more work-groups stream faster).  The library

@@ -17,7 +17,7 @@ SOURCES = ["pop_api.cpp", "pop_elementwise.hip", "pop_gemm.hip", "pop_attention.
 # AGPR<->VGPR copy of every accumulator in every key tile.  The GEMM keeps the default (AGPR
 # accumulators): it needs all 512 registers.
 EXTRA_FLAGS = {"pop_attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
-FLAGS = [*os.environ.get("POP_EXTRA_FLAGS", "").split(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
 

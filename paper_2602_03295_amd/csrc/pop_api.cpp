@@ -1630,33 +1630,6 @@ pop_status pop_op_gemm(const void* A, int64_t lda, const void* W, int64_t ldw, v
   return POP_OK;
 }
 
-pop_status pop_op_pack_w(const void* W, int64_t ldw, int32_t rows, int32_t K, void* out, pop_stream stream) {
-  if (!W || !out) return fail(POP_EINVAL, "NULL pointer");
-  if (rows < 0 || K < 32 || rows % 16 || K % 32 || ldw % 8 || ldw < K)
-    return fail(POP_ESHAPE, "rows must be a multiple of 16, K of 32, ldw of 8 and at least K");
-  if (!aligned16(W) || !aligned16(out)) return fail(POP_EALIGN, "pointer not 16-byte aligned");
-  hipError_t e = pop::launch_pack_w((const bf16_t*)W, ldw, rows, K, (bf16_t*)out, reinterpret_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return fail(POP_EHIP, "pack launch failed: %s", hipGetErrorString(e));
-  return POP_OK;
-}
-
-pop_status pop_op_gemm_packed(const void* A, int64_t lda, const void* Wp, void* out, int64_t ldc, int32_t M, int32_t N,
-                              int32_t K, int32_t epilogue, int32_t act, pop_stream stream) {
-  if (!A || !Wp || !out) return fail(POP_EINVAL, "NULL pointer");
-  if (M < 0 || N < 0 || K < 1) return fail(POP_EINVAL, "bad sizes");
-  if (epilogue < 0 || epilogue > 3) return fail(POP_EINVAL, "unknown epilogue %d", epilogue);
-  if (K % 64 || N % 16 || lda % 8 || ldc % 4 || lda < K || ldc < N)
-    return fail(POP_ESHAPE, "K must be a multiple of 64, N of 16, lda of 8, ldc of 4, and strides must cover the rows");
-  if (!aligned16(A) || !aligned16(Wp) || !aligned16(out)) return fail(POP_EALIGN, "pointer not 16-byte aligned");
-  pop::GemmArgs g{};
-  g.A = (const bf16_t*)A; g.lda = lda; g.W = (const bf16_t*)Wp; g.ldw = K; g.out = out; g.ldc = ldc;
-  g.M = M; g.N = N; g.K = K; g.epilogue = epilogue; g.act = act; g.batch = 1; g.w_packed = true;
-  hipError_t e = pop::launch_gemm(g, reinterpret_cast<hipStream_t>(stream));
-  if (e == hipErrorInvalidValue) return fail(POP_ESHAPE, "operand too large or misaligned for the GEMM kernel");
-  if (e != hipSuccess) return fail(POP_EHIP, "GEMM launch failed: %s", hipGetErrorString(e));
-  return POP_OK;
-}
-
 pop_status pop_op_gemm_splitk(const void* A, int64_t lda, const void* W, int64_t ldw, void* out, int64_t ldc, int32_t M,
                               int32_t N, int32_t K, int32_t epilogue, void* dev_scratch, size_t scratch_bytes,
                               pop_stream stream) {

@@ -89,22 +89,16 @@ __device__ __forceinline__ void for_each_index(F&& f, std::integer_sequence<int,
 // KFULL: K is a multiple of BK.  Then no lane ever needs a tail mask and the main loop carries no
 // vector-ALU instruction besides the MFMAs (address arithmetic is loop invariant or scalar): vector
 // ALU instructions share the issue port with the MFMAs and every one of them delays the next MFMA.
-//
-// WDIR: W is in the packed layout of pack_w_kernel (every 16-row x 32-k block is the 1 KB that one
-// v_mfma_f32_16x16x32_bf16 takes as its first operand, lane-major), and a wave loads its W fragments straight from
-// global memory into registers, one K-step ahead; only the activation tile goes through LDS.  That halves the bytes
-// a work-group sends to LDS and the fragment reads it takes from there.
-template <int BM, int BN, int WGM, int WGN, int STAGES, int EPI, bool KFULL, bool WDIR = false>
+template <int BM, int BN, int WGM, int WGN, int STAGES, int EPI, bool KFULL>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)  // the buffer-resource builtins exist in the device pass only
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int MB = WTM / 16, NB = WTN / 16;   // 16x16 output blocks of a wave tile
-  constexpr int LA = BM / 8 / NW, LB = WDIR ? 0 : BN / 8 / NW;  // wave-loads per stage and wave
-  static_assert(!WDIR || (STAGES == 2 && KFULL), "the register-fed W path is written for two stages and K % 64 == 0");
+  constexpr int LA = BM / 8 / NW, LB = BN / 8 / NW;  // wave-loads per stage and wave
   static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/wave mismatch");
   static_assert(EPI != EPI_GLU_BF16 || NB % 2 == 0, "GLU needs an even number of column blocks");
-  constexpr int A_BYTES = BM * BK * 2, B_BYTES = WDIR ? 0 : BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -139,8 +133,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   // ---- buffer descriptors; rows beyond the operand are out of range and load zeros
   const uint32_t a_bytes = (uint32_t)(((long long)(p.M - 1) * p.lda + p.K) * 2);
   const int w_rows = EPI == EPI_GLU_BF16 ? 2 * p.N : p.N;
-  const uint32_t w_bytes = WDIR ? (uint32_t)((long long)w_rows * p.K * 2)
-                                : (uint32_t)(((long long)(w_rows - 1) * p.ldw + p.K) * 2);
+  const uint32_t w_bytes = (uint32_t)(((long long)(w_rows - 1) * p.ldw + p.K) * 2);
   const __amdgpu_buffer_rsrc_t rA =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, a_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rW =
@@ -152,30 +145,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   // logical chunk that belongs at this lane's LDS position: key = (tile row >> 1) & 7, and the tile
   // row is (j * NW + wave) * 8 + lr with NW even, so the key is ((wave & 1) << 2) | (lr >> 1)
   const int lc = (lane & 7) ^ (((wave & 1) << 2) | (lr >> 1));
-  uint32_t offA[LA], offB[LB > 0 ? LB : 1];
+  uint32_t offA[LA], offB[LB];
 #pragma unroll
   for (int j = 0; j < LA; ++j) {
     const int row = m0 + (j * NW + wave) * 8 + lr;
     offA[j] = row < p.M ? (uint32_t)(((long long)row * p.lda + lc * 8) * 2) : kOOB;
-  }
-  // Packed W: byte offset of this lane's 16 bytes in the k-block 0 fragment of the wave's i-th 16-row block
-  // (blocks beyond N are out of range and load zeros); the k-block goes into the scalar offset.
-  uint32_t voffW[WDIR ? NB : 1];
-  if constexpr (WDIR) {
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      int wrow0;
-      bool ok;
-      if (EPI == EPI_GLU_BF16) {
-        const int oc = n0 + wn * (WTN / 2) + (i % (NB / 2)) * 16;
-        ok = oc < p.N;
-        wrow0 = (i >= NB / 2 ? p.N : 0) + oc;
-      } else {
-        wrow0 = n0 + wn * WTN + i * 16;
-        ok = wrow0 < p.N;
-      }
-      voffW[i] = ok ? (uint32_t)((long long)(wrow0 >> 4) * (p.K >> 5) * 1024 + lane * 16) : kOOB;
-    }
   }
 #pragma unroll
   for (int j = 0; j < LB; ++j) {
@@ -247,22 +221,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
         wrow = n0 + jn;
         ok = ok && wrow < p.N;
       }
-      if constexpr (WDIR) {
-        // the slice is two 16-row blocks, 2 KB (16 lines) of each per K-step: lane -> block lane / 16, line lane % 16
-        const int blk = (tm & 7) * (BN / 128) + (lane >> 4);
-        const int jb = blk * 16;
-        int wr; bool okb = lane < 32;
-        if (EPI == EPI_GLU_BF16) {
-          const int w2 = jb / WTN, r = jb % WTN;
-          const int oc = n0 + w2 * (WTN / 2) + (r % (WTN / 2));
-          okb = okb && oc < p.N;
-          wr = (r >= WTN / 2 ? p.N : 0) + oc;
-        } else {
-          wr = n0 + jb;
-          okb = okb && wr < p.N;
-        }
-        pf_off = okb ? (uint32_t)((long long)(wr >> 4) * (p.K >> 5) * 1024 + (lane & 15) * 128) : kOOB;
-      } else
       pf_off = ok ? (uint32_t)((long long)wrow * p.ldw * 2) : kOOB;
     } else if (wave <= 2) {
       const int row = m0 + (tn & 3) * (BM / 4) + (wave - 1) * 32 + l32;
@@ -275,7 +233,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   auto prefetch = [&](int kt) {   // one DMA load per wave; lanes beyond K or beyond the tile are masked
     const uint32_t off = KFULL ? pf_off : ((kt * BK < p.K) ? pf_off : kOOB);
     const int kk = KFULL ? min(kt, nk - 1) : kt;
-    if (wave == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rW, (lds_ptr_t)pf_scratch, 4, off, WDIR ? kk * 2048 : kk * BK * 2, 0, 0);
+    if (wave == 0) __builtin_amdgcn_raw_ptr_buffer_load_lds(rW, (lds_ptr_t)pf_scratch, 4, off, kk * BK * 2, 0, 0);
     else __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_ptr_t)(pf_scratch + 256), 4, off, kk * BK * 2, 0, 0);
   };
 
@@ -321,31 +279,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
   for (int i = 0; i < NB; ++i)
 #pragma unroll
     for (int v = 0; v < 8; ++v) bfr[1][i][v] = (__bf16)0.f;
-  // Register-fed W: bw[parity of the K-step][sub-step][block]; the loads of K-step kt + 1 are issued during K-step
-  // kt.  The rotated MFMAs of the first iteration read bw[1][STEPS - 1] (times the zero activations above).
-  bf16x8_t bw[WDIR ? 2 : 1][WDIR ? STEPS : 1][WDIR ? NB : 1];
-  if constexpr (WDIR) {
-#pragma unroll
-    for (int i = 0; i < NB; ++i)
-#pragma unroll
-      for (int v = 0; v < 8; ++v) bw[1][STEPS - 1][i][v] = (__bf16)0.f;
-  }
-  auto load_w = [&](int kt_w, int sub, int i, auto par_c) {   // fragment (sub, i) of K-step kt_w into parity par
-    constexpr int par = decltype(par_c)::value;
-    if constexpr (WDIR) {
-      const int kk = min(kt_w, nk - 1);
-      typedef int v4i __attribute__((ext_vector_type(4)));
-      const v4i w = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rW, (int)voffW[i], (kk * STEPS + sub) * 1024, 0));
-      bw[par][sub][i] = __builtin_bit_cast(bf16x8_t, w);
-    }
-  };
-  if constexpr (WDIR) {
-#pragma unroll
-    for (int sub = 0; sub < STEPS; ++sub)
-#pragma unroll
-      for (int i = 0; i < NB; ++i) load_w(0, sub, i, std::integral_constant<int, 0>{});
-  }
-  constexpr int READS = WDIR ? MB : MB + NB, MFMAS = MB * NB;
+  constexpr int READS = MB + NB, MFMAS = MB * NB;
   constexpr int G = MB % 2 == 0 ? 2 * NB : NB;      // groups per sub-step: half a W block's MFMAs (64 cycles) each
   constexpr int MPG = MFMAS / G;                    // MFMAs per group
   constexpr int RPG = (READS + G - 1) / G;          // LDS reads per group
@@ -392,8 +326,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     // the memory pipeline's issue queue while its MFMAs could run.
     auto load_frag = [&](int ks, int buf, int r) {    // r-th fragment read of sub-step ks
       const int pc = ((4 * ks + frag_hi) ^ ((frag_row >> 1) & 7)) * 16;
-      if constexpr (WDIR) af[buf][r] = *reinterpret_cast<const bf16x8_t*>(sa + a_base + r * 16 * 128 + pc);
-      else if (r < NB) bfr[buf][r] = *reinterpret_cast<const bf16x8_t*>(sb + b_base + r * 16 * 128 + pc);
+      if (r < NB) bfr[buf][r] = *reinterpret_cast<const bf16x8_t*>(sb + b_base + r * 16 * 128 + pc);
       else af[buf][r - NB] = *reinterpret_cast<const bf16x8_t*>(sa + a_base + (r - NB) * 16 * 128 + pc);
     };
     __builtin_amdgcn_sched_barrier(0);
@@ -405,25 +338,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
         for (int r = g * RPG; r < (g + 1) * RPG && r < READS; ++r) load_frag(slot, slot & 1, r);
 #pragma unroll
         for (int q = g * LPG; q < (g + 1) * LPG && q < LPS; ++q) issue_one(slot * LPS + q, tp, fill_base, pmask);
-        if constexpr (WDIR) {
-          // W fragment i of sub-step `slot` of the next K-step, one per group of the slot's second half... spread
-          // evenly: fragment i goes with group (2 i + 1) G / (2 NB).  Its registers were last read by the MFMAs of
-          // this sub-step's counterpart one K-step ago (slot 0: in slot 1 of the previous K-step; slot 1: by the
-          // rotated MFMAs in slot 0 of this one).
-#pragma unroll
-          for (int i = 0; i < NB; ++i)
-            if (((2 * i + 1) * G) / (2 * NB) == g) load_w(tp, slot, i, fill_c);
-        }
 #pragma unroll
         for (int e = g * MPG; e < (g + 1) * MPG; ++e) {
           // W block by W block, the activation blocks forwards and backwards in turn: from one MFMA to the next
           // only one of the two operands changes (measured 0.3 to 1.2 % faster than restarting at block 0:
           // the clock under this load is set by power, and operand switching is part of it)
           const int i = e / MB, j = (i & 1) ? MB - 1 - e % MB : e % MB;
-          if constexpr (WDIR)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(slot == 0 ? bw[fill][STEPS - 1][i] : bw[stage][slot - 1][i],
-                                                                af[(slot + 1) & 1][j], acc[i][j], 0, 0, 0);
-          else
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[(slot + 1) & 1][i], af[(slot + 1) & 1][j],
                                                               acc[i][j], 0, 0, 0);
         }
@@ -464,28 +384,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmParams p) {
     }
   }
   // last sub-step of the last K-step
-  if constexpr (WDIR) {
-    // The last K-step's parity is only known at run time: its fragments are picked with bit masks (a branch around
-    // two copies of the MFMAs makes the compiler merge all accumulators behind it, through scratch memory).
-    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-    const uint32_t m1 = ((nk - 1) & 1) ? 0xffffffffu : 0u;
-    bf16x8_t bl[NB];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const u4 x0 = __builtin_bit_cast(u4, bw[0][STEPS - 1][i]), x1 = __builtin_bit_cast(u4, bw[1][STEPS - 1][i]);
-      bl[i] = __builtin_bit_cast(bf16x8_t, (u4)((x1 & m1) | (x0 & ~m1)));
-    }
-#pragma unroll
-    for (int e = 0; e < MFMAS; ++e) {
-      const int i = e / MB, j = (i & 1) ? MB - 1 - e % MB : e % MB;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bl[i], af[(STEPS - 1) & 1][j], acc[i][j], 0, 0, 0);
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < MFMAS; ++e) {
-      const int i = e / MB, j = (i & 1) ? MB - 1 - e % MB : e % MB;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[(STEPS - 1) & 1][i], af[(STEPS - 1) & 1][j], acc[i][j], 0, 0, 0);
-    }
+  for (int e = 0; e < MFMAS; ++e) {
+    const int i = e / MB, j = (i & 1) ? MB - 1 - e % MB : e % MB;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[(STEPS - 1) & 1][i], af[(STEPS - 1) & 1][j], acc[i][j], 0, 0, 0);
   }
   // masked staging loads and prefetches of the last iterations still target this group's LDS
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -704,69 +606,6 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_
   return hipGetLastError();
 }
 
-// Packed-W form (gemm_kernel<..., WDIR>): 256-row tiles, two LDS stages of the activation tile only.
-template <int BM, int BN, int WGM, int WGN, int EPI>
-hipError_t launch_cfg_wdir(const GemmArgs& g, hipStream_t st, int n_tile0 = 0, int n_tiles = -1) {
-  constexpr int BN_OUT = EPI == EPI_GLU_BF16 ? BN / 2 : BN;
-  constexpr int smem = 2 * BM * BK * 2 + 1024;
-  GemmParams p{};
-  p.A = g.A; p.W = g.W; p.out = g.out;
-  p.M = g.M; p.N = g.N; p.K = g.K;
-  p.lda = (int)g.lda; p.ldw = g.K; p.ldc = (int)g.ldc;
-  p.act = g.act;
-  p.scale = residual_scale(g);
-  p.tiles_m = (g.M + BM - 1) / BM;
-  p.tiles_n = n_tiles >= 0 ? n_tiles : (g.N + BN_OUT - 1) / BN_OUT;
-  p.n_tile0 = n_tile0;
-  if (p.tiles_n <= 0) return hipSuccess;
-  static const hipError_t attr_err = hipFuncSetAttribute(
-      reinterpret_cast<const void*>(&gemm_kernel<BM, BN, WGM, WGN, 2, EPI, true, true>),
-      hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-  if (attr_err != hipSuccess) return attr_err;
-  const int total = p.tiles_m * p.tiles_n;
-  const int grid = ((total + 7) / 8) * 8;
-  hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, 2, EPI, true, true>), dim3(grid), dim3(64 * WGM * WGN), smem, st, p);
-  return hipGetLastError();
-}
-
-#ifndef POP_WDIR_WGM
-#define POP_WDIR_WGM 2
-#define POP_WDIR_WGN 2
-#endif
-template <int EPI>
-hipError_t launch_epi_wdir(const GemmArgs& g, hipStream_t st) {
-  const long long cols = EPI == EPI_GLU_BF16 ? 2LL * g.N : g.N;
-  const int tiles_m = (g.M + 255) / 256;
-  const int tiles_n = (int)((cols + 255) / 256);
-  const long long total = (long long)tiles_m * tiles_n;
-  const long long rem = total % 256;
-  if (total > 256 && rem > 0 && rem <= 128 && g.M > 128) {
-    const int tail_cols = (int)((rem + tiles_m - 1) / tiles_m);
-    const int head_cols = tiles_n - tail_cols;
-    if (head_cols > 0 && (long long)tail_cols * ((g.M + 127) / 128) <= 256) {
-      hipError_t e = launch_cfg_wdir<256, 256, POP_WDIR_WGM, POP_WDIR_WGN, EPI>(g, st, 0, head_cols);
-      if (e != hipSuccess) return e;
-      return launch_cfg_wdir<128, 256, POP_WDIR_WGM, POP_WDIR_WGN, EPI>(g, st, head_cols, tail_cols);
-    }
-  }
-  return launch_cfg_wdir<256, 256, POP_WDIR_WGM, POP_WDIR_WGN, EPI>(g, st);
-}
-
-// W [rows, ldw] row-major -> packed: block (rows / 16, K / 32) is 1 KB, lane l = 16 (k chunk) + row holds
-// W[16 nb + l % 16][32 kb + 8 (l / 16) .. + 7].  One thread per 16-byte chunk.
-__global__ __launch_bounds__(256) void pack_w_kernel(const bf16_t* __restrict__ W, long long ldw, int rows, int K,
-                                                      bf16_t* __restrict__ out) {
-  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-  const long long chunks = (long long)rows * (K >> 3);
-  if (idx >= chunks) return;
-  const int lane = (int)(idx & 63);
-  const long long blk = idx >> 6;
-  const int kbs = K >> 5;
-  const int nb = (int)(blk / kbs), kb = (int)(blk % kbs);
-  const uint4 v = *reinterpret_cast<const uint4*>(W + (long long)(nb * 16 + (lane & 15)) * ldw + kb * 32 + (lane >> 4) * 8);
-  *reinterpret_cast<uint4*>(out + idx * 8) = v;
-}
-
 // Tile choice: minimise the estimated time on the critical path,
 //     rounds * K-steps * max(latency floor of a K-step, work-groups per CU * compute time of a K-step),
 //     rounds = ceil(tiles / (256 CUs * work-groups per CU)).
@@ -934,17 +773,6 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
   const long long w_rows = g.epilogue == EPI_GLU_BF16 ? 2LL * g.N : g.N;
   if (((long long)(g.M - 1) * g.lda + g.K) * 2 >= (1LL << 31) || ((w_rows - 1) * g.ldw + g.K) * 2 >= (1LL << 31))
     return hipErrorInvalidValue;
-  if (g.w_packed) {
-    if (g.K % BK || w_rows % 16 || g.N % 16 || (g.batch > 1) || g.W_list) return hipErrorInvalidValue;
-    switch (g.epilogue) {
-      case EPI_STORE_BF16: return launch_epi_wdir<EPI_STORE_BF16>(g, st);
-      case EPI_ADD_F32: return launch_epi_wdir<EPI_ADD_F32>(g, st);
-      case EPI_GLU_BF16: return launch_epi_wdir<EPI_GLU_BF16>(g, st);
-      case EPI_STORE_F32: return launch_epi_wdir<EPI_STORE_F32>(g, st);
-      case EPI_STORE_F16: return launch_epi_wdir<EPI_STORE_F16>(g, st);
-    }
-    return hipErrorInvalidValue;
-  }
   if (const int S = choose_split(g); S > 1) {
     GemmArgs part = g;
     part.K = g.K / S;
@@ -996,14 +824,6 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t st) {
       return launch_cfg<256, 256, 4, 1, 2, EPI_KV256>(g, st);
   }
   return hipErrorInvalidValue;
-}
-
-hipError_t launch_pack_w(const bf16_t* W, int64_t ldw, int rows, int K, bf16_t* out, hipStream_t st) {
-  if (rows % 16 || K % 32 || ldw % 8 || ldw < K) return hipErrorInvalidValue;
-  const long long chunks = (long long)rows * (K / 8);
-  if (chunks == 0) return hipSuccess;
-  hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, W, (long long)ldw, rows, K, out);
-  return hipGetLastError();
 }
 
 bool gemm_kv_cache_supported(int n_kv_heads, int hd) {

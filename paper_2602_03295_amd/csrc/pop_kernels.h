@@ -141,13 +141,7 @@ struct GemmArgs {
   int kv_heads, kv_hd, kv_page_size;
   int64_t kv_pool_stride;    // elements from a layer's K pool to its V pool
   KvQuant kvq;               // bf16 entries or e4m3 codes
-  // W is in the packed layout written by launch_pack_w (ldw ignored): K % 64 == 0, W rows % 16 == 0, plain
-  // (unbatched, unsplit) problems only
-  bool w_packed;
 };
-// Packs W [rows, ldw] (row-major) into 1 KB blocks of 16 rows x 32 k in MFMA operand order; rows % 16 == 0,
-// K % 32 == 0.  `out` holds rows * K elements.
-hipError_t launch_pack_w(const bf16_t* W, int64_t ldw, int rows, int K, bf16_t* out, hipStream_t st);
 // Whether launch_gemm can run EPI_KV_CACHE for this shape (otherwise the caller projects to a scratch matrix
 // and appends with launch_rope_write): head_dim 64 / 128 / 256 and whole heads per wave tile.
 bool gemm_kv_cache_supported(int n_kv_heads, int hd);

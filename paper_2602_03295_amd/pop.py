@@ -92,9 +92,6 @@ lib.pop_generate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(pop_prefill_args)
 lib.pop_op_rmsnorm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p]
 lib.pop_op_gemm.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                             C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
-lib.pop_op_pack_w.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
-lib.pop_op_gemm_packed.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
-                                   C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
 lib.pop_op_gemm_splitk.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                                    C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
 lib.pop_static_scratch_bytes.argtypes = []
@@ -119,7 +116,7 @@ EXPORTED = ["pop_timing_enable", "pop_timing_read", "pop_last_error", "pop_versi
             "pop_workspace_bytes", "pop_cache_create", "pop_cache_destroy", "pop_cache_n_seqs",
             "pop_cache_seq_lens", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_decode_step_gated", "pop_generate",
             "pop_generate_workspace_bytes", "pop_op_rmsnorm",
-            "pop_op_gemm", "pop_op_pack_w", "pop_op_gemm_packed", "pop_op_gemm_splitk", "pop_op_gemm_splitk_static", "pop_static_scratch_bytes", "pop_op_gemv", "pop_op_gemv_norm", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
+            "pop_op_gemm", "pop_op_gemm_splitk", "pop_op_gemm_splitk_static", "pop_static_scratch_bytes", "pop_op_gemv", "pop_op_gemv_norm", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
 
 
 def _check(status: int) -> None:
@@ -400,25 +397,6 @@ def pop_op_gemm(A: torch.Tensor, W: torch.Tensor, epilogue: int = EPI_STORE_BF16
         out = torch.zeros(M, N, dtype=dt, device=A.device)
     _check(lib.pop_op_gemm(A.data_ptr(), A.stride(0), W.data_ptr(), W.stride(0), out.data_ptr(), out.stride(0),
                            M, N, K, epilogue, act, _stream(stream)))
-    return out
-
-
-def pop_op_pack_w(W: torch.Tensor, stream=None) -> torch.Tensor:
-    """W [rows, K] bf16 -> the same values in the blocked layout pop_op_gemm_packed reads."""
-    rows, K = W.shape
-    out = torch.empty(rows * K, dtype=torch.bfloat16, device=W.device)
-    _check(lib.pop_op_pack_w(W.data_ptr(), W.stride(0), rows, K, out.data_ptr(), _stream(stream)))
-    return out
-
-
-def pop_op_gemm_packed(A: torch.Tensor, Wp: torch.Tensor, N: int, epilogue: int = EPI_STORE_BF16, act: int = 0,
-                       out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    M, K = A.shape
-    if out is None:
-        dt = torch.bfloat16 if epilogue in (EPI_STORE_BF16, EPI_GLU_BF16) else torch.float32
-        out = torch.zeros(M, N, dtype=dt, device=A.device)
-    _check(lib.pop_op_gemm_packed(A.data_ptr(), A.stride(0), Wp.data_ptr(), out.data_ptr(), out.stride(0),
-                                  M, N, K, epilogue, act, _stream(stream)))
     return out
 
 
