@@ -187,9 +187,10 @@ def test_qwen3vl_shape_full_depth_6144_positions(pop):
     """The Qwen3-VL-8B-style workload as stated: all 36 layers, vocab 151936, 6144 positions of which 64..4159 are
     supplied hidden states ~ N(0, 1), L_keep = 26.  Every layer's K and V and the logits against the oracle, which
     needs a few minutes on the host and reports after every layer.  Asserted: the error stays under the guard derived
-    from the bf16-input floor of the 32-layer Llama-shape run (same width, same recipe, six FFN columns in seven; the
-    visual rows are unit-variance hidden states like any other row after the first norm); the per-layer table is
-    printed, and the stated 2e-2 is reported as met or missed per layer."""
+    from the bf16-input floor of this same workload (CPU only, tests/golden/make_bf16_input_floor.py --shape qwen3vl8b
+    --tokens 6144 --l-keep 26 --visual 64 4096: it crosses 2e-2 at layer 8 and ends at 4.3 %; at equal depth it lies
+    above the Llama-shape floor, 2.0 % against 1.6 % at layer 8, which is why that table cannot serve here); the
+    per-layer table is printed, and the stated 2e-2 is reported as met or missed per layer."""
     cfg = synth.get_config("qwen3vl8b")
     n, l_keep = 6144, 26
     tokens = synth.make_tokens(cfg["vocab"], n, seed=1)
@@ -214,7 +215,7 @@ def test_qwen3vl_shape_full_depth_6144_positions(pop):
             f.write(f"oracle layer {l} of {cfg['n_layers']} done\n")
 
     Kc, Vc, ref = oracle_pop_prefill_with_progress(cfg, host, tokens, l_keep, emb.numpy(), [(64, 4096)], progress)
-    floor, floor_logits = load_floor("bf16_input_floor_llama8b_2048_lkeep24_of_32.txt")
+    floor, floor_logits = load_floor("bf16_input_floor_qwen3vl8b_6144_lkeep26_of_36.txt")
     table, late = [], []
     for l in range(cfg["n_layers"]):
         k = cache.gather(l, 0, bt[0], n).float().cpu().numpy()
@@ -223,7 +224,7 @@ def test_qwen3vl_shape_full_depth_6144_positions(pop):
         table.append(f"{l + 1}:{100 * ek:.2f}/{100 * ev:.2f}")
         if max(ek, ev) > TOL:
             late.append(l + 1)
-        bound = floor_guard(floor[min(l + 1, 32)])
+        bound = floor_guard(floor[l + 1])
         assert max(ek, ev) <= bound, f"layer {l + 1}: K {ek:.4f} V {ev:.4f} (guard {bound:.4f})"
     el = rel_err(logits, ref)
     top = np.argsort(ref)[-2:]
