@@ -76,10 +76,14 @@ def test_ragged_batch_paged_matches_oracle_and_single_runs(pop):
     b = 3
     solo = DeviceRun(pop, cfg, W, [lens[b]])
     l2 = solo.prefill(tokens[run.cu[b]:run.cu[b + 1]], 2)
-    k1, v1 = run.kv(3, b)
-    k2, v2 = solo.kv(3, 0)
-    assert np.array_equal(k1, k2) and np.array_equal(v1, v2)
-    assert rel_err(l2[0], logits[b].astype(np.float64)) <= 1e-3
+    # body rows bit for bit in every layer; the boundary row (the last one) takes another route in a batch of five
+    # (tiled projections with a split of K) than alone (the few-row kernels): another summation order, so a bf16 step
+    for l in range(cfg["n_layers"]):
+        k1, v1 = run.kv(l, b)
+        k2, v2 = solo.kv(l, 0)
+        assert np.array_equal(k1[:-1], k2[:-1]) and np.array_equal(v1[:-1], v2[:-1]), f"layer {l + 1}"
+        assert rel_err(k1[-1], k2[-1].astype(np.float64)) <= 2.0 ** -7 and rel_err(v1[-1], v2[-1].astype(np.float64)) <= 2.0 ** -7
+    assert rel_err(l2[0], logits[b].astype(np.float64)) <= 2.0 ** -8    # (the boundary row's logits, for the same reason)
 
 
 def test_body_only_then_decode_step_equals_pop_mode(pop):
