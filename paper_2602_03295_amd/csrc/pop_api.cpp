@@ -489,7 +489,9 @@ void record_kv_first(pop_cache* c, const pop_prefill_args* a, const PrunePlan& p
 
 // Projection of the B rows of a decode-style layer.  The GEMV kernel streams every weight row once per row
 // group and is the fastest form for one or a few rows; from kRowsForGemm rows on the tiled MFMA GEMM with
-// its small tiles (and the split of a long K) reads the weights faster than the GEMV kernel's 8-row form.
+// its small tiles (and the split of a long K) reads the weights faster than the GEMV kernel's 8-row form
+// (measured on decode steps of 8 sequences at the Llama-3.1-8B shape: 4.75 ms per step through the tiled GEMM, 7.6 ms
+// through the 8-row GEMV, whose 256 work-groups for 4096 output rows leave a CU with four waves' worth of loads).
 constexpr int kRowsForGemm = 5;
 constexpr int rows_for_gemm() { return kRowsForGemm; }
 

@@ -17,10 +17,15 @@ __device__ __forceinline__ float glu_act_f(float g, int act) {
   return 0.5f * g * (1.f + tanhf(u));
 }
 
+// acc += sum of the eight bf16 products of w and x, with v_dot2_f32_bf16 (two products and the fp32 sum per
+// instruction, operands taken as packed bf16 without conversion): a quarter of the vector instructions of
+// converting to fp32 and multiplying, which is what kept the forms with several batch rows below the HBM rate.
 __device__ __forceinline__ void fma8(float (&acc), const uint4& w, const uint4& x) {
-  acc += bf16lo(w.x) * bf16lo(x.x) + bf16hi(w.x) * bf16hi(x.x) + bf16lo(w.y) * bf16lo(x.y) +
-         bf16hi(w.y) * bf16hi(x.y) + bf16lo(w.z) * bf16lo(x.z) + bf16hi(w.z) * bf16hi(x.z) +
-         bf16lo(w.w) * bf16lo(x.w) + bf16hi(w.w) * bf16hi(x.w);
+  typedef __bf16 bf2_t __attribute__((ext_vector_type(2)));
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2_t, w.x), __builtin_bit_cast(bf2_t, x.x), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2_t, w.y), __builtin_bit_cast(bf2_t, x.y), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2_t, w.z), __builtin_bit_cast(bf2_t, x.z), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2_t, w.w), __builtin_bit_cast(bf2_t, x.w), acc, false);
 }
 
 // Each wave owns RW weight rows (for GLU: RW gate rows and the matching RW up rows) and all M batch
@@ -35,7 +40,8 @@ template <int M, int EPI, int RW, int U, bool NORM>
 __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x, const float* __restrict__ xf,
                                                    const float* __restrict__ gamma, float eps,
                                                    const bf16_t* __restrict__ W, void* __restrict__ out, int N, int K,
-                                                   long long ldo, int act, float scale /* ADD: out += scale * C */) {
+                                                   long long ldo, int act, float scale /* ADD: out += scale * C */,
+                                                   int m_valid /* rows that exist (<= M); the others repeat the last */) {
   constexpr int NR = EPI == GEMV_GLU_BF16 ? 2 * RW : RW;  // weight rows streamed per wave
   typedef __attribute__((__vector_size__(16))) unsigned int u32x4_t;
   extern __shared__ __attribute__((aligned(16))) unsigned char gemv_smem[];   // NORM: bf16 [M][K], then float [M][4]
@@ -101,7 +107,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x,
   if (n0 >= N) return;
   auto x_chunk = [&](int m, int k) {
     return NORM ? *reinterpret_cast<const uint4*>(xs + (size_t)m * K + k)
-                : *reinterpret_cast<const uint4*>(x + (size_t)m * K + k);
+                : *reinterpret_cast<const uint4*>(x + (size_t)min(m, m_valid - 1) * K + k);
   };
   float acc[NR][M];
 #pragma unroll
@@ -153,6 +159,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(const bf16_t* __restrict__ x,
     if (n >= N) break;
 #pragma unroll
     for (int m = 0; m < M; ++m) {
+      if (m >= m_valid) break;
       if (EPI == GEMV_GLU_BF16) {
         reinterpret_cast<bf16_t*>(out)[(size_t)m * ldo + n] = f32_to_bf16(glu_act_f(acc[r][m], act) * acc[r + RW][m]);
       } else {
@@ -170,6 +177,7 @@ struct GemvIn {
   const float* gamma;
   float eps;
   float scale;   // GEMV_ADD_F32: out += scale * C
+  int m_valid = 0;   // 0: all M rows of the instantiation exist; otherwise how many do (bf16 input only)
 };
 
 template <int M, int EPI, int RW, int U>
@@ -177,10 +185,10 @@ void launch_gemv_cfg(const GemvIn& in, const bf16_t* W, void* out, int N, int K,
   const int blocks = (N + 4 * RW - 1) / (4 * RW);
   if (in.xf)
     hipLaunchKernelGGL((gemv_kernel<M, EPI, RW, U, true>), dim3(blocks), dim3(256), (size_t)M * K * 2 + 16 * M, st,
-                       in.x, in.xf, in.gamma, in.eps, W, out, N, K, ldo, act, in.scale);
+                       in.x, in.xf, in.gamma, in.eps, W, out, N, K, ldo, act, in.scale, M);
   else
     hipLaunchKernelGGL((gemv_kernel<M, EPI, RW, U, false>), dim3(blocks), dim3(256), 0, st, in.x, in.xf, in.gamma,
-                       in.eps, W, out, N, K, ldo, act, in.scale);
+                       in.eps, W, out, N, K, ldo, act, in.scale, in.m_valid > 0 ? in.m_valid : M);
 }
 
 // Rows per wave and unroll depth: few batch rows leave registers for deep unrolling; a small N gets
@@ -234,8 +242,13 @@ void launch_gemv_in(const GemvIn& in, const bf16_t* W, void* out, int M, int N, 
       if (mm == 3) { launch_gemv_m<2>(xs, W, os, N, K, ldo, epilogue, act, st);
                      launch_gemv_m<1>(rows_from(xs, 2, K), W, reinterpret_cast<char*>(os) + 2 * ldo * osz, N, K, ldo, epilogue, act, st); }
       else launch_gemv_m<4>(xs, W, os, N, K, ldo, epilogue, act, st);
-    } else if (mm == 8) launch_gemv_m<8>(xs, W, os, N, K, ldo, epilogue, act, st);
-    else {  // 5..7: 4 + remainder
+    } else if (mm == 8 || !xs.xf) {
+      // 5..7 rows of bf16 input run the 8-row form with the missing rows repeating the last one (never stored):
+      // the weights are streamed once
+      GemvIn x8 = xs;
+      x8.m_valid = mm;
+      launch_gemv_m<8>(x8, W, os, N, K, ldo, epilogue, act, st);
+    } else {  // 5..7 fp32 rows to be normalised: 4 + remainder
       launch_gemv_m<4>(xs, W, os, N, K, ldo, epilogue, act, st);
       launch_gemv_in(rows_from(xs, 4, K), W, reinterpret_cast<char*>(os) + 4 * ldo * osz, mm - 4, N, K, ldo, epilogue, act, st);
     }
@@ -247,7 +260,7 @@ using namespace decode_impl;
 
 void launch_gemv(const bf16_t* x, const bf16_t* W, void* out, int M, int N, int K, int64_t ldo, int epilogue,
                  int act, hipStream_t st, float scale) {
-  launch_gemv_in(GemvIn{x, nullptr, nullptr, 0.f, scale}, W, out, M, N, K, ldo, epilogue, act, st);
+  launch_gemv_in(GemvIn{x, nullptr, nullptr, 0.f, scale, 0}, W, out, M, N, K, ldo, epilogue, act, st);
 }
 
 bool gemv_norm_supported(int M, int K) {
@@ -256,7 +269,7 @@ bool gemv_norm_supported(int M, int K) {
 
 void launch_gemv_norm(const float* xf, const float* gamma, float eps, const bf16_t* W, void* out, int M, int N, int K,
                       int64_t ldo, int epilogue, int act, hipStream_t st) {
-  launch_gemv_in(GemvIn{nullptr, xf, gamma, eps, 1.f}, W, out, M, N, K, ldo, epilogue, act, st);
+  launch_gemv_in(GemvIn{nullptr, xf, gamma, eps, 1.f, 0}, W, out, M, N, K, ldo, epilogue, act, st);
 }
 
 // ------------------------------------------------------------------------------------- RoPE + append
