@@ -210,7 +210,8 @@ struct Workspace {
       o_tr_cu, o_tr_t64_seq, o_tr_t64_start;
   // device buffers
   size_t o_h, o_a, o_qkv, o_attn, o_u, o_vT, o_cs_g, o_cs_l, o_cs_tail, o_a_multi, o_kv_out;
-  size_t o_xb, o_ab, o_qkvb, o_qb, o_attnb, o_ub, o_part, o_splitk;
+  size_t o_dcs_g, o_dcs_l;   // (cos, sin) of the decode-style rows' positions, [B][hd/2] per RoPE base
+  size_t o_xb, o_ab, o_qkvb, o_attnb, o_ub, o_part, o_splitk;
   size_t splitk_bytes;
   size_t total;
   int Tp_max, nt64_max, nta_max, n_splits_max;
@@ -268,13 +269,14 @@ Workspace carve(const pop_config& c, int T, int B, int maxp) {
   w.o_cs_g = take(8 * (size_t)T * (hd / 2));
   w.o_cs_l = take(8 * (size_t)T * (hd / 2));
   w.o_cs_tail = c.sliding_window > 0 ? take(8 * (size_t)T * (hd / 2)) : o;
+  w.o_dcs_g = take(8 * (size_t)B * (hd / 2));
+  w.o_dcs_l = take(8 * (size_t)B * (hd / 2));
   const size_t rc = std::min(kKvChunk, c.n_layers);
   w.o_a_multi = take(2 * rc * (size_t)T * d);
   w.o_kv_out = take(2 * rc * (size_t)T * 2 * Dkv);
   w.o_xb = take(4 * (size_t)B * d);
   w.o_ab = take(2 * (size_t)B * std::max(d, Dq));
   w.o_qkvb = take(4 * (size_t)B * Dqkv);
-  w.o_qb = take(2 * (size_t)B * Dq);
   w.o_attnb = take(2 * (size_t)B * Dq);
   w.o_ub = take(2 * (size_t)B * f);
   w.o_part = take(4 * (size_t)B * c.n_q_heads * w.n_splits_max * (hd + 2));
@@ -393,6 +395,17 @@ struct LayerCtx {
   const float* gates = nullptr;       // HOST [n_layers] virtual gates of the stage this context runs, or nullptr
   float gate(int l /*1-based*/) const { return gates ? gates[l - 1] : 1.f; }
 };
+
+// (cos, sin) tables of the B decode-style rows at positions pos[0..B-1], one per RoPE base in use: what the decode
+// attention kernel rotates the query token's q and k with.  Once per pass over the layers.
+void decode_rope_tables(const LayerCtx& x, const int32_t* pos, int B) {
+  const pop_config& c = x.m->cfg;
+  pop::launch_rope_table(pos, at<float2>(x.ws, x.w->o_dcs_g), B, c.head_dim, (double)c.rope_theta, x.st);
+  bool any_local = false;
+  for (int l = 1; l <= c.n_layers; ++l) any_local = any_local || !layer_is_global(c, l);
+  if (any_local)
+    pop::launch_rope_table(pos, at<float2>(x.ws, x.w->o_dcs_l), B, c.head_dim, (double)c.rope_theta_local, x.st);
+}
 
 // The prefill's pruning, resolved from the arguments (Sec. 2.2: a skip set; Sec. 3.3: applied to the
 // body tokens of the prefill only).
@@ -581,7 +594,6 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   float* xb = at<float>(x.ws, x.w->o_xb);
   bf16_t* ab = at<bf16_t>(x.ws, x.w->o_ab);
   float* qkvb = at<float>(x.ws, x.w->o_qkvb);
-  bf16_t* qb = at<bf16_t>(x.ws, x.w->o_qb);
   bf16_t* attnb = at<bf16_t>(x.ws, x.w->o_attnb);
   bf16_t* ub = at<bf16_t>(x.ws, x.w->o_ub);
   const bool glob = layer_is_global(c, l);
@@ -590,12 +602,14 @@ pop_status decode_layer(const LayerCtx& x, int l /*1-based*/, int B, const int32
   if (pop_status s = normed_few_rows_projection(x, xb, (const float*)lw.norm_in, ab, lw.wqkv, qkvb, B, Dqkv, d, Dqkv,
                                                 pop::GEMV_STORE_F32, 0, &qkv_parts))
     return s;
-  pop::launch_rope_append(qkv_parts > 1 ? at<float>(x.ws, x.w->o_splitk) : qkvb, Dqkv, qb, c.n_q_heads, c.n_kv_heads, c.head_dim, pos, slot,
-                          glob ? (double)c.rope_theta : (double)c.rope_theta_local, x.c->k_pool(l - 1),
-                          x.c->v_pool(l - 1), c.page_size, B, x.st, (const float*)lw.q_norm, (const float*)lw.k_norm,
-                          c.rms_eps, qkv_parts, (size_t)B * Dqkv, kv_quant(c));
+  // RoPE and the append of the new entries happen inside the attention kernel (decode_rope_tables has run for
+  // these positions); `slot` is implied by the block table there
+  (void)slot;
   pop::AttnDecodeArgs ad{};
-  ad.q = qb;
+  ad.qkv_raw = qkv_parts > 1 ? at<float>(x.ws, x.w->o_splitk) : qkvb;
+  ad.ld = Dqkv; ad.n_parts = qkv_parts; ad.part_stride = (size_t)B * Dqkv;
+  ad.cs = at<float2>(x.ws, glob ? x.w->o_dcs_g : x.w->o_dcs_l);
+  ad.q_gamma = (const float*)lw.q_norm; ad.k_gamma = (const float*)lw.k_norm; ad.qk_eps = c.rms_eps;
   ad.k_pool = x.c->k_pool(l - 1);
   ad.v_pool = x.c->v_pool(l - 1);
   ad.block_table = at<int32_t>(x.ws, x.w->o_bt);
@@ -1397,6 +1411,7 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
   const int32_t* bnd_row = at<int32_t>(ws, w.o_bnd_row);
   float* xb = at<float>(ws, w.o_xb);
   bool rows_in_xb = false;   // the boundary rows' current state is in xb rather than in h
+  bool dec_tables_done = false;
   for (int l = 1; l <= cfg.n_layers;) {
     if (!plan.pruned[l]) {
       if (rows_in_xb) {
@@ -1417,6 +1432,10 @@ pop_status pop_prefill(pop_model* m, pop_cache* c, const pop_prefill_args* a, fl
       pop::launch_gather_rows(h, bnd_row, xb, B, d, st);
       x.ab_gamma = nullptr;
       rows_in_xb = true;
+      if (!dec_tables_done) {
+        decode_rope_tables(x, at<int32_t>(ws, w.o_bnd_pos), B);
+        dec_tables_done = true;
+      }
       for (int j = l; j <= r; ++j) {
         // what reads these rows next: the following layer of the run, the LM head, or (a kept layer follows) h
         const float* next = j < r ? (const float*)m->layers[j].norm_in
@@ -1498,6 +1517,7 @@ pop_status pop_decode_step_gated(pop_model* m, pop_cache* c, const int32_t* host
   x.gates = host_gates;
   pop::launch_embed((const bf16_t*)m->w.embed, at<int32_t>(ws, w.o_tokens), nullptr, nullptr, at<float>(ws, w.o_xb),
                     B, cfg.d_model, st);
+  decode_rope_tables(x, at<int32_t>(ws, w.o_bnd_pos), B);
   for (int l = 1; l <= cfg.n_layers; ++l) {
     const float* next = (const float*)(l < cfg.n_layers ? m->layers[l].norm_in : m->w.final_norm);
     if (pop_status s = decode_layer(x, l, B, at<int32_t>(ws, w.o_bnd_pos), at<int32_t>(ws, w.o_bnd_slot), max_len, next))
@@ -1588,6 +1608,7 @@ pop_status pop_generate(pop_model* m, pop_cache* c, const pop_prefill_args* a, i
     for (int s = 1; s < n_new; ++s) {
       pop::launch_embed((const bf16_t*)m->w.embed, d_tok, nullptr, nullptr, at<float>(ws, w.o_xb), B, cfg.d_model, st);
       x.ab_gamma = nullptr;
+      decode_rope_tables(x, d_gpos + (size_t)(s - 1) * B, B);
       for (int l = 1; l <= cfg.n_layers; ++l) {
         const float* next = (const float*)(l < cfg.n_layers ? m->layers[l].norm_in : m->w.final_norm);
         if (pop_status e = decode_layer(x, l, B, d_gpos + (size_t)(s - 1) * B, d_gslot + (size_t)(s - 1) * B, max_len + s,

@@ -1,4 +1,5 @@
-// Decode-step kernels: one row per sequence through a full layer against the paged KV cache.
+// Decode-step kernels: one row per sequence through a full layer against the paged KV cache (few-row
+// projections, attention over the cache with RoPE and the append of the new entry inside, greedy choice).
 // They carry the boundary token of Sec. 3.3 ("Boundary Handling for the Last Input Token": x_N is
 // the first decode step with the full model) and pop_decode_step (Sec. 3.2, decode operator).
 // With M <= 8 rows every projection streams its weights once: these kernels are HBM-bound.
@@ -272,93 +273,6 @@ void launch_gemv_norm(const float* xf, const float* gamma, float eps, const bf16
   launch_gemv_in(GemvIn{nullptr, xf, gamma, eps, 1.f, 0}, W, out, M, N, K, ldo, epilogue, act, st);
 }
 
-// ------------------------------------------------------------------------------------- RoPE + append
-namespace decode_impl {
-__global__ __launch_bounds__(128) void rope_append_kernel(const float* __restrict__ qkv, int ld,
-                                                          bf16_t* __restrict__ q_out, int n_q_heads,
-                                                          int n_kv_heads, int hd, const int32_t* __restrict__ pos,
-                                                          const int32_t* __restrict__ slot,
-                                                          double neg2_over_hd_log2theta, bf16_t* __restrict__ k_pool,
-                                                          bf16_t* __restrict__ v_pool, int P,
-                                                          const float* __restrict__ q_gamma,
-                                                          const float* __restrict__ k_gamma, float qk_eps,
-                                                          int n_parts, size_t part_stride, KvQuant kvq) {
-  __shared__ float red[2];
-  const int b = blockIdx.x, head = blockIdx.y;
-  const int half = hd >> 1;
-  const int i = threadIdx.x;
-  const float* row = qkv + (size_t)b * ld + (size_t)head * hd;
-  const int s = slot[b];
-  // per-head QK-norm (uniform over the block): RMS over the head's hd values, before the rotation
-  const float* gamma = head < n_q_heads ? q_gamma : (head < n_q_heads + n_kv_heads ? k_gamma : nullptr);
-  float x = i < half ? row[i] : 0.f, y = i < half ? row[i + half] : 0.f;
-  for (int p = 1; p < n_parts; ++p)
-    if (i < half) {
-      x += row[p * part_stride + i];
-      y += row[p * part_stride + i + half];
-    }
-  if (gamma) {
-    const float ss = wave_sum(x * x + y * y);
-    if ((i & 63) == 0) red[i >> 6] = ss;
-    __syncthreads();
-    const float rstd = 1.0f / sqrtf((red[0] + red[1]) / (float)hd + qk_eps);
-    if (i < half) {
-      x *= rstd * gamma[i];
-      y *= rstd * gamma[i + half];
-    }
-  }
-  if (i >= half) return;
-  if (head < n_q_heads + n_kv_heads) {
-    const double ang = (double)pos[b] * exp2((double)i * neg2_over_hd_log2theta);
-    double sd, cd;
-    sincos(ang, &sd, &cd);
-    const float c = (float)cd, sn = (float)sd;
-    const float rlo = x * c - y * sn, rhi = y * c + x * sn;
-    const bf16_t lo = f32_to_bf16(rlo), hi = f32_to_bf16(rhi);
-    if (head < n_q_heads) {
-      bf16_t* o = q_out + ((size_t)b * n_q_heads + head) * hd;
-      o[i] = lo;
-      o[i + half] = hi;
-    } else {
-      const int hh = head - n_q_heads;
-      const size_t eoff = (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
-      if (kvq.fp8) {     // one-byte e4m3 codes
-        unsigned char* o = reinterpret_cast<unsigned char*>(k_pool) + eoff;
-        o[i] = (unsigned char)e4m3_encode(rlo * kvq.k_inv);
-        o[i + half] = (unsigned char)e4m3_encode(rhi * kvq.k_inv);
-      } else {
-        bf16_t* o = k_pool + eoff;
-        o[i] = lo;
-        o[i + half] = hi;
-      }
-    }
-  } else {
-    const int hh = head - n_q_heads - n_kv_heads;
-    const size_t eoff = (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
-    if (kvq.fp8) {
-      unsigned char* o = reinterpret_cast<unsigned char*>(v_pool) + eoff;
-      o[i] = (unsigned char)e4m3_encode(x * kvq.v_inv);
-      o[i + half] = (unsigned char)e4m3_encode(y * kvq.v_inv);
-    } else {
-      bf16_t* o = v_pool + eoff;
-      o[i] = f32_to_bf16(x);
-      o[i + half] = f32_to_bf16(y);
-    }
-  }
-}
-}  // namespace decode_impl
-using namespace decode_impl;
-
-void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
-                        const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool, bf16_t* v_pool,
-                        int page_size, int B, hipStream_t st, const float* q_gamma, const float* k_gamma,
-                        float qk_eps, int n_parts, size_t part_stride, KvQuant kvq) {
-  if (B <= 0) return;
-  hipLaunchKernelGGL(rope_append_kernel, dim3(B, n_q_heads + 2 * n_kv_heads), dim3(128), 0, st, qkv, ld, q_out,
-                     n_q_heads, n_kv_heads, hd, pos, slot, -2.0 / (double)hd * log2(theta), k_pool, v_pool,
-                     page_size, q_gamma, k_gamma, qk_eps, n_parts, part_stride, kvq);
-}
-
 // ------------------------------------------------------------------------------------- decode attention
 namespace decode_impl {
 
@@ -399,17 +313,8 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
     return;
   }
 
-  // ---- scores
-  float qv[GT][8];
-#pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    if (g < G) {
-      const uint4 w = *reinterpret_cast<const uint4*>(a.q + ((size_t)b * a.n_q_heads + kvh * G + g) * HD + li * 8);
-      qv[g][0] = bf16lo(w.x); qv[g][1] = bf16hi(w.x); qv[g][2] = bf16lo(w.y); qv[g][3] = bf16hi(w.y);
-      qv[g][4] = bf16lo(w.z); qv[g][5] = bf16hi(w.z); qv[g][6] = bf16lo(w.w); qv[g][7] = bf16hi(w.w);
-    }
-  }
-  // this thread's K and V chunks of the split are requested up front (one memory round trip)
+  // this thread's K and V chunks of the split are requested up front (one memory round trip), before the query
+  // rows are prepared (the slot of the query position is read too, and replaced further down)
   constexpr int NIT = KCH / KPI;
   uint4 kw[NIT], vw[NIT];
 #pragma unroll
@@ -429,6 +334,97 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
       } else {
         kw[it] = *reinterpret_cast<const uint4*>(a.k_pool + off);
         vw[it] = *reinterpret_cast<const uint4*>(a.v_pool + off);
+      }
+    }
+  }
+  // ---- RoPE + append inside this kernel: head rows from the projection's fp32 output
+  constexpr int HALF = HD / 2;
+  const bool hi_half = li * 8 >= HALF;          // this thread's 8 dims are the second members of their pairs
+  float rc[8], rs[8];                           // (cos, sin) of those pairs
+  {
+    const float4* csp = reinterpret_cast<const float4*>(a.cs + (size_t)b * HALF + (li * 8) % HALF);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float4 t = csp[e];
+      rc[2 * e] = t.x; rs[2 * e] = t.y; rc[2 * e + 1] = t.z; rs[2 * e + 1] = t.w;
+    }
+  }
+  // This thread's 8 values of the head that starts at column `col` of the raw row: parts added, optionally
+  // RMS-normalised over the head (its LPK lanes are an aligned group), optionally rotated.  x = own dims, y = the
+  // other members of their pairs; first members become x c - y s, second members x c + y s.
+  auto head8 = [&](int col, const float* gamma, bool rotate, float* out8) {
+    const float* row = a.qkv_raw + (size_t)b * a.ld + col;
+    float x[8], y[8];
+    {
+      const float4 x0 = *reinterpret_cast<const float4*>(row + li * 8), x1 = *reinterpret_cast<const float4*>(row + li * 8 + 4);
+      const float4 y0 = *reinterpret_cast<const float4*>(row + ((li * 8) ^ HALF)), y1 = *reinterpret_cast<const float4*>(row + ((li * 8) ^ HALF) + 4);
+      x[0] = x0.x; x[1] = x0.y; x[2] = x0.z; x[3] = x0.w; x[4] = x1.x; x[5] = x1.y; x[6] = x1.z; x[7] = x1.w;
+      y[0] = y0.x; y[1] = y0.y; y[2] = y0.z; y[3] = y0.w; y[4] = y1.x; y[5] = y1.y; y[6] = y1.z; y[7] = y1.w;
+    }
+    for (int p = 1; p < a.n_parts; ++p) {
+      const float* rp = row + (size_t)p * a.part_stride;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { x[e] += rp[li * 8 + e]; y[e] += rp[((li * 8) ^ HALF) + e]; }
+    }
+    if (gamma) {
+      float s2 = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s2 += x[e] * x[e];
+      s2 = group_sum<(LPK < 16 ? LPK : 16)>(s2);
+      if (LPK > 16) s2 += __shfl_xor(s2, 16, 64);
+      const float rstd = 1.0f / sqrtf(s2 / (float)HD + a.qk_eps);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { x[e] *= rstd * gamma[li * 8 + e]; y[e] *= rstd * gamma[((li * 8) ^ HALF) + e]; }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      out8[e] = !rotate ? x[e] : (hi_half ? x[e] * rc[e] + y[e] * rs[e] : x[e] * rc[e] - y[e] * rs[e]);
+  };
+
+  // ---- scores
+  float qv[GT][8];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    if (g < G) {
+      head8((kvh * G + g) * HD, a.q_gamma, true, qv[g]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qv[g][e] = bf16_to_f32(f32_to_bf16(qv[g][e]));   // q enters the scores as bf16
+    }
+  }
+  // The query position's own entry, if its key falls into this split: formed here (every group of lanes computes
+  // the same values; the group whose key it is stores them and keeps them in place of a load).
+  const int kk_new = qpos - k_first;
+  const bool has_new = kk_new >= 0 && kk_new < n_keys;
+  uint4 k_new = make_uint4(0, 0, 0, 0), v_new = make_uint4(0, 0, 0, 0);
+  if (has_new) {
+    float k8[8], v8[8];
+    head8((a.n_q_heads + kvh) * HD, a.k_gamma, true, k8);
+    head8((a.n_q_heads + a.n_kv_heads + kvh) * HD, nullptr, false, v8);
+    if (fp8) {
+      k_new.x = e4m3_pack4(k8[0] * a.kvq.k_inv, k8[1] * a.kvq.k_inv, k8[2] * a.kvq.k_inv, k8[3] * a.kvq.k_inv);
+      k_new.y = e4m3_pack4(k8[4] * a.kvq.k_inv, k8[5] * a.kvq.k_inv, k8[6] * a.kvq.k_inv, k8[7] * a.kvq.k_inv);
+      v_new.x = e4m3_pack4(v8[0] * a.kvq.v_inv, v8[1] * a.kvq.v_inv, v8[2] * a.kvq.v_inv, v8[3] * a.kvq.v_inv);
+      v_new.y = e4m3_pack4(v8[4] * a.kvq.v_inv, v8[5] * a.kvq.v_inv, v8[6] * a.kvq.v_inv, v8[7] * a.kvq.v_inv);
+    } else {
+      k_new = make_uint4(pack_bf16x2(k8[0], k8[1]), pack_bf16x2(k8[2], k8[3]), pack_bf16x2(k8[4], k8[5]), pack_bf16x2(k8[6], k8[7]));
+      v_new = make_uint4(pack_bf16x2(v8[0], v8[1]), pack_bf16x2(v8[2], v8[3]), pack_bf16x2(v8[4], v8[5]), pack_bf16x2(v8[6], v8[7]));
+    }
+  }
+  if (has_new) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      if (kslot + it * KPI != kk_new) continue;
+      // the new entry: stored (the pools are written in this mode) and kept in place of what was loaded
+      kw[it] = k_new;
+      vw[it] = v_new;
+      const int page = bt[qpos >> lgP];
+      const size_t off = (((size_t)page * a.n_kv_heads + kvh) * P + (qpos & (P - 1))) * HD + li * 8;
+      if (fp8) {
+        *reinterpret_cast<uint2*>(reinterpret_cast<unsigned char*>(const_cast<bf16_t*>(a.k_pool)) + off) = make_uint2(k_new.x, k_new.y);
+        *reinterpret_cast<uint2*>(reinterpret_cast<unsigned char*>(const_cast<bf16_t*>(a.v_pool)) + off) = make_uint2(v_new.x, v_new.y);
+      } else {
+        *reinterpret_cast<uint4*>(const_cast<bf16_t*>(a.k_pool) + off) = k_new;
+        *reinterpret_cast<uint4*>(const_cast<bf16_t*>(a.v_pool) + off) = v_new;
       }
     }
   }
