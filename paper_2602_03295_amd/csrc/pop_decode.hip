@@ -273,6 +273,93 @@ void launch_gemv_norm(const float* xf, const float* gamma, float eps, const bf16
   launch_gemv_in(GemvIn{nullptr, xf, gamma, eps, 1.f, 0}, W, out, M, N, K, ldo, epilogue, act, st);
 }
 
+// ------------------------------------------------------------------------------------- RoPE + append
+namespace decode_impl {
+__global__ __launch_bounds__(128) void rope_append_kernel(const float* __restrict__ qkv, int ld,
+                                                          bf16_t* __restrict__ q_out, int n_q_heads,
+                                                          int n_kv_heads, int hd, const int32_t* __restrict__ pos,
+                                                          const int32_t* __restrict__ slot,
+                                                          double neg2_over_hd_log2theta, bf16_t* __restrict__ k_pool,
+                                                          bf16_t* __restrict__ v_pool, int P,
+                                                          const float* __restrict__ q_gamma,
+                                                          const float* __restrict__ k_gamma, float qk_eps,
+                                                          int n_parts, size_t part_stride, KvQuant kvq) {
+  __shared__ float red[2];
+  const int b = blockIdx.x, head = blockIdx.y;
+  const int half = hd >> 1;
+  const int i = threadIdx.x;
+  const float* row = qkv + (size_t)b * ld + (size_t)head * hd;
+  const int s = slot[b];
+  // per-head QK-norm (uniform over the block): RMS over the head's hd values, before the rotation
+  const float* gamma = head < n_q_heads ? q_gamma : (head < n_q_heads + n_kv_heads ? k_gamma : nullptr);
+  float x = i < half ? row[i] : 0.f, y = i < half ? row[i + half] : 0.f;
+  for (int p = 1; p < n_parts; ++p)
+    if (i < half) {
+      x += row[p * part_stride + i];
+      y += row[p * part_stride + i + half];
+    }
+  if (gamma) {
+    const float ss = wave_sum(x * x + y * y);
+    if ((i & 63) == 0) red[i >> 6] = ss;
+    __syncthreads();
+    const float rstd = 1.0f / sqrtf((red[0] + red[1]) / (float)hd + qk_eps);
+    if (i < half) {
+      x *= rstd * gamma[i];
+      y *= rstd * gamma[i + half];
+    }
+  }
+  if (i >= half) return;
+  if (head < n_q_heads + n_kv_heads) {
+    const double ang = (double)pos[b] * exp2((double)i * neg2_over_hd_log2theta);
+    double sd, cd;
+    sincos(ang, &sd, &cd);
+    const float c = (float)cd, sn = (float)sd;
+    const float rlo = x * c - y * sn, rhi = y * c + x * sn;
+    const bf16_t lo = f32_to_bf16(rlo), hi = f32_to_bf16(rhi);
+    if (head < n_q_heads) {
+      bf16_t* o = q_out + ((size_t)b * n_q_heads + head) * hd;
+      o[i] = lo;
+      o[i + half] = hi;
+    } else {
+      const int hh = head - n_q_heads;
+      const size_t eoff = (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
+      if (kvq.fp8) {     // one-byte e4m3 codes
+        unsigned char* o = reinterpret_cast<unsigned char*>(k_pool) + eoff;
+        o[i] = (unsigned char)e4m3_encode(rlo * kvq.k_inv);
+        o[i + half] = (unsigned char)e4m3_encode(rhi * kvq.k_inv);
+      } else {
+        bf16_t* o = k_pool + eoff;
+        o[i] = lo;
+        o[i + half] = hi;
+      }
+    }
+  } else {
+    const int hh = head - n_q_heads - n_kv_heads;
+    const size_t eoff = (((size_t)(s / P) * n_kv_heads + hh) * P + (s % P)) * hd;
+    if (kvq.fp8) {
+      unsigned char* o = reinterpret_cast<unsigned char*>(v_pool) + eoff;
+      o[i] = (unsigned char)e4m3_encode(x * kvq.v_inv);
+      o[i + half] = (unsigned char)e4m3_encode(y * kvq.v_inv);
+    } else {
+      bf16_t* o = v_pool + eoff;
+      o[i] = f32_to_bf16(x);
+      o[i + half] = f32_to_bf16(y);
+    }
+  }
+}
+}  // namespace decode_impl
+using namespace decode_impl;
+
+void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
+                        const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool, bf16_t* v_pool,
+                        int page_size, int B, hipStream_t st, const float* q_gamma, const float* k_gamma,
+                        float qk_eps, int n_parts, size_t part_stride, KvQuant kvq) {
+  if (B <= 0) return;
+  hipLaunchKernelGGL(rope_append_kernel, dim3(B, n_q_heads + 2 * n_kv_heads), dim3(128), 0, st, qkv, ld, q_out,
+                     n_q_heads, n_kv_heads, hd, pos, slot, -2.0 / (double)hd * log2(theta), k_pool, v_pool,
+                     page_size, q_gamma, k_gamma, qk_eps, n_parts, part_stride, kvq);
+}
+
 // ------------------------------------------------------------------------------------- decode attention
 namespace decode_impl {
 
@@ -282,7 +369,9 @@ constexpr int GMAX = 8;   // query heads per KV head
 // grid (n_splits, Hkv, B), 256 threads.  Split s of sequence b covers keys lo + s*KCH .. +KCH-1,
 // lo = first visible key (window start, or the first position the layer holds an entry for).  Writes the unnormalised partial output, its max and its sum.
 // GT: compile-time bound of the number of query heads per KV head (registers and loops are sized by it).
-template <int HD, int GT>
+// FUSED: RoPE + append inside this kernel (a.qkv_raw given); a template parameter because the preparation's registers
+// would otherwise halve the occupancy of the plain form as well.
+template <int HD, int GT, bool FUSED>
 __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a, float scale) {
   constexpr int LPK = HD / 8;        // lanes per key (16-byte chunk each)
   constexpr int KPI = 256 / LPK;     // keys per block iteration
@@ -314,7 +403,7 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
   }
 
   // this thread's K and V chunks of the split are requested up front (one memory round trip), before the query
-  // rows are prepared (the slot of the query position is read too, and replaced further down)
+  // rows are prepared (in the fused mode the slot of the query position is read too, and replaced further down)
   constexpr int NIT = KCH / KPI;
   uint4 kw[NIT], vw[NIT];
 #pragma unroll
@@ -338,10 +427,11 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
     }
   }
   // ---- RoPE + append inside this kernel: head rows from the projection's fp32 output
+  constexpr bool fused = FUSED;
   constexpr int HALF = HD / 2;
   const bool hi_half = li * 8 >= HALF;          // this thread's 8 dims are the second members of their pairs
   float rc[8], rs[8];                           // (cos, sin) of those pairs
-  {
+  if constexpr (fused) {
     const float4* csp = reinterpret_cast<const float4*>(a.cs + (size_t)b * HALF + (li * 8) % HALF);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -386,15 +476,21 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
 #pragma unroll
   for (int g = 0; g < GT; ++g) {
     if (g < G) {
-      head8((kvh * G + g) * HD, a.q_gamma, true, qv[g]);
+      if constexpr (fused) {
+        head8((kvh * G + g) * HD, a.q_gamma, true, qv[g]);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) qv[g][e] = bf16_to_f32(f32_to_bf16(qv[g][e]));   // q enters the scores as bf16
+        for (int e = 0; e < 8; ++e) qv[g][e] = bf16_to_f32(f32_to_bf16(qv[g][e]));   // q enters the scores as bf16
+      } else {
+        const uint4 w = *reinterpret_cast<const uint4*>(a.q + ((size_t)b * a.n_q_heads + kvh * G + g) * HD + li * 8);
+        qv[g][0] = bf16lo(w.x); qv[g][1] = bf16hi(w.x); qv[g][2] = bf16lo(w.y); qv[g][3] = bf16hi(w.y);
+        qv[g][4] = bf16lo(w.z); qv[g][5] = bf16hi(w.z); qv[g][6] = bf16lo(w.w); qv[g][7] = bf16hi(w.w);
+      }
     }
   }
   // The query position's own entry, if its key falls into this split: formed here (every group of lanes computes
   // the same values; the group whose key it is stores them and keeps them in place of a load).
   const int kk_new = qpos - k_first;
-  const bool has_new = kk_new >= 0 && kk_new < n_keys;
+  const bool has_new = fused && kk_new >= 0 && kk_new < n_keys;
   uint4 k_new = make_uint4(0, 0, 0, 0), v_new = make_uint4(0, 0, 0, 0);
   if (has_new) {
     float k8[8], v8[8];
@@ -589,10 +685,15 @@ void launch_decode_hd(const AttnDecodeArgs& a, hipStream_t st) {
   const float scale = 1.f / sqrtf((float)HD);
   const dim3 grid(a.n_splits, a.n_kv_heads, a.B);
   const int G = a.n_q_heads / a.n_kv_heads;
-  if (G <= 1) hipLaunchKernelGGL((attn_decode_split_kernel<HD, 1>), grid, dim3(256), 0, st, a, scale);
-  else if (G <= 2) hipLaunchKernelGGL((attn_decode_split_kernel<HD, 2>), grid, dim3(256), 0, st, a, scale);
-  else if (G <= 4) hipLaunchKernelGGL((attn_decode_split_kernel<HD, 4>), grid, dim3(256), 0, st, a, scale);
-  else hipLaunchKernelGGL((attn_decode_split_kernel<HD, GMAX>), grid, dim3(256), 0, st, a, scale);
+  auto go = [&](auto fused_c) {
+    constexpr bool F = decltype(fused_c)::value;
+    if (G <= 1) hipLaunchKernelGGL((attn_decode_split_kernel<HD, 1, F>), grid, dim3(256), 0, st, a, scale);
+    else if (G <= 2) hipLaunchKernelGGL((attn_decode_split_kernel<HD, 2, F>), grid, dim3(256), 0, st, a, scale);
+    else if (G <= 4) hipLaunchKernelGGL((attn_decode_split_kernel<HD, 4, F>), grid, dim3(256), 0, st, a, scale);
+    else hipLaunchKernelGGL((attn_decode_split_kernel<HD, GMAX, F>), grid, dim3(256), 0, st, a, scale);
+  };
+  if (a.qkv_raw) go(std::true_type{});
+  else go(std::false_type{});
   hipLaunchKernelGGL(attn_decode_combine_kernel, dim3(a.B * a.n_q_heads), dim3(256), 0, st, a.part, a.out,
                      a.n_splits, HD);
 }

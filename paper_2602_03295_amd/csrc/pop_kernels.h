@@ -192,8 +192,17 @@ constexpr int kDecodeKeysPerSplit = 64;
 
 // Attention of one query row per sequence over its paged cache entries 0..len-1 (len = pos + 1),
 // split over the key range; `part` holds the per-split partial results.
+// RoPE of one new token per sequence + cache append: qkv fp32 [B, ld] -> q bf16 [B, Hq*hd] rotated,
+// k (rotated) and v stored at slot[b].
+void launch_rope_append(const float* qkv, int ld, bf16_t* q_out, int n_q_heads, int n_kv_heads, int hd,
+                        const int32_t* pos, const int32_t* slot, double theta, bf16_t* k_pool,
+                        bf16_t* v_pool, int page_size, int B, hipStream_t st, const float* q_gamma = nullptr,
+                        const float* k_gamma = nullptr, float qk_eps = 0.f, int n_parts = 1, size_t part_stride = 0,
+                        KvQuant kvq = KvQuant{0, 1.f, 1.f, 1.f, 1.f});
+
 struct AttnDecodeArgs {
-  const bf16_t* k_pool;   // this layer's pools; the query position's entry is written by the kernel
+  const bf16_t* q;        // [B, Hq*hd] rotated query rows (launch_rope_append), unused when qkv_raw is given
+  const bf16_t* k_pool;   // this layer's pools; with qkv_raw the query position's entry is written by the kernel
   const bf16_t* v_pool;
   const int32_t* block_table;  // [B, max_pages]
   int max_pages, page_size;
@@ -207,10 +216,11 @@ struct AttnDecodeArgs {
   float* part;          // [B, Hq, n_splits, hd + 2]
   bf16_t* out;          // [B, Hq*hd]
   KvQuant kvq;          // bf16 entries or e4m3 codes in the pools
-  // RoPE + append happen inside this kernel: the query token's q, k, v rows come as the QKV projection left them,
-  // every work-group rotates the query heads it needs, and the work-group whose keys include the query position
-  // also forms that position's cache entry (per-head key norm, rotation, rounding to the cache's type), stores it
-  // and uses it from registers.
+  // qkv_raw != nullptr: RoPE + append happen inside this kernel.  The query token's q, k, v rows come as the QKV
+  // projection left them, every work-group rotates the query heads it needs, and the work-group whose keys include
+  // the query position also forms that position's cache entry (per-head key norm, rotation, rounding to the cache's
+  // type), stores it and uses it from registers.  One launch less; pays with few sequences (each of the
+  // n_splits x Hkv x B work-groups repeats the preparation of its query heads).
   const float* qkv_raw;     // fp32 [n_parts][B, ld], rows q | k | v; the parts (a split projection) are added
   int ld, n_parts;
   size_t part_stride;       // elements between parts

@@ -202,3 +202,54 @@ def test_gemm_split_k_small_scratch_and_strides(pop):
     ref2 = As.double().cpu().numpy() @ Ws.double().cpu().numpy().T
     assert rel(out[:, 512:1536].cpu().numpy(), ref2) <= 1e-5
     assert float(out[:, :512].abs().max()) == 0 and float(out[:, 1536:].abs().max()) == 0
+
+
+@pytest.mark.parametrize("M", [1, 5, 8, 13, 16])
+@pytest.mark.parametrize("epi", [0, 1, 2, 3])
+def test_gemm_few_rows(pop, M, epi):
+    """At most 16 rows: the projection runs as weight streaming (decode steps and boundary rows of a batch of
+    sequences).  Same definition, every epilogue, strided operands, a K that is not a multiple of the unroll depth,
+    and a ragged number of 16-row blocks per work-group."""
+    N, K = 16 * 23, 32 * 19
+    rng = np.random.default_rng(100 * M + epi)
+    xbuf = bf16_round(rng.standard_normal((M, K + 64)).astype(np.float32) * 0.3).cuda()
+    x = xbuf[:, 32:32 + K]
+    W = bf16_round(rng.standard_normal(((2 if epi == 2 else 1) * N, K)).astype(np.float32) * 0.3).cuda()
+    xd, Wd = x.double().cpu().numpy(), W.double().cpu().numpy()
+    if epi == 2:
+        ref = O.glu_act(xd @ Wd[:N].T, 1) * (xd @ Wd[N:].T)
+    else:
+        ref = xd @ Wd.T
+    wide = torch.zeros(M, N + 32, dtype=torch.float32 if epi in (1, 3) else torch.bfloat16, device="cuda")
+    out = wide[:, 16:16 + N]
+    if epi == 1:
+        base = rng.standard_normal((M, N)).astype(np.float32)
+        out.copy_(torch.from_numpy(base))
+        ref = ref + base
+    pop.pop_op_gemm(x, W, epilogue=epi, act=1, out=out)
+    torch.cuda.synchronize()
+    tol = 1e-5 if epi in (1, 3) else 2.0 ** -7
+    assert rel(out.float().cpu().numpy(), ref) <= tol
+    assert float(wide[:, :16].float().abs().max()) == 0 and float(wide[:, 16 + N:].float().abs().max()) == 0
+
+
+@pytest.mark.parametrize("M,N,K,epi", [(8, 4096, 4096, 1), (16, 1024, 14336, 3), (5, 6144, 4096, 0)])
+def test_gemm_few_rows_split_k(pop, M, N, K, epi):
+    """The same with the K range split over parts (few rows, fewer work-groups than CUs): against the definition,
+    and bit-identical from run to run."""
+    rng = np.random.default_rng(M + N + K)
+    A = bf16_round(rng.standard_normal((M, K)).astype(np.float32) * 0.5)
+    W = bf16_round(rng.standard_normal((N, K)).astype(np.float32) * 0.05)
+    ref = A.double().numpy() @ W.double().numpy().T
+    base = rng.standard_normal((M, N)).astype(np.float32)
+    if epi == 1:
+        ref = ref + base
+    outs = []
+    for _ in range(2):
+        out = torch.from_numpy(base.copy()).cuda() if epi == 1 else None
+        got = pop.pop_op_gemm_splitk(A.cuda(), W.cuda(), epilogue=epi, out=out)
+        torch.cuda.synchronize()
+        outs.append(got.float().cpu().numpy())
+    tol = 2.0 ** -8 if epi == 0 else 1e-5
+    assert rel(outs[0], ref) <= tol, (rel(outs[0], ref), tol)
+    assert np.array_equal(outs[0], outs[1])
