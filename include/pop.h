@@ -145,6 +145,12 @@ void pop_cache_destroy(pop_cache* c); /* does not free dev_pool */
 /* Number of live sequences and their current lengths (host_out has room for max_seqs values). */
 int32_t pop_cache_n_seqs(const pop_cache* c);
 pop_status pop_cache_seq_lens(const pop_cache* c, int32_t* host_out);
+/* The page table the cache object holds (Sec. 2.1, cache append: where the entries of each sequence are) and the
+ * current lengths: host_out HOST [max_seqs][max_pages_per_seq] receives the page ids the last pop_prefill was
+ * given (negative = unassigned; all negative before the first prefill), host_seq_lens HOST [max_seqs] (may be
+ * NULL) the lengths as of now.  Read-only: the table stays the caller's to decide (see pop_prefill_args), this
+ * call hands back the copy the library addresses the pool with.  POP_EINVAL on NULL. */
+pop_status pop_cache_block_table(const pop_cache* c, int32_t* host_out, int32_t* host_seq_lens);
 
 /*
  * Cache slot of every packed token (integer, host-only):
@@ -167,9 +173,9 @@ typedef struct {
                                   later decode steps.  The table is the CALLER's: which page a sequence
                                   gets is the serving engine's allocation policy (free lists, prefix
                                   sharing, eviction), not part of the method, so the library exports no
-                                  allocator and no call that hands a table out; it validates the table it
-                                  is given (pop_slot_map's rules), copies it into the cache object, and
-                                  reports the lengths it has recorded through pop_cache_seq_lens        */
+                                  allocator; it validates the table it is given (pop_slot_map's rules),
+                                  copies it into the cache object, and reports that copy and the lengths it
+                                  has recorded through pop_cache_block_table / pop_cache_seq_lens       */
   const void* embeds;          /* DEVICE bf16 [sum of counts, d] or NULL: rows that replace the
                                   embedding lookup (e.g. visual tokens fed as hidden states)        */
   const int32_t* embed_ranges; /* HOST [n_ranges][3] = (seq, first_pos, count), rows of `embeds`

@@ -1062,6 +1062,13 @@ pop_status pop_cache_seq_lens(const pop_cache* c, int32_t* host_out) {
   return POP_OK;
 }
 
+pop_status pop_cache_block_table(const pop_cache* c, int32_t* host_out, int32_t* host_seq_lens) {
+  if (!c || !host_out) return fail(POP_EINVAL, "cache / host_out is NULL");
+  std::copy(c->block_table.begin(), c->block_table.end(), host_out);
+  if (host_seq_lens) std::copy(c->seq_lens.begin(), c->seq_lens.end(), host_seq_lens);
+  return POP_OK;
+}
+
 pop_status pop_slot_map(const int32_t* host_cu_seqlens, int32_t n_seqs, const int32_t* host_block_table,
                         int32_t max_pages_per_seq, int32_t page_size, int32_t n_pages, int32_t* host_slots_out) {
   if (!host_slots_out) return fail(POP_EINVAL, "host_slots_out is NULL");

@@ -78,6 +78,7 @@ lib.pop_cache_destroy.argtypes = [C.c_void_p]
 lib.pop_cache_destroy.restype = None
 lib.pop_cache_n_seqs.argtypes = [C.c_void_p]
 lib.pop_cache_seq_lens.argtypes = [C.c_void_p, _i32p]
+lib.pop_cache_block_table.argtypes = [C.c_void_p, _i32p, _i32p]
 lib.pop_slot_map.argtypes = [_i32p, C.c_int32, _i32p, C.c_int32, C.c_int32, C.c_int32, _i32p]
 lib.pop_prefill.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(pop_prefill_args), C.c_void_p, C.c_void_p,
                             C.c_size_t, C.c_void_p]
@@ -114,7 +115,7 @@ STEP_NAMES = ["embed", "norm", "qkv_gemm", "rope_write", "attention", "o_gemm", 
 
 EXPORTED = ["pop_timing_enable", "pop_timing_read", "pop_last_error", "pop_version", "pop_load_weights", "pop_free_model", "pop_cache_bytes",
             "pop_workspace_bytes", "pop_cache_create", "pop_cache_destroy", "pop_cache_n_seqs",
-            "pop_cache_seq_lens", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_decode_step_gated", "pop_generate",
+            "pop_cache_seq_lens", "pop_cache_block_table", "pop_slot_map", "pop_prefill", "pop_decode_step", "pop_decode_step_gated", "pop_generate",
             "pop_generate_workspace_bytes", "pop_op_rmsnorm",
             "pop_op_gemm", "pop_op_gemm_splitk", "pop_op_gemm_splitk_static", "pop_static_scratch_bytes", "pop_op_gemv", "pop_op_gemv_norm", "pop_op_rope_attention_workspace", "pop_op_rope_attention"]
 
@@ -293,6 +294,13 @@ class Cache:
 
     def n_seqs(self) -> int:
         return lib.pop_cache_n_seqs(self.handle)
+
+    def block_table(self):
+        """(page table [max_seqs, max_pages_per_seq], lengths [max_seqs]) as the cache object holds them."""
+        bt = np.zeros((self.max_seqs, self.max_pages), dtype=np.int32)
+        lens = np.zeros(self.max_seqs, dtype=np.int32)
+        _check(lib.pop_cache_block_table(self.handle, _ptr(bt), _ptr(lens)))
+        return bt, lens
 
     def __del__(self):
         if getattr(self, "handle", None) and lib is not None:

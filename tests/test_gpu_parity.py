@@ -60,6 +60,9 @@ def test_slot_placement_is_exact_and_nothing_else_is_written(pop):
     assert np.all(flat[:, :, ~written] == sent), "a slot outside the map was written"
     assert not np.any(np.all(flat[:, :, written] == sent, axis=(-1, -2))), "a mapped slot was left unwritten"
     assert run.cache.n_seqs() == 4 and run.cache.seq_lens().tolist() == lens
+    # the cache object hands back the page table it was given, and the same lengths
+    bt_back, lens_back = run.cache.block_table()
+    assert np.array_equal(bt_back, run.bt) and lens_back.tolist() == lens
 
 
 def test_ragged_batch_paged_matches_oracle_and_single_runs(pop):

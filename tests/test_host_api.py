@@ -327,3 +327,19 @@ def test_qk_norm_pointers_come_in_pairs():
         assert st == want, (q, k, st, err())
         if st == 0:
             pop.lib.pop_free_model(h)
+
+
+def test_cache_block_table_before_any_prefill():
+    """A fresh cache object holds no pages and no sequences: the table reads back all negative, the lengths zero
+    (no device work: the pool pointer is never dereferenced)."""
+    cfg = synth.get_config("tiny", dtype=synth.DTYPE_BF16)
+    c_cfg = pop.make_config(cfg)
+    st, h = fake_cache(c_cfg, 12, 3, 5)
+    assert st == 0
+    bt = np.full((3, 5), 7, dtype=np.int32)
+    lens = np.full(3, 7, dtype=np.int32)
+    assert pop.lib.pop_cache_block_table(h, bt.ctypes.data_as(C.POINTER(C.c_int32)), lens.ctypes.data_as(C.POINTER(C.c_int32))) == 0
+    assert np.all(bt < 0) and np.all(lens == 0)
+    assert pop.lib.pop_cache_block_table(h, None, None) == -1 and "NULL" in err()
+    assert pop.lib.pop_cache_block_table(h, bt.ctypes.data_as(C.POINTER(C.c_int32)), None) == 0   # lengths are optional
+    pop.lib.pop_cache_destroy(h)
