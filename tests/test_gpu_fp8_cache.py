@@ -127,21 +127,22 @@ def test_fp32_path_codes_and_values(pop, monkeypatch, l_keep):
     assert int(np.argmax(logits)) == int(np.argmax(ref)) or differing > 0
 
 
-def test_bf16_path_ragged_batch_then_decode_steps(pop, monkeypatch):
+@pytest.mark.parametrize("lens", [[128, 1, 77], [128, 1, 77, 30, 5]])
+def test_bf16_path_ragged_batch_then_decode_steps(pop, monkeypatch, lens):
     """One-byte codes in the pools: kept layers (append kernel), pruned layers (few rows: the append kernel after the
-    batched GEMM), boundary rows and decode steps (decode append + decode attention reading codes)."""
+    batched GEMM), boundary rows and decode steps (three sequences: the decode attention forms and stores the codes
+    itself; five: the separate append kernel, then the decode attention reading codes)."""
     ks, vs = 1.0 / 64, 1.0 / 128
     cfg = synth.get_config("tiny", dtype=synth.DTYPE_BF16, kv_dtype=O.KV_FP8_E4M3, k_scale=ks, v_scale=vs)
     W = synth.make_weights(cfg, seed=1234)
     synth.randomize_norms(W, cfg)
-    lens = [128, 1, 77]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=1)
     run = DeviceRun(pop, cfg, W, lens, reserve_pages=1, shuffle_seed=3, poison=float("nan"))
     n_elems = cfg["n_layers"] * 2 * run.n_pages * cfg["n_kv_heads"] * cfg["page_size"] * cfg["head_dim"]
     assert run.cache.pool.dtype == torch.uint8 and run.cache.pool.numel() == n_elems
     drift, drift_logits = simulated_drift("bf16_input_floor_tiny_128_lkeep5_of_8_kvfp8.txt")
     logits = run.prefill(tokens, 5)
-    nxt = [7, 8, 9]
+    nxt = [7, 8, 9, 10, 11][:len(lens)]
     logits2 = run.decode(nxt)
     for b, n in enumerate(lens):
         seq = tokens[run.cu[b]:run.cu[b + 1]]

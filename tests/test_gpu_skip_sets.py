@@ -199,9 +199,12 @@ def test_windowed_kv_writes_change_no_logit(pop):
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("head_dim", [64, 128, 256])
-def test_qk_norm(pop, dtype, head_dim):
+@pytest.mark.parametrize("lens", [[140, 3, 66], [60, 3, 66, 17, 41, 9]])
+def test_qk_norm(pop, dtype, head_dim, lens):
     """Per-head QK-norm before RoPE (a family extra): kept layers, the pruned layers' key projection (one of
-    them a sliding-window layer with windowed writes), the boundary rows and decode steps, against the oracle."""
+    them a sliding-window layer with windowed writes), the boundary rows and decode steps, against the oracle.
+    Three sequences take the decode attention that rotates and appends itself, six the separate kernel and the
+    tiled projections."""
     cfg = synth.get_config("tiny", n_layers=5, sliding_window=40, global_every=2, rope_theta_local=100.0,
                            head_dim=head_dim, rms_eps=1e-6)
     if dtype == "bf16":
@@ -209,7 +212,6 @@ def test_qk_norm(pop, dtype, head_dim):
     W = synth.make_weights(cfg, seed=41)
     synth.randomize_norms(W, cfg)
     synth.add_qk_norms(W, cfg)
-    lens = [140, 3, 66]
     tokens = synth.make_tokens(cfg["vocab"], sum(lens), seed=12)
     tol = TOL32 if dtype == "fp32" else TOL
     worst = check_against_oracle(pop, cfg, W, lens, tokens, (3, 4), True, True, tol, n_decode=3, seed=3,
