@@ -527,8 +527,10 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(AttnDecodeArgs a
   // the 8 values of a chunk as floats: bf16 entries, or e4m3 codes times the tensor's scale
   auto unpack8 = [&](const uint4& w, float* f, float scale8) {
     if (fp8) {
+      e4m3_decode4_hw(w.x, f);
+      e4m3_decode4_hw(w.y, f + 4);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] = e4m3_decode(((e < 4 ? w.x : w.y) >> (8 * (e & 3))) & 0xffu) * scale8;
+      for (int e = 0; e < 8; ++e) f[e] *= scale8;
     } else {
       f[0] = bf16lo(w.x); f[1] = bf16hi(w.x); f[2] = bf16lo(w.y); f[3] = bf16hi(w.y);
       f[4] = bf16lo(w.z); f[5] = bf16hi(w.z); f[6] = bf16lo(w.w); f[7] = bf16hi(w.w);
